@@ -1,0 +1,34 @@
+"""Glue used by the tests: exact bf16 -> fp64 conversion of the seeded inputs and the oracle's
+parameter / config objects for a workload."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import indexmem_oracle as O
+from workloads import Workload, layer_params
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    """Exact conversion of a (bf16 / fp32 / int) tensor to a float64 numpy array."""
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def oracle_params(p: dict) -> O.OracleParams:
+    return O.OracleParams(Uq=f64(p["Uq"]), G=f64(p["G"]), Uk=f64(p["Uk"]),
+                          norm_q_w=f64(p["norm_q_w"]), norm_k_w=f64(p["norm_k_w"]),
+                          Wtheta=f64(p["Wtheta"]), wg=f64(p["wg"]), cg=float(p["cg"]))
+
+
+def oracle_config(w: Workload, capacity=None, batch=None, kv_head_ids=None) -> O.OracleConfig:
+    return O.OracleConfig(batch=w.batch if batch is None else batch,
+                          n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
+                          capacity=w.capacity if capacity is None else capacity,
+                          n_idx_heads=w.n_idx_heads, head_dim=w.head_dim, idx_dim=w.idx_dim,
+                          mem_dim=w.mem_dim, n_sink=w.n_sink, n_recent=w.n_recent,
+                          softmax_scale=1.0 / np.sqrt(float(w.head_dim)),
+                          kv_head_ids=kv_head_ids)
+
+
+def make_oracle_layer(w: Workload, layer: int = 0, device="cpu", **kw) -> O.OracleLayer:
+    return O.OracleLayer(oracle_config(w, **kw), oracle_params(layer_params(w, layer, device)))

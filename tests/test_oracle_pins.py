@@ -1,0 +1,420 @@
+"""Pins of the CPU oracle: each test checks an oracle function against something the paper or
+the mathematics fixes and that is computed here WITHOUT the oracle's own formula: library
+routines (torch SDPA, torch Linear / RMS statistics, torch bf16 conversion), closed forms,
+brute force and invariants.  The paper prints no worked numeric example, so there are no
+golden values of the paper's; the parameter counts of Section 4 are the only printed numbers
+that touch this path and they are pinned in test_parameter_counts."""
+import itertools
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import indexmem_oracle as O
+from workloads import WORKLOADS, layer_params, token_stream
+from helpers import f64, make_oracle_layer, oracle_params
+
+RNG = np.random.default_rng(1234)
+
+
+def bf(x):
+    """numpy fp64 -> bf16-representable fp64 via torch (library conversion from fp32)."""
+    return torch.tensor(np.asarray(x, np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+
+
+# ----------------------------------------------------------------------------- roundings
+def test_round_bf16_matches_torch_on_fp32_inputs():
+    x = np.concatenate([RNG.standard_normal(20000) * 10.0 ** RNG.integers(-6, 6, 20000),
+                        [0.0, -0.0, 1.0, -1.0, 3.0e-40, 1.0e-45]]).astype(np.float32)
+    want = torch.tensor(x).to(torch.bfloat16).to(torch.float64).numpy()
+    got = O.round_bf16(x.astype(np.float64))
+    assert np.array_equal(got, want)
+
+
+def test_round_bf16_is_a_single_rounding():
+    # 1 + 2^-8 is the midpoint of the bf16 neighbours 1 and 1 + 2^-7.  A value just below the
+    # midpoint, but so close that fp32 rounds it onto the midpoint, must still go DOWN.
+    mid = 1.0 + 2.0 ** -8
+    below = mid - 2.0 ** -40
+    above = mid + 2.0 ** -40
+    assert np.float32(below) == np.float32(mid)          # the double-rounding trap is armed
+    assert O.round_bf16(below)[0] == 1.0
+    assert O.round_bf16(above)[0] == 1.0 + 2.0 ** -7
+    assert O.round_bf16(mid)[0] == 1.0                   # tie -> even mantissa
+    mid_odd = 1.0 + 2.0 ** -7 + 2.0 ** -8                # tie whose lower neighbour is odd
+    assert O.round_bf16(mid_odd)[0] == 1.0 + 2.0 ** -6
+    assert O.round_bf16(-below)[0] == -1.0
+
+
+# ----------------------------------------------------------------------------- P4 shapes
+def test_parameter_counts():
+    # Section 4 "Parameter and Efficiency Analysis": 19.92 M indexer and 0.52 M memory
+    # parameters on Llama-3.1-8B (32 layers, H=32, d_head=128, d_model=4096) with the paper's
+    # H_idx = H/4 and d_idx = d_head/8.
+    idx, mem = O.param_count(n_heads=32, head_dim=128, d_model=4096, n_idx_heads=8, idx_dim=16,
+                             mem_dim=128, n_layers=32)
+    assert idx == 19_922_944 and round(idx / 1e6, 2) == 19.92
+    assert mem == 524_288 and round(mem / 1e6, 2) == 0.52
+
+
+# ----------------------------------------------------------------------------- a1 indexer
+def test_key_feature_against_torch_linear_and_rms():
+    K = bf(RNG.standard_normal((37, 128)))
+    Uk = bf(RNG.standard_normal((64, 128)) * 0.02)
+    w = bf(1.0 + 0.1 * RNG.standard_normal(64))
+    got = O.key_feature(K, Uk, w, 1e-6)
+    u = torch.nn.functional.linear(torch.tensor(K), torch.tensor(Uk))       # [out,in] weight
+    want = torch.nn.functional.rms_norm(u, (64,), torch.tensor(w), eps=1e-6)
+    assert got.shape == (37, 64)
+    assert np.allclose(got, want.numpy(), rtol=2 ** -8, atol=0)             # bf16 rounding only
+    assert np.array_equal(got, bf(got))                                     # stored as bf16
+
+
+def test_query_feature_and_gate_against_torch():
+    H, D, Hi, di, nq = 8, 128, 2, 64, 5
+    Q = bf(RNG.standard_normal((nq, H * D)))
+    Uq = bf(RNG.standard_normal((Hi * di, H * D)) * 0.02)
+    G = bf(RNG.standard_normal((Hi, H * D)) * 0.02)
+    w = bf(1.0 + 0.1 * RNG.standard_normal(di))
+    got = O.query_feature(Q, Uq, w, Hi, di, 1e-6)
+    y = torch.nn.functional.linear(torch.tensor(Q), torch.tensor(Uq)).view(nq, Hi, di)
+    want = torch.nn.functional.rms_norm(y, (di,), torch.tensor(w), eps=1e-6).numpy()
+    assert np.allclose(got, want, rtol=1e-6, atol=0)
+    assert np.array_equal(got, got.astype(np.float32).astype(np.float64))
+    a = O.head_gate(Q, G, Hi, di)
+    want_a = (torch.tensor(Q) @ torch.tensor(G).T).numpy() / math.sqrt(Hi * di)
+    assert np.allclose(a, want_a, rtol=1e-6, atol=0)
+
+
+def _rand_indexer(nq, n, Hi=8, di=64):
+    qhat = RNG.standard_normal((nq, Hi, di)).astype(np.float32).astype(np.float64)
+    alpha = (RNG.standard_normal((nq, Hi)) * 0.1).astype(np.float32).astype(np.float64)
+    khat = bf(RNG.standard_normal((n, di)))
+    return qhat, alpha, khat
+
+
+def test_importance_against_explicit_loops():
+    # the definition, as scalar loops over query, key, head and feature
+    nq, n, Hi, di = 4, 9, 3, 8
+    qhat, alpha, khat = _rand_indexer(nq, n, Hi, di)
+    q_pos = np.array([3, 5, 7, 20]); k_pos = np.array([0, 1, 2, 4, 6, 8, 9, 21, 20])
+    want = np.full(n, -np.inf)
+    for t in range(n):
+        for s in range(nq):
+            if k_pos[t] > q_pos[s]:
+                continue
+            a = 0.0
+            for h in range(Hi):
+                z = sum(qhat[s, h, c] * khat[t, c] for c in range(di))
+                a += alpha[s, h] * max(z, 0.0)
+            want[t] = max(want[t], a)
+    got = O.importance(qhat, alpha, q_pos, khat, k_pos)
+    assert np.isneginf(got[7]) and np.isfinite(got[8])      # key newer than every query
+    fin = np.isfinite(want)
+    assert np.array_equal(np.isfinite(got), fin)
+    assert np.allclose(got[fin], want[fin], rtol=1e-6, atol=1e-9)
+
+
+def test_importance_single_head_is_relu_cosine():
+    # H_idx = 1, alpha = 1, unit norm weights: score = ReLU(d_idx * cos(q, k)) up to rms_eps
+    di, n = 64, 50
+    yq = RNG.standard_normal((1, 1, di)); ku = RNG.standard_normal((n, di))
+    qhat = O.rms_norm(yq, np.ones(di), 0.0)
+    khat = O.rms_norm(ku, np.ones(di), 0.0)
+    got = O.importance(qhat, np.ones((1, 1)), np.array([10 ** 6]), khat, np.arange(n))
+    cos = (ku @ yq[0, 0]) / (np.linalg.norm(ku, axis=1) * np.linalg.norm(yq))
+    assert np.allclose(got, np.maximum(di * cos, 0.0), rtol=1e-6, atol=1e-6)
+
+
+def test_importance_invariants():
+    nq, n = 6, 40
+    qhat, alpha, khat = _rand_indexer(nq, n)
+    q_pos = np.arange(100, 100 + nq); k_pos = np.arange(n)
+    imp = O.importance(qhat, alpha, q_pos, khat, k_pos)
+    # max-decomposition over a split of the query set
+    a = O.importance(qhat[:2], alpha[:2], q_pos[:2], khat, k_pos)
+    b = O.importance(qhat[2:], alpha[2:], q_pos[2:], khat, k_pos)
+    assert np.array_equal(imp, np.maximum(a, b))
+    # bound: |q_h . k| <= |q_h| |k|  =>  |imp| <= max_s sum_h |alpha_sh| |q_sh| |k_t|
+    bound = np.max(np.sum(np.abs(alpha)[:, :, None] * np.linalg.norm(qhat, axis=2)[:, :, None]
+                          * np.linalg.norm(khat, axis=1)[None, None, :], axis=1), axis=0)
+    assert np.all(np.abs(imp) <= bound * (1 + 1e-6))
+    # one query: linear in the gate
+    one = O.importance(qhat[:1], alpha[:1], q_pos[:1], khat, k_pos)
+    two = O.importance(qhat[:1], 2 * alpha[:1], q_pos[:1], khat, k_pos)
+    assert np.allclose(two, 2 * one, rtol=1e-6)
+    # zero gate -> every visible score is 0
+    z = O.importance(qhat, 0 * alpha, q_pos, khat, k_pos)
+    assert np.all(z == 0.0)
+
+
+def test_key_feature_scale_invariance():
+    # RMSNorm removes the key's scale, so a planted high-norm key keeps its indexer key
+    K = bf(RNG.standard_normal((20, 128)))
+    Uk = bf(RNG.standard_normal((64, 128)) * 0.02)
+    one = np.ones(64)
+    a = O.key_feature(K, Uk, one, 1e-12)
+    b = O.key_feature(4.0 * K, Uk, one, 1e-12)
+    assert np.max(np.abs(a - b)) <= 2 ** -7 * np.max(np.abs(a))   # at most one bf16 ulp
+    assert np.mean(a != b) < 0.01
+
+
+# ----------------------------------------------------------------------------- a2 selection
+def _brute_select(scores, pos, budget, n_sink, n_recent):
+    n = len(scores)
+    mx = max(pos) if n else 0
+    s = [math.inf if (pos[t] < n_sink or pos[t] > mx - n_recent) else scores[t] for t in range(n)]
+    keep, evict = [], []
+    for t in range(n):
+        rank = sum(1 for u in range(n) if s[u] > s[t] or (s[u] == s[t] and pos[u] < pos[t]))
+        (keep if rank < budget else evict).append(t)
+    return keep, evict
+
+
+@pytest.mark.parametrize("kind", ["random", "quantised", "all_equal", "infs"])
+def test_select_against_brute_force(kind):
+    for n in [0, 1, 3, 7, 16, 33]:
+        for trial in range(3):
+            pos = RNG.permutation(n + 5)[:n]
+            if kind == "random":
+                sc = RNG.standard_normal(n)
+            elif kind == "quantised":
+                sc = RNG.integers(0, 3, n).astype(np.float64)
+            elif kind == "all_equal":
+                sc = np.zeros(n)
+            else:
+                sc = RNG.choice([-np.inf, np.inf, 0.0, 1.0], n)
+            sc = sc.astype(np.float32).astype(np.float64)
+            for n_recent in (0, 2):
+                for budget in range(4 + n_recent, n + 2):
+                    keep, evict = O.select(sc, pos, budget, 4, n_recent)
+                    bk, be = _brute_select(list(sc), list(pos), budget, 4, n_recent)
+                    assert list(keep) == bk and list(evict) == be
+
+
+def test_select_invariants_and_ties():
+    n, B = 500, 100
+    pos = np.arange(n)
+    sc = RNG.integers(0, 8, n).astype(np.float64)
+    keep, evict = O.select(sc, pos, B, 4)
+    assert len(keep) == B and len(evict) == n - B
+    assert sorted(set(keep) | set(evict)) == list(range(n)) and not set(keep) & set(evict)
+    assert all(t in set(keep) for t in range(4))                       # sinks kept
+    nonforced = [t for t in keep if pos[t] >= 4]
+    worst_kept = min((sc[t], -pos[t]) for t in nonforced)
+    best_evicted = max((sc[t], -pos[t]) for t in evict)
+    assert worst_kept > best_evicted
+    # all scores equal -> the B oldest positions survive
+    keep0, _ = O.select(np.zeros(n), pos[::-1].copy(), B, 4)
+    assert sorted(pos[::-1][keep0]) == list(range(B))
+    # -0.0 and +0.0 are the same score
+    sz = np.where(RNG.integers(0, 2, n) == 0, 0.0, -0.0)
+    keepz, _ = O.select(sz, pos, B, 4)
+    assert list(keepz) == list(range(B))
+
+
+# ----------------------------------------------------------------------------- a3 memory write
+def test_memory_write_against_outer_product_loop():
+    ne = 7
+    K = bf(RNG.standard_normal((ne, 128))); V = bf(RNG.standard_normal((ne, 128)))
+    W = bf(RNG.standard_normal((128, 128)) * 0.02)
+    M0 = RNG.standard_normal((128, 128)); b0 = np.abs(RNG.standard_normal(128))
+    lam, eta = 0.9, 0.5
+    M, b = O.memory_write(M0, b0, K, V, W, lam, eta)
+    Mw, bw = lam * M0, lam * b0
+    for i in range(ne):
+        phi = torch.nn.functional.linear(torch.tensor(K[i]), torch.tensor(W)).numpy()
+        Mw = Mw + eta * np.outer(phi, V[i])
+        bw = bw + eta * phi ** 2
+    assert np.allclose(M, Mw, rtol=1e-12, atol=1e-14) and np.allclose(b, bw, rtol=1e-12, atol=1e-14)
+
+
+def test_memory_write_chunks_are_order_independent_and_sum_to_batch_update():
+    ne = 200
+    K = bf(RNG.standard_normal((ne, 128))); V = bf(RNG.standard_normal((ne, 128)))
+    W = bf(RNG.standard_normal((128, 128)) * 0.02)
+    M0 = RNG.standard_normal((128, 128)); b0 = np.abs(RNG.standard_normal(128))
+    # lam = 1: any partition into blocks, in any order, equals the one-shot update
+    M1, b1 = O.memory_write(M0, b0, K, V, W, 1.0, 0.5)
+    perm = RNG.permutation(ne)
+    M2, b2 = M0, b0
+    for blk in np.array_split(perm, 7):
+        M2, b2 = O.memory_write(M2, b2, K[blk], V[blk], W, 1.0, 0.5)
+    assert np.allclose(M1, M2, rtol=1e-12, atol=1e-13) and np.allclose(b1, b2, rtol=1e-12, atol=1e-13)
+    # lam < 1 is applied once per event: event(lam, E1) then event(1, E2) == event(lam, E1 u E2)
+    Ma, ba = O.memory_write(M0, b0, K, V, W, 0.9, 0.5)
+    Mb, bb = O.memory_write(M0, b0, K[:64], V[:64], W, 0.9, 0.5)
+    Mb, bb = O.memory_write(Mb, bb, K[64:], V[64:], W, 1.0, 0.5)
+    assert np.allclose(Ma, Mb, rtol=1e-12, atol=1e-13) and np.allclose(ba, bb, rtol=1e-12, atol=1e-13)
+    # nothing evicted is not an event: no decay
+    Mn, bn = O.memory_write(M0, b0, K[:0], V[:0], W, 0.5, 0.5)
+    assert Mn is M0 and bn is b0
+
+
+# ----------------------------------------------------------------------------- a5 readout
+def test_associative_recall_closed_form():
+    # W_theta = I, one evicted token k = e_j with value v, lam = 1:
+    # M = eta e_j v^T, b = eta e_j, so reading with q = k returns v (eps -> 0)
+    I = np.eye(128); j = 17
+    k = np.zeros((1, 128)); k[0, j] = 1.0
+    v = bf(RNG.standard_normal((1, 128)))
+    M, b = O.memory_write(np.zeros((128, 128)), np.zeros(128), k, v, I, 1.0, 0.5)
+    m = O.memory_read(k, M, b, I, 1e-30)
+    assert np.allclose(m[0], v[0], rtol=1e-12)
+    # a transposed state would return v_j e_j instead
+    assert not np.allclose(O.memory_read(k, M.T, b, I, 1e-30)[0], v[0])
+
+
+def test_single_token_readout_closed_form_and_eta_invariance():
+    W = bf(RNG.standard_normal((128, 128)) * 0.1)
+    k = bf(RNG.standard_normal((1, 128))); v = bf(RNG.standard_normal((1, 128)))
+    q = bf(RNG.standard_normal((3, 128)))
+    fk = np.array([sum(W[c, d] * k[0, d] for d in range(128)) for c in range(128)])
+    for eta in (0.5, 3.0):
+        M, b = O.memory_write(np.zeros((128, 128)), np.zeros(128), k, v, W, 0.7, eta)
+        m = O.memory_read(q, M, b, W, 0.0)
+        for r in range(3):
+            fq = np.array([sum(W[c, d] * q[r, d] for d in range(128)) for c in range(128)])
+            want = (fq @ fk) * v[0] / np.sum(fq ** 2 * fk ** 2)
+            assert np.allclose(m[r], want, rtol=1e-10)
+
+
+def test_empty_memory_reads_zero_and_closed_gate_falls_back_to_attention():
+    q = bf(RNG.standard_normal((4, 128)))
+    W = bf(RNG.standard_normal((128, 128)) * 0.02)
+    m = O.memory_read(q, np.zeros((128, 128)), np.zeros(128), W, 1e-6)
+    assert np.all(m == 0.0)
+    g = O.read_gate(q, bf(RNG.standard_normal(128) * 0.02), -1e4)
+    assert np.all(g == 0.0)
+    o = RNG.standard_normal((4, 128))
+    out, res = O.fuse(o, g, RNG.standard_normal((4, 128)))
+    assert np.array_equal(out, O.round_bf16(o)) and np.all(res == 0.0)
+    g1 = O.read_gate(q, np.zeros(128), 0.0)
+    assert np.all(g1 == 0.5)
+
+
+# ----------------------------------------------------------------------------- a5 attention
+@pytest.mark.parametrize("n", [1, 5, 300])
+def test_attend_equals_library_softmax_attention(n):
+    g, D = 4, 128
+    q = bf(RNG.standard_normal((g, D))); K = bf(RNG.standard_normal((n, D))); V = bf(RNG.standard_normal((n, D)))
+    scale = 1 / math.sqrt(D)
+    got = O.attend(q, K, V, scale)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.tensor(q)[None], torch.tensor(K)[None], torch.tensor(V)[None], scale=scale)[0].numpy()
+    assert np.allclose(got, want, rtol=1e-10, atol=1e-12)
+    perm = RNG.permutation(n)
+    assert np.allclose(O.attend(q, K[perm], V[perm], scale), got, rtol=1e-12, atol=1e-14)
+    assert np.all(O.attend(q, K[:0], V[:0], scale) == 0)
+
+
+# ----------------------------------------------------------------------------- a4 compaction
+def test_compaction_moves_fill_holes():
+    for n, B in [(10, 4), (33, 32), (64, 1), (20, 20), (7, 0)]:
+        for _ in range(20):
+            keep = np.sort(RNG.permutation(n)[:B]); evict = np.setdiff1d(np.arange(n), keep)
+            slots = list(range(n))
+            moves = O.compaction_moves(keep, evict)
+            assert all(s >= B > d for s, d in moves)
+            assert [s for s, _ in moves] == sorted(s for s, _ in moves)
+            assert [d for _, d in moves] == sorted(d for _, d in moves)
+            for s, d in moves:
+                slots[d] = slots[s]
+            assert sorted(slots[:B]) == list(keep)
+
+
+# ----------------------------------------------------------------------------- whole layer
+def _small_layer(context=96, budget=32, steps=3, name="cfg1", batch=None):
+    w = WORKLOADS[name].scaled(context=context, budget=budget, decode_steps=steps,
+                               batch=WORKLOADS[name].batch if batch is None else batch)
+    K, V, Q = token_stream(w, 0)
+    return w, f64(K), f64(V), f64(Q)
+
+
+def _prefill(layer, w, K, V, Q, budget, lam=None, eta=None):
+    L = w.context
+    pos = np.tile(np.arange(L, dtype=np.int32), (w.batch, 1))
+    q = Q[:, :L]
+    return layer.step(K[:, :, :L], V[:, :, :L], pos, q, q.reshape(w.batch, L, -1), pos,
+                      Q[:, L - 1], budget, w.lam if lam is None else lam, w.eta if eta is None else eta)
+
+
+def test_budget_at_least_context_is_plain_attention_and_leaves_memory_untouched():
+    w, K, V, Q = _small_layer()
+    layer = make_oracle_layer(w)
+    scores, keep, evict, out, res = _prefill(layer, w, K, V, Q, budget=w.context + 5)
+    assert all(len(e) == 0 for row in evict for e in row)
+    assert np.all(layer.M == 0) and np.all(layer.b == 0) and np.all(res == 0)
+    assert np.all(layer.len == w.context)
+    L, g = w.context, w.group
+    qh = torch.tensor(Q[:, L - 1]).view(w.batch, w.n_kv_heads, g, w.head_dim)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        qh, torch.tensor(K[:, :, :L]), torch.tensor(V[:, :, :L]), scale=1 / math.sqrt(w.head_dim)).numpy()
+    assert np.array_equal(out, O.round_bf16(want).reshape(out.shape)) or \
+        np.max(np.abs(out - want)) <= 2 ** -8 * np.max(np.abs(want))
+
+
+def test_trajectory_indices_do_not_depend_on_values_or_memory():
+    w, K, V, Q = _small_layer(context=80, budget=24, steps=4)
+    L = w.context
+
+    def run(Vx, eta):
+        layer = make_oracle_layer(w)
+        traj = []
+        _, keep, evict, _, _ = _prefill(layer, w, K, Vx, Q, w.budget, eta=eta)
+        traj.append((keep, evict))
+        for t in range(L, L + w.decode_steps):
+            p = np.full((w.batch, 1), t, np.int32)
+            q = Q[:, t:t + 1]
+            _, keep, evict, _, _ = layer.step(K[:, :, t:t + 1], Vx[:, :, t:t + 1], p, q,
+                                              q.reshape(w.batch, 1, -1), p, Q[:, t], w.budget, w.lam, eta)
+            traj.append((keep, evict))
+        return traj, layer
+
+    t1, l1 = run(V, 0.5)
+    t2, l2 = run(V[:, :, ::-1].copy(), 2.0)
+    for (k1, e1), (k2, e2) in zip(t1, t2):
+        for bi, hi in l1.units():
+            assert np.array_equal(k1[bi][hi], k2[bi][hi]) and np.array_equal(e1[bi][hi], e2[bi][hi])
+    assert np.all(l1.len == w.budget)
+    # decode steps evict exactly one entry and the compacted cache holds exactly the kept set
+    for (k, e) in t1[1:]:
+        assert all(len(x) == 1 for row in e for x in row)
+    for bi, hi in l1.units():
+        assert len(set(l1.pos[bi, hi, :w.budget].tolist())) == w.budget
+        assert set(range(4)) <= set(l1.pos[bi, hi, :w.budget].tolist())
+
+
+def test_compacted_cache_is_the_kept_multiset():
+    w, K, V, Q = _small_layer(context=70, budget=20, steps=0)
+    layer = make_oracle_layer(w)
+    ref = make_oracle_layer(w)
+    L = w.context
+    pos = np.tile(np.arange(L, dtype=np.int32), (w.batch, 1))
+    ref.append_kv(K[:, :, :L], V[:, :, :L], pos)
+    q = Q[:, :L]
+    ref.index_score(q, q.reshape(w.batch, L, -1), pos)
+    _, keep, evict, _, _ = _prefill(layer, w, K, V, Q, w.budget)
+    for bi, hi in layer.units():
+        kept = keep[bi][hi]
+        got = {int(layer.pos[bi, hi, s]): (layer.K[bi, hi, s].tobytes(), layer.V[bi, hi, s].tobytes(),
+                                           layer.Kidx[bi, hi, s].tobytes()) for s in range(w.budget)}
+        want = {int(ref.pos[bi, hi, s]): (ref.K[bi, hi, s].tobytes(), ref.V[bi, hi, s].tobytes(),
+                                          ref.Kidx[bi, hi, s].tobytes()) for s in kept}
+        assert got == want
+
+
+def test_planted_high_norm_keys_change_attention_but_not_selection():
+    w = WORKLOADS["cfg2"].scaled(context=128, budget=32, decode_steps=0, batch=1, n_layers=1)
+    K, V, Q = (f64(t) for t in token_stream(w, 0))
+    w_plain = w.scaled(dist="normal")
+    K0, _, _ = (f64(t) for t in token_stream(w_plain, 0))
+    ratio = np.linalg.norm(K, axis=-1) / np.linalg.norm(K0, axis=-1)
+    assert int(np.sum(ratio[0, 0] > 3.9)) == int(0.05 * 128)             # exactly floor(5% of L) planted
+    la, lb = make_oracle_layer(w), make_oracle_layer(w)
+    _, ka, _, oa, _ = _prefill(la, w, K, V, Q, w.budget)
+    _, kb, _, ob, _ = _prefill(lb, w, K0, V, Q, w.budget)
+    same = np.mean([len(set(ka[0][h]) & set(kb[0][h])) / w.budget for h in range(w.n_kv_heads)])
+    assert same > 0.95                                                   # up to bf16 ties in the indexer keys
+    assert np.max(np.abs(oa - ob)) > 1e-2
