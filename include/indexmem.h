@@ -1,0 +1,173 @@
+/*
+ * indexmem.h - C ABI of libindexmem: the bounded-budget KV step of IndexMem on one MI355X.
+ *
+ * One attention layer keeps, per unit (batch element b, KV head h), a slot array of cached
+ * keys / values, their indexer keys and token positions, a live length, and a fixed-size
+ * latent memory state (M, b).  A step of the path is
+ *     append new (k, v)  ->  im_index_score  ->  im_topb_select  ->  im_memory_update
+ *                        ->  im_compact_kv   ->  im_decode_attn_with_readout
+ * i.e. the score -> TopK -> Gather eviction framework of Section 2.2 of the paper with the
+ * learnable indexer of Section 3.1 as the score function, the online latent-memory write of
+ * Section 3.2 for the evicted entries, and decode attention over the retained entries plus
+ * the gated memory readout (Eq. latent_residual_fuse).
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless a comment says "host".  The caller owns all
+ *     device memory, including the workspace; the library never allocates device memory.
+ *   - `stream` is a hipStream_t passed as void*.  Calls only enqueue work on it; they do not
+ *     synchronise (im_query_status is the one exception) and may be captured in a HIP graph.
+ *   - bf16 tensors are raw 16-bit patterns (uint16_t).  Tensors are dense, row-major, in the
+ *     shapes given, with no padding.
+ *   - Return value: IM_OK, or a negative error.  Argument validation is done on the host
+ *     before anything is enqueued, so an invalid call leaves all buffers untouched.
+ *     im_last_error() gives a text for the last error of a handle.
+ *   - Calls on one handle must not overlap (they share the workspace); different layers may
+ *     share a handle when their calls are issued in stream order.
+ */
+#ifndef INDEXMEM_H
+#define INDEXMEM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define IM_OK 0
+#define IM_ERR_INVALID_ARG (-1)  /* null pointer, shape or range violation                  */
+#define IM_ERR_UNSUPPORTED (-2)  /* valid in principle, not built (e.g. head_dim != 128)     */
+#define IM_ERR_LAUNCH (-3)       /* a HIP call failed; see im_last_error()                   */
+
+/* bits of the device-side status word returned by im_query_status() */
+#define IM_STATUS_APPEND_OVERFLOW 1 /* an append would have exceeded `capacity`; it was dropped */
+#define IM_STATUS_LIVE_EXCEEDED 2   /* a unit's length exceeded the im_set_max_live() promise   */
+
+typedef struct im_handle im_handle; /* opaque: validated config + workspace pointer, host memory */
+
+/* Shape of one layer's state and the method's constants. */
+typedef struct im_config {
+  int32_t batch;        /* B                                                                  */
+  int32_t n_q_heads;    /* H   (multiple of n_kv_heads; H / H_kv <= 8)                        */
+  int32_t n_kv_heads;   /* H_kv                                                               */
+  int32_t head_dim;     /* d_head, must be 128                                                */
+  int32_t capacity;     /* C: slots per unit in K, V, Kidx, pos, scores and the index lists   */
+  int32_t n_idx_heads;  /* H_index (1..16); the paper uses H / 4 (Section 4)                  */
+  int32_t idx_dim;      /* d_index, must be 64                                                */
+  int32_t mem_dim;      /* d_mem, must be 128                                                 */
+  int32_t gate_in_dim;  /* width of the gate input X_s (multiple of 16)                       */
+  int32_t n_sink;       /* first token positions always kept (4 in the paper, Section 4)      */
+  int32_t n_recent;     /* newest positions always kept (0: none)                             */
+  int32_t fold_block;   /* evicted rows are folded into the memory in blocks of this (64)     */
+  int32_t max_queries;  /* largest n_q a call to im_index_score will pass                     */
+  float rms_eps;        /* RMSNorm epsilon of the indexer's QK-Norm                           */
+  float mem_eps;        /* epsilon of the readout denominator (Eq. latent_readout)            */
+  float softmax_scale;  /* attention logit scale, 1/sqrt(d_head)                              */
+} im_config;
+
+/* Slow weights of one layer (device pointers, bf16, read-only). */
+typedef struct im_params {
+  const void* Uq;       /* [H_index * d_index, H * d_head]  query down-projection            */
+  const void* G;        /* [H_index, gate_in_dim]           head gate                        */
+  const void* Uk;       /* [d_index, d_head]                key projection, shared by heads  */
+  const void* norm_q_w; /* [d_index] RMSNorm weight of indexer queries, or NULL for ones     */
+  const void* norm_k_w; /* [d_index] RMSNorm weight of indexer keys, or NULL for ones        */
+  const void* Wtheta;   /* [d_mem, d_head] Linear_theta of the memory (no bias)              */
+  const void* wg;       /* [d_head] weight of the read gate g(q) = sigmoid(wg . q + cg)      */
+  float cg;             /* bias of the read gate                                             */
+} im_params;
+
+/* State of one layer (device pointers, read and written in place). */
+typedef struct im_state {
+  void* K;              /* [B, H_kv, C, d_head]  bf16                                        */
+  void* V;              /* [B, H_kv, C, d_head]  bf16                                        */
+  void* Kidx;           /* [B, H_kv, C, d_index] bf16: normalised indexer keys               */
+  int32_t* pos;         /* [B, H_kv, C] token position of each slot                          */
+  int32_t* len;         /* [B, H_kv] live slots: [0, len)                                    */
+  int32_t* n_projected; /* [B, H_kv] slots [0, n_projected) have a valid Kidx row            */
+  float* M;             /* [B, H_kv, d_mem, d_head] fp32 fast weights                        */
+  float* b;             /* [B, H_kv, d_mem]         fp32 stabiliser                          */
+} im_state;
+
+/* Bytes of workspace a handle for `cfg` needs (0 if cfg is invalid).  Host only. */
+size_t im_workspace_bytes(const im_config* cfg);
+
+/* Validate `cfg` (host pointer) and create a handle that uses `workspace` (device pointer,
+ * 256-byte aligned, at least im_workspace_bytes(cfg) bytes, contents arbitrary).  Host only:
+ * touches no GPU.  The first enqueuing call clears the part of the workspace that needs it. */
+int32_t im_create(const im_config* cfg, void* workspace, size_t workspace_bytes, im_handle** out);
+void im_destroy(im_handle* h);
+const char* im_last_error(const im_handle* h);
+
+/* Promise that no unit's `len` exceeds `max_live` until the next call of this function;
+ * kernels size their grids by it (default: capacity).  A violated promise sets
+ * IM_STATUS_LIVE_EXCEEDED and the entries beyond max_live are ignored. */
+int32_t im_set_max_live(im_handle* h, int32_t max_live);
+
+/* Copy the device status word to *status_host (host pointer), clear it, and WAIT for `stream`. */
+int32_t im_query_status(im_handle* h, int32_t* status_host, void* stream);
+
+/* Helper: new tokens enter the cache.  Copies k_new, v_new [B, H_kv, n_new, d_head] (bf16) to
+ * slots [len, len + n_new) of every unit, pos_new [B, n_new] to their positions, and adds n_new
+ * to len.  A unit with len + n_new > capacity is left unchanged and IM_STATUS_APPEND_OVERFLOW is
+ * set.  1 <= n_new <= capacity. */
+int32_t im_append_kv(im_handle* h, const im_state* st, const void* k_new, const void* v_new,
+                     const int32_t* pos_new, int32_t n_new, void* stream);
+
+/* Step a1, the indexer (Section 3.1 "Architecture"; Algorithm 1, `indexer`).
+ *  (i)  keys: every slot in [n_projected, len) gets Kidx = bf16(RMSNorm(Uk K_slot)); then
+ *       n_projected = len.
+ *  (ii) queries, once per (b, s) and shared by the KV heads: q_s = RMSNorm per indexer head of
+ *       Uq flatten(q_new[b, s]) (kept in fp32), alpha_s = G x_gate[b, s] / sqrt(H_index d_index).
+ *  (iii) scores_out[b, h, t] = max over s with q_pos[b, s] >= pos[b, h, t] of
+ *        sum_j alpha_{s,j} ReLU(q_{s,j} . Kidx[b, h, t]),  -inf if no query may see slot t.
+ * q_new [B, n_q, H, d_head] bf16; x_gate [B, n_q, gate_in_dim] bf16; q_pos [B, n_q] int32;
+ * scores_out [B, H_kv, C] fp32, written for slots < len only.  1 <= n_q <= max_queries.
+ * All arithmetic that feeds the stored bf16 / fp32 values is fp64. */
+int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, const void* q_new,
+                       const void* x_gate, const int32_t* q_pos, int32_t n_q, float* scores_out,
+                       void* stream);
+
+/* Step a2, per-unit top-B (Section 2.2, I = TopK(S, L'); sink retention: Section 4 "Models and
+ * Evaluation Setup").  Keeps n_keep = min(budget, len) slots: those whose position is < n_sink
+ * or among the n_recent newest count as score +inf; the order is score descending, then position
+ * ascending, then slot ascending (-0 equals +0; NaN scores are a caller error).
+ * keep_idx / evict_idx [B, H_kv, C] int32 receive the kept / evicted slots in ascending order,
+ * n_keep / n_evict [B, H_kv] their counts (n_keep + n_evict = len).
+ * n_sink + n_recent <= budget <= capacity. */
+int32_t im_topb_select(im_handle* h, const float* scores, const im_state* st, int32_t budget,
+                       int32_t* keep_idx, int32_t* evict_idx, int32_t* n_keep, int32_t* n_evict,
+                       void* stream);
+
+/* Step a3, latent-memory write (Eqs. latent_write_A, latent_write_b; Algorithm 1, `mem_write`):
+ * for every unit with n_evict > 0, with phi_i = Wtheta K_i over the evicted slots i,
+ *     M <- lambda M + eta sum_i phi_i V_i^T,     b <- lambda b + eta sum_i phi_i * phi_i.
+ * One call is one eviction event: lambda is applied once.  Units with n_evict = 0 are untouched.
+ * Reads the evicted rows through evict_idx from the cache as it is BEFORE im_compact_kv.
+ * 0 < lambda <= 1, eta > 0. */
+int32_t im_memory_update(im_handle* h, const im_params* p, const im_state* st,
+                         const int32_t* evict_idx, const int32_t* n_evict, float lambda, float eta,
+                         void* stream);
+
+/* Step a4, the Gather of Section 2.2 in place: kept entries in slots >= n_keep move, in ascending
+ * order, into the evicted slots < n_keep, in ascending order (rows of K, V, Kidx and pos); then
+ * len = n_projected = n_keep.  Requires n_projected == len on entry (im_index_score was called
+ * after the last append) and the lists of im_topb_select for the current cache. */
+int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
+                      const int32_t* n_keep, const int32_t* evict_idx, const int32_t* n_evict,
+                      void* stream);
+
+/* Step a5, decode attention over the retained entries plus the gated memory readout
+ * (Section 2.1 "KV Caching"; Eqs. latent_readout, latent_residual_fuse): for query head j of
+ * KV head h = j / (H / H_kv),
+ *     o_attn = softmax(softmax_scale q_j K^T) V over slots [0, len)   (0 if len = 0)
+ *     phi = Wtheta q_j,  m = phi^T M / (sum_c phi_c^2 b_c + mem_eps),  g = sigmoid(wg . q_j + cg)
+ *     out[b, j] = bf16(o_attn + g m);   readout_dbg[b, j] = g m  (fp32; may be NULL).
+ * q, out [B, H, d_head] bf16; readout_dbg [B, H, d_head] fp32. */
+int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_state* st,
+                                    const void* q, void* out, float* readout_dbg, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INDEXMEM_H */

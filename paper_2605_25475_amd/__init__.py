@@ -1,0 +1,10 @@
+"""MI355X-native bounded-budget KV step of IndexMem: HIP kernels behind libindexmem's C ABI
+(include/indexmem.h) and a thin ctypes binding with the same call names."""
+from .binding import (  # noqa: F401
+    Config, Params, State, Handle, IndexMemError, load_library, EXPORTS,
+    im_set_max_live, im_query_status, im_append_kv, im_index_score, im_topb_select,
+    im_memory_update, im_compact_kv, im_decode_attn_with_readout,
+    IM_OK, IM_ERR_INVALID_ARG, IM_ERR_UNSUPPORTED, IM_ERR_LAUNCH,
+    IM_STATUS_APPEND_OVERFLOW, IM_STATUS_LIVE_EXCEEDED,
+)
+from .layer import Layer  # noqa: F401

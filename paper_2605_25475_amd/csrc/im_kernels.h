@@ -1,0 +1,789 @@
+// Kernels of the step-by-step path (one or more launches per entry point of indexmem.h).
+// gfx950, wave64.  All index arithmetic that can exceed 2^31 is done in size_t.
+#pragma once
+#include "im_device.h"
+
+// ------------------------------------------------------------------------------------------
+// workspace clear (status word + counters); a kernel so that callers may capture the stream
+// ------------------------------------------------------------------------------------------
+__global__ void k_fill_i32(int32_t* p, int n, int32_t v) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ------------------------------------------------------------------------------------------
+// helper: append rows
+// ------------------------------------------------------------------------------------------
+// grid (ceil(n_new*16/256), units); one thread moves one 16-byte chunk of a K row and of a V row
+__global__ __launch_bounds__(256) void k_append_rows(bf16_t* __restrict__ K, bf16_t* __restrict__ V,
+                                                     int32_t* __restrict__ pos,
+                                                     const int32_t* __restrict__ len,
+                                                     const bf16_t* __restrict__ k_new,
+                                                     const bf16_t* __restrict__ v_new,
+                                                     const int32_t* __restrict__ pos_new, int n_new,
+                                                     int H_kv, int C) {
+  const int unit = blockIdx.y;
+  const int idx = blockIdx.x * 256 + threadIdx.x;
+  const int row = idx >> 4, ch = idx & 15;
+  if (row >= n_new) return;
+  const int n = len[unit];
+  if (n + n_new > C) return;  // dropped; k_append_len raises the status bit
+  const size_t src = ((size_t)unit * n_new + row) * IM_D + ch * 8;
+  const size_t dst = ((size_t)unit * C + n + row) * IM_D + ch * 8;
+  *(uint4*)(K + dst) = *(const uint4*)(k_new + src);
+  *(uint4*)(V + dst) = *(const uint4*)(v_new + src);
+  if (ch == 0) pos[(size_t)unit * C + n + row] = pos_new[(size_t)(unit / H_kv) * n_new + row];
+}
+
+__global__ void k_append_len(int32_t* __restrict__ len, int n_units, int n_new, int C,
+                             int32_t* __restrict__ status) {
+  int u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= n_units) return;
+  int n = len[u];
+  if (n + n_new > C)
+    atomicOr(status, 1);
+  else
+    len[u] = n + n_new;
+}
+
+// ------------------------------------------------------------------------------------------
+// a1 (i): indexer keys of the slots not yet projected:  Kidx = bf16(RMSNorm(Uk K_slot)), fp64
+// ------------------------------------------------------------------------------------------
+// grid (tiles of 64 rows, units).  Thread t: row t/4 of the tile, outputs c = t%4 + 4 i.
+__global__ __launch_bounds__(256) void k_project_keys(const bf16_t* __restrict__ K,
+                                                      bf16_t* __restrict__ Kidx,
+                                                      const int32_t* __restrict__ len,
+                                                      const int32_t* __restrict__ n_projected,
+                                                      const bf16_t* __restrict__ Uk,
+                                                      const bf16_t* __restrict__ norm_w, int C,
+                                                      int max_live, float rms_eps,
+                                                      int32_t* __restrict__ status) {
+  __shared__ float Ks[64][129];
+  __shared__ float Us[64][129];
+  const int unit = blockIdx.y, tid = threadIdx.x;
+  int n = len[unit];
+  if (n > max_live) {
+    if (tid == 0 && blockIdx.x == 0) atomicOr(status, 2);
+    n = max_live;
+  }
+  const int row0 = n_projected[unit] + blockIdx.x * 64;
+  if (row0 >= n) return;
+  const int rows = min(64, n - row0);
+  // stage Uk (64 x 128) and the K tile, 8 bf16 per thread per pass
+  for (int i = tid; i < 64 * 16; i += 256) {
+    const int r = i >> 4, ch = i & 15;
+    uint4 u = *(const uint4*)(Uk + r * IM_D + ch * 8);
+    float* d = &Us[r][ch * 8];
+    d[0] = bf_lo(u.x); d[1] = bf_hi(u.x); d[2] = bf_lo(u.y); d[3] = bf_hi(u.y);
+    d[4] = bf_lo(u.z); d[5] = bf_hi(u.z); d[6] = bf_lo(u.w); d[7] = bf_hi(u.w);
+    uint4 k = make_uint4(0, 0, 0, 0);
+    if (r < rows) k = *(const uint4*)(K + ((size_t)unit * C + row0 + r) * IM_D + ch * 8);
+    float* e = &Ks[r][ch * 8];
+    e[0] = bf_lo(k.x); e[1] = bf_hi(k.x); e[2] = bf_lo(k.y); e[3] = bf_hi(k.y);
+    e[4] = bf_lo(k.z); e[5] = bf_hi(k.z); e[6] = bf_lo(k.w); e[7] = bf_hi(k.w);
+  }
+  __syncthreads();
+  const int r = tid >> 2, og = tid & 3;
+  double acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.0;
+  for (int d = 0; d < IM_D; ++d) {
+    const double kd = (double)Ks[r][d];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = fma(kd, (double)Us[og + 4 * i][d], acc[i]);
+  }
+  double ss = 0.0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) ss = fma(acc[i], acc[i], ss);
+  ss += __shfl_xor(ss, 1, 64);
+  ss += __shfl_xor(ss, 2, 64);
+  const double rr = sqrt(ss / (double)IM_DI + (double)rms_eps);
+  if (r < rows) {
+    bf16_t* out = Kidx + ((size_t)unit * C + row0 + r) * IM_DI;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int c = og + 4 * i;
+      const double w = norm_w ? (double)bf2f(norm_w[c]) : 1.0;
+      out[c] = d2bf_rne(acc[i] / rr * w);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// a1 (ii): query side.  C[m][n] = sum_k A[m][k] B[n][k], bf16 inputs, fp64 accumulate/output.
+// ------------------------------------------------------------------------------------------
+// Tiled version for many rows (prefill events).  grid (ceil(N/64), ceil(M/64)); K % 16 == 0.
+__global__ __launch_bounds__(256) void k_gemm_nt_f64(const bf16_t* __restrict__ A,
+                                                     const bf16_t* __restrict__ B,
+                                                     double* __restrict__ Cm, int M, int N, int Kd) {
+  __shared__ double As[16][64 + 2];
+  __shared__ double Bs[16][64 + 2];
+  const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+  const int lr = tid >> 2, lc = (tid & 3) * 4;  // loader: row lr of the tile, k offset lc..lc+3
+  double acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
+  for (int k0 = 0; k0 < Kd; k0 += 16) {
+    uint2 a = make_uint2(0, 0), b = make_uint2(0, 0);
+    if (m0 + lr < M) a = *(const uint2*)(A + (size_t)(m0 + lr) * Kd + k0 + lc);
+    if (n0 + lr < N) b = *(const uint2*)(B + (size_t)(n0 + lr) * Kd + k0 + lc);
+    __syncthreads();
+    As[lc + 0][lr] = (double)bf_lo(a.x); As[lc + 1][lr] = (double)bf_hi(a.x);
+    As[lc + 2][lr] = (double)bf_lo(a.y); As[lc + 3][lr] = (double)bf_hi(a.y);
+    Bs[lc + 0][lr] = (double)bf_lo(b.x); Bs[lc + 1][lr] = (double)bf_hi(b.x);
+    Bs[lc + 2][lr] = (double)bf_lo(b.y); Bs[lc + 3][lr] = (double)bf_hi(b.y);
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+      double av[4], bv[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) av[i] = As[k][ty * 4 + i];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) bv[j] = Bs[k][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fma(av[i], bv[j], acc[i][j]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int m = m0 + ty * 4 + i;
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int n = n0 + tx * 4 + j;
+      if (n < N) Cm[(size_t)m * N + n] = acc[i][j];
+    }
+  }
+}
+
+// Few rows (decode): every workgroup owns 2 rows of B and streams them once for all M rows of A.
+// grid (ceil(N/2)); Kd % 8 == 0.
+__global__ __launch_bounds__(256) void k_gemv_nt_f64(const bf16_t* __restrict__ A,
+                                                     const bf16_t* __restrict__ B,
+                                                     double* __restrict__ Cm, int M, int N, int Kd) {
+  __shared__ double red[4][16];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int n0 = blockIdx.x * 2;
+  for (int mb = 0; mb < M; mb += 8) {
+    double acc[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i][0] = acc[i][1] = 0.0;
+    for (int k = tid * 8; k < Kd; k += 256 * 8) {
+      float bv[2][8];
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        uint4 u = make_uint4(0, 0, 0, 0);
+        if (n0 + r < N) u = *(const uint4*)(B + (size_t)(n0 + r) * Kd + k);
+        bv[r][0] = bf_lo(u.x); bv[r][1] = bf_hi(u.x); bv[r][2] = bf_lo(u.y); bv[r][3] = bf_hi(u.y);
+        bv[r][4] = bf_lo(u.z); bv[r][5] = bf_hi(u.z); bv[r][6] = bf_lo(u.w); bv[r][7] = bf_hi(u.w);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (mb + i < M) {
+          uint4 u = *(const uint4*)(A + (size_t)(mb + i) * Kd + k);
+          float av[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
+                         bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            acc[i][0] = fma((double)av[e], (double)bv[0][e], acc[i][0]);
+            acc[i][1] = fma((double)av[e], (double)bv[1][e], acc[i][1]);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      acc[i][0] = wave_sum_d(acc[i][0]);
+      acc[i][1] = wave_sum_d(acc[i][1]);
+    }
+    __syncthreads();
+    if (lane == 0) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { red[w][2 * i] = acc[i][0]; red[w][2 * i + 1] = acc[i][1]; }
+    }
+    __syncthreads();
+    if (tid < 16) {
+      const int i = tid >> 1, r = tid & 1;
+      if (mb + i < M && n0 + r < N)
+        Cm[(size_t)(mb + i) * N + n0 + r] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
+    }
+  }
+}
+
+// RMSNorm of every indexer query head in place: y[m][j][0..63] -> fp32-rounded q, kept as fp64.
+// One wave per (m, j).  grid (ceil(rows/4)) with rows = M * H_idx.
+__global__ __launch_bounds__(256) void k_qnorm(double* __restrict__ y, int rows,
+                                               const bf16_t* __restrict__ norm_w, float rms_eps) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const double v = y[(size_t)row * IM_DI + lane];
+  const double ss = wave_sum_d(v * v);
+  const double rr = sqrt(ss / (double)IM_DI + (double)rms_eps);
+  const double w = norm_w ? (double)bf2f(norm_w[lane]) : 1.0;
+  y[(size_t)row * IM_DI + lane] = (double)(float)(v / rr * w);
+}
+
+// alpha = fp32(G x / sqrt(H_idx d_idx)), kept as fp64
+__global__ void k_alpha_scale(double* __restrict__ a, int n, double denom) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) a[i] = (double)(float)(a[i] / denom);
+}
+
+// ------------------------------------------------------------------------------------------
+// a1 (iii): scores.  One thread per cached key; the queries' features are wave-uniform operands.
+// ------------------------------------------------------------------------------------------
+// grid (ceil(max_live/256), units)
+__global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
+                                               const int32_t* __restrict__ pos,
+                                               const int32_t* __restrict__ len,
+                                               int32_t* __restrict__ n_projected,
+                                               const double* __restrict__ qhat,
+                                               const double* __restrict__ alpha,
+                                               const int32_t* __restrict__ q_pos, int n_q, int H_kv,
+                                               int C, int H_idx, int max_live,
+                                               float* __restrict__ scores) {
+  __shared__ int s_min[4];
+  const int unit = blockIdx.y, tid = threadIdx.x;
+  const int b = unit / H_kv;
+  const int n = min(len[unit], max_live);
+  if (blockIdx.x == 0 && tid == 0) n_projected[unit] = n;  // the projection kernel ran before
+  const int t0 = blockIdx.x * 256;
+  if (t0 >= n) return;
+  const int slot = t0 + tid;
+  const bool valid = slot < n;
+  const int sl = valid ? slot : n - 1;
+  double k[IM_DI];
+  {
+    const uint4* src = (const uint4*)(Kidx + ((size_t)unit * C + sl) * IM_DI);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      uint4 u = src[i];
+      k[8 * i + 0] = (double)bf_lo(u.x); k[8 * i + 1] = (double)bf_hi(u.x);
+      k[8 * i + 2] = (double)bf_lo(u.y); k[8 * i + 3] = (double)bf_hi(u.y);
+      k[8 * i + 4] = (double)bf_lo(u.z); k[8 * i + 5] = (double)bf_hi(u.z);
+      k[8 * i + 6] = (double)bf_lo(u.w); k[8 * i + 7] = (double)bf_hi(u.w);
+    }
+  }
+  const int mypos = pos[(size_t)unit * C + sl];
+  // smallest position in this tile: queries older than it see none of the tile's keys
+  int mn = valid ? mypos : INT_MAX;
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mn = min(mn, __shfl_xor(mn, o, 64));
+  if ((tid & 63) == 0) s_min[tid >> 6] = mn;
+  __syncthreads();
+  const int tile_min = min(min(s_min[0], s_min[1]), min(s_min[2], s_min[3]));
+  double imp = -INFINITY;
+  for (int s = 0; s < n_q; ++s) {
+    const int qp = q_pos[(size_t)b * n_q + s];
+    if (qp < tile_min) continue;
+    const double* __restrict__ qh = qhat + ((size_t)b * n_q + s) * H_idx * IM_DI;
+    const double* __restrict__ al = alpha + ((size_t)b * n_q + s) * H_idx;
+    double a = 0.0;
+    for (int j = 0; j < H_idx; ++j) {
+      double z0 = 0.0, z1 = 0.0;
+#pragma unroll
+      for (int c = 0; c < IM_DI; c += 2) {
+        z0 = fma(qh[j * IM_DI + c], k[c], z0);
+        z1 = fma(qh[j * IM_DI + c + 1], k[c + 1], z1);
+      }
+      a = fma(al[j], fmax(z0 + z1, 0.0), a);
+    }
+    if (mypos <= qp) imp = fmax(imp, a);
+  }
+  if (valid) scores[(size_t)unit * C + slot] = (float)imp;
+}
+
+// ------------------------------------------------------------------------------------------
+// a2: per-unit top-B by radix selection on (score key, position), then an ordered emission
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned block_excl_scan_1024(bool flag, unsigned* wsum, unsigned& total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const unsigned long long bal = __ballot(flag);
+  const unsigned inwave = __popcll(bal & ((1ull << lane) - 1ull));
+  if (lane == 0) wsum[w] = __popcll(bal);
+  __syncthreads();
+  unsigned off = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const unsigned v = wsum[i];
+    if (i < w) off += v;
+    tot += v;
+  }
+  __syncthreads();
+  total = tot;
+  return off + inwave;
+}
+
+// grid (units), 1024 threads
+__global__ __launch_bounds__(1024) void k_select(const float* __restrict__ scores,
+                                                 const int32_t* __restrict__ pos,
+                                                 const int32_t* __restrict__ len, int C, int max_live,
+                                                 int budget, int n_sink, int n_recent,
+                                                 int32_t* __restrict__ keep_idx,
+                                                 int32_t* __restrict__ evict_idx,
+                                                 int32_t* __restrict__ n_keep,
+                                                 int32_t* __restrict__ n_evict) {
+  __shared__ unsigned hist[256];
+  __shared__ unsigned sh_prefix, sh_rem, sh_cnt;
+  __shared__ int sh_red[16];
+  __shared__ unsigned wsum[16];
+  const int unit = blockIdx.x, tid = threadIdx.x;
+  const int n = min(len[unit], max_live);
+  const float* sc = scores + (size_t)unit * C;
+  const int32_t* ps = pos + (size_t)unit * C;
+  int32_t* keep = keep_idx + (size_t)unit * C;
+  int32_t* evict = evict_idx + (size_t)unit * C;
+  const int k = min(budget, n);
+
+  int maxpos = INT_MIN;
+  if (n_recent > 0) {
+    int m = INT_MIN;
+    for (int i = tid; i < n; i += 1024) m = max(m, ps[i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = max(m, __shfl_xor(m, o, 64));
+    if ((tid & 63) == 0) sh_red[tid >> 6] = m;
+    __syncthreads();
+    for (int i = 0; i < 16; ++i) maxpos = max(maxpos, sh_red[i]);
+    __syncthreads();
+  }
+  auto key_of = [&](int i) -> uint32_t {
+    const int p = ps[i];
+    const bool forced = (p < n_sink) || (n_recent > 0 && (long long)p > (long long)maxpos - n_recent);
+    return forced ? IM_KEY_PINF : score_key(sc[i]);
+  };
+
+  // mode: 0 = keep all, 1 = keep none, 2 = threshold
+  uint32_t T = 0, P = 0xffffffffu;
+  unsigned rem2 = 0;
+  bool all_ties = true;
+  const int mode = (k >= n) ? 0 : (k == 0 ? 1 : 2);
+  if (mode == 2) {
+    // k-th largest score key
+    if (tid == 0) { sh_prefix = 0; sh_rem = (unsigned)k; }
+    uint32_t mask = 0;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      const uint32_t prefix = sh_prefix;
+      for (int i = tid; i < n; i += 1024) {
+        const uint32_t key = key_of(i);
+        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        unsigned rem = sh_rem, cum = 0;
+        int d = 255;
+        for (; d > 0; --d) {
+          if (cum + hist[d] >= rem) break;
+          cum += hist[d];
+        }
+        sh_prefix = prefix | ((uint32_t)d << shift);
+        sh_rem = rem - cum;
+        sh_cnt = hist[d];
+      }
+      mask |= 255u << shift;
+      __syncthreads();
+    }
+    T = sh_prefix;
+    const unsigned rem = sh_rem, cnt = sh_cnt;  // take `rem` of the `cnt` entries with key == T
+    __syncthreads();
+    if (rem < cnt) {
+      // rem-th smallest position among the ties
+      all_ties = false;
+      if (tid == 0) { sh_prefix = 0; sh_rem = rem; }
+      mask = 0;
+      for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        const uint32_t prefix = sh_prefix;
+        for (int i = tid; i < n; i += 1024) {
+          if (key_of(i) != T) continue;
+          const uint32_t pk = (uint32_t)ps[i] ^ 0x80000000u;
+          if ((pk & mask) == prefix) atomicAdd(&hist[(pk >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+          unsigned r = sh_rem, cum = 0;
+          int d = 0;
+          for (; d < 255; ++d) {
+            if (cum + hist[d] >= r) break;
+            cum += hist[d];
+          }
+          sh_prefix = prefix | ((uint32_t)d << shift);
+          sh_rem = r - cum;
+        }
+        mask |= 255u << shift;
+        __syncthreads();
+      }
+      P = sh_prefix;
+      rem2 = sh_rem;  // take the first rem2 (in slot order) of the entries equal in score and position
+      __syncthreads();
+    }
+  }
+
+  // ordered emission
+  unsigned kb = 0, eb = 0, qb = 0;
+  for (int base = 0; base < n; base += 1024) {
+    const int i = base + tid;
+    const bool in = i < n;
+    bool f = false, eq = false;
+    if (in) {
+      if (mode == 0) f = true;
+      else if (mode == 2) {
+        const uint32_t key = key_of(i);
+        if (key > T) f = true;
+        else if (key == T) {
+          if (all_ties) f = true;
+          else {
+            const uint32_t pk = (uint32_t)ps[i] ^ 0x80000000u;
+            if (pk < P) f = true;
+            else if (pk == P) eq = true;
+          }
+        }
+      }
+    }
+    if (mode == 2 && !all_ties) {  // uniform branch
+      unsigned tot;
+      const unsigned r = block_excl_scan_1024(eq, wsum, tot);
+      if (eq && qb + r < rem2) f = true;
+      qb += tot;
+    }
+    unsigned tot;
+    const unsigned r = block_excl_scan_1024(f, wsum, tot);
+    if (in) {
+      if (f) keep[kb + r] = i;
+      else evict[eb + (unsigned)tid - r] = i;
+    }
+    kb += tot;
+    eb += (unsigned)min(1024, n - base) - tot;
+  }
+  if (tid == 0) { n_keep[unit] = (int)kb; n_evict[unit] = (int)eb; }
+}
+
+// ------------------------------------------------------------------------------------------
+// a3: latent-memory write.  Partial sums over a split of the evicted rows, then the decayed
+// update.  fp32 (inputs bf16: products exact, fp32 accumulation).
+// ------------------------------------------------------------------------------------------
+#define IM_MEM_TOK 16  // rows staged per inner iteration (a sub-tile of the fold block)
+
+__device__ __forceinline__ int im_mem_blocks_per_split(int ne, int fold_block, int n_split) {
+  const int blocks = (ne + fold_block - 1) / fold_block;
+  return (blocks + n_split - 1) / n_split;
+}
+
+// grid (n_split, units).  Thread t owns M[c][d] for c = (t/16)*8 .. +7, d = t%16 + 16 m.
+__global__ __launch_bounds__(256) void k_mem_partial(const bf16_t* __restrict__ K,
+                                                     const bf16_t* __restrict__ V,
+                                                     const int32_t* __restrict__ evict_idx,
+                                                     const int32_t* __restrict__ n_evict,
+                                                     const bf16_t* __restrict__ Wtheta, int C,
+                                                     int fold_block, int n_split,
+                                                     float* __restrict__ part) {
+  __shared__ __attribute__((aligned(16))) bf16_t Ws[IM_DM * IM_D];  // swizzled: word (d/2) ^ (c & 31)
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[IM_MEM_TOK][IM_D + 2];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[IM_MEM_TOK][IM_D];
+  __shared__ float Ps[IM_MEM_TOK][IM_DM];
+  const int unit = blockIdx.y, split = blockIdx.x, tid = threadIdx.x;
+  const int ne = n_evict[unit];
+  if (ne <= 0) return;
+  const int bps = im_mem_blocks_per_split(ne, fold_block, n_split);
+  const int i0 = split * bps * fold_block;
+  const int i1 = min(ne, i0 + bps * fold_block);
+  if (i0 >= i1) return;
+  for (int i = tid; i < IM_DM * 16; i += 256) {
+    const int c = i >> 4, ch = i & 15;
+    const uint4 u = *(const uint4*)(Wtheta + c * IM_D + ch * 8);
+    uint32_t* row = (uint32_t*)(Ws + c * IM_D);
+    row[(ch * 4 + 0) ^ (c & 31)] = u.x; row[(ch * 4 + 1) ^ (c & 31)] = u.y;
+    row[(ch * 4 + 2) ^ (c & 31)] = u.z; row[(ch * 4 + 3) ^ (c & 31)] = u.w;
+  }
+  const int tr = tid >> 4, tcn = tid & 15;
+  float macc[8][8];
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int m = 0; m < 8; ++m) macc[a][m] = 0.f;
+  float bacc = 0.f;
+  const int32_t* ev = evict_idx + (size_t)unit * C;
+  for (int t0 = i0; t0 < i1; t0 += IM_MEM_TOK) {
+    __syncthreads();
+    {  // stage 16 evicted rows of K and V (zero rows past the end): one 16-byte chunk per thread
+      const int r = tid >> 4, ch = tid & 15;
+      uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+      if (t0 + r < i1) {
+        const size_t row = (size_t)unit * C + ev[t0 + r];
+        kk = *(const uint4*)(K + row * IM_D + ch * 8);
+        vv = *(const uint4*)(V + row * IM_D + ch * 8);
+      }
+      uint32_t* kd = (uint32_t*)&Ks[r][ch * 8];
+      kd[0] = kk.x; kd[1] = kk.y; kd[2] = kk.z; kd[3] = kk.w;
+      *(uint4*)&Vs[r][ch * 8] = vv;
+    }
+    __syncthreads();
+    {  // Phi[token tr][c = tcn + 16 m]
+      float p[8];
+#pragma unroll
+      for (int m = 0; m < 8; ++m) p[m] = 0.f;
+      for (int d2 = 0; d2 < IM_D / 2; ++d2) {
+        const uint32_t kw = *(const uint32_t*)&Ks[tr][d2 * 2];
+        const float k0 = bf_lo(kw), k1 = bf_hi(kw);
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+          const int c = tcn + 16 * m;
+          const uint32_t ww = ((const uint32_t*)(Ws + c * IM_D))[d2 ^ (c & 31)];
+          p[m] = fmaf(k0, bf_lo(ww), p[m]);
+          p[m] = fmaf(k1, bf_hi(ww), p[m]);
+        }
+      }
+#pragma unroll
+      for (int m = 0; m < 8; ++m) Ps[tr][tcn + 16 * m] = p[m];
+    }
+    __syncthreads();
+    if (tid < IM_DM) {
+#pragma unroll
+      for (int i = 0; i < IM_MEM_TOK; ++i) bacc = fmaf(Ps[i][tid], Ps[i][tid], bacc);
+    }
+#pragma unroll 4
+    for (int i = 0; i < IM_MEM_TOK; ++i) {
+      float ph[8], vv[8];
+#pragma unroll
+      for (int a = 0; a < 8; ++a) ph[a] = Ps[i][tr * 8 + a];
+#pragma unroll
+      for (int m = 0; m < 8; ++m) vv[m] = bf2f(Vs[i][tcn + 16 * m]);
+#pragma unroll
+      for (int a = 0; a < 8; ++a)
+#pragma unroll
+        for (int m = 0; m < 8; ++m) macc[a][m] = fmaf(ph[a], vv[m], macc[a][m]);
+    }
+  }
+  float* out = part + ((size_t)unit * n_split + split) * (IM_DM * IM_D + IM_DM);
+#pragma unroll
+  for (int a = 0; a < 8; ++a)
+#pragma unroll
+    for (int m = 0; m < 8; ++m) out[(tr * 8 + a) * IM_D + tcn + 16 * m] = macc[a][m];
+  if (tid < IM_DM) out[IM_DM * IM_D + tid] = bacc;
+}
+
+// grid (ceil((DM*D + DM)/256), units)
+__global__ __launch_bounds__(256) void k_mem_finalize(float* __restrict__ M, float* __restrict__ bvec,
+                                                      const int32_t* __restrict__ n_evict,
+                                                      const float* __restrict__ part, int fold_block,
+                                                      int n_split, float lambda, float eta) {
+  const int unit = blockIdx.y;
+  const int ne = n_evict[unit];
+  if (ne <= 0) return;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= IM_DM * IM_D + IM_DM) return;
+  const int bps = im_mem_blocks_per_split(ne, fold_block, n_split);
+  const int active = ((ne + fold_block - 1) / fold_block + bps - 1) / bps;
+  float s = 0.f;
+  for (int sp = 0; sp < active; ++sp)
+    s += part[((size_t)unit * n_split + sp) * (IM_DM * IM_D + IM_DM) + e];
+  float* dst = (e < IM_DM * IM_D) ? (M + (size_t)unit * IM_DM * IM_D + e)
+                                  : (bvec + (size_t)unit * IM_DM + (e - IM_DM * IM_D));
+  *dst = fmaf(lambda, *dst, eta * s);
+}
+
+// ------------------------------------------------------------------------------------------
+// a4: in-place compaction by hole filling.  One wave moves one entry (K, V, Kidx rows and pos).
+// ------------------------------------------------------------------------------------------
+// grid (gx, units)
+__global__ __launch_bounds__(256) void k_compact(bf16_t* __restrict__ K, bf16_t* __restrict__ V,
+                                                 bf16_t* __restrict__ Kidx, int32_t* __restrict__ pos,
+                                                 int32_t* __restrict__ len,
+                                                 int32_t* __restrict__ n_projected,
+                                                 const int32_t* __restrict__ keep_idx,
+                                                 const int32_t* __restrict__ n_keep,
+                                                 const int32_t* __restrict__ evict_idx, int C) {
+  const int unit = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int nk = n_keep[unit];
+  const int32_t* keep = keep_idx + (size_t)unit * C;
+  const int32_t* evict = evict_idx + (size_t)unit * C;
+  // p = number of kept slots below nk (keep is ascending)
+  int lo = 0, hi = nk;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (keep[mid] < nk) lo = mid + 1; else hi = mid;
+  }
+  const int p = lo, n_moves = nk - p;
+  for (int j = blockIdx.x * 4 + w; j < n_moves; j += gridDim.x * 4) {
+    const size_t src = (size_t)unit * C + keep[p + j];
+    const size_t dst = (size_t)unit * C + evict[j];
+    if (lane < 16) *(uint4*)(K + dst * IM_D + lane * 8) = *(const uint4*)(K + src * IM_D + lane * 8);
+    else if (lane < 32) *(uint4*)(V + dst * IM_D + (lane - 16) * 8) = *(const uint4*)(V + src * IM_D + (lane - 16) * 8);
+    else if (lane < 40) *(uint4*)(Kidx + dst * IM_DI + (lane - 32) * 8) = *(const uint4*)(Kidx + src * IM_DI + (lane - 32) * 8);
+    else if (lane == 40) pos[dst] = pos[src];
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) { len[unit] = nk; n_projected[unit] = nk; }
+}
+
+// ------------------------------------------------------------------------------------------
+// a5: split-K decode attention, then the combine with the gated memory readout
+// ------------------------------------------------------------------------------------------
+#define IM_ATT_CHUNK 256
+#define IM_ATT_REC (IM_D + 2)  // partial record: running max, denominator, 128 numerators
+
+// grid (chunks, units).  16 lanes share a key row (8 dims each); a wave handles 4 keys at a time.
+template <int G>
+__global__ __launch_bounds__(256) void k_attn_partial(const bf16_t* __restrict__ K,
+                                                      const bf16_t* __restrict__ V,
+                                                      const int32_t* __restrict__ len,
+                                                      const bf16_t* __restrict__ q, int H, int H_kv,
+                                                      int C, int max_live, float scale,
+                                                      float* __restrict__ part, int n_chunks) {
+  __shared__ float s_ml[4][G][2];
+  __shared__ float s_acc[4][G][IM_D];
+  const int unit = blockIdx.y, chunk = blockIdx.x;
+  const int b = unit / H_kv, h = unit % H_kv;
+  const int n = min(len[unit], max_live);
+  const int k0 = chunk * IM_ATT_CHUNK;
+  if (k0 >= n) return;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, grp = lane >> 4, l16 = lane & 15;
+  float qf[G][8];
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    const uint4 u = *(const uint4*)(q + ((size_t)b * H + h * G + j) * IM_D + l16 * 8);
+    qf[j][0] = bf_lo(u.x) * scale; qf[j][1] = bf_hi(u.x) * scale;
+    qf[j][2] = bf_lo(u.y) * scale; qf[j][3] = bf_hi(u.y) * scale;
+    qf[j][4] = bf_lo(u.z) * scale; qf[j][5] = bf_hi(u.z) * scale;
+    qf[j][6] = bf_lo(u.w) * scale; qf[j][7] = bf_hi(u.w) * scale;
+  }
+  float mx[G], ls[G], acc[G][8];
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    mx[j] = -1e30f; ls[j] = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
+  }
+  const bf16_t* Kb = K + (size_t)unit * C * IM_D;
+  const bf16_t* Vb = V + (size_t)unit * C * IM_D;
+  for (int it = 0; it < 16; ++it) {
+    const int key = k0 + w * 64 + it * 4 + grp;
+    const bool valid = key < n;
+    const int kc = valid ? key : n - 1;
+    const uint4 ku = *(const uint4*)(Kb + (size_t)kc * IM_D + l16 * 8);
+    const uint4 vu = *(const uint4*)(Vb + (size_t)kc * IM_D + l16 * 8);
+    const float kf[8] = {bf_lo(ku.x), bf_hi(ku.x), bf_lo(ku.y), bf_hi(ku.y),
+                         bf_lo(ku.z), bf_hi(ku.z), bf_lo(ku.w), bf_hi(ku.w)};
+    const float vf[8] = {bf_lo(vu.x), bf_hi(vu.x), bf_lo(vu.y), bf_hi(vu.y),
+                         bf_lo(vu.z), bf_hi(vu.z), bf_lo(vu.w), bf_hi(vu.w)};
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s = fmaf(qf[j][e], kf[e], s);
+      s += __shfl_xor(s, 1, 64); s += __shfl_xor(s, 2, 64);
+      s += __shfl_xor(s, 4, 64); s += __shfl_xor(s, 8, 64);
+      if (!valid) s = -INFINITY;
+      const float mn = fmaxf(mx[j], s);
+      const float corr = __expf(mx[j] - mn), p = __expf(s - mn);
+      ls[j] = fmaf(ls[j], corr, p);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(acc[j][e], corr, p * vf[e]);
+      mx[j] = mn;
+    }
+  }
+  // merge the 4 key streams of the wave
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    float m = mx[j];
+    m = fmaxf(m, __shfl_xor(m, 16, 64));
+    m = fmaxf(m, __shfl_xor(m, 32, 64));
+    const float sc = __expf(mx[j] - m);
+    float l = ls[j] * sc;
+    l += __shfl_xor(l, 16, 64); l += __shfl_xor(l, 32, 64);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float a = acc[j][e] * sc;
+      a += __shfl_xor(a, 16, 64); a += __shfl_xor(a, 32, 64);
+      acc[j][e] = a;
+    }
+    if (grp == 0) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s_acc[w][j][l16 * 8 + e] = acc[j][e];
+      if (l16 == 0) { s_ml[w][j][0] = m; s_ml[w][j][1] = l; }
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * IM_D; idx += 256) {
+    const int j = idx >> 7, d = idx & 127;
+    float m = fmaxf(fmaxf(s_ml[0][j][0], s_ml[1][j][0]), fmaxf(s_ml[2][j][0], s_ml[3][j][0]));
+    float o = 0.f, l = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+      const float sc = __expf(s_ml[ww][j][0] - m);
+      o = fmaf(sc, s_acc[ww][j][d], o);
+      l = fmaf(sc, s_ml[ww][j][1], l);
+    }
+    float* rec = part + (((size_t)b * H + h * G + j) * n_chunks + chunk) * IM_ATT_REC;
+    rec[2 + d] = o;
+    if (d == 0) { rec[0] = m; rec[1] = l; }
+  }
+}
+
+// grid (B*H), 128 threads (thread = output dim)
+__global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ part, int n_chunks,
+                                                      const int32_t* __restrict__ len,
+                                                      const bf16_t* __restrict__ q,
+                                                      const bf16_t* __restrict__ Wtheta,
+                                                      const bf16_t* __restrict__ wg, float cg,
+                                                      const float* __restrict__ M,
+                                                      const float* __restrict__ bvec, int H, int H_kv,
+                                                      int max_live, float mem_eps,
+                                                      bf16_t* __restrict__ out,
+                                                      float* __restrict__ readout_dbg) {
+  __shared__ float qs[IM_D];
+  __shared__ float phi[IM_DM];
+  __shared__ float red[2][2];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const int b = bh / H, j = bh % H, G = H / H_kv, h = j / G;
+  const int unit = b * H_kv + h;
+  const int n = min(len[unit], max_live);
+  const int nch = min((n + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK, n_chunks);
+  const float* rec = part + (size_t)bh * n_chunks * IM_ATT_REC;
+  float m = -1e30f;
+  for (int c = 0; c < nch; ++c) m = fmaxf(m, rec[(size_t)c * IM_ATT_REC]);
+  float o = 0.f, l = 0.f;
+  for (int c = 0; c < nch; ++c) {
+    const float sc = __expf(rec[(size_t)c * IM_ATT_REC] - m);
+    o = fmaf(sc, rec[(size_t)c * IM_ATT_REC + 2 + tid], o);
+    l = fmaf(sc, rec[(size_t)c * IM_ATT_REC + 1], l);
+  }
+  const float o_attn = (nch > 0) ? o / l : 0.f;
+  // memory readout
+  const float qd = bf2f(q[(size_t)bh * IM_D + tid]);
+  qs[tid] = qd;
+  __syncthreads();
+  float ph = 0.f;
+  {
+    const uint4* wr = (const uint4*)(Wtheta + tid * IM_D);
+#pragma unroll 4
+    for (int i = 0; i < 16; ++i) {
+      const uint4 u = wr[i];
+      ph = fmaf(bf_lo(u.x), qs[8 * i + 0], ph); ph = fmaf(bf_hi(u.x), qs[8 * i + 1], ph);
+      ph = fmaf(bf_lo(u.y), qs[8 * i + 2], ph); ph = fmaf(bf_hi(u.y), qs[8 * i + 3], ph);
+      ph = fmaf(bf_lo(u.z), qs[8 * i + 4], ph); ph = fmaf(bf_hi(u.z), qs[8 * i + 5], ph);
+      ph = fmaf(bf_lo(u.w), qs[8 * i + 6], ph); ph = fmaf(bf_hi(u.w), qs[8 * i + 7], ph);
+    }
+  }
+  phi[tid] = ph;
+  float den = wave_sum_f(ph * ph * bvec[(size_t)unit * IM_DM + tid]);
+  float gz = wave_sum_f(bf2f(wg[tid]) * qd);
+  if ((tid & 63) == 0) { red[tid >> 6][0] = den; red[tid >> 6][1] = gz; }
+  __syncthreads();
+  den = red[0][0] + red[1][0] + mem_eps;
+  gz = red[0][1] + red[1][1] + cg;
+  const float gate = 1.f / (1.f + __expf(-gz));
+  const float* Mu = M + (size_t)unit * IM_DM * IM_D;
+  float mr = 0.f;
+#pragma unroll 8
+  for (int c = 0; c < IM_DM; ++c) mr = fmaf(phi[c], Mu[c * IM_D + tid], mr);
+  const float res = gate * (mr / den);
+  out[(size_t)bh * IM_D + tid] = f2bf_rne(o_attn + res);
+  if (readout_dbg) readout_dbg[(size_t)bh * IM_D + tid] = res;
+}

@@ -1,0 +1,315 @@
+// libindexmem: host side of the C ABI declared in include/indexmem.h.
+// Validation happens first and touches no GPU; the rest only enqueues kernels on the caller's
+// stream.  No device memory is allocated here.
+#include "../../include/indexmem.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "im_kernels.h"
+
+struct im_handle {
+  im_config cfg;
+  char* ws;
+  size_t ws_bytes;
+  int max_live;
+  bool ws_ready;
+  // workspace layout (byte offsets)
+  size_t off_status, off_qy, off_alpha, off_mem, off_attn, total;
+  int mem_split, attn_chunks;
+  char err[256];
+};
+
+namespace {
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int set_err(im_handle* h, int code, const char* fmt, ...) {
+  if (h) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(h->err, sizeof(h->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+const char* config_problem(const im_config* c, int* code) {
+  *code = IM_ERR_INVALID_ARG;
+  if (!c) return "config is NULL";
+  if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return "batch and head counts must be >= 1";
+  if (c->n_q_heads % c->n_kv_heads != 0) return "n_q_heads must be a multiple of n_kv_heads";
+  if (c->capacity < 1) return "capacity must be >= 1";
+  if (c->n_idx_heads < 1 || c->n_idx_heads > 16) return "n_idx_heads must be in 1..16";
+  if (c->gate_in_dim < 16 || c->gate_in_dim % 16 != 0) return "gate_in_dim must be a positive multiple of 16";
+  if (c->n_sink < 0 || c->n_recent < 0) return "n_sink and n_recent must be >= 0";
+  if ((long long)c->n_sink + c->n_recent > c->capacity) return "n_sink + n_recent exceeds capacity";
+  if (c->fold_block < 16 || c->fold_block % 16 != 0) return "fold_block must be a positive multiple of 16";
+  if (c->max_queries < 1) return "max_queries must be >= 1";
+  if (!(c->rms_eps >= 0.f) || !(c->mem_eps > 0.f) || !(c->softmax_scale > 0.f))
+    return "rms_eps >= 0, mem_eps > 0 and softmax_scale > 0 are required";
+  if ((long long)c->batch * c->n_kv_heads > 65535) return "batch * n_kv_heads must be <= 65535";
+  *code = IM_ERR_UNSUPPORTED;
+  if (c->head_dim != IM_D) return "head_dim must be 128";
+  if (c->idx_dim != IM_DI) return "idx_dim must be 64";
+  if (c->mem_dim != IM_DM) return "mem_dim must be 128";
+  if (c->n_q_heads / c->n_kv_heads > 8) return "more than 8 query heads per KV head";
+  *code = IM_OK;
+  return nullptr;
+}
+
+void layout(const im_config* c, im_handle* h) {
+  const size_t B = c->batch, Hi = c->n_idx_heads, units = (size_t)c->batch * c->n_kv_heads;
+  h->mem_split = (c->capacity + 1023) / 1024;
+  if (h->mem_split < 1) h->mem_split = 1;
+  if (h->mem_split > 32) h->mem_split = 32;
+  h->attn_chunks = (c->capacity + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK;
+  size_t off = 0;
+  h->off_status = off; off = align256(off + 256);
+  h->off_qy = off;     off = align256(off + B * c->max_queries * Hi * IM_DI * sizeof(double));
+  h->off_alpha = off;  off = align256(off + B * c->max_queries * Hi * sizeof(double));
+  h->off_mem = off;    off = align256(off + units * h->mem_split * (IM_DM * IM_D + IM_DM) * sizeof(float));
+  h->off_attn = off;   off = align256(off + B * c->n_q_heads * h->attn_chunks * IM_ATT_REC * sizeof(float));
+  h->total = off;
+}
+
+int launch_check(im_handle* h, const char* what) {
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return set_err(h, IM_ERR_LAUNCH, "%s: %s", what, hipGetErrorString(e));
+  return IM_OK;
+}
+
+int ensure_ws(im_handle* h, hipStream_t s) {
+  if (h->ws_ready) return IM_OK;
+  k_fill_i32<<<1, 64, 0, s>>>((int32_t*)(h->ws + h->off_status), 64, 0);
+  int rc = launch_check(h, "workspace clear");
+  if (rc == IM_OK) h->ws_ready = true;
+  return rc;
+}
+
+int32_t* status_ptr(im_handle* h) { return (int32_t*)(h->ws + h->off_status); }
+
+bool state_ok(const im_state* st) {
+  return st && st->K && st->V && st->Kidx && st->pos && st->len && st->n_projected && st->M && st->b;
+}
+bool params_ok(const im_params* p) { return p && p->Uq && p->G && p->Uk && p->Wtheta && p->wg; }
+
+#define IM_REQUIRE(cond, msg) \
+  do { if (!(cond)) return set_err(h, IM_ERR_INVALID_ARG, "%s: %s", __func__, msg); } while (0)
+
+}  // namespace
+
+extern "C" {
+
+size_t im_workspace_bytes(const im_config* cfg) {
+  int code;
+  if (config_problem(cfg, &code)) return 0;
+  im_handle tmp;
+  layout(cfg, &tmp);
+  return tmp.total;
+}
+
+int32_t im_create(const im_config* cfg, void* workspace, size_t workspace_bytes, im_handle** out) {
+  if (!out) return IM_ERR_INVALID_ARG;
+  *out = nullptr;
+  int code;
+  if (config_problem(cfg, &code)) return code;
+  im_handle* h = (im_handle*)calloc(1, sizeof(im_handle));
+  if (!h) return IM_ERR_LAUNCH;
+  h->cfg = *cfg;
+  layout(cfg, h);
+  if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < h->total) {
+    free(h);
+    return IM_ERR_INVALID_ARG;
+  }
+  h->ws = (char*)workspace;
+  h->ws_bytes = workspace_bytes;
+  h->max_live = cfg->capacity;
+  h->ws_ready = false;
+  h->err[0] = 0;
+  *out = h;
+  return IM_OK;
+}
+
+void im_destroy(im_handle* h) { free(h); }
+
+const char* im_last_error(const im_handle* h) { return h ? h->err : "handle is NULL"; }
+
+int32_t im_set_max_live(im_handle* h, int32_t max_live) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(max_live >= 1 && max_live <= h->cfg.capacity, "max_live must be in 1..capacity");
+  h->max_live = max_live;
+  return IM_OK;
+}
+
+int32_t im_query_status(im_handle* h, int32_t* status_host, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(status_host, "status_host is NULL");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  hipError_t e = hipMemcpyAsync(status_host, status_ptr(h), sizeof(int32_t), hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return set_err(h, IM_ERR_LAUNCH, "status copy: %s", hipGetErrorString(e));
+  k_fill_i32<<<1, 64, 0, s>>>(status_ptr(h), 1, 0);
+  rc = launch_check(h, "status clear");
+  if (rc) return rc;
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return set_err(h, IM_ERR_LAUNCH, "stream synchronize: %s", hipGetErrorString(e));
+  return IM_OK;
+}
+
+int32_t im_append_kv(im_handle* h, const im_state* st, const void* k_new, const void* v_new,
+                     const int32_t* pos_new, int32_t n_new, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(state_ok(st), "state has a NULL pointer");
+  IM_REQUIRE(k_new && v_new && pos_new, "k_new / v_new / pos_new is NULL");
+  IM_REQUIRE(n_new >= 1 && n_new <= h->cfg.capacity, "n_new must be in 1..capacity");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  const im_config& c = h->cfg;
+  const int units = c.batch * c.n_kv_heads;
+  dim3 grid((n_new * 16 + 255) / 256, units);
+  k_append_rows<<<grid, 256, 0, s>>>((bf16_t*)st->K, (bf16_t*)st->V, st->pos, st->len,
+                                     (const bf16_t*)k_new, (const bf16_t*)v_new, pos_new, n_new,
+                                     c.n_kv_heads, c.capacity);
+  k_append_len<<<(units + 255) / 256, 256, 0, s>>>(st->len, units, n_new, c.capacity, status_ptr(h));
+  return launch_check(h, "im_append_kv");
+}
+
+int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, const void* q_new,
+                       const void* x_gate, const int32_t* q_pos, int32_t n_q, float* scores_out,
+                       void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(params_ok(p), "params has a NULL pointer");
+  IM_REQUIRE(state_ok(st), "state has a NULL pointer");
+  IM_REQUIRE(q_new && x_gate && q_pos && scores_out, "q_new / x_gate / q_pos / scores_out is NULL");
+  IM_REQUIRE(n_q >= 1 && n_q <= h->cfg.max_queries, "n_q must be in 1..max_queries");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  const im_config& c = h->cfg;
+  const int units = c.batch * c.n_kv_heads;
+  double* qy = (double*)(h->ws + h->off_qy);
+  double* al = (double*)(h->ws + h->off_alpha);
+
+  k_project_keys<<<dim3((h->max_live + 63) / 64, units), 256, 0, s>>>(
+      (const bf16_t*)st->K, (bf16_t*)st->Kidx, st->len, st->n_projected, (const bf16_t*)p->Uk,
+      (const bf16_t*)p->norm_k_w, c.capacity, h->max_live, c.rms_eps, status_ptr(h));
+
+  const int M = c.batch * n_q, Nq = c.n_idx_heads * IM_DI, Kq = c.n_q_heads * IM_D;
+  if (M <= 32) {
+    k_gemv_nt_f64<<<(Nq + 1) / 2, 256, 0, s>>>((const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, M, Nq, Kq);
+    k_gemv_nt_f64<<<(c.n_idx_heads + 1) / 2, 256, 0, s>>>((const bf16_t*)x_gate, (const bf16_t*)p->G, al,
+                                                         M, c.n_idx_heads, c.gate_in_dim);
+  } else {
+    k_gemm_nt_f64<<<dim3((Nq + 63) / 64, (M + 63) / 64), 256, 0, s>>>(
+        (const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, M, Nq, Kq);
+    k_gemm_nt_f64<<<dim3((c.n_idx_heads + 63) / 64, (M + 63) / 64), 256, 0, s>>>(
+        (const bf16_t*)x_gate, (const bf16_t*)p->G, al, M, c.n_idx_heads, c.gate_in_dim);
+  }
+  const int rows = M * c.n_idx_heads;
+  k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, (const bf16_t*)p->norm_q_w, c.rms_eps);
+  k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, sqrt((double)(c.n_idx_heads * IM_DI)));
+  k_score<<<dim3((h->max_live + 255) / 256, units), 256, 0, s>>>(
+      (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q, c.n_kv_heads,
+      c.capacity, c.n_idx_heads, h->max_live, scores_out);
+  return launch_check(h, "im_index_score");
+}
+
+int32_t im_topb_select(im_handle* h, const float* scores, const im_state* st, int32_t budget,
+                       int32_t* keep_idx, int32_t* evict_idx, int32_t* n_keep, int32_t* n_evict,
+                       void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(state_ok(st), "state has a NULL pointer");
+  IM_REQUIRE(scores && keep_idx && evict_idx && n_keep && n_evict, "an array pointer is NULL");
+  IM_REQUIRE(budget >= h->cfg.n_sink + h->cfg.n_recent, "budget is below n_sink + n_recent");
+  IM_REQUIRE(budget <= h->cfg.capacity, "budget exceeds capacity");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  const im_config& c = h->cfg;
+  k_select<<<c.batch * c.n_kv_heads, 1024, 0, s>>>(scores, st->pos, st->len, c.capacity, h->max_live,
+                                                  budget, c.n_sink, c.n_recent, keep_idx, evict_idx,
+                                                  n_keep, n_evict);
+  return launch_check(h, "im_topb_select");
+}
+
+int32_t im_memory_update(im_handle* h, const im_params* p, const im_state* st,
+                         const int32_t* evict_idx, const int32_t* n_evict, float lambda, float eta,
+                         void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(params_ok(p), "params has a NULL pointer");
+  IM_REQUIRE(state_ok(st), "state has a NULL pointer");
+  IM_REQUIRE(evict_idx && n_evict, "evict_idx / n_evict is NULL");
+  IM_REQUIRE(lambda > 0.f && lambda <= 1.f, "lambda must be in (0, 1]");
+  IM_REQUIRE(eta > 0.f, "eta must be > 0");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  const im_config& c = h->cfg;
+  const int units = c.batch * c.n_kv_heads;
+  float* part = (float*)(h->ws + h->off_mem);
+  k_mem_partial<<<dim3(h->mem_split, units), 256, 0, s>>>(
+      (const bf16_t*)st->K, (const bf16_t*)st->V, evict_idx, n_evict, (const bf16_t*)p->Wtheta,
+      c.capacity, c.fold_block, h->mem_split, part);
+  k_mem_finalize<<<dim3((IM_DM * IM_D + IM_DM + 255) / 256, units), 256, 0, s>>>(
+      st->M, st->b, n_evict, part, c.fold_block, h->mem_split, lambda, eta);
+  return launch_check(h, "im_memory_update");
+}
+
+int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx, const int32_t* n_keep,
+                      const int32_t* evict_idx, const int32_t* n_evict, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(state_ok(st), "state has a NULL pointer");
+  IM_REQUIRE(keep_idx && n_keep && evict_idx && n_evict, "a list pointer is NULL");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  const im_config& c = h->cfg;
+  int gx = (h->max_live + 3) / 4;
+  if (gx > 64) gx = 64;
+  k_compact<<<dim3(gx, c.batch * c.n_kv_heads), 256, 0, s>>>(
+      (bf16_t*)st->K, (bf16_t*)st->V, (bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, keep_idx,
+      n_keep, evict_idx, c.capacity);
+  return launch_check(h, "im_compact_kv");
+}
+
+int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_state* st,
+                                    const void* q, void* out, float* readout_dbg, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(params_ok(p), "params has a NULL pointer");
+  IM_REQUIRE(state_ok(st), "state has a NULL pointer");
+  IM_REQUIRE(q && out, "q / out is NULL");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  const im_config& c = h->cfg;
+  const int units = c.batch * c.n_kv_heads, G = c.n_q_heads / c.n_kv_heads;
+  const int chunks = (h->max_live + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK;
+  float* part = (float*)(h->ws + h->off_attn);
+  dim3 grid(chunks, units);
+#define IM_ATT_CASE(g)                                                                          \
+  case g:                                                                                       \
+    k_attn_partial<g><<<grid, 256, 0, s>>>((const bf16_t*)st->K, (const bf16_t*)st->V, st->len,   \
+                                           (const bf16_t*)q, c.n_q_heads, c.n_kv_heads,         \
+                                           c.capacity, h->max_live, c.softmax_scale, part,      \
+                                           h->attn_chunks);                                     \
+    break;
+  switch (G) {
+    IM_ATT_CASE(1) IM_ATT_CASE(2) IM_ATT_CASE(3) IM_ATT_CASE(4)
+    IM_ATT_CASE(5) IM_ATT_CASE(6) IM_ATT_CASE(7) IM_ATT_CASE(8)
+    default: return set_err(h, IM_ERR_UNSUPPORTED, "group size %d", G);
+  }
+#undef IM_ATT_CASE
+  k_attn_combine<<<c.batch * c.n_q_heads, 128, 0, s>>>(
+      part, h->attn_chunks, st->len, (const bf16_t*)q, (const bf16_t*)p->Wtheta, (const bf16_t*)p->wg,
+      p->cg, st->M, st->b, c.n_q_heads, c.n_kv_heads, h->max_live, c.mem_eps, (bf16_t*)out, readout_dbg);
+  return launch_check(h, "im_decode_attn_with_readout");
+}
+
+}  // extern "C"

@@ -1,0 +1,35 @@
+"""One attention layer's buffers and the canonical order of the library calls on them.
+
+Pure sequencing: every method enqueues library calls on the current stream; nothing is
+computed in Python."""
+from __future__ import annotations
+
+import torch
+
+from . import binding as B
+
+
+class Layer:
+    def __init__(self, handle: B.Handle, params: B.Params, device="cuda"):
+        cfg = handle.cfg
+        self.h, self.p, self.cfg = handle, params, cfg
+        self.st = B.State(cfg, device)
+        Bz, Hk, Cc = cfg.batch, cfg.n_kv_heads, cfg.capacity
+        self.scores = torch.empty((Bz, Hk, Cc), dtype=torch.float32, device=device)
+        self.keep_idx = torch.empty((Bz, Hk, Cc), dtype=torch.int32, device=device)
+        self.evict_idx = torch.empty((Bz, Hk, Cc), dtype=torch.int32, device=device)
+        self.n_keep = torch.zeros((Bz, Hk), dtype=torch.int32, device=device)
+        self.n_evict = torch.zeros((Bz, Hk), dtype=torch.int32, device=device)
+        self.out = torch.empty((Bz, cfg.n_q_heads, cfg.head_dim), dtype=torch.bfloat16, device=device)
+        self.readout = torch.empty((Bz, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device=device)
+
+    def step(self, k_new, v_new, pos_new, q_new, x_gate, q_pos, q_attn, budget, lam, eta):
+        """append -> score -> select -> memory update -> compact -> attention + readout."""
+        h, p, st = self.h, self.p, self.st
+        B.im_append_kv(h, st, k_new, v_new, pos_new)
+        B.im_index_score(h, p, st, q_new, x_gate, q_pos, self.scores)
+        B.im_topb_select(h, self.scores, st, budget, self.keep_idx, self.evict_idx, self.n_keep, self.n_evict)
+        B.im_memory_update(h, p, st, self.evict_idx, self.n_evict, lam, eta)
+        B.im_compact_kv(h, st, self.keep_idx, self.n_keep, self.evict_idx, self.n_evict)
+        B.im_decode_attn_with_readout(h, p, st, q_attn, self.out, self.readout)
+        return self.out

@@ -26,7 +26,9 @@ def oracle_config(w: Workload, capacity=None, batch=None, kv_head_ids=None) -> O
                           capacity=w.capacity if capacity is None else capacity,
                           n_idx_heads=w.n_idx_heads, head_dim=w.head_dim, idx_dim=w.idx_dim,
                           mem_dim=w.mem_dim, n_sink=w.n_sink, n_recent=w.n_recent,
-                          softmax_scale=1.0 / np.sqrt(float(w.head_dim)),
+                          # the library takes these three as fp32; the oracle uses the same values
+                          rms_eps=float(np.float32(1e-6)), mem_eps=float(np.float32(1e-6)),
+                          softmax_scale=float(np.float32(float(w.head_dim) ** -0.5)),
                           kv_head_ids=kv_head_ids)
 
 
