@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Benchmark of the bounded-budget KV decode step on one MI355X.
+
+A "step" is one pass of the whole hot path (append -> index score -> top-B select -> memory
+update -> compaction -> decode attention + readout) over every layer of the workload, layers
+issued one after another on one stream, inputs already resident in HBM.  The default workload
+is configuration 3 (32/8 x 128 heads, 32 layers, batch 4, a 16384-token context evicted to a
+budget of 2048): the 16K-context case the headline metric is quoted on.
+
+Prints ONE JSON line with the whole-job decode throughput, the roofline record of the dominant
+kernel and the CPU oracle's throughput on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+import numpy as np
+import torch
+
+import paper_2605_25475_amd as im
+from workloads import WORKLOADS, Workload, layer_params, token_stream
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(w: Workload) -> dict:
+    """Bytes the method itself must move per layer-step of steady-state decode (n = B + 1 live
+    entries per unit, one eviction): what the roofline fraction is priced against."""
+    Bg, D = w.budget, w.head_dim
+    units = w.batch * w.n_kv_heads
+    per_unit = {
+        "indexer_keys": 2 * w.idx_dim * (Bg + 1),          # stream the indexer-key cache
+        "kv": 2 * 2 * D * Bg,                              # stream retained K and V
+        "new_key": 2 * D + 2 * w.idx_dim,                  # project the new key, store its indexer key
+        "evicted_row": 2 * 2 * D,                          # K and V of the evicted entry
+        "memory_state": 2 * 4 * w.mem_dim * D + 2 * 4 * w.mem_dim,   # M, b read + write
+        "compaction_row": 2 * (2 * 2 * D + 2 * w.idx_dim + 4),
+    }
+    per_layer = {
+        "indexer_weights": 2 * (w.n_idx_heads * w.idx_dim * w.n_q_heads * D + w.n_idx_heads * w.gate_in_dim),
+        "q_and_out": w.batch * w.n_q_heads * D * 2 * 2,
+    }
+    unit_total = sum(per_unit.values())
+    layer_total = units * unit_total + sum(per_layer.values())
+    return {"per_unit": unit_total, "per_layer_step": layer_total,
+            "attention_kv_per_layer": units * per_unit["kv"], "detail": {**per_unit, **per_layer}}
+
+
+class Job:
+    """All layers of a workload after their prefill eviction, plus pre-generated decode inputs."""
+
+    def __init__(self, w: Workload, n_steps: int, device="cuda", log=lambda s: None):
+        self.w, self.dev = w, device
+        cap = w.capacity
+        n_q_max = w.context if w.prefill_chunk is None else w.prefill_chunk
+        cfg = im.Config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, capacity=cap,
+                        n_idx_heads=w.n_idx_heads, n_sink=w.n_sink, n_recent=w.n_recent,
+                        fold_block=w.fold_block, max_queries=n_q_max)
+        self.handle = im.Handle(cfg, device)
+        self.layers, self.dec = [], []
+        L = w.context
+        assert n_steps <= w.decode_steps, "the workload defines fewer decode steps"
+        for li in range(w.n_layers):
+            p = layer_params(w, li, device)
+            params = im.Params(p["Uq"], p["G"], p["Uk"], p["Wtheta"], p["wg"], p["cg"],
+                               p["norm_q_w"], p["norm_k_w"])
+            layer = im.Layer(self.handle, params, device)
+            K, V, Q = token_stream(w, li, device, n_tokens=L + n_steps)
+            im.im_set_max_live(self.handle, cap)
+            chunk = L if w.prefill_chunk is None else w.prefill_chunk
+            for c0 in range(0, L, chunk):
+                c1 = min(L, c0 + chunk)
+                pos = torch.arange(c0, c1, dtype=torch.int32, device=device).repeat(w.batch, 1).contiguous()
+                q = Q[:, c0:c1].contiguous()
+                layer.step(K[:, :, c0:c1].contiguous(), V[:, :, c0:c1].contiguous(), pos, q,
+                           q.view(w.batch, c1 - c0, -1), pos, Q[:, c1 - 1].contiguous(), w.budget,
+                           w.lam, w.eta)
+            # decode inputs, one contiguous slab per step
+            kd = K[:, :, L:].permute(2, 0, 1, 3).contiguous().unsqueeze(3)      # [S, B, Hkv, 1, D]
+            vd = V[:, :, L:].permute(2, 0, 1, 3).contiguous().unsqueeze(3)
+            qd = Q[:, L:].permute(1, 0, 2, 3).contiguous().unsqueeze(2)         # [S, B, 1, H, D]
+            self.layers.append(layer)
+            self.dec.append((kd, vd, qd))
+            del K, V, Q
+            torch.cuda.synchronize()
+            log(f"layer {li + 1}/{w.n_layers} prefilled")
+        self.pos = (torch.arange(L, L + n_steps, dtype=torch.int32, device=device)
+                    .view(n_steps, 1, 1).repeat(1, w.batch, 1).contiguous())
+        im.im_set_max_live(self.handle, min(cap, w.budget + 1))
+        assert im.im_query_status(self.handle) == 0
+
+    def step(self, s: int, attn_events=None):
+        w = self.w
+        pos = self.pos[s]
+        for li, layer in enumerate(self.layers):
+            kd, vd, qd = self.dec[li]
+            q = qd[s]
+            if attn_events is None:
+                layer.step(kd[s], vd[s], pos, q, q.view(w.batch, 1, -1), pos, q.view(w.batch, w.n_q_heads, -1),
+                           w.budget, w.lam, w.eta)
+            else:
+                h, p, st = layer.h, layer.p, layer.st
+                im.im_append_kv(h, st, kd[s], vd[s], pos)
+                im.im_index_score(h, p, st, q, q.view(w.batch, 1, -1), pos, layer.scores)
+                im.im_topb_select(h, layer.scores, st, w.budget, layer.keep_idx, layer.evict_idx,
+                                  layer.n_keep, layer.n_evict)
+                im.im_memory_update(h, p, st, layer.evict_idx, layer.n_evict, w.lam, w.eta)
+                im.im_compact_kv(h, st, layer.keep_idx, layer.n_keep, layer.evict_idx, layer.n_evict)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                im.im_decode_attn_with_readout(h, p, st, q.view(w.batch, w.n_q_heads, -1), layer.out,
+                                               layer.readout)
+                e1.record()
+                attn_events.append((e0, e1))
+
+
+def cpu_baseline(w: Workload, budget_s: float = 20.0) -> dict:
+    """The oracle, as it stands, on one unit of the same workload: its own prefill eviction at
+    full context (untimed here, it only builds a realistic state), then timed decode steps."""
+    from helpers import f64, make_oracle_layer
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([t.get("num_threads", 1) for t in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    n_steps = min(512, w.decode_steps)
+    nb = min(4, w.batch)
+    heads = list(range(w.n_kv_heads))
+    K, V, Q = token_stream(w, 0, "cpu", n_tokens=w.context + n_steps)
+    ws = w.scaled(batch=nb)
+    ref = make_oracle_layer(ws, 0, "cpu", capacity=w.context + 1, batch=nb, kv_head_ids=heads)
+    L = w.context
+    K, V, Q = f64(K[:nb]), f64(V[:nb]), f64(Q[:nb])
+    # build the post-prefill state cheaply, for TIMING purposes only: score with the last 64
+    # prompt queries (the parity tests, not this leg, check the full-context event)
+    nq = 64
+    pos = np.tile(np.arange(L, dtype=np.int32), (nb, 1))
+    ref.append_kv(K[:, :, :L], V[:, :, :L], pos)
+    q = Q[:, L - nq:L]
+    sc = ref.index_score(q, q.reshape(nb, nq, -1), pos[:, L - nq:])
+    keep, evict = ref.topb_select(sc, w.budget)
+    ref.memory_update(evict, w.lam, w.eta)
+    ref.compact_kv(keep, evict)
+    t0 = time.perf_counter()
+    done = 0
+    for s in range(n_steps):
+        t = L + s
+        p = np.full((nb, 1), t, np.int32)
+        qs = Q[:, t:t + 1]
+        ref.step(K[:, :, t:t + 1], V[:, :, t:t + 1], p, qs, qs.reshape(nb, 1, -1), p, Q[:, t], w.budget,
+                 w.lam, w.eta)
+        done += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = (time.perf_counter() - t0) / (done * nb)   # one decode step of one (layer, batch element)
+    pairs = w.batch * w.n_layers
+    return {"value": w.batch / (dt * pairs), "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": (f"{done} decode steps of all {w.n_kv_heads} KV heads of {nb} of {pairs} (layer, batch element) "
+                       f"pairs at budget {w.budget}: {dt * 1e3:.2f} ms per pair-step, {dt * done * nb:.1f} s of CPU work, "
+                       "extrapolated to all pairs run one after another")}
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quiet", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
+                 "(units shard by batch / KV head with no communication; see DESIGN.md)")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    w = WORKLOADS[a.workload]
+    log = (lambda s: None) if a.quiet else (lambda s: print("[bench] " + s, file=sys.stderr, flush=True))
+    torch.cuda.set_device(0)
+    n_total = a.warmup + 2 * a.steps
+    t_setup = time.perf_counter()
+    job = Job(w, n_total, log=log)
+    torch.cuda.synchronize()
+    log(f"setup (generation + prefill eviction of {w.n_layers} layers) {time.perf_counter() - t_setup:.1f} s")
+
+    for s in range(a.warmup):
+        job.step(s)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for s in range(a.warmup, a.warmup + a.steps):
+        job.step(s)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / a.steps
+    log(f"timed {a.steps} steps: {ms_per_step:.3f} ms/step wall, {e0.elapsed_time(e1) / a.steps:.3f} ms/step on stream")
+
+    # dominant kernel: its launches bracketed by events on the launch stream, same steps again
+    evs = []
+    for s in range(a.warmup + a.steps, a.warmup + 2 * a.steps):
+        job.step(s, attn_events=evs)
+    torch.cuda.synchronize()
+    attn_ms = float(np.mean([x.elapsed_time(y) for x, y in evs]))
+    ab = algorithmic_bytes(w)
+    achieved = ab["attention_kv_per_layer"] / (attn_ms * 1e-3) / 1e9
+    assert im.im_query_status(job.handle) == 0
+
+    rec = {
+        "metric": "decode tokens/s with eviction+memory at 16K ctx; achieved HBM GB/s vs peak",
+        "value": w.batch / (wall / a.steps), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_q_heads}/{w.n_kv_heads}x{w.head_dim} heads, {w.n_layers} layers, "
+                               f"batch {w.batch}, context {w.context} -> budget {w.budget}, one eviction per decode step",
+                   "layers": w.n_layers, "batch": w.batch, "budget": w.budget, "context": w.context,
+                   "algorithmic_bytes_per_step": ab["per_layer_step"] * w.n_layers,
+                   "whole_step_GBps": ab["per_layer_step"] * w.n_layers / (wall / a.steps) / 1e9},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "k_attn_partial + k_attn_combine (im_decode_attn_with_readout)",
+                     "avg_launch_us": attn_ms * 1e3, "bytes_per_launch": ab["attention_kv_per_layer"]},
+    }
+    if not a.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample ...")
+        rec["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(rec), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -42,6 +42,10 @@ extern "C" {
 /* bits of the device-side status word returned by im_query_status() */
 #define IM_STATUS_APPEND_OVERFLOW 1 /* an append would have exceeded `capacity`; it was dropped */
 #define IM_STATUS_LIVE_EXCEEDED 2   /* a unit's length exceeded the im_set_max_live() promise   */
+#define IM_STATUS_WAIT_TIMEOUT 4    /* im_decode_step: a bounded in-kernel wait ran out (results of
+                                       that call are invalid; the kernel still ended)             */
+#define IM_STATUS_OVER_BUDGET 8     /* im_decode_step: a unit entered with len > budget; only one
+                                       entry was evicted from it                                  */
 
 typedef struct im_handle im_handle; /* opaque: validated config + workspace pointer, host memory */
 
@@ -166,6 +170,25 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
  * q, out [B, H, d_head] bf16; readout_dbg [B, H, d_head] fp32. */
 int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_state* st,
                                     const void* q, void* out, float* readout_dbg, void* stream);
+
+/* The whole step for ONE new token per sequence, fused into two launches: exactly
+ *   im_append_kv(n_new = 1) -> im_index_score(n_q = 1) -> im_topb_select(budget) ->
+ *   im_memory_update(lambda, eta) -> im_compact_kv -> im_decode_attn_with_readout
+ * (Sections 2.2, 3.1, 3.2 of the paper, as cited at those calls) for the steady state of decoding
+ * with one eviction per step: every unit must enter with len <= budget, so that at most one entry
+ * (the one ranked last by im_topb_select's order) leaves.  A unit that enters above the budget
+ * still evicts only one entry and raises IM_STATUS_OVER_BUDGET.
+ * q [B, H, d_head] bf16 is both the indexer's query input and the attention query; x_gate
+ * [B, gate_in_dim] bf16; q_pos [B] int32; k_new, v_new [B, H_kv, 1, d_head] bf16; pos_new [B].
+ * out [B, H, d_head] bf16.  Optional (NULL to skip): readout_dbg [B, H, d_head] fp32,
+ * evicted_slot [B, H_kv] int32 (slot that was evicted, before compaction; -1 if none),
+ * scores_dbg [B, H_kv, C] fp32 (as im_index_score writes them).
+ * batch <= 64.  n_sink + n_recent <= budget <= capacity - 1 is not required, but a unit with
+ * len = capacity cannot take the new token (IM_STATUS_APPEND_OVERFLOW). */
+int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                       const void* x_gate, const int32_t* q_pos, const void* k_new, const void* v_new,
+                       const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,
+                       float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream);
 
 #ifdef __cplusplus
 }

@@ -16,12 +16,12 @@ import torch
 from . import build as _build
 
 IM_OK, IM_ERR_INVALID_ARG, IM_ERR_UNSUPPORTED, IM_ERR_LAUNCH = 0, -1, -2, -3
-IM_STATUS_APPEND_OVERFLOW, IM_STATUS_LIVE_EXCEEDED = 1, 2
+IM_STATUS_APPEND_OVERFLOW, IM_STATUS_LIVE_EXCEEDED, IM_STATUS_WAIT_TIMEOUT, IM_STATUS_OVER_BUDGET = 1, 2, 4, 8
 
 EXPORTS = [
     "im_workspace_bytes", "im_create", "im_destroy", "im_last_error", "im_set_max_live",
     "im_query_status", "im_append_kv", "im_index_score", "im_topb_select", "im_memory_update",
-    "im_compact_kv", "im_decode_attn_with_readout",
+    "im_compact_kv", "im_decode_attn_with_readout", "im_decode_step",
 ]
 
 
@@ -86,6 +86,9 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     lib.im_compact_kv.argtypes = [vp, C.POINTER(ImState), vp, vp, vp, vp, vp]
     lib.im_decode_attn_with_readout.restype = i32
     lib.im_decode_attn_with_readout.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, vp]
+    lib.im_decode_step.restype = i32
+    lib.im_decode_step.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, vp, vp, vp, i32,
+                                   f32, f32, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -232,3 +235,10 @@ def im_compact_kv(h: Handle, st: State, keep_idx, n_keep, evict_idx, n_evict) ->
 def im_decode_attn_with_readout(h: Handle, p: Params, st: State, q, out, readout_dbg=None) -> None:
     h.check(h.lib.im_decode_attn_with_readout(h.h, C.byref(p.c), C.byref(st.c), _ptr(q), _ptr(out),
                                               _ptr(readout_dbg), _stream()))
+
+
+def im_decode_step(h: Handle, p: Params, st: State, q, x_gate, q_pos, k_new, v_new, pos_new, budget: int,
+                   lam: float, eta: float, out, readout_dbg=None, evicted_slot=None, scores_dbg=None) -> None:
+    h.check(h.lib.im_decode_step(h.h, C.byref(p.c), C.byref(st.c), _ptr(q), _ptr(x_gate), _ptr(q_pos),
+                                 _ptr(k_new), _ptr(v_new), _ptr(pos_new), budget, lam, eta, _ptr(out),
+                                 _ptr(readout_dbg), _ptr(evicted_slot), _ptr(scores_dbg), _stream()))

@@ -11,6 +11,7 @@
 #include <string.h>
 
 #include "im_kernels.h"
+#include "im_decode.h"
 
 struct im_handle {
   im_config cfg;
@@ -19,8 +20,8 @@ struct im_handle {
   int max_live;
   bool ws_ready;
   // workspace layout (byte offsets)
-  size_t off_status, off_qy, off_alpha, off_mem, off_attn, total;
-  int mem_split, attn_chunks;
+  size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, total;
+  int mem_split, attn_chunks, dec_splits;
   char err[256];
 };
 
@@ -69,11 +70,15 @@ void layout(const im_config* c, im_handle* h) {
   if (h->mem_split > 32) h->mem_split = 32;
   h->attn_chunks = (c->capacity + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK;
   size_t off = 0;
-  h->off_status = off; off = align256(off + 256);
+  // status word, 16 head counters, then one counter and one newest-position word per unit
+  h->off_status = off; off = align256(off + (32 + 2 * units) * sizeof(int32_t));
+  h->dec_splits = (c->capacity + DEC_KEYS - 1) / DEC_KEYS;
   h->off_qy = off;     off = align256(off + B * c->max_queries * Hi * IM_DI * sizeof(double));
   h->off_alpha = off;  off = align256(off + B * c->max_queries * Hi * sizeof(double));
   h->off_mem = off;    off = align256(off + units * h->mem_split * (IM_DM * IM_D + IM_DM) * sizeof(float));
   h->off_attn = off;   off = align256(off + B * c->n_q_heads * h->attn_chunks * IM_ATT_REC * sizeof(float));
+  h->off_dpart = off;  off = align256(off + units * h->dec_splits * DEC_GMAX * DEC_REC * sizeof(float));
+  h->off_dcand = off;  off = align256(off + units * h->dec_splits * DEC_CAND * sizeof(uint32_t));
   h->total = off;
 }
 
@@ -85,7 +90,8 @@ int launch_check(im_handle* h, const char* what) {
 
 int ensure_ws(im_handle* h, hipStream_t s) {
   if (h->ws_ready) return IM_OK;
-  k_fill_i32<<<1, 64, 0, s>>>((int32_t*)(h->ws + h->off_status), 64, 0);
+  const int n_words = 32 + 2 * h->cfg.batch * h->cfg.n_kv_heads;
+  k_fill_i32<<<(n_words + 255) / 256, 256, 0, s>>>((int32_t*)(h->ws + h->off_status), n_words, 0);
   int rc = launch_check(h, "workspace clear");
   if (rc == IM_OK) h->ws_ready = true;
   return rc;
@@ -310,6 +316,55 @@ int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_s
       part, h->attn_chunks, st->len, (const bf16_t*)q, (const bf16_t*)p->Wtheta, (const bf16_t*)p->wg,
       p->cg, st->M, st->b, c.n_q_heads, c.n_kv_heads, h->max_live, c.mem_eps, (bf16_t*)out, readout_dbg);
   return launch_check(h, "im_decode_attn_with_readout");
+}
+
+int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                       const void* x_gate, const int32_t* q_pos, const void* k_new, const void* v_new,
+                       const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,
+                       float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(params_ok(p), "params has a NULL pointer");
+  IM_REQUIRE(state_ok(st), "state has a NULL pointer");
+  IM_REQUIRE(q && x_gate && q_pos && k_new && v_new && pos_new && out, "an input / output pointer is NULL");
+  IM_REQUIRE(budget >= h->cfg.n_sink + h->cfg.n_recent, "budget is below n_sink + n_recent");
+  IM_REQUIRE(budget <= h->cfg.capacity, "budget exceeds capacity");
+  IM_REQUIRE(lambda > 0.f && lambda <= 1.f, "lambda must be in (0, 1]");
+  IM_REQUIRE(eta > 0.f, "eta must be > 0");
+  const im_config& c = h->cfg;
+  if (c.batch > 64) return set_err(h, IM_ERR_UNSUPPORTED, "im_decode_step: batch above 64");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  const int units = c.batch * c.n_kv_heads, G = c.n_q_heads / c.n_kv_heads;
+  int32_t* words = (int32_t*)(h->ws + h->off_status);
+  DecArgs a;
+  a.K = (bf16_t*)st->K; a.V = (bf16_t*)st->V; a.Kidx = (bf16_t*)st->Kidx;
+  a.pos = st->pos; a.len = st->len; a.nproj = st->n_projected; a.M = st->M; a.bvec = st->b;
+  a.Uq = (const bf16_t*)p->Uq; a.Gw = (const bf16_t*)p->G; a.Uk = (const bf16_t*)p->Uk;
+  a.nqw = (const bf16_t*)p->norm_q_w; a.nkw = (const bf16_t*)p->norm_k_w;
+  a.Wt = (const bf16_t*)p->Wtheta; a.wg = (const bf16_t*)p->wg; a.cg = p->cg;
+  a.q = (const bf16_t*)q; a.xg = (const bf16_t*)x_gate; a.k_new = (const bf16_t*)k_new;
+  a.v_new = (const bf16_t*)v_new; a.pos_new = pos_new; a.q_pos = q_pos;
+  a.out = (bf16_t*)out; a.readout = readout_dbg; a.scores = scores_dbg; a.evicted = evicted_slot;
+  a.qy = (double*)(h->ws + h->off_qy); a.alpha = (double*)(h->ws + h->off_alpha);
+  a.status = words; a.cnt_head = words + 16; a.cnt_unit = words + 32; a.maxpos = words + 32 + units;
+  a.part = (float*)(h->ws + h->off_dpart); a.cand = (uint32_t*)(h->ws + h->off_dcand);
+  a.B = c.batch; a.H = c.n_q_heads; a.H_kv = c.n_kv_heads; a.C = c.capacity; a.H_idx = c.n_idx_heads;
+  a.gate_in = c.gate_in_dim; a.n_sink = c.n_sink; a.n_recent = c.n_recent; a.budget = budget;
+  a.S = (h->max_live + DEC_KEYS - 1) / DEC_KEYS; a.S_alloc = h->dec_splits; a.max_live = h->max_live;
+  a.r_first = units <= 128 ? 1 : 0;
+  a.rms_eps = c.rms_eps; a.mem_eps = c.mem_eps; a.scale = c.softmax_scale; a.lambda = lambda; a.eta = eta;
+  const int prep_blocks = c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2 + units;
+  k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);
+  const int main_blocks = units * (a.S + 1);
+#define IM_DEC_CASE(g) case g: k_dec_main<g><<<main_blocks, 256, 0, s>>>(a); break;
+  switch (G) {
+    IM_DEC_CASE(1) IM_DEC_CASE(2) IM_DEC_CASE(3) IM_DEC_CASE(4)
+    IM_DEC_CASE(5) IM_DEC_CASE(6) IM_DEC_CASE(7) IM_DEC_CASE(8)
+    default: return set_err(h, IM_ERR_UNSUPPORTED, "group size %d", G);
+  }
+#undef IM_DEC_CASE
+  return launch_check(h, "im_decode_step");
 }
 
 }  // extern "C"

@@ -22,6 +22,7 @@ class Layer:
         self.n_evict = torch.zeros((Bz, Hk), dtype=torch.int32, device=device)
         self.out = torch.empty((Bz, cfg.n_q_heads, cfg.head_dim), dtype=torch.bfloat16, device=device)
         self.readout = torch.empty((Bz, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device=device)
+        self.evicted = torch.full((Bz, Hk), -1, dtype=torch.int32, device=device)
 
     def step(self, k_new, v_new, pos_new, q_new, x_gate, q_pos, q_attn, budget, lam, eta):
         """append -> score -> select -> memory update -> compact -> attention + readout."""
@@ -32,4 +33,11 @@ class Layer:
         B.im_memory_update(h, p, st, self.evict_idx, self.n_evict, lam, eta)
         B.im_compact_kv(h, st, self.keep_idx, self.n_keep, self.evict_idx, self.n_evict)
         B.im_decode_attn_with_readout(h, p, st, q_attn, self.out, self.readout)
+        return self.out
+
+    def decode_step(self, k_new, v_new, pos_new, q, x_gate, q_pos, budget, lam, eta, debug=False):
+        """The same step for one new token per sequence through the fused entry point."""
+        B.im_decode_step(self.h, self.p, self.st, q, x_gate, q_pos, k_new, v_new, pos_new, budget, lam, eta,
+                         self.out, self.readout if debug else None, self.evicted if debug else None,
+                         self.scores if debug else None)
         return self.out

@@ -86,12 +86,36 @@ class LockStep:
             self.compare(scores, keep, evict, out, res, tag)
         return scores, keep, evict, out, res
 
-    def compare(self, scores, keep, evict, out, res, tag):
+    def event_fused(self, t: int, budget: int, tag: str, check=True):
+        """One decode token through im_decode_step on the GPU and the step-by-step oracle."""
+        w, dev = self.w, self.dev
+        k_new = self.K[:, :, t:t + 1].contiguous()
+        v_new = self.V[:, :, t:t + 1].contiguous()
+        q_new = self.Q[:, t:t + 1].contiguous()
+        pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+        d = lambda x: x.to(dev)
+        qd = d(q_new).view(w.batch, w.n_q_heads, w.head_dim)
+        posd = d(pos).view(w.batch)
+        self.gpu.decode_step(d(k_new), d(v_new), posd, qd, qd.view(w.batch, -1), posd, budget, w.lam, w.eta,
+                             debug=True)
+        torch.cuda.synchronize()
+        bi, hs = self.batch_ids, self.kv_heads
+        sel = lambda x: f64(x)[bi][:, hs]
+        qn = f64(q_new)[bi]
+        posn = pos.numpy()[bi]
+        scores, keep, evict, out, res = self.ref.step(
+            sel(k_new), sel(v_new), posn, qn, qn.reshape(len(bi), 1, -1), posn, f64(q_new[:, 0])[bi],
+            budget, w.lam, w.eta)
+        if check:
+            self.compare(scores, keep, evict, out, res, tag, fused=True)
+
+    def compare(self, scores, keep, evict, out, res, tag, fused=False):
         w, g = self.w, self.gpu
         G = w.group
         n_keep = g.n_keep.cpu().numpy(); n_evict = g.n_evict.cpu().numpy()
         keep_idx = g.keep_idx.cpu().numpy(); evict_idx = g.evict_idx.cpu().numpy()
         sc = g.scores.cpu().numpy()
+        evicted = g.evicted.cpu().numpy()
         st = g.st
         lens = st.len.cpu().numpy(); nproj = st.n_projected.cpu().numpy()
         pos = st.pos.cpu().numpy()
@@ -108,9 +132,14 @@ class LockStep:
                 same = (s_ref == s_gpu) | (np.isneginf(s_ref) & np.isneginf(s_gpu))
                 assert same.all(), (f"{u}: {int((~same).sum())} of {n_before} scores differ, max "
                                     f"{np.nanmax(np.abs(np.where(same, 0, s_ref - s_gpu))):.3e}")
-                assert n_keep[b, h] == len(kr) and n_evict[b, h] == len(er), u
-                assert np.array_equal(keep_idx[b, h, :len(kr)], kr), f"{u}: keep list differs"
-                assert np.array_equal(evict_idx[b, h, :len(er)], er), f"{u}: evict list differs"
+                if fused:
+                    assert len(er) <= 1, u
+                    want_e = int(er[0]) if len(er) else -1
+                    assert evicted[b, h] == want_e, f"{u}: evicted slot {evicted[b, h]} != {want_e}"
+                else:
+                    assert n_keep[b, h] == len(kr) and n_evict[b, h] == len(er), u
+                    assert np.array_equal(keep_idx[b, h, :len(kr)], kr), f"{u}: keep list differs"
+                    assert np.array_equal(evict_idx[b, h, :len(er)], er), f"{u}: evict list differs"
                 n = int(self.ref.len[ib, ih])
                 assert lens[b, h] == n and nproj[b, h] == n, u
                 assert np.array_equal(pos[b, h, :n], self.ref.pos[ib, ih, :n]), f"{u}: positions"
@@ -125,7 +154,7 @@ class LockStep:
                 assert dmax <= 1e-3 * float(np.max(np.abs(rr))) + 1e-30, f"{u}: readout diff {dmax:.3e}"
 
     # -- schedules --------------------------------------------------------------------------------
-    def run_schedule(self, decode_steps=None):
+    def run_schedule(self, decode_steps=None, fused_decode=False):
         w = self.w
         steps = w.decode_steps if decode_steps is None else decode_steps
         L = w.context
@@ -136,5 +165,8 @@ class LockStep:
                 self.event(c0, min(L, c0 + w.prefill_chunk), w.budget, f"chunk@{c0}")
         im.im_set_max_live(self.handle, min(self.cap, w.budget + 1))
         for t in range(L, L + steps):
-            self.event(t, t + 1, w.budget, f"decode@{t}")
+            if fused_decode:
+                self.event_fused(t, w.budget, f"fused decode@{t}")
+            else:
+                self.event(t, t + 1, w.budget, f"decode@{t}")
         assert im.im_query_status(self.handle) == 0

@@ -30,6 +30,33 @@ def test_reduced_configurations(name, kw):
     LockStep(WORKLOADS[name].scaled(n_layers=1, **kw)).run_schedule()
 
 
+def test_cfg1_full_trajectory_fused_decode():
+    # the same trajectory with every decode step through im_decode_step (two launches per step)
+    LockStep(WORKLOADS["cfg1"]).run_schedule(fused_decode=True)
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("cfg2", dict(batch=2, context=1100, budget=300, decode_steps=4)),
+    ("cfg3", dict(batch=2, context=1500, budget=333, decode_steps=4)),
+    ("cfg4", dict(batch=3, context=1300, budget=130, decode_steps=4)),       # 7 query heads per KV head
+    ("cfg4", dict(batch=2, context=700, budget=128, decode_steps=3)),        # n = 129: a one-key last split
+    ("cfg5", dict(batch=1, context=1536, budget=512, decode_steps=4, prefill_chunk=512)),
+    ("cfg1", dict(context=40, budget=64, decode_steps=30)),                  # grows to the budget, then evicts
+    ("cfg1", dict(context=300, budget=64, decode_steps=3, n_recent=8)),      # recent window forced
+])
+def test_reduced_configurations_fused_decode(name, kw):
+    w = WORKLOADS[name].scaled(n_layers=1, **kw)
+    LockStep(w, capacity=max(w.capacity, w.budget + 2)).run_schedule(fused_decode=True)
+
+
+def test_fused_decode_ties_evict_newest_then_largest_slot():
+    # a zero gate makes every visible score 0: the entry ranked last is the newest position
+    w = WORKLOADS["cfg1"].scaled(context=200, budget=200, decode_steps=5, param_std=0.0)
+    ls = LockStep(w, capacity=256)
+    ls.run_schedule(fused_decode=True)
+    assert int(ls.gpu.st.len.max()) == 200
+
+
 def test_recent_window_and_budget_above_context():
     w = WORKLOADS["cfg1"].scaled(context=300, budget=64, decode_steps=2, n_recent=8)
     LockStep(w).run_schedule()
