@@ -42,8 +42,6 @@ extern "C" {
 /* bits of the device-side status word returned by im_query_status() */
 #define IM_STATUS_APPEND_OVERFLOW 1 /* an append would have exceeded `capacity`; it was dropped */
 #define IM_STATUS_LIVE_EXCEEDED 2   /* a unit's length exceeded the im_set_max_live() promise   */
-#define IM_STATUS_WAIT_TIMEOUT 4    /* im_decode_step: a bounded in-kernel wait ran out (results of
-                                       that call are invalid; the kernel still ended)             */
 #define IM_STATUS_OVER_BUDGET 8     /* im_decode_step: a unit entered with len > budget; only one
                                        entry was evicted from it                                  */
 
@@ -171,7 +169,7 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
 int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_state* st,
                                     const void* q, void* out, float* readout_dbg, void* stream);
 
-/* The whole step for ONE new token per sequence, fused into two launches: exactly
+/* The whole step for ONE new token per sequence, fused into three launches: exactly
  *   im_append_kv(n_new = 1) -> im_index_score(n_q = 1) -> im_topb_select(budget) ->
  *   im_memory_update(lambda, eta) -> im_compact_kv -> im_decode_attn_with_readout
  * (Sections 2.2, 3.1, 3.2 of the paper, as cited at those calls) for the steady state of decoding
@@ -189,6 +187,16 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
                        const void* x_gate, const int32_t* q_pos, const void* k_new, const void* v_new,
                        const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,
                        float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream);
+
+/* Kernel timing for benchmarks (not part of the method).  After im_profile_start, every
+ * im_decode_step on this handle brackets its main kernel (scoring and attention partials of
+ * every 128-key split: the launch that streams the cache) with a pair of HIP events on the
+ * launch stream, for at most
+ * max_records calls.  im_profile_stop WAITS for `stream`, writes the elapsed milliseconds of the
+ * recorded launches to ms_host[0 .. *n_records) (host pointers; ms_host holds max_records floats)
+ * and releases the events.  Do not use while the stream is being captured into a graph. */
+int32_t im_profile_start(im_handle* h, int32_t max_records);
+int32_t im_profile_stop(im_handle* h, float* ms_host, int32_t* n_records, void* stream);
 
 #ifdef __cplusplus
 }

@@ -16,12 +16,13 @@ import torch
 from . import build as _build
 
 IM_OK, IM_ERR_INVALID_ARG, IM_ERR_UNSUPPORTED, IM_ERR_LAUNCH = 0, -1, -2, -3
-IM_STATUS_APPEND_OVERFLOW, IM_STATUS_LIVE_EXCEEDED, IM_STATUS_WAIT_TIMEOUT, IM_STATUS_OVER_BUDGET = 1, 2, 4, 8
+IM_STATUS_APPEND_OVERFLOW, IM_STATUS_LIVE_EXCEEDED, IM_STATUS_OVER_BUDGET = 1, 2, 8
 
 EXPORTS = [
     "im_workspace_bytes", "im_create", "im_destroy", "im_last_error", "im_set_max_live",
     "im_query_status", "im_append_kv", "im_index_score", "im_topb_select", "im_memory_update",
-    "im_compact_kv", "im_decode_attn_with_readout", "im_decode_step",
+    "im_compact_kv", "im_decode_attn_with_readout", "im_decode_step", "im_profile_start",
+    "im_profile_stop",
 ]
 
 
@@ -89,6 +90,10 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     lib.im_decode_step.restype = i32
     lib.im_decode_step.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, vp, vp, vp, i32,
                                    f32, f32, vp, vp, vp, vp, vp]
+    lib.im_profile_start.restype = i32
+    lib.im_profile_start.argtypes = [vp, i32]
+    lib.im_profile_stop.restype = i32
+    lib.im_profile_stop.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32), vp]
     _lib = lib
     return lib
 
@@ -242,3 +247,16 @@ def im_decode_step(h: Handle, p: Params, st: State, q, x_gate, q_pos, k_new, v_n
     h.check(h.lib.im_decode_step(h.h, C.byref(p.c), C.byref(st.c), _ptr(q), _ptr(x_gate), _ptr(q_pos),
                                  _ptr(k_new), _ptr(v_new), _ptr(pos_new), budget, lam, eta, _ptr(out),
                                  _ptr(readout_dbg), _ptr(evicted_slot), _ptr(scores_dbg), _stream()))
+
+
+def im_profile_start(h: Handle, max_records: int) -> None:
+    h._prof_max = max_records
+    h.check(h.lib.im_profile_start(h.h, max_records))
+
+
+def im_profile_stop(h: Handle):
+    """Returns the list of main-kernel durations (ms) recorded since im_profile_start."""
+    buf = (C.c_float * h._prof_max)()
+    n = C.c_int32(0)
+    h.check(h.lib.im_profile_stop(h.h, buf, C.byref(n), _stream()))
+    return [buf[i] for i in range(n.value)]

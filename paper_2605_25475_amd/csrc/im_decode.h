@@ -1,11 +1,14 @@
-// Fused decode step: the whole path for one new token per sequence in two launches.
+// Fused decode step: the whole path for one new token per sequence in three launches.
 //   k_dec_prep : query-side indexer features (U_q, G GEMVs + QK-Norm), append of the new
 //                (k, v), its indexer key.
 //   k_dec_main : per (unit, 128-key split) workgroups score their keys, find their local
-//                eviction candidate and accumulate softmax-attention partials without it;
-//                one tail workgroup per unit prepares the memory readout meanwhile, then waits
-//                for its splits, picks the evicted entry, folds it into the memory state,
-//                merges the partials, fills the hole and writes the output.
+//                eviction candidate (the entry ranked last) and accumulate softmax-attention
+//                partials WITHOUT it; the candidate's logits and K / V rows go to a record.
+//   k_dec_tail : one workgroup per unit picks the evicted entry among the candidates, folds it
+//                into the memory state, merges the partials plus the candidates that stay,
+//                adds the gated readout, fills the hole and writes the output.
+// A kernel boundary separates main and tail on purpose: on this chip a device-scope release
+// (L2 write-back) per workgroup or an in-kernel wait costs several microseconds more than a launch.
 // Same results as append -> index_score (n_q = 1) -> topb_select -> memory_update -> compact_kv
 // -> decode_attn_with_readout whenever every unit enters with len <= budget.
 #pragma once
@@ -14,16 +17,27 @@
 #define DEC_KEYS 128                 // keys per split workgroup (8 MFMA tiles of 16)
 #define DEC_REC (IM_D + 2)           // partial record per (unit, split, head): max, denom, 128 numerators
 #define DEC_GMAX 8                   // query heads per KV head supported
-#define DEC_CAND 16                  // words per candidate record
-#define DEC_SPIN_LIMIT (1 << 20)
+#define DEC_CAND 144                 // words per candidate record: 16 header, 64 K row, 64 V row
+#define DEC_CAND_K 16
+#define DEC_CAND_V 80
 
 #define IM_STATUS_APPEND_OVERFLOW_BIT 1
 #define IM_STATUS_LIVE_EXCEEDED_BIT 2
-#define IM_STATUS_WAIT_TIMEOUT_BIT 4
 #define IM_STATUS_OVER_BUDGET_BIT 8
+
+// Optional phase stamps for kernel tuning (compiled out unless IM_DEC_TRACE is defined):
+// workgroup `IM_DEC_TRACE` writes wall_clock64() (100 MHz) at phase boundaries into a buffer.
+#ifdef IM_DEC_TRACE
+extern "C" __device__ unsigned long long im_trace_buf[256];
+__device__ unsigned long long im_trace_buf[256];
+#define DEC_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x == (IM_DEC_TRACE)) im_trace_buf[slot] = wall_clock64(); } while (0)
+#else
+#define DEC_STAMP(slot) do { } while (0)
+#endif
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef double v4d __attribute__((ext_vector_type(4)));
 
 struct DecArgs {
   // state
@@ -43,11 +57,11 @@ struct DecArgs {
   int32_t* evicted;   // optional
   // workspace
   double *qy, *alpha;
-  int32_t *cnt_head, *cnt_unit, *status, *maxpos;
+  int32_t *status, *maxpos;
   float* part;
   uint32_t* cand;
   // scalars
-  int B, H, H_kv, C, H_idx, gate_in, n_sink, n_recent, budget, S, S_alloc, max_live, r_first;
+  int B, H, H_kv, C, H_idx, gate_in, n_sink, n_recent, budget, S, S_alloc, max_live;
   float rms_eps, mem_eps, scale, lambda, eta;
 };
 
@@ -57,8 +71,8 @@ __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
 }
 
 // --------------------------------------------------------------------------------------------
-// k_dec_prep.  Blocks [0, nU): two rows of U_q each, all batch rows; the last block of an
-// indexer head to finish normalises that head.  Blocks [nU, nU + nG): two rows of G.
+// k_dec_prep.  Blocks [0, nU): two rows of U_q each, all batch rows (raw projections, fp64).
+// Blocks [nU, nU + nG): two rows of G.
 // Blocks after: one per unit, append + indexer key of the new token.
 // --------------------------------------------------------------------------------------------
 __device__ void dec_gemv2(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Bm, int n0, int N,
@@ -110,7 +124,6 @@ __device__ void dec_gemv2(const bf16_t* __restrict__ A, const bf16_t* __restrict
 __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   __shared__ double red[4][16];
   __shared__ double rows[64 * 2];   // up to 64 batch rows x 2 outputs
-  __shared__ int s_last;
   __shared__ float s_k[IM_D];
   __shared__ double s_u[IM_DI];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -120,36 +133,16 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   if (blk < nU) {
     const int n0 = blk * 2;
     dec_gemv2(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, red, rows);
+    // raw projections; the consumer applies the QK-Norm (it needs a whole head, this block has 2 rows)
     for (int i = tid; i < a.B * 2; i += 256) a.qy[(size_t)(i >> 1) * Nq + n0 + (i & 1)] = rows[i];
-    __threadfence();
-    __syncthreads();
-    const int head = n0 / IM_DI;
-    if (tid == 0) {
-      const int old = __hip_atomic_fetch_add(a.cnt_head + head, 1, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-      s_last = (old == IM_DI / 2 - 1);
-    }
-    __syncthreads();
-    if (s_last) {  // every row of this head is in memory: QK-Norm for all batch rows
-      __threadfence();
-      for (int b = w; b < a.B; b += 4) {
-        double* y = a.qy + (size_t)b * Nq + head * IM_DI;
-        const double v = __hip_atomic_load(y + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const double ss = wave_sum_d(v * v);
-        const double rr = sqrt(ss / (double)IM_DI + (double)a.rms_eps);
-        const double wt = a.nqw ? (double)bf2f(a.nqw[lane]) : 1.0;
-        y[lane] = (double)(float)(v / rr * wt);
-      }
-      if (tid == 0) a.cnt_head[head] = 0;
-    }
     return;
   }
   if (blk < nU + nG) {
     const int n0 = (blk - nU) * 2;
     dec_gemv2(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, red, rows);
-    const double denom = sqrt((double)(a.H_idx * IM_DI));
     for (int i = tid; i < a.B * 2; i += 256) {
       const int r = n0 + (i & 1);
-      if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = (double)(float)(rows[i] / denom);
+      if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = rows[i];   // raw G x; scaled by the consumer
     }
     return;
   }
@@ -218,31 +211,20 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
 // k_dec_main
 // --------------------------------------------------------------------------------------------
 struct DecSplitSmem {
-  bf16_t ks[DEC_KEYS][72];           // indexer keys of the split, row stride 144 B
-  double pa[DEC_KEYS];               // second half of the heads' gated sum
-  float pl[DEC_KEYS][8];             // logits, then probabilities, [key][head]
-  float oacc[4][DEC_GMAX][IM_D];     // per-wave output partials
+  union {
+    double zs[DEC_KEYS][17];         // gated similarities alpha_j ReLU(q_j . k) [key][indexer head]
+    float oacc[16][4][IM_D];         // later: output partials of the 16 (wave, key group) streams,
+  };                                 //        4 heads at a time
+  float pl[DEC_KEYS][8];             // probabilities [key][head]
   float wm[4][8], wl[4][8];
   float clog[8];
   unsigned long long c64[2];
   int cslot[2];
 };
 
-struct DecTailSmem {
-  float qs[DEC_GMAX][IM_D];
-  float php[2][DEC_GMAX][IM_DM];
-  float phq[DEC_GMAX][IM_DM];
-  float red[4][DEC_GMAX][IM_D];
-  float rold[DEC_GMAX][IM_D];
-  float ke[IM_D], ve[IM_D], phe2[2][IM_DM], phe[IM_DM], bnew[IM_DM];
-  float gate[DEC_GMAX], den[DEC_GMAX], dot[DEC_GMAX];
-  unsigned long long c64[4];
-  int cidx[4];
-  int e_slot, e_split, timeout;
-};
-
 template <int G>
-__device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const int s, DecSplitSmem& sm) {
+__device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const int s, DecSplitSmem& sm,
+                                          const double* __restrict__ qy, const double* __restrict__ alpha) {
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int b = u / a.H_kv, h = u % a.H_kv;
   const int n_old = a.len[u];
@@ -253,18 +235,26 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   if (nk > 0) {
     const size_t base = (size_t)u * a.C + k0;
     const int l16 = lane & 15, kq = lane >> 4;
-    // ---- issue every load of this split up front
-    uint4 kst[4];
+    DEC_STAMP(0);
+    // ---- issue every load of this split up front; the query features first (they are used first)
+    // Indexer query features as the B operand of the fp64 MFMA: lane (head l16, kq) holds
+    // dims 16 kq .. 16 kq + 15 of head l16.
+    const bool hv = l16 < a.H_idx;
+    double qd[16];
+    {
+      const double* yrow = qy + ((size_t)b * a.H_idx + (hv ? l16 : 0)) * IM_DI + 16 * kq;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int ch = tid + 256 * i, row = ch >> 3, c8 = ch & 7;
-      kst[i] = (row < nk) ? *(const uint4*)(a.Kidx + (base + row) * IM_DI + c8 * 8) : make_uint4(0, 0, 0, 0);
+      for (int m = 0; m < 16; ++m) qd[m] = yrow[m];
     }
-    uint4 kf[2][4], vf[2][4], qf[4];
+    const double araw = alpha[(size_t)b * a.H_idx + (hv ? l16 : 0)];
+    uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
       const int T = 2 * w + tt;
       const int kr = 16 * T + l16;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        kif[tt][i] = (kr < nk) ? *(const uint4*)(a.Kidx + (base + kr) * IM_DI + 16 * kq + 8 * i) : make_uint4(0, 0, 0, 0);
 #pragma unroll
       for (int c = 0; c < 4; ++c)
         kf[tt][c] = (kr < nk) ? *(const uint4*)(a.K + (base + kr) * IM_D + 32 * c + 8 * kq) : make_uint4(0, 0, 0, 0);
@@ -278,48 +268,51 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     for (int c = 0; c < 4; ++c)
       qf[c] = (l16 < G) ? *(const uint4*)(a.q + ((size_t)b * a.H + h * G + l16) * IM_D + 32 * c + 8 * kq)
                         : make_uint4(0, 0, 0, 0);
-    const int kk = tid & 127, half = tid >> 7;
+    const int kk = tid & 127;
     const int mypos = (kk < nk) ? a.pos[base + kk] : 0;
     const int qpos = a.q_pos[b];
-    // ---- indexer keys to LDS, then one key per thread (two threads share a key, half the heads each)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int ch = tid + 256 * i, row = ch >> 3, c8 = ch & 7;
-      *(uint4*)&sm.ks[row][c8 * 8] = kst[i];
-    }
-    __syncthreads();
-    double part = 0.0;
+    DEC_STAMP(1);
+    // ---- QK-Norm of the query features (per head over its 64 dims), head gate
+    double alj;
     {
-      double kd[IM_DI];
+      double ss = 0.0;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const uint4 v = *(const uint4*)&sm.ks[kk][i * 8];
-        float f[8];
-        unpack8(v, f);
+      for (int m = 0; m < 16; ++m) ss = fma(qd[m], qd[m], ss);
+      ss += __shfl_xor(ss, 16, 64);
+      ss += __shfl_xor(ss, 32, 64);
+      const double rr = sqrt(ss / (double)IM_DI + (double)a.rms_eps);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) kd[8 * i + e] = (double)f[e];
+      for (int m = 0; m < 16; ++m) {
+        const double wt = a.nqw ? (double)bf2f(a.nqw[16 * kq + m]) : 1.0;
+        qd[m] = hv ? (double)(float)(qd[m] / rr * wt) : 0.0;
       }
-      const int Hh = (a.H_idx + 1) >> 1;
-      const int j0 = half ? Hh : 0, j1 = half ? a.H_idx : Hh;
-      const double* __restrict__ qh = a.qy + (size_t)b * a.H_idx * IM_DI;
-      const double* __restrict__ al = a.alpha + (size_t)b * a.H_idx;
-      for (int j = j0; j < j1; ++j) {
-        double z0 = 0.0, z1 = 0.0;
+      alj = hv ? (double)(float)(araw / sqrt((double)(a.H_idx * IM_DI))) : 0.0;
+    }
+    DEC_STAMP(2);
+    // ---- gated similarities of the 2 tiles of this wave: Z[key][head] = Kidx_tile . q^T (fp64 MFMA)
 #pragma unroll
-        for (int c = 0; c < IM_DI; c += 2) {
-          z0 = fma(qh[j * IM_DI + c], kd[c], z0);
-          z1 = fma(qh[j * IM_DI + c + 1], kd[c + 1], z1);
-        }
-        part = fma(al[j], fmax(z0 + z1, 0.0), part);
+    for (int tt = 0; tt < 2; ++tt) {
+      float f[16];
+      unpack8(kif[tt][0], f);
+      unpack8(kif[tt][1], f + 8);
+      v4d z = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int m = 0; m < 16; ++m) z = __builtin_amdgcn_mfma_f64_16x16x4f64((double)f[m], qd[m], z, 0, 0, 0);
+      const int T = 2 * w + tt;
+      if (hv) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) sm.zs[16 * T + 4 * kq + r][l16] = alj * fmax(z[r], 0.0);
       }
     }
-    if (half) sm.pa[kk] = part;
+    DEC_STAMP(3);
     __syncthreads();
     // ---- score, forced flag, split-local candidate = the entry ranked last
-    if (!half) {
+    if (tid < DEC_KEYS) {
       unsigned long long c64 = ~0ull;
       if (kk < nk) {
-        const float sc = (mypos <= qpos) ? (float)(part + sm.pa[kk]) : -INFINITY;
+        double asum = 0.0;
+        for (int j = 0; j < a.H_idx; ++j) asum += sm.zs[kk][j];
+        const float sc = (mypos <= qpos) ? (float)asum : -INFINITY;
         if (a.scores) a.scores[base + kk] = sc;
         const bool forced = (mypos < a.n_sink) ||
                             (a.n_recent > 0 && (long long)mypos > (long long)a.maxpos[u] - a.n_recent);
@@ -347,6 +340,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       const int s0 = sm.cslot[0], s1 = sm.cslot[1];
       if (s1 >= 0 && (s0 < 0 || c1 <= c0)) { cl = s1; cbest = c1; } else { cl = s0; cbest = c0; }
     }
+    DEC_STAMP(4);
     // ---- logits of the 2 tiles of this wave:  S[key][head] = K_tile . Q^T  (bf16 MFMA, fp32 acc)
     float sreg[2][4];
     float lmax = -INFINITY;
@@ -395,6 +389,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     lsum += __shfl_xor(lsum, 32, 64);
     if (kq == 0 && l16 < 8) sm.wl[w][l16] = lsum;
     __syncthreads();
+    DEC_STAMP(5);
     // ---- O[head][d] += P[head][key] V[key][d]; 16 lanes share a key row (8 dims each)
     float acc[G][8];
 #pragma unroll
@@ -417,46 +412,100 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
           for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(pv[j], v[e], acc[j][e]);
       }
     }
-#pragma unroll
-    for (int j = 0; j < G; ++j)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float x = acc[j][e];
-        x += __shfl_xor(x, 16, 64);
-        x += __shfl_xor(x, 32, 64);
-        if (kq == 0) sm.oacc[w][j][8 * l16 + e] = x;
-      }
-    __syncthreads();
+    DEC_STAMP(6);
+    // the 16 (wave, key group) streams meet in LDS, 4 heads at a time
     float* prec = a.part + ((size_t)u * a.S_alloc + s) * DEC_GMAX * DEC_REC;
-    for (int idx = tid; idx < G * IM_D; idx += 256) {
-      const int j = idx >> 7, d = idx & 127;
-      prec[j * DEC_REC + 2 + d] = sm.oacc[0][j][d] + sm.oacc[1][j][d] + sm.oacc[2][j][d] + sm.oacc[3][j][d];
-      if (d == 0) {
-        float m = fmaxf(fmaxf(sm.wm[0][j], sm.wm[1][j]), fmaxf(sm.wm[2][j], sm.wm[3][j]));
-        prec[j * DEC_REC] = (m == -INFINITY) ? -1e30f : m;
-        prec[j * DEC_REC + 1] = sm.wl[0][j] + sm.wl[1][j] + sm.wl[2][j] + sm.wl[3][j];
+    __syncthreads();   // zs is dead: its space now holds oacc
+#pragma unroll
+    for (int j0 = 0; j0 < G; j0 += 4) {
+      if (j0 > 0) __syncthreads();
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        if (j0 + jj < G) {
+          float* dst = &sm.oacc[w * 4 + kq][jj][8 * l16];
+          *(float4*)dst = make_float4(acc[j0 + jj][0], acc[j0 + jj][1], acc[j0 + jj][2], acc[j0 + jj][3]);
+          *(float4*)(dst + 4) = make_float4(acc[j0 + jj][4], acc[j0 + jj][5], acc[j0 + jj][6], acc[j0 + jj][7]);
+        }
+      }
+      __syncthreads();
+      const int nj = (G - j0 < 4) ? G - j0 : 4;
+      for (int idx = tid; idx < nj * IM_D; idx += 256) {
+        const int jj = idx >> 7, d = idx & 127, j = j0 + jj;
+        float o = 0.f;
+#pragma unroll
+        for (int st = 0; st < 16; ++st) o += sm.oacc[st][jj][d];
+        prec[j * DEC_REC + 2 + d] = o;
+        if (d == 0) {
+          float m = fmaxf(fmaxf(sm.wm[0][j], sm.wm[1][j]), fmaxf(sm.wm[2][j], sm.wm[3][j]));
+          prec[j * DEC_REC] = (m == -INFINITY) ? -1e30f : m;
+          prec[j * DEC_REC + 1] = sm.wl[0][j] + sm.wl[1][j] + sm.wl[2][j] + sm.wl[3][j];
+        }
       }
     }
+    DEC_STAMP(7);
     if (tid == 0) {
       crec[0] = (uint32_t)(cbest >> 32);
       crec[1] = (uint32_t)cbest;
       crec[2] = (uint32_t)(k0 + cl);
     }
     if (tid < G) crec[4 + tid] = __float_as_uint(sm.clog[tid]);
+    // the candidate's rows travel with the record, so the tail has no dependent loads
+    if (tid >= 64 && tid < 80)
+      *(uint4*)(crec + DEC_CAND_K + (tid - 64) * 4) = *(const uint4*)(a.K + (base + cl) * IM_D + (tid - 64) * 8);
+    else if (tid >= 128 && tid < 144)
+      *(uint4*)(crec + DEC_CAND_V + (tid - 128) * 4) = *(const uint4*)(a.V + (base + cl) * IM_D + (tid - 128) * 8);
   }
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) __hip_atomic_fetch_add(a.cnt_unit + u, 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+
+
+template <int G>
+struct DecTailSmem {
+  static constexpr int CH = (G <= 4) ? 16 : 4;   // splits staged per round
+  float pst[CH][G][DEC_REC];                      // partial records of the staged splits
+  uint32_t cst[CH][DEC_CAND];                     // their candidate records
+  float qs[G][IM_D];
+  float php[2][G][IM_DM];
+  float phq[G][IM_DM];
+  float red[4][G][IM_D];
+  float rold[G][IM_D];
+  float ke[IM_D], ve[IM_D], phe2[2][IM_DM], phe[IM_DM], bnew[IM_DM];
+  float gate[G], den[G], dot[G];
+  unsigned long long c64[4];
+  int cidx[4];
+  int e_slot, e_split;
+};
+
+// copy `count` floats (count even, both sides 8-byte aligned) with many loads in flight
+__device__ __forceinline__ void dec_stage(float* dst, const float* __restrict__ src, int count) {
+  const int n2 = count >> 1;
+  for (int base = 0; base < n2; base += 256 * 8) {
+    float2 r[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int i = base + threadIdx.x + 256 * k;
+      r[k] = (i < n2) ? ((const float2*)src)[i] : make_float2(0.f, 0.f);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int i = base + threadIdx.x + 256 * k;
+      if (i < n2) ((float2*)dst)[i] = r[k];
+    }
+  }
 }
 
 template <int G>
-__device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem& sm) {
+__device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem<G>& sm) {
+  constexpr int CH = DecTailSmem<G>::CH;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int b = u / a.H_kv, h = u % a.H_kv;
   const int n_old = a.len[u];
   const bool has_new = n_old + 1 <= a.C;
   const int n = min(n_old + (has_new ? 1 : 0), a.max_live);
-  // ---------------- independent of the eviction decision ----------------
+  const int n_act = (n + DEC_KEYS - 1) / DEC_KEYS;
+  const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
+  const float* pbase = a.part + (size_t)u * a.S_alloc * DEC_GMAX * DEC_REC;
+  // ---------------- every load whose address is known now ----------------
   const int d4 = tid & 31, cg = tid >> 5;
   float4 Mr[16];
   float* Mu = a.M + (size_t)u * IM_DM * IM_D;
@@ -469,8 +518,30 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const float b_old = (tid < IM_DM) ? a.bvec[(size_t)u * IM_DM + tid] : 0.f;
   for (int idx = tid; idx < G * IM_D; idx += 256)
     sm.qs[idx >> 7][idx & 127] = bf2f(a.q[((size_t)b * a.H + h * G) * IM_D + idx]);
-  if (tid == 0) sm.timeout = 0;
+  // candidate keys of the splits beyond the first staged round (none in the usual case)
+  unsigned long long best = ~0ull;
+  int bidx = -1;
+  for (int sp = CH + tid; sp < n_act; sp += 256) {
+    const unsigned long long c = ((unsigned long long)cbase[(size_t)sp * DEC_CAND] << 32) | cbase[(size_t)sp * DEC_CAND + 1];
+    if (c <= best) { best = c; bidx = sp; }   // later splits hold larger slots: they win full ties
+  }
+  // the entry that moves into the hole: the last live slot (rows are read before any write)
+  const int n_last = n - 1;
+  uint4 mv = make_uint4(0, 0, 0, 0);
+  int mvpos = 0;
+  if (n > 0) {
+    const size_t src = (size_t)u * a.C + n_last;
+    if (tid < 16) mv = *(const uint4*)(a.K + src * IM_D + tid * 8);
+    else if (tid < 32) mv = *(const uint4*)(a.V + src * IM_D + (tid - 16) * 8);
+    else if (tid < 40) mv = *(const uint4*)(a.Kidx + src * IM_DI + (tid - 32) * 8);
+    else if (tid == 40) mvpos = a.pos[src];
+  }
+  // first round of split records to LDS
+  const int cn0 = min(CH, n_act);
+  for (int sp = 0; sp < cn0; ++sp) dec_stage(&sm.pst[sp][0][0], pbase + (size_t)sp * DEC_GMAX * DEC_REC, G * DEC_REC);
+  dec_stage((float*)&sm.cst[0][0], (const float*)cbase, cn0 * DEC_CAND);
   __syncthreads();
+  // ---------------- memory readout terms that do not depend on the eviction ----------------
   {  // phi(q_j)[c], two threads per c (64 dims each)
     float pq[G];
 #pragma unroll
@@ -487,13 +558,39 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
 #pragma unroll
     for (int j = 0; j < G; ++j) sm.php[hh][j][wc] = pq[j];
   }
+  // candidate ranked last among the staged splits (one thread per split), merged with the rest
+  if (tid < cn0) {
+    const unsigned long long c = ((unsigned long long)sm.cst[tid][0] << 32) | sm.cst[tid][1];
+    if (bidx < 0 || c < best) { best = c; bidx = tid; }   // staged splits are the EARLIER ones: they lose full ties
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const unsigned long long ob = __shfl_xor(best, o, 64);
+    const int oi = __shfl_xor(bidx, o, 64);
+    if (oi >= 0 && (bidx < 0 || ob < best || (ob == best && oi > bidx))) { best = ob; bidx = oi; }
+  }
+  if (lane == 0) { sm.c64[w] = best; sm.cidx[w] = bidx; }
   __syncthreads();
+  const bool evict = n > a.budget;
+  if (n > a.budget + 1 && tid == 0) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
+  if (tid == 0) {
+    unsigned long long bb = sm.c64[0];
+    int bi = sm.cidx[0];
+    for (int i = 1; i < 4; ++i) {
+      const int oi = sm.cidx[i];
+      if (oi >= 0 && (bi < 0 || sm.c64[i] < bb || (sm.c64[i] == bb && oi > bi))) { bb = sm.c64[i]; bi = oi; }
+    }
+    const bool ev = evict && bi >= 0;
+    sm.e_split = ev ? bi : -1;
+    sm.e_slot = ev ? (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]) : -1;
+  }
   for (int idx = tid; idx < G * IM_DM; idx += 256) {
     const int j = idx >> 7, c = idx & 127;
     sm.phq[j][c] = sm.php[0][j][c] + sm.php[1][j][c];
   }
   __syncthreads();
-  // gate and the old denominator: one wave per head
+  const int e_split = sm.e_split, e_slot = sm.e_slot;
+  // gate: one wave per head
   for (int j = w; j < G; j += 4) {
     float gz = bf2f(a.wg[lane]) * sm.qs[j][lane] + bf2f(a.wg[lane + 64]) * sm.qs[j][lane + 64];
     gz = wave_sum_f(gz);
@@ -521,63 +618,22 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
         if (lane < 32) sm.red[w][j][4 * d4 + e] = x;
       }
   }
+  // the evicted entry's rows come with its candidate record
+  if (e_slot >= 0 && tid < IM_D) {
+    const bf16_t* kr = (e_split < CH) ? (const bf16_t*)&sm.cst[e_split][DEC_CAND_K]
+                                      : (const bf16_t*)(cbase + (size_t)e_split * DEC_CAND + DEC_CAND_K);
+    const bf16_t* vr = (e_split < CH) ? (const bf16_t*)&sm.cst[e_split][DEC_CAND_V]
+                                      : (const bf16_t*)(cbase + (size_t)e_split * DEC_CAND + DEC_CAND_V);
+    sm.ke[tid] = bf2f(kr[tid]);
+    sm.ve[tid] = bf2f(vr[tid]);
+  }
   __syncthreads();
   for (int idx = tid; idx < G * IM_D; idx += 256) {
     const int j = idx >> 7, d = idx & 127;
     sm.rold[j][d] = sm.red[0][j][d] + sm.red[1][j][d] + sm.red[2][j][d] + sm.red[3][j][d];
   }
-  // ---------------- wait for the splits of this unit ----------------
-  if (tid == 0) {
-    int spins = 0;
-    while (__hip_atomic_load(a.cnt_unit + u, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < a.S) {
-      if (++spins > DEC_SPIN_LIMIT) { sm.timeout = 1; break; }
-      __builtin_amdgcn_s_sleep(4);
-    }
-  }
-  __syncthreads();
-  __threadfence();
-  if (sm.timeout && tid == 0) atomicOr(a.status, IM_STATUS_WAIT_TIMEOUT_BIT);
-  const int n_act = (n + DEC_KEYS - 1) / DEC_KEYS;
-  const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
-  const float* pbase = a.part + (size_t)u * a.S_alloc * DEC_GMAX * DEC_REC;
-  // ---------------- the evicted entry: ranked last over all splits ----------------
-  const bool evict = n > a.budget;
-  if (n > a.budget + 1 && tid == 0) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
-  {
-    unsigned long long best = ~0ull;
-    int bidx = -1;
-    for (int sp = tid; sp < n_act; sp += 256) {
-      const unsigned long long c = ((unsigned long long)cbase[sp * DEC_CAND] << 32) |
-                                   cbase[sp * DEC_CAND + 1];
-      // later splits hold larger slots: on a full tie the larger slot is ranked last
-      if (c <= best) { best = c; bidx = sp; }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-      const unsigned long long ob = __shfl_xor(best, o, 64);
-      const int oi = __shfl_xor(bidx, o, 64);
-      if (ob < best || (ob == best && oi > bidx)) { best = ob; bidx = oi; }
-    }
-    if (lane == 0) { sm.c64[w] = best; sm.cidx[w] = bidx; }
-    __syncthreads();
-    if (tid == 0) {
-      unsigned long long bb = sm.c64[0];
-      int bi = sm.cidx[0];
-      for (int i = 1; i < 4; ++i)
-        if (sm.c64[i] < bb || (sm.c64[i] == bb && sm.cidx[i] > bi)) { bb = sm.c64[i]; bi = sm.cidx[i]; }
-      sm.e_split = (evict && bi >= 0) ? bi : -1;
-      sm.e_slot = (evict && bi >= 0) ? (int)cbase[bi * DEC_CAND + 2] : -1;
-    }
-    __syncthreads();
-  }
-  const int e_split = sm.e_split, e_slot = sm.e_slot;
-  // ---------------- memory write (rank one) and readout with the new state ----------------
+  // ---------------- memory write (rank one) ----------------
   if (e_slot >= 0) {
-    if (tid < IM_D) {
-      sm.ke[tid] = bf2f(a.K[((size_t)u * a.C + e_slot) * IM_D + tid]);
-      sm.ve[tid] = bf2f(a.V[((size_t)u * a.C + e_slot) * IM_D + tid]);
-    }
-    __syncthreads();
     {
       float pe = 0.f;
 #pragma unroll
@@ -621,70 +677,87 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   }
   __syncthreads();
   // ---------------- merge the attention partials, add back the candidates that stay ----------------
-  for (int idx = tid; idx < G * IM_D; idx += 256) {
-    const int j = idx >> 7, d = idx & 127;
-    float m = -1e30f;
-    for (int sp = 0; sp < n_act; ++sp) {
-      m = fmaxf(m, pbase[(sp * DEC_GMAX + j) * DEC_REC]);
-      if (sp != e_split) m = fmaxf(m, __uint_as_float(cbase[sp * DEC_CAND + 4 + j]));
+  constexpr int NP = (G * IM_D + 255) / 256;   // outputs per thread
+  float rm[NP], rl[NP], ro[NP];
+#pragma unroll
+  for (int k = 0; k < NP; ++k) { rm[k] = -1e30f; rl[k] = 0.f; ro[k] = 0.f; }
+  for (int c0 = 0; c0 < n_act; c0 += CH) {
+    const int cn = min(CH, n_act - c0);
+    if (c0 > 0) {
+      __syncthreads();
+      for (int sp = 0; sp < cn; ++sp)
+        dec_stage(&sm.pst[sp][0][0], pbase + (size_t)(c0 + sp) * DEC_GMAX * DEC_REC, G * DEC_REC);
+      dec_stage((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
+      __syncthreads();
     }
-    float o = 0.f, l = 0.f;
-    for (int sp = 0; sp < n_act; ++sp) {
-      const float* rec = pbase + (sp * DEC_GMAX + j) * DEC_REC;
-      const float sc = __expf(rec[0] - m);
-      o = fmaf(sc, rec[2 + d], o);
-      l = fmaf(sc, rec[1], l);
-      if (sp != e_split) {
-        const float pc = __expf(__uint_as_float(cbase[sp * DEC_CAND + 4 + j]) - m);
-        const int cs = (int)cbase[sp * DEC_CAND + 2];
-        o = fmaf(pc, bf2f(a.V[((size_t)u * a.C + cs) * IM_D + d]), o);
-        l += pc;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+      const int idx = tid + 256 * k;
+      if (idx < G * IM_D) {
+        const int j = idx >> 7, d = idx & 127;
+        float m = rm[k];
+        for (int sp = 0; sp < cn; ++sp) {
+          m = fmaxf(m, sm.pst[sp][j][0]);
+          if (c0 + sp != e_split) m = fmaxf(m, __uint_as_float(sm.cst[sp][4 + j]));
+        }
+        const float resc = __expf(rm[k] - m);
+        float o = ro[k] * resc, l = rl[k] * resc;
+        for (int sp = 0; sp < cn; ++sp) {
+          const float sc = __expf(sm.pst[sp][j][0] - m);
+          o = fmaf(sc, sm.pst[sp][j][2 + d], o);
+          l = fmaf(sc, sm.pst[sp][j][1], l);
+          if (c0 + sp != e_split) {
+            const float pc = __expf(__uint_as_float(sm.cst[sp][4 + j]) - m);
+            o = fmaf(pc, bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]), o);
+            l += pc;
+          }
+        }
+        rm[k] = m; rl[k] = l; ro[k] = o;
       }
     }
-    const float o_attn = (n_act > 0 && l > 0.f) ? o / l : 0.f;
-    float mr = sm.rold[j][d];
-    if (e_slot >= 0) mr = fmaf(a.lambda, mr, a.eta * sm.dot[j] * sm.ve[d]);
-    const float res = sm.gate[j] * (mr / sm.den[j]);
-    const size_t oi = ((size_t)b * a.H + h * G + j) * IM_D + d;
-    a.out[oi] = f2bf_rne(o_attn + res);
-    if (a.readout) a.readout[oi] = res;
   }
-  __syncthreads();
+#pragma unroll
+  for (int k = 0; k < NP; ++k) {
+    const int idx = tid + 256 * k;
+    if (idx < G * IM_D) {
+      const int j = idx >> 7, d = idx & 127;
+      const float o_attn = (n_act > 0 && rl[k] > 0.f) ? ro[k] / rl[k] : 0.f;
+      float mr = sm.rold[j][d];
+      if (e_slot >= 0) mr = fmaf(a.lambda, mr, a.eta * sm.dot[j] * sm.ve[d]);
+      const float res = sm.gate[j] * (mr / sm.den[j]);
+      const size_t oi = ((size_t)b * a.H + h * G + j) * IM_D + d;
+      a.out[oi] = f2bf_rne(o_attn + res);
+      if (a.readout) a.readout[oi] = res;
+    }
+  }
   // ---------------- fill the hole with the last entry, publish the new length ----------------
   const int n_keep = (e_slot >= 0) ? n - 1 : n;
   if (e_slot >= 0 && e_slot < n_keep) {
-    const size_t src = (size_t)u * a.C + n_keep, dst = (size_t)u * a.C + e_slot;
-    if (tid < 16) *(uint4*)(a.K + dst * IM_D + tid * 8) = *(const uint4*)(a.K + src * IM_D + tid * 8);
-    else if (tid < 32) *(uint4*)(a.V + dst * IM_D + (tid - 16) * 8) = *(const uint4*)(a.V + src * IM_D + (tid - 16) * 8);
-    else if (tid < 40) *(uint4*)(a.Kidx + dst * IM_DI + (tid - 32) * 8) = *(const uint4*)(a.Kidx + src * IM_DI + (tid - 32) * 8);
-    else if (tid == 40) a.pos[dst] = a.pos[src];
+    const size_t dst = (size_t)u * a.C + e_slot;
+    if (tid < 16) *(uint4*)(a.K + dst * IM_D + tid * 8) = mv;
+    else if (tid < 32) *(uint4*)(a.V + dst * IM_D + (tid - 16) * 8) = mv;
+    else if (tid < 40) *(uint4*)(a.Kidx + dst * IM_DI + (tid - 32) * 8) = mv;
+    else if (tid == 40) a.pos[dst] = mvpos;
   }
   if (tid == 0) {
     a.len[u] = n_keep;
     a.nproj[u] = n_keep;
     if (a.evicted) a.evicted[u] = e_slot;
-    a.cnt_unit[u] = 0;
   }
 }
 
-union DecSmem {
-  DecSplitSmem s;
-  DecTailSmem t;
-};
-
-// grid: units tail blocks + units * S split blocks (tail blocks first when r_first)
+// grid: units * S blocks; consecutive blocks take different units, the short last splits come last
 template <int G>
-__global__ __launch_bounds__(256, 2) void k_dec_main(const DecArgs a) {
-  __shared__ __attribute__((aligned(16))) DecSmem sm;
+__global__ __launch_bounds__(256, 2) void k_dec_main(const DecArgs a, const double* __restrict__ qy,
+                                                     const double* __restrict__ alpha) {
+  __shared__ __attribute__((aligned(16))) DecSplitSmem sm;
   const int U = a.B * a.H_kv;
-  int blk = blockIdx.x;
-  if (a.r_first) {
-    if (blk < U) { dec_tail<G>(a, blk, sm.t); return; }
-    blk -= U;
-  } else if (blk >= U * a.S) {
-    dec_tail<G>(a, blk - U * a.S, sm.t);
-    return;
-  }
-  // consecutive blocks take different units: the short last splits come last
-  dec_split<G>(a, blk % U, blk / U, sm.s);
+  dec_split<G>(a, blockIdx.x % U, blockIdx.x / U, sm, qy, alpha);
+}
+
+// grid: units
+template <int G>
+__global__ __launch_bounds__(256) void k_dec_tail(const DecArgs a) {
+  __shared__ __attribute__((aligned(16))) DecTailSmem<G> sm;
+  dec_tail<G>(a, blockIdx.x, sm);
 }

@@ -22,6 +22,9 @@ struct im_handle {
   // workspace layout (byte offsets)
   size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, total;
   int mem_split, attn_chunks, dec_splits;
+  // optional kernel timing (im_profile_start / im_profile_stop)
+  hipEvent_t* prof_ev;
+  int prof_max, prof_n;
   char err[256];
 };
 
@@ -70,8 +73,8 @@ void layout(const im_config* c, im_handle* h) {
   if (h->mem_split > 32) h->mem_split = 32;
   h->attn_chunks = (c->capacity + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK;
   size_t off = 0;
-  // status word, 16 head counters, then one counter and one newest-position word per unit
-  h->off_status = off; off = align256(off + (32 + 2 * units) * sizeof(int32_t));
+  // status word, 16 head counters, then one newest-position word per unit
+  h->off_status = off; off = align256(off + (32 + units) * sizeof(int32_t));
   h->dec_splits = (c->capacity + DEC_KEYS - 1) / DEC_KEYS;
   h->off_qy = off;     off = align256(off + B * c->max_queries * Hi * IM_DI * sizeof(double));
   h->off_alpha = off;  off = align256(off + B * c->max_queries * Hi * sizeof(double));
@@ -90,7 +93,7 @@ int launch_check(im_handle* h, const char* what) {
 
 int ensure_ws(im_handle* h, hipStream_t s) {
   if (h->ws_ready) return IM_OK;
-  const int n_words = 32 + 2 * h->cfg.batch * h->cfg.n_kv_heads;
+  const int n_words = 32 + h->cfg.batch * h->cfg.n_kv_heads;
   k_fill_i32<<<(n_words + 255) / 256, 256, 0, s>>>((int32_t*)(h->ws + h->off_status), n_words, 0);
   int rc = launch_check(h, "workspace clear");
   if (rc == IM_OK) h->ws_ready = true;
@@ -141,7 +144,53 @@ int32_t im_create(const im_config* cfg, void* workspace, size_t workspace_bytes,
   return IM_OK;
 }
 
-void im_destroy(im_handle* h) { free(h); }
+static void release_profile(im_handle* h) {
+  if (!h->prof_ev) return;
+  for (int i = 0; i < 2 * h->prof_max; ++i) (void)hipEventDestroy(h->prof_ev[i]);
+  free(h->prof_ev);
+  h->prof_ev = nullptr;
+  h->prof_max = h->prof_n = 0;
+}
+
+void im_destroy(im_handle* h) {
+  if (!h) return;
+  release_profile(h);
+  free(h);
+}
+
+int32_t im_profile_start(im_handle* h, int32_t max_records) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(max_records >= 1 && max_records <= (1 << 20), "max_records must be in 1..2^20");
+  release_profile(h);
+  h->prof_ev = (hipEvent_t*)calloc(2 * (size_t)max_records, sizeof(hipEvent_t));
+  if (!h->prof_ev) return set_err(h, IM_ERR_LAUNCH, "im_profile_start: out of host memory");
+  h->prof_max = max_records;
+  for (int i = 0; i < 2 * max_records; ++i) {
+    hipError_t e = hipEventCreate(&h->prof_ev[i]);
+    if (e != hipSuccess) {
+      h->prof_max = i / 2;
+      release_profile(h);
+      return set_err(h, IM_ERR_LAUNCH, "hipEventCreate: %s", hipGetErrorString(e));
+    }
+  }
+  h->prof_n = 0;
+  return IM_OK;
+}
+
+int32_t im_profile_stop(im_handle* h, float* ms_host, int32_t* n_records, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(ms_host && n_records, "ms_host / n_records is NULL");
+  IM_REQUIRE(h->prof_ev, "im_profile_start was not called");
+  hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return set_err(h, IM_ERR_LAUNCH, "stream synchronize: %s", hipGetErrorString(e));
+  for (int i = 0; i < h->prof_n; ++i) {
+    e = hipEventElapsedTime(&ms_host[i], h->prof_ev[2 * i], h->prof_ev[2 * i + 1]);
+    if (e != hipSuccess) return set_err(h, IM_ERR_LAUNCH, "hipEventElapsedTime: %s", hipGetErrorString(e));
+  }
+  *n_records = h->prof_n;
+  release_profile(h);
+  return IM_OK;
+}
 
 const char* im_last_error(const im_handle* h) { return h ? h->err : "handle is NULL"; }
 
@@ -347,24 +396,37 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
   a.v_new = (const bf16_t*)v_new; a.pos_new = pos_new; a.q_pos = q_pos;
   a.out = (bf16_t*)out; a.readout = readout_dbg; a.scores = scores_dbg; a.evicted = evicted_slot;
   a.qy = (double*)(h->ws + h->off_qy); a.alpha = (double*)(h->ws + h->off_alpha);
-  a.status = words; a.cnt_head = words + 16; a.cnt_unit = words + 32; a.maxpos = words + 32 + units;
+  a.status = words; a.maxpos = words + 32;
   a.part = (float*)(h->ws + h->off_dpart); a.cand = (uint32_t*)(h->ws + h->off_dcand);
   a.B = c.batch; a.H = c.n_q_heads; a.H_kv = c.n_kv_heads; a.C = c.capacity; a.H_idx = c.n_idx_heads;
   a.gate_in = c.gate_in_dim; a.n_sink = c.n_sink; a.n_recent = c.n_recent; a.budget = budget;
   a.S = (h->max_live + DEC_KEYS - 1) / DEC_KEYS; a.S_alloc = h->dec_splits; a.max_live = h->max_live;
-  a.r_first = units <= 128 ? 1 : 0;
   a.rms_eps = c.rms_eps; a.mem_eps = c.mem_eps; a.scale = c.softmax_scale; a.lambda = lambda; a.eta = eta;
   const int prep_blocks = c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2 + units;
   k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);
-  const int main_blocks = units * (a.S + 1);
-#define IM_DEC_CASE(g) case g: k_dec_main<g><<<main_blocks, 256, 0, s>>>(a); break;
+  const int main_blocks = units * a.S;
+  const bool prof = h->prof_ev && h->prof_n < h->prof_max;
+  if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n], s);
+#define IM_DEC_CASE(g)                                              \
+  case g:                                                           \
+    k_dec_main<g><<<main_blocks, 256, 0, s>>>(a, a.qy, a.alpha);    \
+    if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n + 1], s); \
+    k_dec_tail<g><<<units, 256, 0, s>>>(a);                         \
+    break;
   switch (G) {
     IM_DEC_CASE(1) IM_DEC_CASE(2) IM_DEC_CASE(3) IM_DEC_CASE(4)
     IM_DEC_CASE(5) IM_DEC_CASE(6) IM_DEC_CASE(7) IM_DEC_CASE(8)
     default: return set_err(h, IM_ERR_UNSUPPORTED, "group size %d", G);
   }
 #undef IM_DEC_CASE
+  if (prof) h->prof_n++;
   return launch_check(h, "im_decode_step");
 }
 
 }  // extern "C"
+
+#ifdef IM_DEC_TRACE
+extern "C" int im_trace_read(unsigned long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(im_trace_buf), 256 * sizeof(unsigned long long));
+}
+#endif
