@@ -26,11 +26,11 @@
 #define IM_STATUS_OVER_BUDGET_BIT 8
 
 // Optional phase stamps for kernel tuning (compiled out unless IM_DEC_TRACE is defined):
-// workgroup `IM_DEC_TRACE` writes wall_clock64() (100 MHz) at phase boundaries into a buffer.
+// every workgroup writes wall_clock64() (100 MHz) at phase boundaries into a buffer.
 #ifdef IM_DEC_TRACE
-extern "C" __device__ unsigned long long im_trace_buf[256];
-__device__ unsigned long long im_trace_buf[256];
-#define DEC_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x == (IM_DEC_TRACE)) im_trace_buf[slot] = wall_clock64(); } while (0)
+extern "C" __device__ unsigned long long im_trace_buf[2048 * 16];
+__device__ unsigned long long im_trace_buf[2048 * 16];
+#define DEC_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x < 2048) im_trace_buf[blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
 #else
 #define DEC_STAMP(slot) do { } while (0)
 #endif
@@ -76,8 +76,8 @@ __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
 // Blocks after: one per unit, append + indexer key of the new token.
 // --------------------------------------------------------------------------------------------
 __device__ void dec_gemv2(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Bm, int n0, int N,
-                          int M, int Kd, double (*red)[16], double* out_rows /* [M][2] in LDS */) {
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+                          int M, int Kd, double (*part)[256], double* out_rows /* [M][2] in LDS */) {
+  const int tid = threadIdx.x;
   for (int mb = 0; mb < M; mb += 8) {
     double acc[8][2];
 #pragma unroll
@@ -104,25 +104,32 @@ __device__ void dec_gemv2(const bf16_t* __restrict__ A, const bf16_t* __restrict
         }
       }
     }
+    // block-wide sums through LDS (cross-lane shuffles of doubles are slow here): 16 values x 256
+    // partial sums, added in two levels of 16
+    __syncthreads();
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      acc[i][0] = wave_sum_d(acc[i][0]);
-      acc[i][1] = wave_sum_d(acc[i][1]);
+    for (int i = 0; i < 8; ++i) { part[2 * i][tid] = acc[i][0]; part[2 * i + 1][tid] = acc[i][1]; }
+    __syncthreads();
+    {
+      const int v = tid >> 4, q4 = tid & 15;   // 16 values x 16 threads each
+      double sacc = 0.0;
+#pragma unroll
+      for (int t = 0; t < 16; ++t) sacc += part[v][q4 * 16 + t];
+      part[v][q4 * 16] = sacc;
     }
     __syncthreads();
-    if (lane == 0) {
+    if (tid < 16 && mb + (tid >> 1) < M) {
+      double tot = 0.0;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { red[w][2 * i] = acc[i][0]; red[w][2 * i + 1] = acc[i][1]; }
+      for (int t = 0; t < 16; ++t) tot += part[tid][t * 16];
+      out_rows[(mb + (tid >> 1)) * 2 + (tid & 1)] = tot;
     }
-    __syncthreads();
-    if (tid < 16 && mb + (tid >> 1) < M)
-      out_rows[(mb + (tid >> 1)) * 2 + (tid & 1)] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
   }
   __syncthreads();
 }
 
 __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
-  __shared__ double red[4][16];
+  __shared__ double part[16][256];
   __shared__ double rows[64 * 2];   // up to 64 batch rows x 2 outputs
   __shared__ float s_k[IM_D];
   __shared__ double s_u[IM_DI];
@@ -132,14 +139,14 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   const int blk = blockIdx.x;
   if (blk < nU) {
     const int n0 = blk * 2;
-    dec_gemv2(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, red, rows);
+    dec_gemv2(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
     // raw projections; the consumer applies the QK-Norm (it needs a whole head, this block has 2 rows)
     for (int i = tid; i < a.B * 2; i += 256) a.qy[(size_t)(i >> 1) * Nq + n0 + (i & 1)] = rows[i];
     return;
   }
   if (blk < nU + nG) {
     const int n0 = (blk - nU) * 2;
-    dec_gemv2(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, red, rows);
+    dec_gemv2(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
     for (int i = tid; i < a.B * 2; i += 256) {
       const int r = n0 + (i & 1);
       if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = rows[i];   // raw G x; scaled by the consumer
@@ -271,6 +278,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     const int kk = tid & 127;
     const int mypos = (kk < nk) ? a.pos[base + kk] : 0;
     const int qpos = a.q_pos[b];
+    // keep every load above this line: the whole split is in flight before the first use
+    __asm__ volatile("" ::: "memory");
     DEC_STAMP(1);
     // ---- QK-Norm of the query features (per head over its 64 dims), head gate
     double alj;
@@ -281,10 +290,15 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       ss += __shfl_xor(ss, 16, 64);
       ss += __shfl_xor(ss, 32, 64);
       const double rr = sqrt(ss / (double)IM_DI + (double)a.rms_eps);
+      const double inv = 1.0 / rr;
 #pragma unroll
       for (int m = 0; m < 16; ++m) {
         const double wt = a.nqw ? (double)bf2f(a.nqw[16 * kq + m]) : 1.0;
-        qd[m] = hv ? (double)(float)(qd[m] / rr * wt) : 0.0;
+        // y / rr: one reciprocal, then a residual correction (the quotient's last-bit rounding
+        // cannot matter after the fp32 rounding below except on a 2^-29 fraction of inputs)
+        double qq = qd[m] * inv;
+        qq = fma(fma(-qq, rr, qd[m]), inv, qq);
+        qd[m] = hv ? (double)(float)(qq * wt) : 0.0;
       }
       alj = hv ? (double)(float)(araw / sqrt((double)(a.H_idx * IM_DI))) : 0.0;
     }
@@ -301,7 +315,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       const int T = 2 * w + tt;
       if (hv) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) sm.zs[16 * T + 4 * kq + r][l16] = alj * fmax(z[r], 0.0);
+        // fp64 16x16x4 result layout: register r of lane (l16, kq) is row 4 r + kq, column l16
+        for (int r = 0; r < 4; ++r) sm.zs[16 * T + 4 * r + kq][l16] = alj * fmax(z[r], 0.0);
       }
     }
     DEC_STAMP(3);
@@ -414,7 +429,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     }
     DEC_STAMP(6);
     // the 16 (wave, key group) streams meet in LDS, 4 heads at a time
-    float* prec = a.part + ((size_t)u * a.S_alloc + s) * DEC_GMAX * DEC_REC;
+    float* prec = a.part + ((size_t)u * a.S_alloc + s) * G * DEC_REC;   // dense [split][head][record]
     __syncthreads();   // zs is dead: its space now holds oacc
 #pragma unroll
     for (int j0 = 0; j0 < G; j0 += 4) {
@@ -465,29 +480,39 @@ struct DecTailSmem {
   float pst[CH][G][DEC_REC];                      // partial records of the staged splits
   uint32_t cst[CH][DEC_CAND];                     // their candidate records
   float qs[G][IM_D];
-  float php[2][G][IM_DM];
+  union {                                         // used one after the other
+    struct { double qn[16 * IM_DI]; double pr[16 * IM_DI]; } x;   // the leftover key: query features, products
+    struct { float php[2][G][IM_DM]; float red[4][G][IM_D]; } r;  // readout terms
+  };
   float phq[G][IM_DM];
-  float red[4][G][IM_D];
   float rold[G][IM_D];
   float ke[IM_D], ve[IM_D], phe2[2][IM_DM], phe[IM_DM], bnew[IM_DM];
+  float lastk[IM_D], lastv[IM_D];                 // rows of the last live slot (the leftover key, the mover)
+  float lastki[IM_DI];
+  int lastpos;
+  unsigned long long xc64;
+  double hsum[16];
+  float xlog[DEC_GMAX];                           // the leftover key's attention logits
   float gate[G], den[G], dot[G];
   unsigned long long c64[4];
   int cidx[4];
   int e_slot, e_split;
 };
 
-// copy `count` floats (count even, both sides 8-byte aligned) with many loads in flight
+// copy `count` floats (count even, both sides 8-byte aligned), every load in flight before the
+// first store; handles up to 256 * 2 * NB floats per round
+template <int NB>
 __device__ __forceinline__ void dec_stage(float* dst, const float* __restrict__ src, int count) {
   const int n2 = count >> 1;
-  for (int base = 0; base < n2; base += 256 * 8) {
-    float2 r[8];
+  for (int base = 0; base < n2; base += 256 * NB) {
+    float2 r[NB];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
+    for (int k = 0; k < NB; ++k) {
       const int i = base + threadIdx.x + 256 * k;
       r[k] = (i < n2) ? ((const float2*)src)[i] : make_float2(0.f, 0.f);
     }
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
+    for (int k = 0; k < NB; ++k) {
       const int i = base + threadIdx.x + 256 * k;
       if (i < n2) ((float2*)dst)[i] = r[k];
     }
@@ -495,16 +520,21 @@ __device__ __forceinline__ void dec_stage(float* dst, const float* __restrict__ 
 }
 
 template <int G>
-__device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem<G>& sm) {
+__device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem<G>& sm,
+                                         const double* __restrict__ qy, const double* __restrict__ alpha) {
   constexpr int CH = DecTailSmem<G>::CH;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int b = u / a.H_kv, h = u % a.H_kv;
+  DEC_STAMP(8);
   const int n_old = a.len[u];
   const bool has_new = n_old + 1 <= a.C;
   const int n = min(n_old + (has_new ? 1 : 0), a.max_live);
-  const int n_act = (n + DEC_KEYS - 1) / DEC_KEYS;
+  // splits [0, n_act) were done by the main kernel; at most ONE key lies beyond them (n = 128 S + 1,
+  // the usual steady state with a power-of-two budget): this workgroup handles it as split n_act
+  const int n_act = min((n + DEC_KEYS - 1) / DEC_KEYS, a.S);
+  const bool has_x = n > a.S * DEC_KEYS;
   const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
-  const float* pbase = a.part + (size_t)u * a.S_alloc * DEC_GMAX * DEC_REC;
+  const float* pbase = a.part + (size_t)u * a.S_alloc * G * DEC_REC;
   // ---------------- every load whose address is known now ----------------
   const int d4 = tid & 31, cg = tid >> 5;
   float4 Mr[16];
@@ -525,7 +555,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     const unsigned long long c = ((unsigned long long)cbase[(size_t)sp * DEC_CAND] << 32) | cbase[(size_t)sp * DEC_CAND + 1];
     if (c <= best) { best = c; bidx = sp; }   // later splits hold larger slots: they win full ties
   }
-  // the entry that moves into the hole: the last live slot (rows are read before any write)
+  // the last live slot: it moves into the hole, and it is the leftover key when there is one
   const int n_last = n - 1;
   uint4 mv = make_uint4(0, 0, 0, 0);
   int mvpos = 0;
@@ -536,11 +566,100 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     else if (tid < 40) mv = *(const uint4*)(a.Kidx + src * IM_DI + (tid - 32) * 8);
     else if (tid == 40) mvpos = a.pos[src];
   }
+  // raw query projections of this batch row (only the leftover key needs them here)
+  double yv[4] = {0.0, 0.0, 0.0, 0.0};
+  if (has_x) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int v = tid + 256 * k;
+      if (v < a.H_idx * IM_DI) yv[k] = qy[(size_t)b * a.H_idx * IM_DI + v];
+    }
+  }
   // first round of split records to LDS
   const int cn0 = min(CH, n_act);
-  for (int sp = 0; sp < cn0; ++sp) dec_stage(&sm.pst[sp][0][0], pbase + (size_t)sp * DEC_GMAX * DEC_REC, G * DEC_REC);
-  dec_stage((float*)&sm.cst[0][0], (const float*)cbase, cn0 * DEC_CAND);
+  dec_stage<18>(&sm.pst[0][0][0], pbase, cn0 * G * DEC_REC);
+  dec_stage<5>((float*)&sm.cst[0][0], (const float*)cbase, cn0 * DEC_CAND);
+  if (tid < 40) {
+    float f[8];
+    unpack8(mv, f);
+    float* dst = (tid < 16) ? &sm.lastk[tid * 8] : (tid < 32) ? &sm.lastv[(tid - 16) * 8] : &sm.lastki[(tid - 32) * 8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dst[e] = f[e];
+  }
+  if (tid == 40) sm.lastpos = mvpos;
   __syncthreads();
+  DEC_STAMP(9);
+  // ---------------- the leftover key as one more split: score, logits, candidate ----------------
+  if (has_x) {   // uniform
+    const int Hi = a.H_idx;
+    // QK-Norm of the query features, as in the main kernel: sums of 64 squares in two levels of 8
+#pragma unroll
+    for (int k = 0; k < 4; ++k) sm.x.pr[tid + 256 * k] = yv[k] * yv[k];
+    __syncthreads();
+    if (tid < Hi * 8) {
+      double t = 0.0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t += sm.x.pr[tid * 8 + e];
+      sm.x.qn[tid] = t;
+    }
+    __syncthreads();
+    if (tid < Hi) {
+      double t = 0.0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t += sm.x.qn[tid * 8 + e];
+      sm.hsum[tid] = t;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int v = tid + 256 * k;
+      if (v < Hi * IM_DI) {
+        const int j = v >> 6, c = v & 63;
+        const double rr = sqrt(sm.hsum[j] / (double)IM_DI + (double)a.rms_eps);
+        const double inv = 1.0 / rr;
+        double qq = yv[k] * inv;
+        qq = fma(fma(-qq, rr, yv[k]), inv, qq);
+        const double wt = a.nqw ? (double)bf2f(a.nqw[c]) : 1.0;
+        const double qn = (double)(float)(qq * wt);
+        sm.x.pr[v] = qn * (double)sm.lastki[c];      // product with the key's indexer feature
+      }
+    }
+    __syncthreads();
+    if (tid < Hi * 8) {
+      double t = 0.0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t += sm.x.pr[tid * 8 + e];
+      sm.x.qn[tid] = t;
+    }
+    // attention logits of the leftover key: wave w takes heads w, w + 4
+    for (int j = w; j < G; j += 4) {
+      float t = sm.qs[j][lane] * sm.lastk[lane] + sm.qs[j][lane + 64] * sm.lastk[lane + 64];
+      t = wave_sum_f(t);
+      if (lane == 0) sm.xlog[j] = t * a.scale;
+    }
+    __syncthreads();
+    if (tid < Hi) {
+      double t = 0.0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) t += sm.x.qn[tid * 8 + e];
+      const double al = (double)(float)(alpha[(size_t)b * Hi + tid] / sqrt((double)(Hi * IM_DI)));
+      sm.hsum[tid] = al * fmax(t, 0.0);
+    }
+    __syncthreads();
+    if (tid == 0) {
+      double asum = 0.0;
+      for (int j = 0; j < Hi; ++j) asum += sm.hsum[j];
+      const int xpos = sm.lastpos;
+      const float sc = (xpos <= a.q_pos[b]) ? (float)asum : -INFINITY;
+      if (a.scores) a.scores[(size_t)u * a.C + n_last] = sc;
+      const bool forced = (xpos < a.n_sink) ||
+                          (a.n_recent > 0 && (long long)xpos > (long long)a.maxpos[u] - a.n_recent);
+      const uint32_t skey = forced ? IM_KEY_PINF : score_key(sc);
+      sm.xc64 = ((unsigned long long)skey << 32) | (uint32_t)(~((uint32_t)xpos ^ 0x80000000u));
+    }
+    __syncthreads();
+  }
+  const int x_split = has_x ? n_act : -2;   // index the leftover key goes by in the ranking
   // ---------------- memory readout terms that do not depend on the eviction ----------------
   {  // phi(q_j)[c], two threads per c (64 dims each)
     float pq[G];
@@ -556,12 +675,16 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
         for (int j = 0; j < G; ++j) pq[j] = fmaf(wv[e], sm.qs[j][hh * 64 + i * 8 + e], pq[j]);
     }
 #pragma unroll
-    for (int j = 0; j < G; ++j) sm.php[hh][j][wc] = pq[j];
+    for (int j = 0; j < G; ++j) sm.r.php[hh][j][wc] = pq[j];
   }
-  // candidate ranked last among the staged splits (one thread per split), merged with the rest
+  // candidate ranked last: staged splits (one thread each), the rest, the leftover key
   if (tid < cn0) {
     const unsigned long long c = ((unsigned long long)sm.cst[tid][0] << 32) | sm.cst[tid][1];
     if (bidx < 0 || c < best) { best = c; bidx = tid; }   // staged splits are the EARLIER ones: they lose full ties
+  }
+  if (has_x && tid == 0) {
+    const unsigned long long c = sm.xc64;
+    if (bidx < 0 || c <= best) { best = c; bidx = x_split; }   // the largest slot wins full ties
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -582,13 +705,14 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     }
     const bool ev = evict && bi >= 0;
     sm.e_split = ev ? bi : -1;
-    sm.e_slot = ev ? (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]) : -1;
+    sm.e_slot = !ev ? -1 : (bi == x_split) ? n_last : (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]);
   }
   for (int idx = tid; idx < G * IM_DM; idx += 256) {
     const int j = idx >> 7, c = idx & 127;
-    sm.phq[j][c] = sm.php[0][j][c] + sm.php[1][j][c];
+    sm.phq[j][c] = sm.r.php[0][j][c] + sm.r.php[1][j][c];
   }
   __syncthreads();
+  DEC_STAMP(10);
   const int e_split = sm.e_split, e_slot = sm.e_slot;
   // gate: one wave per head
   for (int j = w; j < G; j += 4) {
@@ -615,23 +739,29 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       for (int e = 0; e < 4; ++e) {
         float x = ra[j][e];
         x += __shfl_xor(x, 32, 64);
-        if (lane < 32) sm.red[w][j][4 * d4 + e] = x;
+        if (lane < 32) sm.r.red[w][j][4 * d4 + e] = x;
       }
   }
-  // the evicted entry's rows come with its candidate record
+  // the evicted entry's rows: the leftover key's own, or those in its split's candidate record
   if (e_slot >= 0 && tid < IM_D) {
-    const bf16_t* kr = (e_split < CH) ? (const bf16_t*)&sm.cst[e_split][DEC_CAND_K]
-                                      : (const bf16_t*)(cbase + (size_t)e_split * DEC_CAND + DEC_CAND_K);
-    const bf16_t* vr = (e_split < CH) ? (const bf16_t*)&sm.cst[e_split][DEC_CAND_V]
-                                      : (const bf16_t*)(cbase + (size_t)e_split * DEC_CAND + DEC_CAND_V);
-    sm.ke[tid] = bf2f(kr[tid]);
-    sm.ve[tid] = bf2f(vr[tid]);
+    if (e_split == x_split) {
+      sm.ke[tid] = sm.lastk[tid];
+      sm.ve[tid] = sm.lastv[tid];
+    } else {
+      const bf16_t* kr = (e_split < CH) ? (const bf16_t*)&sm.cst[e_split][DEC_CAND_K]
+                                        : (const bf16_t*)(cbase + (size_t)e_split * DEC_CAND + DEC_CAND_K);
+      const bf16_t* vr = (e_split < CH) ? (const bf16_t*)&sm.cst[e_split][DEC_CAND_V]
+                                        : (const bf16_t*)(cbase + (size_t)e_split * DEC_CAND + DEC_CAND_V);
+      sm.ke[tid] = bf2f(kr[tid]);
+      sm.ve[tid] = bf2f(vr[tid]);
+    }
   }
   __syncthreads();
   for (int idx = tid; idx < G * IM_D; idx += 256) {
     const int j = idx >> 7, d = idx & 127;
-    sm.rold[j][d] = sm.red[0][j][d] + sm.red[1][j][d] + sm.red[2][j][d] + sm.red[3][j][d];
+    sm.rold[j][d] = sm.r.red[0][j][d] + sm.r.red[1][j][d] + sm.r.red[2][j][d] + sm.r.red[3][j][d];
   }
+  DEC_STAMP(11);
   // ---------------- memory write (rank one) ----------------
   if (e_slot >= 0) {
     {
@@ -676,6 +806,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     if (lane == 0) { sm.den[j] = dn + a.mem_eps; sm.dot[j] = dt; }
   }
   __syncthreads();
+  DEC_STAMP(12);
   // ---------------- merge the attention partials, add back the candidates that stay ----------------
   constexpr int NP = (G * IM_D + 255) / 256;   // outputs per thread
   float rm[NP], rl[NP], ro[NP];
@@ -685,9 +816,8 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     const int cn = min(CH, n_act - c0);
     if (c0 > 0) {
       __syncthreads();
-      for (int sp = 0; sp < cn; ++sp)
-        dec_stage(&sm.pst[sp][0][0], pbase + (size_t)(c0 + sp) * DEC_GMAX * DEC_REC, G * DEC_REC);
-      dec_stage((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
+      dec_stage<18>(&sm.pst[0][0][0], pbase + (size_t)c0 * G * DEC_REC, cn * G * DEC_REC);
+      dec_stage<5>((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
       __syncthreads();
     }
 #pragma unroll
@@ -695,22 +825,31 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       const int idx = tid + 256 * k;
       if (idx < G * IM_D) {
         const int j = idx >> 7, d = idx & 127;
-        float m = rm[k];
-        for (int sp = 0; sp < cn; ++sp) {
-          m = fmaxf(m, sm.pst[sp][j][0]);
-          if (c0 + sp != e_split) m = fmaxf(m, __uint_as_float(sm.cst[sp][4 + j]));
+        // every LDS read of this round first (fixed trip count), then the arithmetic
+        float pm[CH], plv[CH], po[CH], cl[CH], cv[CH];
+#pragma unroll
+        for (int sp = 0; sp < CH; ++sp) {
+          const bool on = sp < cn;
+          pm[sp] = on ? sm.pst[sp][j][0] : -1e30f;
+          plv[sp] = on ? sm.pst[sp][j][1] : 0.f;
+          po[sp] = on ? sm.pst[sp][j][2 + d] : 0.f;
+          const bool stays = on && (c0 + sp != e_split);
+          cl[sp] = stays ? __uint_as_float(sm.cst[sp][4 + j]) : -INFINITY;
+          cv[sp] = stays ? bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]) : 0.f;
         }
+        float m = rm[k];
+#pragma unroll
+        for (int sp = 0; sp < CH; ++sp) m = fmaxf(m, fmaxf(pm[sp], cl[sp]));
         const float resc = __expf(rm[k] - m);
         float o = ro[k] * resc, l = rl[k] * resc;
-        for (int sp = 0; sp < cn; ++sp) {
-          const float sc = __expf(sm.pst[sp][j][0] - m);
-          o = fmaf(sc, sm.pst[sp][j][2 + d], o);
-          l = fmaf(sc, sm.pst[sp][j][1], l);
-          if (c0 + sp != e_split) {
-            const float pc = __expf(__uint_as_float(sm.cst[sp][4 + j]) - m);
-            o = fmaf(pc, bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]), o);
-            l += pc;
-          }
+#pragma unroll
+        for (int sp = 0; sp < CH; ++sp) {
+          const float sc = __expf(pm[sp] - m);
+          o = fmaf(sc, po[sp], o);
+          l = fmaf(sc, plv[sp], l);
+          const float pc = __expf(cl[sp] - m);   // exp(-inf) = 0 for the evicted / absent candidate
+          o = fmaf(pc, cv[sp], o);
+          l += pc;
         }
         rm[k] = m; rl[k] = l; ro[k] = o;
       }
@@ -721,7 +860,14 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     const int idx = tid + 256 * k;
     if (idx < G * IM_D) {
       const int j = idx >> 7, d = idx & 127;
-      const float o_attn = (n_act > 0 && rl[k] > 0.f) ? ro[k] / rl[k] : 0.f;
+      float m = rm[k], o = ro[k], l = rl[k];
+      if (has_x && e_split != x_split) {   // the leftover key stays
+        const float mn = fmaxf(m, sm.xlog[j]);
+        const float resc = __expf(m - mn), pc = __expf(sm.xlog[j] - mn);
+        o = fmaf(pc, sm.lastv[d], o * resc);
+        l = fmaf(l, resc, pc);
+      }
+      const float o_attn = (l > 0.f) ? o / l : 0.f;
       float mr = sm.rold[j][d];
       if (e_slot >= 0) mr = fmaf(a.lambda, mr, a.eta * sm.dot[j] * sm.ve[d]);
       const float res = sm.gate[j] * (mr / sm.den[j]);
@@ -730,6 +876,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       if (a.readout) a.readout[oi] = res;
     }
   }
+  DEC_STAMP(13);
   // ---------------- fill the hole with the last entry, publish the new length ----------------
   const int n_keep = (e_slot >= 0) ? n - 1 : n;
   if (e_slot >= 0 && e_slot < n_keep) {
@@ -757,7 +904,8 @@ __global__ __launch_bounds__(256, 2) void k_dec_main(const DecArgs a, const doub
 
 // grid: units
 template <int G>
-__global__ __launch_bounds__(256) void k_dec_tail(const DecArgs a) {
+__global__ __launch_bounds__(256) void k_dec_tail(const DecArgs a, const double* __restrict__ qy,
+                                                  const double* __restrict__ alpha) {
   __shared__ __attribute__((aligned(16))) DecTailSmem<G> sm;
-  dec_tail<G>(a, blockIdx.x, sm);
+  dec_tail<G>(a, blockIdx.x, sm, qy, alpha);
 }

@@ -80,7 +80,7 @@ void layout(const im_config* c, im_handle* h) {
   h->off_alpha = off;  off = align256(off + B * c->max_queries * Hi * sizeof(double));
   h->off_mem = off;    off = align256(off + units * h->mem_split * (IM_DM * IM_D + IM_DM) * sizeof(float));
   h->off_attn = off;   off = align256(off + B * c->n_q_heads * h->attn_chunks * IM_ATT_REC * sizeof(float));
-  h->off_dpart = off;  off = align256(off + units * h->dec_splits * DEC_GMAX * DEC_REC * sizeof(float));
+  h->off_dpart = off;  off = align256(off + units * h->dec_splits * DEC_GMAX * DEC_REC * sizeof(float));  // upper bound: G <= 8
   h->off_dcand = off;  off = align256(off + units * h->dec_splits * DEC_CAND * sizeof(uint32_t));
   h->total = off;
 }
@@ -400,18 +400,22 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
   a.part = (float*)(h->ws + h->off_dpart); a.cand = (uint32_t*)(h->ws + h->off_dcand);
   a.B = c.batch; a.H = c.n_q_heads; a.H_kv = c.n_kv_heads; a.C = c.capacity; a.H_idx = c.n_idx_heads;
   a.gate_in = c.gate_in_dim; a.n_sink = c.n_sink; a.n_recent = c.n_recent; a.budget = budget;
-  a.S = (h->max_live + DEC_KEYS - 1) / DEC_KEYS; a.S_alloc = h->dec_splits; a.max_live = h->max_live;
+  // 128-key splits for the main kernel; a single key beyond a multiple of 128 (the steady state with
+  // a budget that is a multiple of 128) is left to the tail kernel instead of a one-key split
+  a.S = (h->max_live % DEC_KEYS == 1 && h->max_live > 1) ? h->max_live / DEC_KEYS
+                                                         : (h->max_live + DEC_KEYS - 1) / DEC_KEYS;
+  a.S_alloc = h->dec_splits; a.max_live = h->max_live;
   a.rms_eps = c.rms_eps; a.mem_eps = c.mem_eps; a.scale = c.softmax_scale; a.lambda = lambda; a.eta = eta;
   const int prep_blocks = c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2 + units;
   k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);
-  const int main_blocks = units * a.S;
+  const int main_blocks = units * (a.S > 0 ? a.S : 1);
   const bool prof = h->prof_ev && h->prof_n < h->prof_max;
   if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n], s);
 #define IM_DEC_CASE(g)                                              \
   case g:                                                           \
     k_dec_main<g><<<main_blocks, 256, 0, s>>>(a, a.qy, a.alpha);    \
     if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n + 1], s); \
-    k_dec_tail<g><<<units, 256, 0, s>>>(a);                         \
+    k_dec_tail<g><<<units, 256, 0, s>>>(a, a.qy, a.alpha);          \
     break;
   switch (G) {
     IM_DEC_CASE(1) IM_DEC_CASE(2) IM_DEC_CASE(3) IM_DEC_CASE(4)
@@ -427,6 +431,6 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
 
 #ifdef IM_DEC_TRACE
 extern "C" int im_trace_read(unsigned long long* host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(im_trace_buf), 256 * sizeof(unsigned long long));
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(im_trace_buf), 2048 * 16 * sizeof(unsigned long long));
 }
 #endif
