@@ -223,10 +223,11 @@ struct DecSplitSmem {
     float oacc[16][4][IM_D];         // later: output partials of the 16 (wave, key group) streams,
   };                                 //        4 heads at a time
   float pl[DEC_KEYS][8];             // probabilities [key][head]
+  unsigned long long cmin[DEC_KEYS]; // ranking keys of the split's entries
   float wm[4][8], wl[4][8];
   float clog[8];
-  unsigned long long c64[2];
-  int cslot[2];
+  unsigned long long c64[8];
+  int cslot[8];
 };
 
 template <int G>
@@ -249,27 +250,35 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     const bool hv = l16 < a.H_idx;
     double qd[16];
     {
-      const double* yrow = qy + ((size_t)b * a.H_idx + (hv ? l16 : 0)) * IM_DI + 16 * kq;
+      const uint4* yrow = (const uint4*)(qy + ((size_t)b * a.H_idx + (hv ? l16 : 0)) * IM_DI + 16 * kq);
 #pragma unroll
-      for (int m = 0; m < 16; ++m) qd[m] = yrow[m];
+      for (int m = 0; m < 8; ++m) {
+        const uint4 t = yrow[m];
+        qd[2 * m] = __longlong_as_double(((long long)t.y << 32) | t.x);
+        qd[2 * m + 1] = __longlong_as_double(((long long)t.w << 32) | t.z);
+      }
     }
     const double araw = alpha[(size_t)b * a.H_idx + (hv ? l16 : 0)];
+    uint4 nw[2] = {make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u),
+                   make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u)};   // bf16 ones
+    if (a.nqw) {
+      nw[0] = *(const uint4*)(a.nqw + 16 * kq);
+      nw[1] = *(const uint4*)(a.nqw + 16 * kq + 8);
+    }
     uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int T = 2 * w + tt;
-      const int kr = 16 * T + l16;
+      const int kr = 16 * (2 * w + tt) + l16;
 #pragma unroll
       for (int i = 0; i < 2; ++i)
         kif[tt][i] = (kr < nk) ? *(const uint4*)(a.Kidx + (base + kr) * IM_DI + 16 * kq + 8 * i) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int kr = 16 * (2 * w + tt) + l16;
 #pragma unroll
       for (int c = 0; c < 4; ++c)
         kf[tt][c] = (kr < nk) ? *(const uint4*)(a.K + (base + kr) * IM_D + 32 * c + 8 * kq) : make_uint4(0, 0, 0, 0);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int vr = 16 * T + 4 * i + kq;
-        vf[tt][i] = (vr < nk) ? *(const uint4*)(a.V + (base + vr) * IM_D + 8 * l16) : make_uint4(0, 0, 0, 0);
-      }
     }
 #pragma unroll
     for (int c = 0; c < 4; ++c)
@@ -278,7 +287,16 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     const int kk = tid & 127;
     const int mypos = (kk < nk) ? a.pos[base + kk] : 0;
     const int qpos = a.q_pos[b];
-    // keep every load above this line: the whole split is in flight before the first use
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int vr = 16 * (2 * w + tt) + 4 * i + kq;
+        vf[tt][i] = (vr < nk) ? *(const uint4*)(a.V + (base + vr) * IM_D + 8 * l16) : make_uint4(0, 0, 0, 0);
+      }
+    }
+    // keep every load above this line, in this order: loads return in order, so each phase below
+    // waits only for what it uses while the rest of the split is still streaming in
     __asm__ volatile("" ::: "memory");
     DEC_STAMP(1);
     // ---- QK-Norm of the query features (per head over its 64 dims), head gate
@@ -287,18 +305,19 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       double ss = 0.0;
 #pragma unroll
       for (int m = 0; m < 16; ++m) ss = fma(qd[m], qd[m], ss);
-      ss += __shfl_xor(ss, 16, 64);
-      ss += __shfl_xor(ss, 32, 64);
+      ss = rows_sum_d(ss);
       const double rr = sqrt(ss / (double)IM_DI + (double)a.rms_eps);
       const double inv = 1.0 / rr;
+      float wf[16];
+      unpack8(nw[0], wf);
+      unpack8(nw[1], wf + 8);
 #pragma unroll
       for (int m = 0; m < 16; ++m) {
-        const double wt = a.nqw ? (double)bf2f(a.nqw[16 * kq + m]) : 1.0;
         // y / rr: one reciprocal, then a residual correction (the quotient's last-bit rounding
         // cannot matter after the fp32 rounding below except on a 2^-29 fraction of inputs)
         double qq = qd[m] * inv;
         qq = fma(fma(-qq, rr, qd[m]), inv, qq);
-        qd[m] = hv ? (double)(float)(qq * wt) : 0.0;
+        qd[m] = hv ? (double)(float)(qq * (double)wf[m]) : 0.0;
       }
       alj = hv ? (double)(float)(araw / sqrt((double)(a.H_idx * IM_DI))) : 0.0;
     }
@@ -334,26 +353,30 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         const uint32_t skey = forced ? IM_KEY_PINF : score_key(sc);
         c64 = ((unsigned long long)skey << 32) | (uint32_t)(~((uint32_t)mypos ^ 0x80000000u));
       }
-      unsigned long long mn = c64;
-#pragma unroll
-      for (int o = 32; o > 0; o >>= 1) {
-        const unsigned long long other = __shfl_xor(mn, o, 64);
-        mn = other < mn ? other : mn;
-      }
-      // equal (score, position): the largest slot is ranked last
-      const unsigned long long bal = __ballot(c64 == mn && kk < nk);
-      if (lane == 0) {
-        sm.c64[w] = mn;
-        sm.cslot[w] = bal ? (w * 64 + 63 - __builtin_clzll(bal)) : -1;
-      }
+      sm.cmin[kk] = c64;
     }
     __syncthreads();
-    int cl;  // candidate's key index inside the split
-    unsigned long long cbest;
-    {
-      const unsigned long long c0 = sm.c64[0], c1 = sm.c64[1];
-      const int s0 = sm.cslot[0], s1 = sm.cslot[1];
-      if (s1 >= 0 && (s0 < 0 || c1 <= c0)) { cl = s1; cbest = c1; } else { cl = s0; cbest = c0; }
+    // the entry ranked last: smallest key; on equal (score, position) the largest slot.  Two levels
+    // of 16 / 8 through LDS (scanning upwards with <= keeps the largest slot).
+    if (tid < 8) {
+      unsigned long long mn = ~0ull;
+      int at = -1;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const unsigned long long c = sm.cmin[tid * 16 + e];
+        if (tid * 16 + e < nk && c <= mn) { mn = c; at = tid * 16 + e; }
+      }
+      sm.c64[tid] = mn;
+      sm.cslot[tid] = at;
+    }
+    __syncthreads();
+    int cl = -1;  // candidate's key index inside the split
+    unsigned long long cbest = ~0ull;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const unsigned long long c = sm.c64[e];
+      const int at = sm.cslot[e];
+      if (at >= 0 && c <= cbest) { cbest = c; cl = at; }
     }
     DEC_STAMP(4);
     // ---- logits of the 2 tiles of this wave:  S[key][head] = K_tile . Q^T  (bf16 MFMA, fp32 acc)
@@ -383,8 +406,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         lmax = fmaxf(lmax, sv);
       }
     }
-    lmax = fmaxf(lmax, __shfl_xor(lmax, 16, 64));
-    lmax = fmaxf(lmax, __shfl_xor(lmax, 32, 64));
+    lmax = rows_max_f(lmax);
     if (kq == 0 && l16 < 8) sm.wm[w][l16] = lmax;
     __syncthreads();
     float mj = fmaxf(fmaxf(sm.wm[0][l16 & 7], sm.wm[1][l16 & 7]), fmaxf(sm.wm[2][l16 & 7], sm.wm[3][l16 & 7]));
@@ -400,8 +422,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         if (l16 < 8) sm.pl[16 * T + 4 * kq + r][l16] = p;
       }
     }
-    lsum += __shfl_xor(lsum, 16, 64);
-    lsum += __shfl_xor(lsum, 32, 64);
+    lsum = rows_sum_f(lsum);
     if (kq == 0 && l16 < 8) sm.wl[w][l16] = lsum;
     __syncthreads();
     DEC_STAMP(5);
@@ -548,6 +569,21 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const float b_old = (tid < IM_DM) ? a.bvec[(size_t)u * IM_DM + tid] : 0.f;
   for (int idx = tid; idx < G * IM_D; idx += 256)
     sm.qs[idx >> 7][idx & 127] = bf2f(a.q[((size_t)b * a.H + h * G) * IM_D + idx]);
+  // raw query projections of this batch row (only a leftover key needs them here)
+  const bool may_x = a.max_live > a.S * DEC_KEYS;   // host-known: a leftover key can exist
+  double yv[4] = {0.0, 0.0, 0.0, 0.0};
+  if (may_x) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int v = tid + 256 * k;
+      if (v < a.H_idx * IM_DI) yv[k] = qy[(size_t)b * a.H_idx * IM_DI + v];
+    }
+  }
+  // first round of split records to LDS (all launched splits: which ones are live is checked later)
+  const int cs0 = min(CH, a.S);
+  dec_stage<18>(&sm.pst[0][0][0], pbase, cs0 * G * DEC_REC);
+  dec_stage<5>((float*)&sm.cst[0][0], (const float*)cbase, cs0 * DEC_CAND);
+  const int cn0 = min(CH, n_act);
   // candidate keys of the splits beyond the first staged round (none in the usual case)
   unsigned long long best = ~0ull;
   int bidx = -1;
@@ -566,20 +602,32 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     else if (tid < 40) mv = *(const uint4*)(a.Kidx + src * IM_DI + (tid - 32) * 8);
     else if (tid == 40) mvpos = a.pos[src];
   }
-  // raw query projections of this batch row (only the leftover key needs them here)
-  double yv[4] = {0.0, 0.0, 0.0, 0.0};
-  if (has_x) {
+  __syncthreads();
+  DEC_STAMP(9);
+  // ---------------- memory readout terms that do not depend on the eviction ----------------
+  {  // phi(q_j)[c], two threads per c (64 dims each)
+    float pq[G];
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int v = tid + 256 * k;
-      if (v < a.H_idx * IM_DI) yv[k] = qy[(size_t)b * a.H_idx * IM_DI + v];
+    for (int j = 0; j < G; ++j) pq[j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float wv[8];
+      unpack8(Wr[i], wv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int j = 0; j < G; ++j) pq[j] = fmaf(wv[e], sm.qs[j][hh * 64 + i * 8 + e], pq[j]);
     }
+#pragma unroll
+    for (int j = 0; j < G; ++j) sm.r.php[hh][j][wc] = pq[j];
   }
-  // first round of split records to LDS
-  const int cn0 = min(CH, n_act);
-  dec_stage<18>(&sm.pst[0][0][0], pbase, cn0 * G * DEC_REC);
-  dec_stage<5>((float*)&sm.cst[0][0], (const float*)cbase, cn0 * DEC_CAND);
-  if (tid < 40) {
+  // gate: one wave per head
+  for (int j = w; j < G; j += 4) {
+    float gz = bf2f(a.wg[lane]) * sm.qs[j][lane] + bf2f(a.wg[lane + 64]) * sm.qs[j][lane + 64];
+    gz = wave_sum_f(gz);
+    if (lane == 0) sm.gate[j] = 1.f / (1.f + __expf(-(gz + a.cg)));
+  }
+  if (tid < 40) {   // rows of the last live slot, as floats
     float f[8];
     unpack8(mv, f);
     float* dst = (tid < 16) ? &sm.lastk[tid * 8] : (tid < 32) ? &sm.lastv[(tid - 16) * 8] : &sm.lastki[(tid - 32) * 8];
@@ -588,7 +636,39 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   }
   if (tid == 40) sm.lastpos = mvpos;
   __syncthreads();
-  DEC_STAMP(9);
+  for (int idx = tid; idx < G * IM_DM; idx += 256) {
+    const int j = idx >> 7, c = idx & 127;
+    sm.phq[j][c] = sm.r.php[0][j][c] + sm.r.php[1][j][c];
+  }
+  __syncthreads();
+  {  // r_old[j][d] = sum_c phi_q[j][c] M[c][d] over this thread's 16 rows and 4 columns
+    float ra[G][4];
+#pragma unroll
+    for (int j = 0; j < G; ++j) ra[j][0] = ra[j][1] = ra[j][2] = ra[j][3] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+#pragma unroll
+      for (int j = 0; j < G; ++j) {
+        const float f = sm.phq[j][cg * 16 + i];
+        ra[j][0] = fmaf(f, Mr[i].x, ra[j][0]); ra[j][1] = fmaf(f, Mr[i].y, ra[j][1]);
+        ra[j][2] = fmaf(f, Mr[i].z, ra[j][2]); ra[j][3] = fmaf(f, Mr[i].w, ra[j][3]);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float x = halves_sum_f(ra[j][e]);
+        if (lane < 32) sm.r.red[w][j][4 * d4 + e] = x;
+      }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * IM_D; idx += 256) {
+    const int j = idx >> 7, d = idx & 127;
+    sm.rold[j][d] = sm.r.red[0][j][d] + sm.r.red[1][j][d] + sm.r.red[2][j][d] + sm.r.red[3][j][d];
+  }
+  __syncthreads();   // php / red are dead: the leftover key's scratch may use their space
+  DEC_STAMP(10);
   // ---------------- the leftover key as one more split: score, logits, candidate ----------------
   if (has_x) {   // uniform
     const int Hi = a.H_idx;
@@ -660,88 +740,39 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     __syncthreads();
   }
   const int x_split = has_x ? n_act : -2;   // index the leftover key goes by in the ranking
-  // ---------------- memory readout terms that do not depend on the eviction ----------------
-  {  // phi(q_j)[c], two threads per c (64 dims each)
-    float pq[G];
+  // ---------------- the evicted entry: ranked last over all splits and the leftover key ----------------
+  if (n_act > CH) {   // rare: more splits than one staged round; merge the per-thread results
 #pragma unroll
-    for (int j = 0; j < G; ++j) pq[j] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float wv[8];
-      unpack8(Wr[i], wv);
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-#pragma unroll
-        for (int j = 0; j < G; ++j) pq[j] = fmaf(wv[e], sm.qs[j][hh * 64 + i * 8 + e], pq[j]);
+    for (int o = 32; o > 0; o >>= 1) {
+      const unsigned long long ob = __shfl_xor(best, o, 64);
+      const int oi = __shfl_xor(bidx, o, 64);
+      if (oi >= 0 && (bidx < 0 || ob < best || (ob == best && oi > bidx))) { best = ob; bidx = oi; }
     }
-#pragma unroll
-    for (int j = 0; j < G; ++j) sm.r.php[hh][j][wc] = pq[j];
+    if (lane == 0) { sm.c64[w] = best; sm.cidx[w] = bidx; }
+    __syncthreads();
   }
-  // candidate ranked last: staged splits (one thread each), the rest, the leftover key
-  if (tid < cn0) {
-    const unsigned long long c = ((unsigned long long)sm.cst[tid][0] << 32) | sm.cst[tid][1];
-    if (bidx < 0 || c < best) { best = c; bidx = tid; }   // staged splits are the EARLIER ones: they lose full ties
-  }
-  if (has_x && tid == 0) {
-    const unsigned long long c = sm.xc64;
-    if (bidx < 0 || c <= best) { best = c; bidx = x_split; }   // the largest slot wins full ties
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const unsigned long long ob = __shfl_xor(best, o, 64);
-    const int oi = __shfl_xor(bidx, o, 64);
-    if (oi >= 0 && (bidx < 0 || ob < best || (ob == best && oi > bidx))) { best = ob; bidx = oi; }
-  }
-  if (lane == 0) { sm.c64[w] = best; sm.cidx[w] = bidx; }
-  __syncthreads();
   const bool evict = n > a.budget;
   if (n > a.budget + 1 && tid == 0) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
   if (tid == 0) {
-    unsigned long long bb = sm.c64[0];
-    int bi = sm.cidx[0];
-    for (int i = 1; i < 4; ++i) {
-      const int oi = sm.cidx[i];
-      if (oi >= 0 && (bi < 0 || sm.c64[i] < bb || (sm.c64[i] == bb && oi > bi))) { bb = sm.c64[i]; bi = oi; }
+    unsigned long long bb = ~0ull;
+    int bi = -1;
+    for (int sp = 0; sp < cn0; ++sp) {   // ascending: on a full tie the later split (larger slot) wins
+      const unsigned long long c = ((unsigned long long)sm.cst[sp][0] << 32) | sm.cst[sp][1];
+      if (c <= bb) { bb = c; bi = sp; }
     }
+    if (n_act > CH) {
+      for (int i = 0; i < 4; ++i) {
+        const int oi = sm.cidx[i];
+        if (oi >= 0 && (bi < 0 || sm.c64[i] < bb || (sm.c64[i] == bb && oi > bi))) { bb = sm.c64[i]; bi = oi; }
+      }
+    }
+    if (has_x && (bi < 0 || sm.xc64 <= bb)) { bb = sm.xc64; bi = x_split; }
     const bool ev = evict && bi >= 0;
     sm.e_split = ev ? bi : -1;
     sm.e_slot = !ev ? -1 : (bi == x_split) ? n_last : (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]);
   }
-  for (int idx = tid; idx < G * IM_DM; idx += 256) {
-    const int j = idx >> 7, c = idx & 127;
-    sm.phq[j][c] = sm.r.php[0][j][c] + sm.r.php[1][j][c];
-  }
   __syncthreads();
-  DEC_STAMP(10);
   const int e_split = sm.e_split, e_slot = sm.e_slot;
-  // gate: one wave per head
-  for (int j = w; j < G; j += 4) {
-    float gz = bf2f(a.wg[lane]) * sm.qs[j][lane] + bf2f(a.wg[lane + 64]) * sm.qs[j][lane + 64];
-    gz = wave_sum_f(gz);
-    if (lane == 0) sm.gate[j] = 1.f / (1.f + __expf(-(gz + a.cg)));
-  }
-  {  // r_old[j][d] = sum_c phi_q[j][c] M[c][d] over this thread's 16 rows and 4 columns
-    float ra[G][4];
-#pragma unroll
-    for (int j = 0; j < G; ++j) ra[j][0] = ra[j][1] = ra[j][2] = ra[j][3] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-#pragma unroll
-      for (int j = 0; j < G; ++j) {
-        const float f = sm.phq[j][cg * 16 + i];
-        ra[j][0] = fmaf(f, Mr[i].x, ra[j][0]); ra[j][1] = fmaf(f, Mr[i].y, ra[j][1]);
-        ra[j][2] = fmaf(f, Mr[i].z, ra[j][2]); ra[j][3] = fmaf(f, Mr[i].w, ra[j][3]);
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < G; ++j)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        float x = ra[j][e];
-        x += __shfl_xor(x, 32, 64);
-        if (lane < 32) sm.r.red[w][j][4 * d4 + e] = x;
-      }
-  }
   // the evicted entry's rows: the leftover key's own, or those in its split's candidate record
   if (e_slot >= 0 && tid < IM_D) {
     if (e_split == x_split) {
@@ -757,10 +788,6 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     }
   }
   __syncthreads();
-  for (int idx = tid; idx < G * IM_D; idx += 256) {
-    const int j = idx >> 7, d = idx & 127;
-    sm.rold[j][d] = sm.r.red[0][j][d] + sm.r.red[1][j][d] + sm.r.red[2][j][d] + sm.r.red[3][j][d];
-  }
   DEC_STAMP(11);
   // ---------------- memory write (rank one) ----------------
   if (e_slot >= 0) {

@@ -39,18 +39,88 @@ __device__ __forceinline__ uint32_t score_key(float s) {
 }
 #define IM_KEY_PINF 0xff800000u  // score_key(+inf)
 
-__device__ __forceinline__ float wave_sum_f(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+// ---- wave64 reductions on the VALU's DPP paths (ds_bpermute-based shuffles are far slower here) ----
+// row_shr:n = 0x110 + n, row_bcast:15 = 0x142, row_bcast:31 = 0x143.  After the six steps lane 63
+// holds the reduction of all 64 lanes; it is returned as a wave-uniform value.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_zero_f(float v) {   // lanes without a source read 0
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, true));
 }
-__device__ __forceinline__ double wave_sum_d(double v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_keep_f(float v) {   // lanes without a source read their own value
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_sum_f(float v) {
+  v += dpp_zero_f<0x111, 0xF>(v);
+  v += dpp_zero_f<0x112, 0xF>(v);
+  v += dpp_zero_f<0x114, 0xF>(v);
+  v += dpp_zero_f<0x118, 0xF>(v);
+  v += dpp_zero_f<0x142, 0xA>(v);
+  v += dpp_zero_f<0x143, 0xC>(v);
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_max_f(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_keep_f<0x111, 0xF>(v));
+  v = fmaxf(v, dpp_keep_f<0x112, 0xF>(v));
+  v = fmaxf(v, dpp_keep_f<0x114, 0xF>(v));
+  v = fmaxf(v, dpp_keep_f<0x118, 0xF>(v));
+  v = fmaxf(v, dpp_keep_f<0x142, 0xA>(v));
+  v = fmaxf(v, dpp_keep_f<0x143, 0xC>(v));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_zero_d(double v) {
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), CTRL, ROW_MASK, 0xF, true);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, ROW_MASK, 0xF, true);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+__device__ __forceinline__ double wave_sum_d(double v) {
+  v += dpp_zero_d<0x111, 0xF>(v);
+  v += dpp_zero_d<0x112, 0xF>(v);
+  v += dpp_zero_d<0x114, 0xF>(v);
+  v += dpp_zero_d<0x118, 0xF>(v);
+  v += dpp_zero_d<0x142, 0xA>(v);
+  v += dpp_zero_d<0x143, 0xC>(v);
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffll), 63);
+  const int hi = __builtin_amdgcn_readlane((int)(b >> 32), 63);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+// sum over the 4 lanes l, l^16, l^32, l^48 (the same position in the four 16-lane rows), returned
+// in every lane: two swaps of 16- and 32-lane halves (gfx950 v_permlane16_swap / v_permlane32_swap)
+__device__ __forceinline__ float rows_sum_f(float v) {
+  typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+  u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+__device__ __forceinline__ float rows_max_f(float v) {
+  typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+  u2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ double rows_sum_d(double v) {
+  typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+  const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+  unsigned int lo = (unsigned int)b, hi = (unsigned int)(b >> 32);
+  u2 rl = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);
+  u2 rh = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);
+  double s = __longlong_as_double((long long)(((unsigned long long)rh[0] << 32) | rl[0])) +
+             __longlong_as_double((long long)(((unsigned long long)rh[1] << 32) | rl[1]));
+  const unsigned long long c = (unsigned long long)__double_as_longlong(s);
+  lo = (unsigned int)c; hi = (unsigned int)(c >> 32);
+  rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+  rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+  return __longlong_as_double((long long)(((unsigned long long)rh[0] << 32) | rl[0])) +
+         __longlong_as_double((long long)(((unsigned long long)rh[1] << 32) | rl[1]));
+}
+// v + (the same lane of the other 32-lane half), in every lane
+__device__ __forceinline__ float halves_sum_f(float v) {
+  typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+  const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
