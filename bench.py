@@ -51,8 +51,9 @@ def algorithmic_bytes(w: Workload) -> dict:
     }
     unit_total = sum(per_unit.values())
     layer_total = units * unit_total + sum(per_layer.values())
-    # the main kernel of the fused step does everything but the query-side projection and the append
-    main_kernel = layer_total - per_layer["indexer_weights"] - units * per_unit["new_key"]
+    # the main kernel of the fused step (k_dec_main) streams the retained cache: the indexer key and
+    # the K / V rows of the B entries its 128-key splits cover (the newest entry is the tail kernel's)
+    main_kernel = units * (2 * w.idx_dim * Bg + per_unit["kv"])
     return {"per_unit": unit_total, "per_layer_step": layer_total, "main_kernel_per_launch": main_kernel,
             "attention_kv_per_layer": units * per_unit["kv"], "detail": {**per_unit, **per_layer}}
 
@@ -170,6 +171,9 @@ def main() -> None:
     ap.add_argument("--path", default="fused", choices=["fused", "steps"],
                     help="fused: im_decode_step (2 launches per layer); steps: the six separate calls")
     ap.add_argument("--no-graph", action="store_true", help="launch the fused path eagerly")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (torch copy_) so that a counter run "
+                         "has a dispatch of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quiet", action="store_true")
     a = ap.parse_args()
@@ -187,6 +191,12 @@ def main() -> None:
     torch.cuda.synchronize()
     log(f"setup (generation + prefill eviction of {w.n_layers} layers) {time.perf_counter() - t_setup:.1f} s")
 
+    if a.pmc_calibration:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda")     # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     use_graph = (a.path == "fused") and not a.no_graph
 
     def run(s0, s1):
@@ -236,8 +246,13 @@ def main() -> None:
         durs = im.im_profile_stop(job.handle)
         k_ms = float(np.mean(durs))
         achieved = ab["main_kernel_per_launch"] / (k_ms * 1e-3) / 1e9
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
+        if os.path.exists(tpath):   # HBM bytes per launch from the committed rocprofv3 --pmc summary
+            with open(tpath) as f:
+                traffic = json.load(f)["kernels"].get(f"k_dec_main<{w.group}>", {}).get("total_bytes")
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": "k_dec_main",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "k_dec_main",
                 "avg_launch_us": k_ms * 1e3, "launches_timed": len(durs),
                 "bytes_per_launch": ab["main_kernel_per_launch"]}
         log(f"k_dec_main: {k_ms * 1e3:.2f} us per launch over {len(durs)} launches -> {achieved:.0f} GB/s")

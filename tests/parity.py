@@ -71,17 +71,20 @@ class LockStep:
         pos = torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1).contiguous()
         q_attn = self.Q[:, t1 - 1].contiguous()
         d = lambda t: t.to(dev)
+        bi_t = torch.tensor(self.batch_ids, device=k_new.device)
+        hs_t = torch.tensor(self.kv_heads, device=k_new.device)
         qd = d(q_new)
         self.gpu.step(d(k_new), d(v_new), d(pos), qd, qd.view(w.batch, n_new, -1), d(pos), d(q_attn),
                       budget, w.lam, w.eta)
         torch.cuda.synchronize()
-        bi, hs = self.batch_ids, self.kv_heads
-        sel = lambda x: f64(x)[bi][:, hs]
-        qn = f64(q_new)[bi]
+        bi = self.batch_ids
+        # only the sampled units travel to the host (the inputs may live on the GPU)
+        sel = lambda x: f64(x.index_select(0, bi_t).index_select(1, hs_t))
+        qn = f64(q_new.index_select(0, bi_t))
         posn = pos.numpy()[bi]
         scores, keep, evict, out, res = self.ref.step(
-            sel(k_new), sel(v_new), posn, qn, qn.reshape(len(bi), n_new, -1), posn, f64(q_attn)[bi],
-            budget, w.lam, w.eta)
+            sel(k_new), sel(v_new), posn, qn, qn.reshape(len(bi), n_new, -1), posn,
+            f64(q_attn.index_select(0, bi_t)), budget, w.lam, w.eta)
         if check:
             self.compare(scores, keep, evict, out, res, tag)
         return scores, keep, evict, out, res
@@ -94,17 +97,19 @@ class LockStep:
         q_new = self.Q[:, t:t + 1].contiguous()
         pos = torch.full((w.batch, 1), t, dtype=torch.int32)
         d = lambda x: x.to(dev)
+        bi_t = torch.tensor(self.batch_ids, device=k_new.device)
+        hs_t = torch.tensor(self.kv_heads, device=k_new.device)
         qd = d(q_new).view(w.batch, w.n_q_heads, w.head_dim)
         posd = d(pos).view(w.batch)
         self.gpu.decode_step(d(k_new), d(v_new), posd, qd, qd.view(w.batch, -1), posd, budget, w.lam, w.eta,
                              debug=True)
         torch.cuda.synchronize()
-        bi, hs = self.batch_ids, self.kv_heads
-        sel = lambda x: f64(x)[bi][:, hs]
-        qn = f64(q_new)[bi]
+        bi = self.batch_ids
+        sel = lambda x: f64(x.index_select(0, bi_t).index_select(1, hs_t))
+        qn = f64(q_new.index_select(0, bi_t))
         posn = pos.numpy()[bi]
         scores, keep, evict, out, res = self.ref.step(
-            sel(k_new), sel(v_new), posn, qn, qn.reshape(len(bi), 1, -1), posn, f64(q_new[:, 0])[bi],
+            sel(k_new), sel(v_new), posn, qn, qn.reshape(len(bi), 1, -1), posn, qn[:, 0],
             budget, w.lam, w.eta)
         if check:
             self.compare(scores, keep, evict, out, res, tag, fused=True)

@@ -1,0 +1,24 @@
+"""Parity at the benchmark's full size and launch configuration: configuration 3 (batch 4, 8 KV
+heads, a 16384-token prompt evicted to 2048, then decode through im_decode_step with the live
+bound the benchmark sets).  The GPU runs every unit of one layer; the oracle follows a sample of
+units (they are independent) through the same events and every observable of those units is
+compared to the usual bars.  Configuration 4's head shape (7 query heads per KV head, 7 indexer
+heads) gets the same treatment at a reduced batch."""
+import pytest
+
+from parity import LockStep
+from workloads import WORKLOADS
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg3_full_size_sampled_units():
+    w = WORKLOADS["cfg3"].scaled(n_layers=1, decode_steps=6)
+    ls = LockStep(w, gen_device="cuda", batch_ids=[1, 3], kv_heads=[2, 5])
+    ls.run_schedule(fused_decode=True)
+
+
+def test_cfg4_shape_full_context_sampled_units():
+    w = WORKLOADS["cfg4"].scaled(n_layers=1, batch=4, decode_steps=4)
+    ls = LockStep(w, gen_device="cuda", batch_ids=[2], kv_heads=[0, 3])
+    ls.run_schedule(fused_decode=True)
