@@ -17,9 +17,14 @@
 #define DEC_KEYS 128                 // keys per split workgroup (8 MFMA tiles of 16)
 #define DEC_REC (IM_D + 2)           // partial record per (unit, split, head): max, denom, 128 numerators
 #define DEC_GMAX 8                   // query heads per KV head supported
-#define DEC_CAND 144                 // words per candidate record: 16 header, 64 K row, 64 V row
+#define DEC_CAND 176                 // words per candidate record: 16 header, 64 K row, 64 V row, 32 Kidx row
 #define DEC_CAND_K 16
 #define DEC_CAND_V 80
+#define DEC_CAND_KI 144
+// header words: 0 rank key (score part), 1 rank key (position part), 2 slot, 3 live entries n of the
+// unit, 4..11 attention logits of the entry, 12 its token position.  Record index S (one past the
+// splits) describes the LAST live slot: the entry that moves into the hole, and, when n = 128 S + 1,
+// the one key no split covers (then it also carries that key's rank key and logits).
 
 #define IM_STATUS_APPEND_OVERFLOW_BIT 1
 #define IM_STATUS_LIVE_EXCEEDED_BIT 2
@@ -265,35 +270,55 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       nw[0] = *(const uint4*)(a.nqw + 16 * kq);
       nw[1] = *(const uint4*)(a.nqw + 16 * kq + 8);
     }
+    // rows past the end of the split are read from its last row instead (finite values, no branches):
+    // their logits are masked and their probabilities are zero further down
     uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int kr = 16 * (2 * w + tt) + l16;
+      const int kr = min(16 * (2 * w + tt) + l16, nk - 1);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
-        kif[tt][i] = (kr < nk) ? *(const uint4*)(a.Kidx + (base + kr) * IM_DI + 16 * kq + 8 * i) : make_uint4(0, 0, 0, 0);
+        kif[tt][i] = *(const uint4*)(a.Kidx + (base + kr) * IM_DI + 16 * kq + 8 * i);
     }
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int kr = 16 * (2 * w + tt) + l16;
+      const int kr = min(16 * (2 * w + tt) + l16, nk - 1);
 #pragma unroll
-      for (int c = 0; c < 4; ++c)
-        kf[tt][c] = (kr < nk) ? *(const uint4*)(a.K + (base + kr) * IM_D + 32 * c + 8 * kq) : make_uint4(0, 0, 0, 0);
+      for (int c = 0; c < 4; ++c) kf[tt][c] = *(const uint4*)(a.K + (base + kr) * IM_D + 32 * c + 8 * kq);
     }
+    {
+      const int jq = min(l16, G - 1);   // lanes past the group read its last head; masked below
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
-      qf[c] = (l16 < G) ? *(const uint4*)(a.q + ((size_t)b * a.H + h * G + l16) * IM_D + 32 * c + 8 * kq)
-                        : make_uint4(0, 0, 0, 0);
+      for (int c = 0; c < 4; ++c) {
+        qf[c] = *(const uint4*)(a.q + ((size_t)b * a.H + h * G + jq) * IM_D + 32 * c + 8 * kq);
+        if (l16 >= G) qf[c] = make_uint4(0, 0, 0, 0);
+      }
+    }
     const int kk = tid & 127;
-    const int mypos = (kk < nk) ? a.pos[base + kk] : 0;
+    const int mypos = a.pos[base + min(kk, nk - 1)];
     const int qpos = a.q_pos[b];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const int vr = 16 * (2 * w + tt) + 4 * i + kq;
-        vf[tt][i] = (vr < nk) ? *(const uint4*)(a.V + (base + vr) * IM_D + 8 * l16) : make_uint4(0, 0, 0, 0);
+        const int vr = min(16 * (2 * w + tt) + 4 * i + kq, nk - 1);
+        vf[tt][i] = *(const uint4*)(a.V + (base + vr) * IM_D + 8 * l16);
       }
+    }
+    // split 0 also looks after the one key beyond the splits, when there is one
+    const bool do_x = (s == 0) && (n > a.S * DEC_KEYS);
+    uint4 xki[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)}, xk[4], xv = make_uint4(0, 0, 0, 0);
+    int xpos = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) xk[c] = make_uint4(0, 0, 0, 0);
+    if (do_x) {
+      const size_t last = (size_t)u * a.C + (n - 1);
+      xki[0] = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq);
+      xki[1] = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq + 8);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) xk[c] = *(const uint4*)(a.K + last * IM_D + 32 * c + 8 * kq);
+      xv = *(const uint4*)(a.V + last * IM_D + 8 * l16);
+      xpos = a.pos[last];
     }
     // keep every load above this line, in this order: loads return in order, so each phase below
     // waits only for what it uses while the rest of the split is still streaming in
@@ -320,6 +345,49 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         qd[m] = hv ? (double)(float)(qq * (double)wf[m]) : 0.0;
       }
       alj = hv ? (double)(float)(araw / sqrt((double)(a.H_idx * IM_DI))) : 0.0;
+    }
+    if (do_x) {   // uniform per workgroup; every wave computes, wave 0 writes
+      uint32_t* xrec = a.cand + ((size_t)u * a.S_alloc + a.S) * DEC_CAND;
+      float fx[16];
+      unpack8(xki[0], fx);
+      unpack8(xki[1], fx + 8);
+      double zp = 0.0;
+#pragma unroll
+      for (int m = 0; m < 16; ++m) zp = fma(qd[m], (double)fx[m], zp);
+      zp = rows_sum_d(zp);                                   // q_j . k over the 64 dims, in all 4 rows
+      const double asum = wave_sum_d((kq == 0) ? alj * fmax(zp, 0.0) : 0.0);
+      float lp = 0.f;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        float qv[8], kv[8];
+        unpack8(qf[c], qv);
+        unpack8(xk[c], kv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) lp = fmaf(qv[e], kv[e], lp);
+      }
+      lp = rows_sum_f(lp) * a.scale;
+      if (w == 0) {
+        if (kq == 0 && l16 < G) xrec[4 + l16] = __float_as_uint(lp);
+        if (l16 == 0) {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) *(uint4*)(xrec + DEC_CAND_K + 16 * c + 4 * kq) = xk[c];
+          *(uint4*)(xrec + DEC_CAND_KI + 8 * kq) = xki[0];
+          *(uint4*)(xrec + DEC_CAND_KI + 8 * kq + 4) = xki[1];
+        }
+        if (kq == 0) *(uint4*)(xrec + DEC_CAND_V + 4 * l16) = xv;
+        if (lane == 0) {
+          const float sc = (xpos <= qpos) ? (float)asum : -INFINITY;
+          if (a.scores) a.scores[(size_t)u * a.C + (n - 1)] = sc;
+          const bool forced = (xpos < a.n_sink) ||
+                              (a.n_recent > 0 && (long long)xpos > (long long)a.maxpos[u] - a.n_recent);
+          const uint32_t skey = forced ? IM_KEY_PINF : score_key(sc);
+          xrec[0] = skey;
+          xrec[1] = (uint32_t)(~((uint32_t)xpos ^ 0x80000000u));
+          xrec[2] = (uint32_t)(n - 1);
+          xrec[3] = (uint32_t)n;
+          xrec[12] = (uint32_t)xpos;
+        }
+      }
     }
     DEC_STAMP(2);
     // ---- gated similarities of the 2 tiles of this wave: Z[key][head] = Kidx_tile . q^T (fp64 MFMA)
@@ -483,36 +551,52 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       crec[0] = (uint32_t)(cbest >> 32);
       crec[1] = (uint32_t)cbest;
       crec[2] = (uint32_t)(k0 + cl);
+      crec[3] = (uint32_t)n;
     }
     if (tid < G) crec[4 + tid] = __float_as_uint(sm.clog[tid]);
-    // the candidate's rows travel with the record, so the tail has no dependent loads
-    if (tid >= 64 && tid < 80)
-      *(uint4*)(crec + DEC_CAND_K + (tid - 64) * 4) = *(const uint4*)(a.K + (base + cl) * IM_D + (tid - 64) * 8);
-    else if (tid >= 128 && tid < 144)
-      *(uint4*)(crec + DEC_CAND_V + (tid - 128) * 4) = *(const uint4*)(a.V + (base + cl) * IM_D + (tid - 128) * 8);
+    // the candidate's rows travel with the record (straight from the fragments), so the tail has
+    // no dependent loads; the split that holds the last live slot also fills the last-slot record
+    const bool own_last = (n <= a.S * DEC_KEYS) && (k0 + nk == n);
+    uint32_t* lrec = a.cand + ((size_t)u * a.S_alloc + a.S) * DEC_CAND;
+    const int ll = n - 1 - k0;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int T = 2 * w + tt;
+      if (16 * T + l16 == cl) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) *(uint4*)(crec + DEC_CAND_K + 16 * c + 4 * kq) = kf[tt][c];
+      }
+      if (own_last && 16 * T + l16 == ll) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) *(uint4*)(lrec + DEC_CAND_K + 16 * c + 4 * kq) = kf[tt][c];
+        *(uint4*)(lrec + DEC_CAND_KI + 8 * kq) = kif[tt][0];
+        *(uint4*)(lrec + DEC_CAND_KI + 8 * kq + 4) = kif[tt][1];
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int vr = 16 * T + 4 * i + kq;
+        if (vr == cl) *(uint4*)(crec + DEC_CAND_V + 4 * l16) = vf[tt][i];
+        if (own_last && vr == ll) *(uint4*)(lrec + DEC_CAND_V + 4 * l16) = vf[tt][i];
+      }
+    }
+    if (own_last && tid == ll) { lrec[2] = (uint32_t)(n - 1); lrec[3] = (uint32_t)n; lrec[12] = (uint32_t)mypos; }
+  } else if (s == 0 && tid == 0) {
+    crec[3] = (uint32_t)n;   // an empty unit still tells the tail its length
   }
 }
-
-
 
 template <int G>
 struct DecTailSmem {
   static constexpr int CH = (G <= 4) ? 16 : 4;   // splits staged per round
   float pst[CH][G][DEC_REC];                      // partial records of the staged splits
-  uint32_t cst[CH][DEC_CAND];                     // their candidate records
+  uint32_t cst[CH + 1][DEC_CAND];                 // their candidate records (+ the last-slot record)
   float qs[G][IM_D];
-  union {                                         // used one after the other
-    struct { double qn[16 * IM_DI]; double pr[16 * IM_DI]; } x;   // the leftover key: query features, products
-    struct { float php[2][G][IM_DM]; float red[4][G][IM_D]; } r;  // readout terms
-  };
+  float php[2][G][IM_DM];
+  float red[4][G][IM_D];
   float phq[G][IM_DM];
   float rold[G][IM_D];
   float ke[IM_D], ve[IM_D], phe2[2][IM_DM], phe[IM_DM], bnew[IM_DM];
-  float lastk[IM_D], lastv[IM_D];                 // rows of the last live slot (the leftover key, the mover)
-  float lastki[IM_DI];
-  int lastpos;
-  unsigned long long xc64;
-  double hsum[16];
+  float lastv[IM_D];                              // V row of the last live slot
   float xlog[DEC_GMAX];                           // the leftover key's attention logits
   float gate[G], den[G], dot[G];
   unsigned long long c64[4];
@@ -525,12 +609,13 @@ struct DecTailSmem {
 template <int NB>
 __device__ __forceinline__ void dec_stage(float* dst, const float* __restrict__ src, int count) {
   const int n2 = count >> 1;
+  if (n2 <= 0) return;
   for (int base = 0; base < n2; base += 256 * NB) {
     float2 r[NB];
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
       const int i = base + threadIdx.x + 256 * k;
-      r[k] = (i < n2) ? ((const float2*)src)[i] : make_float2(0.f, 0.f);
+      r[k] = ((const float2*)src)[min(i, n2 - 1)];   // clamped: no branch around the load
     }
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
@@ -541,22 +626,14 @@ __device__ __forceinline__ void dec_stage(float* dst, const float* __restrict__ 
 }
 
 template <int G>
-__device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem<G>& sm,
-                                         const double* __restrict__ qy, const double* __restrict__ alpha) {
+__device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem<G>& sm) {
   constexpr int CH = DecTailSmem<G>::CH;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int b = u / a.H_kv, h = u % a.H_kv;
   DEC_STAMP(8);
-  const int n_old = a.len[u];
-  const bool has_new = n_old + 1 <= a.C;
-  const int n = min(n_old + (has_new ? 1 : 0), a.max_live);
-  // splits [0, n_act) were done by the main kernel; at most ONE key lies beyond them (n = 128 S + 1,
-  // the usual steady state with a power-of-two budget): this workgroup handles it as split n_act
-  const int n_act = min((n + DEC_KEYS - 1) / DEC_KEYS, a.S);
-  const bool has_x = n > a.S * DEC_KEYS;
   const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
   const float* pbase = a.part + (size_t)u * a.S_alloc * G * DEC_REC;
-  // ---------------- every load whose address is known now ----------------
+  // ---------------- every load is issued now: no address depends on another load ----------------
   const int d4 = tid & 31, cg = tid >> 5;
   float4 Mr[16];
   float* Mu = a.M + (size_t)u * IM_DM * IM_D;
@@ -569,21 +646,20 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const float b_old = (tid < IM_DM) ? a.bvec[(size_t)u * IM_DM + tid] : 0.f;
   for (int idx = tid; idx < G * IM_D; idx += 256)
     sm.qs[idx >> 7][idx & 127] = bf2f(a.q[((size_t)b * a.H + h * G) * IM_D + idx]);
-  // raw query projections of this batch row (only a leftover key needs them here)
-  const bool may_x = a.max_live > a.S * DEC_KEYS;   // host-known: a leftover key can exist
-  double yv[4] = {0.0, 0.0, 0.0, 0.0};
-  if (may_x) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int v = tid + 256 * k;
-      if (v < a.H_idx * IM_DI) yv[k] = qy[(size_t)b * a.H_idx * IM_DI + v];
-    }
-  }
-  // first round of split records to LDS (all launched splits: which ones are live is checked later)
+  // first round of split records (all launched splits; which are live is known once n is read
+  // from record 0) and, right behind them, the last-slot record
   const int cs0 = min(CH, a.S);
+  const int LS = a.S;                          // index of the last-slot record
+  const bool ls_staged = LS <= CH;
   dec_stage<18>(&sm.pst[0][0][0], pbase, cs0 * G * DEC_REC);
-  dec_stage<5>((float*)&sm.cst[0][0], (const float*)cbase, cs0 * DEC_CAND);
-  const int cn0 = min(CH, n_act);
+  dec_stage<6>((float*)&sm.cst[0][0], (const float*)cbase, (ls_staged ? LS + 1 : cs0) * DEC_CAND);
+  __syncthreads();
+  DEC_STAMP(9);
+  const int n = (int)sm.cst[0][3];
+  const int n_act = min((n + DEC_KEYS - 1) / DEC_KEYS, a.S);
+  const bool has_x = n > a.S * DEC_KEYS;      // one key beyond the splits: described by the last-slot record
+  const int n_last = n - 1;
+  const uint32_t* lsrec = ls_staged ? (const uint32_t*)&sm.cst[LS][0] : cbase + (size_t)LS * DEC_CAND;
   // candidate keys of the splits beyond the first staged round (none in the usual case)
   unsigned long long best = ~0ull;
   int bidx = -1;
@@ -591,19 +667,22 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     const unsigned long long c = ((unsigned long long)cbase[(size_t)sp * DEC_CAND] << 32) | cbase[(size_t)sp * DEC_CAND + 1];
     if (c <= best) { best = c; bidx = sp; }   // later splits hold larger slots: they win full ties
   }
-  // the last live slot: it moves into the hole, and it is the leftover key when there is one
-  const int n_last = n - 1;
+  // the last live slot's rows: they move into the hole
   uint4 mv = make_uint4(0, 0, 0, 0);
   int mvpos = 0;
   if (n > 0) {
-    const size_t src = (size_t)u * a.C + n_last;
-    if (tid < 16) mv = *(const uint4*)(a.K + src * IM_D + tid * 8);
-    else if (tid < 32) mv = *(const uint4*)(a.V + src * IM_D + (tid - 16) * 8);
-    else if (tid < 40) mv = *(const uint4*)(a.Kidx + src * IM_DI + (tid - 32) * 8);
-    else if (tid == 40) mvpos = a.pos[src];
+    if (tid < 16) mv = *(const uint4*)(lsrec + DEC_CAND_K + 4 * tid);
+    else if (tid < 32) mv = *(const uint4*)(lsrec + DEC_CAND_V + 4 * (tid - 16));
+    else if (tid < 40) mv = *(const uint4*)(lsrec + DEC_CAND_KI + 4 * (tid - 32));
+    else if (tid == 40) mvpos = (int)lsrec[12];
   }
-  __syncthreads();
-  DEC_STAMP(9);
+  if (tid >= 16 && tid < 32) {
+    float f[8];
+    unpack8(mv, f);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sm.lastv[(tid - 16) * 8 + e] = f[e];
+  }
+  if (tid < G) sm.xlog[tid] = __uint_as_float(lsrec[4 + tid]);
   // ---------------- memory readout terms that do not depend on the eviction ----------------
   {  // phi(q_j)[c], two threads per c (64 dims each)
     float pq[G];
@@ -619,7 +698,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
         for (int j = 0; j < G; ++j) pq[j] = fmaf(wv[e], sm.qs[j][hh * 64 + i * 8 + e], pq[j]);
     }
 #pragma unroll
-    for (int j = 0; j < G; ++j) sm.r.php[hh][j][wc] = pq[j];
+    for (int j = 0; j < G; ++j) sm.php[hh][j][wc] = pq[j];
   }
   // gate: one wave per head
   for (int j = w; j < G; j += 4) {
@@ -627,120 +706,9 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     gz = wave_sum_f(gz);
     if (lane == 0) sm.gate[j] = 1.f / (1.f + __expf(-(gz + a.cg)));
   }
-  if (tid < 40) {   // rows of the last live slot, as floats
-    float f[8];
-    unpack8(mv, f);
-    float* dst = (tid < 16) ? &sm.lastk[tid * 8] : (tid < 32) ? &sm.lastv[(tid - 16) * 8] : &sm.lastki[(tid - 32) * 8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) dst[e] = f[e];
-  }
-  if (tid == 40) sm.lastpos = mvpos;
-  __syncthreads();
-  for (int idx = tid; idx < G * IM_DM; idx += 256) {
-    const int j = idx >> 7, c = idx & 127;
-    sm.phq[j][c] = sm.r.php[0][j][c] + sm.r.php[1][j][c];
-  }
-  __syncthreads();
-  {  // r_old[j][d] = sum_c phi_q[j][c] M[c][d] over this thread's 16 rows and 4 columns
-    float ra[G][4];
-#pragma unroll
-    for (int j = 0; j < G; ++j) ra[j][0] = ra[j][1] = ra[j][2] = ra[j][3] = 0.f;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-#pragma unroll
-      for (int j = 0; j < G; ++j) {
-        const float f = sm.phq[j][cg * 16 + i];
-        ra[j][0] = fmaf(f, Mr[i].x, ra[j][0]); ra[j][1] = fmaf(f, Mr[i].y, ra[j][1]);
-        ra[j][2] = fmaf(f, Mr[i].z, ra[j][2]); ra[j][3] = fmaf(f, Mr[i].w, ra[j][3]);
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < G; ++j)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float x = halves_sum_f(ra[j][e]);
-        if (lane < 32) sm.r.red[w][j][4 * d4 + e] = x;
-      }
-  }
-  __syncthreads();
-  for (int idx = tid; idx < G * IM_D; idx += 256) {
-    const int j = idx >> 7, d = idx & 127;
-    sm.rold[j][d] = sm.r.red[0][j][d] + sm.r.red[1][j][d] + sm.r.red[2][j][d] + sm.r.red[3][j][d];
-  }
-  __syncthreads();   // php / red are dead: the leftover key's scratch may use their space
-  DEC_STAMP(10);
-  // ---------------- the leftover key as one more split: score, logits, candidate ----------------
-  if (has_x) {   // uniform
-    const int Hi = a.H_idx;
-    // QK-Norm of the query features, as in the main kernel: sums of 64 squares in two levels of 8
-#pragma unroll
-    for (int k = 0; k < 4; ++k) sm.x.pr[tid + 256 * k] = yv[k] * yv[k];
-    __syncthreads();
-    if (tid < Hi * 8) {
-      double t = 0.0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) t += sm.x.pr[tid * 8 + e];
-      sm.x.qn[tid] = t;
-    }
-    __syncthreads();
-    if (tid < Hi) {
-      double t = 0.0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) t += sm.x.qn[tid * 8 + e];
-      sm.hsum[tid] = t;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      const int v = tid + 256 * k;
-      if (v < Hi * IM_DI) {
-        const int j = v >> 6, c = v & 63;
-        const double rr = sqrt(sm.hsum[j] / (double)IM_DI + (double)a.rms_eps);
-        const double inv = 1.0 / rr;
-        double qq = yv[k] * inv;
-        qq = fma(fma(-qq, rr, yv[k]), inv, qq);
-        const double wt = a.nqw ? (double)bf2f(a.nqw[c]) : 1.0;
-        const double qn = (double)(float)(qq * wt);
-        sm.x.pr[v] = qn * (double)sm.lastki[c];      // product with the key's indexer feature
-      }
-    }
-    __syncthreads();
-    if (tid < Hi * 8) {
-      double t = 0.0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) t += sm.x.pr[tid * 8 + e];
-      sm.x.qn[tid] = t;
-    }
-    // attention logits of the leftover key: wave w takes heads w, w + 4
-    for (int j = w; j < G; j += 4) {
-      float t = sm.qs[j][lane] * sm.lastk[lane] + sm.qs[j][lane + 64] * sm.lastk[lane + 64];
-      t = wave_sum_f(t);
-      if (lane == 0) sm.xlog[j] = t * a.scale;
-    }
-    __syncthreads();
-    if (tid < Hi) {
-      double t = 0.0;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) t += sm.x.qn[tid * 8 + e];
-      const double al = (double)(float)(alpha[(size_t)b * Hi + tid] / sqrt((double)(Hi * IM_DI)));
-      sm.hsum[tid] = al * fmax(t, 0.0);
-    }
-    __syncthreads();
-    if (tid == 0) {
-      double asum = 0.0;
-      for (int j = 0; j < Hi; ++j) asum += sm.hsum[j];
-      const int xpos = sm.lastpos;
-      const float sc = (xpos <= a.q_pos[b]) ? (float)asum : -INFINITY;
-      if (a.scores) a.scores[(size_t)u * a.C + n_last] = sc;
-      const bool forced = (xpos < a.n_sink) ||
-                          (a.n_recent > 0 && (long long)xpos > (long long)a.maxpos[u] - a.n_recent);
-      const uint32_t skey = forced ? IM_KEY_PINF : score_key(sc);
-      sm.xc64 = ((unsigned long long)skey << 32) | (uint32_t)(~((uint32_t)xpos ^ 0x80000000u));
-    }
-    __syncthreads();
-  }
-  const int x_split = has_x ? n_act : -2;   // index the leftover key goes by in the ranking
   // ---------------- the evicted entry: ranked last over all splits and the leftover key ----------------
+  const int x_split = has_x ? n_act : -2;   // index the leftover key goes by in the ranking
+  const int cn0 = min(CH, n_act);
   if (n_act > CH) {   // rare: more splits than one staged round; merge the per-thread results
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -766,51 +734,80 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
         if (oi >= 0 && (bi < 0 || sm.c64[i] < bb || (sm.c64[i] == bb && oi > bi))) { bb = sm.c64[i]; bi = oi; }
       }
     }
-    if (has_x && (bi < 0 || sm.xc64 <= bb)) { bb = sm.xc64; bi = x_split; }
+    if (has_x) {
+      const unsigned long long xc = ((unsigned long long)lsrec[0] << 32) | lsrec[1];
+      if (bi < 0 || xc <= bb) { bb = xc; bi = x_split; }
+    }
     const bool ev = evict && bi >= 0;
     sm.e_split = ev ? bi : -1;
     sm.e_slot = !ev ? -1 : (bi == x_split) ? n_last : (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]);
   }
   __syncthreads();
+  for (int idx = tid; idx < G * IM_DM; idx += 256) {
+    const int j = idx >> 7, c = idx & 127;
+    sm.phq[j][c] = sm.php[0][j][c] + sm.php[1][j][c];
+  }
   const int e_split = sm.e_split, e_slot = sm.e_slot;
-  // the evicted entry's rows: the leftover key's own, or those in its split's candidate record
+  // the evicted entry's rows: in the record of its split, or in the last-slot record
   if (e_slot >= 0 && tid < IM_D) {
-    if (e_split == x_split) {
-      sm.ke[tid] = sm.lastk[tid];
-      sm.ve[tid] = sm.lastv[tid];
-    } else {
-      const bf16_t* kr = (e_split < CH) ? (const bf16_t*)&sm.cst[e_split][DEC_CAND_K]
-                                        : (const bf16_t*)(cbase + (size_t)e_split * DEC_CAND + DEC_CAND_K);
-      const bf16_t* vr = (e_split < CH) ? (const bf16_t*)&sm.cst[e_split][DEC_CAND_V]
-                                        : (const bf16_t*)(cbase + (size_t)e_split * DEC_CAND + DEC_CAND_V);
-      sm.ke[tid] = bf2f(kr[tid]);
-      sm.ve[tid] = bf2f(vr[tid]);
+    const uint32_t* er = (e_split == x_split) ? lsrec
+                       : (e_split < CH) ? (const uint32_t*)&sm.cst[e_split][0] : cbase + (size_t)e_split * DEC_CAND;
+    sm.ke[tid] = bf2f(((const bf16_t*)(er + DEC_CAND_K))[tid]);
+    sm.ve[tid] = bf2f(((const bf16_t*)(er + DEC_CAND_V))[tid]);
+  }
+  __syncthreads();
+  DEC_STAMP(10);
+  {  // r_old[j][d] = sum_c phi_q[j][c] M[c][d] over this thread's 16 rows and 4 columns
+    float ra[G][4];
+#pragma unroll
+    for (int j = 0; j < G; ++j) ra[j][0] = ra[j][1] = ra[j][2] = ra[j][3] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+#pragma unroll
+      for (int j = 0; j < G; ++j) {
+        const float f = sm.phq[j][cg * 16 + i];
+        ra[j][0] = fmaf(f, Mr[i].x, ra[j][0]); ra[j][1] = fmaf(f, Mr[i].y, ra[j][1]);
+        ra[j][2] = fmaf(f, Mr[i].z, ra[j][2]); ra[j][3] = fmaf(f, Mr[i].w, ra[j][3]);
+      }
     }
+#pragma unroll
+    for (int j = 0; j < G; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float x = halves_sum_f(ra[j][e]);
+        if (lane < 32) sm.red[w][j][4 * d4 + e] = x;
+      }
+  }
+  // ---------------- memory write (rank one) ----------------
+  if (e_slot >= 0) {
+    float pe = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float wv[8];
+      unpack8(Wr[i], wv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pe = fmaf(wv[e], sm.ke[hh * 64 + i * 8 + e], pe);
+    }
+    sm.phe2[hh][wc] = pe;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * IM_D; idx += 256) {
+    const int j = idx >> 7, d = idx & 127;
+    sm.rold[j][d] = sm.red[0][j][d] + sm.red[1][j][d] + sm.red[2][j][d] + sm.red[3][j][d];
+  }
+  if (tid < IM_DM) {
+    float bn = b_old;
+    if (e_slot >= 0) {
+      const float pe = sm.phe2[0][tid] + sm.phe2[1][tid];
+      sm.phe[tid] = pe;
+      bn = fmaf(a.lambda, b_old, a.eta * pe * pe);
+      a.bvec[(size_t)u * IM_DM + tid] = bn;
+    }
+    sm.bnew[tid] = bn;
   }
   __syncthreads();
   DEC_STAMP(11);
-  // ---------------- memory write (rank one) ----------------
   if (e_slot >= 0) {
-    {
-      float pe = 0.f;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        float wv[8];
-        unpack8(Wr[i], wv);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pe = fmaf(wv[e], sm.ke[hh * 64 + i * 8 + e], pe);
-      }
-      sm.phe2[hh][wc] = pe;
-    }
-    __syncthreads();
-    if (tid < IM_DM) {
-      const float pe = sm.phe2[0][tid] + sm.phe2[1][tid];
-      sm.phe[tid] = pe;
-      const float bn = fmaf(a.lambda, b_old, a.eta * pe * pe);
-      sm.bnew[tid] = bn;
-      a.bvec[(size_t)u * IM_DM + tid] = bn;
-    }
-    __syncthreads();
     // M <- lambda M + eta phi_e v_e^T for this thread's 16 x 4 patch
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -818,11 +815,10 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       float4 m = Mr[i];
       m.x = fmaf(a.lambda, m.x, f * sm.ve[4 * d4 + 0]); m.y = fmaf(a.lambda, m.y, f * sm.ve[4 * d4 + 1]);
       m.z = fmaf(a.lambda, m.z, f * sm.ve[4 * d4 + 2]); m.w = fmaf(a.lambda, m.w, f * sm.ve[4 * d4 + 3]);
+#ifndef DEC_EXP_NO_MSTORE
       *(float4*)(Mu + (cg * 16 + i) * IM_D + 4 * d4) = m;
+#endif
     }
-  } else {
-    if (tid < IM_DM) sm.bnew[tid] = b_old;
-    __syncthreads();
   }
   for (int j = w; j < G; j += 4) {
     float dn = sm.phq[j][lane] * sm.phq[j][lane] * sm.bnew[lane] +
@@ -839,12 +835,16 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   float rm[NP], rl[NP], ro[NP];
 #pragma unroll
   for (int k = 0; k < NP; ++k) { rm[k] = -1e30f; rl[k] = 0.f; ro[k] = 0.f; }
+#ifdef DEC_EXP_NO_MERGE
+  for (int c0 = 0; c0 < 0; c0 += CH) {
+#else
   for (int c0 = 0; c0 < n_act; c0 += CH) {
+#endif
     const int cn = min(CH, n_act - c0);
     if (c0 > 0) {
       __syncthreads();
       dec_stage<18>(&sm.pst[0][0][0], pbase + (size_t)c0 * G * DEC_REC, cn * G * DEC_REC);
-      dec_stage<5>((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
+      dec_stage<6>((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
       __syncthreads();
     }
 #pragma unroll
@@ -856,13 +856,17 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
         float pm[CH], plv[CH], po[CH], cl[CH], cv[CH];
 #pragma unroll
         for (int sp = 0; sp < CH; ++sp) {
+          // unconditional LDS reads (slots past cn hold stale words), then selects: no branches
+          const float r0 = sm.pst[sp][j][0], r1 = sm.pst[sp][j][1], r2 = sm.pst[sp][j][2 + d];
+          const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
+          const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
           const bool on = sp < cn;
-          pm[sp] = on ? sm.pst[sp][j][0] : -1e30f;
-          plv[sp] = on ? sm.pst[sp][j][1] : 0.f;
-          po[sp] = on ? sm.pst[sp][j][2 + d] : 0.f;
           const bool stays = on && (c0 + sp != e_split);
-          cl[sp] = stays ? __uint_as_float(sm.cst[sp][4 + j]) : -INFINITY;
-          cv[sp] = stays ? bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]) : 0.f;
+          pm[sp] = on ? r0 : -1e30f;
+          plv[sp] = on ? r1 : 0.f;
+          po[sp] = on ? r2 : 0.f;
+          cl[sp] = stays ? r3 : -INFINITY;
+          cv[sp] = stays ? r4 : 0.f;
         }
         float m = rm[k];
 #pragma unroll
@@ -931,8 +935,7 @@ __global__ __launch_bounds__(256, 2) void k_dec_main(const DecArgs a, const doub
 
 // grid: units
 template <int G>
-__global__ __launch_bounds__(256) void k_dec_tail(const DecArgs a, const double* __restrict__ qy,
-                                                  const double* __restrict__ alpha) {
+__global__ __launch_bounds__(256) void k_dec_tail(const DecArgs a) {
   __shared__ __attribute__((aligned(16))) DecTailSmem<G> sm;
-  dec_tail<G>(a, blockIdx.x, sm, qy, alpha);
+  dec_tail<G>(a, blockIdx.x, sm);
 }

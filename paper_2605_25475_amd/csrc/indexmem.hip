@@ -75,7 +75,7 @@ void layout(const im_config* c, im_handle* h) {
   size_t off = 0;
   // status word, 16 head counters, then one newest-position word per unit
   h->off_status = off; off = align256(off + (32 + units) * sizeof(int32_t));
-  h->dec_splits = (c->capacity + DEC_KEYS - 1) / DEC_KEYS;
+  h->dec_splits = (c->capacity + DEC_KEYS - 1) / DEC_KEYS + 1;   // + the last-slot record
   h->off_qy = off;     off = align256(off + B * c->max_queries * Hi * IM_DI * sizeof(double));
   h->off_alpha = off;  off = align256(off + B * c->max_queries * Hi * sizeof(double));
   h->off_mem = off;    off = align256(off + units * h->mem_split * (IM_DM * IM_D + IM_DM) * sizeof(float));
@@ -415,7 +415,7 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
   case g:                                                           \
     k_dec_main<g><<<main_blocks, 256, 0, s>>>(a, a.qy, a.alpha);    \
     if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n + 1], s); \
-    k_dec_tail<g><<<units, 256, 0, s>>>(a, a.qy, a.alpha);          \
+    k_dec_tail<g><<<units, 256, 0, s>>>(a);                         \
     break;
   switch (G) {
     IM_DEC_CASE(1) IM_DEC_CASE(2) IM_DEC_CASE(3) IM_DEC_CASE(4)
