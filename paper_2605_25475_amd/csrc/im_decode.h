@@ -585,41 +585,46 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   }
 }
 
+#define DEC_TT 1024   // threads of a tail workgroup: the tail is a chain of short phases, so it is
+                      // spread thin over 16 waves of one CU
+
 template <int G>
 struct DecTailSmem {
   static constexpr int CH = (G <= 4) ? 16 : 4;   // splits staged per round
+  static constexpr int NS = (G <= 4) ? 2 : 1;    // threads sharing one output in the merge
   float pst[CH][G][DEC_REC];                      // partial records of the staged splits
   uint32_t cst[CH + 1][DEC_CAND];                 // their candidate records (+ the last-slot record)
   float qs[G][IM_D];
-  float php[2][G][IM_DM];
-  float red[4][G][IM_D];
+  float php[8][G][IM_DM];
+  float red[16][G][IM_D];
   float phq[G][IM_DM];
   float rold[G][IM_D];
-  float ke[IM_D], ve[IM_D], phe2[2][IM_DM], phe[IM_DM], bnew[IM_DM];
+  float mrg[3][G * IM_D];                         // second half's (max, denominator, numerator) in the merge
+  float ke[IM_D], ve[IM_D], phe2[8][IM_DM], phe[IM_DM], bnew[IM_DM];
   float lastv[IM_D];                              // V row of the last live slot
   float xlog[DEC_GMAX];                           // the leftover key's attention logits
   float gate[G], den[G], dot[G];
-  unsigned long long c64[4];
-  int cidx[4];
+  unsigned long long c64[16];
+  int cidx[16];
   int e_slot, e_split;
 };
 
 // copy `count` floats (count even, both sides 8-byte aligned), every load in flight before the
-// first store; handles up to 256 * 2 * NB floats per round
+// first store; one round handles DEC_TT * 2 * NB floats
 template <int NB>
 __device__ __forceinline__ void dec_stage(float* dst, const float* __restrict__ src, int count) {
   const int n2 = count >> 1;
   if (n2 <= 0) return;
-  for (int base = 0; base < n2; base += 256 * NB) {
+  for (int base = 0; base < n2; base += DEC_TT * NB) {
     float2 r[NB];
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
-      const int i = base + threadIdx.x + 256 * k;
+      const int i = base + threadIdx.x + DEC_TT * k;
       r[k] = ((const float2*)src)[min(i, n2 - 1)];   // clamped: no branch around the load
     }
 #pragma unroll
     for (int k = 0; k < NB; ++k) {
-      const int i = base + threadIdx.x + 256 * k;
+      const int i = base + threadIdx.x + DEC_TT * k;
       if (i < n2) ((float2*)dst)[i] = r[k];
     }
   }
@@ -628,31 +633,31 @@ __device__ __forceinline__ void dec_stage(float* dst, const float* __restrict__ 
 template <int G>
 __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem<G>& sm) {
   constexpr int CH = DecTailSmem<G>::CH;
+  constexpr int NS = DecTailSmem<G>::NS;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int b = u / a.H_kv, h = u % a.H_kv;
   DEC_STAMP(8);
   const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
   const float* pbase = a.part + (size_t)u * a.S_alloc * G * DEC_REC;
   // ---------------- every load is issued now: no address depends on another load ----------------
-  const int d4 = tid & 31, cg = tid >> 5;
-  float4 Mr[16];
+  const int d4 = tid & 31, rg = tid >> 5;    // this thread's patch of M: rows 4 rg .. 4 rg + 3, columns 4 d4 .. 4 d4 + 3
+  float4 Mr[4];
   float* Mu = a.M + (size_t)u * IM_DM * IM_D;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) Mr[i] = *(const float4*)(Mu + (cg * 16 + i) * IM_D + 4 * d4);
-  const int wc = tid & 127, hh = tid >> 7;
-  uint4 Wr[8];
-#pragma unroll
-  for (int i = 0; i < 8; ++i) Wr[i] = *(const uint4*)(a.Wt + wc * IM_D + hh * 64 + i * 8);
+  for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);
+  const int wc = tid & 127, hh = tid >> 7;   // W_theta row wc, dims 16 hh .. 16 hh + 15
+  const uint4 Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
+  const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
   const float b_old = (tid < IM_DM) ? a.bvec[(size_t)u * IM_DM + tid] : 0.f;
-  for (int idx = tid; idx < G * IM_D; idx += 256)
+  for (int idx = tid; idx < G * IM_D; idx += DEC_TT)
     sm.qs[idx >> 7][idx & 127] = bf2f(a.q[((size_t)b * a.H + h * G) * IM_D + idx]);
   // first round of split records (all launched splits; which are live is known once n is read
   // from record 0) and, right behind them, the last-slot record
   const int cs0 = min(CH, a.S);
   const int LS = a.S;                          // index of the last-slot record
   const bool ls_staged = LS <= CH;
-  dec_stage<18>(&sm.pst[0][0][0], pbase, cs0 * G * DEC_REC);
-  dec_stage<6>((float*)&sm.cst[0][0], (const float*)cbase, (ls_staged ? LS + 1 : cs0) * DEC_CAND);
+  dec_stage<5>(&sm.pst[0][0][0], pbase, cs0 * G * DEC_REC);
+  dec_stage<2>((float*)&sm.cst[0][0], (const float*)cbase, (ls_staged ? LS + 1 : cs0) * DEC_CAND);
   __syncthreads();
   DEC_STAMP(9);
   const int n = (int)sm.cst[0][3];
@@ -663,7 +668,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   // candidate keys of the splits beyond the first staged round (none in the usual case)
   unsigned long long best = ~0ull;
   int bidx = -1;
-  for (int sp = CH + tid; sp < n_act; sp += 256) {
+  for (int sp = CH + tid; sp < n_act; sp += DEC_TT) {
     const unsigned long long c = ((unsigned long long)cbase[(size_t)sp * DEC_CAND] << 32) | cbase[(size_t)sp * DEC_CAND + 1];
     if (c <= best) { best = c; bidx = sp; }   // later splits hold larger slots: they win full ties
   }
@@ -684,24 +689,20 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   }
   if (tid < G) sm.xlog[tid] = __uint_as_float(lsrec[4 + tid]);
   // ---------------- memory readout terms that do not depend on the eviction ----------------
-  {  // phi(q_j)[c], two threads per c (64 dims each)
-    float pq[G];
+  float wv[16];
+  unpack8(Wr0, wv);
+  unpack8(Wr1, wv + 8);
+  {  // phi(q_j)[c]: eight threads per c (16 dims each)
 #pragma unroll
-    for (int j = 0; j < G; ++j) pq[j] = 0.f;
+    for (int j = 0; j < G; ++j) {
+      float pq = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float wv[8];
-      unpack8(Wr[i], wv);
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-#pragma unroll
-        for (int j = 0; j < G; ++j) pq[j] = fmaf(wv[e], sm.qs[j][hh * 64 + i * 8 + e], pq[j]);
+      for (int e = 0; e < 16; ++e) pq = fmaf(wv[e], sm.qs[j][hh * 16 + e], pq);
+      sm.php[hh][j][wc] = pq;
     }
-#pragma unroll
-    for (int j = 0; j < G; ++j) sm.php[hh][j][wc] = pq[j];
   }
   // gate: one wave per head
-  for (int j = w; j < G; j += 4) {
+  for (int j = w; j < G; j += DEC_TT / 64) {
     float gz = bf2f(a.wg[lane]) * sm.qs[j][lane] + bf2f(a.wg[lane + 64]) * sm.qs[j][lane + 64];
     gz = wave_sum_f(gz);
     if (lane == 0) sm.gate[j] = 1.f / (1.f + __expf(-(gz + a.cg)));
@@ -729,7 +730,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       if (c <= bb) { bb = c; bi = sp; }
     }
     if (n_act > CH) {
-      for (int i = 0; i < 4; ++i) {
+      for (int i = 0; i < DEC_TT / 64; ++i) {
         const int oi = sm.cidx[i];
         if (oi >= 0 && (bi < 0 || sm.c64[i] < bb || (sm.c64[i] == bb && oi > bi))) { bb = sm.c64[i]; bi = oi; }
       }
@@ -743,9 +744,12 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     sm.e_slot = !ev ? -1 : (bi == x_split) ? n_last : (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]);
   }
   __syncthreads();
-  for (int idx = tid; idx < G * IM_DM; idx += 256) {
+  for (int idx = tid; idx < G * IM_DM; idx += DEC_TT) {
     const int j = idx >> 7, c = idx & 127;
-    sm.phq[j][c] = sm.php[0][j][c] + sm.php[1][j][c];
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += sm.php[k][j][c];
+    sm.phq[j][c] = t;
   }
   const int e_split = sm.e_split, e_slot = sm.e_slot;
   // the evicted entry's rows: in the record of its split, or in the last-slot record
@@ -757,48 +761,41 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   }
   __syncthreads();
   DEC_STAMP(10);
-  {  // r_old[j][d] = sum_c phi_q[j][c] M[c][d] over this thread's 16 rows and 4 columns
-    float ra[G][4];
+  {  // r_old[j][d] = sum_c phi_q[j][c] M[c][d] over this thread's 4 rows and 4 columns
 #pragma unroll
-    for (int j = 0; j < G; ++j) ra[j][0] = ra[j][1] = ra[j][2] = ra[j][3] = 0.f;
+    for (int j = 0; j < G; ++j) {
+      float r0 = 0.f, r1 = 0.f, r2 = 0.f, r3 = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-#pragma unroll
-      for (int j = 0; j < G; ++j) {
-        const float f = sm.phq[j][cg * 16 + i];
-        ra[j][0] = fmaf(f, Mr[i].x, ra[j][0]); ra[j][1] = fmaf(f, Mr[i].y, ra[j][1]);
-        ra[j][2] = fmaf(f, Mr[i].z, ra[j][2]); ra[j][3] = fmaf(f, Mr[i].w, ra[j][3]);
+      for (int i = 0; i < 4; ++i) {
+        const float f = sm.phq[j][rg * 4 + i];
+        r0 = fmaf(f, Mr[i].x, r0); r1 = fmaf(f, Mr[i].y, r1);
+        r2 = fmaf(f, Mr[i].z, r2); r3 = fmaf(f, Mr[i].w, r3);
       }
+      r0 = halves_sum_f(r0); r1 = halves_sum_f(r1); r2 = halves_sum_f(r2); r3 = halves_sum_f(r3);
+      if (lane < 32) *(float4*)&sm.red[w][j][4 * d4] = make_float4(r0, r1, r2, r3);
     }
-#pragma unroll
-    for (int j = 0; j < G; ++j)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float x = halves_sum_f(ra[j][e]);
-        if (lane < 32) sm.red[w][j][4 * d4 + e] = x;
-      }
   }
   // ---------------- memory write (rank one) ----------------
   if (e_slot >= 0) {
     float pe = 0.f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      float wv[8];
-      unpack8(Wr[i], wv);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) pe = fmaf(wv[e], sm.ke[hh * 64 + i * 8 + e], pe);
-    }
+    for (int e = 0; e < 16; ++e) pe = fmaf(wv[e], sm.ke[hh * 16 + e], pe);
     sm.phe2[hh][wc] = pe;
   }
   __syncthreads();
-  for (int idx = tid; idx < G * IM_D; idx += 256) {
+  for (int idx = tid; idx < G * IM_D; idx += DEC_TT) {
     const int j = idx >> 7, d = idx & 127;
-    sm.rold[j][d] = sm.red[0][j][d] + sm.red[1][j][d] + sm.red[2][j][d] + sm.red[3][j][d];
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) t += sm.red[k][j][d];
+    sm.rold[j][d] = t;
   }
   if (tid < IM_DM) {
     float bn = b_old;
     if (e_slot >= 0) {
-      const float pe = sm.phe2[0][tid] + sm.phe2[1][tid];
+      float pe = 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) pe += sm.phe2[k][tid];
       sm.phe[tid] = pe;
       bn = fmaf(a.lambda, b_old, a.eta * pe * pe);
       a.bvec[(size_t)u * IM_DM + tid] = bn;
@@ -808,19 +805,18 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   __syncthreads();
   DEC_STAMP(11);
   if (e_slot >= 0) {
-    // M <- lambda M + eta phi_e v_e^T for this thread's 16 x 4 patch
+    // M <- lambda M + eta phi_e v_e^T for this thread's 4 x 4 patch
+    const float4 vv = *(const float4*)&sm.ve[4 * d4];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const float f = a.eta * sm.phe[cg * 16 + i];
+    for (int i = 0; i < 4; ++i) {
+      const float f = a.eta * sm.phe[rg * 4 + i];
       float4 m = Mr[i];
-      m.x = fmaf(a.lambda, m.x, f * sm.ve[4 * d4 + 0]); m.y = fmaf(a.lambda, m.y, f * sm.ve[4 * d4 + 1]);
-      m.z = fmaf(a.lambda, m.z, f * sm.ve[4 * d4 + 2]); m.w = fmaf(a.lambda, m.w, f * sm.ve[4 * d4 + 3]);
-#ifndef DEC_EXP_NO_MSTORE
-      *(float4*)(Mu + (cg * 16 + i) * IM_D + 4 * d4) = m;
-#endif
+      m.x = fmaf(a.lambda, m.x, f * vv.x); m.y = fmaf(a.lambda, m.y, f * vv.y);
+      m.z = fmaf(a.lambda, m.z, f * vv.z); m.w = fmaf(a.lambda, m.w, f * vv.w);
+      *(float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4) = m;
     }
   }
-  for (int j = w; j < G; j += 4) {
+  for (int j = w; j < G; j += DEC_TT / 64) {
     float dn = sm.phq[j][lane] * sm.phq[j][lane] * sm.bnew[lane] +
                sm.phq[j][lane + 64] * sm.phq[j][lane + 64] * sm.bnew[lane + 64];
     dn = wave_sum_f(dn);
@@ -828,84 +824,83 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     if (e_slot >= 0) dt = wave_sum_f(sm.phq[j][lane] * sm.phe[lane] + sm.phq[j][lane + 64] * sm.phe[lane + 64]);
     if (lane == 0) { sm.den[j] = dn + a.mem_eps; sm.dot[j] = dt; }
   }
-  __syncthreads();
   DEC_STAMP(12);
   // ---------------- merge the attention partials, add back the candidates that stay ----------------
-  constexpr int NP = (G * IM_D + 255) / 256;   // outputs per thread
-  float rm[NP], rl[NP], ro[NP];
-#pragma unroll
-  for (int k = 0; k < NP; ++k) { rm[k] = -1e30f; rl[k] = 0.f; ro[k] = 0.f; }
-#ifdef DEC_EXP_NO_MERGE
-  for (int c0 = 0; c0 < 0; c0 += CH) {
-#else
+  // NS threads share one output (head j, dim d): each takes CH / NS of the staged splits
+  constexpr int NO = G * IM_D;                    // outputs
+  constexpr int PER = CH / NS;                    // splits per thread and round
+  const int oidx = (NS == 2) ? (tid & 511) : tid;
+  const int part = (NS == 2) ? (tid >> 9) : 0;
+  const bool act = oidx < NO;
+  const int j = act ? (oidx >> 7) : 0, d = oidx & 127;
+  float rm = -1e30f, rl = 0.f, ro = 0.f;
   for (int c0 = 0; c0 < n_act; c0 += CH) {
-#endif
     const int cn = min(CH, n_act - c0);
     if (c0 > 0) {
       __syncthreads();
-      dec_stage<18>(&sm.pst[0][0][0], pbase + (size_t)c0 * G * DEC_REC, cn * G * DEC_REC);
-      dec_stage<6>((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
+      dec_stage<5>(&sm.pst[0][0][0], pbase + (size_t)c0 * G * DEC_REC, cn * G * DEC_REC);
+      dec_stage<2>((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
       __syncthreads();
     }
+    // unconditional LDS reads (slots past cn hold stale words), then selects: no branches
+    float pm[PER], plv[PER], po[PER], cl[PER], cv[PER];
 #pragma unroll
-    for (int k = 0; k < NP; ++k) {
-      const int idx = tid + 256 * k;
-      if (idx < G * IM_D) {
-        const int j = idx >> 7, d = idx & 127;
-        // every LDS read of this round first (fixed trip count), then the arithmetic
-        float pm[CH], plv[CH], po[CH], cl[CH], cv[CH];
-#pragma unroll
-        for (int sp = 0; sp < CH; ++sp) {
-          // unconditional LDS reads (slots past cn hold stale words), then selects: no branches
-          const float r0 = sm.pst[sp][j][0], r1 = sm.pst[sp][j][1], r2 = sm.pst[sp][j][2 + d];
-          const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
-          const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
-          const bool on = sp < cn;
-          const bool stays = on && (c0 + sp != e_split);
-          pm[sp] = on ? r0 : -1e30f;
-          plv[sp] = on ? r1 : 0.f;
-          po[sp] = on ? r2 : 0.f;
-          cl[sp] = stays ? r3 : -INFINITY;
-          cv[sp] = stays ? r4 : 0.f;
-        }
-        float m = rm[k];
-#pragma unroll
-        for (int sp = 0; sp < CH; ++sp) m = fmaxf(m, fmaxf(pm[sp], cl[sp]));
-        const float resc = __expf(rm[k] - m);
-        float o = ro[k] * resc, l = rl[k] * resc;
-#pragma unroll
-        for (int sp = 0; sp < CH; ++sp) {
-          const float sc = __expf(pm[sp] - m);
-          o = fmaf(sc, po[sp], o);
-          l = fmaf(sc, plv[sp], l);
-          const float pc = __expf(cl[sp] - m);   // exp(-inf) = 0 for the evicted / absent candidate
-          o = fmaf(pc, cv[sp], o);
-          l += pc;
-        }
-        rm[k] = m; rl[k] = l; ro[k] = o;
-      }
+    for (int k = 0; k < PER; ++k) {
+      const int sp = part * PER + k;
+      const float r0 = sm.pst[sp][j][0], r1 = sm.pst[sp][j][1], r2 = sm.pst[sp][j][2 + d];
+      const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
+      const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
+      const bool on = sp < cn;
+      const bool stays = on && (c0 + sp != e_split);
+      pm[k] = on ? r0 : -1e30f;
+      plv[k] = on ? r1 : 0.f;
+      po[k] = on ? r2 : 0.f;
+      cl[k] = stays ? r3 : -INFINITY;
+      cv[k] = stays ? r4 : 0.f;
     }
+    float m = rm;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) m = fmaxf(m, fmaxf(pm[k], cl[k]));
+    const float resc = __expf(rm - m);
+    float o = ro * resc, l = rl * resc;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const float sc = __expf(pm[k] - m);
+      o = fmaf(sc, po[k], o);
+      l = fmaf(sc, plv[k], l);
+      const float pc = __expf(cl[k] - m);   // exp(-inf) = 0 for the evicted / absent candidate
+      o = fmaf(pc, cv[k], o);
+      l += pc;
+    }
+    rm = m; rl = l; ro = o;
   }
-#pragma unroll
-  for (int k = 0; k < NP; ++k) {
-    const int idx = tid + 256 * k;
-    if (idx < G * IM_D) {
-      const int j = idx >> 7, d = idx & 127;
-      float m = rm[k], o = ro[k], l = rl[k];
-      if (has_x && e_split != x_split) {   // the leftover key stays
-        const float mn = fmaxf(m, sm.xlog[j]);
-        const float resc = __expf(m - mn), pc = __expf(sm.xlog[j] - mn);
-        o = fmaf(pc, sm.lastv[d], o * resc);
-        l = fmaf(l, resc, pc);
-      }
-      const float o_attn = (l > 0.f) ? o / l : 0.f;
-      float mr = sm.rold[j][d];
-      if (e_slot >= 0) mr = fmaf(a.lambda, mr, a.eta * sm.dot[j] * sm.ve[d]);
-      const float res = sm.gate[j] * (mr / sm.den[j]);
-      const size_t oi = ((size_t)b * a.H + h * G + j) * IM_D + d;
-      a.out[oi] = f2bf_rne(o_attn + res);
-      if (a.readout) a.readout[oi] = res;
+  if (NS == 2) {
+    if (part == 1 && act) { sm.mrg[0][oidx] = rm; sm.mrg[1][oidx] = rl; sm.mrg[2][oidx] = ro; }
+  }
+  __syncthreads();   // also orders den / dot / rold before their use below
+  if (part == 0 && act) {
+    float m = rm, o = ro, l = rl;
+    if (NS == 2) {
+      const float m2 = sm.mrg[0][oidx];
+      const float mn = fmaxf(m, m2);
+      const float s1 = __expf(m - mn), s2 = __expf(m2 - mn);
+      o = fmaf(o, s1, s2 * sm.mrg[2][oidx]);
+      l = fmaf(l, s1, s2 * sm.mrg[1][oidx]);
+      m = mn;
     }
+    if (has_x && e_split != x_split) {   // the leftover key stays
+      const float mn = fmaxf(m, sm.xlog[j]);
+      const float resc = __expf(m - mn), pc = __expf(sm.xlog[j] - mn);
+      o = fmaf(pc, sm.lastv[d], o * resc);
+      l = fmaf(l, resc, pc);
+    }
+    const float o_attn = (l > 0.f) ? o / l : 0.f;
+    float mr = sm.rold[j][d];
+    if (e_slot >= 0) mr = fmaf(a.lambda, mr, a.eta * sm.dot[j] * sm.ve[d]);
+    const float res = sm.gate[j] * (mr / sm.den[j]);
+    const size_t oi = ((size_t)b * a.H + h * G + j) * IM_D + d;
+    a.out[oi] = f2bf_rne(o_attn + res);
+    if (a.readout) a.readout[oi] = res;
   }
   DEC_STAMP(13);
   // ---------------- fill the hole with the last entry, publish the new length ----------------
@@ -935,7 +930,7 @@ __global__ __launch_bounds__(256, 2) void k_dec_main(const DecArgs a, const doub
 
 // grid: units
 template <int G>
-__global__ __launch_bounds__(256) void k_dec_tail(const DecArgs a) {
+__global__ __launch_bounds__(DEC_TT) void k_dec_tail(const DecArgs a) {
   __shared__ __attribute__((aligned(16))) DecTailSmem<G> sm;
   dec_tail<G>(a, blockIdx.x, sm);
 }

@@ -415,7 +415,7 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
   case g:                                                           \
     k_dec_main<g><<<main_blocks, 256, 0, s>>>(a, a.qy, a.alpha);    \
     if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n + 1], s); \
-    k_dec_tail<g><<<units, 256, 0, s>>>(a);                         \
+    k_dec_tail<g><<<units, DEC_TT, 0, s>>>(a);                      \
     break;
   switch (G) {
     IM_DEC_CASE(1) IM_DEC_CASE(2) IM_DEC_CASE(3) IM_DEC_CASE(4)
