@@ -80,61 +80,69 @@ __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
 // Blocks [nU, nU + nG): two rows of G.
 // Blocks after: one per unit, append + indexer key of the new token.
 // --------------------------------------------------------------------------------------------
-__device__ void dec_gemv2(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Bm, int n0, int N,
-                          int M, int Kd, double (*part)[256], double* out_rows /* [M][2] in LDS */) {
+// out_rows[m][r] = sum_k A[m][k] Bm[n0 + r][k] for r = 0, 1 and every batch row m (bf16 inputs, fp64
+// accumulation).  Each round issues the loads of two 2048-wide slabs before any arithmetic.
+template <int MB>
+__device__ __forceinline__ void dec_gemv2(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Bm, int n0,
+                                          int N, int M, int Kd, double (*part)[16], double* out_rows) {
   const int tid = threadIdx.x;
-  for (int mb = 0; mb < M; mb += 8) {
-    double acc[8][2];
+  const int r1 = (n0 + 1 < N) ? n0 + 1 : n0;   // an absent second row repeats the first (result unused)
+  for (int mb = 0; mb < M; mb += MB) {
+    double acc[MB][2];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i][0] = acc[i][1] = 0.0;
-    for (int k = tid * 8; k < Kd; k += 256 * 8) {
-      float bv[2][8];
+    for (int i = 0; i < MB; ++i) acc[i][0] = acc[i][1] = 0.0;
+    for (int k0 = tid * 8; k0 < Kd; k0 += 2 * 2048) {
+      uint4 bu[2][2], au[2][MB];
 #pragma unroll
-      for (int r = 0; r < 2; ++r) {
-        uint4 u = make_uint4(0, 0, 0, 0);
-        if (n0 + r < N) u = *(const uint4*)(Bm + (size_t)(n0 + r) * Kd + k);
-        unpack8(u, bv[r]);
+      for (int it = 0; it < 2; ++it) {
+        const int k = (k0 + it * 2048 < Kd) ? k0 + it * 2048 : k0;
+        bu[it][0] = *(const uint4*)(Bm + (size_t)n0 * Kd + k);
+        bu[it][1] = *(const uint4*)(Bm + (size_t)r1 * Kd + k);
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+          const int m = (mb + i < M) ? mb + i : M - 1;
+          au[it][i] = *(const uint4*)(A + (size_t)m * Kd + k);
+        }
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (mb + i < M) {
-          const uint4 u = *(const uint4*)(A + (size_t)(mb + i) * Kd + k);
-          float av[8];
-          unpack8(u, av);
+      for (int it = 0; it < 2; ++it) {
+        if (k0 + it * 2048 < Kd) {
+          float b0[8], b1[8];
+          unpack8(bu[it][0], b0);
+          unpack8(bu[it][1], b1);
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            acc[i][0] = fma((double)av[e], (double)bv[0][e], acc[i][0]);
-            acc[i][1] = fma((double)av[e], (double)bv[1][e], acc[i][1]);
+          for (int i = 0; i < MB; ++i) {
+            float av[8];
+            unpack8(au[it][i], av);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              acc[i][0] = fma((double)av[e], (double)b0[e], acc[i][0]);
+              acc[i][1] = fma((double)av[e], (double)b1[e], acc[i][1]);
+            }
           }
         }
       }
     }
-    // block-wide sums through LDS (cross-lane shuffles of doubles are slow here): 16 values x 256
-    // partial sums, added in two levels of 16
-    __syncthreads();
+    // wave sums on the DPP path, then the 4 waves meet in LDS
 #pragma unroll
-    for (int i = 0; i < 8; ++i) { part[2 * i][tid] = acc[i][0]; part[2 * i + 1][tid] = acc[i][1]; }
-    __syncthreads();
-    {
-      const int v = tid >> 4, q4 = tid & 15;   // 16 values x 16 threads each
-      double sacc = 0.0;
-#pragma unroll
-      for (int t = 0; t < 16; ++t) sacc += part[v][q4 * 16 + t];
-      part[v][q4 * 16] = sacc;
+    for (int i = 0; i < MB; ++i) {
+      acc[i][0] = wave_sum_d(acc[i][0]);
+      acc[i][1] = wave_sum_d(acc[i][1]);
     }
     __syncthreads();
-    if (tid < 16 && mb + (tid >> 1) < M) {
-      double tot = 0.0;
+    if ((tid & 63) == 0) {
 #pragma unroll
-      for (int t = 0; t < 16; ++t) tot += part[tid][t * 16];
-      out_rows[(mb + (tid >> 1)) * 2 + (tid & 1)] = tot;
+      for (int i = 0; i < MB; ++i) { part[tid >> 6][2 * i] = acc[i][0]; part[tid >> 6][2 * i + 1] = acc[i][1]; }
     }
+    __syncthreads();
+    if (tid < 2 * MB && mb + (tid >> 1) < M)
+      out_rows[(mb + (tid >> 1)) * 2 + (tid & 1)] = part[0][tid] + part[1][tid] + part[2][tid] + part[3][tid];
   }
   __syncthreads();
 }
 
 __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
-  __shared__ double part[16][256];
+  __shared__ double part[4][16];
   __shared__ double rows[64 * 2];   // up to 64 batch rows x 2 outputs
   __shared__ float s_k[IM_D];
   __shared__ double s_u[IM_DI];
@@ -144,14 +152,16 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   const int blk = blockIdx.x;
   if (blk < nU) {
     const int n0 = blk * 2;
-    dec_gemv2(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
+    if (a.B <= 4) dec_gemv2<4>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
+    else dec_gemv2<8>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
     // raw projections; the consumer applies the QK-Norm (it needs a whole head, this block has 2 rows)
     for (int i = tid; i < a.B * 2; i += 256) a.qy[(size_t)(i >> 1) * Nq + n0 + (i & 1)] = rows[i];
     return;
   }
   if (blk < nU + nG) {
     const int n0 = (blk - nU) * 2;
-    dec_gemv2(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
+    if (a.B <= 4) dec_gemv2<4>(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
+    else dec_gemv2<8>(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
     for (int i = tid; i < a.B * 2; i += 256) {
       const int r = n0 + (i & 1);
       if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = rows[i];   // raw G x; scaled by the consumer
@@ -162,11 +172,21 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   const int u = blk - nU - nG;
   const int b = u / a.H_kv;
   const int n_old = a.len[u];
+  // loads that do not depend on the length go out together with it
+  uint4 ukr[4], newrow = make_uint4(0, 0, 0, 0);
+  {
+    const uint4* ur = (const uint4*)(a.Uk + (tid >> 2) * IM_D + (tid & 3) * 32);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ukr[i] = ur[i];
+    if (tid < 16) newrow = *(const uint4*)(a.k_new + (size_t)u * IM_D + tid * 8);
+    else if (tid < 32) newrow = *(const uint4*)(a.v_new + (size_t)u * IM_D + (tid - 16) * 8);
+  }
+  const int newpos = a.pos_new[b];
   if (a.n_recent > 0) {  // newest position of the unit (new token included) for the recent window
     int m = INT_MIN;
     const int nn = min(n_old, a.max_live);
     for (int i = tid; i < nn; i += 256) m = max(m, a.pos[(size_t)u * a.C + i]);
-    if (n_old + 1 <= a.C) m = max(m, a.pos_new[b]);
+    if (n_old + 1 <= a.C) m = max(m, newpos);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = max(m, __shfl_xor(m, o, 64));
     __shared__ int s_mp[4];
@@ -181,27 +201,24 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   if (n_old + 1 > a.max_live && tid == 0) atomicOr(a.status, IM_STATUS_LIVE_EXCEEDED_BIT);
   const size_t slot = (size_t)u * a.C + n_old;
   if (tid < 16) {
-    const uint4 kk = *(const uint4*)(a.k_new + (size_t)u * IM_D + tid * 8);
-    *(uint4*)(a.K + slot * IM_D + tid * 8) = kk;
+    *(uint4*)(a.K + slot * IM_D + tid * 8) = newrow;
     float f[8];
-    unpack8(kk, f);
+    unpack8(newrow, f);
 #pragma unroll
     for (int e = 0; e < 8; ++e) s_k[tid * 8 + e] = f[e];
   } else if (tid < 32) {
-    const int t = tid - 16;
-    *(uint4*)(a.V + slot * IM_D + t * 8) = *(const uint4*)(a.v_new + (size_t)u * IM_D + t * 8);
+    *(uint4*)(a.V + slot * IM_D + (tid - 16) * 8) = newrow;
   } else if (tid == 32) {
-    a.pos[slot] = a.pos_new[b];
+    a.pos[slot] = newpos;
   }
   __syncthreads();
   {  // u_c = Uk[c] . k : thread (c = tid/4, quarter = tid%4)
     const int c = tid >> 2, qd = tid & 3;
-    const uint4* ur = (const uint4*)(a.Uk + c * IM_D + qd * 32);
     double acc = 0.0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       float f[8];
-      unpack8(ur[i], f);
+      unpack8(ukr[i], f);
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc = fma((double)f[e], (double)s_k[qd * 32 + i * 8 + e], acc);
     }
