@@ -60,7 +60,8 @@ typedef struct im_config {
   int32_t gate_in_dim;  /* width of the gate input X_s (multiple of 16)                       */
   int32_t n_sink;       /* first token positions always kept (4 in the paper, Section 4)      */
   int32_t n_recent;     /* newest positions always kept (0: none)                             */
-  int32_t fold_block;   /* evicted rows are folded into the memory in blocks of this (64)     */
+  int32_t fold_block;   /* evicted rows are folded into the memory in blocks of this (64;
+                           a multiple of 32)                                                   */
   int32_t max_queries;  /* largest n_q a call to im_index_score will pass                     */
   float rms_eps;        /* RMSNorm epsilon of the indexer's QK-Norm                           */
   float mem_eps;        /* epsilon of the readout denominator (Eq. latent_readout)            */

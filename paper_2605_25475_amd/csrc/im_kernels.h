@@ -466,17 +466,25 @@ __global__ __launch_bounds__(1024) void k_select(const float* __restrict__ score
 }
 
 // ------------------------------------------------------------------------------------------
-// a3: latent-memory write.  Partial sums over a split of the evicted rows, then the decayed
-// update.  fp32 (inputs bf16: products exact, fp32 accumulation).
+// a3: latent-memory write.  Partial sums over a split of the evicted rows on the matrix cores,
+// then the decayed update (deterministic: splits are added in order).
 // ------------------------------------------------------------------------------------------
-#define IM_MEM_TOK 16  // rows staged per inner iteration (a sub-tile of the fold block)
+#define IM_MEM_TOK 32  // evicted rows per MFMA tile (a sub-tile of the fold block)
+
+typedef short im_v4s __attribute__((ext_vector_type(4)));
+typedef float im_v16f __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ int im_mem_blocks_per_split(int ne, int fold_block, int n_split) {
   const int blocks = (ne + fold_block - 1) / fold_block;
   return (blocks + n_split - 1) / n_split;
 }
 
-// grid (n_split, units).  Thread t owns M[c][d] for c = (t/16)*8 .. +7, d = t%16 + 16 m.
+// grid (n_split, units), 4 waves.  Two chained bf16 MFMA products per tile of 32 evicted rows:
+//   Phi^T[c][i] = sum_d W[c][d] K_i[d]            (wave w owns memory rows c = 32 w .. 32 w + 31)
+//   M[c][d]    += sum_i Phi[i][c] V_i[d]          (Phi split into hi + lo bf16 parts, so the
+//                                                  product carries 16 mantissa bits of Phi)
+// 32x32x8 operand layout: lane l supplies row / column l % 32 and k = 4 (l / 32) .. + 3; result
+// register r of lane l is row 8 (r / 4) + 4 (l / 32) + r % 4, column l % 32.
 __global__ __launch_bounds__(256) void k_mem_partial(const bf16_t* __restrict__ K,
                                                      const bf16_t* __restrict__ V,
                                                      const int32_t* __restrict__ evict_idx,
@@ -484,10 +492,8 @@ __global__ __launch_bounds__(256) void k_mem_partial(const bf16_t* __restrict__ 
                                                      const bf16_t* __restrict__ Wtheta, int C,
                                                      int fold_block, int n_split,
                                                      float* __restrict__ part) {
-  __shared__ __attribute__((aligned(16))) bf16_t Ws[IM_DM * IM_D];  // swizzled: word (d/2) ^ (c & 31)
-  __shared__ __attribute__((aligned(16))) bf16_t Ks[IM_MEM_TOK][IM_D + 2];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[IM_MEM_TOK][IM_D];
-  __shared__ float Ps[IM_MEM_TOK][IM_DM];
+  __shared__ float Ps[IM_DM][IM_MEM_TOK + 1];                                  // Phi^T [c][row]
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[IM_MEM_TOK][IM_D + 8];     // V rows of the tile
   const int unit = blockIdx.y, split = blockIdx.x, tid = threadIdx.x;
   const int ne = n_evict[unit];
   if (ne <= 0) return;
@@ -495,78 +501,90 @@ __global__ __launch_bounds__(256) void k_mem_partial(const bf16_t* __restrict__ 
   const int i0 = split * bps * fold_block;
   const int i1 = min(ne, i0 + bps * fold_block);
   if (i0 >= i1) return;
-  for (int i = tid; i < IM_DM * 16; i += 256) {
-    const int c = i >> 4, ch = i & 15;
-    const uint4 u = *(const uint4*)(Wtheta + c * IM_D + ch * 8);
-    uint32_t* row = (uint32_t*)(Ws + c * IM_D);
-    row[(ch * 4 + 0) ^ (c & 31)] = u.x; row[(ch * 4 + 1) ^ (c & 31)] = u.y;
-    row[(ch * 4 + 2) ^ (c & 31)] = u.z; row[(ch * 4 + 3) ^ (c & 31)] = u.w;
-  }
-  const int tr = tid >> 4, tcn = tid & 15;
-  float macc[8][8];
+  const int w = tid >> 6, lane = tid & 63, l32 = lane & 31, kh = lane >> 5;
+  // W rows of this wave as the A operand of the first product: k-step ks covers dims 8 ks .. 8 ks + 7
+  im_v4s wa[16];
 #pragma unroll
-  for (int a = 0; a < 8; ++a)
+  for (int ks = 0; ks < 16; ++ks)
+    wa[ks] = *(const im_v4s*)(Wtheta + (32 * w + l32) * IM_D + 8 * ks + 4 * kh);
+  im_v16f macc[4];
 #pragma unroll
-    for (int m = 0; m < 8; ++m) macc[a][m] = 0.f;
-  float bacc = 0.f;
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) macc[db][r] = 0.f;
+  float bsum[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) bsum[r] = 0.f;
   const int32_t* ev = evict_idx + (size_t)unit * C;
   for (int t0 = i0; t0 < i1; t0 += IM_MEM_TOK) {
+    // B operand of the first product: K^T, this lane's evicted row t0 + l32 (zero past the end)
+    const int tt = t0 + l32;
+    const bool live = tt < i1;
+    const size_t krow = ((size_t)unit * C + (live ? ev[tt] : ev[i1 - 1])) * IM_D;
+    im_v4s kb[16];
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) {
+      kb[ks] = *(const im_v4s*)(K + krow + 8 * ks + 4 * kh);
+      if (!live) kb[ks] = im_v4s{0, 0, 0, 0};
+    }
+    __syncthreads();   // the previous tile's LDS reads are done
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {   // stage the V rows: 32 rows x 16 chunks of 16 bytes
+      const int ch = tid + 256 * i, r = ch >> 4, c16 = ch & 15;
+      const bool lv = t0 + r < i1;
+      uint4 vv = *(const uint4*)(V + ((size_t)unit * C + ev[lv ? t0 + r : i1 - 1]) * IM_D + c16 * 8);
+      if (!lv) vv = make_uint4(0, 0, 0, 0);
+      *(uint4*)&Vs[r][c16 * 8] = vv;
+    }
+    im_v16f ph;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ph[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) ph = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(wa[ks], kb[ks], ph, 0, 0, 0);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      Ps[32 * w + 8 * (r >> 2) + 4 * kh + (r & 3)][l32] = ph[r];
+      bsum[r] = fmaf(ph[r], ph[r], bsum[r]);
+    }
     __syncthreads();
-    {  // stage 16 evicted rows of K and V (zero rows past the end): one 16-byte chunk per thread
-      const int r = tid >> 4, ch = tid & 15;
-      uint4 kk = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if (t0 + r < i1) {
-        const size_t row = (size_t)unit * C + ev[t0 + r];
-        kk = *(const uint4*)(K + row * IM_D + ch * 8);
-        vv = *(const uint4*)(V + row * IM_D + ch * 8);
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt) {   // k-step kt covers rows 8 kt .. 8 kt + 7 of the tile
+      im_v4s ah, al;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float p = Ps[32 * w + l32][8 * kt + 4 * kh + e];
+        const bf16_t hi = f2bf_rne(p);
+        const bf16_t lo = f2bf_rne(p - bf2f(hi));
+        ah[e] = (short)hi;
+        al[e] = (short)lo;
       }
-      uint32_t* kd = (uint32_t*)&Ks[r][ch * 8];
-      kd[0] = kk.x; kd[1] = kk.y; kd[2] = kk.z; kd[3] = kk.w;
-      *(uint4*)&Vs[r][ch * 8] = vv;
-    }
-    __syncthreads();
-    {  // Phi[token tr][c = tcn + 16 m]
-      float p[8];
 #pragma unroll
-      for (int m = 0; m < 8; ++m) p[m] = 0.f;
-      for (int d2 = 0; d2 < IM_D / 2; ++d2) {
-        const uint32_t kw = *(const uint32_t*)&Ks[tr][d2 * 2];
-        const float k0 = bf_lo(kw), k1 = bf_hi(kw);
+      for (int db = 0; db < 4; ++db) {
+        im_v4s vb;
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
-          const int c = tcn + 16 * m;
-          const uint32_t ww = ((const uint32_t*)(Ws + c * IM_D))[d2 ^ (c & 31)];
-          p[m] = fmaf(k0, bf_lo(ww), p[m]);
-          p[m] = fmaf(k1, bf_hi(ww), p[m]);
-        }
+        for (int e = 0; e < 4; ++e) vb[e] = (short)Vs[8 * kt + 4 * kh + e][32 * db + l32];
+        macc[db] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ah, vb, macc[db], 0, 0, 0);
+        macc[db] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(al, vb, macc[db], 0, 0, 0);
       }
-#pragma unroll
-      for (int m = 0; m < 8; ++m) Ps[tr][tcn + 16 * m] = p[m];
-    }
-    __syncthreads();
-    if (tid < IM_DM) {
-#pragma unroll
-      for (int i = 0; i < IM_MEM_TOK; ++i) bacc = fmaf(Ps[i][tid], Ps[i][tid], bacc);
-    }
-#pragma unroll 4
-    for (int i = 0; i < IM_MEM_TOK; ++i) {
-      float ph[8], vv[8];
-#pragma unroll
-      for (int a = 0; a < 8; ++a) ph[a] = Ps[i][tr * 8 + a];
-#pragma unroll
-      for (int m = 0; m < 8; ++m) vv[m] = bf2f(Vs[i][tcn + 16 * m]);
-#pragma unroll
-      for (int a = 0; a < 8; ++a)
-#pragma unroll
-        for (int m = 0; m < 8; ++m) macc[a][m] = fmaf(ph[a], vv[m], macc[a][m]);
     }
   }
   float* out = part + ((size_t)unit * n_split + split) * (IM_DM * IM_D + IM_DM);
 #pragma unroll
-  for (int a = 0; a < 8; ++a)
+  for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int m = 0; m < 8; ++m) out[(tr * 8 + a) * IM_D + tcn + 16 * m] = macc[a][m];
-  if (tid < IM_DM) out[IM_DM * IM_D + tid] = bacc;
+    for (int r = 0; r < 16; ++r)
+      out[(32 * w + 8 * (r >> 2) + 4 * kh + (r & 3)) * IM_D + 32 * db + l32] = macc[db][r];
+  // sum_i Phi[i][c]^2: every lane holds the partial of its row position; add the 32 positions
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 16; ++r) Ps[32 * w + 8 * (r >> 2) + 4 * kh + (r & 3)][l32] = bsum[r];
+  __syncthreads();
+  if (tid < IM_DM) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < IM_MEM_TOK; ++i) t += Ps[tid][i];
+    out[IM_DM * IM_D + tid] = t;
+  }
 }
 
 // grid (ceil((DM*D + DM)/256), units)

@@ -52,7 +52,7 @@ const char* config_problem(const im_config* c, int* code) {
   if (c->gate_in_dim < 16 || c->gate_in_dim % 16 != 0) return "gate_in_dim must be a positive multiple of 16";
   if (c->n_sink < 0 || c->n_recent < 0) return "n_sink and n_recent must be >= 0";
   if ((long long)c->n_sink + c->n_recent > c->capacity) return "n_sink + n_recent exceeds capacity";
-  if (c->fold_block < 16 || c->fold_block % 16 != 0) return "fold_block must be a positive multiple of 16";
+  if (c->fold_block < 32 || c->fold_block % 32 != 0) return "fold_block must be a positive multiple of 32";
   if (c->max_queries < 1) return "max_queries must be >= 1";
   if (!(c->rms_eps >= 0.f) || !(c->mem_eps > 0.f) || !(c->softmax_scale > 0.f))
     return "rms_eps >= 0, mem_eps > 0 and softmax_scale > 0 are required";

@@ -38,7 +38,7 @@ def test_workspace_bytes_and_config_validation(lib):
     bigger = good_cfg(max_queries=64).c_struct()
     assert lib.im_workspace_bytes(C.byref(bigger)) > n
     bad = [dict(batch=0), dict(n_q_heads=30), dict(capacity=0), dict(n_idx_heads=0), dict(n_idx_heads=17),
-           dict(gate_in_dim=100), dict(n_sink=-1), dict(fold_block=8), dict(max_queries=0),
+           dict(gate_in_dim=100), dict(n_sink=-1), dict(fold_block=16), dict(max_queries=0),
            dict(mem_eps=0.0), dict(n_sink=600)]
     for kw in bad:
         cc = good_cfg(**kw).c_struct()
