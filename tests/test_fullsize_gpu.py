@@ -3,7 +3,9 @@ heads, a 16384-token prompt evicted to 2048, then decode through im_decode_step 
 bound the benchmark sets).  The GPU runs every unit of one layer; the oracle follows a sample of
 units (they are independent) through the same events and every observable of those units is
 compared to the usual bars.  Configuration 4's head shape (7 query heads per KV head, 7 indexer
-heads) gets the same treatment at a reduced batch."""
+heads) gets the same treatment at a reduced batch; configuration 2 (batch 8, 4096 -> 1024) and
+configuration 5 (one sequence of 131072 tokens in 32 chunks of 4096, running cache evicted to
+4096 after every chunk) run one layer at their stated sizes."""
 import pytest
 
 from parity import LockStep
@@ -21,4 +23,17 @@ def test_cfg3_full_size_sampled_units():
 def test_cfg4_shape_full_context_sampled_units():
     w = WORKLOADS["cfg4"].scaled(n_layers=1, batch=4, decode_steps=4)
     ls = LockStep(w, gen_device="cuda", batch_ids=[2], kv_heads=[0, 3])
+    ls.run_schedule(fused_decode=True)
+
+
+def test_cfg2_full_size_sampled_units():
+    w = WORKLOADS["cfg2"].scaled(n_layers=1, decode_steps=6)
+    ls = LockStep(w, gen_device="cuda", batch_ids=[0, 5], kv_heads=[1, 6])
+    ls.run_schedule(fused_decode=True)
+
+
+def test_cfg5_full_size_chunked_prefill_sampled_unit():
+    # 31 chunk evictions of 4096 out of 8192 live entries, then decode at 4097 live entries
+    w = WORKLOADS["cfg5"].scaled(n_layers=1, decode_steps=4)
+    ls = LockStep(w, gen_device="cuda", kv_heads=[3])
     ls.run_schedule(fused_decode=True)
