@@ -35,10 +35,11 @@
 #ifdef IM_DEC_TRACE
 extern "C" __device__ unsigned long long im_trace_buf[2048 * 16];
 __device__ unsigned long long im_trace_buf[2048 * 16];
-#define DEC_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x < 2048) im_trace_buf[blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
+#define DEC_STAMP_AT(slot, thread) do { if (threadIdx.x == (thread) && blockIdx.x < 2048) im_trace_buf[blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
 #else
-#define DEC_STAMP(slot) do { } while (0)
+#define DEC_STAMP_AT(slot, thread) do { } while (0)
 #endif
+#define DEC_STAMP(slot) DEC_STAMP_AT(slot, 0)
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -65,6 +66,7 @@ struct DecArgs {
   int32_t *status, *maxpos;
   float* part;
   uint32_t* cand;
+  float* qm;          // per unit: the eviction-independent terms of the memory readout (DEC_QM floats per head)
   // scalars
   int B, H, H_kv, C, H_idx, gate_in, n_sink, n_recent, budget, S, S_alloc, max_live;
   float rms_eps, mem_eps, scale, lambda, eta;
@@ -76,9 +78,10 @@ __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
 }
 
 // --------------------------------------------------------------------------------------------
-// k_dec_prep.  Blocks [0, nU): two rows of U_q each, all batch rows (raw projections, fp64).
+// k_dec_prep.  Block roles, in the order of `blk` below.  Blocks [0, nU): two rows of U_q each, all batch rows (raw projections, fp64).
 // Blocks [nU, nU + nG): two rows of G.
-// Blocks after: one per unit, append + indexer key of the new token.
+// Blocks after: one per unit, append + indexer key of the new token; then DEC_MP more per unit, the
+// eviction-independent terms of the memory readout.
 // --------------------------------------------------------------------------------------------
 // out_rows[m][r] = sum_k A[m][k] Bm[n0 + r][k] for r = 0, 1 and every batch row m (bf16 inputs, fp64
 // accumulation).  Each round issues the loads of two 2048-wide slabs before any arithmetic.
@@ -141,6 +144,83 @@ __device__ __forceinline__ void dec_gemv2(const bf16_t* __restrict__ A, const bf
   __syncthreads();
 }
 
+#define DEC_MP 4                        // workgroups sharing the memory-readout terms of one unit
+#define DEC_QM (IM_DM + DEC_MP * IM_D + 2 + DEC_MP)
+// per unit, G * DEC_QM floats: phi(q) [G][128] | partial phi(q)^T M [DEC_MP][G][128] | gate [G] |
+// unused [G] | partial phi(q)^2 . b [DEC_MP][G]
+
+// The terms of the memory readout that do not depend on this step's eviction, for the G query heads
+// of one unit against the memory state as it stands: phi_q = W_theta q, phi_q^T M, sum_c phi_q[c]^2
+// b[c], and the gate sigmoid(w_g . q + c_g).  Workgroup mp of a unit takes rows 32 mp .. 32 mp + 31
+// of the memory (its slice of phi_q, and partial sums over those rows).  The tail kernel applies
+// the rank-one update of this step to these terms instead of reading the updated state back.
+__device__ __forceinline__ void dec_prep_memory(const DecArgs& a, const int u, const int mp) {
+  __shared__ float s_phq[DEC_GMAX][32];
+  __shared__ float s_red[4][DEC_GMAX][IM_D];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int b = u / a.H_kv, h = u % a.H_kv, G = a.H / a.H_kv;
+  float* qm = a.qm + (size_t)u * G * DEC_QM;
+  // every load first
+  const int d4 = tid & 31, rg = tid >> 5;    // patch of M: rows 32 mp + 4 rg .. + 3, columns 4 d4 .. 4 d4 + 3
+  const float* Mu = a.M + ((size_t)u * IM_DM + 32 * mp) * IM_D;
+  float4 Mr[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);
+  const int cl = tid >> 3, pt = tid & 7;     // W_theta row 32 mp + cl, dims 16 pt .. 16 pt + 15
+  const uint4 Wr0 = *(const uint4*)(a.Wt + (32 * mp + cl) * IM_D + 16 * pt);
+  const uint4 Wr1 = *(const uint4*)(a.Wt + (32 * mp + cl) * IM_D + 16 * pt + 8);
+  const float bc = a.bvec[(size_t)u * IM_DM + 32 * mp + (lane & 31)];
+  const float g0 = bf2f(a.wg[lane]), g1 = bf2f(a.wg[lane + 64]);
+  const bf16_t* qb = a.q + ((size_t)b * a.H + h * G) * IM_D;
+  float wv[16];
+  unpack8(Wr0, wv);
+  unpack8(Wr1, wv + 8);
+  for (int j = 0; j < G; ++j) {
+    float qv[16];
+    unpack8(*(const uint4*)(qb + j * IM_D + 16 * pt), qv);
+    unpack8(*(const uint4*)(qb + j * IM_D + 16 * pt + 8), qv + 8);
+    float pq = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) pq = fmaf(wv[e], qv[e], pq);
+    // the 8 parts of a row sit in adjacent lanes: after three shifted adds lane pt = 7 has the sum
+    pq += dpp_zero_f<0x111, 0xF>(pq);
+    pq += dpp_zero_f<0x112, 0xF>(pq);
+    pq += dpp_zero_f<0x114, 0xF>(pq);
+    if (pt == 7) {
+      s_phq[j][cl] = pq;
+      qm[j * IM_DM + 32 * mp + cl] = pq;
+    }
+  }
+  if (mp == 0) {
+    for (int j = w; j < G; j += 4) {   // gate: one wave per head
+      const float gz = wave_sum_f(fmaf(g0, bf2f(qb[j * IM_D + lane]), g1 * bf2f(qb[j * IM_D + lane + 64])));
+      if (lane == 0) qm[G * (IM_DM + DEC_MP * IM_D) + j] = 1.f / (1.f + __expf(-(gz + a.cg)));
+    }
+  }
+  __syncthreads();
+  for (int j = 0; j < G; ++j) {   // partial phi_q^T M over this thread's 4 rows, then over the wave's 8
+    float r0 = 0.f, r1 = 0.f, r2 = 0.f, r3 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float f = s_phq[j][rg * 4 + i];
+      r0 = fmaf(f, Mr[i].x, r0); r1 = fmaf(f, Mr[i].y, r1);
+      r2 = fmaf(f, Mr[i].z, r2); r3 = fmaf(f, Mr[i].w, r3);
+    }
+    r0 = halves_sum_f(r0); r1 = halves_sum_f(r1); r2 = halves_sum_f(r2); r3 = halves_sum_f(r3);
+    if (lane < 32) *(float4*)&s_red[w][j][4 * d4] = make_float4(r0, r1, r2, r3);
+  }
+  for (int j = w; j < G; j += 4) {
+    const float p = s_phq[j][lane & 31];
+    const float dn = wave_sum_f((lane < 32) ? p * p * bc : 0.f);
+    if (lane == 0) qm[G * (IM_DM + DEC_MP * IM_D + 2) + mp * G + j] = dn;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < G * IM_D; idx += 256) {
+    const int j = idx >> 7, d = idx & 127;
+    qm[G * IM_DM + (mp * G + j) * IM_D + d] = s_red[0][j][d] + s_red[1][j][d] + s_red[2][j][d] + s_red[3][j][d];
+  }
+}
+
 __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   __shared__ double part[4][16];
   __shared__ double rows[64 * 2];   // up to 64 batch rows x 2 outputs
@@ -149,7 +229,10 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int Nq = a.H_idx * IM_DI;
   const int nU = Nq / 2, nG = (a.H_idx + 1) / 2;
-  const int blk = blockIdx.x;
+  const int U = a.B * a.H_kv;
+  // the per-unit blocks (longer chains of short phases) are dispatched first
+  const int blk = ((int)blockIdx.x >= (1 + DEC_MP) * U) ? (int)blockIdx.x - (1 + DEC_MP) * U
+                                                        : nU + nG + (int)blockIdx.x;
   if (blk < nU) {
     const int n0 = blk * 2;
     if (a.B <= 4) dec_gemv2<4>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
@@ -166,6 +249,10 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
       const int r = n0 + (i & 1);
       if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = rows[i];   // raw G x; scaled by the consumer
     }
+    return;
+  }
+  if (blk >= nU + nG + U) {
+    dec_prep_memory(a, (blk - nU - nG - U) / DEC_MP, (blk - nU - nG - U) % DEC_MP);
     return;
   }
   // ---- unit block: append the new (k, v, pos) at slot len, compute its indexer key
@@ -245,30 +332,50 @@ struct DecSplitSmem {
     float oacc[16][4][IM_D];         // later: output partials of the 16 (wave, key group) streams,
   };                                 //        4 heads at a time
   float pl[DEC_KEYS][8];             // probabilities [key][head]
-  unsigned long long cmin[DEC_KEYS]; // ranking keys of the split's entries
   float wm[4][8], wl[4][8];
   float clog[8];
-  unsigned long long c64[8];
-  int cslot[8];
+  float xlp[4][8];                   // the leftover key's partial logits [scoring wave][head]
+  unsigned long long c64[4];         // per scoring wave: rank key and key index of its last-ranked entry
+  int cslot[4];
 };
 
+#define DEC_MT 512   // threads of a split workgroup: 4 attention waves and 4 scoring waves
+
+// One (unit, split) workgroup.  Waves 0-3 stream the split's K and V rows (64 KB) and do the
+// attention partial; waves 4-7 stream the indexer keys (16 KB), score them and find the split's
+// last-ranked entry while the K / V rows are still arriving.  The two roles meet at the first
+// workgroup barrier, when the attention waves have issued their loads.
 template <int G>
 __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const int s, DecSplitSmem& sm,
                                           const double* __restrict__ qy, const double* __restrict__ alpha) {
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int wl = w & 3;                 // wave within its role
+  const bool scoring = w >= 4;          // wave-uniform role
   const int b = u / a.H_kv, h = u % a.H_kv;
   const int n_old = a.len[u];
   const int n = min(n_old + ((n_old + 1 <= a.C) ? 1 : 0), a.max_live);
   const int k0 = s * DEC_KEYS;
   const int nk = max(0, min(DEC_KEYS, n - k0));
   uint32_t* crec = a.cand + ((size_t)u * a.S_alloc + s) * DEC_CAND;
-  if (nk > 0) {
-    const size_t base = (size_t)u * a.C + k0;
-    const int l16 = lane & 15, kq = lane >> 4;
-    DEC_STAMP(0);
-    // ---- issue every load of this split up front; the query features first (they are used first)
-    // Indexer query features as the B operand of the fp64 MFMA: lane (head l16, kq) holds
-    // dims 16 kq .. 16 kq + 15 of head l16.
+  if (nk <= 0) {
+    if (s == 0 && tid == 0) crec[3] = (uint32_t)n;   // an empty unit still tells the tail its length
+    return;
+  }
+  const size_t base = (size_t)u * a.C + k0;
+  const int l16 = lane & 15, kq = lane >> 4;
+  const bool own_last = (n <= a.S * DEC_KEYS) && (k0 + nk == n);   // this split holds the last live slot
+  uint32_t* lrec = a.cand + ((size_t)u * a.S_alloc + a.S) * DEC_CAND;
+  const int ll = n - 1 - k0;
+  const bool do_x_any = (s == 0) && (n > a.S * DEC_KEYS);   // split 0 also covers the one key beyond the splits
+  DEC_STAMP(0);
+  // rows past the end of the split are read from its last row instead (finite values, no branches):
+  // their logits are masked and their probabilities are zero further down
+  uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
+  int mypos = 0;
+  if (scoring) {
+    // ================= scoring waves: tiles 2 wl, 2 wl + 1 (keys 32 wl .. 32 wl + 31) =================
+    // Indexer query features as the B operand of the fp64 MFMA: lane (head l16, kq) holds dims
+    // 16 kq .. 16 kq + 15 of head l16.
     const bool hv = l16 < a.H_idx;
     double qd[16];
     {
@@ -287,60 +394,34 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       nw[0] = *(const uint4*)(a.nqw + 16 * kq);
       nw[1] = *(const uint4*)(a.nqw + 16 * kq + 8);
     }
-    // rows past the end of the split are read from its last row instead (finite values, no branches):
-    // their logits are masked and their probabilities are zero further down
-    uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int kr = min(16 * (2 * w + tt) + l16, nk - 1);
+      const int kr = min(16 * (2 * wl + tt) + l16, nk - 1);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
         kif[tt][i] = *(const uint4*)(a.Kidx + (base + kr) * IM_DI + 16 * kq + 8 * i);
     }
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      const int kr = min(16 * (2 * w + tt) + l16, nk - 1);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) kf[tt][c] = *(const uint4*)(a.K + (base + kr) * IM_D + 32 * c + 8 * kq);
-    }
-    {
-      const int jq = min(l16, G - 1);   // lanes past the group read its last head; masked below
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
-        qf[c] = *(const uint4*)(a.q + ((size_t)b * a.H + h * G + jq) * IM_D + 32 * c + 8 * kq);
-        if (l16 >= G) qf[c] = make_uint4(0, 0, 0, 0);
-      }
-    }
-    const int kk = tid & 127;
-    const int mypos = a.pos[base + min(kk, nk - 1)];
+    const int kk = 32 * wl + (lane & 31);       // the key this lane ranks (both half-waves hold it)
+    mypos = a.pos[base + min(kk, nk - 1)];
     const int qpos = a.q_pos[b];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int vr = min(16 * (2 * w + tt) + 4 * i + kq, nk - 1);
-        vf[tt][i] = *(const uint4*)(a.V + (base + vr) * IM_D + 8 * l16);
-      }
-    }
+    const int mxp = (a.n_recent > 0) ? a.maxpos[u] : 0;
     // split 0 also looks after the one key beyond the splits, when there is one
-    const bool do_x = (s == 0) && (n > a.S * DEC_KEYS);
-    uint4 xki[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)}, xk[4], xv = make_uint4(0, 0, 0, 0);
+    const bool do_x = do_x_any;
+    // (its attention logits: wave wl takes dims 32 wl .. 32 wl + 31, lane (head l16, kq) 8 of them)
+    uint4 xk = make_uint4(0, 0, 0, 0), xq = xk, xkv = xk, xki0 = xk, xki1 = xk;
     int xpos = 0;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) xk[c] = make_uint4(0, 0, 0, 0);
     if (do_x) {
       const size_t last = (size_t)u * a.C + (n - 1);
-      xki[0] = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq);
-      xki[1] = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq + 8);
-#pragma unroll
-      for (int c = 0; c < 4; ++c) xk[c] = *(const uint4*)(a.K + last * IM_D + 32 * c + 8 * kq);
-      xv = *(const uint4*)(a.V + last * IM_D + 8 * l16);
+      xki0 = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq);
+      xki1 = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq + 8);
+      xk = *(const uint4*)(a.K + last * IM_D + 32 * wl + 8 * kq);
+      xq = *(const uint4*)(a.q + ((size_t)b * a.H + h * G + min(l16, G - 1)) * IM_D + 32 * wl + 8 * kq);
+      // rows for the record: lanes 0-15 the K row, lanes 16-31 the V row (8 elements each)
+      xkv = *(const uint4*)(((lane & 16) ? a.V : a.K) + last * IM_D + 8 * l16);
       xpos = a.pos[last];
     }
-    // keep every load above this line, in this order: loads return in order, so each phase below
-    // waits only for what it uses while the rest of the split is still streaming in
-    __asm__ volatile("" ::: "memory");
-    DEC_STAMP(1);
+    __asm__ volatile("" ::: "memory");   // every load above is issued before the arithmetic below
+    DEC_STAMP_AT(14, 256);
     // ---- QK-Norm of the query features (per head over its 64 dims), head gate
     double alj;
     {
@@ -363,50 +444,44 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       }
       alj = hv ? (double)(float)(araw / sqrt((double)(a.H_idx * IM_DI))) : 0.0;
     }
-    if (do_x) {   // uniform per workgroup; every wave computes, wave 0 writes
-      uint32_t* xrec = a.cand + ((size_t)u * a.S_alloc + a.S) * DEC_CAND;
+    if (do_x) {   // uniform per workgroup; every scoring wave computes, the first writes
       float fx[16];
-      unpack8(xki[0], fx);
-      unpack8(xki[1], fx + 8);
+      unpack8(xki0, fx);
+      unpack8(xki1, fx + 8);
       double zp = 0.0;
 #pragma unroll
       for (int m = 0; m < 16; ++m) zp = fma(qd[m], (double)fx[m], zp);
       zp = rows_sum_d(zp);                                   // q_j . k over the 64 dims, in all 4 rows
       const double asum = wave_sum_d((kq == 0) ? alj * fmax(zp, 0.0) : 0.0);
       float lp = 0.f;
-#pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      {
         float qv[8], kv[8];
-        unpack8(qf[c], qv);
-        unpack8(xk[c], kv);
+        unpack8(xq, qv);
+        unpack8(xk, kv);
 #pragma unroll
         for (int e = 0; e < 8; ++e) lp = fmaf(qv[e], kv[e], lp);
       }
-      lp = rows_sum_f(lp) * a.scale;
-      if (w == 0) {
-        if (kq == 0 && l16 < G) xrec[4 + l16] = __float_as_uint(lp);
+      lp = rows_sum_f(lp);
+      if (kq == 0 && l16 < 8) sm.xlp[wl][l16] = lp;   // summed over the 4 waves after the barrier
+      if (wl == 0) {
         if (l16 == 0) {
-#pragma unroll
-          for (int c = 0; c < 4; ++c) *(uint4*)(xrec + DEC_CAND_K + 16 * c + 4 * kq) = xk[c];
-          *(uint4*)(xrec + DEC_CAND_KI + 8 * kq) = xki[0];
-          *(uint4*)(xrec + DEC_CAND_KI + 8 * kq + 4) = xki[1];
+          *(uint4*)(lrec + DEC_CAND_KI + 8 * kq) = xki0;
+          *(uint4*)(lrec + DEC_CAND_KI + 8 * kq + 4) = xki1;
         }
-        if (kq == 0) *(uint4*)(xrec + DEC_CAND_V + 4 * l16) = xv;
+        if (lane < 32) *(uint4*)(lrec + ((lane & 16) ? DEC_CAND_V : DEC_CAND_K) + 4 * l16) = xkv;
         if (lane == 0) {
           const float sc = (xpos <= qpos) ? (float)asum : -INFINITY;
           if (a.scores) a.scores[(size_t)u * a.C + (n - 1)] = sc;
-          const bool forced = (xpos < a.n_sink) ||
-                              (a.n_recent > 0 && (long long)xpos > (long long)a.maxpos[u] - a.n_recent);
+          const bool forced = (xpos < a.n_sink) || (a.n_recent > 0 && (long long)xpos > (long long)mxp - a.n_recent);
           const uint32_t skey = forced ? IM_KEY_PINF : score_key(sc);
-          xrec[0] = skey;
-          xrec[1] = (uint32_t)(~((uint32_t)xpos ^ 0x80000000u));
-          xrec[2] = (uint32_t)(n - 1);
-          xrec[3] = (uint32_t)n;
-          xrec[12] = (uint32_t)xpos;
+          lrec[0] = skey;
+          lrec[1] = (uint32_t)(~((uint32_t)xpos ^ 0x80000000u));
+          lrec[2] = (uint32_t)(n - 1);
+          lrec[3] = (uint32_t)n;
+          lrec[12] = (uint32_t)xpos;
         }
       }
     }
-    DEC_STAMP(2);
     // ---- gated similarities of the 2 tiles of this wave: Z[key][head] = Kidx_tile . q^T (fp64 MFMA)
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -416,56 +491,92 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       v4d z = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
       for (int m = 0; m < 16; ++m) z = __builtin_amdgcn_mfma_f64_16x16x4f64((double)f[m], qd[m], z, 0, 0, 0);
-      const int T = 2 * w + tt;
+      const int T = 2 * wl + tt;
       if (hv) {
 #pragma unroll
         // fp64 16x16x4 result layout: register r of lane (l16, kq) is row 4 r + kq, column l16
         for (int r = 0; r < 4; ++r) sm.zs[16 * T + 4 * r + kq][l16] = alj * fmax(z[r], 0.0);
       }
     }
-    DEC_STAMP(3);
-    __syncthreads();
-    // ---- score, forced flag, split-local candidate = the entry ranked last
-    if (tid < DEC_KEYS) {
-      unsigned long long c64 = ~0ull;
-      if (kk < nk) {
-        double asum = 0.0;
-        for (int j = 0; j < a.H_idx; ++j) asum += sm.zs[kk][j];
-        const float sc = (mypos <= qpos) ? (float)asum : -INFINITY;
-        if (a.scores) a.scores[base + kk] = sc;
-        const bool forced = (mypos < a.n_sink) ||
-                            (a.n_recent > 0 && (long long)mypos > (long long)a.maxpos[u] - a.n_recent);
-        const uint32_t skey = forced ? IM_KEY_PINF : score_key(sc);
-        c64 = ((unsigned long long)skey << 32) | (uint32_t)(~((uint32_t)mypos ^ 0x80000000u));
-      }
-      sm.cmin[kk] = c64;
-    }
-    __syncthreads();
-    // the entry ranked last: smallest key; on equal (score, position) the largest slot.  Two levels
-    // of 16 / 8 through LDS (scanning upwards with <= keeps the largest slot).
-    if (tid < 8) {
-      unsigned long long mn = ~0ull;
-      int at = -1;
+    if (own_last) {   // the last live slot's indexer key and position go to the last-slot record
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const unsigned long long c = sm.cmin[tid * 16 + e];
-        if (tid * 16 + e < nk && c <= mn) { mn = c; at = tid * 16 + e; }
+      for (int tt = 0; tt < 2; ++tt) {
+        if (16 * (2 * wl + tt) + l16 == ll) {
+          *(uint4*)(lrec + DEC_CAND_KI + 8 * kq) = kif[tt][0];
+          *(uint4*)(lrec + DEC_CAND_KI + 8 * kq + 4) = kif[tt][1];
+        }
       }
-      sm.c64[tid] = mn;
-      sm.cslot[tid] = at;
+      if (lane < 32 && kk == ll) { lrec[2] = (uint32_t)(n - 1); lrec[3] = (uint32_t)n; lrec[12] = (uint32_t)mypos; }
     }
-    __syncthreads();
-    int cl = -1;  // candidate's key index inside the split
-    unsigned long long cbest = ~0ull;
+    // the rows just written belong to this wave's own keys: it reads them back without a
+    // workgroup barrier (LDS operations of one wave complete in order)
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // ---- score, forced flag, and the wave's last-ranked entry: smallest rank key; on equal
+    // (score, position) the largest slot
+    const bool valid = lane < 32 && kk < nk;
+    uint32_t khi = 0xffffffffu, klo = 0xffffffffu;
+    if (valid) {
+      double asum = 0.0;
+      for (int j = 0; j < a.H_idx; ++j) asum += sm.zs[kk][j];
+      const float sc = (mypos <= qpos) ? (float)asum : -INFINITY;
+      if (a.scores) a.scores[base + kk] = sc;
+      const bool forced = (mypos < a.n_sink) || (a.n_recent > 0 && (long long)mypos > (long long)mxp - a.n_recent);
+      khi = forced ? IM_KEY_PINF : score_key(sc);
+      klo = (uint32_t)(~((uint32_t)mypos ^ 0x80000000u));
+    }
+    const uint32_t mh = wave_min_u(khi);
+    const uint32_t ml = wave_min_u(khi == mh ? klo : 0xffffffffu);
+    const int win = (int)wave_max_u((valid && khi == mh && klo == ml) ? (uint32_t)(lane + 1) : 0u) - 1;
+    if (lane == 0) {
+      sm.c64[wl] = ((unsigned long long)mh << 32) | ml;
+      sm.cslot[wl] = (win >= 0) ? 32 * wl + win : -1;
+    }
+    DEC_STAMP_AT(15, 256);
+  } else {
+    // ================= attention waves: issue the K, Q and V loads =================
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const unsigned long long c = sm.c64[e];
-      const int at = sm.cslot[e];
-      if (at >= 0 && c <= cbest) { cbest = c; cl = at; }
+    for (int tt = 0; tt < 2; ++tt) {
+      const int kr = min(16 * (2 * wl + tt) + l16, nk - 1);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) kf[tt][c] = *(const uint4*)(a.K + (base + kr) * IM_D + 32 * c + 8 * kq);
     }
-    DEC_STAMP(4);
-    // ---- logits of the 2 tiles of this wave:  S[key][head] = K_tile . Q^T  (bf16 MFMA, fp32 acc)
-    float sreg[2][4];
+    {
+      const int jq = min(l16, G - 1);   // lanes past the group read its last head; masked below
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        qf[c] = *(const uint4*)(a.q + ((size_t)b * a.H + h * G + jq) * IM_D + 32 * c + 8 * kq);
+        if (l16 >= G) qf[c] = make_uint4(0, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int vr = min(16 * (2 * wl + tt) + 4 * i + kq, nk - 1);
+        vf[tt][i] = *(const uint4*)(a.V + (base + vr) * IM_D + 8 * l16);
+      }
+    }
+    // keep every load above this line, in this order: loads return in order, so each phase below
+    // waits only for what it uses while the rest is still streaming in
+    __asm__ volatile("" ::: "memory");
+    DEC_STAMP(1);
+  }
+  __syncthreads();
+  DEC_STAMP(2);
+  // ---- the split's candidate: last-ranked over the 4 scoring waves (upwards with <= keeps the largest slot)
+  int cl = -1;  // candidate's key index inside the split
+  unsigned long long cbest = ~0ull;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const unsigned long long c = sm.c64[e];
+    const int at = sm.cslot[e];
+    if (at >= 0 && c <= cbest) { cbest = c; cl = at; }
+  }
+  // ---- logits of the 2 tiles of an attention wave:  S[key][head] = K_tile . Q^T  (bf16 MFMA, fp32 acc)
+  float sreg[2][4];
+  if (!scoring) {
     float lmax = -INFINITY;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -480,7 +591,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a0, b0, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1, b1, acc, 0, 0, 0);
       }
-      const int T = 2 * w + tt;
+      const int T = 2 * wl + tt;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int kl = 16 * T + 4 * kq + r;  // this lane: head l16, key kl
@@ -492,14 +603,35 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       }
     }
     lmax = rows_max_f(lmax);
-    if (kq == 0 && l16 < 8) sm.wm[w][l16] = lmax;
-    __syncthreads();
+    if (kq == 0 && l16 < 8) sm.wm[wl][l16] = lmax;
+    // the candidate's rows travel with the record (straight from the fragments), so the tail has
+    // no dependent loads; the split that holds the last live slot also fills the last-slot record
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int T = 2 * wl + tt;
+      if (16 * T + l16 == cl) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) *(uint4*)(crec + DEC_CAND_K + 16 * c + 4 * kq) = kf[tt][c];
+      }
+      if (own_last && 16 * T + l16 == ll) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) *(uint4*)(lrec + DEC_CAND_K + 16 * c + 4 * kq) = kf[tt][c];
+      }
+    }
+  } else if (do_x_any && tid - 256 < G) {
+    // the leftover key's logits: the 4 scoring waves' partial dot products
+    const int j = tid - 256;
+    lrec[4 + j] = __float_as_uint((sm.xlp[0][j] + sm.xlp[1][j] + sm.xlp[2][j] + sm.xlp[3][j]) * a.scale);
+  }
+  __syncthreads();
+  DEC_STAMP(3);
+  if (!scoring) {
     float mj = fmaxf(fmaxf(sm.wm[0][l16 & 7], sm.wm[1][l16 & 7]), fmaxf(sm.wm[2][l16 & 7], sm.wm[3][l16 & 7]));
     if (mj == -INFINITY) mj = -1e30f;
     float lsum = 0.f;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int T = 2 * w + tt;
+      const int T = 2 * wl + tt;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const float p = (sreg[tt][r] == -INFINITY) ? 0.f : __expf(sreg[tt][r] - mj);
@@ -508,18 +640,20 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       }
     }
     lsum = rows_sum_f(lsum);
-    if (kq == 0 && l16 < 8) sm.wl[w][l16] = lsum;
-    __syncthreads();
-    DEC_STAMP(5);
-    // ---- O[head][d] += P[head][key] V[key][d]; 16 lanes share a key row (8 dims each)
-    float acc[G][8];
+    if (kq == 0 && l16 < 8) sm.wl[wl][l16] = lsum;
+  }
+  __syncthreads();   // also: zs is dead from here on, its space holds oacc
+  DEC_STAMP(4);
+  // ---- O[head][d] += P[head][key] V[key][d]; 16 lanes share a key row (8 dims each)
+  float acc[G][8];
+  if (!scoring) {
 #pragma unroll
     for (int j = 0; j < G; ++j)
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int T = 2 * w + tt;
+      const int T = 2 * wl + tt;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int kl = 16 * T + 4 * i + kq;
@@ -533,62 +667,50 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
           for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(pv[j], v[e], acc[j][e]);
       }
     }
-    DEC_STAMP(6);
-    // the 16 (wave, key group) streams meet in LDS, 4 heads at a time
-    float* prec = a.part + ((size_t)u * a.S_alloc + s) * G * DEC_REC;   // dense [split][head][record]
-    __syncthreads();   // zs is dead: its space now holds oacc
+  }
+  DEC_STAMP(5);
+  // the 16 (attention wave, key group) streams meet in LDS, 4 heads at a time; all 8 waves add them up
+  float* prec = a.part + ((size_t)u * a.S_alloc + s) * G * DEC_REC;   // dense [split][head][record]
 #pragma unroll
-    for (int j0 = 0; j0 < G; j0 += 4) {
-      if (j0 > 0) __syncthreads();
+  for (int j0 = 0; j0 < G; j0 += 4) {
+    if (j0 > 0) __syncthreads();
+    if (!scoring) {
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
         if (j0 + jj < G) {
-          float* dst = &sm.oacc[w * 4 + kq][jj][8 * l16];
+          float* dst = &sm.oacc[wl * 4 + kq][jj][8 * l16];
           *(float4*)dst = make_float4(acc[j0 + jj][0], acc[j0 + jj][1], acc[j0 + jj][2], acc[j0 + jj][3]);
           *(float4*)(dst + 4) = make_float4(acc[j0 + jj][4], acc[j0 + jj][5], acc[j0 + jj][6], acc[j0 + jj][7]);
         }
       }
-      __syncthreads();
-      const int nj = (G - j0 < 4) ? G - j0 : 4;
-      for (int idx = tid; idx < nj * IM_D; idx += 256) {
-        const int jj = idx >> 7, d = idx & 127, j = j0 + jj;
-        float o = 0.f;
+    }
+    __syncthreads();
+    const int nj = (G - j0 < 4) ? G - j0 : 4;
+    for (int idx = tid; idx < nj * IM_D; idx += DEC_MT) {
+      const int jj = idx >> 7, d = idx & 127, j = j0 + jj;
+      float o = 0.f;
 #pragma unroll
-        for (int st = 0; st < 16; ++st) o += sm.oacc[st][jj][d];
-        prec[j * DEC_REC + 2 + d] = o;
-        if (d == 0) {
-          float m = fmaxf(fmaxf(sm.wm[0][j], sm.wm[1][j]), fmaxf(sm.wm[2][j], sm.wm[3][j]));
-          prec[j * DEC_REC] = (m == -INFINITY) ? -1e30f : m;
-          prec[j * DEC_REC + 1] = sm.wl[0][j] + sm.wl[1][j] + sm.wl[2][j] + sm.wl[3][j];
-        }
+      for (int st = 0; st < 16; ++st) o += sm.oacc[st][jj][d];
+      prec[j * DEC_REC + 2 + d] = o;
+      if (d == 0) {
+        float m = fmaxf(fmaxf(sm.wm[0][j], sm.wm[1][j]), fmaxf(sm.wm[2][j], sm.wm[3][j]));
+        prec[j * DEC_REC] = (m == -INFINITY) ? -1e30f : m;
+        prec[j * DEC_REC + 1] = sm.wl[0][j] + sm.wl[1][j] + sm.wl[2][j] + sm.wl[3][j];
       }
     }
-    DEC_STAMP(7);
-    if (tid == 0) {
-      crec[0] = (uint32_t)(cbest >> 32);
-      crec[1] = (uint32_t)cbest;
-      crec[2] = (uint32_t)(k0 + cl);
-      crec[3] = (uint32_t)n;
-    }
-    if (tid < G) crec[4 + tid] = __float_as_uint(sm.clog[tid]);
-    // the candidate's rows travel with the record (straight from the fragments), so the tail has
-    // no dependent loads; the split that holds the last live slot also fills the last-slot record
-    const bool own_last = (n <= a.S * DEC_KEYS) && (k0 + nk == n);
-    uint32_t* lrec = a.cand + ((size_t)u * a.S_alloc + a.S) * DEC_CAND;
-    const int ll = n - 1 - k0;
+  }
+  DEC_STAMP(6);
+  if (tid == 0) {
+    crec[0] = (uint32_t)(cbest >> 32);
+    crec[1] = (uint32_t)cbest;
+    crec[2] = (uint32_t)(k0 + cl);
+    crec[3] = (uint32_t)n;
+  }
+  if (tid < G) crec[4 + tid] = __float_as_uint(sm.clog[tid]);
+  if (!scoring) {
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const int T = 2 * w + tt;
-      if (16 * T + l16 == cl) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) *(uint4*)(crec + DEC_CAND_K + 16 * c + 4 * kq) = kf[tt][c];
-      }
-      if (own_last && 16 * T + l16 == ll) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) *(uint4*)(lrec + DEC_CAND_K + 16 * c + 4 * kq) = kf[tt][c];
-        *(uint4*)(lrec + DEC_CAND_KI + 8 * kq) = kif[tt][0];
-        *(uint4*)(lrec + DEC_CAND_KI + 8 * kq + 4) = kif[tt][1];
-      }
+      const int T = 2 * wl + tt;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int vr = 16 * T + 4 * i + kq;
@@ -596,10 +718,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         if (own_last && vr == ll) *(uint4*)(lrec + DEC_CAND_V + 4 * l16) = vf[tt][i];
       }
     }
-    if (own_last && tid == ll) { lrec[2] = (uint32_t)(n - 1); lrec[3] = (uint32_t)n; lrec[12] = (uint32_t)mypos; }
-  } else if (s == 0 && tid == 0) {
-    crec[3] = (uint32_t)n;   // an empty unit still tells the tail its length
   }
+  DEC_STAMP(7);
 }
 
 #define DEC_TT 1024   // threads of a tail workgroup: the tail is a chain of short phases, so it is
@@ -611,16 +731,16 @@ struct DecTailSmem {
   static constexpr int NS = (G <= 4) ? 2 : 1;    // threads sharing one output in the merge
   float pst[CH][G][DEC_REC];                      // partial records of the staged splits
   uint32_t cst[CH + 1][DEC_CAND];                 // their candidate records (+ the last-slot record)
-  float qs[G][IM_D];
-  float php[8][G][IM_DM];
-  float red[16][G][IM_D];
-  float phq[G][IM_DM];
-  float rold[G][IM_D];
+  float phq[G][IM_DM];                            // the unit's readout terms, in the order k_dec_prep
+  float rpart[DEC_MP][G][IM_D];                   //   writes them: these five arrays are one block
+  float gate[G];
+  float unused[G];
+  float denp[DEC_MP][G];
   float mrg[3][G * IM_D];                         // second half's (max, denominator, numerator) in the merge
-  float ke[IM_D], ve[IM_D], phe2[8][IM_DM], phe[IM_DM], bnew[IM_DM];
+  float phe2[8][IM_DM], phe[IM_DM];
   float lastv[IM_D];                              // V row of the last live slot
   float xlog[DEC_GMAX];                           // the leftover key's attention logits
-  float gate[G], den[G], dot[G];
+  float den[G], dot[G];
   unsigned long long c64[16];
   int cidx[16];
   int e_slot, e_split;
@@ -665,16 +785,15 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const int wc = tid & 127, hh = tid >> 7;   // W_theta row wc, dims 16 hh .. 16 hh + 15
   const uint4 Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
   const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
-  const float b_old = (tid < IM_DM) ? a.bvec[(size_t)u * IM_DM + tid] : 0.f;
-  for (int idx = tid; idx < G * IM_D; idx += DEC_TT)
-    sm.qs[idx >> 7][idx & 127] = bf2f(a.q[((size_t)b * a.H + h * G) * IM_D + idx]);
+  const float b_old = a.bvec[(size_t)u * IM_DM + wc];
   // first round of split records (all launched splits; which are live is known once n is read
-  // from record 0) and, right behind them, the last-slot record
+  // from record 0), right behind them the last-slot record, and the readout terms of the queries
   const int cs0 = min(CH, a.S);
   const int LS = a.S;                          // index of the last-slot record
   const bool ls_staged = LS <= CH;
   dec_stage<5>(&sm.pst[0][0][0], pbase, cs0 * G * DEC_REC);
   dec_stage<2>((float*)&sm.cst[0][0], (const float*)cbase, (ls_staged ? LS + 1 : cs0) * DEC_CAND);
+  dec_stage<2>(&sm.phq[0][0], a.qm + (size_t)u * G * DEC_QM, G * DEC_QM);
   __syncthreads();
   DEC_STAMP(9);
   const int n = (int)sm.cst[0][3];
@@ -705,25 +824,6 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     for (int e = 0; e < 8; ++e) sm.lastv[(tid - 16) * 8 + e] = f[e];
   }
   if (tid < G) sm.xlog[tid] = __uint_as_float(lsrec[4 + tid]);
-  // ---------------- memory readout terms that do not depend on the eviction ----------------
-  float wv[16];
-  unpack8(Wr0, wv);
-  unpack8(Wr1, wv + 8);
-  {  // phi(q_j)[c]: eight threads per c (16 dims each)
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-      float pq = 0.f;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) pq = fmaf(wv[e], sm.qs[j][hh * 16 + e], pq);
-      sm.php[hh][j][wc] = pq;
-    }
-  }
-  // gate: one wave per head
-  for (int j = w; j < G; j += DEC_TT / 64) {
-    float gz = bf2f(a.wg[lane]) * sm.qs[j][lane] + bf2f(a.wg[lane + 64]) * sm.qs[j][lane + 64];
-    gz = wave_sum_f(gz);
-    if (lane == 0) sm.gate[j] = 1.f / (1.f + __expf(-(gz + a.cg)));
-  }
   // ---------------- the evicted entry: ranked last over all splits and the leftover key ----------------
   const int x_split = has_x ? n_act : -2;   // index the leftover key goes by in the ranking
   const int cn0 = min(CH, n_act);
@@ -739,107 +839,76 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   }
   const bool evict = n > a.budget;
   if (n > a.budget + 1 && tid == 0) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
-  if (tid == 0) {
-    unsigned long long bb = ~0ull;
-    int bi = -1;
-    for (int sp = 0; sp < cn0; ++sp) {   // ascending: on a full tie the later split (larger slot) wins
-      const unsigned long long c = ((unsigned long long)sm.cst[sp][0] << 32) | sm.cst[sp][1];
-      if (c <= bb) { bb = c; bi = sp; }
-    }
-    if (n_act > CH) {
-      for (int i = 0; i < DEC_TT / 64; ++i) {
-        const int oi = sm.cidx[i];
-        if (oi >= 0 && (bi < 0 || sm.c64[i] < bb || (sm.c64[i] == bb && oi > bi))) { bb = sm.c64[i]; bi = oi; }
+  if (w == 0) {
+    // smallest rank key over the staged candidates, lane = split; on a full tie the later split
+    // (larger slot) wins
+    const bool on = lane < cn0;
+    const int ls = on ? lane : 0;
+    const uint32_t khi = on ? sm.cst[ls][0] : 0xffffffffu;
+    const uint32_t klo = on ? sm.cst[ls][1] : 0xffffffffu;
+    const uint32_t mh = wave_min_u(khi);
+    const uint32_t ml = wave_min_u(khi == mh ? klo : 0xffffffffu);
+    const int win = (int)wave_max_u((on && khi == mh && klo == ml) ? (uint32_t)lane + 1u : 0u) - 1;
+    if (lane == 0) {
+      unsigned long long bb = ((unsigned long long)mh << 32) | ml;
+      int bi = win;
+      if (n_act > CH) {
+        for (int i = 0; i < DEC_TT / 64; ++i) {
+          const int oi = sm.cidx[i];
+          if (oi >= 0 && (bi < 0 || sm.c64[i] < bb || (sm.c64[i] == bb && oi > bi))) { bb = sm.c64[i]; bi = oi; }
+        }
       }
+      if (has_x) {
+        const unsigned long long xc = ((unsigned long long)lsrec[0] << 32) | lsrec[1];
+        if (bi < 0 || xc <= bb) { bb = xc; bi = x_split; }
+      }
+      const bool ev = evict && bi >= 0;
+      sm.e_split = ev ? bi : -1;
+      sm.e_slot = !ev ? -1 : (bi == x_split) ? n_last : (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]);
     }
-    if (has_x) {
-      const unsigned long long xc = ((unsigned long long)lsrec[0] << 32) | lsrec[1];
-      if (bi < 0 || xc <= bb) { bb = xc; bi = x_split; }
-    }
-    const bool ev = evict && bi >= 0;
-    sm.e_split = ev ? bi : -1;
-    sm.e_slot = !ev ? -1 : (bi == x_split) ? n_last : (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]);
-  }
-  __syncthreads();
-  for (int idx = tid; idx < G * IM_DM; idx += DEC_TT) {
-    const int j = idx >> 7, c = idx & 127;
-    float t = 0.f;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) t += sm.php[k][j][c];
-    sm.phq[j][c] = t;
-  }
-  const int e_split = sm.e_split, e_slot = sm.e_slot;
-  // the evicted entry's rows: in the record of its split, or in the last-slot record
-  if (e_slot >= 0 && tid < IM_D) {
-    const uint32_t* er = (e_split == x_split) ? lsrec
-                       : (e_split < CH) ? (const uint32_t*)&sm.cst[e_split][0] : cbase + (size_t)e_split * DEC_CAND;
-    sm.ke[tid] = bf2f(((const bf16_t*)(er + DEC_CAND_K))[tid]);
-    sm.ve[tid] = bf2f(((const bf16_t*)(er + DEC_CAND_V))[tid]);
   }
   __syncthreads();
   DEC_STAMP(10);
-  {  // r_old[j][d] = sum_c phi_q[j][c] M[c][d] over this thread's 4 rows and 4 columns
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-      float r0 = 0.f, r1 = 0.f, r2 = 0.f, r3 = 0.f;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float f = sm.phq[j][rg * 4 + i];
-        r0 = fmaf(f, Mr[i].x, r0); r1 = fmaf(f, Mr[i].y, r1);
-        r2 = fmaf(f, Mr[i].z, r2); r3 = fmaf(f, Mr[i].w, r3);
-      }
-      r0 = halves_sum_f(r0); r1 = halves_sum_f(r1); r2 = halves_sum_f(r2); r3 = halves_sum_f(r3);
-      if (lane < 32) *(float4*)&sm.red[w][j][4 * d4] = make_float4(r0, r1, r2, r3);
-    }
-  }
-  // ---------------- memory write (rank one) ----------------
+  const int e_split = sm.e_split, e_slot = sm.e_slot;
+  // the evicted entry's rows: in the record of its split, or in the last-slot record
+  const uint32_t* er = (e_split == x_split) ? lsrec
+                     : (e_split >= 0 && e_split < CH) ? (const uint32_t*)&sm.cst[e_split][0]
+                     : cbase + (size_t)max(e_split, 0) * DEC_CAND;
+  // ---------------- memory write (rank one): phi_e = W_theta k_e, eight threads per row ----------------
   if (e_slot >= 0) {
+    float wv[16], kv[16];
+    unpack8(Wr0, wv);
+    unpack8(Wr1, wv + 8);
+    unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh), kv);
+    unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh + 4), kv + 8);
     float pe = 0.f;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) pe = fmaf(wv[e], sm.ke[hh * 16 + e], pe);
+    for (int e = 0; e < 16; ++e) pe = fmaf(wv[e], kv[e], pe);
     sm.phe2[hh][wc] = pe;
   }
   __syncthreads();
-  for (int idx = tid; idx < G * IM_D; idx += DEC_TT) {
-    const int j = idx >> 7, d = idx & 127;
-    float t = 0.f;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) t += sm.red[k][j][d];
-    sm.rold[j][d] = t;
-  }
-  if (tid < IM_DM) {
-    float bn = b_old;
-    if (e_slot >= 0) {
-      float pe = 0.f;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) pe += sm.phe2[k][tid];
-      sm.phe[tid] = pe;
-      bn = fmaf(a.lambda, b_old, a.eta * pe * pe);
-      a.bvec[(size_t)u * IM_DM + tid] = bn;
-    }
-    sm.bnew[tid] = bn;
-  }
-  __syncthreads();
   DEC_STAMP(11);
-  if (e_slot >= 0) {
-    // M <- lambda M + eta phi_e v_e^T for this thread's 4 x 4 patch
-    const float4 vv = *(const float4*)&sm.ve[4 * d4];
+  if (w < G) {   // one wave per head: phi_q . phi_e and the readout's denominator
+    const int j = w;
+    float dn = 0.f, dt = 0.f;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float f = a.eta * sm.phe[rg * 4 + i];
-      float4 m = Mr[i];
-      m.x = fmaf(a.lambda, m.x, f * vv.x); m.y = fmaf(a.lambda, m.y, f * vv.y);
-      m.z = fmaf(a.lambda, m.z, f * vv.z); m.w = fmaf(a.lambda, m.w, f * vv.w);
-      *(float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4) = m;
+    for (int k = 0; k < DEC_MP; ++k) dn += sm.denp[k][j];
+    if (e_slot >= 0) {
+      float p0 = 0.f, p1 = 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { p0 += sm.phe2[k][lane]; p1 += sm.phe2[k][lane + 64]; }
+      const float q0 = sm.phq[j][lane], q1 = sm.phq[j][lane + 64];
+      dt = wave_sum_f(fmaf(q0, p0, q1 * p1));
+      const float sq = wave_sum_f(fmaf(q0 * q0, p0 * p0, q1 * q1 * p1 * p1));
+      dn = fmaf(a.lambda, dn, a.eta * sq);
     }
-  }
-  for (int j = w; j < G; j += DEC_TT / 64) {
-    float dn = sm.phq[j][lane] * sm.phq[j][lane] * sm.bnew[lane] +
-               sm.phq[j][lane + 64] * sm.phq[j][lane + 64] * sm.bnew[lane + 64];
-    dn = wave_sum_f(dn);
-    float dt = 0.f;
-    if (e_slot >= 0) dt = wave_sum_f(sm.phq[j][lane] * sm.phe[lane] + sm.phq[j][lane + 64] * sm.phe[lane + 64]);
     if (lane == 0) { sm.den[j] = dn + a.mem_eps; sm.dot[j] = dt; }
+  } else if (w >= 8 && w < 10 && e_slot >= 0) {   // b <- lambda b + eta phi_e^2 (wc = tid - 512 here)
+    float pe = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) pe += sm.phe2[k][wc];
+    sm.phe[wc] = pe;
+    a.bvec[(size_t)u * IM_DM + wc] = fmaf(a.lambda, b_old, a.eta * pe * pe);
   }
   DEC_STAMP(12);
   // ---------------- merge the attention partials, add back the candidates that stay ----------------
@@ -850,6 +919,13 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const int part = (NS == 2) ? (tid >> 9) : 0;
   const bool act = oidx < NO;
   const int j = act ? (oidx >> 7) : 0, d = oidx & 127;
+  // the evicted entry's value row, read before a later staging round can overwrite the records
+  const float ve_d = (e_slot >= 0) ? bf2f(((const bf16_t*)(er + DEC_CAND_V))[d]) : 0.f;
+  float4 ve4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (e_slot >= 0) {
+    const uint2 t = *(const uint2*)(er + DEC_CAND_V + 2 * d4);
+    ve4 = make_float4(bf_lo(t.x), bf_hi(t.x), bf_lo(t.y), bf_hi(t.y));
+  }
   float rm = -1e30f, rl = 0.f, ro = 0.f;
   for (int c0 = 0; c0 < n_act; c0 += CH) {
     const int cn = min(CH, n_act - c0);
@@ -894,7 +970,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   if (NS == 2) {
     if (part == 1 && act) { sm.mrg[0][oidx] = rm; sm.mrg[1][oidx] = rl; sm.mrg[2][oidx] = ro; }
   }
-  __syncthreads();   // also orders den / dot / rold before their use below
+  __syncthreads();   // also orders den / dot / phe before their use below
   if (part == 0 && act) {
     float m = rm, o = ro, l = rl;
     if (NS == 2) {
@@ -912,14 +988,28 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       l = fmaf(l, resc, pc);
     }
     const float o_attn = (l > 0.f) ? o / l : 0.f;
-    float mr = sm.rold[j][d];
-    if (e_slot >= 0) mr = fmaf(a.lambda, mr, a.eta * sm.dot[j] * sm.ve[d]);
+    // phi_q^T (lambda M + eta phi_e v_e^T) = lambda phi_q^T M + eta (phi_q . phi_e) v_e
+    float mr = 0.f;
+#pragma unroll
+    for (int k = 0; k < DEC_MP; ++k) mr += sm.rpart[k][j][d];
+    if (e_slot >= 0) mr = fmaf(a.lambda, mr, a.eta * sm.dot[j] * ve_d);
     const float res = sm.gate[j] * (mr / sm.den[j]);
     const size_t oi = ((size_t)b * a.H + h * G + j) * IM_D + d;
     a.out[oi] = f2bf_rne(o_attn + res);
     if (a.readout) a.readout[oi] = res;
   }
   DEC_STAMP(13);
+  if (e_slot >= 0) {
+    // M <- lambda M + eta phi_e v_e^T for this thread's 4 x 4 patch
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float f = a.eta * sm.phe[rg * 4 + i];
+      float4 m = Mr[i];
+      m.x = fmaf(a.lambda, m.x, f * ve4.x); m.y = fmaf(a.lambda, m.y, f * ve4.y);
+      m.z = fmaf(a.lambda, m.z, f * ve4.z); m.w = fmaf(a.lambda, m.w, f * ve4.w);
+      *(float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4) = m;
+    }
+  }
   // ---------------- fill the hole with the last entry, publish the new length ----------------
   const int n_keep = (e_slot >= 0) ? n - 1 : n;
   if (e_slot >= 0 && e_slot < n_keep) {
@@ -938,7 +1028,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
 
 // grid: units * S blocks; consecutive blocks take different units, the short last splits come last
 template <int G>
-__global__ __launch_bounds__(256, 2) void k_dec_main(const DecArgs a, const double* __restrict__ qy,
+__global__ __launch_bounds__(DEC_MT, 4) void k_dec_main(const DecArgs a, const double* __restrict__ qy,
                                                      const double* __restrict__ alpha) {
   __shared__ __attribute__((aligned(16))) DecSplitSmem sm;
   const int U = a.B * a.H_kv;

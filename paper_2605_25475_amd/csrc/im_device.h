@@ -69,6 +69,28 @@ __device__ __forceinline__ float wave_max_f(float v) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_keep_u(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+__device__ __forceinline__ uint32_t wave_min_u(uint32_t v) {
+  v = min(v, dpp_keep_u<0x111, 0xF>(v));
+  v = min(v, dpp_keep_u<0x112, 0xF>(v));
+  v = min(v, dpp_keep_u<0x114, 0xF>(v));
+  v = min(v, dpp_keep_u<0x118, 0xF>(v));
+  v = min(v, dpp_keep_u<0x142, 0xA>(v));
+  v = min(v, dpp_keep_u<0x143, 0xC>(v));
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+__device__ __forceinline__ uint32_t wave_max_u(uint32_t v) {
+  v = max(v, dpp_keep_u<0x111, 0xF>(v));
+  v = max(v, dpp_keep_u<0x112, 0xF>(v));
+  v = max(v, dpp_keep_u<0x114, 0xF>(v));
+  v = max(v, dpp_keep_u<0x118, 0xF>(v));
+  v = max(v, dpp_keep_u<0x142, 0xA>(v));
+  v = max(v, dpp_keep_u<0x143, 0xC>(v));
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ double dpp_zero_d(double v) {
   const long long b = __double_as_longlong(v);
   const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), CTRL, ROW_MASK, 0xF, true);

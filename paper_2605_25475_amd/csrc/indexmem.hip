@@ -20,7 +20,7 @@ struct im_handle {
   int max_live;
   bool ws_ready;
   // workspace layout (byte offsets)
-  size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, total;
+  size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, off_dqm, total;
   int mem_split, attn_chunks, dec_splits;
   // optional kernel timing (im_profile_start / im_profile_stop)
   hipEvent_t* prof_ev;
@@ -82,6 +82,7 @@ void layout(const im_config* c, im_handle* h) {
   h->off_attn = off;   off = align256(off + B * c->n_q_heads * h->attn_chunks * IM_ATT_REC * sizeof(float));
   h->off_dpart = off;  off = align256(off + units * h->dec_splits * DEC_GMAX * DEC_REC * sizeof(float));  // upper bound: G <= 8
   h->off_dcand = off;  off = align256(off + units * h->dec_splits * DEC_CAND * sizeof(uint32_t));
+  h->off_dqm = off;    off = align256(off + units * DEC_GMAX * DEC_QM * sizeof(float));
   h->total = off;
 }
 
@@ -398,6 +399,7 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
   a.qy = (double*)(h->ws + h->off_qy); a.alpha = (double*)(h->ws + h->off_alpha);
   a.status = words; a.maxpos = words + 32;
   a.part = (float*)(h->ws + h->off_dpart); a.cand = (uint32_t*)(h->ws + h->off_dcand);
+  a.qm = (float*)(h->ws + h->off_dqm);
   a.B = c.batch; a.H = c.n_q_heads; a.H_kv = c.n_kv_heads; a.C = c.capacity; a.H_idx = c.n_idx_heads;
   a.gate_in = c.gate_in_dim; a.n_sink = c.n_sink; a.n_recent = c.n_recent; a.budget = budget;
   // 128-key splits for the main kernel; a single key beyond a multiple of 128 (the steady state with
@@ -406,14 +408,14 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
                                                          : (h->max_live + DEC_KEYS - 1) / DEC_KEYS;
   a.S_alloc = h->dec_splits; a.max_live = h->max_live;
   a.rms_eps = c.rms_eps; a.mem_eps = c.mem_eps; a.scale = c.softmax_scale; a.lambda = lambda; a.eta = eta;
-  const int prep_blocks = c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2 + units;
+  const int prep_blocks = c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2 + (1 + DEC_MP) * units;
   k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);
   const int main_blocks = units * (a.S > 0 ? a.S : 1);
   const bool prof = h->prof_ev && h->prof_n < h->prof_max;
   if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n], s);
 #define IM_DEC_CASE(g)                                              \
   case g:                                                           \
-    k_dec_main<g><<<main_blocks, 256, 0, s>>>(a, a.qy, a.alpha);    \
+    k_dec_main<g><<<main_blocks, DEC_MT, 0, s>>>(a, a.qy, a.alpha);    \
     if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n + 1], s); \
     k_dec_tail<g><<<units, DEC_TT, 0, s>>>(a);                      \
     break;
