@@ -374,6 +374,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   int mypos = 0;
   if (scoring) {
     // ================= scoring waves: tiles 2 wl, 2 wl + 1 (keys 32 wl .. 32 wl + 31) =================
+    // their few loads go ahead of the attention waves' many: the scoring chain is the longer one
+    __builtin_amdgcn_s_setprio(3);
     // Indexer query features as the B operand of the fp64 MFMA: lane (head l16, kq) holds dims
     // 16 kq .. 16 kq + 15 of head l16.
     const bool hv = l16 < a.H_idx;
@@ -738,8 +740,6 @@ struct DecTailSmem {
   float denp[DEC_MP][G];
   float mrg[3][G * IM_D];                         // second half's (max, denominator, numerator) in the merge
   float phe2[8][IM_DM], phe[IM_DM];
-  float lastv[IM_D];                              // V row of the last live slot
-  float xlog[DEC_GMAX];                           // the leftover key's attention logits
   float den[G], dot[G];
   unsigned long long c64[16];
   int cidx[16];
@@ -787,47 +787,56 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
   const float b_old = a.bvec[(size_t)u * IM_DM + wc];
   // first round of split records (all launched splits; which are live is known once n is read
-  // from record 0), right behind them the last-slot record, and the readout terms of the queries
+  // from record 0), the last-slot record, and the readout terms of the queries
   const int cs0 = min(CH, a.S);
   const int LS = a.S;                          // index of the last-slot record
-  const bool ls_staged = LS <= CH;
-  dec_stage<5>(&sm.pst[0][0][0], pbase, cs0 * G * DEC_REC);
-  dec_stage<2>((float*)&sm.cst[0][0], (const float*)cbase, (ls_staged ? LS + 1 : cs0) * DEC_CAND);
-  dec_stage<2>(&sm.phq[0][0], a.qm + (size_t)u * G * DEC_QM, G * DEC_QM);
+  const int LSI = min(LS, CH);                 // where it is staged
+  {
+    // one batch: every load of the regions is in flight before the first LDS store
+    constexpr int NBP = (CH * G * DEC_REC / 2 + DEC_TT - 1) / DEC_TT;
+    constexpr int NBC = (CH * DEC_CAND / 2 + DEC_TT - 1) / DEC_TT;
+    constexpr int NBQ = (G * DEC_QM / 2 + DEC_TT - 1) / DEC_TT;
+    const int np2 = cs0 * G * DEC_REC / 2, nc2 = cs0 * DEC_CAND / 2;
+    constexpr int nq2 = G * DEC_QM / 2;
+    const float2* qsrc = (const float2*)(a.qm + (size_t)u * G * DEC_QM);
+    float2 rp[NBP], rc[NBC], rq[NBQ];
+    const float2 rl = ((const float2*)(cbase + (size_t)LS * DEC_CAND))[min(tid, DEC_CAND / 2 - 1)];
+#pragma unroll
+    for (int k = 0; k < NBP; ++k) rp[k] = ((const float2*)pbase)[min(tid + DEC_TT * k, np2 - 1)];
+#pragma unroll
+    for (int k = 0; k < NBC; ++k) rc[k] = ((const float2*)cbase)[min(tid + DEC_TT * k, nc2 - 1)];
+#pragma unroll
+    for (int k = 0; k < NBQ; ++k) rq[k] = qsrc[min(tid + DEC_TT * k, nq2 - 1)];
+    __asm__ volatile("" ::: "memory");
+    if (tid < DEC_CAND / 2) ((float2*)&sm.cst[LSI][0])[tid] = rl;
+#pragma unroll
+    for (int k = 0; k < NBC; ++k)
+      if (tid + DEC_TT * k < nc2) ((float2*)&sm.cst[0][0])[tid + DEC_TT * k] = rc[k];
+#pragma unroll
+    for (int k = 0; k < NBP; ++k)
+      if (tid + DEC_TT * k < np2) ((float2*)&sm.pst[0][0][0])[tid + DEC_TT * k] = rp[k];
+#pragma unroll
+    for (int k = 0; k < NBQ; ++k)
+      if (tid + DEC_TT * k < nq2) ((float2*)&sm.phq[0][0])[tid + DEC_TT * k] = rq[k];
+  }
   __syncthreads();
   DEC_STAMP(9);
   const int n = (int)sm.cst[0][3];
   const int n_act = min((n + DEC_KEYS - 1) / DEC_KEYS, a.S);
   const bool has_x = n > a.S * DEC_KEYS;      // one key beyond the splits: described by the last-slot record
   const int n_last = n - 1;
-  const uint32_t* lsrec = ls_staged ? (const uint32_t*)&sm.cst[LS][0] : cbase + (size_t)LS * DEC_CAND;
-  // candidate keys of the splits beyond the first staged round (none in the usual case)
-  unsigned long long best = ~0ull;
-  int bidx = -1;
-  for (int sp = CH + tid; sp < n_act; sp += DEC_TT) {
-    const unsigned long long c = ((unsigned long long)cbase[(size_t)sp * DEC_CAND] << 32) | cbase[(size_t)sp * DEC_CAND + 1];
-    if (c <= best) { best = c; bidx = sp; }   // later splits hold larger slots: they win full ties
-  }
-  // the last live slot's rows: they move into the hole
-  uint4 mv = make_uint4(0, 0, 0, 0);
-  int mvpos = 0;
-  if (n > 0) {
-    if (tid < 16) mv = *(const uint4*)(lsrec + DEC_CAND_K + 4 * tid);
-    else if (tid < 32) mv = *(const uint4*)(lsrec + DEC_CAND_V + 4 * (tid - 16));
-    else if (tid < 40) mv = *(const uint4*)(lsrec + DEC_CAND_KI + 4 * (tid - 32));
-    else if (tid == 40) mvpos = (int)lsrec[12];
-  }
-  if (tid >= 16 && tid < 32) {
-    float f[8];
-    unpack8(mv, f);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) sm.lastv[(tid - 16) * 8 + e] = f[e];
-  }
-  if (tid < G) sm.xlog[tid] = __uint_as_float(lsrec[4 + tid]);
-  // ---------------- the evicted entry: ranked last over all splits and the leftover key ----------------
+  const uint32_t* lsrec = (const uint32_t*)&sm.cst[LSI][0];
   const int x_split = has_x ? n_act : -2;   // index the leftover key goes by in the ranking
   const int cn0 = min(CH, n_act);
-  if (n_act > CH) {   // rare: more splits than one staged round; merge the per-thread results
+  const bool evict = n > a.budget;
+  // ---------------- the evicted entry: ranked last over all splits and the leftover key ----------------
+  if (n_act > CH) {   // rare: more splits than one staged round; their rank keys come from global memory
+    unsigned long long best = ~0ull;
+    int bidx = -1;
+    for (int sp = CH + tid; sp < n_act; sp += DEC_TT) {
+      const unsigned long long c = ((unsigned long long)cbase[(size_t)sp * DEC_CAND] << 32) | cbase[(size_t)sp * DEC_CAND + 1];
+      if (c <= best) { best = c; bidx = sp; }   // later splits hold larger slots: they win full ties
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
       const unsigned long long ob = __shfl_xor(best, o, 64);
@@ -837,8 +846,6 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     if (lane == 0) { sm.c64[w] = best; sm.cidx[w] = bidx; }
     __syncthreads();
   }
-  const bool evict = n > a.budget;
-  if (n > a.budget + 1 && tid == 0) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
   if (w == 0) {
     // smallest rank key over the staged candidates, lane = split; on a full tie the later split
     // (larger slot) wins
@@ -865,53 +872,11 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       const bool ev = evict && bi >= 0;
       sm.e_split = ev ? bi : -1;
       sm.e_slot = !ev ? -1 : (bi == x_split) ? n_last : (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]);
+      if (n > a.budget + 1) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
     }
   }
-  __syncthreads();
-  DEC_STAMP(10);
-  const int e_split = sm.e_split, e_slot = sm.e_slot;
-  // the evicted entry's rows: in the record of its split, or in the last-slot record
-  const uint32_t* er = (e_split == x_split) ? lsrec
-                     : (e_split >= 0 && e_split < CH) ? (const uint32_t*)&sm.cst[e_split][0]
-                     : cbase + (size_t)max(e_split, 0) * DEC_CAND;
-  // ---------------- memory write (rank one): phi_e = W_theta k_e, eight threads per row ----------------
-  if (e_slot >= 0) {
-    float wv[16], kv[16];
-    unpack8(Wr0, wv);
-    unpack8(Wr1, wv + 8);
-    unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh), kv);
-    unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh + 4), kv + 8);
-    float pe = 0.f;
-#pragma unroll
-    for (int e = 0; e < 16; ++e) pe = fmaf(wv[e], kv[e], pe);
-    sm.phe2[hh][wc] = pe;
-  }
-  __syncthreads();
-  DEC_STAMP(11);
-  if (w < G) {   // one wave per head: phi_q . phi_e and the readout's denominator
-    const int j = w;
-    float dn = 0.f, dt = 0.f;
-#pragma unroll
-    for (int k = 0; k < DEC_MP; ++k) dn += sm.denp[k][j];
-    if (e_slot >= 0) {
-      float p0 = 0.f, p1 = 0.f;
-#pragma unroll
-      for (int k = 0; k < 8; ++k) { p0 += sm.phe2[k][lane]; p1 += sm.phe2[k][lane + 64]; }
-      const float q0 = sm.phq[j][lane], q1 = sm.phq[j][lane + 64];
-      dt = wave_sum_f(fmaf(q0, p0, q1 * p1));
-      const float sq = wave_sum_f(fmaf(q0 * q0, p0 * p0, q1 * q1 * p1 * p1));
-      dn = fmaf(a.lambda, dn, a.eta * sq);
-    }
-    if (lane == 0) { sm.den[j] = dn + a.mem_eps; sm.dot[j] = dt; }
-  } else if (w >= 8 && w < 10 && e_slot >= 0) {   // b <- lambda b + eta phi_e^2 (wc = tid - 512 here)
-    float pe = 0.f;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) pe += sm.phe2[k][wc];
-    sm.phe[wc] = pe;
-    a.bvec[(size_t)u * IM_DM + wc] = fmaf(a.lambda, b_old, a.eta * pe * pe);
-  }
-  DEC_STAMP(12);
-  // ---------------- merge the attention partials, add back the candidates that stay ----------------
+  // ---------------- merge, first pass: the attention partials of the staged splits ----------------
+  // (does not depend on the eviction: it runs beside the ranking above)
   // NS threads share one output (head j, dim d): each takes CH / NS of the staged splits
   constexpr int NO = G * IM_D;                    // outputs
   constexpr int PER = CH / NS;                    // splits per thread and round
@@ -919,23 +884,110 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const int part = (NS == 2) ? (tid >> 9) : 0;
   const bool act = oidx < NO;
   const int j = act ? (oidx >> 7) : 0, d = oidx & 127;
-  // the evicted entry's value row, read before a later staging round can overwrite the records
-  const float ve_d = (e_slot >= 0) ? bf2f(((const bf16_t*)(er + DEC_CAND_V))[d]) : 0.f;
+  float rm = -1e30f, rl = 0.f, ro = 0.f;
+  {
+    // unconditional LDS reads (slots past cn0 hold stale words), then selects: no branches
+    float pm[PER], plv[PER], po[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const int sp = part * PER + k;
+      const float r0 = sm.pst[sp][j][0], r1 = sm.pst[sp][j][1], r2 = sm.pst[sp][j][2 + d];
+      const bool on = sp < cn0;
+      pm[k] = on ? r0 : -1e30f;
+      plv[k] = on ? r1 : 0.f;
+      po[k] = on ? r2 : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) rm = fmaxf(rm, pm[k]);
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const float sc = __expf(pm[k] - rm);
+      ro = fmaf(sc, po[k], ro);
+      rl = fmaf(sc, plv[k], rl);
+    }
+  }
+  __syncthreads();
+  DEC_STAMP(10);
+  const int e_split = sm.e_split, e_slot = sm.e_slot;
+  // the evicted entry's rows: in the staged record of its split or the last-slot record (LDS), or,
+  // with more splits than one staging round holds, in its split's record in global memory
+  const bool e_lds = (e_split == x_split) || (e_split < CH);
+  const uint32_t* erl = (e_split == x_split) ? lsrec
+                      : (const uint32_t*)&sm.cst[(e_split >= 0 && e_split < CH) ? e_split : 0][0];
+  const uint32_t* erg = cbase + (size_t)max(e_split, 0) * DEC_CAND;
+  // ---------------- memory write (rank one): phi_e = W_theta k_e, eight threads per row ----------------
+  float ve_d = 0.f;
   float4 ve4 = make_float4(0.f, 0.f, 0.f, 0.f);
   if (e_slot >= 0) {
-    const uint2 t = *(const uint2*)(er + DEC_CAND_V + 2 * d4);
-    ve4 = make_float4(bf_lo(t.x), bf_hi(t.x), bf_lo(t.y), bf_hi(t.y));
-  }
-  float rm = -1e30f, rl = 0.f, ro = 0.f;
-  for (int c0 = 0; c0 < n_act; c0 += CH) {
-    const int cn = min(CH, n_act - c0);
-    if (c0 > 0) {
-      __syncthreads();
-      dec_stage<5>(&sm.pst[0][0][0], pbase + (size_t)c0 * G * DEC_REC, cn * G * DEC_REC);
-      dec_stage<2>((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
-      __syncthreads();
+    uint4 k0, k1;
+    uint2 t;
+    if (e_lds) {
+      k0 = *(const uint4*)(erl + DEC_CAND_K + 8 * hh);
+      k1 = *(const uint4*)(erl + DEC_CAND_K + 8 * hh + 4);
+      ve_d = bf2f(((const bf16_t*)(erl + DEC_CAND_V))[d]);
+      t = *(const uint2*)(erl + DEC_CAND_V + 2 * d4);
+    } else {
+      k0 = *(const uint4*)(erg + DEC_CAND_K + 8 * hh);
+      k1 = *(const uint4*)(erg + DEC_CAND_K + 8 * hh + 4);
+      ve_d = bf2f(((const bf16_t*)(erg + DEC_CAND_V))[d]);
+      t = *(const uint2*)(erg + DEC_CAND_V + 2 * d4);
     }
-    // unconditional LDS reads (slots past cn hold stale words), then selects: no branches
+    ve4 = make_float4(bf_lo(t.x), bf_hi(t.x), bf_lo(t.y), bf_hi(t.y));
+    float wv[16], kv[16];
+    unpack8(Wr0, wv);
+    unpack8(Wr1, wv + 8);
+    unpack8(k0, kv);
+    unpack8(k1, kv + 8);
+    float pe = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) pe = fmaf(wv[e], kv[e], pe);
+    sm.phe2[hh][wc] = pe;
+  }
+  // the last live slot's rows (they move into the hole): K, V and indexer-key rows are adjacent in the record
+  uint4 mv = make_uint4(0, 0, 0, 0);
+  if (tid < 40) mv = *(const uint4*)(lsrec + DEC_CAND_K + 4 * tid);
+  const int mvpos = (int)lsrec[12];
+  // ---------------- merge, second pass: add back the candidates that stay ----------------
+  {
+    float cl[PER], cv[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const int sp = part * PER + k;
+      const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
+      const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
+      const bool stays = sp < cn0 && sp != e_split;
+      cl[k] = stays ? r3 : -INFINITY;
+      cv[k] = stays ? r4 : 0.f;
+    }
+    float m = rm;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) m = fmaxf(m, cl[k]);
+    const float resc = __expf(rm - m);
+    float o = ro * resc, l = rl * resc;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const float pc = __expf(cl[k] - m);   // exp(-inf) = 0 for the evicted / absent candidate
+      o = fmaf(pc, cv[k], o);
+      l += pc;
+    }
+    rm = m; rl = l; ro = o;
+  }
+  if (has_x && e_split != x_split && part == 0) {   // the leftover key stays
+    const float xl = __uint_as_float(lsrec[4 + j]);
+    const float xv = bf2f(((const bf16_t*)(lsrec + DEC_CAND_V))[d]);
+    const float mn = fmaxf(rm, xl);
+    const float resc = __expf(rm - mn), pc = __expf(xl - mn);
+    ro = fmaf(pc, xv, ro * resc);
+    rl = fmaf(rl, resc, pc);
+    rm = mn;
+  }
+  // splits beyond the first staged round (none in the usual case): restage, both passes at once
+  for (int c0 = CH; c0 < n_act; c0 += CH) {
+    const int cn = min(CH, n_act - c0);
+    __syncthreads();
+    dec_stage<5>(&sm.pst[0][0][0], pbase + (size_t)c0 * G * DEC_REC, cn * G * DEC_REC);
+    dec_stage<2>((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
+    __syncthreads();
     float pm[PER], plv[PER], po[PER], cl[PER], cv[PER];
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
@@ -961,7 +1013,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       const float sc = __expf(pm[k] - m);
       o = fmaf(sc, po[k], o);
       l = fmaf(sc, plv[k], l);
-      const float pc = __expf(cl[k] - m);   // exp(-inf) = 0 for the evicted / absent candidate
+      const float pc = __expf(cl[k] - m);
       o = fmaf(pc, cv[k], o);
       l += pc;
     }
@@ -970,7 +1022,31 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   if (NS == 2) {
     if (part == 1 && act) { sm.mrg[0][oidx] = rm; sm.mrg[1][oidx] = rl; sm.mrg[2][oidx] = ro; }
   }
-  __syncthreads();   // also orders den / dot / phe before their use below
+  __syncthreads();
+  DEC_STAMP(11);
+  if (w >= 16 - G) {   // one wave per head: phi_q . phi_e and the readout's denominator
+    const int jj = 15 - w;
+    float dn = 0.f, dt = 0.f;
+#pragma unroll
+    for (int k = 0; k < DEC_MP; ++k) dn += sm.denp[k][jj];
+    if (e_slot >= 0) {
+      float p0 = 0.f, p1 = 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { p0 += sm.phe2[k][lane]; p1 += sm.phe2[k][lane + 64]; }
+      const float q0 = sm.phq[jj][lane], q1 = sm.phq[jj][lane + 64];
+      dt = wave_sum_f(fmaf(q0, p0, q1 * p1));
+      const float sq = wave_sum_f(fmaf(q0 * q0, p0 * p0, q1 * q1 * p1 * p1));
+      dn = fmaf(a.lambda, dn, a.eta * sq);
+    }
+    if (lane == 0) { sm.den[jj] = dn + a.mem_eps; sm.dot[jj] = dt; }
+  } else if (w >= 6 && w < 8 && e_slot >= 0) {   // b <- lambda b + eta phi_e^2 (wc = tid - 384 here)
+    float pe = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) pe += sm.phe2[k][wc];
+    sm.phe[wc] = pe;
+    a.bvec[(size_t)u * IM_DM + wc] = fmaf(a.lambda, b_old, a.eta * pe * pe);
+  }
+  float o_attn = 0.f;
   if (part == 0 && act) {
     float m = rm, o = ro, l = rl;
     if (NS == 2) {
@@ -979,15 +1055,12 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       const float s1 = __expf(m - mn), s2 = __expf(m2 - mn);
       o = fmaf(o, s1, s2 * sm.mrg[2][oidx]);
       l = fmaf(l, s1, s2 * sm.mrg[1][oidx]);
-      m = mn;
     }
-    if (has_x && e_split != x_split) {   // the leftover key stays
-      const float mn = fmaxf(m, sm.xlog[j]);
-      const float resc = __expf(m - mn), pc = __expf(sm.xlog[j] - mn);
-      o = fmaf(pc, sm.lastv[d], o * resc);
-      l = fmaf(l, resc, pc);
-    }
-    const float o_attn = (l > 0.f) ? o / l : 0.f;
+    o_attn = (l > 0.f) ? o / l : 0.f;
+  }
+  __syncthreads();
+  DEC_STAMP(12);
+  if (part == 0 && act) {
     // phi_q^T (lambda M + eta phi_e v_e^T) = lambda phi_q^T M + eta (phi_q . phi_e) v_e
     float mr = 0.f;
 #pragma unroll
