@@ -49,7 +49,28 @@ __global__ void k_append_len(int32_t* __restrict__ len, int n_units, int n_new, 
 // ------------------------------------------------------------------------------------------
 // a1 (i): indexer keys of the slots not yet projected:  Kidx = bf16(RMSNorm(Uk K_slot)), fp64
 // ------------------------------------------------------------------------------------------
-// grid (tiles of 64 rows, units).  Thread t: row t/4 of the tile, outputs c = t%4 + 4 i.
+// grid (tiles of 64 rows, units), 4 waves; wave w projects rows 16 w .. 16 w + 15 of the tile on the
+// fp64 matrix cores: U[key][c] = sum_d K[key][d] Uk[c][d] as 4 column blocks x 32 steps of the
+// 16x16x4 product (lane (l16, kq) supplies A[row l16][k = kq] and B[k = kq][column l16]; step m of
+// this kernel covers dims 32 kq + m; result register r of the lane is row 4 r + kq, column l16).
+typedef double im_v4d __attribute__((ext_vector_type(4)));
+
+template <int N>
+__device__ __forceinline__ double row16_ror_d(double v) {   // value of the lane N to the right in its 16-lane row
+  const long long b = __double_as_longlong(v);
+  const int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), 0x120 + N, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), 0x120 + N, 0xF, 0xF, false);
+  return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+// sum over the 16 lanes of a row, in every lane (rotations of 1, 2, 4, 8)
+__device__ __forceinline__ double row16_sum_d(double v) {
+  v += row16_ror_d<1>(v);
+  v += row16_ror_d<2>(v);
+  v += row16_ror_d<4>(v);
+  v += row16_ror_d<8>(v);
+  return v;
+}
+
 __global__ __launch_bounds__(256) void k_project_keys(const bf16_t* __restrict__ K,
                                                       bf16_t* __restrict__ Kidx,
                                                       const int32_t* __restrict__ len,
@@ -58,54 +79,65 @@ __global__ __launch_bounds__(256) void k_project_keys(const bf16_t* __restrict__
                                                       const bf16_t* __restrict__ norm_w, int C,
                                                       int max_live, float rms_eps,
                                                       int32_t* __restrict__ status) {
-  __shared__ float Ks[64][129];
-  __shared__ float Us[64][129];
-  const int unit = blockIdx.y, tid = threadIdx.x;
+  __shared__ __attribute__((aligned(16))) bf16_t outs[4][16][IM_DI + 8];
+  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, kq = lane >> 4;
   int n = len[unit];
   if (n > max_live) {
     if (tid == 0 && blockIdx.x == 0) atomicOr(status, 2);
     n = max_live;
   }
-  const int row0 = n_projected[unit] + blockIdx.x * 64;
-  if (row0 >= n) return;
-  const int rows = min(64, n - row0);
-  // stage Uk (64 x 128) and the K tile, 8 bf16 per thread per pass
-  for (int i = tid; i < 64 * 16; i += 256) {
-    const int r = i >> 4, ch = i & 15;
-    uint4 u = *(const uint4*)(Uk + r * IM_D + ch * 8);
-    float* d = &Us[r][ch * 8];
-    d[0] = bf_lo(u.x); d[1] = bf_hi(u.x); d[2] = bf_lo(u.y); d[3] = bf_hi(u.y);
-    d[4] = bf_lo(u.z); d[5] = bf_hi(u.z); d[6] = bf_lo(u.w); d[7] = bf_hi(u.w);
-    uint4 k = make_uint4(0, 0, 0, 0);
-    if (r < rows) k = *(const uint4*)(K + ((size_t)unit * C + row0 + r) * IM_D + ch * 8);
-    float* e = &Ks[r][ch * 8];
-    e[0] = bf_lo(k.x); e[1] = bf_hi(k.x); e[2] = bf_lo(k.y); e[3] = bf_hi(k.y);
-    e[4] = bf_lo(k.z); e[5] = bf_hi(k.z); e[6] = bf_lo(k.w); e[7] = bf_hi(k.w);
-  }
-  __syncthreads();
-  const int r = tid >> 2, og = tid & 3;
-  double acc[16];
+  const int row0 = n_projected[unit] + blockIdx.x * 64 + 16 * w;
+  if (row0 >= n) return;                       // wave-uniform; no workgroup barrier below
+  const int rows = min(16, n - row0);
+  const size_t krow = ((size_t)unit * C + row0 + min(l16, rows - 1)) * IM_D;   // rows past the end repeat the last
+  uint4 ka[4], ub[4][4];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) acc[i] = 0.0;
-  for (int d = 0; d < IM_D; ++d) {
-    const double kd = (double)Ks[r][d];
+  for (int i = 0; i < 4; ++i) ka[i] = *(const uint4*)(K + krow + 32 * kq + 8 * i);
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = fma(kd, (double)Us[og + 4 * i][d], acc[i]);
-  }
-  double ss = 0.0;
+  for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-  for (int i = 0; i < 16; ++i) ss = fma(acc[i], acc[i], ss);
-  ss += __shfl_xor(ss, 1, 64);
-  ss += __shfl_xor(ss, 2, 64);
-  const double rr = sqrt(ss / (double)IM_DI + (double)rms_eps);
-  if (r < rows) {
-    bf16_t* out = Kidx + ((size_t)unit * C + row0 + r) * IM_DI;
+    for (int i = 0; i < 4; ++i) ub[cb][i] = *(const uint4*)(Uk + (16 * cb + l16) * IM_D + 32 * kq + 8 * i);
+  im_v4d acc[4];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int c = og + 4 * i;
-      const double w = norm_w ? (double)bf2f(norm_w[c]) : 1.0;
-      out[c] = d2bf_rne(acc[i] / rr * w);
+  for (int cb = 0; cb < 4; ++cb) acc[cb] = im_v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float fa[8] = {bf_lo(ka[i].x), bf_hi(ka[i].x), bf_lo(ka[i].y), bf_hi(ka[i].y),
+                         bf_lo(ka[i].z), bf_hi(ka[i].z), bf_lo(ka[i].w), bf_hi(ka[i].w)};
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+      const uint4 u = ub[cb][i];
+      const float fb[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
+                           bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        acc[cb] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)fa[e], (double)fb[e], acc[cb], 0, 0, 0);
     }
+  }
+  // RMSNorm over the 64 outputs of a row: this lane's 4 columns, then the 16 lanes of its row
+  double wn[4];
+#pragma unroll
+  for (int cb = 0; cb < 4; ++cb) wn[cb] = norm_w ? (double)bf2f(norm_w[16 * cb + l16]) : 1.0;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    double ss = 0.0;
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) ss = fma(acc[cb][r], acc[cb][r], ss);
+    ss = row16_sum_d(ss);
+    const double rr = sqrt(ss / (double)IM_DI + (double)rms_eps);
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) outs[w][4 * r + kq][16 * cb + l16] = d2bf_rne(acc[cb][r] / rr * wn[cb]);
+  }
+  // the wave's own 16 x 64 tile goes out in 16-byte pieces (LDS operations of one wave complete in order)
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+  for (int k = 0; k < 2; ++k) {
+    const int idx = lane + 64 * k, r = idx >> 3, ch = idx & 7;
+    if (r < rows)
+      *(uint4*)(Kidx + ((size_t)unit * C + row0 + r) * IM_DI + 8 * ch) = *(const uint4*)&outs[w][r][8 * ch];
   }
 }
 
@@ -516,26 +548,50 @@ __global__ __launch_bounds__(256) void k_mem_partial(const bf16_t* __restrict__ 
 #pragma unroll
   for (int r = 0; r < 16; ++r) bsum[r] = 0.f;
   const int32_t* ev = evict_idx + (size_t)unit * C;
+  // Software pipeline: the rows of tile t + 1 and the list entries of tile t + 2 are in flight while
+  // tile t is in the matrix cores.  Entries past the end of the split repeat its last one and are
+  // zeroed after the load.  This thread's rows: l32 for the K operand, vr0 / vr0 + 16 for V staging.
+  const int vr0 = tid >> 4, vc16 = tid & 15;
+  auto list_at = [&](int t) { return ev[min(t, i1 - 1)]; };
+  int ek_n = list_at(i0 + l32), ev0_n = list_at(i0 + vr0), ev1_n = list_at(i0 + vr0 + 16);   // tile 0
+  im_v4s kb[16], kb_n[16];
+  uint4 vv0, vv1, vv0_n, vv1_n;
+  {
+    const bf16_t* kr = K + ((size_t)unit * C + ek_n) * IM_D + 4 * kh;
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) kb_n[ks] = *(const im_v4s*)(kr + 8 * ks);
+    vv0_n = *(const uint4*)(V + ((size_t)unit * C + ev0_n) * IM_D + vc16 * 8);
+    vv1_n = *(const uint4*)(V + ((size_t)unit * C + ev1_n) * IM_D + vc16 * 8);
+  }
+  ek_n = list_at(i0 + IM_MEM_TOK + l32);                                                     // tile 1
+  ev0_n = list_at(i0 + IM_MEM_TOK + vr0);
+  ev1_n = list_at(i0 + IM_MEM_TOK + vr0 + 16);
+#pragma unroll 1
   for (int t0 = i0; t0 < i1; t0 += IM_MEM_TOK) {
-    // B operand of the first product: K^T, this lane's evicted row t0 + l32 (zero past the end)
-    const int tt = t0 + l32;
-    const bool live = tt < i1;
-    const size_t krow = ((size_t)unit * C + (live ? ev[tt] : ev[i1 - 1])) * IM_D;
-    im_v4s kb[16];
+    // rotate: the prefetched rows become this tile's; issue the next tile's rows and the list
+    // entries of the tile after it
 #pragma unroll
-    for (int ks = 0; ks < 16; ++ks) {
-      kb[ks] = *(const im_v4s*)(K + krow + 8 * ks + 4 * kh);
-      if (!live) kb[ks] = im_v4s{0, 0, 0, 0};
+    for (int ks = 0; ks < 16; ++ks) kb[ks] = kb_n[ks];
+    vv0 = vv0_n; vv1 = vv1_n;
+    {
+      const bf16_t* kr = K + ((size_t)unit * C + ek_n) * IM_D + 4 * kh;
+#pragma unroll
+      for (int ks = 0; ks < 16; ++ks) kb_n[ks] = *(const im_v4s*)(kr + 8 * ks);
+      vv0_n = *(const uint4*)(V + ((size_t)unit * C + ev0_n) * IM_D + vc16 * 8);
+      vv1_n = *(const uint4*)(V + ((size_t)unit * C + ev1_n) * IM_D + vc16 * 8);
     }
+    ek_n = list_at(t0 + 2 * IM_MEM_TOK + l32);
+    ev0_n = list_at(t0 + 2 * IM_MEM_TOK + vr0);
+    ev1_n = list_at(t0 + 2 * IM_MEM_TOK + vr0 + 16);
+    if (t0 + l32 >= i1) {
+#pragma unroll
+      for (int ks = 0; ks < 16; ++ks) kb[ks] = im_v4s{0, 0, 0, 0};
+    }
+    if (t0 + vr0 >= i1) vv0 = make_uint4(0, 0, 0, 0);
+    if (t0 + vr0 + 16 >= i1) vv1 = make_uint4(0, 0, 0, 0);
     __syncthreads();   // the previous tile's LDS reads are done
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {   // stage the V rows: 32 rows x 16 chunks of 16 bytes
-      const int ch = tid + 256 * i, r = ch >> 4, c16 = ch & 15;
-      const bool lv = t0 + r < i1;
-      uint4 vv = *(const uint4*)(V + ((size_t)unit * C + ev[lv ? t0 + r : i1 - 1]) * IM_D + c16 * 8);
-      if (!lv) vv = make_uint4(0, 0, 0, 0);
-      *(uint4*)&Vs[r][c16 * 8] = vv;
-    }
+    *(uint4*)&Vs[vr0][vc16 * 8] = vv0;
+    *(uint4*)&Vs[vr0 + 16][vc16 * 8] = vv1;
     im_v16f ph;
 #pragma unroll
     for (int r = 0; r < 16; ++r) ph[r] = 0.f;
