@@ -267,9 +267,16 @@ __global__ void k_alpha_scale(double* __restrict__ a, int n, double denom) {
 }
 
 // ------------------------------------------------------------------------------------------
-// a1 (iii): scores.  One thread per cached key; the queries' features are wave-uniform operands.
+// a1 (iii): scores on the fp64 matrix cores.  imp[key] = max over the queries that may see the key
+// of sum_j alpha[s][j] ReLU(q[s][j] . k[key]).
 // ------------------------------------------------------------------------------------------
-// grid (ceil(max_live/256), units)
+// grid (ceil(max_live/256), units) read as one list of (tile, unit) pairs, 4 waves; a wave owns 64 keys = 4 tiles of 16 rows (the A operand,
+// kept in registers as packed bf16) and walks over the queries.  One pass of the 16x16x4 product
+// (16 steps over the 64 dims) takes 16 columns = 16 / HS queries x HS head lanes (HS = 8 when
+// H_idx <= 8, else 16); the gated ReLU terms of a query are then added over its HS lanes with
+// shifted adds inside the 16-lane row, so the last lane of each group holds the query's score of
+// the 4 keys of its register rows, and keeps the running maximum.
+template <int HS>
 __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
                                                const int32_t* __restrict__ pos,
                                                const int32_t* __restrict__ len,
@@ -279,55 +286,119 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
                                                const int32_t* __restrict__ q_pos, int n_q, int H_kv,
                                                int C, int H_idx, int max_live,
                                                float* __restrict__ scores) {
+  constexpr int QPP = 16 / HS;   // queries per pass
   __shared__ int s_min[4];
-  const int unit = blockIdx.y, tid = threadIdx.x;
+  __shared__ int s_first[4];
+  // tiles of low slots see the most queries in a prefill event: they are dispatched first, for
+  // every unit, so the launch does not end on a few long workgroups
+  const int units = gridDim.y, bid = blockIdx.y * gridDim.x + blockIdx.x;
+  const int unit = bid % units, tile = bid / units;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, kq = lane >> 4;
   const int b = unit / H_kv;
   const int n = min(len[unit], max_live);
-  if (blockIdx.x == 0 && tid == 0) n_projected[unit] = n;  // the projection kernel ran before
-  const int t0 = blockIdx.x * 256;
+  if (tile == 0 && tid == 0) n_projected[unit] = n;  // the projection kernel ran before
+  const int t0 = tile * 256;
   if (t0 >= n) return;
-  const int slot = t0 + tid;
-  const bool valid = slot < n;
-  const int sl = valid ? slot : n - 1;
-  double k[IM_DI];
-  {
-    const uint4* src = (const uint4*)(Kidx + ((size_t)unit * C + sl) * IM_DI);
+  const int kbase = t0 + 64 * w;
+  // A operands: lane (row l16, kq) holds dims 16 kq .. 16 kq + 15 of its row in each of the 4 tiles
+  // (rows past the end repeat the last live one; their scores are never written)
+  uint4 ka[4][2];
+  int posk[4][4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      uint4 u = src[i];
-      k[8 * i + 0] = (double)bf_lo(u.x); k[8 * i + 1] = (double)bf_hi(u.x);
-      k[8 * i + 2] = (double)bf_lo(u.y); k[8 * i + 3] = (double)bf_hi(u.y);
-      k[8 * i + 4] = (double)bf_lo(u.z); k[8 * i + 5] = (double)bf_hi(u.z);
-      k[8 * i + 6] = (double)bf_lo(u.w); k[8 * i + 7] = (double)bf_hi(u.w);
+  for (int t = 0; t < 4; ++t) {
+    const size_t row = (size_t)unit * C + min(kbase + 16 * t + l16, n - 1);
+    ka[t][0] = *(const uint4*)(Kidx + row * IM_DI + 16 * kq);
+    ka[t][1] = *(const uint4*)(Kidx + row * IM_DI + 16 * kq + 8);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {   // positions of the keys of this lane's result registers
+      const int key = kbase + 16 * t + 4 * r + kq;
+      const int p = pos[(size_t)unit * C + min(key, n - 1)];
+      posk[t][r] = (key < n) ? p : INT_MAX;
     }
   }
-  const int mypos = pos[(size_t)unit * C + sl];
-  // smallest position in this tile: queries older than it see none of the tile's keys
-  int mn = valid ? mypos : INT_MAX;
+  // smallest key position of the workgroup's tile, and the first query that sees it: the walk over
+  // the queries starts there (visibility is decided per key further down)
+  int mn = INT_MAX;
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) mn = min(mn, __shfl_xor(mn, o, 64));
-  if ((tid & 63) == 0) s_min[tid >> 6] = mn;
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) mn = min(mn, posk[t][r]);
+  mn = (int)(wave_min_u((uint32_t)mn ^ 0x80000000u) ^ 0x80000000u);
+  if (lane == 0) s_min[w] = mn;
   __syncthreads();
   const int tile_min = min(min(s_min[0], s_min[1]), min(s_min[2], s_min[3]));
-  double imp = -INFINITY;
-  for (int s = 0; s < n_q; ++s) {
-    const int qp = q_pos[(size_t)b * n_q + s];
-    if (qp < tile_min) continue;
-    const double* __restrict__ qh = qhat + ((size_t)b * n_q + s) * H_idx * IM_DI;
-    const double* __restrict__ al = alpha + ((size_t)b * n_q + s) * H_idx;
-    double a = 0.0;
-    for (int j = 0; j < H_idx; ++j) {
-      double z0 = 0.0, z1 = 0.0;
+  const int32_t* qp_b = q_pos + (size_t)b * n_q;
+  int first = n_q;
+  for (int i = tid; i < n_q; i += 256)
+    if (qp_b[i] >= tile_min) { first = i; break; }
+  first = (int)wave_min_u((uint32_t)first);
+  if (lane == 0) s_first[w] = first;
+  __syncthreads();
+  first = min(min(s_first[0], s_first[1]), min(s_first[2], s_first[3]));
+  float imp[4][4];
 #pragma unroll
-      for (int c = 0; c < IM_DI; c += 2) {
-        z0 = fma(qh[j * IM_DI + c], k[c], z0);
-        z1 = fma(qh[j * IM_DI + c + 1], k[c + 1], z1);
+  for (int t = 0; t < 4; ++t)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) imp[t][r] = -INFINITY;
+  const int jl = l16 % HS, sl = l16 / HS;
+  const bool jv = jl < H_idx;
+#pragma unroll 1
+  for (int s0 = (first / QPP) * QPP; s0 < n_q; s0 += QPP) {
+    const int s = min(s0 + sl, n_q - 1);
+    const bool sv = s0 + sl < n_q;
+    const int qp = qp_b[s];
+    // B operand: lane (column l16 = query sl, head jl; kq) holds dims 16 kq .. 16 kq + 15 of that head
+    double qd[16];
+    {
+      const uint4* src = (const uint4*)(qhat + (((size_t)b * n_q + s) * H_idx + (jv ? jl : 0)) * IM_DI + 16 * kq);
+#pragma unroll
+      for (int m = 0; m < 8; ++m) {
+        const uint4 u = src[m];
+        qd[2 * m] = __longlong_as_double(((long long)u.y << 32) | u.x);
+        qd[2 * m + 1] = __longlong_as_double(((long long)u.w << 32) | u.z);
       }
-      a = fma(al[j], fmax(z0 + z1, 0.0), a);
     }
-    if (mypos <= qp) imp = fmax(imp, a);
+    const double al = (jv && sv) ? alpha[((size_t)b * n_q + s) * H_idx + jl] : 0.0;   // idle lanes add 0
+    im_v4d z[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) z[t] = im_v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int m = 0; m < 16; ++m) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint4 u = ka[t][m >> 3];
+        const uint32_t wd = ((m & 7) < 2) ? u.x : ((m & 7) < 4) ? u.y : ((m & 7) < 6) ? u.z : u.w;
+        const float f = (m & 1) ? bf_hi(wd) : bf_lo(wd);
+        z[t] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)f, qd[m], z[t], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        double v = al * fmax(z[t][r], 0.0);
+        v += dpp_zero_d<0x111, 0xF>(v);
+        v += dpp_zero_d<0x112, 0xF>(v);
+        v += dpp_zero_d<0x114, 0xF>(v);
+        if (HS == 16) v += dpp_zero_d<0x118, 0xF>(v);
+        // meaningful in the last lane of each group of HS: the score of query s for key row 4 r + kq
+        const bool vis = sv && posk[t][r] <= qp;
+        imp[t][r] = vis ? fmaxf(imp[t][r], (float)v) : imp[t][r];
+      }
+    }
   }
-  if (valid) scores[(size_t)unit * C + slot] = (float)imp;
+  // the groups' maxima meet in lane 15 of each row, which writes the 16 keys of its register rows
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float v = imp[t][r];
+      if (HS == 8) v = fmaxf(v, dpp_keep_f<0x118, 0xF>(v));
+      const int key = kbase + 16 * t + 4 * r + kq;
+      if (l16 == 15 && key < n) scores[(size_t)unit * C + key] = v;
+    }
+  }
 }
 
 // ------------------------------------------------------------------------------------------

@@ -271,9 +271,14 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
   const int rows = M * c.n_idx_heads;
   k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, (const bf16_t*)p->norm_q_w, c.rms_eps);
   k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, sqrt((double)(c.n_idx_heads * IM_DI)));
-  k_score<<<dim3((h->max_live + 255) / 256, units), 256, 0, s>>>(
-      (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q, c.n_kv_heads,
-      c.capacity, c.n_idx_heads, h->max_live, scores_out);
+  if (c.n_idx_heads <= 8)
+    k_score<8><<<dim3((h->max_live + 255) / 256, units), 256, 0, s>>>(
+        (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q, c.n_kv_heads,
+        c.capacity, c.n_idx_heads, h->max_live, scores_out);
+  else
+    k_score<16><<<dim3((h->max_live + 255) / 256, units), 256, 0, s>>>(
+        (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q, c.n_kv_heads,
+        c.capacity, c.n_idx_heads, h->max_live, scores_out);
   return launch_check(h, "im_index_score");
 }
 

@@ -43,6 +43,8 @@ def test_cfg1_full_trajectory_fused_decode():
     ("cfg5", dict(batch=1, context=1536, budget=512, decode_steps=4, prefill_chunk=512)),
     ("cfg1", dict(context=40, budget=64, decode_steps=30)),                  # grows to the budget, then evicts
     ("cfg1", dict(context=300, budget=64, decode_steps=3, n_recent=8)),      # recent window forced
+    ("cfg1", dict(n_q_heads=40, context=600, budget=150, decode_steps=3)),   # 10 indexer heads, 5 per group
+    ("cfg1", dict(n_q_heads=16, context=600, budget=150, decode_steps=3)),   # 4 indexer heads, 2 per group
 ])
 def test_reduced_configurations_fused_decode(name, kw):
     w = WORKLOADS[name].scaled(n_layers=1, **kw)
