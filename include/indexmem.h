@@ -190,13 +190,21 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
                        float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream);
 
 /* Kernel timing for benchmarks (not part of the method).  After im_profile_start, every
- * im_decode_step on this handle brackets its main kernel (scoring and attention partials of
- * every 128-key split: the launch that streams the cache) with a pair of HIP events on the
- * launch stream, for at most
- * max_records calls.  im_profile_stop WAITS for `stream`, writes the elapsed milliseconds of the
- * recorded launches to ms_host[0 .. *n_records) (host pointers; ms_host holds max_records floats)
- * and releases the events.  Do not use while the stream is being captured into a graph. */
-int32_t im_profile_start(im_handle* h, int32_t max_records);
+ * im_decode_step on this handle brackets part of its launch sequence (prep kernel, main kernel,
+ * tail kernel) with a pair of HIP events on the launch stream, for at most max_records calls:
+ *   IM_PROFILE_MAIN           the main kernel alone (scoring and attention partials of every
+ *                             128-key split: the launch that streams the cache);
+ *   IM_PROFILE_PREP           the prep kernel alone;
+ *   IM_PROFILE_PREP_AND_MAIN  both, with no event between them.
+ * An event pair around one launch also spans the hand-over between the event and the dispatch;
+ * mean(PREP_AND_MAIN) - mean(PREP) is the main kernel as it runs behind the prep kernel.
+ * im_profile_stop WAITS for `stream`, writes the elapsed milliseconds of the recorded spans to
+ * ms_host[0 .. *n_records) (host pointers; ms_host holds max_records floats) and releases the
+ * events.  Do not use while the stream is being captured into a graph. */
+#define IM_PROFILE_MAIN 0
+#define IM_PROFILE_PREP 1
+#define IM_PROFILE_PREP_AND_MAIN 2
+int32_t im_profile_start(im_handle* h, int32_t max_records, int32_t span);
 int32_t im_profile_stop(im_handle* h, float* ms_host, int32_t* n_records, void* stream);
 
 #ifdef __cplusplus

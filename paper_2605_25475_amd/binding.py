@@ -91,7 +91,7 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     lib.im_decode_step.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, vp, vp, vp, i32,
                                    f32, f32, vp, vp, vp, vp, vp]
     lib.im_profile_start.restype = i32
-    lib.im_profile_start.argtypes = [vp, i32]
+    lib.im_profile_start.argtypes = [vp, i32, i32]
     lib.im_profile_stop.restype = i32
     lib.im_profile_stop.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32), vp]
     _lib = lib
@@ -249,13 +249,17 @@ def im_decode_step(h: Handle, p: Params, st: State, q, x_gate, q_pos, k_new, v_n
                                  _ptr(readout_dbg), _ptr(evicted_slot), _ptr(scores_dbg), _stream()))
 
 
-def im_profile_start(h: Handle, max_records: int) -> None:
+IM_PROFILE_MAIN, IM_PROFILE_PREP, IM_PROFILE_PREP_AND_MAIN = 0, 1, 2
+
+
+def im_profile_start(h: Handle, max_records: int, span: int = IM_PROFILE_MAIN) -> None:
+    """Bracket part of every following im_decode_step's launches with HIP events (see indexmem.h)."""
     h._prof_max = max_records
-    h.check(h.lib.im_profile_start(h.h, max_records))
+    h.check(h.lib.im_profile_start(h.h, max_records, span))
 
 
 def im_profile_stop(h: Handle):
-    """Returns the list of main-kernel durations (ms) recorded since im_profile_start."""
+    """Returns the list of span durations (ms) recorded since im_profile_start."""
     buf = (C.c_float * h._prof_max)()
     n = C.c_int32(0)
     h.check(h.lib.im_profile_stop(h.h, buf, C.byref(n), _stream()))

@@ -24,7 +24,7 @@ struct im_handle {
   int mem_split, attn_chunks, dec_splits;
   // optional kernel timing (im_profile_start / im_profile_stop)
   hipEvent_t* prof_ev;
-  int prof_max, prof_n;
+  int prof_max, prof_n, prof_span;
   char err[256];
 };
 
@@ -159,9 +159,10 @@ void im_destroy(im_handle* h) {
   free(h);
 }
 
-int32_t im_profile_start(im_handle* h, int32_t max_records) {
+int32_t im_profile_start(im_handle* h, int32_t max_records, int32_t span) {
   if (!h) return IM_ERR_INVALID_ARG;
   IM_REQUIRE(max_records >= 1 && max_records <= (1 << 20), "max_records must be in 1..2^20");
+  IM_REQUIRE(span >= IM_PROFILE_MAIN && span <= IM_PROFILE_PREP_AND_MAIN, "span must be one of IM_PROFILE_*");
   release_profile(h);
   h->prof_ev = (hipEvent_t*)calloc(2 * (size_t)max_records, sizeof(hipEvent_t));
   if (!h->prof_ev) return set_err(h, IM_ERR_LAUNCH, "im_profile_start: out of host memory");
@@ -175,6 +176,7 @@ int32_t im_profile_start(im_handle* h, int32_t max_records) {
     }
   }
   h->prof_n = 0;
+  h->prof_span = span;
   return IM_OK;
 }
 
@@ -414,14 +416,17 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
   a.S_alloc = h->dec_splits; a.max_live = h->max_live;
   a.rms_eps = c.rms_eps; a.mem_eps = c.mem_eps; a.scale = c.softmax_scale; a.lambda = lambda; a.eta = eta;
   const int prep_blocks = c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2 + (1 + DEC_MP) * units;
-  k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);
   const int main_blocks = units * (a.S > 0 ? a.S : 1);
   const bool prof = h->prof_ev && h->prof_n < h->prof_max;
-  if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n], s);
+  hipEvent_t ev0 = prof ? h->prof_ev[2 * h->prof_n] : nullptr, ev1 = prof ? h->prof_ev[2 * h->prof_n + 1] : nullptr;
+  if (prof && h->prof_span != IM_PROFILE_MAIN) (void)hipEventRecord(ev0, s);
+  k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);
+  if (prof && h->prof_span == IM_PROFILE_MAIN) (void)hipEventRecord(ev0, s);
+  if (prof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(ev1, s);
 #define IM_DEC_CASE(g)                                              \
   case g:                                                           \
-    k_dec_main<g><<<main_blocks, DEC_MT, 0, s>>>(a, a.qy, a.alpha);    \
-    if (prof) (void)hipEventRecord(h->prof_ev[2 * h->prof_n + 1], s); \
+    k_dec_main<g><<<main_blocks, DEC_MT, 0, s>>>(a, a.qy, a.alpha); \
+    if (prof && h->prof_span != IM_PROFILE_PREP) (void)hipEventRecord(ev1, s); \
     k_dec_tail<g><<<units, DEC_TT, 0, s>>>(a);                      \
     break;
   switch (G) {
