@@ -61,7 +61,7 @@ def algorithmic_bytes(w: Workload) -> dict:
 class Job:
     """All layers of a workload after their prefill eviction, plus pre-generated decode inputs."""
 
-    def __init__(self, w: Workload, n_steps: int, device="cuda", log=lambda s: None):
+    def __init__(self, w: Workload, n_steps: int, device="cuda", log=lambda s: None, tau: int = 0):
         self.w, self.dev = w, device
         cap = w.capacity
         n_q_max = w.context if w.prefill_chunk is None else w.prefill_chunk
@@ -69,7 +69,7 @@ class Job:
                         n_idx_heads=w.n_idx_heads, n_sink=w.n_sink, n_recent=w.n_recent,
                         fold_block=w.fold_block, max_queries=n_q_max)
         self.handle = im.Handle(cfg, device)
-        self.layers, self.dec = [], []
+        self.layers, self.dec, self.qwin, self.tau = [], [], [], tau
         L = w.context
         assert n_steps <= w.decode_steps, "the workload defines fewer decode steps"
         for li in range(w.n_layers):
@@ -93,12 +93,17 @@ class Job:
             qd = Q[:, L:].permute(1, 0, 2, 3).contiguous().unsqueeze(2)         # [S, B, 1, H, D]
             self.layers.append(layer)
             self.dec.append((kd, vd, qd))
+            if tau:   # the query set of every compression interval, [B, tau, H, D] each
+                self.qwin.append([Q[:, L + k * tau:L + (k + 1) * tau].contiguous() for k in range(n_steps // tau)])
             del K, V, Q
             torch.cuda.synchronize()
             log(f"layer {li + 1}/{w.n_layers} prefilled")
         self.pos = (torch.arange(L, L + n_steps, dtype=torch.int32, device=device)
                     .view(n_steps, 1, 1).repeat(1, w.batch, 1).contiguous())
-        im.im_set_max_live(self.handle, min(cap, w.budget + 1))
+        im.im_set_max_live(self.handle, min(cap, w.budget + max(1, tau)))
+        if tau:
+            self.posw = [torch.arange(L + k * tau, L + (k + 1) * tau, dtype=torch.int32, device=device)
+                         .repeat(w.batch, 1).contiguous() for k in range(n_steps // tau)]
         assert im.im_query_status(self.handle) == 0
 
     def step(self, s: int, path: str = "fused"):
@@ -108,12 +113,19 @@ class Job:
         for li, layer in enumerate(self.layers):
             kd, vd, qd = self.dec[li]
             q = qd[s]
-            if path == "fused":
+            if path == "periodic":
+                layer.attend_step(kd[s], vd[s], pos, q.view(w.batch, w.n_q_heads, -1), debug=False)
+            elif path == "fused":
                 layer.decode_step(kd[s], vd[s], pos.view(w.batch), q.view(w.batch, w.n_q_heads, -1),
                                   q.view(w.batch, -1), pos.view(w.batch), w.budget, w.lam, w.eta)
             else:
                 layer.step(kd[s], vd[s], pos, q, q.view(w.batch, 1, -1), pos, q.view(w.batch, w.n_q_heads, -1),
                            w.budget, w.lam, w.eta)
+        if path == "periodic" and (s + 1) % self.tau == 0:
+            k = s // self.tau
+            for li, layer in enumerate(self.layers):
+                qw = self.qwin[li][k]
+                layer.compress(qw, qw.view(w.batch, self.tau, -1), self.posw[k], w.budget, w.lam, w.eta)
 
 
 def cpu_baseline(w: Workload, budget_s: float = 20.0) -> dict:
@@ -168,8 +180,11 @@ def main() -> None:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
-    ap.add_argument("--path", default="fused", choices=["fused", "steps"],
-                    help="fused: im_decode_step (2 launches per layer); steps: the six separate calls")
+    ap.add_argument("--path", default="fused", choices=["fused", "steps", "periodic"],
+                    help="fused: im_decode_step (3 launches per layer); steps: the six separate calls; "
+                         "periodic: the paper's decode schedule (append + attention every step, one "
+                         "compression event per --tau steps with the interval's queries as the query set)")
+    ap.add_argument("--tau", type=int, default=128, help="compression interval of --path periodic")
     ap.add_argument("--no-graph", action="store_true", help="launch the fused path eagerly")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (torch copy_) so that a counter run "
@@ -185,9 +200,14 @@ def main() -> None:
     w = WORKLOADS[a.workload]
     log = (lambda s: None) if a.quiet else (lambda s: print("[bench] " + s, file=sys.stderr, flush=True))
     torch.cuda.set_device(0)
-    n_total = a.warmup + 2 * a.steps
+    tau = a.tau if a.path == "periodic" else 0
+    if tau:
+        if a.steps % tau or a.warmup % tau:
+            sys.exit(f"bench.py: with --path periodic, --steps and --warmup must be multiples of --tau ({tau})")
+        assert w.budget + tau <= w.capacity
+    n_total = a.warmup + (1 if tau else 2) * a.steps
     t_setup = time.perf_counter()
-    job = Job(w, n_total, log=log)
+    job = Job(w, n_total, log=log, tau=tau)
     torch.cuda.synchronize()
     log(f"setup (generation + prefill eviction of {w.n_layers} layers) {time.perf_counter() - t_setup:.1f} s")
 
@@ -197,7 +217,7 @@ def main() -> None:
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    use_graph = (a.path == "fused") and not a.no_graph
+    use_graph = (a.path in ("fused", "periodic")) and not a.no_graph
 
     def run(s0, s1):
         for s in range(s0, s1):
@@ -273,7 +293,8 @@ def main() -> None:
         "warmup": a.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n_q_heads}/{w.n_kv_heads}x{w.head_dim} heads, {w.n_layers} layers, "
-                               f"batch {w.batch}, context {w.context} -> budget {w.budget}, one eviction per decode step",
+                               f"batch {w.batch}, context {w.context} -> budget {w.budget}, "
+                               + (f"one compression event per {tau} decode steps" if tau else "one eviction per decode step"),
                    "layers": w.n_layers, "batch": w.batch, "budget": w.budget, "context": w.context,
                    "path": a.path, "hip_graph": use_graph,
                    "algorithmic_bytes_per_step": ab["per_layer_step"] * w.n_layers,

@@ -189,6 +189,16 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
                        const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,
                        float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream);
 
+/* One token of the periodic decode schedule (Section 4, "Models and Evaluation Setup": attention
+ * every step, compression once per interval), fused into three launches: exactly
+ *   im_append_kv(n_new = 1) -> im_decode_attn_with_readout
+ * Nothing is scored or evicted; the new entry's indexer key is computed on the way (n_projected
+ * follows len), so the interval's im_index_score has nothing left to project.  The caller bounds
+ * the live length with im_set_max_live (budget + interval).  Arguments as in im_decode_step. */
+int32_t im_attend_step(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                       const void* k_new, const void* v_new, const int32_t* pos_new, void* out,
+                       float* readout_dbg, void* stream);
+
 /* Kernel timing for benchmarks (not part of the method).  After im_profile_start, every
  * im_decode_step on this handle brackets part of its launch sequence (prep kernel, main kernel,
  * tail kernel) with a pair of HIP events on the launch stream, for at most max_records calls:

@@ -69,6 +69,7 @@ struct DecArgs {
   float* qm;          // per unit: the eviction-independent terms of the memory readout (DEC_QM floats per head)
   // scalars
   int B, H, H_kv, C, H_idx, gate_in, n_sink, n_recent, budget, S, S_alloc, max_live;
+  int no_score;       // attend-only step: nothing is scored, excluded or evicted
   float rms_eps, mem_eps, scale, lambda, eta;
 };
 
@@ -372,7 +373,9 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   // their logits are masked and their probabilities are zero further down
   uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
   int mypos = 0;
-  if (scoring) {
+  if (scoring && a.no_score) {
+    if (lane == 0) { sm.c64[wl] = ~0ull; sm.cslot[wl] = -1; }   // no candidate: nothing is left out
+  } else if (scoring) {
     // ================= scoring waves: tiles 2 wl, 2 wl + 1 (keys 32 wl .. 32 wl + 31) =================
     // their few loads go ahead of the attention waves' many: the scoring chain is the longer one
     __builtin_amdgcn_s_setprio(3);
@@ -708,7 +711,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     crec[2] = (uint32_t)(k0 + cl);
     crec[3] = (uint32_t)n;
   }
-  if (tid < G) crec[4 + tid] = __float_as_uint(sm.clog[tid]);
+  if (tid < G) crec[4 + tid] = __float_as_uint(cl >= 0 ? sm.clog[tid] : -INFINITY);   // -inf: no candidate
   if (!scoring) {
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -727,9 +730,11 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
 #define DEC_TT 1024   // threads of a tail workgroup: the tail is a chain of short phases, so it is
                       // spread thin over 16 waves of one CU
 
-template <int G>
+// CHW: splits staged per round; a thread of a head group of up to 4 handles CHW / 2 of them per
+// round, so the host picks the smallest CHW that holds the launch's splits
+template <int G, int CHW>
 struct DecTailSmem {
-  static constexpr int CH = (G <= 4) ? 16 : 4;   // splits staged per round
+  static constexpr int CH = CHW;                 // splits staged per round
   static constexpr int NS = (G <= 4) ? 2 : 1;    // threads sharing one output in the merge
   float pst[CH][G][DEC_REC];                      // partial records of the staged splits
   uint32_t cst[CH + 1][DEC_CAND];                 // their candidate records (+ the last-slot record)
@@ -767,10 +772,10 @@ __device__ __forceinline__ void dec_stage(float* dst, const float* __restrict__ 
   }
 }
 
-template <int G>
-__device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem<G>& sm) {
-  constexpr int CH = DecTailSmem<G>::CH;
-  constexpr int NS = DecTailSmem<G>::NS;
+template <int G, int CHW>
+__device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem<G, CHW>& sm) {
+  constexpr int CH = DecTailSmem<G, CHW>::CH;
+  constexpr int NS = DecTailSmem<G, CHW>::NS;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int b = u / a.H_kv, h = u % a.H_kv;
   DEC_STAMP(8);
@@ -955,7 +960,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       const int sp = part * PER + k;
       const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
       const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
-      const bool stays = sp < cn0 && sp != e_split;
+      const bool stays = sp < cn0 && sp != e_split && r3 != -INFINITY;   // -inf: the split left nothing out
       cl[k] = stays ? r3 : -INFINITY;
       cv[k] = stays ? r4 : 0.f;
     }
@@ -996,7 +1001,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
       const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
       const bool on = sp < cn;
-      const bool stays = on && (c0 + sp != e_split);
+      const bool stays = on && (c0 + sp != e_split) && r3 != -INFINITY;
       pm[k] = on ? r0 : -1e30f;
       plv[k] = on ? r1 : 0.f;
       po[k] = on ? r2 : 0.f;
@@ -1109,8 +1114,8 @@ __global__ __launch_bounds__(DEC_MT, 4) void k_dec_main(const DecArgs a, const d
 }
 
 // grid: units
-template <int G>
+template <int G, int CHW>
 __global__ __launch_bounds__(DEC_TT) void k_dec_tail(const DecArgs a) {
-  __shared__ __attribute__((aligned(16))) DecTailSmem<G> sm;
-  dec_tail<G>(a, blockIdx.x, sm);
+  __shared__ __attribute__((aligned(16))) DecTailSmem<G, CHW> sm;
+  dec_tail<G, CHW>(a, blockIdx.x, sm);
 }

@@ -111,6 +111,20 @@ bool params_ok(const im_params* p) { return p && p->Uq && p->G && p->Uk && p->Wt
 #define IM_REQUIRE(cond, msg) \
   do { if (!(cond)) return set_err(h, IM_ERR_INVALID_ARG, "%s: %s", __func__, msg); } while (0)
 
+// the tail kernel stages CHW split records per round: the smallest variant that holds the launch's
+// splits (more splits than the largest variant are merged in several rounds)
+template <int G>
+void launch_tail(const DecArgs& a, int units, hipStream_t s) {
+  if constexpr (G <= 4) {
+    if (a.S <= 8) k_dec_tail<G, 8><<<units, DEC_TT, 0, s>>>(a);
+    else if (a.S <= 16) k_dec_tail<G, 16><<<units, DEC_TT, 0, s>>>(a);
+    else k_dec_tail<G, 24><<<units, DEC_TT, 0, s>>>(a);
+  } else {
+    if (a.S <= 4) k_dec_tail<G, 4><<<units, DEC_TT, 0, s>>>(a);
+    else k_dec_tail<G, 8><<<units, DEC_TT, 0, s>>>(a);
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -375,20 +389,22 @@ int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_s
   return launch_check(h, "im_decode_attn_with_readout");
 }
 
-int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, const void* q,
-                       const void* x_gate, const int32_t* q_pos, const void* k_new, const void* v_new,
-                       const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,
-                       float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream) {
+static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                             const void* x_gate, const int32_t* q_pos, const void* k_new, const void* v_new,
+                             const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,
+                             float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream,
+                             const bool no_score, const char* what) {
   if (!h) return IM_ERR_INVALID_ARG;
   IM_REQUIRE(params_ok(p), "params has a NULL pointer");
   IM_REQUIRE(state_ok(st), "state has a NULL pointer");
-  IM_REQUIRE(q && x_gate && q_pos && k_new && v_new && pos_new && out, "an input / output pointer is NULL");
+  IM_REQUIRE(q && k_new && v_new && pos_new && out, "an input / output pointer is NULL");
+  IM_REQUIRE(no_score || (x_gate && q_pos), "x_gate / q_pos is NULL");
   IM_REQUIRE(budget >= h->cfg.n_sink + h->cfg.n_recent, "budget is below n_sink + n_recent");
   IM_REQUIRE(budget <= h->cfg.capacity, "budget exceeds capacity");
   IM_REQUIRE(lambda > 0.f && lambda <= 1.f, "lambda must be in (0, 1]");
   IM_REQUIRE(eta > 0.f, "eta must be > 0");
   const im_config& c = h->cfg;
-  if (c.batch > 64) return set_err(h, IM_ERR_UNSUPPORTED, "im_decode_step: batch above 64");
+  if (c.batch > 64) return set_err(h, IM_ERR_UNSUPPORTED, "%s: batch above 64", what);
   hipStream_t s = (hipStream_t)stream;
   int rc = ensure_ws(h, s);
   if (rc) return rc;
@@ -411,11 +427,14 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
   a.gate_in = c.gate_in_dim; a.n_sink = c.n_sink; a.n_recent = c.n_recent; a.budget = budget;
   // 128-key splits for the main kernel; a single key beyond a multiple of 128 (the steady state with
   // a budget that is a multiple of 128) is left to the tail kernel instead of a one-key split
-  a.S = (h->max_live % DEC_KEYS == 1 && h->max_live > 1) ? h->max_live / DEC_KEYS
-                                                         : (h->max_live + DEC_KEYS - 1) / DEC_KEYS;
+  a.S = (!no_score && h->max_live % DEC_KEYS == 1 && h->max_live > 1) ? h->max_live / DEC_KEYS
+                                                                      : (h->max_live + DEC_KEYS - 1) / DEC_KEYS;
+  a.no_score = no_score ? 1 : 0;
   a.S_alloc = h->dec_splits; a.max_live = h->max_live;
   a.rms_eps = c.rms_eps; a.mem_eps = c.mem_eps; a.scale = c.softmax_scale; a.lambda = lambda; a.eta = eta;
-  const int prep_blocks = c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2 + (1 + DEC_MP) * units;
+  // the per-unit blocks come first in the prep kernel's block order: an attend-only step launches
+  // just those (no query-side indexer projections)
+  const int prep_blocks = (no_score ? 0 : c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2) + (1 + DEC_MP) * units;
   const int main_blocks = units * (a.S > 0 ? a.S : 1);
   const bool prof = h->prof_ev && h->prof_n < h->prof_max;
   hipEvent_t ev0 = prof ? h->prof_ev[2 * h->prof_n] : nullptr, ev1 = prof ? h->prof_ev[2 * h->prof_n + 1] : nullptr;
@@ -427,7 +446,7 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
   case g:                                                           \
     k_dec_main<g><<<main_blocks, DEC_MT, 0, s>>>(a, a.qy, a.alpha); \
     if (prof && h->prof_span != IM_PROFILE_PREP) (void)hipEventRecord(ev1, s); \
-    k_dec_tail<g><<<units, DEC_TT, 0, s>>>(a);                      \
+    launch_tail<g>(a, units, s);                                    \
     break;
   switch (G) {
     IM_DEC_CASE(1) IM_DEC_CASE(2) IM_DEC_CASE(3) IM_DEC_CASE(4)
@@ -436,7 +455,24 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
   }
 #undef IM_DEC_CASE
   if (prof) h->prof_n++;
-  return launch_check(h, "im_decode_step");
+  return launch_check(h, what);
+}
+
+int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                       const void* x_gate, const int32_t* q_pos, const void* k_new, const void* v_new,
+                       const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,
+                       float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream) {
+  return decode_launch(h, p, st, q, x_gate, q_pos, k_new, v_new, pos_new, budget, lambda, eta, out,
+                       readout_dbg, evicted_slot, scores_dbg, stream, false, "im_decode_step");
+}
+
+int32_t im_attend_step(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                       const void* k_new, const void* v_new, const int32_t* pos_new, void* out,
+                       float* readout_dbg, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  // budget = capacity: no unit can be above it, so nothing is evicted; lambda, eta are unused
+  return decode_launch(h, p, st, q, nullptr, nullptr, k_new, v_new, pos_new, h->cfg.capacity, 1.f, 1.f, out,
+                       readout_dbg, nullptr, nullptr, stream, true, "im_attend_step");
 }
 
 }  // extern "C"

@@ -35,6 +35,27 @@ class Layer:
         B.im_decode_attn_with_readout(h, p, st, q_attn, self.out, self.readout)
         return self.out
 
+    def attend_step(self, k_new, v_new, pos_new, q_attn, fused=True, debug=True):
+        """One token of the periodic schedule (Section 4, setup: compress every tau steps): append,
+        then attention + readout over everything cached; nothing is scored or evicted.  fused: the
+        three-launch entry point; else the two separate calls."""
+        if fused:
+            B.im_attend_step(self.h, self.p, self.st, q_attn, k_new, v_new, pos_new.view(-1), self.out,
+                             self.readout if debug else None)
+        else:
+            B.im_append_kv(self.h, self.st, k_new, v_new, pos_new)
+            B.im_decode_attn_with_readout(self.h, self.p, self.st, q_attn, self.out, self.readout)
+        return self.out
+
+    def compress(self, q_win, x_gate_win, q_pos_win, budget, lam, eta):
+        """The compression event of the periodic schedule: the queries of the interval score the
+        cache, the cache is cut back to the budget, the evicted entries go to the memory."""
+        h, p, st = self.h, self.p, self.st
+        B.im_index_score(h, p, st, q_win, x_gate_win, q_pos_win, self.scores)
+        B.im_topb_select(h, self.scores, st, budget, self.keep_idx, self.evict_idx, self.n_keep, self.n_evict)
+        B.im_memory_update(h, p, st, self.evict_idx, self.n_evict, lam, eta)
+        B.im_compact_kv(h, st, self.keep_idx, self.n_keep, self.evict_idx, self.n_evict)
+
     def decode_step(self, k_new, v_new, pos_new, q, x_gate, q_pos, budget, lam, eta, debug=False):
         """The same step for one new token per sequence through the fused entry point."""
         B.im_decode_step(self.h, self.p, self.st, q, x_gate, q_pos, k_new, v_new, pos_new, budget, lam, eta,

@@ -114,7 +114,7 @@ class LockStep:
         if check:
             self.compare(scores, keep, evict, out, res, tag, fused=True)
 
-    def compare(self, scores, keep, evict, out, res, tag, fused=False):
+    def compare(self, scores, keep, evict, out, res, tag, fused=False, lists=True, outputs=True):
         w, g = self.w, self.gpu
         G = w.group
         n_keep = g.n_keep.cpu().numpy(); n_evict = g.n_evict.cpu().numpy()
@@ -130,35 +130,86 @@ class LockStep:
         for ib, b in enumerate(self.batch_ids):
             for ih, h in enumerate(self.kv_heads):
                 u = f"{tag} unit(b={b},h={h})"
-                kr, er = keep[ib][ih], evict[ib][ih]
-                n_before = len(kr) + len(er)
-                # scores: same fp32 value (a mismatch is reported with its size)
-                s_ref = scores[ib, ih, :n_before]; s_gpu = sc[b, h, :n_before].astype(np.float64)
-                same = (s_ref == s_gpu) | (np.isneginf(s_ref) & np.isneginf(s_gpu))
-                assert same.all(), (f"{u}: {int((~same).sum())} of {n_before} scores differ, max "
-                                    f"{np.nanmax(np.abs(np.where(same, 0, s_ref - s_gpu))):.3e}")
-                if fused:
-                    assert len(er) <= 1, u
-                    want_e = int(er[0]) if len(er) else -1
-                    assert evicted[b, h] == want_e, f"{u}: evicted slot {evicted[b, h]} != {want_e}"
-                else:
-                    assert n_keep[b, h] == len(kr) and n_evict[b, h] == len(er), u
-                    assert np.array_equal(keep_idx[b, h, :len(kr)], kr), f"{u}: keep list differs"
-                    assert np.array_equal(evict_idx[b, h, :len(er)], er), f"{u}: evict list differs"
+                if lists:
+                    kr, er = keep[ib][ih], evict[ib][ih]
+                    n_before = len(kr) + len(er)
+                    # scores: same fp32 value (a mismatch is reported with its size)
+                    s_ref = scores[ib, ih, :n_before]; s_gpu = sc[b, h, :n_before].astype(np.float64)
+                    same = (s_ref == s_gpu) | (np.isneginf(s_ref) & np.isneginf(s_gpu))
+                    assert same.all(), (f"{u}: {int((~same).sum())} of {n_before} scores differ, max "
+                                        f"{np.nanmax(np.abs(np.where(same, 0, s_ref - s_gpu))):.3e}")
+                    if fused:
+                        assert len(er) <= 1, u
+                        want_e = int(er[0]) if len(er) else -1
+                        assert evicted[b, h] == want_e, f"{u}: evicted slot {evicted[b, h]} != {want_e}"
+                    else:
+                        assert n_keep[b, h] == len(kr) and n_evict[b, h] == len(er), u
+                        assert np.array_equal(keep_idx[b, h, :len(kr)], kr), f"{u}: keep list differs"
+                        assert np.array_equal(evict_idx[b, h, :len(er)], er), f"{u}: evict list differs"
                 n = int(self.ref.len[ib, ih])
-                assert lens[b, h] == n and nproj[b, h] == n, u
+                assert lens[b, h] == n, u
+                if lists:
+                    assert nproj[b, h] == n, u
                 assert np.array_equal(pos[b, h, :n], self.ref.pos[ib, ih, :n]), f"{u}: positions"
                 assert np.array_equal(f64(st.K[b, h, :n]), self.ref.K[ib, ih, :n]), f"{u}: K rows"
                 assert np.array_equal(f64(st.V[b, h, :n]), self.ref.V[ib, ih, :n]), f"{u}: V rows"
-                assert np.array_equal(f64(st.Kidx[b, h, :n]), self.ref.Kidx[ib, ih, :n]), f"{u}: indexer keys"
+                if lists:   # (rows appended since the last scoring call have no indexer key yet)
+                    assert np.array_equal(f64(st.Kidx[b, h, :n]), self.ref.Kidx[ib, ih, :n]), f"{u}: indexer keys"
                 assert_state_close(u + " M", Mg[b, h], self.ref.M[ib, ih])
                 assert_state_close(u + " b", bg[b, h], self.ref.b[ib, ih])
-                assert_out_close(u + " out", out_g[b, h], out[ib, ih])
-                rr = res[ib, ih]
-                dmax = float(np.max(np.abs(res_g[b, h] - rr)))
-                assert dmax <= 1e-3 * float(np.max(np.abs(rr))) + 1e-30, f"{u}: readout diff {dmax:.3e}"
+                if outputs:
+                    assert_out_close(u + " out", out_g[b, h], out[ib, ih])
+                    rr = res[ib, ih]
+                    dmax = float(np.max(np.abs(res_g[b, h] - rr)))
+                    assert dmax <= 1e-3 * float(np.max(np.abs(rr))) + 1e-30, f"{u}: readout diff {dmax:.3e}"
+
+    def window(self, t0: int, tau: int, budget: int, tag: str, fused=True):
+        """The paper's decode schedule (Section 4, setup): tau tokens are appended and attended to one
+        by one, then the interval's queries score the cache and it is cut back to `budget`."""
+        w, dev = self.w, self.dev
+        d = lambda x: x.to(dev)
+        bi_t = torch.tensor(self.batch_ids, device=self.K.device)
+        hs_t = torch.tensor(self.kv_heads, device=self.K.device)
+        sel = lambda x: f64(x.index_select(0, bi_t).index_select(1, hs_t))
+        bi = self.batch_ids
+        for t in range(t0, t0 + tau):
+            k_new = self.K[:, :, t:t + 1].contiguous(); v_new = self.V[:, :, t:t + 1].contiguous()
+            q_attn = self.Q[:, t].contiguous()
+            pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+            self.gpu.attend_step(d(k_new), d(v_new), d(pos), d(q_attn), fused=fused)
+            torch.cuda.synchronize()
+            self.ref.append_kv(sel(k_new), sel(v_new), pos.numpy()[bi])
+            out, res = self.ref.decode_attn_with_readout(f64(q_attn.index_select(0, bi_t)))
+            self.compare(None, None, None, out, res, f"{tag} attend@{t}", lists=False)
+            if fused:   # the fused entry point projects the new key on the way
+                assert np.array_equal(self.gpu.st.n_projected.cpu().numpy(), self.gpu.st.len.cpu().numpy())
+        q_win = self.Q[:, t0:t0 + tau].contiguous()
+        posw = torch.arange(t0, t0 + tau, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+        qd = d(q_win)
+        self.gpu.compress(qd, qd.view(w.batch, tau, -1), d(posw), budget, w.lam, w.eta)
+        torch.cuda.synchronize()
+        qn = f64(q_win.index_select(0, bi_t))
+        scores = self.ref.index_score(qn, qn.reshape(len(bi), tau, -1), posw.numpy()[bi])
+        keep, evict = self.ref.topb_select(scores, budget)
+        self.ref.memory_update(evict, w.lam, w.eta)
+        self.ref.compact_kv(keep, evict)
+        self.compare(scores, keep, evict, None, None, f"{tag} compress@{t0 + tau}", outputs=False)
 
     # -- schedules --------------------------------------------------------------------------------
+    def run_window_schedule(self, tau: int, n_windows: int, fused=True):
+        """Prefill eviction, then n_windows compression intervals of tau tokens each."""
+        w = self.w
+        L = w.context
+        if w.prefill_chunk is None:
+            self.event(0, L, w.budget, "prefill")
+        else:
+            for c0 in range(0, L, w.prefill_chunk):
+                self.event(c0, min(L, c0 + w.prefill_chunk), w.budget, f"chunk@{c0}")
+        im.im_set_max_live(self.handle, min(self.cap, w.budget + tau))
+        for k in range(n_windows):
+            self.window(L + k * tau, tau, w.budget, f"window {k}", fused=fused)
+        assert im.im_query_status(self.handle) == 0
+
     def run_schedule(self, decode_steps=None, fused_decode=False):
         w = self.w
         steps = w.decode_steps if decode_steps is None else decode_steps

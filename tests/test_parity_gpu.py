@@ -40,6 +40,7 @@ def test_cfg1_full_trajectory_fused_decode():
     ("cfg3", dict(batch=2, context=1500, budget=333, decode_steps=4)),
     ("cfg4", dict(batch=3, context=1300, budget=130, decode_steps=4)),       # 7 query heads per KV head
     ("cfg4", dict(batch=2, context=700, budget=128, decode_steps=3)),        # n = 129: a one-key last split
+    ("cfg4", dict(batch=1, context=1500, budget=1200, decode_steps=3)),      # 10 splits: two staging rounds in the tail
     ("cfg5", dict(batch=1, context=1536, budget=512, decode_steps=4, prefill_chunk=512)),
     ("cfg1", dict(context=40, budget=64, decode_steps=30)),                  # grows to the budget, then evicts
     ("cfg1", dict(context=300, budget=64, decode_steps=3, n_recent=8)),      # recent window forced
@@ -49,6 +50,21 @@ def test_cfg1_full_trajectory_fused_decode():
 def test_reduced_configurations_fused_decode(name, kw):
     w = WORKLOADS[name].scaled(n_layers=1, **kw)
     LockStep(w, capacity=max(w.capacity, w.budget + 2)).run_schedule(fused_decode=True)
+
+
+@pytest.mark.parametrize("name,kw,tau,n_win", [
+    ("cfg1", dict(context=600, budget=200, decode_steps=96), 32, 3),
+    ("cfg1", dict(context=500, budget=160, decode_steps=80, n_recent=16), 40, 2),   # recent window kept
+    ("cfg4", dict(batch=2, context=700, budget=130, decode_steps=128), 128, 1),      # the paper's tau
+    ("cfg3", dict(batch=1, context=900, budget=300, decode_steps=48), 24, 2),
+])
+@pytest.mark.parametrize("fused", [True, False])
+def test_periodic_compression_schedule(name, kw, tau, n_win, fused):
+    # Section 4 (setup): attention every step, compression once per interval with the interval's
+    # queries as the query set; the cache grows to budget + tau between compressions
+    w = WORKLOADS[name].scaled(n_layers=1, **kw)
+    ls = LockStep(w, capacity=max(w.context, w.budget + tau), max_queries=max(w.context, tau))
+    ls.run_window_schedule(tau, n_win, fused=fused)
 
 
 def test_fused_decode_ties_evict_newest_then_largest_slot():
