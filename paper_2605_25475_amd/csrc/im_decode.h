@@ -346,12 +346,14 @@ struct DecSplitSmem {
 // attention partial; waves 4-7 stream the indexer keys (16 KB), score them and find the split's
 // last-ranked entry while the K / V rows are still arriving.  The two roles meet at the first
 // workgroup barrier, when the attention waves have issued their loads.
-template <int G>
+// SCORE = false is the attend-only step: no scoring waves (the workgroup is the 4 attention waves
+// alone, so twice as many fit on a CU), nothing is left out of the partial.
+template <int G, bool SCORE>
 __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const int s, DecSplitSmem& sm,
                                           const double* __restrict__ qy, const double* __restrict__ alpha) {
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int wl = w & 3;                 // wave within its role
-  const bool scoring = w >= 4;          // wave-uniform role
+  const bool scoring = SCORE && w >= 4; // wave-uniform role
   const int b = u / a.H_kv, h = u % a.H_kv;
   const int n_old = a.len[u];
   const int n = min(n_old + ((n_old + 1 <= a.C) ? 1 : 0), a.max_live);
@@ -373,9 +375,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   // their logits are masked and their probabilities are zero further down
   uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
   int mypos = 0;
-  if (scoring && a.no_score) {
-    if (lane == 0) { sm.c64[wl] = ~0ull; sm.cslot[wl] = -1; }   // no candidate: nothing is left out
-  } else if (scoring) {
+  if (!SCORE && tid < 4) { sm.c64[tid] = ~0ull; sm.cslot[tid] = -1; }   // no candidate: nothing is left out
+  if (scoring) {
     // ================= scoring waves: tiles 2 wl, 2 wl + 1 (keys 32 wl .. 32 wl + 31) =================
     // their few loads go ahead of the attention waves' many: the scoring chain is the longer one
     __builtin_amdgcn_s_setprio(3);
@@ -623,7 +624,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         for (int c = 0; c < 4; ++c) *(uint4*)(lrec + DEC_CAND_K + 16 * c + 4 * kq) = kf[tt][c];
       }
     }
-  } else if (do_x_any && tid - 256 < G) {
+  } else if (SCORE && do_x_any && tid - 256 < G) {
     // the leftover key's logits: the 4 scoring waves' partial dot products
     const int j = tid - 256;
     lrec[4 + j] = __float_as_uint((sm.xlp[0][j] + sm.xlp[1][j] + sm.xlp[2][j] + sm.xlp[3][j]) * a.scale);
@@ -691,7 +692,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     }
     __syncthreads();
     const int nj = (G - j0 < 4) ? G - j0 : 4;
-    for (int idx = tid; idx < nj * IM_D; idx += DEC_MT) {
+    for (int idx = tid; idx < nj * IM_D; idx += (SCORE ? DEC_MT : DEC_MT / 2)) {
       const int jj = idx >> 7, d = idx & 127, j = j0 + jj;
       float o = 0.f;
 #pragma unroll
@@ -1107,10 +1108,18 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
 // grid: units * S blocks; consecutive blocks take different units, the short last splits come last
 template <int G>
 __global__ __launch_bounds__(DEC_MT, 4) void k_dec_main(const DecArgs a, const double* __restrict__ qy,
-                                                     const double* __restrict__ alpha) {
+                                                        const double* __restrict__ alpha) {
   __shared__ __attribute__((aligned(16))) DecSplitSmem sm;
   const int U = a.B * a.H_kv;
-  dec_split<G>(a, blockIdx.x % U, blockIdx.x / U, sm, qy, alpha);
+  dec_split<G, true>(a, blockIdx.x % U, blockIdx.x / U, sm, qy, alpha);
+}
+
+// the attend-only variant: same grid, 4 waves per workgroup
+template <int G>
+__global__ __launch_bounds__(DEC_MT / 2, 4) void k_att_main(const DecArgs a) {
+  __shared__ __attribute__((aligned(16))) DecSplitSmem sm;
+  const int U = a.B * a.H_kv;
+  dec_split<G, false>(a, blockIdx.x % U, blockIdx.x / U, sm, nullptr, nullptr);
 }
 
 // grid: units

@@ -193,6 +193,76 @@ __global__ __launch_bounds__(256) void k_gemm_nt_f64(const bf16_t* __restrict__ 
   }
 }
 
+// The same product on the fp64 matrix cores, for Kd % 32 == 0.  A workgroup is 2 x 2 waves; a wave
+// owns TM x TN tiles of 16 x 16 outputs and streams its 16 TM rows of A and 16 TN rows of B from
+// L2 in 32-wide chunks (lane (l16, kq) loads the 8 values k = 32 c + 8 kq .. + 7 of row l16 of a
+// tile; step e of the chunk contracts k = 32 c + 8 kq + e over the 4 kq).  Result register r of
+// lane (l16, kq) is C[row 4 r + kq of the A tile][row l16 of the B tile].
+// grid (ceil(N / (32 TN)), ceil(M / (32 TM))).
+template <int TM, int TN>
+__global__ __launch_bounds__(256) void k_gemm_nt_mfma(const bf16_t* __restrict__ A,
+                                                      const bf16_t* __restrict__ B,
+                                                      double* __restrict__ Cm, int M, int N, int Kd) {
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l16 = lane & 15, kq = lane >> 4;
+  const int m0 = (blockIdx.y * 2 + (w >> 1)) * 16 * TM, n0 = (blockIdx.x * 2 + (w & 1)) * 16 * TN;
+  if (m0 >= M || n0 >= N) return;   // wave-uniform; no barrier in this kernel
+  const bf16_t* ap[TM];
+  const bf16_t* bp[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) ap[i] = A + (size_t)min(m0 + 16 * i + l16, M - 1) * Kd + 8 * kq;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) bp[j] = B + (size_t)min(n0 + 16 * j + l16, N - 1) * Kd + 8 * kq;
+  im_v4d acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) acc[i][j] = im_v4d{0.0, 0.0, 0.0, 0.0};
+  for (int k0 = 0; k0 < Kd; k0 += 64) {
+    uint4 au[2][TM], bu[2][TN];
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      const int k = (k0 + 32 * c < Kd) ? k0 + 32 * c : k0;   // an absent second chunk repeats the first, unused
+#pragma unroll
+      for (int i = 0; i < TM; ++i) au[c][i] = *(const uint4*)(ap[i] + k);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bu[c][j] = *(const uint4*)(bp[j] + k);
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      if (k0 + 32 * c < Kd) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          double av[TM], bv[TN];
+#pragma unroll
+          for (int i = 0; i < TM; ++i) {
+            const uint32_t wd = (e < 2) ? au[c][i].x : (e < 4) ? au[c][i].y : (e < 6) ? au[c][i].z : au[c][i].w;
+            av[i] = (double)((e & 1) ? bf_hi(wd) : bf_lo(wd));
+          }
+#pragma unroll
+          for (int j = 0; j < TN; ++j) {
+            const uint32_t wd = (e < 2) ? bu[c][j].x : (e < 4) ? bu[c][j].y : (e < 6) ? bu[c][j].z : bu[c][j].w;
+            bv[j] = (double)((e & 1) ? bf_hi(wd) : bf_lo(wd));
+          }
+#pragma unroll
+          for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+              acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[i], bv[j], acc[i][j], 0, 0, 0);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = m0 + 16 * i + 4 * r + kq, n = n0 + 16 * j + l16;
+        if (m < M && n < N) Cm[(size_t)m * N + n] = acc[i][j][r];
+      }
+}
+
 // Few rows (decode): every workgroup owns 2 rows of B and streams them once for all M rows of A.
 // grid (ceil(N/2)); Kd % 8 == 0.
 __global__ __launch_bounds__(256) void k_gemv_nt_f64(const bf16_t* __restrict__ A,

@@ -125,6 +125,18 @@ void launch_tail(const DecArgs& a, int units, hipStream_t s) {
   }
 }
 
+// C[m][n] = sum_k A[m][k] B[n][k] in fp64: matrix cores when the contraction length allows, one
+// tile per wave for small products (more waves), 2 x 2 tiles per wave for large ones (less L2 traffic)
+void gemm_nt(hipStream_t s, const bf16_t* A, const bf16_t* B, double* Cm, int M, int N, int Kd) {
+  if (Kd % 32 != 0) {
+    k_gemm_nt_f64<<<dim3((N + 63) / 64, (M + 63) / 64), 256, 0, s>>>(A, B, Cm, M, N, Kd);
+  } else if ((long long)M * N <= (1ll << 21) || N <= 16) {
+    k_gemm_nt_mfma<1, 1><<<dim3((N + 31) / 32, (M + 31) / 32), 256, 0, s>>>(A, B, Cm, M, N, Kd);
+  } else {
+    k_gemm_nt_mfma<2, 2><<<dim3((N + 63) / 64, (M + 63) / 64), 256, 0, s>>>(A, B, Cm, M, N, Kd);
+  }
+}
+
 }  // namespace
 
 extern "C" {
@@ -279,10 +291,8 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
     k_gemv_nt_f64<<<(c.n_idx_heads + 1) / 2, 256, 0, s>>>((const bf16_t*)x_gate, (const bf16_t*)p->G, al,
                                                          M, c.n_idx_heads, c.gate_in_dim);
   } else {
-    k_gemm_nt_f64<<<dim3((Nq + 63) / 64, (M + 63) / 64), 256, 0, s>>>(
-        (const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, M, Nq, Kq);
-    k_gemm_nt_f64<<<dim3((c.n_idx_heads + 63) / 64, (M + 63) / 64), 256, 0, s>>>(
-        (const bf16_t*)x_gate, (const bf16_t*)p->G, al, M, c.n_idx_heads, c.gate_in_dim);
+    gemm_nt(s, (const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, M, Nq, Kq);
+    gemm_nt(s, (const bf16_t*)x_gate, (const bf16_t*)p->G, al, M, c.n_idx_heads, c.gate_in_dim);
   }
   const int rows = M * c.n_idx_heads;
   k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, (const bf16_t*)p->norm_q_w, c.rms_eps);
@@ -444,7 +454,8 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   if (prof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(ev1, s);
 #define IM_DEC_CASE(g)                                              \
   case g:                                                           \
-    k_dec_main<g><<<main_blocks, DEC_MT, 0, s>>>(a, a.qy, a.alpha); \
+    if (no_score) k_att_main<g><<<main_blocks, DEC_MT / 2, 0, s>>>(a); \
+    else k_dec_main<g><<<main_blocks, DEC_MT, 0, s>>>(a, a.qy, a.alpha); \
     if (prof && h->prof_span != IM_PROFILE_PREP) (void)hipEventRecord(ev1, s); \
     launch_tail<g>(a, units, s);                                    \
     break;
