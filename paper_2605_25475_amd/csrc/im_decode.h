@@ -784,14 +784,8 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const float* pbase = a.part + (size_t)u * a.S_alloc * G * DEC_REC;
   // ---------------- every load is issued now: no address depends on another load ----------------
   const int d4 = tid & 31, rg = tid >> 5;    // this thread's patch of M: rows 4 rg .. 4 rg + 3, columns 4 d4 .. 4 d4 + 3
-  float4 Mr[4];
   float* Mu = a.M + (size_t)u * IM_DM * IM_D;
-#pragma unroll
-  for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);
   const int wc = tid & 127, hh = tid >> 7;   // W_theta row wc, dims 16 hh .. 16 hh + 15
-  const uint4 Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
-  const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
-  const float b_old = a.bvec[(size_t)u * IM_DM + wc];
   // first round of split records (all launched splits; which are live is known once n is read
   // from record 0), the last-slot record, and the readout terms of the queries
   const int cs0 = min(CH, a.S);
@@ -825,6 +819,14 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     for (int k = 0; k < NBQ; ++k)
       if (tid + DEC_TT * k < nq2) ((float2*)&sm.phq[0][0])[tid + DEC_TT * k] = rq[k];
   }
+  // the memory state and W_theta are used further down (rank-one update, phi_e): their loads go out
+  // behind the staging batch, whose registers are free again
+  float4 Mr[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);
+  const uint4 Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
+  const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
+  const float b_old = a.bvec[(size_t)u * IM_DM + wc];
   __syncthreads();
   DEC_STAMP(9);
   const int n = (int)sm.cst[0][3];
@@ -890,27 +892,35 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const int part = (NS == 2) ? (tid >> 9) : 0;
   const bool act = oidx < NO;
   const int j = act ? (oidx >> 7) : 0, d = oidx & 127;
+  constexpr int CK = (PER <= 8) ? PER : (PER % 8 == 0) ? 8 : (PER % 6 == 0) ? 6 : 4;   // splits folded at a time
+  static_assert(PER % CK == 0, "the fold size divides the splits per thread");
   float rm = -1e30f, rl = 0.f, ro = 0.f;
-  {
-    // unconditional LDS reads (slots past cn0 hold stale words), then selects: no branches
-    float pm[PER], plv[PER], po[PER];
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-      const int sp = part * PER + k;
+  for (int k0 = 0; k0 < PER; k0 += CK) {
+    // unconditional LDS reads (slots past cn0 hold stale words), then selects: no branches
+    float pm[CK], plv[CK], po[CK];
+#pragma unroll
+    for (int k = 0; k < CK; ++k) {
+      const int sp = part * PER + k0 + k;
       const float r0 = sm.pst[sp][j][0], r1 = sm.pst[sp][j][1], r2 = sm.pst[sp][j][2 + d];
       const bool on = sp < cn0;
       pm[k] = on ? r0 : -1e30f;
       plv[k] = on ? r1 : 0.f;
       po[k] = on ? r2 : 0.f;
     }
+    float m = rm;
 #pragma unroll
-    for (int k = 0; k < PER; ++k) rm = fmaxf(rm, pm[k]);
+    for (int k = 0; k < CK; ++k) m = fmaxf(m, pm[k]);
+    const float resc = __expf(rm - m);
+    ro *= resc;
+    rl *= resc;
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-      const float sc = __expf(pm[k] - rm);
+    for (int k = 0; k < CK; ++k) {
+      const float sc = __expf(pm[k] - m);
       ro = fmaf(sc, po[k], ro);
       rl = fmaf(sc, plv[k], rl);
     }
+    rm = m;
   }
   __syncthreads();
   DEC_STAMP(10);
@@ -954,11 +964,12 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   if (tid < 40) mv = *(const uint4*)(lsrec + DEC_CAND_K + 4 * tid);
   const int mvpos = (int)lsrec[12];
   // ---------------- merge, second pass: add back the candidates that stay ----------------
-  {
-    float cl[PER], cv[PER];
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-      const int sp = part * PER + k;
+  for (int k0 = 0; k0 < PER; k0 += CK) {
+    float cl[CK], cv[CK];
+#pragma unroll
+    for (int k = 0; k < CK; ++k) {
+      const int sp = part * PER + k0 + k;
       const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
       const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
       const bool stays = sp < cn0 && sp != e_split && r3 != -INFINITY;   // -inf: the split left nothing out
@@ -967,11 +978,11 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     }
     float m = rm;
 #pragma unroll
-    for (int k = 0; k < PER; ++k) m = fmaxf(m, cl[k]);
+    for (int k = 0; k < CK; ++k) m = fmaxf(m, cl[k]);
     const float resc = __expf(rm - m);
     float o = ro * resc, l = rl * resc;
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
+    for (int k = 0; k < CK; ++k) {
       const float pc = __expf(cl[k] - m);   // exp(-inf) = 0 for the evicted / absent candidate
       o = fmaf(pc, cv[k], o);
       l += pc;
@@ -994,36 +1005,39 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     dec_stage<5>(&sm.pst[0][0][0], pbase + (size_t)c0 * G * DEC_REC, cn * G * DEC_REC);
     dec_stage<2>((float*)&sm.cst[0][0], (const float*)(cbase + (size_t)c0 * DEC_CAND), cn * DEC_CAND);
     __syncthreads();
-    float pm[PER], plv[PER], po[PER], cl[PER], cv[PER];
 #pragma unroll
-    for (int k = 0; k < PER; ++k) {
-      const int sp = part * PER + k;
-      const float r0 = sm.pst[sp][j][0], r1 = sm.pst[sp][j][1], r2 = sm.pst[sp][j][2 + d];
-      const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
-      const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
-      const bool on = sp < cn;
-      const bool stays = on && (c0 + sp != e_split) && r3 != -INFINITY;
-      pm[k] = on ? r0 : -1e30f;
-      plv[k] = on ? r1 : 0.f;
-      po[k] = on ? r2 : 0.f;
-      cl[k] = stays ? r3 : -INFINITY;
-      cv[k] = stays ? r4 : 0.f;
+    for (int k0 = 0; k0 < PER; k0 += CK) {
+      float pm[CK], plv[CK], po[CK], cl[CK], cv[CK];
+#pragma unroll
+      for (int k = 0; k < CK; ++k) {
+        const int sp = part * PER + k0 + k;
+        const float r0 = sm.pst[sp][j][0], r1 = sm.pst[sp][j][1], r2 = sm.pst[sp][j][2 + d];
+        const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
+        const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
+        const bool on = sp < cn;
+        const bool stays = on && (c0 + sp != e_split) && r3 != -INFINITY;
+        pm[k] = on ? r0 : -1e30f;
+        plv[k] = on ? r1 : 0.f;
+        po[k] = on ? r2 : 0.f;
+        cl[k] = stays ? r3 : -INFINITY;
+        cv[k] = stays ? r4 : 0.f;
+      }
+      float m = rm;
+#pragma unroll
+      for (int k = 0; k < CK; ++k) m = fmaxf(m, fmaxf(pm[k], cl[k]));
+      const float resc = __expf(rm - m);
+      float o = ro * resc, l = rl * resc;
+#pragma unroll
+      for (int k = 0; k < CK; ++k) {
+        const float sc = __expf(pm[k] - m);
+        o = fmaf(sc, po[k], o);
+        l = fmaf(sc, plv[k], l);
+        const float pc = __expf(cl[k] - m);
+        o = fmaf(pc, cv[k], o);
+        l += pc;
+      }
+      rm = m; rl = l; ro = o;
     }
-    float m = rm;
-#pragma unroll
-    for (int k = 0; k < PER; ++k) m = fmaxf(m, fmaxf(pm[k], cl[k]));
-    const float resc = __expf(rm - m);
-    float o = ro * resc, l = rl * resc;
-#pragma unroll
-    for (int k = 0; k < PER; ++k) {
-      const float sc = __expf(pm[k] - m);
-      o = fmaf(sc, po[k], o);
-      l = fmaf(sc, plv[k], l);
-      const float pc = __expf(cl[k] - m);
-      o = fmaf(pc, cv[k], o);
-      l += pc;
-    }
-    rm = m; rl = l; ro = o;
   }
   if (NS == 2) {
     if (part == 1 && act) { sm.mrg[0][oidx] = rm; sm.mrg[1][oidx] = rl; sm.mrg[2][oidx] = ro; }

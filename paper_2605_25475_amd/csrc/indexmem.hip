@@ -121,7 +121,8 @@ void launch_tail(const DecArgs& a, int units, hipStream_t s) {
     else k_dec_tail<G, 24><<<units, DEC_TT, 0, s>>>(a);
   } else {
     if (a.S <= 4) k_dec_tail<G, 4><<<units, DEC_TT, 0, s>>>(a);
-    else k_dec_tail<G, 8><<<units, DEC_TT, 0, s>>>(a);
+    else if (a.S <= 8) k_dec_tail<G, 8><<<units, DEC_TT, 0, s>>>(a);
+    else k_dec_tail<G, 16><<<units, DEC_TT, 0, s>>>(a);
   }
 }
 
