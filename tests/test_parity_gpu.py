@@ -159,3 +159,44 @@ def test_append_overflow_sets_status_and_leaves_state():
     assert im.im_query_status(h) == im.IM_STATUS_APPEND_OVERFLOW
     assert st.len.tolist() == [[5, 5]] and float(st.K[0, 0, 5:].float().abs().max()) == 0.0
     assert im.im_query_status(h) == 0
+
+
+def test_decode_step_in_a_hip_graph_matches_eager_replay_by_replay():
+    # the benchmark replays decode steps from HIP graphs: a captured step, replayed with fresh
+    # inputs copied into its static buffers, must leave the same state and output as the same step
+    # launched eagerly on a twin layer
+    w = WORKLOADS["cfg1"].scaled(context=700, budget=256, decode_steps=8)
+    twins = [LockStep(w) for _ in range(2)]
+    for ls in twins:
+        ls.event(0, w.context, w.budget, "prefill", check=False)
+        im.im_set_max_live(ls.handle, w.budget + 1)
+    g_ls, e_ls = twins
+    dev = "cuda"
+    k_s = torch.empty((w.batch, w.n_kv_heads, 1, 128), dtype=torch.bfloat16, device=dev)
+    v_s = torch.empty_like(k_s)
+    q_s = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    p_s = torch.empty((w.batch,), dtype=torch.int32, device=dev)
+
+    def load(t):
+        k_s.copy_(g_ls.K[:, :, t:t + 1]); v_s.copy_(g_ls.V[:, :, t:t + 1]); q_s.copy_(g_ls.Q[:, t])
+        p_s.fill_(t)
+
+    def step(ls):
+        ls.gpu.decode_step(k_s, v_s, p_s, q_s, q_s.view(w.batch, -1), p_s, w.budget, w.lam, w.eta, debug=True)
+
+    load(w.context)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):   # capture records the three launches; nothing runs yet
+        step(g_ls)
+    for t in range(w.context, w.context + 6):
+        load(t)
+        graph.replay()
+        step(e_ls)
+        torch.cuda.synchronize()
+        for n in ("len", "pos", "K", "V", "Kidx", "M", "b"):
+            assert torch.equal(getattr(g_ls.gpu.st, n), getattr(e_ls.gpu.st, n)), f"replay@{t}: {n} differs"
+        assert torch.equal(g_ls.gpu.out, e_ls.gpu.out), f"replay@{t}: output differs"
+        assert torch.equal(g_ls.gpu.evicted, e_ls.gpu.evicted), f"replay@{t}: evicted slot differs"
+        # eager work between the replays, as in a real program
+        _ = (g_ls.gpu.st.M.sum() + e_ls.gpu.st.M.sum()).item()
+    assert im.im_query_status(g_ls.handle) == 0 and im.im_query_status(e_ls.handle) == 0
