@@ -374,6 +374,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   // rows past the end of the split are read from its last row instead (finite values, no branches):
   // their logits are masked and their probabilities are zero further down
   uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
+  float sreg[2][4];
   int mypos = 0;
   if (!SCORE && tid < 4) { sm.c64[tid] = ~0ull; sm.cslot[tid] = -1; }   // no candidate: nothing is left out
   if (scoring) {
@@ -568,22 +569,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     // waits only for what it uses while the rest is still streaming in
     __asm__ volatile("" ::: "memory");
     DEC_STAMP(1);
-  }
-  __syncthreads();
-  DEC_STAMP(2);
-  // ---- the split's candidate: last-ranked over the 4 scoring waves (upwards with <= keeps the largest slot)
-  int cl = -1;  // candidate's key index inside the split
-  unsigned long long cbest = ~0ull;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const unsigned long long c = sm.c64[e];
-    const int at = sm.cslot[e];
-    if (at >= 0 && c <= cbest) { cbest = c; cl = at; }
-  }
-  // ---- logits of the 2 tiles of an attention wave:  S[key][head] = K_tile . Q^T  (bf16 MFMA, fp32 acc)
-  float sreg[2][4];
-  if (!scoring) {
-    float lmax = -INFINITY;
+    // ---- raw logits of the wave's 2 tiles:  S[key][head] = K_tile . Q^T  (bf16 MFMA, fp32 acc);
+    // they need no score, so they are taken while the scoring waves are still at work
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
       v4f acc = {0.f, 0.f, 0.f, 0.f};
@@ -597,19 +584,54 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a0, b0, acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a1, b1, acc, 0, 0, 0);
       }
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sreg[tt][r] = acc[r] * a.scale;   // this lane: head l16, key 16 T + 4 kq + r
+    }
+  }
+  __syncthreads();
+  DEC_STAMP(2);
+  // ---- the split's candidate: last-ranked over the 4 scoring waves (upwards with <= keeps the largest slot)
+  int cl = -1;  // candidate's key index inside the split
+  unsigned long long cbest = ~0ull;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const unsigned long long c = sm.c64[e];
+    const int at = sm.cslot[e];
+    if (at >= 0 && c <= cbest) { cbest = c; cl = at; }
+  }
+  // ---- attention waves: leave the candidate out, softmax statistics and probabilities PER WAVE
+  // (each wave relative to the maximum of its own 32 keys; the final reduction rescales), P V
+  float acc[G][8];
+  if (!scoring) {
+    float lmax = -INFINITY;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
       const int T = 2 * wl + tt;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int kl = 16 * T + 4 * kq + r;  // this lane: head l16, key kl
-        float sv = acc[r] * a.scale;
+        float sv = sreg[tt][r];
         if (kl == cl && l16 < G) sm.clog[l16] = sv;
         if (kl >= nk || kl == cl) sv = -INFINITY;
         sreg[tt][r] = sv;
         lmax = fmaxf(lmax, sv);
       }
     }
-    lmax = rows_max_f(lmax);
-    if (kq == 0 && l16 < 8) sm.wm[wl][l16] = lmax;
+    lmax = rows_max_f(lmax);               // over the wave's 32 keys, per head (lane column)
+    const float mw = (lmax == -INFINITY) ? -1e30f : lmax;
+    float lsum = 0.f;
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const int T = 2 * wl + tt;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float p = (sreg[tt][r] == -INFINITY) ? 0.f : __expf(sreg[tt][r] - mw);
+        lsum += p;
+        if (l16 < 8) sm.pl[16 * T + 4 * kq + r][l16] = p;
+      }
+    }
+    lsum = rows_sum_f(lsum);
+    if (kq == 0 && l16 < 8) { sm.wm[wl][l16] = mw; sm.wl[wl][l16] = lsum; }
     // the candidate's rows travel with the record (straight from the fragments), so the tail has
     // no dependent loads; the split that holds the last live slot also fills the last-slot record
 #pragma unroll
@@ -624,35 +646,12 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         for (int c = 0; c < 4; ++c) *(uint4*)(lrec + DEC_CAND_K + 16 * c + 4 * kq) = kf[tt][c];
       }
     }
-  } else if (SCORE && do_x_any && tid - 256 < G) {
-    // the leftover key's logits: the 4 scoring waves' partial dot products
-    const int j = tid - 256;
-    lrec[4 + j] = __float_as_uint((sm.xlp[0][j] + sm.xlp[1][j] + sm.xlp[2][j] + sm.xlp[3][j]) * a.scale);
-  }
-  __syncthreads();
-  DEC_STAMP(3);
-  if (!scoring) {
-    float mj = fmaxf(fmaxf(sm.wm[0][l16 & 7], sm.wm[1][l16 & 7]), fmaxf(sm.wm[2][l16 & 7], sm.wm[3][l16 & 7]));
-    if (mj == -INFINITY) mj = -1e30f;
-    float lsum = 0.f;
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      const int T = 2 * wl + tt;
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const float p = (sreg[tt][r] == -INFINITY) ? 0.f : __expf(sreg[tt][r] - mj);
-        lsum += p;
-        if (l16 < 8) sm.pl[16 * T + 4 * kq + r][l16] = p;
-      }
-    }
-    lsum = rows_sum_f(lsum);
-    if (kq == 0 && l16 < 8) sm.wl[wl][l16] = lsum;
-  }
-  __syncthreads();   // also: zs is dead from here on, its space holds oacc
-  DEC_STAMP(4);
-  // ---- O[head][d] += P[head][key] V[key][d]; 16 lanes share a key row (8 dims each)
-  float acc[G][8];
-  if (!scoring) {
+    // the probabilities just written are this wave's own keys: read back without a workgroup barrier
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    DEC_STAMP(4);
+    // O[head][d] += P[head][key] V[key][d]; 16 lanes share a key row (8 dims each)
 #pragma unroll
     for (int j = 0; j < G; ++j)
 #pragma unroll
@@ -673,6 +672,10 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
           for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(pv[j], v[e], acc[j][e]);
       }
     }
+  } else if (SCORE && do_x_any && tid - 256 < G) {
+    // the leftover key's logits: the 4 scoring waves' partial dot products
+    const int j = tid - 256;
+    lrec[4 + j] = __float_as_uint((sm.xlp[0][j] + sm.xlp[1][j] + sm.xlp[2][j] + sm.xlp[3][j]) * a.scale);
   }
   DEC_STAMP(5);
   // the 16 (attention wave, key group) streams meet in LDS, 4 heads at a time; all 8 waves add them up
@@ -694,14 +697,20 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     const int nj = (G - j0 < 4) ? G - j0 : 4;
     for (int idx = tid; idx < nj * IM_D; idx += (SCORE ? DEC_MT : DEC_MT / 2)) {
       const int jj = idx >> 7, d = idx & 127, j = j0 + jj;
-      float o = 0.f;
+      // every wave's partial is relative to its own maximum: rescale to the split's
+      const float m = fmaxf(fmaxf(sm.wm[0][j], sm.wm[1][j]), fmaxf(sm.wm[2][j], sm.wm[3][j]));
+      float o = 0.f, l = 0.f;
 #pragma unroll
-      for (int st = 0; st < 16; ++st) o += sm.oacc[st][jj][d];
+      for (int wv = 0; wv < 4; ++wv) {
+        const float sc = __expf(sm.wm[wv][j] - m);
+        o = fmaf(sc, (sm.oacc[4 * wv][jj][d] + sm.oacc[4 * wv + 1][jj][d]) +
+                     (sm.oacc[4 * wv + 2][jj][d] + sm.oacc[4 * wv + 3][jj][d]), o);
+        l = fmaf(sc, sm.wl[wv][j], l);
+      }
       prec[j * DEC_REC + 2 + d] = o;
       if (d == 0) {
-        float m = fmaxf(fmaxf(sm.wm[0][j], sm.wm[1][j]), fmaxf(sm.wm[2][j], sm.wm[3][j]));
-        prec[j * DEC_REC] = (m == -INFINITY) ? -1e30f : m;
-        prec[j * DEC_REC + 1] = sm.wl[0][j] + sm.wl[1][j] + sm.wl[2][j] + sm.wl[3][j];
+        prec[j * DEC_REC] = m;
+        prec[j * DEC_REC + 1] = l;
       }
     }
   }
