@@ -194,7 +194,7 @@ def main() -> None:
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
-                 "(units shard by batch / KV head with no communication; see DESIGN.md)")
+                 "(units would shard by batch or by KV head with no communication)")
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     w = WORKLOADS[a.workload]

@@ -1,14 +1,17 @@
 // Fused decode step: the whole path for one new token per sequence in three launches.
-//   k_dec_prep : query-side indexer features (U_q, G GEMVs + QK-Norm), append of the new
-//                (k, v), its indexer key.
-//   k_dec_main : per (unit, 128-key split) workgroups score their keys, find their local
-//                eviction candidate (the entry ranked last) and accumulate softmax-attention
-//                partials WITHOUT it; the candidate's logits and K / V rows go to a record.
+//   k_dec_prep : query-side indexer features (U_q, G GEMVs; the consumer applies the QK-Norm),
+//                append of the new (k, v), its indexer key, and the terms of the memory readout
+//                that do not depend on this step's eviction (phi_q, phi_q^T M, phi_q^2 . b, gate).
+//   k_dec_main : per (unit, 128-key split) workgroups of two wave roles.  Scoring waves score
+//                the split's keys and find its local eviction candidate (the entry ranked last);
+//                attention waves stream K / V and accumulate the softmax-attention partial
+//                WITHOUT that candidate; the candidate's logits and K / V rows go to a record.
+//   k_att_main : the attend-only variant (no scoring waves, nothing left out).
 //   k_dec_tail : one workgroup per unit picks the evicted entry among the candidates, folds it
 //                into the memory state, merges the partials plus the candidates that stay,
 //                adds the gated readout, fills the hole and writes the output.
-// A kernel boundary separates main and tail on purpose: on this chip a device-scope release
-// (L2 write-back) per workgroup or an in-kernel wait costs several microseconds more than a launch.
+// Kernel boundaries separate the three on purpose: on this chip a device-scope release (L2
+// write-back) per workgroup or an in-kernel wait costs several microseconds more than a launch.
 // Same results as append -> index_score (n_q = 1) -> topb_select -> memory_update -> compact_kv
 // -> decode_attn_with_readout whenever every unit enters with len <= budget.
 #pragma once
@@ -69,7 +72,6 @@ struct DecArgs {
   float* qm;          // per unit: the eviction-independent terms of the memory readout (DEC_QM floats per head)
   // scalars
   int B, H, H_kv, C, H_idx, gate_in, n_sink, n_recent, budget, S, S_alloc, max_live;
-  int no_score;       // attend-only step: nothing is scored, excluded or evicted
   float rms_eps, mem_eps, scale, lambda, eta;
 };
 

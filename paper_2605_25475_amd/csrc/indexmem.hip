@@ -440,7 +440,6 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   // a budget that is a multiple of 128) is left to the tail kernel instead of a one-key split
   a.S = (!no_score && h->max_live % DEC_KEYS == 1 && h->max_live > 1) ? h->max_live / DEC_KEYS
                                                                       : (h->max_live + DEC_KEYS - 1) / DEC_KEYS;
-  a.no_score = no_score ? 1 : 0;
   a.S_alloc = h->dec_splits; a.max_live = h->max_live;
   a.rms_eps = c.rms_eps; a.mem_eps = c.mem_eps; a.scale = c.softmax_scale; a.lambda = lambda; a.eta = eta;
   // the per-unit blocks come first in the prep kernel's block order: an attend-only step launches
