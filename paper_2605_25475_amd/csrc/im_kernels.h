@@ -263,6 +263,52 @@ __global__ __launch_bounds__(256) void k_gemm_nt_mfma(const bf16_t* __restrict__
       }
 }
 
+// The same for small products: ONE 16 x 16 output tile per workgroup, its 4 waves take a quarter of
+// the contraction each (Kd % 128 == 0) and meet in LDS.  grid (ceil(N / 16), ceil(M / 16)).
+__global__ __launch_bounds__(256) void k_gemm_nt_mfma_k4(const bf16_t* __restrict__ A,
+                                                         const bf16_t* __restrict__ B,
+                                                         double* __restrict__ Cm, int M, int N, int Kd) {
+  __shared__ double red[3][64][4];
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, l16 = lane & 15, kq = lane >> 4;
+  const int m0 = blockIdx.y * 16, n0 = blockIdx.x * 16, kw = Kd / 4;
+  const bf16_t* ap = A + (size_t)min(m0 + l16, M - 1) * Kd + w * kw + 8 * kq;
+  const bf16_t* bp = B + (size_t)min(n0 + l16, N - 1) * Kd + w * kw + 8 * kq;
+  im_v4d acc = {0.0, 0.0, 0.0, 0.0};
+  for (int k0 = 0; k0 < kw; k0 += 128) {      // 4 chunks of 32 in flight
+    uint4 au[4], bu[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int k = (k0 + 32 * c < kw) ? k0 + 32 * c : k0;
+      au[c] = *(const uint4*)(ap + k);
+      bu[c] = *(const uint4*)(bp + k);
+    }
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      if (k0 + 32 * c < kw) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t wa = (e < 2) ? au[c].x : (e < 4) ? au[c].y : (e < 6) ? au[c].z : au[c].w;
+          const uint32_t wb = (e < 2) ? bu[c].x : (e < 4) ? bu[c].y : (e < 6) ? bu[c].z : bu[c].w;
+          acc = __builtin_amdgcn_mfma_f64_16x16x4f64((double)((e & 1) ? bf_hi(wa) : bf_lo(wa)),
+                                                     (double)((e & 1) ? bf_hi(wb) : bf_lo(wb)), acc, 0, 0, 0);
+        }
+      }
+    }
+  }
+  if (w > 0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[w - 1][lane][r] = acc[r];
+  }
+  __syncthreads();
+  if (w == 0) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int m = m0 + 4 * r + kq, n = n0 + l16;
+      if (m < M && n < N) Cm[(size_t)m * N + n] = ((acc[r] + red[0][lane][r]) + red[1][lane][r]) + red[2][lane][r];
+    }
+  }
+}
+
 // Few rows (decode): every workgroup owns 2 rows of B and streams them once for all M rows of A.
 // grid (ceil(N/2)); Kd % 8 == 0.
 __global__ __launch_bounds__(256) void k_gemv_nt_f64(const bf16_t* __restrict__ A,
@@ -340,13 +386,14 @@ __global__ void k_alpha_scale(double* __restrict__ a, int n, double denom) {
 // a1 (iii): scores on the fp64 matrix cores.  imp[key] = max over the queries that may see the key
 // of sum_j alpha[s][j] ReLU(q[s][j] . k[key]).
 // ------------------------------------------------------------------------------------------
-// grid (ceil(max_live/256), units) read as one list of (tile, unit) pairs, 4 waves; a wave owns 64 keys = 4 tiles of 16 rows (the A operand,
+// grid (ceil(max_live / (64 TPW)), units) read as one list of (tile, unit) pairs, 4 waves; a wave owns
+// TPW tiles of 16 rows (TPW = 4 for long caches, 1 when that gives too few workgroups; the A operand,
 // kept in registers as packed bf16) and walks over the queries.  One pass of the 16x16x4 product
 // (16 steps over the 64 dims) takes 16 columns = 16 / HS queries x HS head lanes (HS = 8 when
 // H_idx <= 8, else 16); the gated ReLU terms of a query are then added over its HS lanes with
 // shifted adds inside the 16-lane row, so the last lane of each group holds the query's score of
 // the 4 keys of its register rows, and keeps the running maximum.
-template <int HS>
+template <int HS, int TPW>
 __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
                                                const int32_t* __restrict__ pos,
                                                const int32_t* __restrict__ len,
@@ -355,7 +402,10 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
                                                const double* __restrict__ alpha,
                                                const int32_t* __restrict__ q_pos, int n_q, int H_kv,
                                                int C, int H_idx, int max_live,
-                                               float* __restrict__ scores) {
+                                               float* __restrict__ scores, int q_per_group) {
+  // grid z: groups of q_per_group queries (a multiple of 2), each with workgroups of its own; with
+  // more than one group, group g writes its maxima to scores + g * units * C and k_score_max
+  // folds the groups
   constexpr int QPP = 16 / HS;   // queries per pass
   __shared__ int s_min[4];
   __shared__ int s_first[4];
@@ -367,16 +417,16 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
   const int l16 = lane & 15, kq = lane >> 4;
   const int b = unit / H_kv;
   const int n = min(len[unit], max_live);
-  if (tile == 0 && tid == 0) n_projected[unit] = n;  // the projection kernel ran before
-  const int t0 = tile * 256;
+  if (tile == 0 && blockIdx.z == 0 && tid == 0) n_projected[unit] = n;  // the projection kernel ran before
+  const int t0 = tile * (64 * TPW);
   if (t0 >= n) return;
-  const int kbase = t0 + 64 * w;
+  const int kbase = t0 + 16 * TPW * w;
   // A operands: lane (row l16, kq) holds dims 16 kq .. 16 kq + 15 of its row in each of the 4 tiles
   // (rows past the end repeat the last live one; their scores are never written)
-  uint4 ka[4][2];
-  int posk[4][4];
+  uint4 ka[TPW][2];
+  int posk[TPW][4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < TPW; ++t) {
     const size_t row = (size_t)unit * C + min(kbase + 16 * t + l16, n - 1);
     ka[t][0] = *(const uint4*)(Kidx + row * IM_DI + 16 * kq);
     ka[t][1] = *(const uint4*)(Kidx + row * IM_DI + 16 * kq + 8);
@@ -391,7 +441,7 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
   // the queries starts there (visibility is decided per key further down)
   int mn = INT_MAX;
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
+  for (int t = 0; t < TPW; ++t)
 #pragma unroll
     for (int r = 0; r < 4; ++r) mn = min(mn, posk[t][r]);
   mn = (int)(wave_min_u((uint32_t)mn ^ 0x80000000u) ^ 0x80000000u);
@@ -406,15 +456,17 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
   if (lane == 0) s_first[w] = first;
   __syncthreads();
   first = min(min(s_first[0], s_first[1]), min(s_first[2], s_first[3]));
-  float imp[4][4];
+  float imp[TPW][4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t)
+  for (int t = 0; t < TPW; ++t)
 #pragma unroll
     for (int r = 0; r < 4; ++r) imp[t][r] = -INFINITY;
   const int jl = l16 % HS, sl = l16 / HS;
   const bool jv = jl < H_idx;
+  const int q_lo = blockIdx.z * q_per_group, q_hi = min(n_q, q_lo + q_per_group);
+  scores += (size_t)blockIdx.z * units * C;
 #pragma unroll 1
-  for (int s0 = (first / QPP) * QPP; s0 < n_q; s0 += QPP) {
+  for (int s0 = max((first / QPP) * QPP, q_lo); s0 < q_hi; s0 += QPP) {
     const int s = min(s0 + sl, n_q - 1);
     const bool sv = s0 + sl < n_q;
     const int qp = qp_b[s];
@@ -430,13 +482,13 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
       }
     }
     const double al = (jv && sv) ? alpha[((size_t)b * n_q + s) * H_idx + jl] : 0.0;   // idle lanes add 0
-    im_v4d z[4];
+    im_v4d z[TPW];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) z[t] = im_v4d{0.0, 0.0, 0.0, 0.0};
+    for (int t = 0; t < TPW; ++t) z[t] = im_v4d{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int m = 0; m < 16; ++m) {
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
+      for (int t = 0; t < TPW; ++t) {
         const uint4 u = ka[t][m >> 3];
         const uint32_t wd = ((m & 7) < 2) ? u.x : ((m & 7) < 4) ? u.y : ((m & 7) < 6) ? u.z : u.w;
         const float f = (m & 1) ? bf_hi(wd) : bf_lo(wd);
@@ -444,7 +496,7 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
       }
     }
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
+    for (int t = 0; t < TPW; ++t) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         double v = al * fmax(z[t][r], 0.0);
@@ -460,7 +512,7 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
   }
   // the groups' maxima meet in lane 15 of each row, which writes the 16 keys of its register rows
 #pragma unroll
-  for (int t = 0; t < 4; ++t) {
+  for (int t = 0; t < TPW; ++t) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       float v = imp[t][r];
@@ -469,6 +521,17 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
       if (l16 == 15 && key < n) scores[(size_t)unit * C + key] = v;
     }
   }
+}
+
+// scores[unit][key] = max over the query groups' partial maxima.  grid (ceil(max_live/256), units)
+__global__ __launch_bounds__(256) void k_score_max(const float* __restrict__ part, int groups,
+                                                   const int32_t* __restrict__ len, int C, int max_live,
+                                                   float* __restrict__ scores) {
+  const int unit = blockIdx.y, units = gridDim.y, key = blockIdx.x * 256 + threadIdx.x;
+  if (key >= min(len[unit], max_live)) return;
+  float v = -INFINITY;
+  for (int g = 0; g < groups; ++g) v = fmaxf(v, part[((size_t)g * units + unit) * C + key]);
+  scores[(size_t)unit * C + key] = v;
 }
 
 // ------------------------------------------------------------------------------------------

@@ -20,13 +20,15 @@ struct im_handle {
   int max_live;
   bool ws_ready;
   // workspace layout (byte offsets)
-  size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, off_dqm, total;
+  size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, off_dqm, off_spart, total;
   int mem_split, attn_chunks, dec_splits;
   // optional kernel timing (im_profile_start / im_profile_stop)
   hipEvent_t* prof_ev;
   int prof_max, prof_n, prof_span;
   char err[256];
 };
+
+#define IM_SCORE_GROUPS 8   // query groups of a scoring launch over a short cache
 
 namespace {
 
@@ -83,6 +85,7 @@ void layout(const im_config* c, im_handle* h) {
   h->off_dpart = off;  off = align256(off + units * h->dec_splits * DEC_GMAX * DEC_REC * sizeof(float));  // upper bound: G <= 8
   h->off_dcand = off;  off = align256(off + units * h->dec_splits * DEC_CAND * sizeof(uint32_t));
   h->off_dqm = off;    off = align256(off + units * DEC_GMAX * DEC_QM * sizeof(float));
+  h->off_spart = off;  off = align256(off + (size_t)IM_SCORE_GROUPS * units * c->capacity * sizeof(float));
   h->total = off;
 }
 
@@ -131,6 +134,8 @@ void launch_tail(const DecArgs& a, int units, hipStream_t s) {
 void gemm_nt(hipStream_t s, const bf16_t* A, const bf16_t* B, double* Cm, int M, int N, int Kd) {
   if (Kd % 32 != 0) {
     k_gemm_nt_f64<<<dim3((N + 63) / 64, (M + 63) / 64), 256, 0, s>>>(A, B, Cm, M, N, Kd);
+  } else if (Kd % 128 == 0 && (long long)((M + 15) / 16) * ((N + 15) / 16) <= 2048) {
+    k_gemm_nt_mfma_k4<<<dim3((N + 15) / 16, (M + 15) / 16), 256, 0, s>>>(A, B, Cm, M, N, Kd);
   } else if ((long long)M * N <= (1ll << 21) || N <= 16) {
     k_gemm_nt_mfma<1, 1><<<dim3((N + 31) / 32, (M + 31) / 32), 256, 0, s>>>(A, B, Cm, M, N, Kd);
   } else {
@@ -298,14 +303,30 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
   const int rows = M * c.n_idx_heads;
   k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, (const bf16_t*)p->norm_q_w, c.rms_eps);
   k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, sqrt((double)(c.n_idx_heads * IM_DI)));
-  if (c.n_idx_heads <= 8)
-    k_score<8><<<dim3((h->max_live + 255) / 256, units), 256, 0, s>>>(
-        (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q, c.n_kv_heads,
-        c.capacity, c.n_idx_heads, h->max_live, scores_out);
-  else
-    k_score<16><<<dim3((h->max_live + 255) / 256, units), 256, 0, s>>>(
-        (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q, c.n_kv_heads,
-        c.capacity, c.n_idx_heads, h->max_live, scores_out);
+  // a launch over a short cache has few (256-key tile, unit) workgroups: its queries then go in up
+  // to IM_SCORE_GROUPS groups with workgroups of their own (partial maxima in the workspace,
+  // folded by k_score_max); a very short one also drops to 16 keys per wave
+  const long long tile_wgs = (long long)((h->max_live + 255) / 256) * units;
+  const bool small = tile_wgs * IM_SCORE_GROUPS < 1024;
+  int groups = 1, q_per_group = n_q;
+  if (tile_wgs < 1024 && n_q >= 32) {
+    const int want = (int)((1024 + tile_wgs - 1) / tile_wgs), most = (n_q + 15) / 16;
+    groups = want < most ? want : most;
+    if (groups > IM_SCORE_GROUPS) groups = IM_SCORE_GROUPS;
+    q_per_group = ((n_q + groups - 1) / groups + 1) & ~1;
+    groups = (n_q + q_per_group - 1) / q_per_group;
+  }
+  float* sc_out = groups > 1 ? (float*)(h->ws + h->off_spart) : scores_out;
+#define IM_SCORE(HS, TPW)                                                                                    \
+  k_score<HS, TPW><<<dim3((h->max_live + 64 * TPW - 1) / (64 * TPW), units, groups), 256, 0, s>>>(           \
+      (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q, c.n_kv_heads,          \
+      c.capacity, c.n_idx_heads, h->max_live, sc_out, q_per_group)
+  if (c.n_idx_heads <= 8) { if (small) IM_SCORE(8, 1); else IM_SCORE(8, 4); }
+  else { if (small) IM_SCORE(16, 1); else IM_SCORE(16, 4); }
+#undef IM_SCORE
+  if (groups > 1)
+    k_score_max<<<dim3((h->max_live + 255) / 256, units), 256, 0, s>>>(sc_out, groups, st->len, c.capacity,
+                                                                      h->max_live, scores_out);
   return launch_check(h, "im_index_score");
 }
 
