@@ -61,7 +61,7 @@ def algorithmic_bytes(w: Workload) -> dict:
 class Job:
     """All layers of a workload after their prefill eviction, plus pre-generated decode inputs."""
 
-    def __init__(self, w: Workload, n_steps: int, device="cuda", log=lambda s: None, tau: int = 0):
+    def __init__(self, w: Workload, n_steps: int, device="cuda", log=lambda s: None, tau: int = 0, share: int = 1):
         self.w, self.dev = w, device
         cap = w.capacity
         n_q_max = w.context if w.prefill_chunk is None else w.prefill_chunk
@@ -69,7 +69,7 @@ class Job:
                         n_idx_heads=w.n_idx_heads, n_sink=w.n_sink, n_recent=w.n_recent,
                         fold_block=w.fold_block, max_queries=n_q_max)
         self.handle = im.Handle(cfg, device)
-        self.layers, self.dec, self.qwin, self.tau = [], [], [], tau
+        self.layers, self.dec, self.qwin, self.tau, self.share = [], [], [], tau, share
         L = w.context
         assert n_steps <= w.decode_steps, "the workload defines fewer decode steps"
         for li in range(w.n_layers):
@@ -84,9 +84,13 @@ class Job:
                 c1 = min(L, c0 + chunk)
                 pos = torch.arange(c0, c1, dtype=torch.int32, device=device).repeat(w.batch, 1).contiguous()
                 q = Q[:, c0:c1].contiguous()
-                layer.step(K[:, :, c0:c1].contiguous(), V[:, :, c0:c1].contiguous(), pos, q,
-                           q.view(w.batch, c1 - c0, -1), pos, Q[:, c1 - 1].contiguous(), w.budget,
-                           w.lam, w.eta)
+                if li % share:   # a follower of an index-sharing group applies its leader's lists
+                    layer.follow_event(K[:, :, c0:c1].contiguous(), V[:, :, c0:c1].contiguous(), pos,
+                                       Q[:, c1 - 1].contiguous(), self.layers[li - li % share], w.lam, w.eta)
+                else:
+                    layer.step(K[:, :, c0:c1].contiguous(), V[:, :, c0:c1].contiguous(), pos, q,
+                               q.view(w.batch, c1 - c0, -1), pos, Q[:, c1 - 1].contiguous(), w.budget,
+                               w.lam, w.eta)
             # decode inputs, one contiguous slab per step
             kd = K[:, :, L:].permute(2, 0, 1, 3).contiguous().unsqueeze(3)      # [S, B, Hkv, 1, D]
             vd = V[:, :, L:].permute(2, 0, 1, 3).contiguous().unsqueeze(3)
@@ -113,7 +117,15 @@ class Job:
         for li, layer in enumerate(self.layers):
             kd, vd, qd = self.dec[li]
             q = qd[s]
-            if path == "periodic":
+            if path == "shared":
+                if li % self.share:
+                    layer.follow_step(kd[s], vd[s], pos.view(w.batch), q.view(w.batch, w.n_q_heads, -1),
+                                      self.layers[li - li % self.share].evicted, w.lam, w.eta)
+                else:
+                    layer.decode_step(kd[s], vd[s], pos.view(w.batch), q.view(w.batch, w.n_q_heads, -1),
+                                      q.view(w.batch, -1), pos.view(w.batch), w.budget, w.lam, w.eta,
+                                      want_evicted=True)
+            elif path == "periodic":
                 layer.attend_step(kd[s], vd[s], pos, q.view(w.batch, w.n_q_heads, -1), debug=False)
             elif path == "fused":
                 layer.decode_step(kd[s], vd[s], pos.view(w.batch), q.view(w.batch, w.n_q_heads, -1),
@@ -180,10 +192,13 @@ def main() -> None:
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg3", choices=sorted(WORKLOADS))
-    ap.add_argument("--path", default="fused", choices=["fused", "steps", "periodic"],
+    ap.add_argument("--path", default="fused", choices=["fused", "steps", "periodic", "shared"],
                     help="fused: im_decode_step (3 launches per layer); steps: the six separate calls; "
                          "periodic: the paper's decode schedule (append + attention every step, one "
-                         "compression event per --tau steps with the interval's queries as the query set)")
+                         "compression event per --tau steps with the interval's queries as the query set); "
+                         "shared: index reuse over groups of --share consecutive layers (the first layer "
+                         "of a group scores and selects, the others apply its decision)")
+    ap.add_argument("--share", type=int, default=4, help="layers per index-sharing group of --path shared")
     ap.add_argument("--tau", type=int, default=128, help="compression interval of --path periodic")
     ap.add_argument("--no-graph", action="store_true", help="launch the fused path eagerly")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -207,7 +222,7 @@ def main() -> None:
         assert w.budget + tau <= w.capacity
     n_total = a.warmup + (1 if tau else 2) * a.steps
     t_setup = time.perf_counter()
-    job = Job(w, n_total, log=log, tau=tau)
+    job = Job(w, n_total, log=log, tau=tau, share=a.share if a.path == "shared" else 1)
     torch.cuda.synchronize()
     log(f"setup (generation + prefill eviction of {w.n_layers} layers) {time.perf_counter() - t_setup:.1f} s")
 
@@ -217,7 +232,7 @@ def main() -> None:
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    use_graph = (a.path in ("fused", "periodic")) and not a.no_graph
+    use_graph = (a.path in ("fused", "periodic", "shared")) and not a.no_graph
 
     def run(s0, s1):
         for s in range(s0, s1):
@@ -294,7 +309,8 @@ def main() -> None:
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n_q_heads}/{w.n_kv_heads}x{w.head_dim} heads, {w.n_layers} layers, "
                                f"batch {w.batch}, context {w.context} -> budget {w.budget}, "
-                               + (f"one compression event per {tau} decode steps" if tau else "one eviction per decode step"),
+                               + (f"one compression event per {tau} decode steps" if tau else "one eviction per decode step")
+                               + (f", index decisions shared by groups of {a.share} layers" if a.path == "shared" else ""),
                    "layers": w.n_layers, "batch": w.batch, "budget": w.budget, "context": w.context,
                    "path": a.path, "hip_graph": use_graph,
                    "algorithmic_bytes_per_step": ab["per_layer_step"] * w.n_layers,

@@ -199,6 +199,21 @@ int32_t im_attend_step(im_handle* h, const im_params* p, const im_state* st, con
                        const void* k_new, const void* v_new, const int32_t* pos_new, void* out,
                        float* readout_dbg, void* stream);
 
+/* Index reuse across neighbouring layers (Appendix "From Running Mean to IndexCache": the indexer
+ * runs once per group of layers and the other layers of the group reuse its decision).  The step
+ * of a FOLLOWER layer for one new token per sequence, three launches, nothing scored: exactly
+ *   im_append_kv(n_new = 1) -> im_memory_update + im_compact_kv with the single entry in slot
+ *   evict_slot[b, h] (as the cache stands after the append; -1 or >= len: nothing leaves) ->
+ *   im_decode_attn_with_readout.
+ * evict_slot [B, H_kv] int32 is what im_decode_step wrote to its evicted_slot output for the
+ * group's leading layer; the follower's cache must have the leader's slot layout (same appends,
+ * same evictions since the start, e.g. a prefill compacted with the leader's keep / evict lists).
+ * Other arguments as in im_decode_step. */
+int32_t im_decode_step_shared(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                              const void* k_new, const void* v_new, const int32_t* pos_new,
+                              const int32_t* evict_slot, float lambda, float eta, void* out,
+                              float* readout_dbg, void* stream);
+
 /* Kernel timing for benchmarks (not part of the method).  After im_profile_start, every
  * im_decode_step on this handle brackets part of its launch sequence (prep kernel, main kernel,
  * tail kernel) with a pair of HIP events on the launch stream, for at most max_records calls:

@@ -59,6 +59,7 @@ struct DecArgs {
   // inputs
   const bf16_t *q, *xg, *k_new, *v_new;
   const int32_t *pos_new, *q_pos;
+  const int32_t* ext_evict;   // optional [units]: the slot to evict is given (no scoring), -1 for none
   // outputs
   bf16_t* out;
   float* readout;
@@ -378,7 +379,21 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
   float sreg[2][4];
   int mypos = 0;
-  if (!SCORE && tid < 4) { sm.c64[tid] = ~0ull; sm.cslot[tid] = -1; }   // no candidate: nothing is left out
+  uint4 lkx = make_uint4(0, 0, 0, 0);
+  int lpos = 0;
+  if (!SCORE) {
+    // no scoring waves: nothing is left out of the partial, unless the caller names the slot to
+    // evict; that entry is then this split's candidate if it lies here (wave tid's 32 keys)
+    if (tid < 4) {
+      const int fl = (a.ext_evict ? a.ext_evict[u] : -1) - k0;
+      const bool here = fl >= 32 * tid && fl < 32 * tid + 32 && fl < nk;
+      sm.c64[tid] = here ? 0ull : ~0ull;
+      sm.cslot[tid] = here ? fl : -1;
+    }
+    // the last live slot's indexer key and position for the last-slot record
+    if (own_last && tid < 8) lkx = *(const uint4*)(a.Kidx + ((size_t)u * a.C + (n - 1)) * IM_DI + 8 * tid);
+    if (own_last && tid == 8) lpos = a.pos[(size_t)u * a.C + (n - 1)];
+  }
   if (scoring) {
     // ================= scoring waves: tiles 2 wl, 2 wl + 1 (keys 32 wl .. 32 wl + 31) =================
     // their few loads go ahead of the attention waves' many: the scoring chain is the longer one
@@ -567,10 +582,46 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         vf[tt][i] = *(const uint4*)(a.V + (base + vr) * IM_D + 8 * l16);
       }
     }
+    // without scoring waves, split 0's attention waves look after the one key beyond the splits
+    // (wave wl: dims 32 wl .. 32 wl + 31 of its logits; wave 0: its rows for the last-slot record)
+    uint4 yk = make_uint4(0, 0, 0, 0), yq = yk, ykv = yk, yki0 = yk, yki1 = yk;
+    int ypos = 0;
+    if (!SCORE && do_x_any) {
+      const size_t last = (size_t)u * a.C + (n - 1);
+      yki0 = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq);
+      yki1 = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq + 8);
+      yk = *(const uint4*)(a.K + last * IM_D + 32 * wl + 8 * kq);
+      yq = *(const uint4*)(a.q + ((size_t)b * a.H + h * G + min(l16, G - 1)) * IM_D + 32 * wl + 8 * kq);
+      ykv = *(const uint4*)(((lane & 16) ? a.V : a.K) + last * IM_D + 8 * l16);
+      ypos = a.pos[last];
+    }
     // keep every load above this line, in this order: loads return in order, so each phase below
     // waits only for what it uses while the rest is still streaming in
     __asm__ volatile("" ::: "memory");
     DEC_STAMP(1);
+    if (!SCORE && do_x_any) {
+      float qv[8], kv[8], lp = 0.f;
+      unpack8(yq, qv);
+      unpack8(yk, kv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) lp = fmaf(qv[e], kv[e], lp);
+      lp = rows_sum_f(lp);
+      if (kq == 0 && l16 < 8) sm.xlp[wl][l16] = lp;   // summed over the 4 waves after the barrier
+      if (wl == 0) {
+        if (l16 == 0) {
+          *(uint4*)(lrec + DEC_CAND_KI + 8 * kq) = yki0;
+          *(uint4*)(lrec + DEC_CAND_KI + 8 * kq + 4) = yki1;
+        }
+        if (lane < 32) *(uint4*)(lrec + ((lane & 16) ? DEC_CAND_V : DEC_CAND_K) + 4 * l16) = ykv;
+        if (lane == 0) {
+          lrec[0] = 0xffffffffu;   // never ranked: the caller names the evicted slot, if any
+          lrec[1] = 0xffffffffu;
+          lrec[2] = (uint32_t)(n - 1);
+          lrec[3] = (uint32_t)n;
+          lrec[12] = (uint32_t)ypos;
+        }
+      }
+    }
     // ---- raw logits of the wave's 2 tiles:  S[key][head] = K_tile . Q^T  (bf16 MFMA, fp32 acc);
     // they need no score, so they are taken while the scoring waves are still at work
 #pragma unroll
@@ -674,6 +725,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
           for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(pv[j], v[e], acc[j][e]);
       }
     }
+    if (!SCORE && do_x_any && tid < G)   // the leftover key's logits: the 4 waves' partial dot products
+      lrec[4 + tid] = __float_as_uint((sm.xlp[0][tid] + sm.xlp[1][tid] + sm.xlp[2][tid] + sm.xlp[3][tid]) * a.scale);
   } else if (SCORE && do_x_any && tid - 256 < G) {
     // the leftover key's logits: the 4 scoring waves' partial dot products
     const int j = tid - 256;
@@ -724,6 +777,10 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     crec[3] = (uint32_t)n;
   }
   if (tid < G) crec[4 + tid] = __float_as_uint(cl >= 0 ? sm.clog[tid] : -INFINITY);   // -inf: no candidate
+  if (!SCORE && own_last) {
+    if (tid < 8) *(uint4*)(lrec + DEC_CAND_KI + 4 * tid) = lkx;
+    if (tid == 8) { lrec[2] = (uint32_t)(n - 1); lrec[3] = (uint32_t)n; lrec[12] = (uint32_t)lpos; }
+  }
   if (!scoring) {
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -888,10 +945,17 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
         const unsigned long long xc = ((unsigned long long)lsrec[0] << 32) | lsrec[1];
         if (bi < 0 || xc <= bb) { bb = xc; bi = x_split; }
       }
-      const bool ev = evict && bi >= 0;
-      sm.e_split = ev ? bi : -1;
-      sm.e_slot = !ev ? -1 : (bi == x_split) ? n_last : (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]);
-      if (n > a.budget + 1) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
+      if (a.ext_evict) {   // the caller names the slot: the record of its split holds its rows
+        const int e = a.ext_evict[u];
+        const bool ev = e >= 0 && e < n;
+        sm.e_split = ev ? e / DEC_KEYS : -1;
+        sm.e_slot = ev ? e : -1;
+      } else {
+        const bool ev = evict && bi >= 0;
+        sm.e_split = ev ? bi : -1;
+        sm.e_slot = !ev ? -1 : (bi == x_split) ? n_last : (int)((bi < CH) ? sm.cst[bi][2] : cbase[(size_t)bi * DEC_CAND + 2]);
+        if (n > a.budget + 1) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
+      }
     }
   }
   // ---------------- merge, first pass: the attention partials of the staged splits ----------------

@@ -425,7 +425,7 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
                              const void* x_gate, const int32_t* q_pos, const void* k_new, const void* v_new,
                              const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,
                              float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream,
-                             const bool no_score, const char* what) {
+                             const bool no_score, const int32_t* ext_evict, const char* what) {
   if (!h) return IM_ERR_INVALID_ARG;
   IM_REQUIRE(params_ok(p), "params has a NULL pointer");
   IM_REQUIRE(state_ok(st), "state has a NULL pointer");
@@ -442,14 +442,14 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   if (rc) return rc;
   const int units = c.batch * c.n_kv_heads, G = c.n_q_heads / c.n_kv_heads;
   int32_t* words = (int32_t*)(h->ws + h->off_status);
-  DecArgs a;
+  DecArgs a = {};
   a.K = (bf16_t*)st->K; a.V = (bf16_t*)st->V; a.Kidx = (bf16_t*)st->Kidx;
   a.pos = st->pos; a.len = st->len; a.nproj = st->n_projected; a.M = st->M; a.bvec = st->b;
   a.Uq = (const bf16_t*)p->Uq; a.Gw = (const bf16_t*)p->G; a.Uk = (const bf16_t*)p->Uk;
   a.nqw = (const bf16_t*)p->norm_q_w; a.nkw = (const bf16_t*)p->norm_k_w;
   a.Wt = (const bf16_t*)p->Wtheta; a.wg = (const bf16_t*)p->wg; a.cg = p->cg;
   a.q = (const bf16_t*)q; a.xg = (const bf16_t*)x_gate; a.k_new = (const bf16_t*)k_new;
-  a.v_new = (const bf16_t*)v_new; a.pos_new = pos_new; a.q_pos = q_pos;
+  a.v_new = (const bf16_t*)v_new; a.pos_new = pos_new; a.q_pos = q_pos; a.ext_evict = ext_evict;
   a.out = (bf16_t*)out; a.readout = readout_dbg; a.scores = scores_dbg; a.evicted = evicted_slot;
   a.qy = (double*)(h->ws + h->off_qy); a.alpha = (double*)(h->ws + h->off_alpha);
   a.status = words; a.maxpos = words + 32;
@@ -459,8 +459,8 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   a.gate_in = c.gate_in_dim; a.n_sink = c.n_sink; a.n_recent = c.n_recent; a.budget = budget;
   // 128-key splits for the main kernel; a single key beyond a multiple of 128 (the steady state with
   // a budget that is a multiple of 128) is left to the tail kernel instead of a one-key split
-  a.S = (!no_score && h->max_live % DEC_KEYS == 1 && h->max_live > 1) ? h->max_live / DEC_KEYS
-                                                                      : (h->max_live + DEC_KEYS - 1) / DEC_KEYS;
+  a.S = (h->max_live % DEC_KEYS == 1 && h->max_live > 1) ? h->max_live / DEC_KEYS
+                                                         : (h->max_live + DEC_KEYS - 1) / DEC_KEYS;
   a.S_alloc = h->dec_splits; a.max_live = h->max_live;
   a.rms_eps = c.rms_eps; a.mem_eps = c.mem_eps; a.scale = c.softmax_scale; a.lambda = lambda; a.eta = eta;
   // the per-unit blocks come first in the prep kernel's block order: an attend-only step launches
@@ -495,7 +495,7 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
                        const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,
                        float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream) {
   return decode_launch(h, p, st, q, x_gate, q_pos, k_new, v_new, pos_new, budget, lambda, eta, out,
-                       readout_dbg, evicted_slot, scores_dbg, stream, false, "im_decode_step");
+                       readout_dbg, evicted_slot, scores_dbg, stream, false, nullptr, "im_decode_step");
 }
 
 int32_t im_attend_step(im_handle* h, const im_params* p, const im_state* st, const void* q,
@@ -504,7 +504,17 @@ int32_t im_attend_step(im_handle* h, const im_params* p, const im_state* st, con
   if (!h) return IM_ERR_INVALID_ARG;
   // budget = capacity: no unit can be above it, so nothing is evicted; lambda, eta are unused
   return decode_launch(h, p, st, q, nullptr, nullptr, k_new, v_new, pos_new, h->cfg.capacity, 1.f, 1.f, out,
-                       readout_dbg, nullptr, nullptr, stream, true, "im_attend_step");
+                       readout_dbg, nullptr, nullptr, stream, true, nullptr, "im_attend_step");
+}
+
+int32_t im_decode_step_shared(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                              const void* k_new, const void* v_new, const int32_t* pos_new,
+                              const int32_t* evict_slot, float lambda, float eta, void* out,
+                              float* readout_dbg, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(evict_slot, "evict_slot is NULL");
+  return decode_launch(h, p, st, q, nullptr, nullptr, k_new, v_new, pos_new, h->cfg.capacity, lambda, eta, out,
+                       readout_dbg, nullptr, nullptr, stream, true, evict_slot, "im_decode_step_shared");
 }
 
 }  // extern "C"

@@ -56,9 +56,27 @@ class Layer:
         B.im_memory_update(h, p, st, self.evict_idx, self.n_evict, lam, eta)
         B.im_compact_kv(h, st, self.keep_idx, self.n_keep, self.evict_idx, self.n_evict)
 
-    def decode_step(self, k_new, v_new, pos_new, q, x_gate, q_pos, budget, lam, eta, debug=False):
+    def follow_event(self, k_new, v_new, pos_new, q_attn, leader: "Layer", lam, eta):
+        """An eviction event of a follower layer of an index-sharing group: the leader's keep / evict
+        lists are applied to this layer's cache (same slot layout), nothing is scored here (a follower
+        keeps no indexer keys: its Kidx rows are moved along but never read)."""
+        h, p, st = self.h, self.p, self.st
+        B.im_append_kv(h, st, k_new, v_new, pos_new)
+        B.im_memory_update(h, p, st, leader.evict_idx, leader.n_evict, lam, eta)
+        B.im_compact_kv(h, st, leader.keep_idx, leader.n_keep, leader.evict_idx, leader.n_evict)
+        B.im_decode_attn_with_readout(h, p, st, q_attn, self.out, self.readout)
+        return self.out
+
+    def follow_step(self, k_new, v_new, pos_new, q, evict_slot, lam, eta, debug=False):
+        """One decode token of a follower layer: the slot its leader evicted leaves here too."""
+        B.im_decode_step_shared(self.h, self.p, self.st, q, k_new, v_new, pos_new, evict_slot, lam, eta,
+                                self.out, self.readout if debug else None)
+        return self.out
+
+    def decode_step(self, k_new, v_new, pos_new, q, x_gate, q_pos, budget, lam, eta, debug=False,
+                    want_evicted=False):
         """The same step for one new token per sequence through the fused entry point."""
         B.im_decode_step(self.h, self.p, self.st, q, x_gate, q_pos, k_new, v_new, pos_new, budget, lam, eta,
-                         self.out, self.readout if debug else None, self.evicted if debug else None,
-                         self.scores if debug else None)
+                         self.out, self.readout if debug else None,
+                         self.evicted if (debug or want_evicted) else None, self.scores if debug else None)
         return self.out

@@ -113,6 +113,7 @@ class LockStep:
             budget, w.lam, w.eta)
         if check:
             self.compare(scores, keep, evict, out, res, tag, fused=True)
+        return scores, keep, evict, out, res
 
     def compare(self, scores, keep, evict, out, res, tag, fused=False, lists=True, outputs=True):
         w, g = self.w, self.gpu
@@ -162,6 +163,50 @@ class LockStep:
                     rr = res[ib, ih]
                     dmax = float(np.max(np.abs(res_g[b, h] - rr)))
                     assert dmax <= 1e-3 * float(np.max(np.abs(rr))) + 1e-30, f"{u}: readout diff {dmax:.3e}"
+
+    # -- a follower layer of an index-sharing group (Appendix, IndexCache-style reuse) -------------
+    def _keep_from(self, evict):
+        return [[np.setdiff1d(np.arange(int(self.ref.len[ib, ih])), evict[ib][ih]).astype(np.int64)
+                 for ih in range(len(self.kv_heads))] for ib in range(len(self.batch_ids))]
+
+    def follow_event(self, t0: int, t1: int, leader: "LockStep", evict, tag: str):
+        """Tokens [t0, t1) enter this layer; the LEADER's evict lists (oracle's, per sampled unit)
+        are applied on both sides; attend with the last token's query."""
+        w, dev = self.w, self.dev
+        d = lambda x: x.to(dev)
+        k_new = self.K[:, :, t0:t1].contiguous(); v_new = self.V[:, :, t0:t1].contiguous()
+        pos = torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+        q_attn = self.Q[:, t1 - 1].contiguous()
+        self.gpu.follow_event(d(k_new), d(v_new), d(pos), d(q_attn), leader.gpu, w.lam, w.eta)
+        torch.cuda.synchronize()
+        bi = self.batch_ids
+        bi_t = torch.tensor(bi); hs_t = torch.tensor(self.kv_heads)
+        sel = lambda x: f64(x.index_select(0, bi_t).index_select(1, hs_t))
+        self.ref.append_kv(sel(k_new), sel(v_new), pos.numpy()[bi])
+        keep = self._keep_from(evict)
+        self.ref.memory_update(evict, w.lam, w.eta)
+        self.ref.compact_kv(keep, evict)
+        out, res = self.ref.decode_attn_with_readout(f64(q_attn.index_select(0, bi_t)))
+        self.compare(None, None, None, out, res, tag, lists=False)
+
+    def follow_step(self, t: int, leader: "LockStep", evict, tag: str):
+        """One decode token through im_decode_step_shared with the slot the leader evicted."""
+        w, dev = self.w, self.dev
+        d = lambda x: x.to(dev)
+        k_new = self.K[:, :, t:t + 1].contiguous(); v_new = self.V[:, :, t:t + 1].contiguous()
+        q = self.Q[:, t].contiguous()
+        pos = torch.full((w.batch,), t, dtype=torch.int32)
+        self.gpu.follow_step(d(k_new), d(v_new), d(pos), d(q), leader.gpu.evicted, w.lam, w.eta, debug=True)
+        torch.cuda.synchronize()
+        bi = self.batch_ids
+        bi_t = torch.tensor(bi); hs_t = torch.tensor(self.kv_heads)
+        sel = lambda x: f64(x.index_select(0, bi_t).index_select(1, hs_t))
+        self.ref.append_kv(sel(k_new), sel(v_new), pos.numpy()[bi].reshape(-1, 1))
+        keep = self._keep_from(evict)
+        self.ref.memory_update(evict, w.lam, w.eta)
+        self.ref.compact_kv(keep, evict)
+        out, res = self.ref.decode_attn_with_readout(f64(q.index_select(0, bi_t)))
+        self.compare(None, None, None, out, res, tag, lists=False)
 
     def window(self, t0: int, tau: int, budget: int, tag: str, fused=True):
         """The paper's decode schedule (Section 4, setup): tau tokens are appended and attended to one

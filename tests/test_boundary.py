@@ -105,6 +105,9 @@ def test_calls_validate_before_enqueuing(lib):
     assert lib.im_attend_step(h, C.byref(pr), C.byref(st), None, X, X, X, X, None, None) == E
     assert lib.im_attend_step(h, C.byref(pr), C.byref(st_bad), X, X, X, X, X, None, None) == E
     assert lib.im_attend_step(h, C.byref(pr), C.byref(st), X, X, X, X, None, None, None) == E
+    assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, X, X, None, 0.9, 0.5, X, None, None) == E
+    assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, X, X, X, 1.5, 0.5, X, None, None) == E
+    assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, None, X, X, 0.9, 0.5, X, None, None) == E
     assert lib.im_profile_start(h, 0, 0) == E and lib.im_profile_start(h, 4, 3) == E
     assert lib.im_query_status(h, None, None) == E
     assert b"status_host" in lib.im_last_error(h)

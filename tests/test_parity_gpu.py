@@ -57,6 +57,7 @@ def test_reduced_configurations_fused_decode(name, kw):
     ("cfg1", dict(context=500, budget=160, decode_steps=80, n_recent=16), 40, 2),   # recent window kept
     ("cfg4", dict(batch=2, context=700, budget=130, decode_steps=128), 128, 1),      # the paper's tau
     ("cfg3", dict(batch=1, context=900, budget=300, decode_steps=48), 24, 2),
+    ("cfg1", dict(context=500, budget=200, decode_steps=114), 57, 2),    # live bound 257: one key beyond the splits
 ])
 @pytest.mark.parametrize("fused", [True, False])
 def test_periodic_compression_schedule(name, kw, tau, n_win, fused):
@@ -65,6 +66,28 @@ def test_periodic_compression_schedule(name, kw, tau, n_win, fused):
     w = WORKLOADS[name].scaled(n_layers=1, **kw)
     ls = LockStep(w, capacity=max(w.context, w.budget + tau), max_queries=max(w.context, tau))
     ls.run_window_schedule(tau, n_win, fused=fused)
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("cfg1", dict(context=700, budget=256, decode_steps=6)),
+    ("cfg4", dict(batch=2, context=600, budget=130, decode_steps=5)),     # 7 query heads per KV head
+    ("cfg3", dict(batch=1, context=2900, budget=2700, decode_steps=3)),   # 22 splits: two staging rounds
+])
+def test_index_reuse_across_layers(name, kw):
+    # Appendix "From Running Mean to IndexCache": layer 0 scores and selects; layer 1 (its own
+    # weights and K / V / Q) applies layer 0's lists at the prefill event and layer 0's evicted slot
+    # at every decode step
+    w = WORKLOADS[name].scaled(n_layers=2, **kw)
+    lead = LockStep(w, layer=0, capacity=max(w.capacity, w.budget + 2))
+    foll = LockStep(w, layer=1, capacity=max(w.capacity, w.budget + 2))
+    _, _, evict, _, _ = lead.event(0, w.context, w.budget, "leader prefill")
+    foll.follow_event(0, w.context, lead, evict, "follower prefill")
+    for ls in (lead, foll):
+        im.im_set_max_live(ls.handle, w.budget + 1)
+    for t in range(w.context, w.context + w.decode_steps):
+        _, _, evict, _, _ = lead.event_fused(t, w.budget, f"leader decode@{t}")
+        foll.follow_step(t, lead, evict, f"follower decode@{t}")
+    assert im.im_query_status(lead.handle) == 0 and im.im_query_status(foll.handle) == 0
 
 
 def test_fused_decode_ties_evict_newest_then_largest_slot():
