@@ -1,11 +1,12 @@
 """Pins of the CPU oracle: each test checks an oracle function against something the paper or
 the mathematics fixes and that is computed here WITHOUT the oracle's own formula: library
 routines (torch SDPA, torch Linear / RMS statistics, torch bf16 conversion), closed forms,
-brute force and invariants.  The paper prints no worked numeric example, so there are no
-golden values of the paper's; the parameter counts of Section 4 are the only printed numbers
-that touch this path and they are pinned in test_parameter_counts."""
+brute force and invariants.  The paper prints no worked numeric example; the parameter counts of Section 4 are
+the only printed numbers that touch this path: they are kept in tests/golden/ with their
+citation and pinned in test_parameter_counts."""
 import itertools
 import math
+import os
 
 import numpy as np
 import pytest
@@ -52,10 +53,16 @@ def test_parameter_counts():
     # Section 4 "Parameter and Efficiency Analysis": 19.92 M indexer and 0.52 M memory
     # parameters on Llama-3.1-8B (32 layers, H=32, d_head=128, d_model=4096) with the paper's
     # H_idx = H/4 and d_idx = d_head/8.
+    golden = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "parameter_counts.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                k, v = line.split()
+                golden[k] = float(v)
     idx, mem = O.param_count(n_heads=32, head_dim=128, d_model=4096, n_idx_heads=8, idx_dim=16,
                              mem_dim=128, n_layers=32)
-    assert idx == 19_922_944 and round(idx / 1e6, 2) == 19.92
-    assert mem == 524_288 and round(mem / 1e6, 2) == 0.52
+    assert idx == 19_922_944 and round(idx / 1e6, 2) == golden["indexer_millions"]
+    assert mem == 524_288 and round(mem / 1e6, 2) == golden["memory_millions"]
 
 
 # ----------------------------------------------------------------------------- a1 indexer
