@@ -46,6 +46,8 @@ def test_cfg1_full_trajectory_fused_decode():
     ("cfg1", dict(context=300, budget=64, decode_steps=3, n_recent=8)),      # recent window forced
     ("cfg1", dict(n_q_heads=40, context=600, budget=150, decode_steps=3)),   # 10 indexer heads, 5 per group
     ("cfg1", dict(n_q_heads=16, context=600, budget=150, decode_steps=3)),   # 4 indexer heads, 2 per group
+    ("cfg1", dict(n_q_heads=64, context=500, budget=140, decode_steps=3)),   # 16 indexer heads, 8 per group
+    ("cfg1", dict(n_q_heads=8, context=500, budget=140, decode_steps=3)),    # 2 indexer heads, 1 per group
 ])
 def test_reduced_configurations_fused_decode(name, kw):
     w = WORKLOADS[name].scaled(n_layers=1, **kw)
