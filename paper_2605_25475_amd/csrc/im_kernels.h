@@ -388,12 +388,13 @@ __global__ void k_alpha_scale(double* __restrict__ a, int n, double denom) {
 // ------------------------------------------------------------------------------------------
 // grid (ceil(max_live / (64 TPW)), units) read as one list of (tile, unit) pairs, 4 waves; a wave owns
 // TPW tiles of 16 rows (TPW = 4 for long caches, 1 when that gives too few workgroups; the A operand,
-// kept in registers as packed bf16) and walks over the queries.  One pass of the 16x16x4 product
-// (16 steps over the 64 dims) takes 16 columns = 16 / HS queries x HS head lanes (HS = 8 when
-// H_idx <= 8, else 16); the gated ReLU terms of a query are then added over its HS lanes with
-// shifted adds inside the 16-lane row, so the last lane of each group holds the query's score of
-// the 4 keys of its register rows, and keeps the running maximum.
-template <int HS, int TPW>
+// kept in registers as packed bf16) and walks over the queries 16 at a time.  One pass of the
+// 16x16x4 product (16 steps over the 64 dims) takes ONE indexer head of 16 queries as its 16
+// columns, so a lane's result registers belong to one query and the gated ReLU terms of the heads
+// are added in place, head after head, with no cross-lane step; after the last head the block's
+// scores go into the running maximum under the position mask.  The maxima of the 16 query columns
+// meet once, at the end.
+template <int TPW>
 __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
                                                const int32_t* __restrict__ pos,
                                                const int32_t* __restrict__ len,
@@ -403,10 +404,9 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
                                                const int32_t* __restrict__ q_pos, int n_q, int H_kv,
                                                int C, int H_idx, int max_live,
                                                float* __restrict__ scores, int q_per_group) {
-  // grid z: groups of q_per_group queries (a multiple of 2), each with workgroups of its own; with
+  // grid z: groups of q_per_group queries (a multiple of 16), each with workgroups of its own; with
   // more than one group, group g writes its maxima to scores + g * units * C and k_score_max
   // folds the groups
-  constexpr int QPP = 16 / HS;   // queries per pass
   __shared__ int s_min[4];
   __shared__ int s_first[4];
   // tiles of low slots see the most queries in a prefill event: they are dispatched first, for
@@ -421,7 +421,7 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
   const int t0 = tile * (64 * TPW);
   if (t0 >= n) return;
   const int kbase = t0 + 16 * TPW * w;
-  // A operands: lane (row l16, kq) holds dims 16 kq .. 16 kq + 15 of its row in each of the 4 tiles
+  // A operands: lane (row l16, kq) holds dims 16 kq .. 16 kq + 15 of its row in each of the tiles
   // (rows past the end repeat the last live one; their scores are never written)
   uint4 ka[TPW][2];
   int posk[TPW][4];
@@ -461,62 +461,76 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
   for (int t = 0; t < TPW; ++t)
 #pragma unroll
     for (int r = 0; r < 4; ++r) imp[t][r] = -INFINITY;
-  const int jl = l16 % HS, sl = l16 / HS;
-  const bool jv = jl < H_idx;
   const int q_lo = blockIdx.z * q_per_group, q_hi = min(n_q, q_lo + q_per_group);
   scores += (size_t)blockIdx.z * units * C;
 #pragma unroll 1
-  for (int s0 = max((first / QPP) * QPP, q_lo); s0 < q_hi; s0 += QPP) {
-    const int s = min(s0 + sl, n_q - 1);
-    const bool sv = s0 + sl < n_q;
+  for (int s0 = max(first & ~15, q_lo); s0 < q_hi; s0 += 16) {
+    // this lane's query column; columns past the end repeat the last query and are masked
+    const int s = min(s0 + l16, n_q - 1);
+    const bool sv = s0 + l16 < q_hi;
     const int qp = qp_b[s];
-    // B operand: lane (column l16 = query sl, head jl; kq) holds dims 16 kq .. 16 kq + 15 of that head
-    double qd[16];
-    {
-      const uint4* src = (const uint4*)(qhat + (((size_t)b * n_q + s) * H_idx + (jv ? jl : 0)) * IM_DI + 16 * kq);
+    double acc[TPW][4];
 #pragma unroll
-      for (int m = 0; m < 8; ++m) {
-        const uint4 u = src[m];
-        qd[2 * m] = __longlong_as_double(((long long)u.y << 32) | u.x);
-        qd[2 * m + 1] = __longlong_as_double(((long long)u.w << 32) | u.z);
+    for (int t = 0; t < TPW; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[t][r] = 0.0;
+#pragma unroll 1
+    for (int j = 0; j < H_idx; ++j) {
+      // B operand: lane (column l16 = query s, kq) holds dims 16 kq .. 16 kq + 15 of head j
+      double qd[16];
+      {
+        const uint4* src = (const uint4*)(qhat + (((size_t)b * n_q + s) * H_idx + j) * IM_DI + 16 * kq);
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+          const uint4 u = src[m];
+          qd[2 * m] = __longlong_as_double(((long long)u.y << 32) | u.x);
+          qd[2 * m + 1] = __longlong_as_double(((long long)u.w << 32) | u.z);
+        }
       }
-    }
-    const double al = (jv && sv) ? alpha[((size_t)b * n_q + s) * H_idx + jl] : 0.0;   // idle lanes add 0
-    im_v4d z[TPW];
+      const double al = alpha[((size_t)b * n_q + s) * H_idx + j];
+      // keep the A operand packed: converted to fp64 ahead of the loop it would take 32 registers
+      // per tile and halve the occupancy; the conversions hide under the matrix cores
 #pragma unroll
-    for (int t = 0; t < TPW; ++t) z[t] = im_v4d{0.0, 0.0, 0.0, 0.0};
+      for (int t = 0; t < TPW; ++t)
 #pragma unroll
-    for (int m = 0; m < 16; ++m) {
+        for (int i = 0; i < 2; ++i)
+          __asm__ volatile("" : "+v"(ka[t][i].x), "+v"(ka[t][i].y), "+v"(ka[t][i].z), "+v"(ka[t][i].w));
+      im_v4d z[TPW];
 #pragma unroll
-      for (int t = 0; t < TPW; ++t) {
-        const uint4 u = ka[t][m >> 3];
-        const uint32_t wd = ((m & 7) < 2) ? u.x : ((m & 7) < 4) ? u.y : ((m & 7) < 6) ? u.z : u.w;
-        const float f = (m & 1) ? bf_hi(wd) : bf_lo(wd);
-        z[t] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)f, qd[m], z[t], 0, 0, 0);
+      for (int t = 0; t < TPW; ++t) z[t] = im_v4d{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int m = 0; m < 16; ++m) {
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+          const uint4 u = ka[t][m >> 3];
+          const uint32_t wd = ((m & 7) < 2) ? u.x : ((m & 7) < 4) ? u.y : ((m & 7) < 6) ? u.z : u.w;
+          const float f = (m & 1) ? bf_hi(wd) : bf_lo(wd);
+          z[t] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)f, qd[m], z[t], 0, 0, 0);
+        }
       }
+#pragma unroll
+      for (int t = 0; t < TPW; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) acc[t][r] = fma(al, fmax(z[t][r], 0.0), acc[t][r]);
     }
 #pragma unroll
-    for (int t = 0; t < TPW; ++t) {
+    for (int t = 0; t < TPW; ++t)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        double v = al * fmax(z[t][r], 0.0);
-        v += dpp_zero_d<0x111, 0xF>(v);
-        v += dpp_zero_d<0x112, 0xF>(v);
-        v += dpp_zero_d<0x114, 0xF>(v);
-        if (HS == 16) v += dpp_zero_d<0x118, 0xF>(v);
-        // meaningful in the last lane of each group of HS: the score of query s for key row 4 r + kq
-        const bool vis = sv && posk[t][r] <= qp;
-        imp[t][r] = vis ? fmaxf(imp[t][r], (float)v) : imp[t][r];
+        const bool vis = sv && posk[t][r] <= qp;     // key row 4 r + kq of tile t, query s
+        imp[t][r] = vis ? fmaxf(imp[t][r], (float)acc[t][r]) : imp[t][r];
       }
-    }
   }
-  // the groups' maxima meet in lane 15 of each row, which writes the 16 keys of its register rows
+  // the 16 query columns' maxima meet in lane 15 of each row, which writes the keys of its register rows
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       float v = imp[t][r];
-      if (HS == 8) v = fmaxf(v, dpp_keep_f<0x118, 0xF>(v));
+      v = fmaxf(v, dpp_keep_f<0x111, 0xF>(v));
+      v = fmaxf(v, dpp_keep_f<0x112, 0xF>(v));
+      v = fmaxf(v, dpp_keep_f<0x114, 0xF>(v));
+      v = fmaxf(v, dpp_keep_f<0x118, 0xF>(v));
       const int key = kbase + 16 * t + 4 * r + kq;
       if (l16 == 15 && key < n) scores[(size_t)unit * C + key] = v;
     }

@@ -313,16 +313,15 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
     const int want = (int)((1024 + tile_wgs - 1) / tile_wgs), most = (n_q + 15) / 16;
     groups = want < most ? want : most;
     if (groups > IM_SCORE_GROUPS) groups = IM_SCORE_GROUPS;
-    q_per_group = ((n_q + groups - 1) / groups + 1) & ~1;
+    q_per_group = ((n_q + groups - 1) / groups + 15) & ~15;
     groups = (n_q + q_per_group - 1) / q_per_group;
   }
   float* sc_out = groups > 1 ? (float*)(h->ws + h->off_spart) : scores_out;
-#define IM_SCORE(HS, TPW)                                                                                    \
-  k_score<HS, TPW><<<dim3((h->max_live + 64 * TPW - 1) / (64 * TPW), units, groups), 256, 0, s>>>(           \
+#define IM_SCORE(TPW)                                                                                        \
+  k_score<TPW><<<dim3((h->max_live + 64 * TPW - 1) / (64 * TPW), units, groups), 256, 0, s>>>(               \
       (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q, c.n_kv_heads,          \
       c.capacity, c.n_idx_heads, h->max_live, sc_out, q_per_group)
-  if (c.n_idx_heads <= 8) { if (small) IM_SCORE(8, 1); else IM_SCORE(8, 4); }
-  else { if (small) IM_SCORE(16, 1); else IM_SCORE(16, 4); }
+  if (small) IM_SCORE(1); else IM_SCORE(4);
 #undef IM_SCORE
   if (groups > 1)
     k_score_max<<<dim3((h->max_live + 255) / 256, units), 256, 0, s>>>(sc_out, groups, st->len, c.capacity,
