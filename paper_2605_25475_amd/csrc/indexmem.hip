@@ -75,7 +75,7 @@ void layout(const im_config* c, im_handle* h) {
   if (h->mem_split > 32) h->mem_split = 32;
   h->attn_chunks = (c->capacity + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK;
   size_t off = 0;
-  // status word, 16 head counters, then one newest-position word per unit
+  // status word (in a 32-word slot of its own), then one newest-position word per unit
   h->off_status = off; off = align256(off + (32 + units) * sizeof(int32_t));
   h->dec_splits = (c->capacity + DEC_KEYS - 1) / DEC_KEYS + 1;   // + the last-slot record
   h->off_qy = off;     off = align256(off + B * c->max_queries * Hi * IM_DI * sizeof(double));

@@ -31,7 +31,7 @@ def test_reduced_configurations(name, kw):
 
 
 def test_cfg1_full_trajectory_fused_decode():
-    # the same trajectory with every decode step through im_decode_step (two launches per step)
+    # the same trajectory with every decode step through im_decode_step (three launches per step)
     LockStep(WORKLOADS["cfg1"]).run_schedule(fused_decode=True)
 
 
