@@ -1194,6 +1194,270 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   }
 }
 
+// --------------------------------------------------------------------------------------------
+// k_dec_tail_head: the tail with one workgroup per (unit, query head), for launches whose units x
+// heads fit the chip once (at most one such workgroup per CU).  Every workgroup ranks the
+// candidates and forms phi_e for itself; it merges only its head's partials, 8 threads per output,
+// and the workgroup of head 0 also updates the memory state, fills the hole and publishes the
+// length.  CHW (a multiple of 8, at most 64) must hold every split of the launch.
+// --------------------------------------------------------------------------------------------
+template <int CHW>
+struct DecTailHeadSmem {
+  float pst[CHW][DEC_REC];                        // this head's partial records
+  uint32_t cst[CHW + 1][DEC_CAND];                // candidate records (+ the last-slot record)
+  float phq[IM_DM];                               // this head's readout terms from k_dec_prep
+  float rpart[DEC_MP][IM_D];
+  float sc[8];                                    // gate, then DEC_MP partial phi_q^2 . b
+  float mrg[3][8][IM_D];                          // (max, denominator, numerator) of the 8 thread groups
+  float phe2[8][IM_DM], phe[IM_DM];
+  float den, dot;
+  int e_slot, e_split;
+};
+
+template <int G, int CHW>
+__device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, const int j, DecTailHeadSmem<CHW>& sm) {
+  constexpr int CH = CHW, PER = CH / 8;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int b = u / a.H_kv, h = u % a.H_kv;
+  const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
+  const float* pbase = a.part + (size_t)u * a.S_alloc * G * DEC_REC;
+  const int d4 = tid & 31, rg = tid >> 5;    // head 0's workgroup: patch of M, rows 4 rg .. + 3, columns 4 d4 .. + 3
+  float* Mu = a.M + (size_t)u * IM_DM * IM_D;
+  const int wc = tid & 127, hh = tid >> 7;   // W_theta row wc, dims 16 hh .. 16 hh + 15
+  const int cs0 = min(CH, a.S);
+  const int LS = min(a.S, CH);               // index (and staged slot) of the last-slot record
+  {
+    // one batch: every load of the regions is in flight before the first LDS store
+    constexpr int NBP = (CH * (DEC_REC / 2) + DEC_TT - 1) / DEC_TT;
+    constexpr int NBC = (CH * DEC_CAND / 2 + DEC_TT - 1) / DEC_TT;
+    const int np2 = cs0 * (DEC_REC / 2), nc2 = cs0 * DEC_CAND / 2;
+    float2 rp[NBP], rc[NBC];
+    const float2 rl = ((const float2*)(cbase + (size_t)LS * DEC_CAND))[min(tid, DEC_CAND / 2 - 1)];
+#pragma unroll
+    for (int k = 0; k < NBP; ++k) {
+      const int idx = min(tid + DEC_TT * k, np2 - 1), sp = idx / (DEC_REC / 2), o = idx % (DEC_REC / 2);
+      rp[k] = ((const float2*)(pbase + ((size_t)sp * G + j) * DEC_REC))[o];
+    }
+#pragma unroll
+    for (int k = 0; k < NBC; ++k) rc[k] = ((const float2*)cbase)[min(tid + DEC_TT * k, nc2 - 1)];
+    // readout terms of head j: phi_q (64 pairs), the DEC_MP partial phi_q^T M (64 pairs each), 5 scalars
+    const float* qb = a.qm + (size_t)u * G * DEC_QM;
+    const int t2 = min(tid, 64 * (1 + DEC_MP) - 1), pp = (t2 - 64) / 64, oo = (t2 - 64) % 64;
+    const float* qsrc = (t2 < 64) ? qb + j * IM_DM + 2 * t2 : qb + G * IM_DM + ((size_t)pp * G + j) * IM_D + 2 * oo;
+    const float2 rq = *(const float2*)qsrc;
+    const int t3 = min(max(tid - 64 * (1 + DEC_MP), 0), DEC_MP);
+    const float rs = qb[(t3 == 0) ? G * (IM_DM + DEC_MP * IM_D) + j : G * (IM_DM + DEC_MP * IM_D + 2) + (t3 - 1) * G + j];
+    __asm__ volatile("" ::: "memory");
+    if (tid < DEC_CAND / 2) ((float2*)&sm.cst[LS][0])[tid] = rl;
+#pragma unroll
+    for (int k = 0; k < NBC; ++k)
+      if (tid + DEC_TT * k < nc2) ((float2*)&sm.cst[0][0])[tid + DEC_TT * k] = rc[k];
+#pragma unroll
+    for (int k = 0; k < NBP; ++k)
+      if (tid + DEC_TT * k < np2) ((float2*)&sm.pst[0][0])[tid + DEC_TT * k] = rp[k];
+    if (tid < 64) ((float2*)&sm.phq[0])[tid] = rq;
+    else if (tid < 64 * (1 + DEC_MP)) ((float2*)&sm.rpart[0][0])[tid - 64] = rq;
+    else if (tid <= 64 * (1 + DEC_MP) + DEC_MP) sm.sc[t3] = rs;
+  }
+  float4 Mr[4] = {};
+  float b_old = 0.f;
+  if (j == 0) {   // uniform per workgroup
+#pragma unroll
+    for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);
+    b_old = a.bvec[(size_t)u * IM_DM + wc];
+  }
+  const uint4 Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
+  const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
+  __syncthreads();
+  const int n = (int)sm.cst[0][3];
+  const int n_act = min((n + DEC_KEYS - 1) / DEC_KEYS, a.S);
+  const bool has_x = n > a.S * DEC_KEYS;      // one key beyond the splits: described by the last-slot record
+  const uint32_t* lsrec = (const uint32_t*)&sm.cst[LS][0];
+  const int x_split = has_x ? n_act : -2;
+  const int cn0 = min(CH, n_act);
+  if (w == 0) {
+    // smallest rank key over the candidates, lane = split; on a full tie the later split wins
+    const bool on = lane < cn0;
+    const int ls = on ? lane : 0;
+    const uint32_t khi = on ? sm.cst[ls][0] : 0xffffffffu;
+    const uint32_t klo = on ? sm.cst[ls][1] : 0xffffffffu;
+    const uint32_t mh = wave_min_u(khi);
+    const uint32_t ml = wave_min_u(khi == mh ? klo : 0xffffffffu);
+    const int win = (int)wave_max_u((on && khi == mh && klo == ml) ? (uint32_t)lane + 1u : 0u) - 1;
+    if (lane == 0) {
+      if (a.ext_evict) {   // the caller names the slot: the record of its split holds its rows
+        const int e = a.ext_evict[u];
+        const bool ev = e >= 0 && e < n;
+        sm.e_split = ev ? e / DEC_KEYS : -1;
+        sm.e_slot = ev ? e : -1;
+      } else {
+        unsigned long long bb = ((unsigned long long)mh << 32) | ml;
+        int bi = win;
+        if (has_x) {
+          const unsigned long long xc = ((unsigned long long)lsrec[0] << 32) | lsrec[1];
+          if (bi < 0 || xc <= bb) { bb = xc; bi = x_split; }
+        }
+        const bool ev = n > a.budget && bi >= 0;
+        sm.e_split = ev ? bi : -1;
+        sm.e_slot = !ev ? -1 : (bi == x_split) ? n - 1 : (int)sm.cst[bi][2];
+        if (j == 0 && n > a.budget + 1) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
+      }
+    }
+  }
+  // merge, first pass (beside the ranking): this thread's PER splits of output d
+  const int d = tid & 127, part = tid >> 7;
+  float rm = -1e30f, rl = 0.f, ro = 0.f;
+  {
+    float pm[PER], plv[PER], po[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const int sp = part * PER + k;
+      const float r0 = sm.pst[sp][0], r1 = sm.pst[sp][1], r2 = sm.pst[sp][2 + d];
+      const bool on = sp < cn0;
+      pm[k] = on ? r0 : -1e30f;
+      plv[k] = on ? r1 : 0.f;
+      po[k] = on ? r2 : 0.f;
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) rm = fmaxf(rm, pm[k]);
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const float s = __expf(pm[k] - rm);
+      ro = fmaf(s, po[k], ro);
+      rl = fmaf(s, plv[k], rl);
+    }
+  }
+  __syncthreads();
+  const int e_split = sm.e_split, e_slot = sm.e_slot;
+  const uint32_t* er = (e_split == x_split) ? lsrec : (const uint32_t*)&sm.cst[max(e_split, 0)][0];
+  float ve_d = 0.f;
+  float4 ve4 = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (e_slot >= 0) {   // phi_e = W_theta k_e, eight threads per row
+    ve_d = bf2f(((const bf16_t*)(er + DEC_CAND_V))[d]);
+    const uint2 t = *(const uint2*)(er + DEC_CAND_V + 2 * d4);
+    ve4 = make_float4(bf_lo(t.x), bf_hi(t.x), bf_lo(t.y), bf_hi(t.y));
+    float wv[16], kv[16];
+    unpack8(Wr0, wv);
+    unpack8(Wr1, wv + 8);
+    unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh), kv);
+    unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh + 4), kv + 8);
+    float pe = 0.f;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) pe = fmaf(wv[e], kv[e], pe);
+    sm.phe2[hh][wc] = pe;
+  }
+  uint4 mv = make_uint4(0, 0, 0, 0);           // the last live slot's rows (they move into the hole)
+  if (tid < 40) mv = *(const uint4*)(lsrec + DEC_CAND_K + 4 * tid);
+  const int mvpos = (int)lsrec[12];
+  {   // merge, second pass: add back the candidates that stay
+    float cl[PER], cv[PER];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const int sp = part * PER + k;
+      const float r3 = __uint_as_float(sm.cst[sp][4 + j]);
+      const float r4 = bf2f(((const bf16_t*)&sm.cst[sp][DEC_CAND_V])[d]);
+      const bool stays = sp < cn0 && sp != e_split && r3 != -INFINITY;   // -inf: the split left nothing out
+      cl[k] = stays ? r3 : -INFINITY;
+      cv[k] = stays ? r4 : 0.f;
+    }
+    float m = rm;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) m = fmaxf(m, cl[k]);
+    const float resc = __expf(rm - m);
+    float o = ro * resc, l = rl * resc;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+      const float pc = __expf(cl[k] - m);
+      o = fmaf(pc, cv[k], o);
+      l += pc;
+    }
+    rm = m; rl = l; ro = o;
+  }
+  if (has_x && e_split != x_split && part == 0) {   // the leftover key stays
+    const float xl = __uint_as_float(lsrec[4 + j]);
+    const float xv = bf2f(((const bf16_t*)(lsrec + DEC_CAND_V))[d]);
+    const float mn = fmaxf(rm, xl);
+    const float resc = __expf(rm - mn), pc = __expf(xl - mn);
+    ro = fmaf(pc, xv, ro * resc);
+    rl = fmaf(rl, resc, pc);
+    rm = mn;
+  }
+  sm.mrg[0][part][d] = rm; sm.mrg[1][part][d] = rl; sm.mrg[2][part][d] = ro;
+  __syncthreads();
+  if (w == 15) {   // phi_q . phi_e and the readout's denominator
+    float dn = 0.f, dt = 0.f;
+#pragma unroll
+    for (int k = 0; k < DEC_MP; ++k) dn += sm.sc[1 + k];
+    if (e_slot >= 0) {
+      float p0 = 0.f, p1 = 0.f;
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { p0 += sm.phe2[k][lane]; p1 += sm.phe2[k][lane + 64]; }
+      const float q0 = sm.phq[lane], q1 = sm.phq[lane + 64];
+      dt = wave_sum_f(fmaf(q0, p0, q1 * p1));
+      const float sq = wave_sum_f(fmaf(q0 * q0, p0 * p0, q1 * q1 * p1 * p1));
+      dn = fmaf(a.lambda, dn, a.eta * sq);
+    }
+    if (lane == 0) { sm.den = dn + a.mem_eps; sm.dot = dt; }
+  } else if (j == 0 && w >= 6 && w < 8 && e_slot >= 0) {   // b <- lambda b + eta phi_e^2 (wc = tid - 384 here)
+    float pe = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) pe += sm.phe2[k][wc];
+    sm.phe[wc] = pe;
+    a.bvec[(size_t)u * IM_DM + wc] = fmaf(a.lambda, b_old, a.eta * pe * pe);
+  }
+  float o_attn = 0.f;
+  if (tid < IM_D) {   // fold the 8 thread groups of output d
+    float m = sm.mrg[0][0][d], l = sm.mrg[1][0][d], o = sm.mrg[2][0][d];
+#pragma unroll
+    for (int p = 1; p < 8; ++p) {
+      const float m2 = sm.mrg[0][p][d], mn = fmaxf(m, m2);
+      const float s1 = __expf(m - mn), s2 = __expf(m2 - mn);
+      o = fmaf(o, s1, s2 * sm.mrg[2][p][d]);
+      l = fmaf(l, s1, s2 * sm.mrg[1][p][d]);
+      m = mn;
+    }
+    o_attn = (l > 0.f) ? o / l : 0.f;
+  }
+  __syncthreads();
+  if (tid < IM_D) {
+    // phi_q^T (lambda M + eta phi_e v_e^T) = lambda phi_q^T M + eta (phi_q . phi_e) v_e
+    float mr = 0.f;
+#pragma unroll
+    for (int k = 0; k < DEC_MP; ++k) mr += sm.rpart[k][d];
+    if (e_slot >= 0) mr = fmaf(a.lambda, mr, a.eta * sm.dot * ve_d);
+    const float res = sm.sc[0] * (mr / sm.den);
+    const size_t oi = ((size_t)b * a.H + h * G + j) * IM_D + d;
+    a.out[oi] = f2bf_rne(o_attn + res);
+    if (a.readout) a.readout[oi] = res;
+  }
+  if (j != 0) return;
+  if (e_slot >= 0) {
+    // M <- lambda M + eta phi_e v_e^T for this thread's 4 x 4 patch
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float f = a.eta * sm.phe[rg * 4 + i];
+      float4 m = Mr[i];
+      m.x = fmaf(a.lambda, m.x, f * ve4.x); m.y = fmaf(a.lambda, m.y, f * ve4.y);
+      m.z = fmaf(a.lambda, m.z, f * ve4.z); m.w = fmaf(a.lambda, m.w, f * ve4.w);
+      *(float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4) = m;
+    }
+  }
+  // fill the hole with the last entry, publish the new length
+  const int n_keep = (e_slot >= 0) ? n - 1 : n;
+  if (e_slot >= 0 && e_slot < n_keep) {
+    const size_t dst = (size_t)u * a.C + e_slot;
+    if (tid < 16) *(uint4*)(a.K + dst * IM_D + tid * 8) = mv;
+    else if (tid < 32) *(uint4*)(a.V + dst * IM_D + (tid - 16) * 8) = mv;
+    else if (tid < 40) *(uint4*)(a.Kidx + dst * IM_DI + (tid - 32) * 8) = mv;
+    else if (tid == 40) a.pos[dst] = mvpos;
+  }
+  if (tid == 0) {
+    a.len[u] = n_keep;
+    a.nproj[u] = n_keep;
+    if (a.evicted) a.evicted[u] = e_slot;
+  }
+}
+
 // grid: units * S blocks; consecutive blocks take different units, the short last splits come last
 template <int G>
 __global__ __launch_bounds__(DEC_MT, 4) void k_dec_main(const DecArgs a, const double* __restrict__ qy,
@@ -1216,4 +1480,11 @@ template <int G, int CHW>
 __global__ __launch_bounds__(DEC_TT) void k_dec_tail(const DecArgs a) {
   __shared__ __attribute__((aligned(16))) DecTailSmem<G, CHW> sm;
   dec_tail<G, CHW>(a, blockIdx.x, sm);
+}
+
+// grid: units * G blocks, one per (unit, query head)
+template <int G, int CHW>
+__global__ __launch_bounds__(DEC_TT) void k_dec_tail_head(const DecArgs a) {
+  __shared__ __attribute__((aligned(16))) DecTailHeadSmem<CHW> sm;
+  dec_tail_head<G, CHW>(a, blockIdx.x / G, blockIdx.x % G, sm);
 }

@@ -118,6 +118,15 @@ bool params_ok(const im_params* p) { return p && p->Uq && p->G && p->Uk && p->Wt
 // splits (more splits than the largest variant are merged in several rounds)
 template <int G>
 void launch_tail(const DecArgs& a, int units, hipStream_t s) {
+  // one workgroup per (unit, head) when those fill at most half the CUs (measured: at 256 such
+  // workgroups the per-unit form is faster again) and one staging round holds the splits
+  if (units * G <= 128 && a.S <= 64) {
+    if (a.S <= 8) k_dec_tail_head<G, 8><<<units * G, DEC_TT, 0, s>>>(a);
+    else if (a.S <= 16) k_dec_tail_head<G, 16><<<units * G, DEC_TT, 0, s>>>(a);
+    else if (a.S <= 32) k_dec_tail_head<G, 32><<<units * G, DEC_TT, 0, s>>>(a);
+    else k_dec_tail_head<G, 64><<<units * G, DEC_TT, 0, s>>>(a);
+    return;
+  }
   if constexpr (G <= 4) {
     if (a.S <= 8) k_dec_tail<G, 8><<<units, DEC_TT, 0, s>>>(a);
     else if (a.S <= 16) k_dec_tail<G, 16><<<units, DEC_TT, 0, s>>>(a);
