@@ -11,6 +11,16 @@
  * Section 3.2 for the evicted entries, and decode attention over the retained entries plus
  * the gated memory readout (Eq. latent_residual_fuse).
  *
+ * Two state layouts.  head_shared = 0 (default): everything above is kept per unit; indexer keys
+ * come from the cached key rows with d_index = 64.  head_shared = 1, the layer-wide form of the
+ * paper's text (Section 3.1: one indexer key per token from the hidden state, shared by all heads;
+ * Section 3.2 and Algorithm 1: one memory module per layer shared across heads, evicted rows summed
+ * across heads per token; Section 4: d_index = d_head / 8 = 16): all KV heads of a sequence form
+ * one SET that holds the same tokens in the same slots; Kidx, pos, len, n_projected, the scores,
+ * the keep / evict lists and (M, b) exist once per sequence (the H_kv axis below is dropped) and
+ * K, V stay per unit.  Tokens enter through im_append_kv_hidden.  The step-by-step entry points
+ * serve both layouts; the fused decode entry points serve head_shared = 0 only.
+ *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers unless a comment says "host".  The caller owns all
  *     device memory, including the workspace; the library never allocates device memory.
@@ -55,7 +65,7 @@ typedef struct im_config {
   int32_t head_dim;     /* d_head, must be 128                                                */
   int32_t capacity;     /* C: slots per unit in K, V, Kidx, pos, scores and the index lists   */
   int32_t n_idx_heads;  /* H_index (1..16); the paper uses H / 4 (Section 4)                  */
-  int32_t idx_dim;      /* d_index, must be 64                                                */
+  int32_t idx_dim;      /* d_index: 64 with head_shared = 0, 16 with head_shared = 1          */
   int32_t mem_dim;      /* d_mem, must be 128                                                 */
   int32_t gate_in_dim;  /* width of the gate input X_s (multiple of 16)                       */
   int32_t n_sink;       /* first token positions always kept (4 in the paper, Section 4)      */
@@ -63,6 +73,8 @@ typedef struct im_config {
   int32_t fold_block;   /* evicted rows are folded into the memory in blocks of this (64;
                            a multiple of 32)                                                   */
   int32_t max_queries;  /* largest n_q a call to im_index_score will pass                     */
+  int32_t head_shared;  /* 0: state per (batch, KV head); 1: one set per sequence (see above);
+                           then gate_in_dim is also d_model, the width of the hidden states     */
   float rms_eps;        /* RMSNorm epsilon of the indexer's QK-Norm                           */
   float mem_eps;        /* epsilon of the readout denominator (Eq. latent_readout)            */
   float softmax_scale;  /* attention logit scale, 1/sqrt(d_head)                              */
@@ -72,7 +84,8 @@ typedef struct im_config {
 typedef struct im_params {
   const void* Uq;       /* [H_index * d_index, H * d_head]  query down-projection            */
   const void* G;        /* [H_index, gate_in_dim]           head gate                        */
-  const void* Uk;       /* [d_index, d_head]                key projection, shared by heads  */
+  const void* Uk;       /* [d_index, d_head]                key projection, shared by heads
+                           (head_shared = 1: [d_index, gate_in_dim], applied to hidden states) */
   const void* norm_q_w; /* [d_index] RMSNorm weight of indexer queries, or NULL for ones     */
   const void* norm_k_w; /* [d_index] RMSNorm weight of indexer keys, or NULL for ones        */
   const void* Wtheta;   /* [d_mem, d_head] Linear_theta of the memory (no bias)              */
@@ -80,7 +93,9 @@ typedef struct im_params {
   float cg;             /* bias of the read gate                                             */
 } im_params;
 
-/* State of one layer (device pointers, read and written in place). */
+/* State of one layer (device pointers, read and written in place).  With head_shared = 1 every
+ * array but K and V drops its H_kv axis: Kidx [B, C, d_index], pos [B, C], len [B], M [B, d_mem,
+ * d_head], ... */
 typedef struct im_state {
   void* K;              /* [B, H_kv, C, d_head]  bf16                                        */
   void* V;              /* [B, H_kv, C, d_head]  bf16                                        */
@@ -117,6 +132,15 @@ int32_t im_query_status(im_handle* h, int32_t* status_host, void* stream);
 int32_t im_append_kv(im_handle* h, const im_state* st, const void* k_new, const void* v_new,
                      const int32_t* pos_new, int32_t n_new, void* stream);
 
+/* The same for head_shared = 1 (im_append_kv then returns IM_ERR_UNSUPPORTED): K, V rows as above,
+ * one position / length per sequence, and the tokens' indexer keys from their hidden states
+ * (Section 3.1 "Architecture": k_t = Norm(U_k X_t), one key for all heads):
+ * Kidx[b, len + i] = bf16(RMSNorm(Uk x_new[b, i])), fp64 arithmetic; n_projected follows len.
+ * x_new [B, n_new, gate_in_dim] bf16.  n_new <= capacity. */
+int32_t im_append_kv_hidden(im_handle* h, const im_params* p, const im_state* st, const void* k_new,
+                            const void* v_new, const void* x_new, const int32_t* pos_new,
+                            int32_t n_new, void* stream);
+
 /* Step a1, the indexer (Section 3.1 "Architecture"; Algorithm 1, `indexer`).
  *  (i)  keys: every slot in [n_projected, len) gets Kidx = bf16(RMSNorm(Uk K_slot)); then
  *       n_projected = len.
@@ -126,7 +150,9 @@ int32_t im_append_kv(im_handle* h, const im_state* st, const void* k_new, const 
  *        sum_j alpha_{s,j} ReLU(q_{s,j} . Kidx[b, h, t]),  -inf if no query may see slot t.
  * q_new [B, n_q, H, d_head] bf16; x_gate [B, n_q, gate_in_dim] bf16; q_pos [B, n_q] int32;
  * scores_out [B, H_kv, C] fp32, written for slots < len only.  1 <= n_q <= max_queries.
- * All arithmetic that feeds the stored bf16 / fp32 values is fp64. */
+ * All arithmetic that feeds the stored bf16 / fp32 values is fp64.
+ * head_shared = 1: (i) is skipped (the keys were made at the append), x_gate holds the queries'
+ * hidden states, and scores_out is [B, C]: one score per token of the sequence. */
 int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, const void* q_new,
                        const void* x_gate, const int32_t* q_pos, int32_t n_q, float* scores_out,
                        void* stream);
@@ -147,7 +173,9 @@ int32_t im_topb_select(im_handle* h, const float* scores, const im_state* st, in
  *     M <- lambda M + eta sum_i phi_i V_i^T,     b <- lambda b + eta sum_i phi_i * phi_i.
  * One call is one eviction event: lambda is applied once.  Units with n_evict = 0 are untouched.
  * Reads the evicted rows through evict_idx from the cache as it is BEFORE im_compact_kv.
- * 0 < lambda <= 1, eta > 0. */
+ * 0 < lambda <= 1, eta > 0.
+ * head_shared = 1: one memory per sequence; K_i and V_i are the sums over the KV heads of the rows
+ * in evicted slot i (Algorithm 1, `mem_write`: evicted rows are summed across heads per token). */
 int32_t im_memory_update(im_handle* h, const im_params* p, const im_state* st,
                          const int32_t* evict_idx, const int32_t* n_evict, float lambda, float eta,
                          void* stream);
@@ -155,7 +183,8 @@ int32_t im_memory_update(im_handle* h, const im_params* p, const im_state* st,
 /* Step a4, the Gather of Section 2.2 in place: kept entries in slots >= n_keep move, in ascending
  * order, into the evicted slots < n_keep, in ascending order (rows of K, V, Kidx and pos); then
  * len = n_projected = n_keep.  Requires n_projected == len on entry (im_index_score was called
- * after the last append) and the lists of im_topb_select for the current cache. */
+ * after the last append) and the lists of im_topb_select for the current cache.
+ * head_shared = 1: the sequence's lists are applied to the rows of each of its KV heads. */
 int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
                       const int32_t* n_keep, const int32_t* evict_idx, const int32_t* n_evict,
                       void* stream);
@@ -166,7 +195,8 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
  *     o_attn = softmax(softmax_scale q_j K^T) V over slots [0, len)   (0 if len = 0)
  *     phi = Wtheta q_j,  m = phi^T M / (sum_c phi_c^2 b_c + mem_eps),  g = sigmoid(wg . q_j + cg)
  *     out[b, j] = bf16(o_attn + g m);   readout_dbg[b, j] = g m  (fp32; may be NULL).
- * q, out [B, H, d_head] bf16; readout_dbg [B, H, d_head] fp32. */
+ * q, out [B, H, d_head] bf16; readout_dbg [B, H, d_head] fp32.
+ * head_shared = 1: every query head of the sequence reads the sequence's one (M, b). */
 int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_state* st,
                                     const void* q, void* out, float* readout_dbg, void* stream);
 

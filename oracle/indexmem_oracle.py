@@ -352,3 +352,111 @@ class OracleLayer:
         self.compact_kv(keep, evict)
         out, res = self.decode_attn_with_readout(q_attn)
         return scores, keep, evict, out, res
+
+
+# --------------------------------------------------------------------------------------
+# the layer-wide (head-shared) form of the paper's text
+# --------------------------------------------------------------------------------------
+class OracleLayerShared:
+    """One attention layer in the form the paper's text and Algorithm 1 describe literally:
+
+      * the indexer key of a token is made from its hidden state, k_t = Norm(U_k X_t), one key
+        for all heads (Section 3.1 "Architecture"; Algorithm 1 `indexer`), with d_index =
+        d_head / 8 (Section 4, hyper-parameters);
+      * hence one importance per token and ONE eviction set per sequence: every KV head keeps
+        the same tokens in the same slots;
+      * one latent memory per layer shared by all heads (Section 3.2, "Slow and fast weights");
+        a write sums the evicted rows across heads per token (Algorithm 1 `mem_write`) - here
+        both the key row fed to Linear_theta and the value row, so the state stays
+        [d_mem, d_head]; every query head reads the same state (Eq. latent_readout).
+
+    State per sequence b: Kidx [C, d_index], pos [C], len, (M, b); per (b, KV head): K, V
+    [C, D].  Built from the same per-equation functions as OracleLayer; `cfg.batch` counts the
+    sequences followed, all KV heads are always followed (the write needs their sum)."""
+
+    def __init__(self, cfg: OracleConfig, params: OracleParams):
+        assert cfg.kv_head_ids is None
+        self.cfg, self.p = cfg, params
+        B, Hk, C, D = cfg.batch, cfg.n_kv_heads, cfg.capacity, cfg.head_dim
+        self.K = np.zeros((B, Hk, C, D), F64)
+        self.V = np.zeros((B, Hk, C, D), F64)
+        self.Kidx = np.zeros((B, C, cfg.idx_dim), F64)
+        self.pos = np.zeros((B, C), np.int32)
+        self.len = np.zeros(B, np.int32)
+        self.M = np.zeros((B, cfg.mem_dim, D), F64)
+        self.b = np.zeros((B, cfg.mem_dim), F64)
+
+    def append_kv_hidden(self, k_new, v_new, x_new, pos_new) -> None:
+        """k_new, v_new [B, H_kv, n_new, D]; x_new [B, n_new, d_model]; pos_new [B, n_new]."""
+        n_new = k_new.shape[2]
+        for bi in range(self.cfg.batch):
+            n = int(self.len[bi])
+            assert n + n_new <= self.cfg.capacity
+            self.K[bi, :, n:n + n_new] = k_new[bi]
+            self.V[bi, :, n:n + n_new] = v_new[bi]
+            self.Kidx[bi, n:n + n_new] = key_feature(x_new[bi], self.p.Uk, self.p.norm_k_w, self.cfg.rms_eps)
+            self.pos[bi, n:n + n_new] = pos_new[bi]
+            self.len[bi] = n + n_new
+
+    def index_score(self, q_new, x_gate, q_pos) -> np.ndarray:
+        """q_new [B, n_q, H, D]; x_gate [B, n_q, d_model] (the queries' hidden states); q_pos [B, n_q]
+        -> scores [B, C] (NaN beyond len)."""
+        cfg, p = self.cfg, self.p
+        scores = np.full((cfg.batch, cfg.capacity), np.nan, F64)
+        for bi in range(cfg.batch):
+            n_q, n = q_new.shape[1], int(self.len[bi])
+            qhat = query_feature(q_new[bi].reshape(n_q, -1), p.Uq, p.norm_q_w,
+                                 cfg.n_idx_heads, cfg.idx_dim, cfg.rms_eps)
+            alpha = head_gate(x_gate[bi], p.G, cfg.n_idx_heads, cfg.idx_dim)
+            scores[bi, :n] = importance(qhat, alpha, q_pos[bi], self.Kidx[bi, :n], self.pos[bi, :n])
+        return scores
+
+    def topb_select(self, scores, budget: int):
+        keep, evict = [], []
+        for bi in range(self.cfg.batch):
+            n = int(self.len[bi])
+            k, e = select(scores[bi, :n], self.pos[bi, :n], budget, self.cfg.n_sink, self.cfg.n_recent)
+            keep.append(k)
+            evict.append(e)
+        return keep, evict
+
+    def memory_update(self, evict, lam: float, eta: float) -> None:
+        for bi in range(self.cfg.batch):
+            e = evict[bi]
+            K_E = self.K[bi][:, e].sum(axis=0)            # rows summed across heads per token
+            V_E = self.V[bi][:, e].sum(axis=0)
+            self.M[bi], self.b[bi] = memory_write(self.M[bi], self.b[bi], K_E, V_E, self.p.Wtheta, lam, eta)
+
+    def compact_kv(self, keep, evict) -> None:
+        for bi in range(self.cfg.batch):
+            for src, dst in compaction_moves(keep[bi], evict[bi]):
+                self.K[bi, :, dst] = self.K[bi, :, src]
+                self.V[bi, :, dst] = self.V[bi, :, src]
+                self.Kidx[bi, dst] = self.Kidx[bi, src]
+                self.pos[bi, dst] = self.pos[bi, src]
+            self.len[bi] = len(keep[bi])
+
+    def decode_attn_with_readout(self, q) -> Tuple[np.ndarray, np.ndarray]:
+        """q [B, H, D] -> (out, residual), each [B, H_kv, g, D]."""
+        cfg, p = self.cfg, self.p
+        g = cfg.n_q_heads // cfg.n_kv_heads
+        out = np.zeros((cfg.batch, cfg.n_kv_heads, g, cfg.head_dim), F64)
+        res = np.zeros_like(out)
+        for bi in range(cfg.batch):
+            n = int(self.len[bi])
+            for h in range(cfg.n_kv_heads):
+                qg = q[bi, h * g:(h + 1) * g]
+                o_attn = attend(qg, self.K[bi, h, :n], self.V[bi, h, :n], cfg.softmax_scale)
+                m = memory_read(qg, self.M[bi], self.b[bi], p.Wtheta, cfg.mem_eps)
+                out[bi, h], res[bi, h] = fuse(o_attn, read_gate(qg, p.wg, p.cg), m)
+        return out, res
+
+    def step(self, k_new, v_new, x_new, pos_new, q_new, x_gate, q_pos, q_attn, budget, lam, eta):
+        """append -> score -> select -> memory update -> compact -> attention + readout."""
+        self.append_kv_hidden(k_new, v_new, x_new, pos_new)
+        scores = self.index_score(q_new, x_gate, q_pos)
+        keep, evict = self.topb_select(scores, budget)
+        self.memory_update(evict, lam, eta)
+        self.compact_kv(keep, evict)
+        out, res = self.decode_attn_with_readout(q_attn)
+        return scores, keep, evict, out, res

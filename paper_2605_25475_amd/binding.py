@@ -20,7 +20,7 @@ IM_STATUS_APPEND_OVERFLOW, IM_STATUS_LIVE_EXCEEDED, IM_STATUS_OVER_BUDGET = 1, 2
 
 EXPORTS = [
     "im_workspace_bytes", "im_create", "im_destroy", "im_last_error", "im_set_max_live",
-    "im_query_status", "im_append_kv", "im_index_score", "im_topb_select", "im_memory_update",
+    "im_query_status", "im_append_kv", "im_append_kv_hidden", "im_index_score", "im_topb_select", "im_memory_update",
     "im_compact_kv", "im_decode_attn_with_readout", "im_decode_step", "im_attend_step", "im_decode_step_shared", "im_profile_start",
     "im_profile_stop",
 ]
@@ -29,7 +29,7 @@ EXPORTS = [
 class ImConfig(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "batch", "n_q_heads", "n_kv_heads", "head_dim", "capacity", "n_idx_heads", "idx_dim",
-        "mem_dim", "gate_in_dim", "n_sink", "n_recent", "fold_block", "max_queries")] + [
+        "mem_dim", "gate_in_dim", "n_sink", "n_recent", "fold_block", "max_queries", "head_shared")] + [
         ("rms_eps", C.c_float), ("mem_eps", C.c_float), ("softmax_scale", C.c_float)]
 
 
@@ -77,6 +77,8 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     lib.im_query_status.argtypes = [vp, C.POINTER(i32), vp]
     lib.im_append_kv.restype = i32
     lib.im_append_kv.argtypes = [vp, C.POINTER(ImState), vp, vp, vp, i32, vp]
+    lib.im_append_kv_hidden.restype = i32
+    lib.im_append_kv_hidden.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, vp, i32, vp]
     lib.im_index_score.restype = i32
     lib.im_index_score.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, i32, vp, vp]
     lib.im_topb_select.restype = i32
@@ -132,14 +134,19 @@ class Config:
     rms_eps: float = 1e-6
     mem_eps: float = 1e-6
     softmax_scale: float = 0.0    # 0: 1 / sqrt(head_dim)
+    head_shared: int = 0          # 1: one indexer key / eviction set / memory per sequence (idx_dim 16)
 
     def c_struct(self) -> ImConfig:
         gate = self.gate_in_dim or self.n_q_heads * self.head_dim
         scale = self.softmax_scale or self.head_dim ** -0.5
         return ImConfig(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.capacity,
                         self.n_idx_heads, self.idx_dim, self.mem_dim, gate, self.n_sink,
-                        self.n_recent, self.fold_block, self.max_queries, self.rms_eps, self.mem_eps,
-                        scale)
+                        self.n_recent, self.fold_block, self.max_queries, self.head_shared, self.rms_eps,
+                        self.mem_eps, scale)
+
+    def set_shape(self):
+        """Leading axes of everything kept per set: (B, H_kv), or (B,) in the head-shared layout."""
+        return (self.batch,) if self.head_shared else (self.batch, self.n_kv_heads)
 
 
 class Params:
@@ -157,15 +164,16 @@ class State:
 
     def __init__(self, cfg: Config, device="cuda"):
         B, Hk, Cc, D = cfg.batch, cfg.n_kv_heads, cfg.capacity, cfg.head_dim
+        S = cfg.set_shape()
         z = dict(device=device)
         self.K = torch.zeros((B, Hk, Cc, D), dtype=torch.bfloat16, **z)
         self.V = torch.zeros((B, Hk, Cc, D), dtype=torch.bfloat16, **z)
-        self.Kidx = torch.zeros((B, Hk, Cc, cfg.idx_dim), dtype=torch.bfloat16, **z)
-        self.pos = torch.zeros((B, Hk, Cc), dtype=torch.int32, **z)
-        self.len = torch.zeros((B, Hk), dtype=torch.int32, **z)
-        self.n_projected = torch.zeros((B, Hk), dtype=torch.int32, **z)
-        self.M = torch.zeros((B, Hk, cfg.mem_dim, D), dtype=torch.float32, **z)
-        self.b = torch.zeros((B, Hk, cfg.mem_dim), dtype=torch.float32, **z)
+        self.Kidx = torch.zeros(S + (Cc, cfg.idx_dim), dtype=torch.bfloat16, **z)
+        self.pos = torch.zeros(S + (Cc,), dtype=torch.int32, **z)
+        self.len = torch.zeros(S, dtype=torch.int32, **z)
+        self.n_projected = torch.zeros(S, dtype=torch.int32, **z)
+        self.M = torch.zeros(S + (cfg.mem_dim, D), dtype=torch.float32, **z)
+        self.b = torch.zeros(S + (cfg.mem_dim,), dtype=torch.float32, **z)
         self.c = ImState(*(_ptr(t) for t in (self.K, self.V, self.Kidx, self.pos, self.len,
                                              self.n_projected, self.M, self.b)))
 
@@ -219,6 +227,12 @@ def im_append_kv(h: Handle, st: State, k_new, v_new, pos_new) -> None:
     n_new = k_new.shape[2]
     h.check(h.lib.im_append_kv(h.h, C.byref(st.c), _ptr(k_new), _ptr(v_new), _ptr(pos_new), n_new,
                                _stream()))
+
+
+def im_append_kv_hidden(h: Handle, p: Params, st: State, k_new, v_new, x_new, pos_new) -> None:
+    n_new = k_new.shape[2]
+    h.check(h.lib.im_append_kv_hidden(h.h, C.byref(p.c), C.byref(st.c), _ptr(k_new), _ptr(v_new), _ptr(x_new),
+                                      _ptr(pos_new), n_new, _stream()))
 
 
 def im_index_score(h: Handle, p: Params, st: State, q_new, x_gate, q_pos, scores_out) -> None:

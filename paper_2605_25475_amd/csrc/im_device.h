@@ -6,7 +6,8 @@
 typedef uint16_t bf16_t;
 
 #define IM_D 128      // head_dim
-#define IM_DI 64      // idx_dim
+#define IM_DI 64      // idx_dim (state per KV head)
+#define IM_DI_SHARED 16   // idx_dim of the head-shared layout (d_head / 8: Section 4, hyper-parameters)
 #define IM_DM 128     // mem_dim
 #define IM_WAVE 64
 

@@ -14,6 +14,9 @@ __global__ void k_fill_i32(int32_t* p, int n, int32_t v) {
 // ------------------------------------------------------------------------------------------
 // helper: append rows
 // ------------------------------------------------------------------------------------------
+// A "set" is what shares one slot order: lengths, positions, indexer keys, lists and the memory
+// state are kept per set.  H_set KV heads form a set: 1 (a set per (batch, KV head) unit) or H_kv
+// (one set per sequence: every KV head of the layer holds the same tokens in the same slots).
 // grid (ceil(n_new*16/256), units); one thread moves one 16-byte chunk of a K row and of a V row
 __global__ __launch_bounds__(256) void k_append_rows(bf16_t* __restrict__ K, bf16_t* __restrict__ V,
                                                      int32_t* __restrict__ pos,
@@ -21,18 +24,42 @@ __global__ __launch_bounds__(256) void k_append_rows(bf16_t* __restrict__ K, bf1
                                                      const bf16_t* __restrict__ k_new,
                                                      const bf16_t* __restrict__ v_new,
                                                      const int32_t* __restrict__ pos_new, int n_new,
-                                                     int H_kv, int C) {
-  const int unit = blockIdx.y;
+                                                     int H_kv, int H_set, int C) {
+  const int unit = blockIdx.y, set = unit / H_set;
   const int idx = blockIdx.x * 256 + threadIdx.x;
   const int row = idx >> 4, ch = idx & 15;
   if (row >= n_new) return;
-  const int n = len[unit];
+  const int n = len[set];
   if (n + n_new > C) return;  // dropped; k_append_len raises the status bit
   const size_t src = ((size_t)unit * n_new + row) * IM_D + ch * 8;
   const size_t dst = ((size_t)unit * C + n + row) * IM_D + ch * 8;
   *(uint4*)(K + dst) = *(const uint4*)(k_new + src);
   *(uint4*)(V + dst) = *(const uint4*)(v_new + src);
-  if (ch == 0) pos[(size_t)unit * C + n + row] = pos_new[(size_t)(unit / H_kv) * n_new + row];
+  if (ch == 0 && unit % H_set == 0) pos[(size_t)set * C + n + row] = pos_new[(size_t)(unit / H_kv) * n_new + row];
+}
+
+// Indexer keys of n_new appended tokens from their hidden states (one key per token, shared by all
+// heads: Section 3.1 "Architecture", k_t = Norm(U_k X_t)): y[b][row][0..15] holds U_k X in fp64;
+// the rows get RMSNorm over their 16 values and go, in bf16, to slots len[b] .. of sequence b.
+// grid (ceil(n_new/16), B), 256 threads = 16 rows x 16 dims.  Runs before k_append_len.
+__global__ __launch_bounds__(256) void k_store_hidden_keys(const double* __restrict__ y,
+                                                           bf16_t* __restrict__ Kidx,
+                                                           const int32_t* __restrict__ len,
+                                                           int32_t* __restrict__ n_projected,
+                                                           const bf16_t* __restrict__ norm_w, int n_new,
+                                                           int C, float rms_eps) {
+  const int b = blockIdx.y, row = blockIdx.x * 16 + (threadIdx.x >> 4), d = threadIdx.x & 15;
+  const int n = len[b];
+  if (n + n_new > C) return;
+  if (blockIdx.x == 0 && threadIdx.x == 0) n_projected[b] = n + n_new;
+  if (row >= n_new) return;
+  const double* yr = y + ((size_t)b * n_new + row) * 16;
+  double ss = 0.0;
+#pragma unroll
+  for (int e = 0; e < 16; ++e) ss = fma(yr[e], yr[e], ss);
+  const double rr = sqrt(ss / 16.0 + (double)rms_eps);
+  const double w = norm_w ? (double)bf2f(norm_w[d]) : 1.0;
+  Kidx[((size_t)b * C + n + row) * 16 + d] = d2bf_rne(yr[d] / rr * w);
 }
 
 __global__ void k_append_len(int32_t* __restrict__ len, int n_units, int n_new, int C,
@@ -363,17 +390,18 @@ __global__ __launch_bounds__(256) void k_gemv_nt_f64(const bf16_t* __restrict__ 
   }
 }
 
-// RMSNorm of every indexer query head in place: y[m][j][0..63] -> fp32-rounded q, kept as fp64.
-// One wave per (m, j).  grid (ceil(rows/4)) with rows = M * H_idx.
-__global__ __launch_bounds__(256) void k_qnorm(double* __restrict__ y, int rows,
+// RMSNorm of every indexer query head in place: y[m][j][0..di-1] -> fp32-rounded q, kept as fp64.
+// One wave per (m, j), di <= 64.  grid (ceil(rows/4)) with rows = M * H_idx.
+__global__ __launch_bounds__(256) void k_qnorm(double* __restrict__ y, int rows, int di,
                                                const bf16_t* __restrict__ norm_w, float rms_eps) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= rows) return;
-  const double v = y[(size_t)row * IM_DI + lane];
+  const bool on = lane < di;
+  const double v = on ? y[(size_t)row * di + lane] : 0.0;
   const double ss = wave_sum_d(v * v);
-  const double rr = sqrt(ss / (double)IM_DI + (double)rms_eps);
-  const double w = norm_w ? (double)bf2f(norm_w[lane]) : 1.0;
-  y[(size_t)row * IM_DI + lane] = (double)(float)(v / rr * w);
+  const double rr = sqrt(ss / (double)di + (double)rms_eps);
+  const double w = (norm_w && on) ? (double)bf2f(norm_w[lane]) : 1.0;
+  if (on) y[(size_t)row * di + lane] = (double)(float)(v / rr * w);
 }
 
 // alpha = fp32(G x / sqrt(H_idx d_idx)), kept as fp64
@@ -389,12 +417,13 @@ __global__ void k_alpha_scale(double* __restrict__ a, int n, double denom) {
 // grid (ceil(max_live / (64 TPW)), units) read as one list of (tile, unit) pairs, 4 waves; a wave owns
 // TPW tiles of 16 rows (TPW = 4 for long caches, 1 when that gives too few workgroups; the A operand,
 // kept in registers as packed bf16) and walks over the queries 16 at a time.  One pass of the
-// 16x16x4 product (16 steps over the 64 dims) takes ONE indexer head of 16 queries as its 16
+// 16x16x4 product (DI / 4 steps over the DI dims) takes ONE indexer head of 16 queries as its 16
 // columns, so a lane's result registers belong to one query and the gated ReLU terms of the heads
 // are added in place, head after head, with no cross-lane step; after the last head the block's
 // scores go into the running maximum under the position mask.  The maxima of the 16 query columns
 // meet once, at the end.
-template <int TPW>
+// DI (64 or 16) is the indexer head dim: a lane holds DI / 4 dims of its row, packed in DI / 8 words.
+template <int TPW, int DI>
 __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
                                                const int32_t* __restrict__ pos,
                                                const int32_t* __restrict__ len,
@@ -423,13 +452,22 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
   const int kbase = t0 + 16 * TPW * w;
   // A operands: lane (row l16, kq) holds dims 16 kq .. 16 kq + 15 of its row in each of the tiles
   // (rows past the end repeat the last live one; their scores are never written)
-  uint4 ka[TPW][2];
+  constexpr int WPL = DI / 8, DPL = DI / 4;
+  uint32_t ka[TPW][WPL];
   int posk[TPW][4];
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
     const size_t row = (size_t)unit * C + min(kbase + 16 * t + l16, n - 1);
-    ka[t][0] = *(const uint4*)(Kidx + row * IM_DI + 16 * kq);
-    ka[t][1] = *(const uint4*)(Kidx + row * IM_DI + 16 * kq + 8);
+    if constexpr (DI == 64) {
+      const uint4 u0 = *(const uint4*)(Kidx + row * DI + DPL * kq);
+      const uint4 u1 = *(const uint4*)(Kidx + row * DI + DPL * kq + 8);
+      ka[t][0] = u0.x; ka[t][1] = u0.y; ka[t][2] = u0.z; ka[t][3] = u0.w;
+      ka[t][4] = u1.x; ka[t][5] = u1.y; ka[t][6] = u1.z; ka[t][7] = u1.w;
+    } else {
+      static_assert(DI == 16, "indexer head dim 64 or 16");
+      const uint2 u0 = *(const uint2*)(Kidx + row * DI + DPL * kq);
+      ka[t][0] = u0.x; ka[t][1] = u0.y;
+    }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {   // positions of the keys of this lane's result registers
       const int key = kbase + 16 * t + 4 * r + kq;
@@ -476,12 +514,12 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
       for (int r = 0; r < 4; ++r) acc[t][r] = 0.0;
 #pragma unroll 1
     for (int j = 0; j < H_idx; ++j) {
-      // B operand: lane (column l16 = query s, kq) holds dims 16 kq .. 16 kq + 15 of head j
-      double qd[16];
+      // B operand: lane (column l16 = query s, kq) holds dims DPL kq .. DPL kq + DPL - 1 of head j
+      double qd[DPL];
       {
-        const uint4* src = (const uint4*)(qhat + (((size_t)b * n_q + s) * H_idx + j) * IM_DI + 16 * kq);
+        const uint4* src = (const uint4*)(qhat + (((size_t)b * n_q + s) * H_idx + j) * DI + DPL * kq);
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
+        for (int m = 0; m < DPL / 2; ++m) {
           const uint4 u = src[m];
           qd[2 * m] = __longlong_as_double(((long long)u.y << 32) | u.x);
           qd[2 * m + 1] = __longlong_as_double(((long long)u.w << 32) | u.z);
@@ -493,17 +531,15 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
 #pragma unroll
       for (int t = 0; t < TPW; ++t)
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-          __asm__ volatile("" : "+v"(ka[t][i].x), "+v"(ka[t][i].y), "+v"(ka[t][i].z), "+v"(ka[t][i].w));
+        for (int i = 0; i < WPL; ++i) __asm__ volatile("" : "+v"(ka[t][i]));
       im_v4d z[TPW];
 #pragma unroll
       for (int t = 0; t < TPW; ++t) z[t] = im_v4d{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-      for (int m = 0; m < 16; ++m) {
+      for (int m = 0; m < DPL; ++m) {
 #pragma unroll
         for (int t = 0; t < TPW; ++t) {
-          const uint4 u = ka[t][m >> 3];
-          const uint32_t wd = ((m & 7) < 2) ? u.x : ((m & 7) < 4) ? u.y : ((m & 7) < 6) ? u.z : u.w;
+          const uint32_t wd = ka[t][m >> 1];
           const float f = (m & 1) ? bf_hi(wd) : bf_lo(wd);
           z[t] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)f, qd[m], z[t], 0, 0, 0);
         }
@@ -861,6 +897,116 @@ __global__ __launch_bounds__(256) void k_mem_partial(const bf16_t* __restrict__ 
   }
 }
 
+// The same for a set of H_set KV heads with one memory (Algorithm 1, `mem_write`: the evicted rows
+// are summed across heads per token): Phi^T = sum_h W K_h and M += sum_h Phi V_h by linearity, so
+// the sums over heads are taken inside the two products' accumulators and no summed row is ever
+// rounded.  K, V are per unit (set * H_set + head); lists, counts and the partials per set.
+// grid (n_split, sets), 4 waves; no prefetch: this runs once per eviction event of a prompt.
+__global__ __launch_bounds__(256) void k_mem_partial_sets(const bf16_t* __restrict__ K,
+                                                          const bf16_t* __restrict__ V,
+                                                          const int32_t* __restrict__ evict_idx,
+                                                          const int32_t* __restrict__ n_evict,
+                                                          const bf16_t* __restrict__ Wtheta, int C,
+                                                          int H_set, int fold_block, int n_split,
+                                                          float* __restrict__ part) {
+  __shared__ float Ps[IM_DM][IM_MEM_TOK + 1];
+  __shared__ __attribute__((aligned(16))) bf16_t Vs[IM_MEM_TOK][IM_D + 8];
+  const int set = blockIdx.y, split = blockIdx.x, tid = threadIdx.x;
+  const int ne = n_evict[set];
+  if (ne <= 0) return;
+  const int bps = im_mem_blocks_per_split(ne, fold_block, n_split);
+  const int i0 = split * bps * fold_block;
+  const int i1 = min(ne, i0 + bps * fold_block);
+  if (i0 >= i1) return;
+  const int w = tid >> 6, lane = tid & 63, l32 = lane & 31, kh = lane >> 5;
+  im_v4s wa[16];
+#pragma unroll
+  for (int ks = 0; ks < 16; ++ks)
+    wa[ks] = *(const im_v4s*)(Wtheta + (32 * w + l32) * IM_D + 8 * ks + 4 * kh);
+  im_v16f macc[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) macc[db][r] = 0.f;
+  float bsum[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) bsum[r] = 0.f;
+  const int32_t* ev = evict_idx + (size_t)set * C;
+  const int vr0 = tid >> 4, vc16 = tid & 15;
+#pragma unroll 1
+  for (int t0 = i0; t0 < i1; t0 += IM_MEM_TOK) {
+    const int ek = ev[min(t0 + l32, i1 - 1)];
+    const int ev0 = ev[min(t0 + vr0, i1 - 1)], ev1 = ev[min(t0 + vr0 + 16, i1 - 1)];
+    const bool k_on = t0 + l32 < i1, v0_on = t0 + vr0 < i1, v1_on = t0 + vr0 + 16 < i1;
+    im_v16f ph;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) ph[r] = 0.f;
+#pragma unroll 1
+    for (int hh = 0; hh < H_set; ++hh) {
+      const bf16_t* kr = K + ((size_t)(set * H_set + hh) * C + ek) * IM_D + 4 * kh;
+      im_v4s kb[16];
+#pragma unroll
+      for (int ks = 0; ks < 16; ++ks) kb[ks] = k_on ? *(const im_v4s*)(kr + 8 * ks) : im_v4s{0, 0, 0, 0};
+#pragma unroll
+      for (int ks = 0; ks < 16; ++ks) ph = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(wa[ks], kb[ks], ph, 0, 0, 0);
+    }
+    __syncthreads();   // the previous tile's reads of Ps are done
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      Ps[32 * w + 8 * (r >> 2) + 4 * kh + (r & 3)][l32] = ph[r];
+      bsum[r] = fmaf(ph[r], ph[r], bsum[r]);
+    }
+    __syncthreads();
+    im_v4s ah[4], al[4];
+#pragma unroll
+    for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float p = Ps[32 * w + l32][8 * kt + 4 * kh + e];
+        const bf16_t hi = f2bf_rne(p);
+        const bf16_t lo = f2bf_rne(p - bf2f(hi));
+        ah[kt][e] = (short)hi;
+        al[kt][e] = (short)lo;
+      }
+#pragma unroll 1
+    for (int hh = 0; hh < H_set; ++hh) {
+      const size_t ub = (size_t)(set * H_set + hh) * C;
+      const uint4 vv0 = v0_on ? *(const uint4*)(V + (ub + ev0) * IM_D + vc16 * 8) : make_uint4(0, 0, 0, 0);
+      const uint4 vv1 = v1_on ? *(const uint4*)(V + (ub + ev1) * IM_D + vc16 * 8) : make_uint4(0, 0, 0, 0);
+      __syncthreads();   // the previous head's reads of Vs are done
+      *(uint4*)&Vs[vr0][vc16 * 8] = vv0;
+      *(uint4*)&Vs[vr0 + 16][vc16 * 8] = vv1;
+      __syncthreads();
+#pragma unroll
+      for (int kt = 0; kt < 4; ++kt)
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          im_v4s vb;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) vb[e] = (short)Vs[8 * kt + 4 * kh + e][32 * db + l32];
+          macc[db] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ah[kt], vb, macc[db], 0, 0, 0);
+          macc[db] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(al[kt], vb, macc[db], 0, 0, 0);
+        }
+    }
+  }
+  float* out = part + ((size_t)set * n_split + split) * (IM_DM * IM_D + IM_DM);
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      out[(32 * w + 8 * (r >> 2) + 4 * kh + (r & 3)) * IM_D + 32 * db + l32] = macc[db][r];
+  __syncthreads();
+#pragma unroll
+  for (int r = 0; r < 16; ++r) Ps[32 * w + 8 * (r >> 2) + 4 * kh + (r & 3)][l32] = bsum[r];
+  __syncthreads();
+  if (tid < IM_DM) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < IM_MEM_TOK; ++i) t += Ps[tid][i];
+    out[IM_DM * IM_D + tid] = t;
+  }
+}
+
 // grid (ceil((DM*D + DM)/256), units)
 __global__ __launch_bounds__(256) void k_mem_finalize(float* __restrict__ M, float* __restrict__ bvec,
                                                       const int32_t* __restrict__ n_evict,
@@ -884,18 +1030,22 @@ __global__ __launch_bounds__(256) void k_mem_finalize(float* __restrict__ M, flo
 // ------------------------------------------------------------------------------------------
 // a4: in-place compaction by hole filling.  One wave moves one entry (K, V, Kidx rows and pos).
 // ------------------------------------------------------------------------------------------
-// grid (gx, units)
+// grid (gx, units): every KV head of a set applies the set's lists to its own K / V rows; the first
+// head of the set also moves the set's indexer-key rows (di values each) and positions
 __global__ __launch_bounds__(256) void k_compact(bf16_t* __restrict__ K, bf16_t* __restrict__ V,
                                                  bf16_t* __restrict__ Kidx, int32_t* __restrict__ pos,
                                                  int32_t* __restrict__ len,
                                                  int32_t* __restrict__ n_projected,
                                                  const int32_t* __restrict__ keep_idx,
                                                  const int32_t* __restrict__ n_keep,
-                                                 const int32_t* __restrict__ evict_idx, int C) {
+                                                 const int32_t* __restrict__ evict_idx, int C, int H_set,
+                                                 int di) {
   const int unit = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int nk = n_keep[unit];
-  const int32_t* keep = keep_idx + (size_t)unit * C;
-  const int32_t* evict = evict_idx + (size_t)unit * C;
+  const int set = unit / H_set;
+  const bool lead = unit % H_set == 0;
+  const int nk = n_keep[set];
+  const int32_t* keep = keep_idx + (size_t)set * C;
+  const int32_t* evict = evict_idx + (size_t)set * C;
   // p = number of kept slots below nk (keep is ascending)
   int lo = 0, hi = nk;
   while (lo < hi) {
@@ -904,14 +1054,16 @@ __global__ __launch_bounds__(256) void k_compact(bf16_t* __restrict__ K, bf16_t*
   }
   const int p = lo, n_moves = nk - p;
   for (int j = blockIdx.x * 4 + w; j < n_moves; j += gridDim.x * 4) {
-    const size_t src = (size_t)unit * C + keep[p + j];
-    const size_t dst = (size_t)unit * C + evict[j];
+    const int ss = keep[p + j], ds = evict[j];
+    const size_t src = (size_t)unit * C + ss, dst = (size_t)unit * C + ds;
+    const size_t isrc = (size_t)set * C + ss, idst = (size_t)set * C + ds;
     if (lane < 16) *(uint4*)(K + dst * IM_D + lane * 8) = *(const uint4*)(K + src * IM_D + lane * 8);
     else if (lane < 32) *(uint4*)(V + dst * IM_D + (lane - 16) * 8) = *(const uint4*)(V + src * IM_D + (lane - 16) * 8);
-    else if (lane < 40) *(uint4*)(Kidx + dst * IM_DI + (lane - 32) * 8) = *(const uint4*)(Kidx + src * IM_DI + (lane - 32) * 8);
-    else if (lane == 40) pos[dst] = pos[src];
+    else if (lane < 32 + di / 8) {
+      if (lead) *(uint4*)(Kidx + idst * di + (lane - 32) * 8) = *(const uint4*)(Kidx + isrc * di + (lane - 32) * 8);
+    } else if (lane == 40 && lead) pos[idst] = pos[isrc];
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0) { len[unit] = nk; n_projected[unit] = nk; }
+  if (lead && blockIdx.x == 0 && threadIdx.x == 0) { len[set] = nk; n_projected[set] = nk; }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -926,13 +1078,13 @@ __global__ __launch_bounds__(256) void k_attn_partial(const bf16_t* __restrict__
                                                       const bf16_t* __restrict__ V,
                                                       const int32_t* __restrict__ len,
                                                       const bf16_t* __restrict__ q, int H, int H_kv,
-                                                      int C, int max_live, float scale,
+                                                      int H_set, int C, int max_live, float scale,
                                                       float* __restrict__ part, int n_chunks) {
   __shared__ float s_ml[4][G][2];
   __shared__ float s_acc[4][G][IM_D];
   const int unit = blockIdx.y, chunk = blockIdx.x;
   const int b = unit / H_kv, h = unit % H_kv;
-  const int n = min(len[unit], max_live);
+  const int n = min(len[unit / H_set], max_live);
   const int k0 = chunk * IM_ATT_CHUNK;
   if (k0 >= n) return;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, grp = lane >> 4, l16 = lane & 15;
@@ -1026,7 +1178,7 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
                                                       const bf16_t* __restrict__ wg, float cg,
                                                       const float* __restrict__ M,
                                                       const float* __restrict__ bvec, int H, int H_kv,
-                                                      int max_live, float mem_eps,
+                                                      int H_set, int max_live, float mem_eps,
                                                       bf16_t* __restrict__ out,
                                                       float* __restrict__ readout_dbg) {
   __shared__ float qs[IM_D];
@@ -1034,7 +1186,7 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
   __shared__ float red[2][2];
   const int bh = blockIdx.x, tid = threadIdx.x;
   const int b = bh / H, j = bh % H, G = H / H_kv, h = j / G;
-  const int unit = b * H_kv + h;
+  const int unit = (b * H_kv + h) / H_set;   // the set: it owns the length and the memory state
   const int n = min(len[unit], max_live);
   const int nch = min((n + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK, n_chunks);
   const float* rec = part + (size_t)bh * n_chunks * IM_ATT_REC;

@@ -20,7 +20,7 @@ struct im_handle {
   int max_live;
   bool ws_ready;
   // workspace layout (byte offsets)
-  size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, off_dqm, off_spart, total;
+  size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, off_dqm, off_spart, off_xk, total;
   int mem_split, attn_chunks, dec_splits;
   // optional kernel timing (im_profile_start / im_profile_stop)
   hipEvent_t* prof_ev;
@@ -59,9 +59,10 @@ const char* config_problem(const im_config* c, int* code) {
   if (!(c->rms_eps >= 0.f) || !(c->mem_eps > 0.f) || !(c->softmax_scale > 0.f))
     return "rms_eps >= 0, mem_eps > 0 and softmax_scale > 0 are required";
   if ((long long)c->batch * c->n_kv_heads > 65535) return "batch * n_kv_heads must be <= 65535";
+  if (c->head_shared != 0 && c->head_shared != 1) return "head_shared must be 0 or 1";
   *code = IM_ERR_UNSUPPORTED;
   if (c->head_dim != IM_D) return "head_dim must be 128";
-  if (c->idx_dim != IM_DI) return "idx_dim must be 64";
+  if (c->idx_dim != (c->head_shared ? IM_DI_SHARED : IM_DI)) return "idx_dim must be 64 (16 with head_shared = 1)";
   if (c->mem_dim != IM_DM) return "mem_dim must be 128";
   if (c->n_q_heads / c->n_kv_heads > 8) return "more than 8 query heads per KV head";
   *code = IM_OK;
@@ -86,6 +87,8 @@ void layout(const im_config* c, im_handle* h) {
   h->off_dcand = off;  off = align256(off + units * h->dec_splits * DEC_CAND * sizeof(uint32_t));
   h->off_dqm = off;    off = align256(off + units * DEC_GMAX * DEC_QM * sizeof(float));
   h->off_spart = off;  off = align256(off + (size_t)IM_SCORE_GROUPS * units * c->capacity * sizeof(float));
+  // head_shared: U_k X of the rows of one append, fp64
+  h->off_xk = off;     off = align256(off + (c->head_shared ? B * c->capacity * IM_DI_SHARED * sizeof(double) : 0));
   h->total = off;
 }
 
@@ -110,6 +113,10 @@ bool state_ok(const im_state* st) {
   return st && st->K && st->V && st->Kidx && st->pos && st->len && st->n_projected && st->M && st->b;
 }
 bool params_ok(const im_params* p) { return p && p->Uq && p->G && p->Uk && p->Wtheta && p->wg; }
+
+// KV heads per set, and the number of sets (what lengths, lists and the memory state are kept per)
+int heads_per_set(const im_config& c) { return c.head_shared ? c.n_kv_heads : 1; }
+int n_sets(const im_config& c) { return c.batch * c.n_kv_heads / heads_per_set(c); }
 
 #define IM_REQUIRE(cond, msg) \
   do { if (!(cond)) return set_err(h, IM_ERR_INVALID_ARG, "%s: %s", __func__, msg); } while (0)
@@ -267,6 +274,7 @@ int32_t im_append_kv(im_handle* h, const im_state* st, const void* k_new, const 
   IM_REQUIRE(state_ok(st), "state has a NULL pointer");
   IM_REQUIRE(k_new && v_new && pos_new, "k_new / v_new / pos_new is NULL");
   IM_REQUIRE(n_new >= 1 && n_new <= h->cfg.capacity, "n_new must be in 1..capacity");
+  if (h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_append_kv: head_shared = 1 takes im_append_kv_hidden");
   hipStream_t s = (hipStream_t)stream;
   int rc = ensure_ws(h, s);
   if (rc) return rc;
@@ -275,9 +283,40 @@ int32_t im_append_kv(im_handle* h, const im_state* st, const void* k_new, const 
   dim3 grid((n_new * 16 + 255) / 256, units);
   k_append_rows<<<grid, 256, 0, s>>>((bf16_t*)st->K, (bf16_t*)st->V, st->pos, st->len,
                                      (const bf16_t*)k_new, (const bf16_t*)v_new, pos_new, n_new,
-                                     c.n_kv_heads, c.capacity);
+                                     c.n_kv_heads, 1, c.capacity);
   k_append_len<<<(units + 255) / 256, 256, 0, s>>>(st->len, units, n_new, c.capacity, status_ptr(h));
   return launch_check(h, "im_append_kv");
+}
+
+int32_t im_append_kv_hidden(im_handle* h, const im_params* p, const im_state* st, const void* k_new,
+                            const void* v_new, const void* x_new, const int32_t* pos_new,
+                            int32_t n_new, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(params_ok(p), "params has a NULL pointer");
+  IM_REQUIRE(state_ok(st), "state has a NULL pointer");
+  IM_REQUIRE(k_new && v_new && x_new && pos_new, "k_new / v_new / x_new / pos_new is NULL");
+  IM_REQUIRE(n_new >= 1 && n_new <= h->cfg.capacity, "n_new must be in 1..capacity");
+  if (!h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_append_kv_hidden: head_shared = 0 takes im_append_kv");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  const im_config& c = h->cfg;
+  const int units = c.batch * c.n_kv_heads;
+  dim3 grid((n_new * 16 + 255) / 256, units);
+  k_append_rows<<<grid, 256, 0, s>>>((bf16_t*)st->K, (bf16_t*)st->V, st->pos, st->len,
+                                     (const bf16_t*)k_new, (const bf16_t*)v_new, pos_new, n_new,
+                                     c.n_kv_heads, c.n_kv_heads, c.capacity);
+  double* xk = (double*)(h->ws + h->off_xk);
+  const int M = c.batch * n_new;
+  if (M <= 32)
+    k_gemv_nt_f64<<<IM_DI_SHARED / 2, 256, 0, s>>>((const bf16_t*)x_new, (const bf16_t*)p->Uk, xk, M, IM_DI_SHARED,
+                                                   c.gate_in_dim);
+  else
+    gemm_nt(s, (const bf16_t*)x_new, (const bf16_t*)p->Uk, xk, M, IM_DI_SHARED, c.gate_in_dim);
+  k_store_hidden_keys<<<dim3((n_new + 15) / 16, c.batch), 256, 0, s>>>(
+      xk, (bf16_t*)st->Kidx, st->len, st->n_projected, (const bf16_t*)p->norm_k_w, n_new, c.capacity, c.rms_eps);
+  k_append_len<<<(c.batch + 255) / 256, 256, 0, s>>>(st->len, c.batch, n_new, c.capacity, status_ptr(h));
+  return launch_check(h, "im_append_kv_hidden");
 }
 
 int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, const void* q_new,
@@ -292,15 +331,16 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
   int rc = ensure_ws(h, s);
   if (rc) return rc;
   const im_config& c = h->cfg;
-  const int units = c.batch * c.n_kv_heads;
+  const int units = n_sets(c), di = c.idx_dim;
   double* qy = (double*)(h->ws + h->off_qy);
   double* al = (double*)(h->ws + h->off_alpha);
 
-  k_project_keys<<<dim3((h->max_live + 63) / 64, units), 256, 0, s>>>(
-      (const bf16_t*)st->K, (bf16_t*)st->Kidx, st->len, st->n_projected, (const bf16_t*)p->Uk,
-      (const bf16_t*)p->norm_k_w, c.capacity, h->max_live, c.rms_eps, status_ptr(h));
+  if (!c.head_shared)
+    k_project_keys<<<dim3((h->max_live + 63) / 64, units), 256, 0, s>>>(
+        (const bf16_t*)st->K, (bf16_t*)st->Kidx, st->len, st->n_projected, (const bf16_t*)p->Uk,
+        (const bf16_t*)p->norm_k_w, c.capacity, h->max_live, c.rms_eps, status_ptr(h));
 
-  const int M = c.batch * n_q, Nq = c.n_idx_heads * IM_DI, Kq = c.n_q_heads * IM_D;
+  const int M = c.batch * n_q, Nq = c.n_idx_heads * di, Kq = c.n_q_heads * IM_D;
   if (M <= 32) {
     k_gemv_nt_f64<<<(Nq + 1) / 2, 256, 0, s>>>((const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, M, Nq, Kq);
     k_gemv_nt_f64<<<(c.n_idx_heads + 1) / 2, 256, 0, s>>>((const bf16_t*)x_gate, (const bf16_t*)p->G, al,
@@ -310,8 +350,8 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
     gemm_nt(s, (const bf16_t*)x_gate, (const bf16_t*)p->G, al, M, c.n_idx_heads, c.gate_in_dim);
   }
   const int rows = M * c.n_idx_heads;
-  k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, (const bf16_t*)p->norm_q_w, c.rms_eps);
-  k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, sqrt((double)(c.n_idx_heads * IM_DI)));
+  k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, di, (const bf16_t*)p->norm_q_w, c.rms_eps);
+  k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, sqrt((double)(c.n_idx_heads * di)));
   // a launch over a short cache has few (256-key tile, unit) workgroups: its queries then go in up
   // to IM_SCORE_GROUPS groups with workgroups of their own (partial maxima in the workspace,
   // folded by k_score_max); a very short one also drops to 16 keys per wave
@@ -326,11 +366,13 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
     groups = (n_q + q_per_group - 1) / q_per_group;
   }
   float* sc_out = groups > 1 ? (float*)(h->ws + h->off_spart) : scores_out;
-#define IM_SCORE(TPW)                                                                                        \
-  k_score<TPW><<<dim3((h->max_live + 64 * TPW - 1) / (64 * TPW), units, groups), 256, 0, s>>>(               \
-      (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q, c.n_kv_heads,          \
-      c.capacity, c.n_idx_heads, h->max_live, sc_out, q_per_group)
-  if (small) IM_SCORE(1); else IM_SCORE(4);
+  // (the kernel's "units" are the sets; H_kv / H_set of them belong to one batch element)
+#define IM_SCORE(TPW, DI)                                                                                    \
+  k_score<TPW, DI><<<dim3((h->max_live + 64 * TPW - 1) / (64 * TPW), units, groups), 256, 0, s>>>(           \
+      (const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al, q_pos, n_q,                        \
+      c.n_kv_heads / heads_per_set(c), c.capacity, c.n_idx_heads, h->max_live, sc_out, q_per_group)
+  if (c.head_shared) { if (small) IM_SCORE(1, IM_DI_SHARED); else IM_SCORE(4, IM_DI_SHARED); }
+  else { if (small) IM_SCORE(1, IM_DI); else IM_SCORE(4, IM_DI); }
 #undef IM_SCORE
   if (groups > 1)
     k_score_max<<<dim3((h->max_live + 255) / 256, units), 256, 0, s>>>(sc_out, groups, st->len, c.capacity,
@@ -350,7 +392,7 @@ int32_t im_topb_select(im_handle* h, const float* scores, const im_state* st, in
   int rc = ensure_ws(h, s);
   if (rc) return rc;
   const im_config& c = h->cfg;
-  k_select<<<c.batch * c.n_kv_heads, 1024, 0, s>>>(scores, st->pos, st->len, c.capacity, h->max_live,
+  k_select<<<n_sets(c), 1024, 0, s>>>(scores, st->pos, st->len, c.capacity, h->max_live,
                                                   budget, c.n_sink, c.n_recent, keep_idx, evict_idx,
                                                   n_keep, n_evict);
   return launch_check(h, "im_topb_select");
@@ -369,11 +411,16 @@ int32_t im_memory_update(im_handle* h, const im_params* p, const im_state* st,
   int rc = ensure_ws(h, s);
   if (rc) return rc;
   const im_config& c = h->cfg;
-  const int units = c.batch * c.n_kv_heads;
+  const int units = n_sets(c);
   float* part = (float*)(h->ws + h->off_mem);
-  k_mem_partial<<<dim3(h->mem_split, units), 256, 0, s>>>(
-      (const bf16_t*)st->K, (const bf16_t*)st->V, evict_idx, n_evict, (const bf16_t*)p->Wtheta,
-      c.capacity, c.fold_block, h->mem_split, part);
+  if (c.head_shared)
+    k_mem_partial_sets<<<dim3(h->mem_split, units), 256, 0, s>>>(
+        (const bf16_t*)st->K, (const bf16_t*)st->V, evict_idx, n_evict, (const bf16_t*)p->Wtheta,
+        c.capacity, c.n_kv_heads, c.fold_block, h->mem_split, part);
+  else
+    k_mem_partial<<<dim3(h->mem_split, units), 256, 0, s>>>(
+        (const bf16_t*)st->K, (const bf16_t*)st->V, evict_idx, n_evict, (const bf16_t*)p->Wtheta,
+        c.capacity, c.fold_block, h->mem_split, part);
   k_mem_finalize<<<dim3((IM_DM * IM_D + IM_DM + 255) / 256, units), 256, 0, s>>>(
       st->M, st->b, n_evict, part, c.fold_block, h->mem_split, lambda, eta);
   return launch_check(h, "im_memory_update");
@@ -392,7 +439,7 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
   if (gx > 64) gx = 64;
   k_compact<<<dim3(gx, c.batch * c.n_kv_heads), 256, 0, s>>>(
       (bf16_t*)st->K, (bf16_t*)st->V, (bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, keep_idx,
-      n_keep, evict_idx, c.capacity);
+      n_keep, evict_idx, c.capacity, heads_per_set(c), c.idx_dim);
   return launch_check(h, "im_compact_kv");
 }
 
@@ -414,7 +461,8 @@ int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_s
   case g:                                                                                       \
     k_attn_partial<g><<<grid, 256, 0, s>>>((const bf16_t*)st->K, (const bf16_t*)st->V, st->len,   \
                                            (const bf16_t*)q, c.n_q_heads, c.n_kv_heads,         \
-                                           c.capacity, h->max_live, c.softmax_scale, part,      \
+                                           heads_per_set(c), c.capacity, h->max_live,           \
+                                           c.softmax_scale, part,                               \
                                            h->attn_chunks);                                     \
     break;
   switch (G) {
@@ -425,7 +473,8 @@ int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_s
 #undef IM_ATT_CASE
   k_attn_combine<<<c.batch * c.n_q_heads, 128, 0, s>>>(
       part, h->attn_chunks, st->len, (const bf16_t*)q, (const bf16_t*)p->Wtheta, (const bf16_t*)p->wg,
-      p->cg, st->M, st->b, c.n_q_heads, c.n_kv_heads, h->max_live, c.mem_eps, (bf16_t*)out, readout_dbg);
+      p->cg, st->M, st->b, c.n_q_heads, c.n_kv_heads, heads_per_set(c), h->max_live, c.mem_eps, (bf16_t*)out,
+      readout_dbg);
   return launch_check(h, "im_decode_attn_with_readout");
 }
 
@@ -445,6 +494,7 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   IM_REQUIRE(eta > 0.f, "eta must be > 0");
   const im_config& c = h->cfg;
   if (c.batch > 64) return set_err(h, IM_ERR_UNSUPPORTED, "%s: batch above 64", what);
+  if (c.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "%s: head_shared = 1 is served step by step only", what);
   hipStream_t s = (hipStream_t)stream;
   int rc = ensure_ws(h, s);
   if (rc) return rc;

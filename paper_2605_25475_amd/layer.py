@@ -14,20 +14,24 @@ class Layer:
         cfg = handle.cfg
         self.h, self.p, self.cfg = handle, params, cfg
         self.st = B.State(cfg, device)
-        Bz, Hk, Cc = cfg.batch, cfg.n_kv_heads, cfg.capacity
-        self.scores = torch.empty((Bz, Hk, Cc), dtype=torch.float32, device=device)
-        self.keep_idx = torch.empty((Bz, Hk, Cc), dtype=torch.int32, device=device)
-        self.evict_idx = torch.empty((Bz, Hk, Cc), dtype=torch.int32, device=device)
-        self.n_keep = torch.zeros((Bz, Hk), dtype=torch.int32, device=device)
-        self.n_evict = torch.zeros((Bz, Hk), dtype=torch.int32, device=device)
+        Bz, Cc, S = cfg.batch, cfg.capacity, cfg.set_shape()
+        self.scores = torch.empty(S + (Cc,), dtype=torch.float32, device=device)
+        self.keep_idx = torch.empty(S + (Cc,), dtype=torch.int32, device=device)
+        self.evict_idx = torch.empty(S + (Cc,), dtype=torch.int32, device=device)
+        self.n_keep = torch.zeros(S, dtype=torch.int32, device=device)
+        self.n_evict = torch.zeros(S, dtype=torch.int32, device=device)
         self.out = torch.empty((Bz, cfg.n_q_heads, cfg.head_dim), dtype=torch.bfloat16, device=device)
         self.readout = torch.empty((Bz, cfg.n_q_heads, cfg.head_dim), dtype=torch.float32, device=device)
-        self.evicted = torch.full((Bz, Hk), -1, dtype=torch.int32, device=device)
+        self.evicted = torch.full(S, -1, dtype=torch.int32, device=device)
 
-    def step(self, k_new, v_new, pos_new, q_new, x_gate, q_pos, q_attn, budget, lam, eta):
-        """append -> score -> select -> memory update -> compact -> attention + readout."""
+    def step(self, k_new, v_new, pos_new, q_new, x_gate, q_pos, q_attn, budget, lam, eta, x_new=None):
+        """append -> score -> select -> memory update -> compact -> attention + readout.
+        x_new: the new tokens' hidden states (head-shared layout only)."""
         h, p, st = self.h, self.p, self.st
-        B.im_append_kv(h, st, k_new, v_new, pos_new)
+        if self.cfg.head_shared:
+            B.im_append_kv_hidden(h, p, st, k_new, v_new, x_new, pos_new)
+        else:
+            B.im_append_kv(h, st, k_new, v_new, pos_new)
         B.im_index_score(h, p, st, q_new, x_gate, q_pos, self.scores)
         B.im_topb_select(h, self.scores, st, budget, self.keep_idx, self.evict_idx, self.n_keep, self.n_evict)
         B.im_memory_update(h, p, st, self.evict_idx, self.n_evict, lam, eta)

@@ -32,5 +32,6 @@ def oracle_config(w: Workload, capacity=None, batch=None, kv_head_ids=None) -> O
                           kv_head_ids=kv_head_ids)
 
 
-def make_oracle_layer(w: Workload, layer: int = 0, device="cpu", **kw) -> O.OracleLayer:
-    return O.OracleLayer(oracle_config(w, **kw), oracle_params(layer_params(w, layer, device)))
+def make_oracle_layer(w: Workload, layer: int = 0, device="cpu", **kw):
+    cls = O.OracleLayerShared if w.head_shared else O.OracleLayer
+    return cls(oracle_config(w, **kw), oracle_params(layer_params(w, layer, device)))

@@ -16,7 +16,7 @@ import torch
 
 import paper_2605_25475_amd as im
 from helpers import f64, make_oracle_layer
-from workloads import Workload, layer_params, token_stream
+from workloads import Workload, hidden_stream, layer_params, token_stream
 
 
 def rms(x):
@@ -270,4 +270,92 @@ class LockStep:
                 self.event_fused(t, w.budget, f"fused decode@{t}")
             else:
                 self.event(t, t + 1, w.budget, f"decode@{t}")
+        assert im.im_query_status(self.handle) == 0
+
+
+class LockStepShared:
+    """The same for the head-shared layout (one indexer key per token from its hidden state, one
+    eviction set and one memory per sequence): events through the step-by-step entry points.  The
+    oracle follows a subset of the sequences, with all their KV heads."""
+
+    def __init__(self, w: Workload, layer: int = 0, device="cuda", gen_device="cpu", batch_ids=None):
+        assert w.head_shared
+        self.w, self.dev = w, device
+        p = layer_params(w, layer, gen_device)
+        cfg = im.Config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, capacity=w.capacity,
+                        n_idx_heads=w.n_idx_heads, idx_dim=w.idx_dim, n_sink=w.n_sink, n_recent=w.n_recent,
+                        fold_block=w.fold_block, head_shared=1,
+                        max_queries=max(w.context if w.prefill_chunk is None else w.prefill_chunk, 1))
+        self.handle = im.Handle(cfg, device)
+        pd = {k: (v.to(device) if torch.is_tensor(v) else v) for k, v in p.items()}
+        self.params = im.Params(pd["Uq"], pd["G"], pd["Uk"], pd["Wtheta"], pd["wg"], pd["cg"],
+                                pd["norm_q_w"], pd["norm_k_w"])
+        self.gpu = im.Layer(self.handle, self.params, device)
+        self.batch_ids = list(range(w.batch)) if batch_ids is None else list(batch_ids)
+        self.ref = make_oracle_layer(w, layer, gen_device, batch=len(self.batch_ids))
+        self.K, self.V, self.Q = token_stream(w, layer, gen_device)
+        self.X = hidden_stream(w, layer, gen_device)
+
+    def event(self, t0: int, t1: int, budget: int, tag: str):
+        w, dev = self.w, self.dev
+        d = lambda t: t.to(dev)
+        k_new = self.K[:, :, t0:t1].contiguous(); v_new = self.V[:, :, t0:t1].contiguous()
+        q_new = self.Q[:, t0:t1].contiguous(); x_new = self.X[:, t0:t1].contiguous()
+        pos = torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+        q_attn = self.Q[:, t1 - 1].contiguous()
+        xd = d(x_new)
+        self.gpu.step(d(k_new), d(v_new), d(pos), d(q_new), xd, d(pos), d(q_attn), budget, w.lam, w.eta, x_new=xd)
+        torch.cuda.synchronize()
+        bi_t = torch.tensor(self.batch_ids, device=k_new.device)
+        sel = lambda x: f64(x.index_select(0, bi_t))
+        posn = pos.numpy()[self.batch_ids]
+        xn = sel(x_new)
+        ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn, posn, sel(q_attn), budget, w.lam, w.eta)
+        self.compare(*ref, tag)
+
+    def compare(self, scores, keep, evict, out, res, tag):
+        w, g, st = self.w, self.gpu, self.gpu.st
+        G = w.group
+        n_keep = g.n_keep.cpu().numpy(); n_evict = g.n_evict.cpu().numpy()
+        keep_idx = g.keep_idx.cpu().numpy(); evict_idx = g.evict_idx.cpu().numpy()
+        sc = g.scores.cpu().numpy()
+        lens = st.len.cpu().numpy(); nproj = st.n_projected.cpu().numpy(); pos = st.pos.cpu().numpy()
+        out_g = f64(g.out).reshape(w.batch, w.n_kv_heads, G, w.head_dim)
+        res_g = g.readout.cpu().numpy().astype(np.float64).reshape(w.batch, w.n_kv_heads, G, w.head_dim)
+        Mg = st.M.cpu().numpy().astype(np.float64); bg = st.b.cpu().numpy().astype(np.float64)
+        for ib, b in enumerate(self.batch_ids):
+            u = f"{tag} sequence {b}"
+            kr, er = keep[ib], evict[ib]
+            n_before = len(kr) + len(er)
+            s_ref = scores[ib, :n_before]; s_gpu = sc[b, :n_before].astype(np.float64)
+            same = (s_ref == s_gpu) | (np.isneginf(s_ref) & np.isneginf(s_gpu))
+            assert same.all(), (f"{u}: {int((~same).sum())} of {n_before} scores differ, max "
+                                f"{np.nanmax(np.abs(np.where(same, 0, s_ref - s_gpu))):.3e}")
+            assert n_keep[b] == len(kr) and n_evict[b] == len(er), u
+            assert np.array_equal(keep_idx[b, :len(kr)], kr), f"{u}: keep list differs"
+            assert np.array_equal(evict_idx[b, :len(er)], er), f"{u}: evict list differs"
+            n = int(self.ref.len[ib])
+            assert lens[b] == n and nproj[b] == n, u
+            assert np.array_equal(pos[b, :n], self.ref.pos[ib, :n]), f"{u}: positions"
+            assert np.array_equal(f64(st.Kidx[b, :n]), self.ref.Kidx[ib, :n]), f"{u}: indexer keys"
+            assert np.array_equal(f64(st.K[b, :, :n]), self.ref.K[ib, :, :n]), f"{u}: K rows"
+            assert np.array_equal(f64(st.V[b, :, :n]), self.ref.V[ib, :, :n]), f"{u}: V rows"
+            assert_state_close(u + " M", Mg[b], self.ref.M[ib])
+            assert_state_close(u + " b", bg[b], self.ref.b[ib])
+            assert_out_close(u + " out", out_g[b], out[ib])
+            dmax = float(np.max(np.abs(res_g[b] - res[ib])))
+            assert dmax <= 1e-3 * float(np.max(np.abs(res[ib]))) + 1e-30, f"{u}: readout diff {dmax:.3e}"
+
+    def run_schedule(self, decode_steps=None):
+        w = self.w
+        steps = w.decode_steps if decode_steps is None else decode_steps
+        L = w.context
+        if w.prefill_chunk is None:
+            self.event(0, L, w.budget, "prefill")
+        else:
+            for c0 in range(0, L, w.prefill_chunk):
+                self.event(c0, min(L, c0 + w.prefill_chunk), w.budget, f"chunk@{c0}")
+        im.im_set_max_live(self.handle, min(w.capacity, w.budget + 1))
+        for t in range(L, L + steps):
+            self.event(t, t + 1, w.budget, f"decode@{t}")
         assert im.im_query_status(self.handle) == 0

@@ -85,6 +85,8 @@ def test_calls_validate_before_enqueuing(lib):
     assert lib.im_append_kv(h, C.byref(st), X, X, X, 513, None) == E
     assert lib.im_append_kv(h, C.byref(st), None, X, X, 1, None) == E
     assert lib.im_append_kv(h, C.byref(st_bad), X, X, X, 1, None) == E
+    assert lib.im_append_kv_hidden(h, C.byref(pr), C.byref(st), X, X, None, X, 1, None) == E
+    assert lib.im_append_kv_hidden(h, C.byref(pr), C.byref(st), X, X, X, X, 1, None) == im.IM_ERR_UNSUPPORTED   # per-head layout
     assert lib.im_index_score(h, C.byref(pr), C.byref(st), X, X, X, 0, X, None) == E
     assert lib.im_index_score(h, C.byref(pr), C.byref(st), X, X, X, 17, X, None) == E
     assert lib.im_index_score(h, C.byref(pr_bad), C.byref(st), X, X, X, 1, X, None) == E
@@ -113,6 +115,27 @@ def test_calls_validate_before_enqueuing(lib):
     assert b"status_host" in lib.im_last_error(h)
     lib.im_destroy(h)
     assert lib.im_set_max_live(None, 1) == E
+
+
+def test_head_shared_layout_validation(lib):
+    ok = good_cfg(head_shared=1, idx_dim=16)
+    assert lib.im_workspace_bytes(C.byref(ok.c_struct())) > lib.im_workspace_bytes(C.byref(good_cfg().c_struct()))
+    h = C.c_void_p()
+    assert lib.im_create(C.byref(good_cfg(head_shared=2, idx_dim=16).c_struct()), 1 << 20, 1 << 40, C.byref(h)) == im.IM_ERR_INVALID_ARG
+    assert lib.im_create(C.byref(good_cfg(head_shared=1).c_struct()), 1 << 20, 1 << 40, C.byref(h)) == im.IM_ERR_UNSUPPORTED   # idx_dim 64
+    assert lib.im_create(C.byref(good_cfg(idx_dim=16).c_struct()), 1 << 20, 1 << 40, C.byref(h)) == im.IM_ERR_UNSUPPORTED
+    h = _fake_handle(lib, ok)
+    X = 1 << 21
+    st = B.ImState(X, X, X, X, X, X, X, X)
+    pr = B.ImParams(X, X, X, None, None, X, X, 0.0)
+    U = im.IM_ERR_UNSUPPORTED
+    assert lib.im_append_kv(h, C.byref(st), X, X, X, 1, None) == U
+    assert lib.im_decode_step(h, C.byref(pr), C.byref(st), X, X, X, X, X, X, 64, 0.9, 0.5, X, None, None, None, None) == U
+    assert lib.im_attend_step(h, C.byref(pr), C.byref(st), X, X, X, X, X, None, None) == U
+    assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, X, X, X, 0.9, 0.5, X, None, None) == U
+    assert lib.im_append_kv_hidden(h, C.byref(pr), C.byref(st), X, X, X, X, 0, None) == im.IM_ERR_INVALID_ARG
+    assert b"head_shared" in lib.im_last_error(h) or b"n_new" in lib.im_last_error(h)
+    lib.im_destroy(h)
 
 
 def test_binding_fails_loudly_on_invalid_config():

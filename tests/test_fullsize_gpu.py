@@ -8,7 +8,7 @@ configuration 5 (one sequence of 131072 tokens in 32 chunks of 4096, running cac
 4096 after every chunk) run one layer at their stated sizes."""
 import pytest
 
-from parity import LockStep
+from parity import LockStep, LockStepShared
 from workloads import WORKLOADS
 
 pytestmark = pytest.mark.gpu
@@ -37,3 +37,10 @@ def test_cfg5_full_size_chunked_prefill_sampled_unit():
     w = WORKLOADS["cfg5"].scaled(n_layers=1, decode_steps=4)
     ls = LockStep(w, gen_device="cuda", kv_heads=[3])
     ls.run_schedule(fused_decode=True)
+
+
+def test_cfg3_head_shared_full_size_sampled_sequence():
+    # configuration 3's cache shape in the head-shared layout: one 16384-query scoring pass over 16384
+    # keys of 16 dims per sequence, one eviction set per sequence, rows of 8 KV heads summed into one memory
+    w = WORKLOADS["cfg3"].shared(n_layers=1, decode_steps=3)
+    LockStepShared(w, gen_device="cuda", batch_ids=[2]).run_schedule()

@@ -13,7 +13,7 @@ import pytest
 import torch
 
 from oracle import indexmem_oracle as O
-from workloads import WORKLOADS, layer_params, token_stream
+from workloads import WORKLOADS, hidden_stream, layer_params, token_stream
 from helpers import f64, make_oracle_layer, oracle_params
 
 RNG = np.random.default_rng(1234)
@@ -425,3 +425,111 @@ def test_planted_high_norm_keys_change_attention_but_not_selection():
     same = np.mean([len(set(ka[0][h]) & set(kb[0][h])) / w.budget for h in range(w.n_kv_heads)])
     assert same > 0.95                                                   # up to bf16 ties in the indexer keys
     assert np.max(np.abs(oa - ob)) > 1e-2
+
+
+# --------------------------------------------------------------------------------------------
+# the head-shared layout (OracleLayerShared)
+# --------------------------------------------------------------------------------------------
+def _shared_inputs(context=60, budget=18, steps=3, batch=2, **kw):
+    w = WORKLOADS["cfg1"].shared(context=context, budget=budget, decode_steps=steps, batch=batch, **kw)
+    K, V, Q = (f64(t) for t in token_stream(w, 0))
+    X = f64(hidden_stream(w, 0))
+    return w, K, V, Q, X
+
+
+def _shared_event(layer, w, K, V, Q, X, t0, t1, budget, lam=None, eta=None):
+    pos = np.tile(np.arange(t0, t1, dtype=np.int32), (w.batch, 1))
+    return layer.step(K[:, :, t0:t1], V[:, :, t0:t1], X[:, t0:t1], pos, Q[:, t0:t1], X[:, t0:t1], pos,
+                      Q[:, t1 - 1], budget, w.lam if lam is None else lam, w.eta if eta is None else eta)
+
+
+def test_shared_layout_with_one_kv_head_fed_its_key_rows_is_the_per_head_layout():
+    # one KV head, d_model = d_head, hidden state := the key row, same d_index: nothing is left to
+    # share, so every observable must equal the (separately pinned) per-head layer's
+    w = WORKLOADS["cfg1"].scaled(n_q_heads=4, n_kv_heads=1, batch=2, context=50, budget=14, decode_steps=3)
+    K, V, Q = (f64(t) for t in token_stream(w, 0))
+    p = oracle_params(layer_params(w, 0))
+    rng = np.random.default_rng(5)
+    p.G = O.round_bf16(rng.normal(size=(w.n_idx_heads, w.head_dim)) * 0.02).reshape(w.n_idx_heads, w.head_dim)
+    from helpers import oracle_config
+    a, b = O.OracleLayer(oracle_config(w), p), O.OracleLayerShared(oracle_config(w), p)
+    for t0, t1 in [(0, w.context)] + [(t, t + 1) for t in range(w.context, w.n_tokens)]:
+        pos = np.tile(np.arange(t0, t1, dtype=np.int32), (w.batch, 1))
+        x = K[:, 0, t0:t1]
+        ra = a.step(K[:, :, t0:t1], V[:, :, t0:t1], pos, Q[:, t0:t1], x, pos, Q[:, t1 - 1], w.budget, w.lam, w.eta)
+        rb = b.step(K[:, :, t0:t1], V[:, :, t0:t1], x, pos, Q[:, t0:t1], x, pos, Q[:, t1 - 1], w.budget, w.lam, w.eta)
+        assert np.array_equal(ra[0][:, 0], rb[0], equal_nan=True)
+        for bi in range(w.batch):
+            assert np.array_equal(ra[1][bi][0], rb[1][bi]) and np.array_equal(ra[2][bi][0], rb[2][bi])
+        assert np.array_equal(ra[3], rb[3]) and np.array_equal(ra[4], rb[4])
+        assert np.array_equal(a.M[:, 0], b.M) and np.array_equal(a.b[:, 0], b.b)
+        assert np.array_equal(a.K, b.K) and np.array_equal(a.Kidx[:, 0], b.Kidx) and np.array_equal(a.pos[:, 0], b.pos)
+
+
+def test_shared_memory_write_is_the_double_sum_over_heads():
+    # M = eta sum_i Linear_theta(sum_h k_{h,i}) (sum_h' v_{h',i})^T, expanded by bilinearity into
+    # explicit loops over tokens and head pairs (Algorithm 1 `mem_write`, rows summed across heads)
+    w, K, V, Q, X = _shared_inputs(context=40, budget=30, steps=0, batch=1)
+    layer = make_oracle_layer(w)
+    _, keep, evict, _, _ = _shared_event(layer, w, K, V, Q, X, 0, w.context, w.budget)
+    e = evict[0]
+    assert len(e) == 10
+    W = f64(layer_params(w, 0)["Wtheta"])
+    M = np.zeros((w.mem_dim, w.head_dim)); bvec = np.zeros(w.mem_dim)
+    ref = make_oracle_layer(w)
+    pos = np.arange(w.context, dtype=np.int32)[None]
+    ref.append_kv_hidden(K[:, :, :w.context], V[:, :, :w.context], X[:, :w.context], pos)
+    for i in e:
+        phi = np.zeros(w.mem_dim)
+        for h in range(w.n_kv_heads):
+            phi += W @ ref.K[0, h, i]
+        for h in range(w.n_kv_heads):
+            M += w.eta * np.outer(phi, ref.V[0, h, i])
+        bvec += w.eta * phi * phi
+    assert np.allclose(layer.M[0], M, rtol=1e-12, atol=1e-12) and np.allclose(layer.b[0], bvec, rtol=1e-12, atol=1e-12)
+
+
+def test_shared_layout_keeps_the_same_tokens_in_the_same_slots_of_every_head():
+    w, K, V, Q, X = _shared_inputs()
+    # tag every row with (head, token) so that a row's origin can be read back after the moves
+    for h in range(w.n_kv_heads):
+        K[:, h, :, 0] = np.arange(K.shape[2]) + 1000 * h
+        V[:, h, :, 1] = np.arange(V.shape[2]) + 1000 * h
+    layer = make_oracle_layer(w)
+    _shared_event(layer, w, K, V, Q, X, 0, w.context, w.budget)
+    for t in range(w.context, w.n_tokens):
+        _, keep, evict, _, _ = _shared_event(layer, w, K, V, Q, X, t, t + 1, w.budget)
+        assert all(len(e) == 1 for e in evict)
+    for bi in range(w.batch):
+        n = int(layer.len[bi])
+        assert n == w.budget and set(range(4)) <= set(layer.pos[bi, :n].tolist())
+        for h in range(w.n_kv_heads):
+            assert np.array_equal(layer.K[bi, h, :n, 0], layer.pos[bi, :n] + 1000 * h)
+            assert np.array_equal(layer.V[bi, h, :n, 1], layer.pos[bi, :n] + 1000 * h)
+        # the indexer key travels with its token: it is the key of the hidden state at that position
+        want = O.key_feature(X[bi, layer.pos[bi, :n]], f64(layer_params(w, 0)["Uk"]),
+                             f64(layer_params(w, 0)["norm_k_w"]), float(np.float32(1e-6)))
+        assert np.array_equal(layer.Kidx[bi, :n], want)
+
+
+def test_shared_scores_against_explicit_loops():
+    w, K, V, Q, X = _shared_inputs(context=24, budget=24, steps=0, batch=1)
+    layer = make_oracle_layer(w)
+    scores, *_ = _shared_event(layer, w, K, V, Q, X, 0, w.context, w.budget)
+    p = layer_params(w, 0)
+    Uq, G, Uk = f64(p["Uq"]), f64(p["G"]), f64(p["Uk"])
+    Hi, di, eps = w.n_idx_heads, w.idx_dim, float(np.float32(1e-6))
+    assert di == 16 and Uk.shape == (16, w.gate_in_dim)
+    for t in range(w.context):
+        kt = Uk @ X[0, t]
+        kt = O.round_bf16(kt / math.sqrt(sum(v * v for v in kt) / di + eps))
+        best = -math.inf
+        for s in range(t, w.context):                       # causal: queries at or after the key
+            y = (Uq @ Q[0, s].reshape(-1)).reshape(Hi, di)
+            a = 0.0
+            for j in range(Hi):
+                qj = O.round_f32(y[j] / math.sqrt(sum(v * v for v in y[j]) / di + eps))
+                al = float(O.round_f32(G[j] @ X[0, s] / math.sqrt(Hi * di)))
+                a += al * max(0.0, float(qj @ kt))
+            best = max(best, a)
+        assert abs(float(O.round_f32(best)) - scores[0, t]) <= 1e-12 * max(1.0, abs(best))

@@ -6,7 +6,7 @@ import torch
 
 import paper_2605_25475_amd as im
 from oracle import indexmem_oracle as O
-from parity import LockStep
+from parity import LockStep, LockStepShared
 from workloads import WORKLOADS
 
 pytestmark = pytest.mark.gpu
@@ -227,3 +227,30 @@ def test_decode_step_in_a_hip_graph_matches_eager_replay_by_replay():
         # eager work between the replays, as in a real program
         _ = (g_ls.gpu.st.M.sum() + e_ls.gpu.st.M.sum()).item()
     assert im.im_query_status(g_ls.handle) == 0 and im.im_query_status(e_ls.handle) == 0
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("cfg1", dict()),                                                        # 1024 -> 256, 16 decode steps
+    ("cfg2", dict(batch=2, context=1100, budget=300, decode_steps=3)),
+    ("cfg3", dict(batch=2, context=1500, budget=333, decode_steps=3)),
+    ("cfg4", dict(batch=3, context=1300, budget=130, decode_steps=3)),       # 4 KV heads of 7 query heads, 7 indexer heads
+    ("cfg5", dict(batch=1, context=1536, budget=512, decode_steps=3, prefill_chunk=512)),
+    ("cfg1", dict(context=40, budget=64, decode_steps=30)),                  # grows to the budget, then evicts
+    ("cfg1", dict(batch=3, context=300, budget=64, decode_steps=3, n_recent=8)),
+])
+def test_head_shared_layout(name, kw):
+    # the layer-wide form of the paper's text (Section 3.1: one indexer key per token from the hidden
+    # state; Algorithm 1 mem_write: rows summed across heads into one memory per layer; d_index 16)
+    LockStepShared(WORKLOADS[name].shared(n_layers=1, **kw)).run_schedule()
+
+
+def test_head_shared_layout_rejects_the_fused_entry_points():
+    w = WORKLOADS["cfg1"].shared()
+    ls = LockStepShared(w)
+    g = ls.gpu
+    d = lambda t: t.cuda()
+    k = d(ls.K[:, :, :1].contiguous()); q = d(ls.Q[:, 0].contiguous()); pos = torch.zeros(w.batch, dtype=torch.int32).cuda()
+    with pytest.raises(im.IndexMemError):
+        im.im_attend_step(ls.handle, ls.params, g.st, q, k, k, pos, g.out)
+    with pytest.raises(im.IndexMemError):
+        im.im_append_kv(ls.handle, g.st, k, k, pos.view(-1, 1))

@@ -20,7 +20,7 @@ import torch
 BASE_SEED = 25475
 
 # tensor-kind ids used to derive independent seeds
-_KIND = {"params": 1, "k": 2, "v": 3, "q": 4, "aux": 5}
+_KIND = {"params": 1, "k": 2, "v": 3, "q": 4, "aux": 5, "x": 6}
 
 
 @dataclass(frozen=True)
@@ -49,6 +49,9 @@ class Workload:
     lam: float = 0.999         # decay of the memory state per eviction event
     eta: float = 0.5           # write strength
     param_std: float = 0.02
+    # the layer-wide form of the paper's text: indexer keys from hidden states (idx_dim 16), one
+    # eviction set and one memory per sequence, shared by all KV heads
+    head_shared: bool = False
 
     @property
     def n_idx_heads(self) -> int:      # H_index = H / 4 (Section 4, hyper-parameters)
@@ -76,6 +79,10 @@ class Workload:
     def scaled(self, **kw) -> "Workload":
         """A reduced copy (same distribution and head shape) for parity tests."""
         return replace(self, **kw)
+
+    def shared(self, **kw) -> "Workload":
+        """The same cache shape in the head-shared layout (d_index = d_head / 8)."""
+        return replace(self, head_shared=True, idx_dim=self.head_dim // 8, name=self.name + "-shared", **kw)
 
 
 WORKLOADS: Dict[str, Workload] = {
@@ -110,7 +117,7 @@ def layer_params(w: Workload, layer: int, device="cpu") -> Dict[str, object]:
     return {
         "Uq": mat(Hi * di, H * D),
         "G": mat(Hi, w.gate_in_dim),
-        "Uk": mat(di, D),
+        "Uk": mat(di, w.gate_in_dim if w.head_shared else D),
         "norm_q_w": torch.ones(di, device=device, dtype=torch.bfloat16),
         "norm_k_w": torch.ones(di, device=device, dtype=torch.bfloat16),
         "Wtheta": mat(dm, D),
@@ -164,3 +171,10 @@ def token_stream(w: Workload, layer: int, device="cpu",
     V = _randn((Bz, Hkv, T, D), gv, device).to(torch.bfloat16)
     Q = _randn((Bz, T, H, D), gq, device).to(torch.bfloat16)
     return K, V, Q
+
+
+def hidden_stream(w: Workload, layer: int, device="cpu", n_tokens: Optional[int] = None) -> torch.Tensor:
+    """Hidden states X [batch, T, d_model] ~ N(0, 1) in bf16 (d_model = H * head_dim): the input of the
+    head-shared layout's key projection and head gate.  Token t has position t."""
+    T = w.n_tokens if n_tokens is None else n_tokens
+    return _randn((w.batch, T, w.gate_in_dim), _gen(device, w, layer, "x"), device).to(torch.bfloat16)
