@@ -27,7 +27,7 @@ import numpy as np
 import torch
 
 import paper_2605_25475_amd as im
-from workloads import WORKLOADS, Workload, layer_params, token_stream
+from workloads import WORKLOADS, Workload, hidden_stream, layer_params, token_stream
 
 HBM_PEAK_GBS = 8000.0
 
@@ -37,6 +37,24 @@ def algorithmic_bytes(w: Workload) -> dict:
     entries per unit, one eviction): what the roofline fraction is priced against."""
     Bg, D = w.budget, w.head_dim
     units = w.batch * w.n_kv_heads
+    if w.head_shared:
+        # one indexer key (16 values), one decision and one memory per sequence; K / V per unit
+        per_unit = {"kv": 2 * 2 * D * Bg, "evicted_row": 2 * 2 * D, "compaction_row": 2 * 2 * 2 * D}
+        per_seq = {
+            "indexer_keys": 2 * w.idx_dim * (Bg + 1),
+            "new_key": 2 * w.gate_in_dim + 2 * w.idx_dim,      # the hidden state in, its indexer key out
+            "memory_state": 2 * 4 * w.mem_dim * D + 2 * 4 * w.mem_dim,
+            "compaction_row": 2 * (2 * w.idx_dim + 4),
+        }
+        per_layer = {
+            "indexer_weights": 2 * (w.n_idx_heads * w.idx_dim * w.n_q_heads * D + w.n_idx_heads * w.gate_in_dim
+                                    + w.idx_dim * w.gate_in_dim),
+            "q_and_out": w.batch * w.n_q_heads * D * 2 * 2,
+        }
+        unit_total = sum(per_unit.values())
+        layer_total = units * unit_total + w.batch * sum(per_seq.values()) + sum(per_layer.values())
+        return {"per_unit": unit_total, "per_layer_step": layer_total, "main_kernel_per_launch": units * per_unit["kv"],
+                "attention_kv_per_layer": units * per_unit["kv"], "detail": {**per_unit, **per_seq, **per_layer}}
     per_unit = {
         "indexer_keys": 2 * w.idx_dim * (Bg + 1),          # stream the indexer-key cache
         "kv": 2 * 2 * D * Bg,                              # stream retained K and V
@@ -66,10 +84,10 @@ class Job:
         cap = w.capacity
         n_q_max = w.context if w.prefill_chunk is None else w.prefill_chunk
         cfg = im.Config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, capacity=cap,
-                        n_idx_heads=w.n_idx_heads, n_sink=w.n_sink, n_recent=w.n_recent,
-                        fold_block=w.fold_block, max_queries=n_q_max)
+                        n_idx_heads=w.n_idx_heads, idx_dim=w.idx_dim, n_sink=w.n_sink, n_recent=w.n_recent,
+                        fold_block=w.fold_block, max_queries=n_q_max, head_shared=int(w.head_shared))
         self.handle = im.Handle(cfg, device)
-        self.layers, self.dec, self.qwin, self.tau, self.share = [], [], [], tau, share
+        self.layers, self.dec, self.qwin, self.tau, self.share, self.xdec = [], [], [], tau, share, []
         L = w.context
         assert n_steps <= w.decode_steps, "the workload defines fewer decode steps"
         for li in range(w.n_layers):
@@ -78,13 +96,18 @@ class Job:
                                p["norm_q_w"], p["norm_k_w"])
             layer = im.Layer(self.handle, params, device)
             K, V, Q = token_stream(w, li, device, n_tokens=L + n_steps)
+            X = hidden_stream(w, li, device, n_tokens=L + n_steps) if w.head_shared else None
             im.im_set_max_live(self.handle, cap)
             chunk = L if w.prefill_chunk is None else w.prefill_chunk
             for c0 in range(0, L, chunk):
                 c1 = min(L, c0 + chunk)
                 pos = torch.arange(c0, c1, dtype=torch.int32, device=device).repeat(w.batch, 1).contiguous()
                 q = Q[:, c0:c1].contiguous()
-                if li % share:   # a follower of an index-sharing group applies its leader's lists
+                if w.head_shared:
+                    x = X[:, c0:c1].contiguous()
+                    layer.step(K[:, :, c0:c1].contiguous(), V[:, :, c0:c1].contiguous(), pos, q, x, pos,
+                               Q[:, c1 - 1].contiguous(), w.budget, w.lam, w.eta, x_new=x)
+                elif li % share:   # a follower of an index-sharing group applies its leader's lists
                     layer.follow_event(K[:, :, c0:c1].contiguous(), V[:, :, c0:c1].contiguous(), pos,
                                        Q[:, c1 - 1].contiguous(), self.layers[li - li % share], w.lam, w.eta)
                 else:
@@ -97,6 +120,9 @@ class Job:
             qd = Q[:, L:].permute(1, 0, 2, 3).contiguous().unsqueeze(2)         # [S, B, 1, H, D]
             self.layers.append(layer)
             self.dec.append((kd, vd, qd))
+            if w.head_shared:
+                self.xdec.append(X[:, L:].permute(1, 0, 2).contiguous().unsqueeze(2))   # [S, B, 1, d_model]
+            del X
             if tau:   # the query set of every compression interval, [B, tau, H, D] each
                 self.qwin.append([Q[:, L + k * tau:L + (k + 1) * tau].contiguous() for k in range(n_steps // tau)])
             del K, V, Q
@@ -117,7 +143,15 @@ class Job:
         for li, layer in enumerate(self.layers):
             kd, vd, qd = self.dec[li]
             q = qd[s]
-            if path == "shared":
+            if w.head_shared:
+                x = self.xdec[li][s]
+                if path == "fused":
+                    layer.decode_step(kd[s], vd[s], pos.view(w.batch), q.view(w.batch, w.n_q_heads, -1),
+                                      x.view(w.batch, -1), pos.view(w.batch), w.budget, w.lam, w.eta)
+                else:
+                    layer.step(kd[s], vd[s], pos, q, x, pos, q.view(w.batch, w.n_q_heads, -1), w.budget, w.lam,
+                               w.eta, x_new=x)
+            elif path == "shared":
                 if li % self.share:
                     layer.follow_step(kd[s], vd[s], pos.view(w.batch), q.view(w.batch, w.n_q_heads, -1),
                                       self.layers[li - li % self.share].evicted, w.lam, w.eta)
@@ -157,15 +191,23 @@ def cpu_baseline(w: Workload, budget_s: float = 20.0) -> dict:
     spent, done_pairs, done = 0.0, 0, 0
     for layer in range(min(2, w.n_layers)):       # up to two layers' worth of pairs, within the budget
         K, V, Q = token_stream(w, layer, "cpu", n_tokens=w.context + n_steps)
-        ref = make_oracle_layer(ws, layer, "cpu", capacity=w.context + 1, batch=nb, kv_head_ids=heads)
+        if w.head_shared:
+            ref = make_oracle_layer(ws, layer, "cpu", capacity=w.context + 1, batch=nb)
+            X = f64(hidden_stream(w, layer, "cpu", n_tokens=w.context + n_steps)[:nb])
+        else:
+            ref = make_oracle_layer(ws, layer, "cpu", capacity=w.context + 1, batch=nb, kv_head_ids=heads)
         K, V, Q = f64(K[:nb]), f64(V[:nb]), f64(Q[:nb])
         # build the post-prefill state cheaply, for TIMING purposes only: score with the last 64
         # prompt queries (the parity tests, not this leg, check the full-context event)
         nq = 64
         pos = np.tile(np.arange(L, dtype=np.int32), (nb, 1))
-        ref.append_kv(K[:, :, :L], V[:, :, :L], pos)
         q = Q[:, L - nq:L]
-        sc = ref.index_score(q, q.reshape(nb, nq, -1), pos[:, L - nq:])
+        if w.head_shared:
+            ref.append_kv_hidden(K[:, :, :L], V[:, :, :L], X[:, :L], pos)
+            sc = ref.index_score(q, X[:, L - nq:L], pos[:, L - nq:])
+        else:
+            ref.append_kv(K[:, :, :L], V[:, :, :L], pos)
+            sc = ref.index_score(q, q.reshape(nb, nq, -1), pos[:, L - nq:])
         keep, evict = ref.topb_select(sc, w.budget)
         ref.memory_update(evict, w.lam, w.eta)
         ref.compact_kv(keep, evict)
@@ -174,8 +216,12 @@ def cpu_baseline(w: Workload, budget_s: float = 20.0) -> dict:
             t = L + s
             p = np.full((nb, 1), t, np.int32)
             qs = Q[:, t:t + 1]
-            ref.step(K[:, :, t:t + 1], V[:, :, t:t + 1], p, qs, qs.reshape(nb, 1, -1), p, Q[:, t], w.budget,
-                     w.lam, w.eta)
+            if w.head_shared:
+                ref.step(K[:, :, t:t + 1], V[:, :, t:t + 1], X[:, t:t + 1], p, qs, X[:, t:t + 1], p, Q[:, t],
+                         w.budget, w.lam, w.eta)
+            else:
+                ref.step(K[:, :, t:t + 1], V[:, :, t:t + 1], p, qs, qs.reshape(nb, 1, -1), p, Q[:, t], w.budget,
+                         w.lam, w.eta)
             done_pairs += nb
             done += 1
             if spent + time.perf_counter() - t0 > budget_s:
@@ -204,6 +250,9 @@ def main() -> None:
                          "compression event per --tau steps with the interval's queries as the query set); "
                          "shared: index reuse over groups of --share consecutive layers (the first layer "
                          "of a group scores and selects, the others apply its decision)")
+    ap.add_argument("--head-shared", action="store_true",
+                    help="the workload's cache shape in the head-shared layout (indexer keys of 16 values from "
+                         "hidden states, one eviction set and one memory per sequence); paths fused and steps")
     ap.add_argument("--share", type=int, default=4, help="layers per index-sharing group of --path shared")
     ap.add_argument("--tau", type=int, default=128, help="compression interval of --path periodic")
     ap.add_argument("--no-graph", action="store_true", help="launch the fused path eagerly")
@@ -219,6 +268,10 @@ def main() -> None:
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     w = WORKLOADS[a.workload]
+    if a.head_shared:
+        if a.path not in ("fused", "steps"):
+            sys.exit("bench.py: --head-shared runs with --path fused or --path steps")
+        w = w.shared()
     log = (lambda s: None) if a.quiet else (lambda s: print("[bench] " + s, file=sys.stderr, flush=True))
     torch.cuda.set_device(0)
     tau = a.tau if a.path == "periodic" else 0
@@ -293,18 +346,19 @@ def main() -> None:
         d_p = im.im_profile_stop(job.handle)
         k_ms = float(np.mean(d_pm)) - float(np.mean(d_p))
         durs = d_pm
+        kname = "k_att_main" if w.head_shared else "k_dec_main"   # the launch that streams the cache
         achieved = ab["main_kernel_per_launch"] / (k_ms * 1e-3) / 1e9
         traffic = None
         tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{w.name}.json")
         if os.path.exists(tpath):   # HBM bytes per launch from the committed rocprofv3 --pmc summary
             with open(tpath) as f:
-                traffic = json.load(f)["kernels"].get(f"k_dec_main<{w.group}>", {}).get("total_bytes")
+                traffic = json.load(f)["kernels"].get(f"{kname}<{w.group}>", {}).get("total_bytes")
         roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "k_dec_main",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": kname,
                 "avg_launch_us": k_ms * 1e3, "launches_timed": len(durs),
                 "prep_and_main_us": float(np.mean(d_pm)) * 1e3, "prep_us": float(np.mean(d_p)) * 1e3,
                 "bytes_per_launch": ab["main_kernel_per_launch"]}
-        log(f"k_dec_main: {k_ms * 1e3:.2f} us per launch over {len(durs)} launches -> {achieved:.0f} GB/s")
+        log(f"{kname}: {k_ms * 1e3:.2f} us per launch over {len(durs)} launches -> {achieved:.0f} GB/s")
     assert im.im_query_status(job.handle) == 0
 
     step_s = wall / a.steps
@@ -316,7 +370,9 @@ def main() -> None:
         "config": {"workload": f"{w.name}: {w.n_q_heads}/{w.n_kv_heads}x{w.head_dim} heads, {w.n_layers} layers, "
                                f"batch {w.batch}, context {w.context} -> budget {w.budget}, "
                                + (f"one compression event per {tau} decode steps" if tau else "one eviction per decode step")
-                               + (f", index decisions shared by groups of {a.share} layers" if a.path == "shared" else ""),
+                               + (f", index decisions shared by groups of {a.share} layers" if a.path == "shared" else "")
+                               + (", head-shared layout (indexer keys of 16 values from hidden states, one "
+                                  "eviction set and one memory per sequence)" if w.head_shared else ""),
                    "layers": w.n_layers, "batch": w.batch, "budget": w.budget, "context": w.context,
                    "path": a.path, "hip_graph": use_graph,
                    "algorithmic_bytes_per_step": ab["per_layer_step"] * w.n_layers,

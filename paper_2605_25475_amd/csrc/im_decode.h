@@ -71,8 +71,12 @@ struct DecArgs {
   float* part;
   uint32_t* cand;
   float* qm;          // per unit: the eviction-independent terms of the memory readout (DEC_QM floats per head)
+  double* xk;         // head-shared layout: U_k x of the new token, [B][16]
   // scalars
   int B, H, H_kv, C, H_idx, gate_in, n_sink, n_recent, budget, S, S_alloc, max_live;
+  // head-shared layout (hs = 1): the H_set = H_kv units of a sequence form one set; len, pos, Kidx
+  // (di = 16 values per row), nproj, M, bvec are indexed by the set u / H_set.  Else H_set = 1, di = 64.
+  int hs, H_set, di;
   float rms_eps, mem_eps, scale, lambda, eta;
 };
 
@@ -166,14 +170,14 @@ __device__ __forceinline__ void dec_prep_memory(const DecArgs& a, const int u, c
   float* qm = a.qm + (size_t)u * G * DEC_QM;
   // every load first
   const int d4 = tid & 31, rg = tid >> 5;    // patch of M: rows 32 mp + 4 rg .. + 3, columns 4 d4 .. 4 d4 + 3
-  const float* Mu = a.M + ((size_t)u * IM_DM + 32 * mp) * IM_D;
+  const float* Mu = a.M + ((size_t)(u / a.H_set) * IM_DM + 32 * mp) * IM_D;
   float4 Mr[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);
   const int cl = tid >> 3, pt = tid & 7;     // W_theta row 32 mp + cl, dims 16 pt .. 16 pt + 15
   const uint4 Wr0 = *(const uint4*)(a.Wt + (32 * mp + cl) * IM_D + 16 * pt);
   const uint4 Wr1 = *(const uint4*)(a.Wt + (32 * mp + cl) * IM_D + 16 * pt + 8);
-  const float bc = a.bvec[(size_t)u * IM_DM + 32 * mp + (lane & 31)];
+  const float bc = a.bvec[(size_t)(u / a.H_set) * IM_DM + 32 * mp + (lane & 31)];
   const float g0 = bf2f(a.wg[lane]), g1 = bf2f(a.wg[lane + 64]);
   const bf16_t* qb = a.q + ((size_t)b * a.H + h * G) * IM_D;
   float wv[16];
@@ -328,6 +332,162 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
 }
 
 // --------------------------------------------------------------------------------------------
+// Head-shared layout: k_hs_prep and k_hs_score take the place of k_dec_prep and of the scoring
+// waves.  One indexer key per token (from its hidden state) and one score per token mean one
+// decision per sequence, so the sequence's workgroup ranks all its keys (16 values each) before the
+// attention launch, which then treats the decision as given (the path of a named slot).
+// --------------------------------------------------------------------------------------------
+// Block roles: [0, U) append the new (k, v) of a unit (the set's position by its first head);
+// [U, (1 + DEC_MP) U) the readout terms; then two rows each of U_q (input q), G and U_k (input x).
+__global__ __launch_bounds__(256) void k_hs_prep(const DecArgs a) {
+  __shared__ double part[4][16];
+  __shared__ double rows[64 * 2];
+  const int tid = threadIdx.x;
+  const int Nq = a.H_idx * IM_DI_SHARED;
+  const int nU = Nq / 2, nG = (a.H_idx + 1) / 2;
+  const int U = a.B * a.H_kv;
+  const int blk = blockIdx.x;
+  if (blk < U) {
+    const int u = blk, b = u / a.H_kv;
+    const int n_old = a.len[b];
+    uint4 newrow = make_uint4(0, 0, 0, 0);
+    if (tid < 16) newrow = *(const uint4*)(a.k_new + (size_t)u * IM_D + tid * 8);
+    else if (tid < 32) newrow = *(const uint4*)(a.v_new + (size_t)u * IM_D + (tid - 16) * 8);
+    const int newpos = a.pos_new[b];
+    const bool lead = u % a.H_kv == 0;
+    if (n_old + 1 > a.C) {
+      if (tid == 0 && lead) atomicOr(a.status, IM_STATUS_APPEND_OVERFLOW_BIT);
+      return;
+    }
+    if (n_old + 1 > a.max_live && tid == 0 && lead) atomicOr(a.status, IM_STATUS_LIVE_EXCEEDED_BIT);
+    const size_t slot = (size_t)u * a.C + n_old;
+    if (tid < 16) *(uint4*)(a.K + slot * IM_D + tid * 8) = newrow;
+    else if (tid < 32) *(uint4*)(a.V + slot * IM_D + (tid - 16) * 8) = newrow;
+    else if (tid == 32 && lead) a.pos[(size_t)b * a.C + n_old] = newpos;
+    return;
+  }
+  if (blk < (1 + DEC_MP) * U) {
+    dec_prep_memory(a, (blk - U) / DEC_MP, (blk - U) % DEC_MP);
+    return;
+  }
+  const int g = blk - (1 + DEC_MP) * U;
+  const bool isq = g < nU, isg = !isq && g < nU + nG;
+  const int n0 = (isq ? g : isg ? g - nU : g - nU - nG) * 2;
+  const int N = isq ? Nq : isg ? a.H_idx : IM_DI_SHARED;
+  const bf16_t* A = isq ? a.q : a.xg;
+  const bf16_t* W = isq ? a.Uq : isg ? a.Gw : a.Uk;
+  const int Kd = isq ? a.H * IM_D : a.gate_in;
+  double* out = isq ? a.qy : isg ? a.alpha : a.xk;
+  if (a.B <= 4) dec_gemv2<4>(A, W, n0, N, a.B, Kd, part, rows);
+  else dec_gemv2<8>(A, W, n0, N, a.B, Kd, part, rows);
+  for (int i = tid; i < a.B * 2; i += 256) {   // raw projections; k_hs_score normalises and scales
+    const int r = n0 + (i & 1);
+    if (r < N) out[(size_t)(i >> 1) * N + r] = rows[i];
+  }
+}
+
+// grid (B), 1024 threads: QK-Norm of the step's query features, head gates, the new token's indexer
+// key (stored), the score of every live key of the sequence, and the entry ranked last by
+// (score, then position, then slot) with sinks and the recent window forced to the top: the one to
+// evict when the sequence is above its budget.  Writes that slot (or -1) for every unit of the
+// sequence to a.ext_evict's array and, optionally, to a.evicted [B] and the scores to a.scores [B][C].
+__global__ __launch_bounds__(1024) void k_hs_score(const DecArgs a, int32_t* __restrict__ evict_units) {
+  constexpr int DI = IM_DI_SHARED;
+  __shared__ double s_q[16][DI];
+  __shared__ double s_al[16];
+  __shared__ float s_kn[DI];
+  __shared__ uint32_t s_hi[16], s_lo[16];
+  __shared__ int s_at[16], s_mp[16];
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int n_old = a.len[b];
+  const bool fits = n_old + 1 <= a.C;
+  const int n = min(n_old + (fits ? 1 : 0), a.max_live);
+  const int newpos = a.pos_new[b], qpos = a.q_pos[b];
+  const bf16_t* kx = a.Kidx + (size_t)b * a.C * DI;
+  const int32_t* ps = a.pos + (size_t)b * a.C;
+  if (tid < 256) {   // thread (head j, dim d)
+    const int j = tid >> 4, d = tid & 15;
+    const bool hv = j < a.H_idx;
+    const double y = hv ? a.qy[((size_t)b * a.H_idx + j) * DI + d] : 0.0;
+    const double ss = row16_sum_d(y * y);
+    const double rr = sqrt(ss / (double)DI + (double)a.rms_eps);
+    const double wq = a.nqw ? (double)bf2f(a.nqw[d]) : 1.0;
+    s_q[j][d] = hv ? (double)(float)(y / rr * wq) : 0.0;
+    if (d == 0) s_al[j] = hv ? (double)(float)(a.alpha[(size_t)b * a.H_idx + j] / sqrt((double)(a.H_idx * DI))) : 0.0;
+  } else if (tid < 256 + DI) {   // one 16-lane row: the new token's key
+    const int d = tid - 256;
+    const double v = a.xk[(size_t)b * DI + d];
+    const double ss = row16_sum_d(v * v);
+    const double rr = sqrt(ss / (double)DI + (double)a.rms_eps);
+    const double wk = a.nkw ? (double)bf2f(a.nkw[d]) : 1.0;
+    const bf16_t kb = d2bf_rne(v / rr * wk);
+    s_kn[d] = bf2f(kb);
+    if (fits) a.Kidx[((size_t)b * a.C + n_old) * DI + d] = kb;
+  }
+  int mxp = 0;
+  if (a.n_recent > 0) {   // newest position of the sequence, the new token included
+    int m = fits ? newpos : INT_MIN;
+    for (int i = tid; i < min(n_old, a.max_live); i += 1024) m = max(m, ps[i]);
+    m = (int)(wave_max_u((uint32_t)m ^ 0x80000000u) ^ 0x80000000u);
+    if (lane == 0) s_mp[w] = m;
+  }
+  __syncthreads();
+  if (a.n_recent > 0) {
+    mxp = s_mp[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) mxp = max(mxp, s_mp[i]);
+  }
+  uint32_t bhi = 0xffffffffu, blo = 0xffffffffu;
+  int bat = -1;
+  for (int t = tid; t < n; t += 1024) {
+    float kf[DI];
+    int p;
+    if (t < n_old) {
+      unpack8(*(const uint4*)(kx + (size_t)t * DI), kf);
+      unpack8(*(const uint4*)(kx + (size_t)t * DI + 8), kf + 8);
+      p = ps[t];
+    } else {
+#pragma unroll
+      for (int d = 0; d < DI; ++d) kf[d] = s_kn[d];
+      p = newpos;
+    }
+    double asum = 0.0;
+    for (int j = 0; j < a.H_idx; ++j) {
+      double z = 0.0;
+#pragma unroll
+      for (int d = 0; d < DI; ++d) z = fma(s_q[j][d], (double)kf[d], z);
+      asum += s_al[j] * fmax(z, 0.0);
+    }
+    const float sc = (p <= qpos) ? (float)asum : -INFINITY;
+    if (a.scores) a.scores[(size_t)b * a.C + t] = sc;
+    const bool forced = (p < a.n_sink) || (a.n_recent > 0 && (long long)p > (long long)mxp - a.n_recent);
+    const uint32_t khi = forced ? IM_KEY_PINF : score_key(sc);
+    const uint32_t klo = (uint32_t)(~((uint32_t)p ^ 0x80000000u));
+    if (khi < bhi || (khi == bhi && klo <= blo)) { bhi = khi; blo = klo; bat = t; }   // ascending t: <= keeps the largest slot
+  }
+  {
+    const uint32_t mh = wave_min_u(bhi);
+    const uint32_t ml = wave_min_u(bhi == mh ? blo : 0xffffffffu);
+    const int win = (int)wave_max_u((bat >= 0 && bhi == mh && blo == ml) ? (uint32_t)bat + 1u : 0u) - 1;
+    if (lane == 0) { s_hi[w] = mh; s_lo[w] = ml; s_at[w] = win; }
+  }
+  __syncthreads();
+  if (tid < 64) {
+    const bool on = lane < 16 && s_at[lane & 15] >= 0;
+    const uint32_t khi = on ? s_hi[lane & 15] : 0xffffffffu, klo = on ? s_lo[lane & 15] : 0xffffffffu;
+    const uint32_t mh = wave_min_u(khi);
+    const uint32_t ml = wave_min_u((on && khi == mh) ? klo : 0xffffffffu);
+    const int win = (int)wave_max_u((on && khi == mh && klo == ml) ? (uint32_t)s_at[lane & 15] + 1u : 0u) - 1;
+    const int e = (n > a.budget && win >= 0) ? win : -1;
+    if (lane < a.H_kv) evict_units[b * a.H_kv + lane] = e;
+    if (lane == 0) {
+      if (a.evicted) a.evicted[b] = e;
+      if (n > a.budget + 1) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
+    }
+  }
+}
+
+// --------------------------------------------------------------------------------------------
 // k_dec_main
 // --------------------------------------------------------------------------------------------
 struct DecSplitSmem {
@@ -358,7 +518,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   const int wl = w & 3;                 // wave within its role
   const bool scoring = SCORE && w >= 4; // wave-uniform role
   const int b = u / a.H_kv, h = u % a.H_kv;
-  const int n_old = a.len[u];
+  const int su = u / a.H_set;           // the set that owns the length, positions and indexer keys
+  const int n_old = a.len[su];
   const int n = min(n_old + ((n_old + 1 <= a.C) ? 1 : 0), a.max_live);
   const int k0 = s * DEC_KEYS;
   const int nk = max(0, min(DEC_KEYS, n - k0));
@@ -391,8 +552,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       sm.cslot[tid] = here ? fl : -1;
     }
     // the last live slot's indexer key and position for the last-slot record
-    if (own_last && tid < 8) lkx = *(const uint4*)(a.Kidx + ((size_t)u * a.C + (n - 1)) * IM_DI + 8 * tid);
-    if (own_last && tid == 8) lpos = a.pos[(size_t)u * a.C + (n - 1)];
+    if (own_last && tid < a.di / 8) lkx = *(const uint4*)(a.Kidx + ((size_t)su * a.C + (n - 1)) * a.di + 8 * tid);
+    if (own_last && tid == 8) lpos = a.pos[(size_t)su * a.C + (n - 1)];
   }
   if (scoring) {
     // ================= scoring waves: tiles 2 wl, 2 wl + 1 (keys 32 wl .. 32 wl + 31) =================
@@ -587,13 +748,17 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     uint4 yk = make_uint4(0, 0, 0, 0), yq = yk, ykv = yk, yki0 = yk, yki1 = yk;
     int ypos = 0;
     if (!SCORE && do_x_any) {
-      const size_t last = (size_t)u * a.C + (n - 1);
-      yki0 = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq);
-      yki1 = *(const uint4*)(a.Kidx + last * IM_DI + 16 * kq + 8);
+      const size_t last = (size_t)u * a.C + (n - 1), ilast = (size_t)su * a.C + (n - 1);
+      if (a.hs) {   // 16 values per indexer key: lanes kq = 0, 1 carry 8 each
+        if (kq < 2) yki0 = *(const uint4*)(a.Kidx + ilast * IM_DI_SHARED + 8 * kq);
+      } else {
+        yki0 = *(const uint4*)(a.Kidx + ilast * IM_DI + 16 * kq);
+        yki1 = *(const uint4*)(a.Kidx + ilast * IM_DI + 16 * kq + 8);
+      }
       yk = *(const uint4*)(a.K + last * IM_D + 32 * wl + 8 * kq);
       yq = *(const uint4*)(a.q + ((size_t)b * a.H + h * G + min(l16, G - 1)) * IM_D + 32 * wl + 8 * kq);
       ykv = *(const uint4*)(((lane & 16) ? a.V : a.K) + last * IM_D + 8 * l16);
-      ypos = a.pos[last];
+      ypos = a.pos[ilast];
     }
     // keep every load above this line, in this order: loads return in order, so each phase below
     // waits only for what it uses while the rest is still streaming in
@@ -608,7 +773,9 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       lp = rows_sum_f(lp);
       if (kq == 0 && l16 < 8) sm.xlp[wl][l16] = lp;   // summed over the 4 waves after the barrier
       if (wl == 0) {
-        if (l16 == 0) {
+        if (l16 == 0 && a.hs) {
+          if (kq < 2) *(uint4*)(lrec + DEC_CAND_KI + 4 * kq) = yki0;
+        } else if (l16 == 0) {
           *(uint4*)(lrec + DEC_CAND_KI + 8 * kq) = yki0;
           *(uint4*)(lrec + DEC_CAND_KI + 8 * kq + 4) = yki1;
         }
@@ -778,7 +945,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   }
   if (tid < G) crec[4 + tid] = __float_as_uint(cl >= 0 ? sm.clog[tid] : -INFINITY);   // -inf: no candidate
   if (!SCORE && own_last) {
-    if (tid < 8) *(uint4*)(lrec + DEC_CAND_KI + 4 * tid) = lkx;
+    if (tid < a.di / 8) *(uint4*)(lrec + DEC_CAND_KI + 4 * tid) = lkx;
     if (tid == 8) { lrec[2] = (uint32_t)(n - 1); lrec[3] = (uint32_t)n; lrec[12] = (uint32_t)lpos; }
   }
   if (!scoring) {
@@ -1212,6 +1379,8 @@ struct DecTailHeadSmem {
   float phe2[8][IM_DM], phe[IM_DM];
   float den, dot;
   int e_slot, e_split;
+  float hk[8][IM_D], hv[8][IM_D];                 // head-shared layout: the evicted rows of the set's heads,
+  float kbar[IM_D], vbar[IM_D];                   // and their sums over the heads
 };
 
 template <int G, int CHW>
@@ -1221,8 +1390,10 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   const int b = u / a.H_kv, h = u % a.H_kv;
   const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
   const float* pbase = a.part + (size_t)u * a.S_alloc * G * DEC_REC;
+  const int su = u / a.H_set;                // the set that owns the lengths, indexer keys and the memory
+  const bool lead = u % a.H_set == 0;        // ... and the unit that updates them
   const int d4 = tid & 31, rg = tid >> 5;    // head 0's workgroup: patch of M, rows 4 rg .. + 3, columns 4 d4 .. + 3
-  float* Mu = a.M + (size_t)u * IM_DM * IM_D;
+  float* Mu = a.M + (size_t)su * IM_DM * IM_D;
   const int wc = tid & 127, hh = tid >> 7;   // W_theta row wc, dims 16 hh .. 16 hh + 15
   const int cs0 = min(CH, a.S);
   const int LS = min(a.S, CH);               // index (and staged slot) of the last-slot record
@@ -1247,7 +1418,21 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     const float2 rq = *(const float2*)qsrc;
     const int t3 = min(max(tid - 64 * (1 + DEC_MP), 0), DEC_MP);
     const float rs = qb[(t3 == 0) ? G * (IM_DM + DEC_MP * IM_D) + j : G * (IM_DM + DEC_MP * IM_D + 2) + (t3 - 1) * G + j];
+    // head-shared layout: the memory takes the evicted rows summed over the set's heads (Algorithm 1,
+    // `mem_write`).  The slot is named before the launch, so every head's copy of the rows (in the
+    // candidate record of the slot's split, or the last-slot record) is fetched with the staging loads.
+    float hks = 0.f, hvs = 0.f;
+    if (a.hs) {
+      const int e_raw = a.ext_evict[u];
+      const int rec = (e_raw >= 0) ? min(e_raw / DEC_KEYS, LS) : 0;
+      for (int hh = tid >> 7; hh < a.H_set; hh += 8) {
+        const uint32_t* r = a.cand + ((size_t)(su * a.H_set + hh) * a.S_alloc + rec) * DEC_CAND;
+        hks += bf2f(((const bf16_t*)(r + DEC_CAND_K))[tid & 127]);
+        hvs += bf2f(((const bf16_t*)(r + DEC_CAND_V))[tid & 127]);
+      }
+    }
     __asm__ volatile("" ::: "memory");
+    if (a.hs) { sm.hk[tid >> 7][tid & 127] = hks; sm.hv[tid >> 7][tid & 127] = hvs; }
     if (tid < DEC_CAND / 2) ((float2*)&sm.cst[LS][0])[tid] = rl;
 #pragma unroll
     for (int k = 0; k < NBC; ++k)
@@ -1261,10 +1446,11 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   }
   float4 Mr[4] = {};
   float b_old = 0.f;
-  if (j == 0) {   // uniform per workgroup
+  const bool writer = j == 0 && lead;   // uniform per workgroup: it updates the memory state
+  if (writer) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);
-    b_old = a.bvec[(size_t)u * IM_DM + wc];
+    b_old = a.bvec[(size_t)su * IM_DM + wc];
   }
   const uint4 Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
   const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
@@ -1304,6 +1490,19 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
       }
     }
   }
+  if (a.hs && tid >= 768) {   // (waves 12-15) the rows' sums over the heads
+    const int dd = tid & 127;
+    float t = 0.f;
+    if (tid < 896) {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) t += sm.hk[p][dd];
+      sm.kbar[dd] = t;
+    } else {
+#pragma unroll
+      for (int p = 0; p < 8; ++p) t += sm.hv[p][dd];
+      sm.vbar[dd] = t;
+    }
+  }
   // merge, first pass (beside the ranking): this thread's PER splits of output d
   const int d = tid & 127, part = tid >> 7;
   float rm = -1e30f, rl = 0.f, ro = 0.f;
@@ -1333,14 +1532,21 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   float ve_d = 0.f;
   float4 ve4 = make_float4(0.f, 0.f, 0.f, 0.f);
   if (e_slot >= 0) {   // phi_e = W_theta k_e, eight threads per row
-    ve_d = bf2f(((const bf16_t*)(er + DEC_CAND_V))[d]);
-    const uint2 t = *(const uint2*)(er + DEC_CAND_V + 2 * d4);
-    ve4 = make_float4(bf_lo(t.x), bf_hi(t.x), bf_lo(t.y), bf_hi(t.y));
     float wv[16], kv[16];
     unpack8(Wr0, wv);
     unpack8(Wr1, wv + 8);
-    unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh), kv);
-    unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh + 4), kv + 8);
+    if (a.hs) {
+      ve_d = sm.vbar[d];
+      ve4 = *(const float4*)&sm.vbar[4 * d4];
+#pragma unroll
+      for (int e = 0; e < 16; e += 4) *(float4*)&kv[e] = *(const float4*)&sm.kbar[16 * hh + e];
+    } else {
+      ve_d = bf2f(((const bf16_t*)(er + DEC_CAND_V))[d]);
+      const uint2 t = *(const uint2*)(er + DEC_CAND_V + 2 * d4);
+      ve4 = make_float4(bf_lo(t.x), bf_hi(t.x), bf_lo(t.y), bf_hi(t.y));
+      unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh), kv);
+      unpack8(*(const uint4*)(er + DEC_CAND_K + 8 * hh + 4), kv + 8);
+    }
     float pe = 0.f;
 #pragma unroll
     for (int e = 0; e < 16; ++e) pe = fmaf(wv[e], kv[e], pe);
@@ -1398,12 +1604,12 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
       dn = fmaf(a.lambda, dn, a.eta * sq);
     }
     if (lane == 0) { sm.den = dn + a.mem_eps; sm.dot = dt; }
-  } else if (j == 0 && w >= 6 && w < 8 && e_slot >= 0) {   // b <- lambda b + eta phi_e^2 (wc = tid - 384 here)
+  } else if (writer && w >= 6 && w < 8 && e_slot >= 0) {   // b <- lambda b + eta phi_e^2 (wc = tid - 384 here)
     float pe = 0.f;
 #pragma unroll
     for (int k = 0; k < 8; ++k) pe += sm.phe2[k][wc];
     sm.phe[wc] = pe;
-    a.bvec[(size_t)u * IM_DM + wc] = fmaf(a.lambda, b_old, a.eta * pe * pe);
+    a.bvec[(size_t)su * IM_DM + wc] = fmaf(a.lambda, b_old, a.eta * pe * pe);
   }
   float o_attn = 0.f;
   if (tid < IM_D) {   // fold the 8 thread groups of output d
@@ -1431,7 +1637,7 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     if (a.readout) a.readout[oi] = res;
   }
   if (j != 0) return;
-  if (e_slot >= 0) {
+  if (e_slot >= 0 && writer) {
     // M <- lambda M + eta phi_e v_e^T for this thread's 4 x 4 patch
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -1445,16 +1651,16 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   // fill the hole with the last entry, publish the new length
   const int n_keep = (e_slot >= 0) ? n - 1 : n;
   if (e_slot >= 0 && e_slot < n_keep) {
-    const size_t dst = (size_t)u * a.C + e_slot;
+    const size_t dst = (size_t)u * a.C + e_slot, idst = (size_t)su * a.C + e_slot;
     if (tid < 16) *(uint4*)(a.K + dst * IM_D + tid * 8) = mv;
     else if (tid < 32) *(uint4*)(a.V + dst * IM_D + (tid - 16) * 8) = mv;
-    else if (tid < 40) *(uint4*)(a.Kidx + dst * IM_DI + (tid - 32) * 8) = mv;
-    else if (tid == 40) a.pos[dst] = mvpos;
+    else if (tid < 32 + a.di / 8) { if (lead) *(uint4*)(a.Kidx + idst * a.di + (tid - 32) * 8) = mv; }
+    else if (tid == 40 && lead) a.pos[idst] = mvpos;
   }
-  if (tid == 0) {
-    a.len[u] = n_keep;
-    a.nproj[u] = n_keep;
-    if (a.evicted) a.evicted[u] = e_slot;
+  if (tid == 0 && lead) {
+    a.len[su] = n_keep;
+    a.nproj[su] = n_keep;
+    if (a.evicted && !a.hs) a.evicted[u] = e_slot;   // (head-shared: k_hs_score reported it per sequence)
   }
 }
 

@@ -494,7 +494,11 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   IM_REQUIRE(eta > 0.f, "eta must be > 0");
   const im_config& c = h->cfg;
   if (c.batch > 64) return set_err(h, IM_ERR_UNSUPPORTED, "%s: batch above 64", what);
-  if (c.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "%s: head_shared = 1 is served step by step only", what);
+  if (c.head_shared && no_score)
+    return set_err(h, IM_ERR_UNSUPPORTED, "%s: not built for head_shared = 1", what);
+  if (c.head_shared && c.n_kv_heads > 64) return set_err(h, IM_ERR_UNSUPPORTED, "%s: more than 64 KV heads", what);
+  if (c.head_shared && h->max_live > 64 * DEC_KEYS + 1)
+    return set_err(h, IM_ERR_UNSUPPORTED, "%s: head_shared = 1 needs max_live <= %d", what, 64 * DEC_KEYS + 1);
   hipStream_t s = (hipStream_t)stream;
   int rc = ensure_ws(h, s);
   if (rc) return rc;
@@ -521,6 +525,40 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
                                                          : (h->max_live + DEC_KEYS - 1) / DEC_KEYS;
   a.S_alloc = h->dec_splits; a.max_live = h->max_live;
   a.rms_eps = c.rms_eps; a.mem_eps = c.mem_eps; a.scale = c.softmax_scale; a.lambda = lambda; a.eta = eta;
+  a.hs = c.head_shared; a.H_set = heads_per_set(c); a.di = c.idx_dim; a.xk = (double*)(h->ws + h->off_xk);
+  if (c.head_shared) {
+    // four launches: projections + append + readout terms; the sequence's scores and decision; the
+    // attention partials with that slot named; the per-(unit, head) tail
+    int32_t* evict_units = words + 32;   // [units]; the recent window's newest position is found in k_hs_score
+    a.ext_evict = evict_units;
+    const int hs_prep_blocks = (1 + DEC_MP) * units + c.n_idx_heads * IM_DI_SHARED / 2 + (c.n_idx_heads + 1) / 2 +
+                               IM_DI_SHARED / 2;
+    const int hs_main_blocks = units * (a.S > 0 ? a.S : 1);
+    const bool hprof = h->prof_ev && h->prof_n < h->prof_max;
+    hipEvent_t hev0 = hprof ? h->prof_ev[2 * h->prof_n] : nullptr, hev1 = hprof ? h->prof_ev[2 * h->prof_n + 1] : nullptr;
+    if (hprof && h->prof_span != IM_PROFILE_MAIN) (void)hipEventRecord(hev0, s);
+    k_hs_prep<<<hs_prep_blocks, 256, 0, s>>>(a);
+    k_hs_score<<<c.batch, 1024, 0, s>>>(a, evict_units);
+    if (hprof && h->prof_span == IM_PROFILE_MAIN) (void)hipEventRecord(hev0, s);
+    if (hprof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(hev1, s);
+#define IM_HS_CASE(g)                                                                  \
+  case g:                                                                              \
+    k_att_main<g><<<hs_main_blocks, DEC_MT / 2, 0, s>>>(a);                            \
+    if (hprof && h->prof_span != IM_PROFILE_PREP) (void)hipEventRecord(hev1, s);       \
+    if (a.S <= 8) k_dec_tail_head<g, 8><<<units * g, DEC_TT, 0, s>>>(a);               \
+    else if (a.S <= 16) k_dec_tail_head<g, 16><<<units * g, DEC_TT, 0, s>>>(a);        \
+    else if (a.S <= 32) k_dec_tail_head<g, 32><<<units * g, DEC_TT, 0, s>>>(a);        \
+    else k_dec_tail_head<g, 64><<<units * g, DEC_TT, 0, s>>>(a);                       \
+    break;
+    switch (G) {
+      IM_HS_CASE(1) IM_HS_CASE(2) IM_HS_CASE(3) IM_HS_CASE(4)
+      IM_HS_CASE(5) IM_HS_CASE(6) IM_HS_CASE(7) IM_HS_CASE(8)
+      default: return set_err(h, IM_ERR_UNSUPPORTED, "group size %d", G);
+    }
+#undef IM_HS_CASE
+    if (hprof) h->prof_n++;
+    return launch_check(h, what);
+  }
   // the per-unit blocks come first in the prep kernel's block order: an attend-only step launches
   // just those (no query-side indexer projections)
   const int prep_blocks = (no_score ? 0 : c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2) + (1 + DEC_MP) * units;

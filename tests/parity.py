@@ -313,7 +313,26 @@ class LockStepShared:
         ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn, posn, sel(q_attn), budget, w.lam, w.eta)
         self.compare(*ref, tag)
 
-    def compare(self, scores, keep, evict, out, res, tag):
+    def event_fused(self, t: int, budget: int, tag: str):
+        """One decode token through im_decode_step (four launches in this layout)."""
+        w, dev = self.w, self.dev
+        d = lambda x: x.to(dev)
+        k_new = self.K[:, :, t:t + 1].contiguous(); v_new = self.V[:, :, t:t + 1].contiguous()
+        q_new = self.Q[:, t:t + 1].contiguous(); x_new = self.X[:, t:t + 1].contiguous()
+        pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+        posd = d(pos).view(w.batch)
+        self.gpu.decode_step(d(k_new), d(v_new), posd, d(q_new).view(w.batch, w.n_q_heads, w.head_dim),
+                             d(x_new).view(w.batch, -1), posd, budget, w.lam, w.eta, debug=True)
+        torch.cuda.synchronize()
+        bi_t = torch.tensor(self.batch_ids, device=k_new.device)
+        sel = lambda x: f64(x.index_select(0, bi_t))
+        posn = pos.numpy()[self.batch_ids]
+        xn = sel(x_new)
+        ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn, posn, sel(q_new)[:, 0], budget,
+                            w.lam, w.eta)
+        self.compare(*ref, tag, fused=True)
+
+    def compare(self, scores, keep, evict, out, res, tag, fused=False):
         w, g, st = self.w, self.gpu, self.gpu.st
         G = w.group
         n_keep = g.n_keep.cpu().numpy(); n_evict = g.n_evict.cpu().numpy()
@@ -331,9 +350,15 @@ class LockStepShared:
             same = (s_ref == s_gpu) | (np.isneginf(s_ref) & np.isneginf(s_gpu))
             assert same.all(), (f"{u}: {int((~same).sum())} of {n_before} scores differ, max "
                                 f"{np.nanmax(np.abs(np.where(same, 0, s_ref - s_gpu))):.3e}")
-            assert n_keep[b] == len(kr) and n_evict[b] == len(er), u
-            assert np.array_equal(keep_idx[b, :len(kr)], kr), f"{u}: keep list differs"
-            assert np.array_equal(evict_idx[b, :len(er)], er), f"{u}: evict list differs"
+            if fused:
+                assert len(er) <= 1, u
+                want_e = int(er[0]) if len(er) else -1
+                got_e = int(g.evicted.cpu().numpy()[b])
+                assert got_e == want_e, f"{u}: evicted slot {got_e} != {want_e}"
+            else:
+                assert n_keep[b] == len(kr) and n_evict[b] == len(er), u
+                assert np.array_equal(keep_idx[b, :len(kr)], kr), f"{u}: keep list differs"
+                assert np.array_equal(evict_idx[b, :len(er)], er), f"{u}: evict list differs"
             n = int(self.ref.len[ib])
             assert lens[b] == n and nproj[b] == n, u
             assert np.array_equal(pos[b, :n], self.ref.pos[ib, :n]), f"{u}: positions"
@@ -346,7 +371,7 @@ class LockStepShared:
             dmax = float(np.max(np.abs(res_g[b] - res[ib])))
             assert dmax <= 1e-3 * float(np.max(np.abs(res[ib]))) + 1e-30, f"{u}: readout diff {dmax:.3e}"
 
-    def run_schedule(self, decode_steps=None):
+    def run_schedule(self, decode_steps=None, fused_decode=False):
         w = self.w
         steps = w.decode_steps if decode_steps is None else decode_steps
         L = w.context
@@ -357,5 +382,8 @@ class LockStepShared:
                 self.event(c0, min(L, c0 + w.prefill_chunk), w.budget, f"chunk@{c0}")
         im.im_set_max_live(self.handle, min(w.capacity, w.budget + 1))
         for t in range(L, L + steps):
-            self.event(t, t + 1, w.budget, f"decode@{t}")
+            if fused_decode:
+                self.event_fused(t, w.budget, f"fused decode@{t}")
+            else:
+                self.event(t, t + 1, w.budget, f"decode@{t}")
         assert im.im_query_status(self.handle) == 0

@@ -44,3 +44,8 @@ def test_cfg3_head_shared_full_size_sampled_sequence():
     # keys of 16 dims per sequence, one eviction set per sequence, rows of 8 KV heads summed into one memory
     w = WORKLOADS["cfg3"].shared(n_layers=1, decode_steps=3)
     LockStepShared(w, gen_device="cuda", batch_ids=[2]).run_schedule()
+
+
+def test_cfg3_head_shared_full_size_fused_decode():
+    w = WORKLOADS["cfg3"].shared(n_layers=1, decode_steps=5)
+    LockStepShared(w, gen_device="cuda", batch_ids=[1]).run_schedule(fused_decode=True)

@@ -244,7 +244,26 @@ def test_head_shared_layout(name, kw):
     LockStepShared(WORKLOADS[name].shared(n_layers=1, **kw)).run_schedule()
 
 
-def test_head_shared_layout_rejects_the_fused_entry_points():
+@pytest.mark.parametrize("name,kw", [
+    ("cfg1", dict()),
+    ("cfg2", dict(batch=2, context=1100, budget=300, decode_steps=4)),
+    ("cfg3", dict(batch=2, context=1500, budget=333, decode_steps=4)),
+    ("cfg4", dict(batch=3, context=1300, budget=130, decode_steps=4)),       # 4 KV heads of 7 query heads
+    ("cfg4", dict(batch=2, context=700, budget=128, decode_steps=3)),        # n = 129: one key beyond the splits
+    ("cfg4", dict(batch=1, context=1500, budget=1200, decode_steps=3)),      # 10 splits
+    ("cfg5", dict(batch=1, context=1536, budget=512, decode_steps=4, prefill_chunk=512)),
+    ("cfg1", dict(context=40, budget=64, decode_steps=30)),                  # grows to the budget, then evicts
+    ("cfg1", dict(batch=3, context=300, budget=64, decode_steps=3, n_recent=8)),   # recent window forced
+    ("cfg1", dict(n_q_heads=64, context=500, budget=140, decode_steps=3)),   # 16 indexer heads, 8 per group
+    ("cfg1", dict(n_q_heads=8, n_kv_heads=1, context=500, budget=140, decode_steps=3)),   # a single KV head
+    ("cfg1", dict(batch=11, context=260, budget=4, decode_steps=3)),         # budget = the sinks alone
+])
+def test_head_shared_layout_fused_decode(name, kw):
+    w = WORKLOADS[name].shared(n_layers=1, **kw)
+    LockStepShared(w).run_schedule(fused_decode=True)
+
+
+def test_head_shared_layout_rejects_what_is_not_built_for_it():
     w = WORKLOADS["cfg1"].shared()
     ls = LockStepShared(w)
     g = ls.gpu
