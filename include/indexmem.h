@@ -18,8 +18,9 @@
  * across heads per token; Section 4: d_index = d_head / 8 = 16): all KV heads of a sequence form
  * one SET that holds the same tokens in the same slots; Kidx, pos, len, n_projected, the scores,
  * the keep / evict lists and (M, b) exist once per sequence (the H_kv axis below is dropped) and
- * K, V stay per unit.  Tokens enter through im_append_kv_hidden.  The step-by-step entry points
- * serve both layouts; the fused decode entry points serve head_shared = 0 only.
+ * K, V stay per unit.  Tokens enter through im_append_kv_hidden.  The step-by-step entry points and
+ * im_decode_step serve both layouts; im_attend_step and im_decode_step_shared serve head_shared = 0
+ * only.
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers unless a comment says "host".  The caller owns all
@@ -213,7 +214,10 @@ int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_s
  * evicted_slot [B, H_kv] int32 (slot that was evicted, before compaction; -1 if none),
  * scores_dbg [B, H_kv, C] fp32 (as im_index_score writes them).
  * batch <= 64.  n_sink + n_recent <= budget <= capacity - 1 is not required, but a unit with
- * len = capacity cannot take the new token (IM_STATUS_APPEND_OVERFLOW). */
+ * len = capacity cannot take the new token (IM_STATUS_APPEND_OVERFLOW).
+ * head_shared = 1: the same step as im_append_kv_hidden(n_new = 1) -> ... in four launches; x_gate
+ * [B, gate_in_dim] is the new token's hidden state (it feeds the head gate and the token's indexer
+ * key); evicted_slot is [B], scores_dbg [B, C]; at most 16 KV heads and max_live <= 8193. */
 int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, const void* q,
                        const void* x_gate, const int32_t* q_pos, const void* k_new, const void* v_new,
                        const int32_t* pos_new, int32_t budget, float lambda, float eta, void* out,

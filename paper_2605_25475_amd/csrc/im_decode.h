@@ -72,6 +72,10 @@ struct DecArgs {
   uint32_t* cand;
   float* qm;          // per unit: the eviction-independent terms of the memory readout (DEC_QM floats per head)
   double* xk;         // head-shared layout: U_k x of the new token, [B][16]
+  uint4* hs_part;     // head-shared layout: [B][HS_NSC] last-ranked entry of each scoring workgroup
+                      // (rank key hi, lo, slot or -1, unused)
+  int32_t* hs_evict;  // head-shared layout: [units] the slot the unit's sequence evicts (-1: none), written
+                      // by the attention kernel for the tail (ext_evict points here)
   // scalars
   int B, H, H_kv, C, H_idx, gate_in, n_sink, n_recent, budget, S, S_alloc, max_live;
   // head-shared layout (hs = 1): the H_set = H_kv units of a sequence form one set; len, pos, Kidx
@@ -79,6 +83,23 @@ struct DecArgs {
   int hs, H_set, di;
   float rms_eps, mem_eps, scale, lambda, eta;
 };
+
+#define HS_NSC 8   // scoring workgroups per sequence in the head-shared layout
+
+// The entry a sequence evicts in the head-shared layout: the last-ranked one over its scoring
+// workgroups' results (on a full tie the largest slot: chunks ascend), if the sequence is above its
+// budget with its n live entries; else -1.
+__device__ __forceinline__ int hs_pick(const DecArgs& a, const int b, const int n) {
+  const uint4* p = a.hs_part + (size_t)b * HS_NSC;
+  uint32_t bh = 0xffffffffu, bl = 0xffffffffu;
+  int at = -1;
+#pragma unroll
+  for (int c = 0; c < HS_NSC; ++c) {
+    const uint4 v = p[c];
+    if ((int)v.z >= 0 && (v.x < bh || (v.x == bh && v.y <= bl))) { bh = v.x; bl = v.y; at = (int)v.z; }
+  }
+  return (n > a.budget) ? at : -1;
+}
 
 __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
   f[0] = bf_lo(u.x); f[1] = bf_hi(u.x); f[2] = bf_lo(u.y); f[3] = bf_hi(u.y);
@@ -334,8 +355,8 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
 // --------------------------------------------------------------------------------------------
 // Head-shared layout: k_hs_prep and k_hs_score take the place of k_dec_prep and of the scoring
 // waves.  One indexer key per token (from its hidden state) and one score per token mean one
-// decision per sequence, so the sequence's workgroup ranks all its keys (16 values each) before the
-// attention launch, which then treats the decision as given (the path of a named slot).
+// decision per sequence, so a few workgroups per sequence rank all its keys (16 values each) before
+// the attention launch, which then treats the decision as given (the path of a named slot).
 // --------------------------------------------------------------------------------------------
 // Block roles: [0, U) append the new (k, v) of a unit (the set's position by its first head);
 // [U, (1 + DEC_MP) U) the readout terms; then two rows each of U_q (input q), G and U_k (input x).
@@ -386,19 +407,22 @@ __global__ __launch_bounds__(256) void k_hs_prep(const DecArgs a) {
   }
 }
 
-// grid (B), 1024 threads: QK-Norm of the step's query features, head gates, the new token's indexer
-// key (stored), the score of every live key of the sequence, and the entry ranked last by
-// (score, then position, then slot) with sinks and the recent window forced to the top: the one to
-// evict when the sequence is above its budget.  Writes that slot (or -1) for every unit of the
-// sequence to a.ext_evict's array and, optionally, to a.evicted [B] and the scores to a.scores [B][C].
-__global__ __launch_bounds__(1024) void k_hs_score(const DecArgs a, int32_t* __restrict__ evict_units) {
+// grid (B * HS_NSC), 512 threads.  Workgroup (b, c) scores chunk c of sequence b's live keys: QK-Norm
+// of the step's query features and the head gates (every workgroup, for itself), the new token's
+// indexer key (stored by c = 0), the scores of the chunk's keys, and the chunk's entry ranked last by
+// (score, then position, then slot) with sinks and the recent window forced to the top.  The
+// consumers (attention and tail kernels) take the last-ranked of the HS_NSC results: hs_pick.
+// Optionally writes the scores to a.scores [B][C].
+#define HS_ST 512
+__global__ __launch_bounds__(HS_ST) void k_hs_score(const DecArgs a) {
   constexpr int DI = IM_DI_SHARED;
   __shared__ double s_q[16][DI];
   __shared__ double s_al[16];
   __shared__ float s_kn[DI];
-  __shared__ uint32_t s_hi[16], s_lo[16];
-  __shared__ int s_at[16], s_mp[16];
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  constexpr int NW = HS_ST / 64;
+  __shared__ uint32_t s_hi[NW], s_lo[NW];
+  __shared__ int s_at[NW], s_mp[NW];
+  const int b = blockIdx.x / HS_NSC, ck = blockIdx.x % HS_NSC, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int n_old = a.len[b];
   const bool fits = n_old + 1 <= a.C;
   const int n = min(n_old + (fits ? 1 : 0), a.max_live);
@@ -422,12 +446,12 @@ __global__ __launch_bounds__(1024) void k_hs_score(const DecArgs a, int32_t* __r
     const double wk = a.nkw ? (double)bf2f(a.nkw[d]) : 1.0;
     const bf16_t kb = d2bf_rne(v / rr * wk);
     s_kn[d] = bf2f(kb);
-    if (fits) a.Kidx[((size_t)b * a.C + n_old) * DI + d] = kb;
+    if (fits && ck == 0) a.Kidx[((size_t)b * a.C + n_old) * DI + d] = kb;
   }
   int mxp = 0;
   if (a.n_recent > 0) {   // newest position of the sequence, the new token included
     int m = fits ? newpos : INT_MIN;
-    for (int i = tid; i < min(n_old, a.max_live); i += 1024) m = max(m, ps[i]);
+    for (int i = tid; i < min(n_old, a.max_live); i += HS_ST) m = max(m, ps[i]);
     m = (int)(wave_max_u((uint32_t)m ^ 0x80000000u) ^ 0x80000000u);
     if (lane == 0) s_mp[w] = m;
   }
@@ -435,35 +459,56 @@ __global__ __launch_bounds__(1024) void k_hs_score(const DecArgs a, int32_t* __r
   if (a.n_recent > 0) {
     mxp = s_mp[0];
 #pragma unroll
-    for (int i = 1; i < 16; ++i) mxp = max(mxp, s_mp[i]);
+    for (int i = 1; i < NW; ++i) mxp = max(mxp, s_mp[i]);
   }
+  // Scores on the fp64 matrix cores, a tile of 16 keys per wave at a time: Z[head][key] = q . Kidx_tile^T
+  // as 4 steps of the 16x16x4 product (lane (l16, kq) supplies dims 4 kq .. 4 kq + 3 of head l16 and of
+  // key l16; result register r is head 4 r + kq, key l16).  A lane adds the gated terms of its 4 heads,
+  // the 4 lanes of a key meet by two half-swaps, and the lanes kq = 0 rank their key.
+  const int l16 = lane & 15, kq = lane >> 4;
+  double qd[4], al4[4];
+#pragma unroll
+  for (int m = 0; m < 4; ++m) { qd[m] = s_q[l16][4 * kq + m]; al4[m] = s_al[4 * m + kq]; }
   uint32_t bhi = 0xffffffffu, blo = 0xffffffffu;
   int bat = -1;
-  for (int t = tid; t < n; t += 1024) {
-    float kf[DI];
-    int p;
-    if (t < n_old) {
-      unpack8(*(const uint4*)(kx + (size_t)t * DI), kf);
-      unpack8(*(const uint4*)(kx + (size_t)t * DI + 8), kf + 8);
-      p = ps[t];
-    } else {
+  const int tpc = ((n + 15) / 16 + HS_NSC - 1) / HS_NSC;           // tiles per chunk
+  const int n_tiles = min((n + 15) / 16, (ck + 1) * tpc);          // this chunk: tiles [ck tpc, n_tiles)
+  constexpr int PF = 4;   // tiles in flight per wave
+#pragma unroll 1
+  for (int t0 = ck * tpc + w; t0 < n_tiles; t0 += NW * PF) {
+    uint2 ka[PF];
+    int pk[PF];
 #pragma unroll
-      for (int d = 0; d < DI; ++d) kf[d] = s_kn[d];
-      p = newpos;
+    for (int i = 0; i < PF; ++i) {
+      const int key = 16 * (t0 + NW * i) + l16;
+      ka[i] = *(const uint2*)(kx + (size_t)max(min(key, n_old - 1), 0) * DI + 4 * kq);
+      pk[i] = ps[max(min(key, n_old - 1), 0)];
     }
-    double asum = 0.0;
-    for (int j = 0; j < a.H_idx; ++j) {
-      double z = 0.0;
 #pragma unroll
-      for (int d = 0; d < DI; ++d) z = fma(s_q[j][d], (double)kf[d], z);
-      asum += s_al[j] * fmax(z, 0.0);
+    for (int i = 0; i < PF; ++i) {
+      const int key = (t0 + NW * i < n_tiles) ? 16 * (t0 + NW * i) + l16 : n;   // past the chunk: never ranked
+      float f[4] = {bf_lo(ka[i].x), bf_hi(ka[i].x), bf_lo(ka[i].y), bf_hi(ka[i].y)};
+      if (key >= n_old) {   // the new token's key (columns past it are never ranked)
+#pragma unroll
+        for (int m = 0; m < 4; ++m) f[m] = s_kn[4 * kq + m];
+      }
+      v4d z = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int m = 0; m < 4; ++m) z = __builtin_amdgcn_mfma_f64_16x16x4f64(qd[m], (double)f[m], z, 0, 0, 0);
+      double asum = 0.0;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) asum = fma(al4[r], fmax(z[r], 0.0), asum);
+      asum = rows_sum_d(asum);
+      if (kq == 0 && key < n) {
+        const int p = (key < n_old) ? pk[i] : newpos;
+        const float sc = (p <= qpos) ? (float)asum : -INFINITY;
+        if (a.scores) a.scores[(size_t)b * a.C + key] = sc;
+        const bool forced = (p < a.n_sink) || (a.n_recent > 0 && (long long)p > (long long)mxp - a.n_recent);
+        const uint32_t khi = forced ? IM_KEY_PINF : score_key(sc);
+        const uint32_t klo = (uint32_t)(~((uint32_t)p ^ 0x80000000u));
+        if (khi < bhi || (khi == bhi && klo <= blo)) { bhi = khi; blo = klo; bat = key; }   // ascending keys: <= keeps the largest slot
+      }
     }
-    const float sc = (p <= qpos) ? (float)asum : -INFINITY;
-    if (a.scores) a.scores[(size_t)b * a.C + t] = sc;
-    const bool forced = (p < a.n_sink) || (a.n_recent > 0 && (long long)p > (long long)mxp - a.n_recent);
-    const uint32_t khi = forced ? IM_KEY_PINF : score_key(sc);
-    const uint32_t klo = (uint32_t)(~((uint32_t)p ^ 0x80000000u));
-    if (khi < bhi || (khi == bhi && klo <= blo)) { bhi = khi; blo = klo; bat = t; }   // ascending t: <= keeps the largest slot
   }
   {
     const uint32_t mh = wave_min_u(bhi);
@@ -473,16 +518,14 @@ __global__ __launch_bounds__(1024) void k_hs_score(const DecArgs a, int32_t* __r
   }
   __syncthreads();
   if (tid < 64) {
-    const bool on = lane < 16 && s_at[lane & 15] >= 0;
-    const uint32_t khi = on ? s_hi[lane & 15] : 0xffffffffu, klo = on ? s_lo[lane & 15] : 0xffffffffu;
+    const bool on = lane < NW && s_at[lane & (NW - 1)] >= 0;
+    const uint32_t khi = on ? s_hi[lane & (NW - 1)] : 0xffffffffu, klo = on ? s_lo[lane & (NW - 1)] : 0xffffffffu;
     const uint32_t mh = wave_min_u(khi);
     const uint32_t ml = wave_min_u((on && khi == mh) ? klo : 0xffffffffu);
-    const int win = (int)wave_max_u((on && khi == mh && klo == ml) ? (uint32_t)s_at[lane & 15] + 1u : 0u) - 1;
-    const int e = (n > a.budget && win >= 0) ? win : -1;
-    if (lane < a.H_kv) evict_units[b * a.H_kv + lane] = e;
+    const int win = (int)wave_max_u((on && khi == mh && klo == ml) ? (uint32_t)s_at[lane & (NW - 1)] + 1u : 0u) - 1;
     if (lane == 0) {
-      if (a.evicted) a.evicted[b] = e;
-      if (n > a.budget + 1) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
+      a.hs_part[(size_t)b * HS_NSC + ck] = make_uint4(mh, ml, (uint32_t)win, 0u);
+      if (ck == 0 && n > a.budget + 1) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
     }
   }
 }
@@ -525,7 +568,10 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   const int nk = max(0, min(DEC_KEYS, n - k0));
   uint32_t* crec = a.cand + ((size_t)u * a.S_alloc + s) * DEC_CAND;
   if (nk <= 0) {
-    if (s == 0 && tid == 0) crec[3] = (uint32_t)n;   // an empty unit still tells the tail its length
+    if (s == 0 && tid == 0) {
+      crec[3] = (uint32_t)n;   // an empty unit still tells the tail its length
+      if (a.hs) a.hs_evict[u] = -1;
+    }
     return;
   }
   const size_t base = (size_t)u * a.C + k0;
@@ -542,14 +588,19 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   int mypos = 0;
   uint4 lkx = make_uint4(0, 0, 0, 0);
   int lpos = 0;
+  uint4 pk[HS_NSC];
+  int ev_in = -1;
   if (!SCORE) {
-    // no scoring waves: nothing is left out of the partial, unless the caller names the slot to
-    // evict; that entry is then this split's candidate if it lies here (wave tid's 32 keys)
+    // no scoring waves: nothing is left out of the partial, unless the slot to evict is named: by the
+    // caller, or (head-shared layout) by the sequence's scoring workgroups.  The loads go out here and
+    // are looked at once the wave's stream loads are in flight.
     if (tid < 4) {
-      const int fl = (a.ext_evict ? a.ext_evict[u] : -1) - k0;
-      const bool here = fl >= 32 * tid && fl < 32 * tid + 32 && fl < nk;
-      sm.c64[tid] = here ? 0ull : ~0ull;
-      sm.cslot[tid] = here ? fl : -1;
+      if (a.hs) {
+#pragma unroll
+        for (int c = 0; c < HS_NSC; ++c) pk[c] = a.hs_part[(size_t)b * HS_NSC + c];
+      } else if (a.ext_evict) {
+        ev_in = a.ext_evict[u];
+      }
     }
     // the last live slot's indexer key and position for the last-slot record
     if (own_last && tid < a.di / 8) lkx = *(const uint4*)(a.Kidx + ((size_t)su * a.C + (n - 1)) * a.di + 8 * tid);
@@ -764,6 +815,23 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     // waits only for what it uses while the rest is still streaming in
     __asm__ volatile("" ::: "memory");
     DEC_STAMP(1);
+    if (!SCORE && tid < 4) {
+      // the named entry is this split's candidate if it lies here (wave tid's 32 keys)
+      int ev = ev_in;
+      if (a.hs) {   // as hs_pick; the sequence's decision is handed to the tail per unit
+        uint32_t bh = 0xffffffffu, bl = 0xffffffffu;
+        int at = -1;
+#pragma unroll
+        for (int c = 0; c < HS_NSC; ++c)
+          if ((int)pk[c].z >= 0 && (pk[c].x < bh || (pk[c].x == bh && pk[c].y <= bl))) { bh = pk[c].x; bl = pk[c].y; at = (int)pk[c].z; }
+        ev = (n > a.budget) ? at : -1;
+        if (s == 0 && tid == 0) a.hs_evict[u] = ev;
+      }
+      const int fl = ev - k0;
+      const bool here = fl >= 32 * tid && fl < 32 * tid + 32 && fl < nk;
+      sm.c64[tid] = here ? 0ull : ~0ull;
+      sm.cslot[tid] = here ? fl : -1;
+    }
     if (!SCORE && do_x_any) {
       float qv[8], kv[8], lp = 0.f;
       unpack8(yq, qv);
@@ -1425,10 +1493,14 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     if (a.hs) {
       const int e_raw = a.ext_evict[u];
       const int rec = (e_raw >= 0) ? min(e_raw / DEC_KEYS, LS) : 0;
-      for (int hh = tid >> 7; hh < a.H_set; hh += 8) {
-        const uint32_t* r = a.cand + ((size_t)(su * a.H_set + hh) * a.S_alloc + rec) * DEC_CAND;
-        hks += bf2f(((const bf16_t*)(r + DEC_CAND_K))[tid & 127]);
-        hvs += bf2f(((const bf16_t*)(r + DEC_CAND_V))[tid & 127]);
+#pragma unroll
+      for (int it = 0; it < 2; ++it) {   // heads (tid >> 7) and (tid >> 7) + 8; absent ones re-read the last, unused
+        const int hh = (tid >> 7) + 8 * it;
+        const uint32_t* r = a.cand + ((size_t)(su * a.H_set + min(hh, a.H_set - 1)) * a.S_alloc + rec) * DEC_CAND;
+        const float kx = bf2f(((const bf16_t*)(r + DEC_CAND_K))[tid & 127]);
+        const float vx = bf2f(((const bf16_t*)(r + DEC_CAND_V))[tid & 127]);
+        hks += (hh < a.H_set) ? kx : 0.f;
+        hvs += (hh < a.H_set) ? vx : 0.f;
       }
     }
     __asm__ volatile("" ::: "memory");
@@ -1660,7 +1732,7 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   if (tid == 0 && lead) {
     a.len[su] = n_keep;
     a.nproj[su] = n_keep;
-    if (a.evicted && !a.hs) a.evicted[u] = e_slot;   // (head-shared: k_hs_score reported it per sequence)
+    if (a.evicted) a.evicted[su] = e_slot;
   }
 }
 
@@ -1675,7 +1747,7 @@ __global__ __launch_bounds__(DEC_MT, 4) void k_dec_main(const DecArgs a, const d
 
 // the attend-only variant: same grid, 4 waves per workgroup
 template <int G>
-__global__ __launch_bounds__(DEC_MT / 2, 4) void k_att_main(const DecArgs a) {
+__global__ __launch_bounds__(DEC_MT / 2, G <= 4 ? 4 : 2) void k_att_main(const DecArgs a) {
   __shared__ __attribute__((aligned(16))) DecSplitSmem sm;
   const int U = a.B * a.H_kv;
   dec_split<G, false>(a, blockIdx.x % U, blockIdx.x / U, sm, nullptr, nullptr);

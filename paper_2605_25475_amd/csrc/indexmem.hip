@@ -20,7 +20,7 @@ struct im_handle {
   int max_live;
   bool ws_ready;
   // workspace layout (byte offsets)
-  size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, off_dqm, off_spart, off_xk, total;
+  size_t off_status, off_qy, off_alpha, off_mem, off_attn, off_dpart, off_dcand, off_dqm, off_spart, off_xk, off_hspart, total;
   int mem_split, attn_chunks, dec_splits;
   // optional kernel timing (im_profile_start / im_profile_stop)
   hipEvent_t* prof_ev;
@@ -89,6 +89,7 @@ void layout(const im_config* c, im_handle* h) {
   h->off_spart = off;  off = align256(off + (size_t)IM_SCORE_GROUPS * units * c->capacity * sizeof(float));
   // head_shared: U_k X of the rows of one append, fp64
   h->off_xk = off;     off = align256(off + (c->head_shared ? B * c->capacity * IM_DI_SHARED * sizeof(double) : 0));
+  h->off_hspart = off; off = align256(off + (c->head_shared ? B * HS_NSC * sizeof(uint4) : 0));
   h->total = off;
 }
 
@@ -496,7 +497,6 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   if (c.batch > 64) return set_err(h, IM_ERR_UNSUPPORTED, "%s: batch above 64", what);
   if (c.head_shared && no_score)
     return set_err(h, IM_ERR_UNSUPPORTED, "%s: not built for head_shared = 1", what);
-  if (c.head_shared && c.n_kv_heads > 64) return set_err(h, IM_ERR_UNSUPPORTED, "%s: more than 64 KV heads", what);
   if (c.head_shared && h->max_live > 64 * DEC_KEYS + 1)
     return set_err(h, IM_ERR_UNSUPPORTED, "%s: head_shared = 1 needs max_live <= %d", what, 64 * DEC_KEYS + 1);
   hipStream_t s = (hipStream_t)stream;
@@ -529,8 +529,10 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   if (c.head_shared) {
     // four launches: projections + append + readout terms; the sequence's scores and decision; the
     // attention partials with that slot named; the per-(unit, head) tail
-    int32_t* evict_units = words + 32;   // [units]; the recent window's newest position is found in k_hs_score
-    a.ext_evict = evict_units;
+    a.hs_part = (uint4*)(h->ws + h->off_hspart);
+    a.hs_evict = words + 32;   // [units]
+    a.ext_evict = a.hs_evict;
+    if (c.n_kv_heads > 16) return set_err(h, IM_ERR_UNSUPPORTED, "%s: head_shared = 1 with more than 16 KV heads", what);
     const int hs_prep_blocks = (1 + DEC_MP) * units + c.n_idx_heads * IM_DI_SHARED / 2 + (c.n_idx_heads + 1) / 2 +
                                IM_DI_SHARED / 2;
     const int hs_main_blocks = units * (a.S > 0 ? a.S : 1);
@@ -538,7 +540,7 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
     hipEvent_t hev0 = hprof ? h->prof_ev[2 * h->prof_n] : nullptr, hev1 = hprof ? h->prof_ev[2 * h->prof_n + 1] : nullptr;
     if (hprof && h->prof_span != IM_PROFILE_MAIN) (void)hipEventRecord(hev0, s);
     k_hs_prep<<<hs_prep_blocks, 256, 0, s>>>(a);
-    k_hs_score<<<c.batch, 1024, 0, s>>>(a, evict_units);
+    k_hs_score<<<c.batch * HS_NSC, HS_ST, 0, s>>>(a);
     if (hprof && h->prof_span == IM_PROFILE_MAIN) (void)hipEventRecord(hev0, s);
     if (hprof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(hev1, s);
 #define IM_HS_CASE(g)                                                                  \

@@ -130,7 +130,7 @@ def test_head_shared_layout_validation(lib):
     pr = B.ImParams(X, X, X, None, None, X, X, 0.0)
     U = im.IM_ERR_UNSUPPORTED
     assert lib.im_append_kv(h, C.byref(st), X, X, X, 1, None) == U
-    assert lib.im_decode_step(h, C.byref(pr), C.byref(st), X, X, X, X, X, X, 64, 0.9, 0.5, X, None, None, None, None) == U
+    assert lib.im_decode_step(h, C.byref(pr), C.byref(st), X, None, X, X, X, X, 64, 0.9, 0.5, X, None, None, None, None) == im.IM_ERR_INVALID_ARG
     assert lib.im_attend_step(h, C.byref(pr), C.byref(st), X, X, X, X, X, None, None) == U
     assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, X, X, X, 0.9, 0.5, X, None, None) == U
     assert lib.im_append_kv_hidden(h, C.byref(pr), C.byref(st), X, X, X, X, 0, None) == im.IM_ERR_INVALID_ARG
