@@ -87,7 +87,7 @@ class Job:
                         n_idx_heads=w.n_idx_heads, idx_dim=w.idx_dim, n_sink=w.n_sink, n_recent=w.n_recent,
                         fold_block=w.fold_block, max_queries=n_q_max, head_shared=int(w.head_shared))
         self.handle = im.Handle(cfg, device)
-        self.layers, self.dec, self.qwin, self.tau, self.share, self.xdec = [], [], [], tau, share, []
+        self.layers, self.dec, self.qwin, self.tau, self.share, self.xdec, self.xwin = [], [], [], tau, share, [], []
         L = w.context
         assert n_steps <= w.decode_steps, "the workload defines fewer decode steps"
         for li in range(w.n_layers):
@@ -122,10 +122,11 @@ class Job:
             self.dec.append((kd, vd, qd))
             if w.head_shared:
                 self.xdec.append(X[:, L:].permute(1, 0, 2).contiguous().unsqueeze(2))   # [S, B, 1, d_model]
-            del X
             if tau:   # the query set of every compression interval, [B, tau, H, D] each
                 self.qwin.append([Q[:, L + k * tau:L + (k + 1) * tau].contiguous() for k in range(n_steps // tau)])
-            del K, V, Q
+                if w.head_shared:
+                    self.xwin.append([X[:, L + k * tau:L + (k + 1) * tau].contiguous() for k in range(n_steps // tau)])
+            del K, V, Q, X
             torch.cuda.synchronize()
             log(f"layer {li + 1}/{w.n_layers} prefilled")
         self.pos = (torch.arange(L, L + n_steps, dtype=torch.int32, device=device)
@@ -148,6 +149,8 @@ class Job:
                 if path == "fused":
                     layer.decode_step(kd[s], vd[s], pos.view(w.batch), q.view(w.batch, w.n_q_heads, -1),
                                       x.view(w.batch, -1), pos.view(w.batch), w.budget, w.lam, w.eta)
+                elif path == "periodic":
+                    layer.attend_step(kd[s], vd[s], pos, q.view(w.batch, w.n_q_heads, -1), debug=False, x_new=x)
                 else:
                     layer.step(kd[s], vd[s], pos, q, x, pos, q.view(w.batch, w.n_q_heads, -1), w.budget, w.lam,
                                w.eta, x_new=x)
@@ -171,7 +174,8 @@ class Job:
             k = s // self.tau
             for li, layer in enumerate(self.layers):
                 qw = self.qwin[li][k]
-                layer.compress(qw, qw.view(w.batch, self.tau, -1), self.posw[k], w.budget, w.lam, w.eta)
+                xg = self.xwin[li][k] if w.head_shared else qw.view(w.batch, self.tau, -1)
+                layer.compress(qw, xg, self.posw[k], w.budget, w.lam, w.eta)
 
 
 def cpu_baseline(w: Workload, budget_s: float = 20.0) -> dict:
@@ -252,7 +256,7 @@ def main() -> None:
                          "of a group scores and selects, the others apply its decision)")
     ap.add_argument("--head-shared", action="store_true",
                     help="the workload's cache shape in the head-shared layout (indexer keys of 16 values from "
-                         "hidden states, one eviction set and one memory per sequence); paths fused and steps")
+                         "hidden states, one eviction set and one memory per sequence); paths fused, steps and periodic")
     ap.add_argument("--share", type=int, default=4, help="layers per index-sharing group of --path shared")
     ap.add_argument("--tau", type=int, default=128, help="compression interval of --path periodic")
     ap.add_argument("--no-graph", action="store_true", help="launch the fused path eagerly")
@@ -269,8 +273,8 @@ def main() -> None:
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     w = WORKLOADS[a.workload]
     if a.head_shared:
-        if a.path not in ("fused", "steps"):
-            sys.exit("bench.py: --head-shared runs with --path fused or --path steps")
+        if a.path not in ("fused", "steps", "periodic"):
+            sys.exit("bench.py: --head-shared runs with --path fused, steps or periodic")
         w = w.shared()
     log = (lambda s: None) if a.quiet else (lambda s: print("[bench] " + s, file=sys.stderr, flush=True))
     torch.cuda.set_device(0)

@@ -19,8 +19,8 @@
  * one SET that holds the same tokens in the same slots; Kidx, pos, len, n_projected, the scores,
  * the keep / evict lists and (M, b) exist once per sequence (the H_kv axis below is dropped) and
  * K, V stay per unit.  Tokens enter through im_append_kv_hidden.  The step-by-step entry points and
- * im_decode_step serve both layouts; im_attend_step and im_decode_step_shared serve head_shared = 0
- * only.
+ * im_decode_step serve both layouts; im_attend_step has the twin im_attend_step_hidden;
+ * im_decode_step_shared serves head_shared = 0 only.
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers unless a comment says "host".  The caller owns all
@@ -232,6 +232,13 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
 int32_t im_attend_step(im_handle* h, const im_params* p, const im_state* st, const void* q,
                        const void* k_new, const void* v_new, const int32_t* pos_new, void* out,
                        float* readout_dbg, void* stream);
+
+/* The same for head_shared = 1: x_new [B, gate_in_dim] bf16 is the new token's hidden state, from
+ * which its indexer key is made on the way (Section 3.1 "Architecture": k_t = Norm(U_k X_t)).
+ * At most 16 KV heads, max_live <= 8193. */
+int32_t im_attend_step_hidden(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                              const void* x_new, const void* k_new, const void* v_new,
+                              const int32_t* pos_new, void* out, float* readout_dbg, void* stream);
 
 /* Index reuse across neighbouring layers (Appendix "From Running Mean to IndexCache": the indexer
  * runs once per group of layers and the other layers of the group reuse its decision).  The step

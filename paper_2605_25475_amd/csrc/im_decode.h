@@ -81,6 +81,8 @@ struct DecArgs {
   // head-shared layout (hs = 1): the H_set = H_kv units of a sequence form one set; len, pos, Kidx
   // (di = 16 values per row), nproj, M, bvec are indexed by the set u / H_set.  Else H_set = 1, di = 64.
   int hs, H_set, di;
+  int attend;         // head-shared layout, attend-only step: no query-side projections, no decision; the
+                      // new token's indexer key is stored by the tail
   float rms_eps, mem_eps, scale, lambda, eta;
 };
 
@@ -391,7 +393,7 @@ __global__ __launch_bounds__(256) void k_hs_prep(const DecArgs a) {
     dec_prep_memory(a, (blk - U) / DEC_MP, (blk - U) % DEC_MP);
     return;
   }
-  const int g = blk - (1 + DEC_MP) * U;
+  const int g = blk - (1 + DEC_MP) * U + (a.attend ? nU + nG : 0);   // an attend-only step has the U_k blocks alone
   const bool isq = g < nU, isg = !isq && g < nU + nG;
   const int n0 = (isq ? g : isg ? g - nU : g - nU - nG) * 2;
   const int N = isq ? Nq : isg ? a.H_idx : IM_DI_SHARED;
@@ -595,10 +597,10 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     // caller, or (head-shared layout) by the sequence's scoring workgroups.  The loads go out here and
     // are looked at once the wave's stream loads are in flight.
     if (tid < 4) {
-      if (a.hs) {
+      if (a.hs && !a.attend) {
 #pragma unroll
         for (int c = 0; c < HS_NSC; ++c) pk[c] = a.hs_part[(size_t)b * HS_NSC + c];
-      } else if (a.ext_evict) {
+      } else if (a.ext_evict && !a.hs) {
         ev_in = a.ext_evict[u];
       }
     }
@@ -821,9 +823,11 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       if (a.hs) {   // as hs_pick; the sequence's decision is handed to the tail per unit
         uint32_t bh = 0xffffffffu, bl = 0xffffffffu;
         int at = -1;
+        if (!a.attend) {
 #pragma unroll
-        for (int c = 0; c < HS_NSC; ++c)
-          if ((int)pk[c].z >= 0 && (pk[c].x < bh || (pk[c].x == bh && pk[c].y <= bl))) { bh = pk[c].x; bl = pk[c].y; at = (int)pk[c].z; }
+          for (int c = 0; c < HS_NSC; ++c)
+            if ((int)pk[c].z >= 0 && (pk[c].x < bh || (pk[c].x == bh && pk[c].y <= bl))) { bh = pk[c].x; bl = pk[c].y; at = (int)pk[c].z; }
+        }
         ev = (n > a.budget) ? at : -1;
         if (s == 0 && tid == 0) a.hs_evict[u] = ev;
       }
@@ -1519,6 +1523,17 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   float4 Mr[4] = {};
   float b_old = 0.f;
   const bool writer = j == 0 && lead;   // uniform per workgroup: it updates the memory state
+  if (a.attend && writer && tid >= 128 && tid < 128 + IM_DI_SHARED) {
+    // attend-only step of the head-shared layout: nothing scored the new token, so its indexer key
+    // Norm(U_k x) is stored here (one 16-lane row), at the slot the append used
+    const int dd = tid - 128, bq = u / a.H_kv;
+    const int n_old = a.len[su];
+    const double v = a.xk[(size_t)bq * IM_DI_SHARED + dd];
+    const double ss = row16_sum_d(v * v);
+    const double rr = sqrt(ss / (double)IM_DI_SHARED + (double)a.rms_eps);
+    const double wk = a.nkw ? (double)bf2f(a.nkw[dd]) : 1.0;
+    if (n_old + 1 <= a.C) a.Kidx[((size_t)su * a.C + n_old) * IM_DI_SHARED + dd] = d2bf_rne(v / rr * wk);
+  }
   if (writer) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);

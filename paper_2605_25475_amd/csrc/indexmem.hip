@@ -489,13 +489,14 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   IM_REQUIRE(state_ok(st), "state has a NULL pointer");
   IM_REQUIRE(q && k_new && v_new && pos_new && out, "an input / output pointer is NULL");
   IM_REQUIRE(no_score || (x_gate && q_pos), "x_gate / q_pos is NULL");
+  IM_REQUIRE(!h->cfg.head_shared || x_gate, "the new token's hidden state is NULL");
   IM_REQUIRE(budget >= h->cfg.n_sink + h->cfg.n_recent, "budget is below n_sink + n_recent");
   IM_REQUIRE(budget <= h->cfg.capacity, "budget exceeds capacity");
   IM_REQUIRE(lambda > 0.f && lambda <= 1.f, "lambda must be in (0, 1]");
   IM_REQUIRE(eta > 0.f, "eta must be > 0");
   const im_config& c = h->cfg;
   if (c.batch > 64) return set_err(h, IM_ERR_UNSUPPORTED, "%s: batch above 64", what);
-  if (c.head_shared && no_score)
+  if (c.head_shared && ext_evict)
     return set_err(h, IM_ERR_UNSUPPORTED, "%s: not built for head_shared = 1", what);
   if (c.head_shared && h->max_live > 64 * DEC_KEYS + 1)
     return set_err(h, IM_ERR_UNSUPPORTED, "%s: head_shared = 1 needs max_live <= %d", what, 64 * DEC_KEYS + 1);
@@ -533,14 +534,15 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
     a.hs_evict = words + 32;   // [units]
     a.ext_evict = a.hs_evict;
     if (c.n_kv_heads > 16) return set_err(h, IM_ERR_UNSUPPORTED, "%s: head_shared = 1 with more than 16 KV heads", what);
-    const int hs_prep_blocks = (1 + DEC_MP) * units + c.n_idx_heads * IM_DI_SHARED / 2 + (c.n_idx_heads + 1) / 2 +
-                               IM_DI_SHARED / 2;
+    a.attend = no_score ? 1 : 0;   // attend-only: U_k alone in the prep launch, no scoring launch
+    const int hs_prep_blocks = (1 + DEC_MP) * units + IM_DI_SHARED / 2 +
+                               (no_score ? 0 : c.n_idx_heads * IM_DI_SHARED / 2 + (c.n_idx_heads + 1) / 2);
     const int hs_main_blocks = units * (a.S > 0 ? a.S : 1);
     const bool hprof = h->prof_ev && h->prof_n < h->prof_max;
     hipEvent_t hev0 = hprof ? h->prof_ev[2 * h->prof_n] : nullptr, hev1 = hprof ? h->prof_ev[2 * h->prof_n + 1] : nullptr;
     if (hprof && h->prof_span != IM_PROFILE_MAIN) (void)hipEventRecord(hev0, s);
     k_hs_prep<<<hs_prep_blocks, 256, 0, s>>>(a);
-    k_hs_score<<<c.batch * HS_NSC, HS_ST, 0, s>>>(a);
+    if (!no_score) k_hs_score<<<c.batch * HS_NSC, HS_ST, 0, s>>>(a);
     if (hprof && h->prof_span == IM_PROFILE_MAIN) (void)hipEventRecord(hev0, s);
     if (hprof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(hev1, s);
 #define IM_HS_CASE(g)                                                                  \
@@ -601,8 +603,18 @@ int32_t im_attend_step(im_handle* h, const im_params* p, const im_state* st, con
                        float* readout_dbg, void* stream) {
   if (!h) return IM_ERR_INVALID_ARG;
   // budget = capacity: no unit can be above it, so nothing is evicted; lambda, eta are unused
+  if (h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_attend_step: head_shared = 1 takes im_attend_step_hidden");
   return decode_launch(h, p, st, q, nullptr, nullptr, k_new, v_new, pos_new, h->cfg.capacity, 1.f, 1.f, out,
                        readout_dbg, nullptr, nullptr, stream, true, nullptr, "im_attend_step");
+}
+
+int32_t im_attend_step_hidden(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                              const void* x_new, const void* k_new, const void* v_new,
+                              const int32_t* pos_new, void* out, float* readout_dbg, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  if (!h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_attend_step_hidden: head_shared = 0 takes im_attend_step");
+  return decode_launch(h, p, st, q, x_new, nullptr, k_new, v_new, pos_new, h->cfg.capacity, 1.f, 1.f, out,
+                       readout_dbg, nullptr, nullptr, stream, true, nullptr, "im_attend_step_hidden");
 }
 
 int32_t im_decode_step_shared(im_handle* h, const im_params* p, const im_state* st, const void* q,
@@ -611,6 +623,7 @@ int32_t im_decode_step_shared(im_handle* h, const im_params* p, const im_state* 
                               float* readout_dbg, void* stream) {
   if (!h) return IM_ERR_INVALID_ARG;
   IM_REQUIRE(evict_slot, "evict_slot is NULL");
+  if (h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_decode_step_shared: not built for head_shared = 1");
   return decode_launch(h, p, st, q, nullptr, nullptr, k_new, v_new, pos_new, h->cfg.capacity, lambda, eta, out,
                        readout_dbg, nullptr, nullptr, stream, true, evict_slot, "im_decode_step_shared");
 }

@@ -39,15 +39,23 @@ class Layer:
         B.im_decode_attn_with_readout(h, p, st, q_attn, self.out, self.readout)
         return self.out
 
-    def attend_step(self, k_new, v_new, pos_new, q_attn, fused=True, debug=True):
+    def attend_step(self, k_new, v_new, pos_new, q_attn, fused=True, debug=True, x_new=None):
         """One token of the periodic schedule (Section 4, setup: compress every tau steps): append,
         then attention + readout over everything cached; nothing is scored or evicted.  fused: the
-        three-launch entry point; else the two separate calls."""
-        if fused:
+        three-launch entry point; else the two separate calls.  x_new [B, 1, d_model]: the token's
+        hidden state (head-shared layout only)."""
+        hs = self.cfg.head_shared
+        if fused and hs:
+            B.im_attend_step_hidden(self.h, self.p, self.st, q_attn, x_new.view(self.cfg.batch, -1), k_new, v_new,
+                                    pos_new.view(-1), self.out, self.readout if debug else None)
+        elif fused:
             B.im_attend_step(self.h, self.p, self.st, q_attn, k_new, v_new, pos_new.view(-1), self.out,
                              self.readout if debug else None)
         else:
-            B.im_append_kv(self.h, self.st, k_new, v_new, pos_new)
+            if hs:
+                B.im_append_kv_hidden(self.h, self.p, self.st, k_new, v_new, x_new, pos_new)
+            else:
+                B.im_append_kv(self.h, self.st, k_new, v_new, pos_new)
             B.im_decode_attn_with_readout(self.h, self.p, self.st, q_attn, self.out, self.readout)
         return self.out
 

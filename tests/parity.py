@@ -278,11 +278,12 @@ class LockStepShared:
     eviction set and one memory per sequence): events through the step-by-step entry points.  The
     oracle follows a subset of the sequences, with all their KV heads."""
 
-    def __init__(self, w: Workload, layer: int = 0, device="cuda", gen_device="cpu", batch_ids=None):
+    def __init__(self, w: Workload, layer: int = 0, device="cuda", gen_device="cpu", batch_ids=None, capacity=None):
         assert w.head_shared
         self.w, self.dev = w, device
+        self.cap = cap = w.capacity if capacity is None else capacity
         p = layer_params(w, layer, gen_device)
-        cfg = im.Config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, capacity=w.capacity,
+        cfg = im.Config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, capacity=cap,
                         n_idx_heads=w.n_idx_heads, idx_dim=w.idx_dim, n_sink=w.n_sink, n_recent=w.n_recent,
                         fold_block=w.fold_block, head_shared=1,
                         max_queries=max(w.context if w.prefill_chunk is None else w.prefill_chunk, 1))
@@ -292,7 +293,7 @@ class LockStepShared:
                                 pd["norm_q_w"], pd["norm_k_w"])
         self.gpu = im.Layer(self.handle, self.params, device)
         self.batch_ids = list(range(w.batch)) if batch_ids is None else list(batch_ids)
-        self.ref = make_oracle_layer(w, layer, gen_device, batch=len(self.batch_ids))
+        self.ref = make_oracle_layer(w, layer, gen_device, batch=len(self.batch_ids), capacity=cap)
         self.K, self.V, self.Q = token_stream(w, layer, gen_device)
         self.X = hidden_stream(w, layer, gen_device)
 
@@ -332,7 +333,7 @@ class LockStepShared:
                             w.lam, w.eta)
         self.compare(*ref, tag, fused=True)
 
-    def compare(self, scores, keep, evict, out, res, tag, fused=False):
+    def compare(self, scores, keep, evict, out, res, tag, fused=False, lists=True, outputs=True):
         w, g, st = self.w, self.gpu, self.gpu.st
         G = w.group
         n_keep = g.n_keep.cpu().numpy(); n_evict = g.n_evict.cpu().numpy()
@@ -344,21 +345,22 @@ class LockStepShared:
         Mg = st.M.cpu().numpy().astype(np.float64); bg = st.b.cpu().numpy().astype(np.float64)
         for ib, b in enumerate(self.batch_ids):
             u = f"{tag} sequence {b}"
-            kr, er = keep[ib], evict[ib]
-            n_before = len(kr) + len(er)
-            s_ref = scores[ib, :n_before]; s_gpu = sc[b, :n_before].astype(np.float64)
-            same = (s_ref == s_gpu) | (np.isneginf(s_ref) & np.isneginf(s_gpu))
-            assert same.all(), (f"{u}: {int((~same).sum())} of {n_before} scores differ, max "
-                                f"{np.nanmax(np.abs(np.where(same, 0, s_ref - s_gpu))):.3e}")
-            if fused:
-                assert len(er) <= 1, u
-                want_e = int(er[0]) if len(er) else -1
-                got_e = int(g.evicted.cpu().numpy()[b])
-                assert got_e == want_e, f"{u}: evicted slot {got_e} != {want_e}"
-            else:
-                assert n_keep[b] == len(kr) and n_evict[b] == len(er), u
-                assert np.array_equal(keep_idx[b, :len(kr)], kr), f"{u}: keep list differs"
-                assert np.array_equal(evict_idx[b, :len(er)], er), f"{u}: evict list differs"
+            if lists:
+                kr, er = keep[ib], evict[ib]
+                n_before = len(kr) + len(er)
+                s_ref = scores[ib, :n_before]; s_gpu = sc[b, :n_before].astype(np.float64)
+                same = (s_ref == s_gpu) | (np.isneginf(s_ref) & np.isneginf(s_gpu))
+                assert same.all(), (f"{u}: {int((~same).sum())} of {n_before} scores differ, max "
+                                    f"{np.nanmax(np.abs(np.where(same, 0, s_ref - s_gpu))):.3e}")
+                if fused:
+                    assert len(er) <= 1, u
+                    want_e = int(er[0]) if len(er) else -1
+                    got_e = int(g.evicted.cpu().numpy()[b])
+                    assert got_e == want_e, f"{u}: evicted slot {got_e} != {want_e}"
+                else:
+                    assert n_keep[b] == len(kr) and n_evict[b] == len(er), u
+                    assert np.array_equal(keep_idx[b, :len(kr)], kr), f"{u}: keep list differs"
+                    assert np.array_equal(evict_idx[b, :len(er)], er), f"{u}: evict list differs"
             n = int(self.ref.len[ib])
             assert lens[b] == n and nproj[b] == n, u
             assert np.array_equal(pos[b, :n], self.ref.pos[ib, :n]), f"{u}: positions"
@@ -367,9 +369,45 @@ class LockStepShared:
             assert np.array_equal(f64(st.V[b, :, :n]), self.ref.V[ib, :, :n]), f"{u}: V rows"
             assert_state_close(u + " M", Mg[b], self.ref.M[ib])
             assert_state_close(u + " b", bg[b], self.ref.b[ib])
-            assert_out_close(u + " out", out_g[b], out[ib])
-            dmax = float(np.max(np.abs(res_g[b] - res[ib])))
-            assert dmax <= 1e-3 * float(np.max(np.abs(res[ib]))) + 1e-30, f"{u}: readout diff {dmax:.3e}"
+            if outputs:
+                assert_out_close(u + " out", out_g[b], out[ib])
+                dmax = float(np.max(np.abs(res_g[b] - res[ib])))
+                assert dmax <= 1e-3 * float(np.max(np.abs(res[ib]))) + 1e-30, f"{u}: readout diff {dmax:.3e}"
+
+    def window(self, t0: int, tau: int, budget: int, tag: str, fused=True):
+        """The paper's decode schedule (Section 4, setup): tau tokens are appended and attended to one
+        by one, then the interval's queries score the cache and it is cut back to `budget`."""
+        w, dev = self.w, self.dev
+        d = lambda x: x.to(dev)
+        bi_t = torch.tensor(self.batch_ids, device=self.K.device)
+        sel = lambda x: f64(x.index_select(0, bi_t))
+        bi = self.batch_ids
+        for t in range(t0, t0 + tau):
+            k_new = self.K[:, :, t:t + 1].contiguous(); v_new = self.V[:, :, t:t + 1].contiguous()
+            x_new = self.X[:, t:t + 1].contiguous(); q_attn = self.Q[:, t].contiguous()
+            pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+            self.gpu.attend_step(d(k_new), d(v_new), d(pos), d(q_attn), fused=fused, x_new=d(x_new))
+            torch.cuda.synchronize()
+            self.ref.append_kv_hidden(sel(k_new), sel(v_new), sel(x_new), pos.numpy()[bi])
+            out, res = self.ref.decode_attn_with_readout(sel(q_attn))
+            self.compare(None, None, None, out, res, f"{tag} attend@{t}", lists=False)
+        q_win = self.Q[:, t0:t0 + tau].contiguous(); x_win = self.X[:, t0:t0 + tau].contiguous()
+        posw = torch.arange(t0, t0 + tau, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+        self.gpu.compress(d(q_win), d(x_win), d(posw), budget, w.lam, w.eta)
+        torch.cuda.synchronize()
+        scores = self.ref.index_score(sel(q_win), sel(x_win), posw.numpy()[bi])
+        keep, evict = self.ref.topb_select(scores, budget)
+        self.ref.memory_update(evict, w.lam, w.eta)
+        self.ref.compact_kv(keep, evict)
+        self.compare(scores, keep, evict, None, None, f"{tag} compress@{t0 + tau}", outputs=False)
+
+    def run_window_schedule(self, tau: int, n_windows: int, fused=True):
+        w = self.w
+        self.event(0, w.context, w.budget, "prefill")
+        im.im_set_max_live(self.handle, min(self.cap, w.budget + tau))
+        for k in range(n_windows):
+            self.window(w.context + k * tau, tau, w.budget, f"window {k}", fused=fused)
+        assert im.im_query_status(self.handle) == 0
 
     def run_schedule(self, decode_steps=None, fused_decode=False):
         w = self.w
@@ -380,7 +418,7 @@ class LockStepShared:
         else:
             for c0 in range(0, L, w.prefill_chunk):
                 self.event(c0, min(L, c0 + w.prefill_chunk), w.budget, f"chunk@{c0}")
-        im.im_set_max_live(self.handle, min(w.capacity, w.budget + 1))
+        im.im_set_max_live(self.handle, min(self.cap, w.budget + 1))
         for t in range(L, L + steps):
             if fused_decode:
                 self.event_fused(t, w.budget, f"fused decode@{t}")

@@ -107,6 +107,7 @@ def test_calls_validate_before_enqueuing(lib):
     assert lib.im_attend_step(h, C.byref(pr), C.byref(st), None, X, X, X, X, None, None) == E
     assert lib.im_attend_step(h, C.byref(pr), C.byref(st_bad), X, X, X, X, X, None, None) == E
     assert lib.im_attend_step(h, C.byref(pr), C.byref(st), X, X, X, X, None, None, None) == E
+    assert lib.im_attend_step_hidden(h, C.byref(pr), C.byref(st), X, X, X, X, X, X, None, None) == im.IM_ERR_UNSUPPORTED   # per-head layout
     assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, X, X, None, 0.9, 0.5, X, None, None) == E
     assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, X, X, X, 1.5, 0.5, X, None, None) == E
     assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, None, X, X, 0.9, 0.5, X, None, None) == E
@@ -133,6 +134,7 @@ def test_head_shared_layout_validation(lib):
     assert lib.im_decode_step(h, C.byref(pr), C.byref(st), X, None, X, X, X, X, 64, 0.9, 0.5, X, None, None, None, None) == im.IM_ERR_INVALID_ARG
     assert lib.im_attend_step(h, C.byref(pr), C.byref(st), X, X, X, X, X, None, None) == U
     assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, X, X, X, 0.9, 0.5, X, None, None) == U
+    assert lib.im_attend_step_hidden(h, C.byref(pr), C.byref(st), X, None, X, X, X, X, None, None) == im.IM_ERR_INVALID_ARG
     assert lib.im_append_kv_hidden(h, C.byref(pr), C.byref(st), X, X, X, X, 0, None) == im.IM_ERR_INVALID_ARG
     assert b"head_shared" in lib.im_last_error(h) or b"n_new" in lib.im_last_error(h)
     lib.im_destroy(h)

@@ -263,6 +263,17 @@ def test_head_shared_layout_fused_decode(name, kw):
     LockStepShared(w).run_schedule(fused_decode=True)
 
 
+@pytest.mark.parametrize("name,kw,tau,n_win", [
+    ("cfg1", dict(context=600, budget=200, decode_steps=96), 32, 3),
+    ("cfg4", dict(batch=2, context=700, budget=130, decode_steps=128), 128, 1),      # the paper's tau
+    ("cfg1", dict(batch=2, context=500, budget=200, decode_steps=114), 57, 2),       # live bound 257: one key beyond the splits
+])
+@pytest.mark.parametrize("fused", [True, False])
+def test_head_shared_layout_periodic_schedule(name, kw, tau, n_win, fused):
+    w = WORKLOADS[name].shared(n_layers=1, **kw)
+    LockStepShared(w, capacity=max(w.context, w.budget + tau)).run_window_schedule(tau, n_win, fused=fused)
+
+
 def test_head_shared_layout_rejects_what_is_not_built_for_it():
     w = WORKLOADS["cfg1"].shared()
     ls = LockStepShared(w)
@@ -271,5 +282,7 @@ def test_head_shared_layout_rejects_what_is_not_built_for_it():
     k = d(ls.K[:, :, :1].contiguous()); q = d(ls.Q[:, 0].contiguous()); pos = torch.zeros(w.batch, dtype=torch.int32).cuda()
     with pytest.raises(im.IndexMemError):
         im.im_attend_step(ls.handle, ls.params, g.st, q, k, k, pos, g.out)
+    with pytest.raises(im.IndexMemError):
+        im.im_decode_step_shared(ls.handle, ls.params, g.st, q, k, k, pos, pos, 0.9, 0.5, g.out)
     with pytest.raises(im.IndexMemError):
         im.im_append_kv(ls.handle, g.st, k, k, pos.view(-1, 1))
