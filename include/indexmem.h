@@ -129,7 +129,12 @@ int32_t im_query_status(im_handle* h, int32_t* status_host, void* stream);
 /* Helper: new tokens enter the cache.  Copies k_new, v_new [B, H_kv, n_new, d_head] (bf16) to
  * slots [len, len + n_new) of every unit, pos_new [B, n_new] to their positions, and adds n_new
  * to len.  A unit with len + n_new > capacity is left unchanged and IM_STATUS_APPEND_OVERFLOW is
- * set.  1 <= n_new <= capacity. */
+ * set.  1 <= n_new <= capacity.
+ * k_new = v_new = NULL: the rows are already in place in slots [len, len + n_new) of K and V (the
+ * state's K / V may be the very buffers a prompt's K / V projections were written to); only the
+ * positions and lengths follow.  This is how a prompt is evicted BEFORE it is cached (Section 3.1,
+ * "pre-eviction"): run the step on such a state of capacity L, then copy the first n_keep slots of
+ * its arrays to the budget-sized state that decoding uses. */
 int32_t im_append_kv(im_handle* h, const im_state* st, const void* k_new, const void* v_new,
                      const int32_t* pos_new, int32_t n_new, void* stream);
 

@@ -226,13 +226,13 @@ def im_query_status(h: Handle) -> int:
 
 
 def im_append_kv(h: Handle, st: State, k_new, v_new, pos_new) -> None:
-    n_new = k_new.shape[2]
+    n_new = pos_new.shape[1]   # (k_new = v_new = None: the rows are already in place)
     h.check(h.lib.im_append_kv(h.h, C.byref(st.c), _ptr(k_new), _ptr(v_new), _ptr(pos_new), n_new,
                                _stream()))
 
 
 def im_append_kv_hidden(h: Handle, p: Params, st: State, k_new, v_new, x_new, pos_new) -> None:
-    n_new = k_new.shape[2]
+    n_new = pos_new.shape[1]
     h.check(h.lib.im_append_kv_hidden(h.h, C.byref(p.c), C.byref(st.c), _ptr(k_new), _ptr(v_new), _ptr(x_new),
                                       _ptr(pos_new), n_new, _stream()))
 

@@ -31,10 +31,12 @@ __global__ __launch_bounds__(256) void k_append_rows(bf16_t* __restrict__ K, bf1
   if (row >= n_new) return;
   const int n = len[set];
   if (n + n_new > C) return;  // dropped; k_append_len raises the status bit
-  const size_t src = ((size_t)unit * n_new + row) * IM_D + ch * 8;
-  const size_t dst = ((size_t)unit * C + n + row) * IM_D + ch * 8;
-  *(uint4*)(K + dst) = *(const uint4*)(k_new + src);
-  *(uint4*)(V + dst) = *(const uint4*)(v_new + src);
+  if (k_new) {   // (NULL: the rows are already in place, only positions and lengths follow)
+    const size_t src = ((size_t)unit * n_new + row) * IM_D + ch * 8;
+    const size_t dst = ((size_t)unit * C + n + row) * IM_D + ch * 8;
+    *(uint4*)(K + dst) = *(const uint4*)(k_new + src);
+    *(uint4*)(V + dst) = *(const uint4*)(v_new + src);
+  }
   if (ch == 0 && unit % H_set == 0) pos[(size_t)set * C + n + row] = pos_new[(size_t)(unit / H_kv) * n_new + row];
 }
 

@@ -273,7 +273,7 @@ int32_t im_append_kv(im_handle* h, const im_state* st, const void* k_new, const 
                      const int32_t* pos_new, int32_t n_new, void* stream) {
   if (!h) return IM_ERR_INVALID_ARG;
   IM_REQUIRE(state_ok(st), "state has a NULL pointer");
-  IM_REQUIRE(k_new && v_new && pos_new, "k_new / v_new / pos_new is NULL");
+  IM_REQUIRE(pos_new && ((k_new && v_new) || (!k_new && !v_new)), "pos_new is NULL, or only one of k_new / v_new is");
   IM_REQUIRE(n_new >= 1 && n_new <= h->cfg.capacity, "n_new must be in 1..capacity");
   if (h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_append_kv: head_shared = 1 takes im_append_kv_hidden");
   hipStream_t s = (hipStream_t)stream;
@@ -295,7 +295,8 @@ int32_t im_append_kv_hidden(im_handle* h, const im_params* p, const im_state* st
   if (!h) return IM_ERR_INVALID_ARG;
   IM_REQUIRE(params_ok(p), "params has a NULL pointer");
   IM_REQUIRE(state_ok(st), "state has a NULL pointer");
-  IM_REQUIRE(k_new && v_new && x_new && pos_new, "k_new / v_new / x_new / pos_new is NULL");
+  IM_REQUIRE(x_new && pos_new && ((k_new && v_new) || (!k_new && !v_new)),
+             "x_new / pos_new is NULL, or only one of k_new / v_new is");
   IM_REQUIRE(n_new >= 1 && n_new <= h->cfg.capacity, "n_new must be in 1..capacity");
   if (!h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_append_kv_hidden: head_shared = 0 takes im_append_kv");
   hipStream_t s = (hipStream_t)stream;

@@ -37,7 +37,7 @@ class LockStep:
     """One layer on the GPU and in the oracle, fed the same events."""
 
     def __init__(self, w: Workload, layer: int = 0, capacity=None, max_queries=None, device="cuda",
-                 gen_device="cpu", kv_heads=None, batch_ids=None):
+                 gen_device="cpu", kv_heads=None, batch_ids=None, ref_capacity=None):
         self.w = w
         self.dev = device
         cap = w.capacity if capacity is None else capacity
@@ -55,7 +55,7 @@ class LockStep:
         # the oracle may follow a subset of units (all by default)
         self.batch_ids = list(range(w.batch)) if batch_ids is None else list(batch_ids)
         self.kv_heads = list(range(w.n_kv_heads)) if kv_heads is None else list(kv_heads)
-        self.ref = make_oracle_layer(w, layer, gen_device, capacity=cap, batch=len(self.batch_ids),
+        self.ref = make_oracle_layer(w, layer, gen_device, capacity=ref_capacity or cap, batch=len(self.batch_ids),
                                      kv_head_ids=self.kv_heads)
         self.K, self.V, self.Q = token_stream(w, layer, gen_device)
 

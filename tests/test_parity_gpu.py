@@ -286,3 +286,50 @@ def test_head_shared_layout_rejects_what_is_not_built_for_it():
         im.im_decode_step_shared(ls.handle, ls.params, g.st, q, k, k, pos, pos, 0.9, 0.5, g.out)
     with pytest.raises(im.IndexMemError):
         im.im_append_kv(ls.handle, g.st, k, k, pos.view(-1, 1))
+
+
+def test_pre_eviction_prompt_buffers_in_place_then_a_budget_sized_cache():
+    # Section 3.1 ("pre-eviction": cache only the selected KV).  The prompt's K / V sit in buffers of
+    # their own, as a model's projections leave them; a state of capacity L adopts them in place
+    # (im_append_kv with no rows), the step runs on it, and only the kept slots are copied to the
+    # cache that decoding uses, which holds budget + 2 entries.  The oracle takes the ordinary path.
+    w = WORKLOADS["cfg3"].scaled(n_layers=1, batch=2, context=1500, budget=333, decode_steps=4)
+    L = w.context
+    ls = LockStep(w, capacity=w.budget + 2, ref_capacity=L, max_queries=L)
+    big_h = im.Handle(im.Config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, capacity=L,
+                                n_idx_heads=w.n_idx_heads, n_sink=w.n_sink, fold_block=w.fold_block, max_queries=L))
+    big = im.Layer(big_h, ls.params)
+    d = lambda t: t.cuda()
+    big.st.K[:, :, :L] = d(ls.K[:, :, :L]); big.st.V[:, :, :L] = d(ls.V[:, :, :L])     # "written by the projections"
+    pos = torch.arange(L, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+    q = d(ls.Q[:, :L].contiguous())
+    im.im_append_kv(big_h, big.st, None, None, d(pos))
+    big.compress(q, q.view(w.batch, L, -1), d(pos), w.budget, w.lam, w.eta)
+    torch.cuda.synchronize()
+    assert im.im_query_status(big_h) == 0
+    n = w.budget
+    assert (big.st.len == n).all()
+    small = ls.gpu.st
+    for name in ("K", "V", "Kidx", "pos"):
+        getattr(small, name)[:, :, :n] = getattr(big.st, name)[:, :, :n]
+    for name in ("len", "n_projected", "M", "b"):
+        getattr(small, name).copy_(getattr(big.st, name))
+    for name in ("scores", "keep_idx", "evict_idx"):
+        getattr(ls.gpu, name)[:, :, :w.budget + 2] = getattr(big, name)[:, :, :w.budget + 2]
+    # the oracle's ordinary prefill event; everything the cache holds must match it
+    f = lambda t: t.to(torch.float64).numpy()
+    qn = f(ls.Q[:, :L])
+    ls.ref.append_kv(f(ls.K[:, :, :L]), f(ls.V[:, :, :L]), pos.numpy())
+    scores = ls.ref.index_score(qn, qn.reshape(w.batch, L, -1), pos.numpy())
+    keep, evict = ls.ref.topb_select(scores, w.budget)
+    ls.ref.memory_update(evict, w.lam, w.eta)
+    ls.ref.compact_kv(keep, evict)
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            assert np.array_equal(big.keep_idx[b, h, :n].cpu().numpy(), keep[b][h])
+            assert np.array_equal(big.evict_idx[b, h, :L - n].cpu().numpy(), evict[b][h])
+    ls.compare(None, None, None, None, None, "adopted cache", lists=False, outputs=False)
+    im.im_set_max_live(ls.handle, w.budget + 1)
+    for t in range(L, L + w.decode_steps):
+        ls.event_fused(t, w.budget, f"fused decode@{t}")
+    assert im.im_query_status(ls.handle) == 0
