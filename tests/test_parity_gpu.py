@@ -188,32 +188,40 @@ def test_append_overflow_sets_status_and_leaves_state():
     assert im.im_query_status(h) == 0
 
 
-def test_decode_step_in_a_hip_graph_matches_eager_replay_by_replay():
+@pytest.mark.parametrize("shared", [False, True])
+def test_decode_step_in_a_hip_graph_matches_eager_replay_by_replay(shared):
     # the benchmark replays decode steps from HIP graphs: a captured step, replayed with fresh
     # inputs copied into its static buffers, must leave the same state and output as the same step
-    # launched eagerly on a twin layer
-    w = WORKLOADS["cfg1"].scaled(context=700, budget=256, decode_steps=8)
-    twins = [LockStep(w) for _ in range(2)]
+    # launched eagerly on a twin layer (both layouts)
+    w = WORKLOADS["cfg1"].scaled(batch=2, context=700, budget=256, decode_steps=8)
+    if shared:
+        w = w.shared()
+    twins = [(LockStepShared if shared else LockStep)(w) for _ in range(2)]
     for ls in twins:
-        ls.event(0, w.context, w.budget, "prefill", check=False)
+        if shared:
+            ls.event(0, w.context, w.budget, "prefill")
+        else:
+            ls.event(0, w.context, w.budget, "prefill", check=False)
         im.im_set_max_live(ls.handle, w.budget + 1)
     g_ls, e_ls = twins
     dev = "cuda"
     k_s = torch.empty((w.batch, w.n_kv_heads, 1, 128), dtype=torch.bfloat16, device=dev)
     v_s = torch.empty_like(k_s)
     q_s = torch.empty((w.batch, w.n_q_heads, 128), dtype=torch.bfloat16, device=dev)
+    x_s = torch.empty((w.batch, w.gate_in_dim), dtype=torch.bfloat16, device=dev)
     p_s = torch.empty((w.batch,), dtype=torch.int32, device=dev)
 
     def load(t):
         k_s.copy_(g_ls.K[:, :, t:t + 1]); v_s.copy_(g_ls.V[:, :, t:t + 1]); q_s.copy_(g_ls.Q[:, t])
+        x_s.copy_(g_ls.X[:, t] if shared else g_ls.Q[:, t].reshape(w.batch, -1))
         p_s.fill_(t)
 
     def step(ls):
-        ls.gpu.decode_step(k_s, v_s, p_s, q_s, q_s.view(w.batch, -1), p_s, w.budget, w.lam, w.eta, debug=True)
+        ls.gpu.decode_step(k_s, v_s, p_s, q_s, x_s, p_s, w.budget, w.lam, w.eta, debug=True)
 
     load(w.context)
     graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph):   # capture records the three launches; nothing runs yet
+    with torch.cuda.graph(graph):   # capture records the launches; nothing runs yet
         step(g_ls)
     for t in range(w.context, w.context + 6):
         load(t)
