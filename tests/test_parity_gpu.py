@@ -341,3 +341,17 @@ def test_pre_eviction_prompt_buffers_in_place_then_a_budget_sized_cache():
     for t in range(L, L + w.decode_steps):
         ls.event_fused(t, w.budget, f"fused decode@{t}")
     assert im.im_query_status(ls.handle) == 0
+
+
+@pytest.mark.parametrize("shared", [False, True])
+def test_fused_decode_from_an_empty_cache(shared):
+    # no prompt at all: the cache grows one token per step through the fused entry point, reaches the
+    # budget and starts evicting (sinks included in the budget)
+    w = WORKLOADS["cfg1"].scaled(batch=2, context=0, budget=9, decode_steps=24)
+    if shared:
+        w = w.shared()
+    ls = (LockStepShared(w, capacity=16) if shared else LockStep(w, capacity=16, max_queries=1))
+    im.im_set_max_live(ls.handle, w.budget + 1)
+    for t in range(w.decode_steps):
+        ls.event_fused(t, w.budget, f"fused decode@{t}")
+    assert im.im_query_status(ls.handle) == 0
