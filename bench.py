@@ -103,7 +103,11 @@ class Job:
                 c1 = min(L, c0 + chunk)
                 pos = torch.arange(c0, c1, dtype=torch.int32, device=device).repeat(w.batch, 1).contiguous()
                 q = Q[:, c0:c1].contiguous()
-                if w.head_shared:
+                if w.head_shared and li % share:
+                    layer.follow_event(K[:, :, c0:c1].contiguous(), V[:, :, c0:c1].contiguous(), pos,
+                                       Q[:, c1 - 1].contiguous(), self.layers[li - li % share], w.lam, w.eta,
+                                       x_new=X[:, c0:c1].contiguous())
+                elif w.head_shared:
                     x = X[:, c0:c1].contiguous()
                     layer.step(K[:, :, c0:c1].contiguous(), V[:, :, c0:c1].contiguous(), pos, q, x, pos,
                                Q[:, c1 - 1].contiguous(), w.budget, w.lam, w.eta, x_new=x)
@@ -146,9 +150,13 @@ class Job:
             q = qd[s]
             if w.head_shared:
                 x = self.xdec[li][s]
-                if path == "fused":
+                if path == "shared" and li % self.share:
+                    layer.follow_step(kd[s], vd[s], pos.view(w.batch), q.view(w.batch, w.n_q_heads, -1),
+                                      self.layers[li - li % self.share].evicted, w.lam, w.eta, x_new=x)
+                elif path in ("fused", "shared"):
                     layer.decode_step(kd[s], vd[s], pos.view(w.batch), q.view(w.batch, w.n_q_heads, -1),
-                                      x.view(w.batch, -1), pos.view(w.batch), w.budget, w.lam, w.eta)
+                                      x.view(w.batch, -1), pos.view(w.batch), w.budget, w.lam, w.eta,
+                                      want_evicted=(path == "shared"))
                 elif path == "periodic":
                     layer.attend_step(kd[s], vd[s], pos, q.view(w.batch, w.n_q_heads, -1), debug=False, x_new=x)
                 else:
@@ -256,7 +264,7 @@ def main() -> None:
                          "of a group scores and selects, the others apply its decision)")
     ap.add_argument("--head-shared", action="store_true",
                     help="the workload's cache shape in the head-shared layout (indexer keys of 16 values from "
-                         "hidden states, one eviction set and one memory per sequence); paths fused, steps and periodic")
+                         "hidden states, one eviction set and one memory per sequence)")
     ap.add_argument("--share", type=int, default=4, help="layers per index-sharing group of --path shared")
     ap.add_argument("--tau", type=int, default=128, help="compression interval of --path periodic")
     ap.add_argument("--no-graph", action="store_true", help="launch the fused path eagerly")
@@ -273,8 +281,7 @@ def main() -> None:
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     w = WORKLOADS[a.workload]
     if a.head_shared:
-        if a.path not in ("fused", "steps", "periodic"):
-            sys.exit("bench.py: --head-shared runs with --path fused, steps or periodic")
+        pass
         w = w.shared()
     log = (lambda s: None) if a.quiet else (lambda s: print("[bench] " + s, file=sys.stderr, flush=True))
     torch.cuda.set_device(0)

@@ -19,8 +19,8 @@
  * one SET that holds the same tokens in the same slots; Kidx, pos, len, n_projected, the scores,
  * the keep / evict lists and (M, b) exist once per sequence (the H_kv axis below is dropped) and
  * K, V stay per unit.  Tokens enter through im_append_kv_hidden.  The step-by-step entry points and
- * im_decode_step serve both layouts; im_attend_step has the twin im_attend_step_hidden;
- * im_decode_step_shared serves head_shared = 0 only.
+ * im_decode_step serve both layouts; im_attend_step and im_decode_step_shared have the twins
+ * im_attend_step_hidden and im_decode_step_shared_hidden.
  *
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers unless a comment says "host".  The caller owns all
@@ -259,6 +259,14 @@ int32_t im_decode_step_shared(im_handle* h, const im_params* p, const im_state* 
                               const void* k_new, const void* v_new, const int32_t* pos_new,
                               const int32_t* evict_slot, float lambda, float eta, void* out,
                               float* readout_dbg, void* stream);
+
+/* The same for head_shared = 1: evict_slot is [B] (one slot per sequence, as im_decode_step reports it
+ * in this layout), x_new [B, gate_in_dim] the new token's hidden state (its indexer key is made and
+ * stored as in im_attend_step_hidden, so that the follower's Kidx stays consistent). */
+int32_t im_decode_step_shared_hidden(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                                     const void* x_new, const void* k_new, const void* v_new,
+                                     const int32_t* pos_new, const int32_t* evict_slot, float lambda,
+                                     float eta, void* out, float* readout_dbg, void* stream);
 
 /* Kernel timing for benchmarks (not part of the method).  After im_profile_start, every
  * im_decode_step on this handle brackets part of its launch sequence (prep kernel, main kernel,

@@ -83,6 +83,8 @@ struct DecArgs {
   int hs, H_set, di;
   int attend;         // head-shared layout, attend-only step: no query-side projections, no decision; the
                       // new token's indexer key is stored by the tail
+  const int32_t* hs_named;   // head-shared layout, optional [B]: with attend = 1, the slot each sequence
+                             // evicts is given by the caller (-1 or >= len: none)
   float rms_eps, mem_eps, scale, lambda, eta;
 };
 
@@ -600,6 +602,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       if (a.hs && !a.attend) {
 #pragma unroll
         for (int c = 0; c < HS_NSC; ++c) pk[c] = a.hs_part[(size_t)b * HS_NSC + c];
+      } else if (a.hs && a.hs_named) {
+        ev_in = a.hs_named[b];
       } else if (a.ext_evict && !a.hs) {
         ev_in = a.ext_evict[u];
       }
@@ -828,7 +832,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
           for (int c = 0; c < HS_NSC; ++c)
             if ((int)pk[c].z >= 0 && (pk[c].x < bh || (pk[c].x == bh && pk[c].y <= bl))) { bh = pk[c].x; bl = pk[c].y; at = (int)pk[c].z; }
         }
-        ev = (n > a.budget) ? at : -1;
+        ev = a.hs_named ? ev_in : (n > a.budget) ? at : -1;
         if (s == 0 && tid == 0) a.hs_evict[u] = ev;
       }
       const int fl = ev - k0;
@@ -1523,16 +1527,18 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   float4 Mr[4] = {};
   float b_old = 0.f;
   const bool writer = j == 0 && lead;   // uniform per workgroup: it updates the memory state
-  if (a.attend && writer && tid >= 128 && tid < 128 + IM_DI_SHARED) {
-    // attend-only step of the head-shared layout: nothing scored the new token, so its indexer key
-    // Norm(U_k x) is stored here (one 16-lane row), at the slot the append used
+  // attend-only / follower step of the head-shared layout: nothing scored the new token, so its
+  // indexer key Norm(U_k x) is made here (one 16-lane row of the writer workgroup) and stored at the
+  // end, where the token's final slot is known
+  bf16_t new_key = 0;
+  const bool new_fits = a.attend && writer && a.len[su] + 1 <= a.C;   // the append took place
+  if (new_fits && tid >= 128 && tid < 128 + IM_DI_SHARED) {
     const int dd = tid - 128, bq = u / a.H_kv;
-    const int n_old = a.len[su];
     const double v = a.xk[(size_t)bq * IM_DI_SHARED + dd];
     const double ss = row16_sum_d(v * v);
     const double rr = sqrt(ss / (double)IM_DI_SHARED + (double)a.rms_eps);
     const double wk = a.nkw ? (double)bf2f(a.nkw[dd]) : 1.0;
-    if (n_old + 1 <= a.C) a.Kidx[((size_t)su * a.C + n_old) * IM_DI_SHARED + dd] = d2bf_rne(v / rr * wk);
+    new_key = d2bf_rne(v / rr * wk);
   }
   if (writer) {
 #pragma unroll
@@ -1741,8 +1747,13 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     const size_t dst = (size_t)u * a.C + e_slot, idst = (size_t)su * a.C + e_slot;
     if (tid < 16) *(uint4*)(a.K + dst * IM_D + tid * 8) = mv;
     else if (tid < 32) *(uint4*)(a.V + dst * IM_D + (tid - 16) * 8) = mv;
-    else if (tid < 32 + a.di / 8) { if (lead) *(uint4*)(a.Kidx + idst * a.di + (tid - 32) * 8) = mv; }
+    else if (tid < 32 + a.di / 8) { if (lead && !new_fits) *(uint4*)(a.Kidx + idst * a.di + (tid - 32) * 8) = mv; }
     else if (tid == 40 && lead) a.pos[idst] = mvpos;
+  }
+  if (new_fits && tid >= 128 && tid < 128 + IM_DI_SHARED) {
+    // the new token sits in the last live slot n - 1, unless that entry has just moved into the hole
+    const int at = (e_slot >= 0 && e_slot < n_keep) ? e_slot : n - 1;
+    if (!(e_slot == n - 1)) a.Kidx[((size_t)su * a.C + at) * IM_DI_SHARED + (tid - 128)] = new_key;
   }
   if (tid == 0 && lead) {
     a.len[su] = n_keep;

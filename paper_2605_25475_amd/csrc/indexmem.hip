@@ -497,8 +497,6 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   IM_REQUIRE(eta > 0.f, "eta must be > 0");
   const im_config& c = h->cfg;
   if (c.batch > 64) return set_err(h, IM_ERR_UNSUPPORTED, "%s: batch above 64", what);
-  if (c.head_shared && ext_evict)
-    return set_err(h, IM_ERR_UNSUPPORTED, "%s: not built for head_shared = 1", what);
   if (c.head_shared && h->max_live > 64 * DEC_KEYS + 1)
     return set_err(h, IM_ERR_UNSUPPORTED, "%s: head_shared = 1 needs max_live <= %d", what, 64 * DEC_KEYS + 1);
   hipStream_t s = (hipStream_t)stream;
@@ -533,6 +531,7 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
     // attention partials with that slot named; the per-(unit, head) tail
     a.hs_part = (uint4*)(h->ws + h->off_hspart);
     a.hs_evict = words + 32;   // [units]
+    a.hs_named = ext_evict;    // a follower step: one slot per sequence from the caller
     a.ext_evict = a.hs_evict;
     if (c.n_kv_heads > 16) return set_err(h, IM_ERR_UNSUPPORTED, "%s: head_shared = 1 with more than 16 KV heads", what);
     a.attend = no_score ? 1 : 0;   // attend-only: U_k alone in the prep launch, no scoring launch
@@ -624,9 +623,20 @@ int32_t im_decode_step_shared(im_handle* h, const im_params* p, const im_state* 
                               float* readout_dbg, void* stream) {
   if (!h) return IM_ERR_INVALID_ARG;
   IM_REQUIRE(evict_slot, "evict_slot is NULL");
-  if (h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_decode_step_shared: not built for head_shared = 1");
+  if (h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_decode_step_shared: head_shared = 1 takes im_decode_step_shared_hidden");
   return decode_launch(h, p, st, q, nullptr, nullptr, k_new, v_new, pos_new, h->cfg.capacity, lambda, eta, out,
                        readout_dbg, nullptr, nullptr, stream, true, evict_slot, "im_decode_step_shared");
+}
+
+int32_t im_decode_step_shared_hidden(im_handle* h, const im_params* p, const im_state* st, const void* q,
+                                     const void* x_new, const void* k_new, const void* v_new,
+                                     const int32_t* pos_new, const int32_t* evict_slot, float lambda,
+                                     float eta, void* out, float* readout_dbg, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(evict_slot, "evict_slot is NULL");
+  if (!h->cfg.head_shared) return set_err(h, IM_ERR_UNSUPPORTED, "im_decode_step_shared_hidden: head_shared = 0 takes im_decode_step_shared");
+  return decode_launch(h, p, st, q, x_new, nullptr, k_new, v_new, pos_new, h->cfg.capacity, lambda, eta, out,
+                       readout_dbg, nullptr, nullptr, stream, true, evict_slot, "im_decode_step_shared_hidden");
 }
 
 }  // extern "C"

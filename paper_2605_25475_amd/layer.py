@@ -68,21 +68,28 @@ class Layer:
         B.im_memory_update(h, p, st, self.evict_idx, self.n_evict, lam, eta)
         B.im_compact_kv(h, st, self.keep_idx, self.n_keep, self.evict_idx, self.n_evict)
 
-    def follow_event(self, k_new, v_new, pos_new, q_attn, leader: "Layer", lam, eta):
+    def follow_event(self, k_new, v_new, pos_new, q_attn, leader: "Layer", lam, eta, x_new=None):
         """An eviction event of a follower layer of an index-sharing group: the leader's keep / evict
         lists are applied to this layer's cache (same slot layout), nothing is scored here (a follower
-        keeps no indexer keys: its Kidx rows are moved along but never read)."""
+        keeps no indexer keys of its own use: its Kidx rows are moved along but never read)."""
         h, p, st = self.h, self.p, self.st
-        B.im_append_kv(h, st, k_new, v_new, pos_new)
+        if self.cfg.head_shared:
+            B.im_append_kv_hidden(h, p, st, k_new, v_new, x_new, pos_new)
+        else:
+            B.im_append_kv(h, st, k_new, v_new, pos_new)
         B.im_memory_update(h, p, st, leader.evict_idx, leader.n_evict, lam, eta)
         B.im_compact_kv(h, st, leader.keep_idx, leader.n_keep, leader.evict_idx, leader.n_evict)
         B.im_decode_attn_with_readout(h, p, st, q_attn, self.out, self.readout)
         return self.out
 
-    def follow_step(self, k_new, v_new, pos_new, q, evict_slot, lam, eta, debug=False):
+    def follow_step(self, k_new, v_new, pos_new, q, evict_slot, lam, eta, debug=False, x_new=None):
         """One decode token of a follower layer: the slot its leader evicted leaves here too."""
-        B.im_decode_step_shared(self.h, self.p, self.st, q, k_new, v_new, pos_new, evict_slot, lam, eta,
-                                self.out, self.readout if debug else None)
+        if self.cfg.head_shared:
+            B.im_decode_step_shared_hidden(self.h, self.p, self.st, q, x_new.view(self.cfg.batch, -1), k_new, v_new,
+                                           pos_new, evict_slot, lam, eta, self.out, self.readout if debug else None)
+        else:
+            B.im_decode_step_shared(self.h, self.p, self.st, q, k_new, v_new, pos_new, evict_slot, lam, eta,
+                                    self.out, self.readout if debug else None)
         return self.out
 
     def decode_step(self, k_new, v_new, pos_new, q, x_gate, q_pos, budget, lam, eta, debug=False,

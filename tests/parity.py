@@ -313,6 +313,7 @@ class LockStepShared:
         xn = sel(x_new)
         ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn, posn, sel(q_attn), budget, w.lam, w.eta)
         self.compare(*ref, tag)
+        return ref
 
     def event_fused(self, t: int, budget: int, tag: str):
         """One decode token through im_decode_step (four launches in this layout)."""
@@ -332,6 +333,39 @@ class LockStepShared:
         ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn, posn, sel(q_new)[:, 0], budget,
                             w.lam, w.eta)
         self.compare(*ref, tag, fused=True)
+        return ref
+
+    # -- a follower layer of an index-sharing group (Appendix, IndexCache-style reuse) -------------
+    def _follow(self, k_new, v_new, x_new, pos, q_attn, evict, tag):
+        bi_t = torch.tensor(self.batch_ids)
+        sel = lambda x: f64(x.index_select(0, bi_t))
+        self.ref.append_kv_hidden(sel(k_new), sel(v_new), sel(x_new), pos.numpy()[self.batch_ids])
+        keep = [np.setdiff1d(np.arange(int(self.ref.len[ib])), evict[ib]).astype(np.int64)
+                for ib in range(len(self.batch_ids))]
+        self.ref.memory_update(evict, self.w.lam, self.w.eta)
+        self.ref.compact_kv(keep, evict)
+        out, res = self.ref.decode_attn_with_readout(sel(q_attn))
+        self.compare(None, None, None, out, res, tag, lists=False)
+
+    def follow_event(self, t0: int, t1: int, leader: "LockStepShared", evict, tag: str):
+        w, d = self.w, (lambda x: x.to(self.dev))
+        k_new = self.K[:, :, t0:t1].contiguous(); v_new = self.V[:, :, t0:t1].contiguous()
+        x_new = self.X[:, t0:t1].contiguous()
+        pos = torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+        q_attn = self.Q[:, t1 - 1].contiguous()
+        self.gpu.follow_event(d(k_new), d(v_new), d(pos), d(q_attn), leader.gpu, w.lam, w.eta, x_new=d(x_new))
+        torch.cuda.synchronize()
+        self._follow(k_new, v_new, x_new, pos, q_attn, evict, tag)
+
+    def follow_step(self, t: int, leader: "LockStepShared", evict, tag: str):
+        w, d = self.w, (lambda x: x.to(self.dev))
+        k_new = self.K[:, :, t:t + 1].contiguous(); v_new = self.V[:, :, t:t + 1].contiguous()
+        x_new = self.X[:, t:t + 1].contiguous(); q = self.Q[:, t].contiguous()
+        pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+        self.gpu.follow_step(d(k_new), d(v_new), d(pos).view(-1), d(q), leader.gpu.evicted, w.lam, w.eta, debug=True,
+                             x_new=d(x_new))
+        torch.cuda.synchronize()
+        self._follow(k_new, v_new, x_new, pos, q, evict, tag)
 
     def compare(self, scores, keep, evict, out, res, tag, fused=False, lists=True, outputs=True):
         w, g, st = self.w, self.gpu, self.gpu.st

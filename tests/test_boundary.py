@@ -135,6 +135,8 @@ def test_head_shared_layout_validation(lib):
     assert lib.im_attend_step(h, C.byref(pr), C.byref(st), X, X, X, X, X, None, None) == U
     assert lib.im_decode_step_shared(h, C.byref(pr), C.byref(st), X, X, X, X, X, 0.9, 0.5, X, None, None) == U
     assert lib.im_attend_step_hidden(h, C.byref(pr), C.byref(st), X, None, X, X, X, X, None, None) == im.IM_ERR_INVALID_ARG
+    assert lib.im_decode_step_shared_hidden(h, C.byref(pr), C.byref(st), X, X, X, X, X, None, 0.9, 0.5, X, None, None) == im.IM_ERR_INVALID_ARG
+    assert lib.im_decode_step_shared_hidden(h, C.byref(pr), C.byref(st), X, X, X, X, X, X, 1.5, 0.5, X, None, None) == im.IM_ERR_INVALID_ARG
     assert lib.im_append_kv_hidden(h, C.byref(pr), C.byref(st), X, X, X, X, 0, None) == im.IM_ERR_INVALID_ARG
     assert b"head_shared" in lib.im_last_error(h) or b"n_new" in lib.im_last_error(h)
     lib.im_destroy(h)

@@ -94,6 +94,24 @@ def test_index_reuse_across_layers(name, kw):
     assert im.im_query_status(lead.handle) == 0 and im.im_query_status(foll.handle) == 0
 
 
+@pytest.mark.parametrize("name,kw", [
+    ("cfg1", dict(batch=2, context=700, budget=256, decode_steps=6)),
+    ("cfg4", dict(batch=2, context=600, budget=130, decode_steps=5)),     # 7 query heads per KV head
+])
+def test_index_reuse_across_layers_head_shared_layout(name, kw):
+    w = WORKLOADS[name].shared(n_layers=2, **kw)
+    cap = max(w.capacity, w.budget + 2)
+    lead, foll = LockStepShared(w, layer=0, capacity=cap), LockStepShared(w, layer=1, capacity=cap)
+    _, _, evict, _, _ = lead.event(0, w.context, w.budget, "leader prefill")
+    foll.follow_event(0, w.context, lead, evict, "follower prefill")
+    for ls in (lead, foll):
+        im.im_set_max_live(ls.handle, w.budget + 1)
+    for t in range(w.context, w.context + w.decode_steps):
+        _, _, evict, _, _ = lead.event_fused(t, w.budget, f"leader decode@{t}")
+        foll.follow_step(t, lead, evict, f"follower decode@{t}")
+    assert im.im_query_status(lead.handle) == 0 and im.im_query_status(foll.handle) == 0
+
+
 def test_fused_decode_ties_evict_newest_then_largest_slot():
     # a zero gate makes every visible score 0: the entry ranked last is the newest position
     w = WORKLOADS["cfg1"].scaled(context=200, budget=200, decode_steps=5, param_std=0.0)
@@ -292,6 +310,10 @@ def test_head_shared_layout_rejects_what_is_not_built_for_it():
         im.im_attend_step(ls.handle, ls.params, g.st, q, k, k, pos, g.out)
     with pytest.raises(im.IndexMemError):
         im.im_decode_step_shared(ls.handle, ls.params, g.st, q, k, k, pos, pos, 0.9, 0.5, g.out)
+    per_head = LockStep(WORKLOADS["cfg1"])
+    with pytest.raises(im.IndexMemError):
+        im.im_decode_step_shared_hidden(per_head.handle, per_head.params, per_head.gpu.st, q, q.view(1, -1), k, k, pos,
+                                        pos, 0.9, 0.5, g.out)
     with pytest.raises(im.IndexMemError):
         im.im_append_kv(ls.handle, g.st, k, k, pos.view(-1, 1))
 
