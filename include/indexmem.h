@@ -229,7 +229,7 @@ int32_t im_decode_step(im_handle* h, const im_params* p, const im_state* st, con
                        float* readout_dbg, int32_t* evicted_slot, float* scores_dbg, void* stream);
 
 /* One token of the periodic decode schedule (Section 4, "Models and Evaluation Setup": attention
- * every step, compression once per interval), fused into three launches: exactly
+ * every step, compression once per interval), fused into two launches: exactly
  *   im_append_kv(n_new = 1) -> im_decode_attn_with_readout
  * Nothing is scored or evicted; the new entry's indexer key is computed on the way (n_projected
  * follows len), so the interval's im_index_score has nothing left to project.  The caller bounds

@@ -6,10 +6,15 @@
 //                the split's keys and find its local eviction candidate (the entry ranked last);
 //                attention waves stream K / V and accumulate the softmax-attention partial
 //                WITHOUT that candidate; the candidate's logits and K / V rows go to a record.
-//   k_att_main : the attend-only variant (no scoring waves, nothing left out).
+//   k_att_main : the attend-only variant (no scoring waves; nothing left out unless the slot to
+//                evict is named).  k_att_merged: the same with the prep roles in its launch, for
+//                steps that score nothing (two launches per step instead of three).
 //   k_dec_tail : one workgroup per unit picks the evicted entry among the candidates, folds it
 //                into the memory state, merges the partials plus the candidates that stay,
 //                adds the gated readout, fills the hole and writes the output.
+//                k_dec_tail_head: the same with one workgroup per (unit, query head).
+// Head-shared layout (one indexer key per token, one decision and one memory per sequence):
+//   k_hs_prep, k_hs_score, k_att_main, k_dec_tail_head; see the comments at k_hs_prep.
 // Kernel boundaries separate the three on purpose: on this chip a device-scope release (L2
 // write-back) per workgroup or an in-kernel wait costs several microseconds more than a launch.
 // Same results as append -> index_score (n_q = 1) -> topb_select -> memory_update -> compact_kv
@@ -187,9 +192,20 @@ __device__ __forceinline__ void dec_gemv2(const bf16_t* __restrict__ A, const bf
 // b[c], and the gate sigmoid(w_g . q + c_g).  Workgroup mp of a unit takes rows 32 mp .. 32 mp + 31
 // of the memory (its slice of phi_q, and partial sums over those rows).  The tail kernel applies
 // the rank-one update of this step to these terms instead of reading the updated state back.
-__device__ __forceinline__ void dec_prep_memory(const DecArgs& a, const int u, const int mp) {
-  __shared__ float s_phq[DEC_GMAX][32];
-  __shared__ float s_red[4][DEC_GMAX][IM_D];
+// LDS of the prep roles (a struct, so that a kernel that also holds split workgroups can overlay it)
+struct DecPrepSmem {
+  float phq[DEC_GMAX][32];
+  float red[4][DEC_GMAX][IM_D];
+  double part[4][16];
+  double rows[64 * 2];   // up to 64 batch rows x 2 outputs
+  float k[IM_D];
+  double u[IM_DI];
+  int mp[4];
+};
+
+__device__ __forceinline__ void dec_prep_memory(const DecArgs& a, const int u, const int mp, DecPrepSmem& ps) {
+  float (*s_phq)[32] = ps.phq;
+  float (*s_red)[DEC_GMAX][IM_D] = ps.red;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int b = u / a.H_kv, h = u % a.H_kv, G = a.H / a.H_kv;
   float* qm = a.qm + (size_t)u * G * DEC_QM;
@@ -254,42 +270,13 @@ __device__ __forceinline__ void dec_prep_memory(const DecArgs& a, const int u, c
   }
 }
 
-__global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
-  __shared__ double part[4][16];
-  __shared__ double rows[64 * 2];   // up to 64 batch rows x 2 outputs
-  __shared__ float s_k[IM_D];
-  __shared__ double s_u[IM_DI];
+// One unit's append in the per-unit layout: the new (k, v, pos) go to slot len, and the slot's
+// indexer key bf16(Norm(U_k k)) is computed (fp64) and stored.
+__device__ __forceinline__ void dec_prep_unit(const DecArgs& a, const int u, DecPrepSmem& ps) {
+  float* s_k = ps.k;
+  double* s_u = ps.u;
+  int* s_mp = ps.mp;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int Nq = a.H_idx * IM_DI;
-  const int nU = Nq / 2, nG = (a.H_idx + 1) / 2;
-  const int U = a.B * a.H_kv;
-  // the per-unit blocks (longer chains of short phases) are dispatched first
-  const int blk = ((int)blockIdx.x >= (1 + DEC_MP) * U) ? (int)blockIdx.x - (1 + DEC_MP) * U
-                                                        : nU + nG + (int)blockIdx.x;
-  if (blk < nU) {
-    const int n0 = blk * 2;
-    if (a.B <= 4) dec_gemv2<4>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
-    else dec_gemv2<8>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
-    // raw projections; the consumer applies the QK-Norm (it needs a whole head, this block has 2 rows)
-    for (int i = tid; i < a.B * 2; i += 256) a.qy[(size_t)(i >> 1) * Nq + n0 + (i & 1)] = rows[i];
-    return;
-  }
-  if (blk < nU + nG) {
-    const int n0 = (blk - nU) * 2;
-    if (a.B <= 4) dec_gemv2<4>(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
-    else dec_gemv2<8>(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
-    for (int i = tid; i < a.B * 2; i += 256) {
-      const int r = n0 + (i & 1);
-      if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = rows[i];   // raw G x; scaled by the consumer
-    }
-    return;
-  }
-  if (blk >= nU + nG + U) {
-    dec_prep_memory(a, (blk - nU - nG - U) / DEC_MP, (blk - nU - nG - U) % DEC_MP);
-    return;
-  }
-  // ---- unit block: append the new (k, v, pos) at slot len, compute its indexer key
-  const int u = blk - nU - nG;
   const int b = u / a.H_kv;
   const int n_old = a.len[u];
   // loads that do not depend on the length go out together with it
@@ -309,7 +296,6 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
     if (n_old + 1 <= a.C) m = max(m, newpos);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = max(m, __shfl_xor(m, o, 64));
-    __shared__ int s_mp[4];
     if (lane == 0) s_mp[w] = m;
     __syncthreads();
     if (tid == 0) a.maxpos[u] = max(max(s_mp[0], s_mp[1]), max(s_mp[2], s_mp[3]));
@@ -356,6 +342,42 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   }
 }
 
+__global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
+  __shared__ DecPrepSmem ps;
+  double (*part)[16] = ps.part;
+  double* rows = ps.rows;
+  const int tid = threadIdx.x;
+  const int Nq = a.H_idx * IM_DI;
+  const int nU = Nq / 2, nG = (a.H_idx + 1) / 2;
+  const int U = a.B * a.H_kv;
+  // the per-unit blocks (longer chains of short phases) are dispatched first
+  const int blk = ((int)blockIdx.x >= (1 + DEC_MP) * U) ? (int)blockIdx.x - (1 + DEC_MP) * U
+                                                        : nU + nG + (int)blockIdx.x;
+  if (blk < nU) {
+    const int n0 = blk * 2;
+    if (a.B <= 4) dec_gemv2<4>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
+    else dec_gemv2<8>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
+    // raw projections; the consumer applies the QK-Norm (it needs a whole head, this block has 2 rows)
+    for (int i = tid; i < a.B * 2; i += 256) a.qy[(size_t)(i >> 1) * Nq + n0 + (i & 1)] = rows[i];
+    return;
+  }
+  if (blk < nU + nG) {
+    const int n0 = (blk - nU) * 2;
+    if (a.B <= 4) dec_gemv2<4>(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
+    else dec_gemv2<8>(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
+    for (int i = tid; i < a.B * 2; i += 256) {
+      const int r = n0 + (i & 1);
+      if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = rows[i];   // raw G x; scaled by the consumer
+    }
+    return;
+  }
+  if (blk >= nU + nG + U) {
+    dec_prep_memory(a, (blk - nU - nG - U) / DEC_MP, (blk - nU - nG - U) % DEC_MP, ps);
+    return;
+  }
+  dec_prep_unit(a, blk - nU - nG, ps);
+}
+
 // --------------------------------------------------------------------------------------------
 // Head-shared layout: k_hs_prep and k_hs_score take the place of k_dec_prep and of the scoring
 // waves.  One indexer key per token (from its hidden state) and one score per token mean one
@@ -364,38 +386,30 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
 // --------------------------------------------------------------------------------------------
 // Block roles: [0, U) append the new (k, v) of a unit (the set's position by its first head);
 // [U, (1 + DEC_MP) U) the readout terms; then two rows each of U_q (input q), G and U_k (input x).
-__global__ __launch_bounds__(256) void k_hs_prep(const DecArgs a) {
-  __shared__ double part[4][16];
-  __shared__ double rows[64 * 2];
+__device__ __forceinline__ void hs_prep_unit(const DecArgs& a, const int u) {
+  const int tid = threadIdx.x, b = u / a.H_kv;
+  const int n_old = a.len[b];
+  uint4 newrow = make_uint4(0, 0, 0, 0);
+  if (tid < 16) newrow = *(const uint4*)(a.k_new + (size_t)u * IM_D + tid * 8);
+  else if (tid < 32) newrow = *(const uint4*)(a.v_new + (size_t)u * IM_D + (tid - 16) * 8);
+  const int newpos = a.pos_new[b];
+  const bool lead = u % a.H_kv == 0;
+  if (n_old + 1 > a.C) {
+    if (tid == 0 && lead) atomicOr(a.status, IM_STATUS_APPEND_OVERFLOW_BIT);
+    return;
+  }
+  if (n_old + 1 > a.max_live && tid == 0 && lead) atomicOr(a.status, IM_STATUS_LIVE_EXCEEDED_BIT);
+  const size_t slot = (size_t)u * a.C + n_old;
+  if (tid < 16) *(uint4*)(a.K + slot * IM_D + tid * 8) = newrow;
+  else if (tid < 32) *(uint4*)(a.V + slot * IM_D + (tid - 16) * 8) = newrow;
+  else if (tid == 32 && lead) a.pos[(size_t)b * a.C + n_old] = newpos;
+}
+
+// two rows of one of the three projections: g counts U_q (input q), then G, then U_k (input x) row pairs
+__device__ __forceinline__ void hs_prep_gemv(const DecArgs& a, const int g, DecPrepSmem& ps) {
   const int tid = threadIdx.x;
   const int Nq = a.H_idx * IM_DI_SHARED;
   const int nU = Nq / 2, nG = (a.H_idx + 1) / 2;
-  const int U = a.B * a.H_kv;
-  const int blk = blockIdx.x;
-  if (blk < U) {
-    const int u = blk, b = u / a.H_kv;
-    const int n_old = a.len[b];
-    uint4 newrow = make_uint4(0, 0, 0, 0);
-    if (tid < 16) newrow = *(const uint4*)(a.k_new + (size_t)u * IM_D + tid * 8);
-    else if (tid < 32) newrow = *(const uint4*)(a.v_new + (size_t)u * IM_D + (tid - 16) * 8);
-    const int newpos = a.pos_new[b];
-    const bool lead = u % a.H_kv == 0;
-    if (n_old + 1 > a.C) {
-      if (tid == 0 && lead) atomicOr(a.status, IM_STATUS_APPEND_OVERFLOW_BIT);
-      return;
-    }
-    if (n_old + 1 > a.max_live && tid == 0 && lead) atomicOr(a.status, IM_STATUS_LIVE_EXCEEDED_BIT);
-    const size_t slot = (size_t)u * a.C + n_old;
-    if (tid < 16) *(uint4*)(a.K + slot * IM_D + tid * 8) = newrow;
-    else if (tid < 32) *(uint4*)(a.V + slot * IM_D + (tid - 16) * 8) = newrow;
-    else if (tid == 32 && lead) a.pos[(size_t)b * a.C + n_old] = newpos;
-    return;
-  }
-  if (blk < (1 + DEC_MP) * U) {
-    dec_prep_memory(a, (blk - U) / DEC_MP, (blk - U) % DEC_MP);
-    return;
-  }
-  const int g = blk - (1 + DEC_MP) * U + (a.attend ? nU + nG : 0);   // an attend-only step has the U_k blocks alone
   const bool isq = g < nU, isg = !isq && g < nU + nG;
   const int n0 = (isq ? g : isg ? g - nU : g - nU - nG) * 2;
   const int N = isq ? Nq : isg ? a.H_idx : IM_DI_SHARED;
@@ -403,11 +417,25 @@ __global__ __launch_bounds__(256) void k_hs_prep(const DecArgs a) {
   const bf16_t* W = isq ? a.Uq : isg ? a.Gw : a.Uk;
   const int Kd = isq ? a.H * IM_D : a.gate_in;
   double* out = isq ? a.qy : isg ? a.alpha : a.xk;
-  if (a.B <= 4) dec_gemv2<4>(A, W, n0, N, a.B, Kd, part, rows);
-  else dec_gemv2<8>(A, W, n0, N, a.B, Kd, part, rows);
-  for (int i = tid; i < a.B * 2; i += 256) {   // raw projections; k_hs_score normalises and scales
+  if (a.B <= 4) dec_gemv2<4>(A, W, n0, N, a.B, Kd, ps.part, ps.rows);
+  else dec_gemv2<8>(A, W, n0, N, a.B, Kd, ps.part, ps.rows);
+  for (int i = tid; i < a.B * 2; i += 256) {   // raw projections; the consumer normalises and scales
     const int r = n0 + (i & 1);
-    if (r < N) out[(size_t)(i >> 1) * N + r] = rows[i];
+    if (r < N) out[(size_t)(i >> 1) * N + r] = ps.rows[i];
+  }
+}
+
+__global__ __launch_bounds__(256) void k_hs_prep(const DecArgs a) {
+  __shared__ DecPrepSmem ps;
+  const int U = a.B * a.H_kv;
+  const int blk = blockIdx.x;
+  if (blk < U) {
+    hs_prep_unit(a, blk);
+  } else if (blk < (1 + DEC_MP) * U) {
+    dec_prep_memory(a, (blk - U) / DEC_MP, (blk - U) % DEC_MP, ps);
+  } else {   // an attend-only step has the U_k blocks alone
+    const int nUG = a.H_idx * IM_DI_SHARED / 2 + (a.H_idx + 1) / 2;
+    hs_prep_gemv(a, blk - (1 + DEC_MP) * U + (a.attend ? nUG : 0), ps);
   }
 }
 
@@ -558,7 +586,8 @@ struct DecSplitSmem {
 // workgroup barrier, when the attention waves have issued their loads.
 // SCORE = false is the attend-only step: no scoring waves (the workgroup is the 4 attention waves
 // alone, so twice as many fit on a CU), nothing is left out of the partial.
-template <int G, bool SCORE>
+// MERGED: the launch also holds the prep roles, so the new token's rows come from the inputs.
+template <int G, bool SCORE, bool MERGED = false>
 __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const int s, DecSplitSmem& sm,
                                           const double* __restrict__ qy, const double* __restrict__ alpha) {
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
@@ -609,8 +638,11 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       }
     }
     // the last live slot's indexer key and position for the last-slot record
-    if (own_last && tid < a.di / 8) lkx = *(const uint4*)(a.Kidx + ((size_t)su * a.C + (n - 1)) * a.di + 8 * tid);
-    if (own_last && tid == 8) lpos = a.pos[(size_t)su * a.C + (n - 1)];
+    // (merged launch: the new token's position comes from the input and its indexer key is not made yet)
+    const bool last_is_new = MERGED && n - 1 == n_old;
+    if (own_last && tid < a.di / 8 && !last_is_new)
+      lkx = *(const uint4*)(a.Kidx + ((size_t)su * a.C + (n - 1)) * a.di + 8 * tid);
+    if (own_last && tid == 8) lpos = last_is_new ? a.pos_new[b] : a.pos[(size_t)su * a.C + (n - 1)];
   }
   if (scoring) {
     // ================= scoring waves: tiles 2 wl, 2 wl + 1 (keys 32 wl .. 32 wl + 31) =================
@@ -781,8 +813,9 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
       const int kr = min(16 * (2 * wl + tt) + l16, nk - 1);
+      const bf16_t* krow = (MERGED && k0 + kr == n_old) ? a.k_new + (size_t)u * IM_D : a.K + (base + kr) * IM_D;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) kf[tt][c] = *(const uint4*)(a.K + (base + kr) * IM_D + 32 * c + 8 * kq);
+      for (int c = 0; c < 4; ++c) kf[tt][c] = *(const uint4*)(krow + 32 * c + 8 * kq);
     }
     {
       const int jq = min(l16, G - 1);   // lanes past the group read its last head; masked below
@@ -797,7 +830,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int vr = min(16 * (2 * wl + tt) + 4 * i + kq, nk - 1);
-        vf[tt][i] = *(const uint4*)(a.V + (base + vr) * IM_D + 8 * l16);
+        const bf16_t* vrow = (MERGED && k0 + vr == n_old) ? a.v_new + (size_t)u * IM_D : a.V + (base + vr) * IM_D;
+        vf[tt][i] = *(const uint4*)(vrow + 8 * l16);
       }
     }
     // without scoring waves, split 0's attention waves look after the one key beyond the splits
@@ -806,16 +840,20 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     int ypos = 0;
     if (!SCORE && do_x_any) {
       const size_t last = (size_t)u * a.C + (n - 1), ilast = (size_t)su * a.C + (n - 1);
-      if (a.hs) {   // 16 values per indexer key: lanes kq = 0, 1 carry 8 each
+      const bool x_new = MERGED && n - 1 == n_old;   // the leftover key is the new token: rows from the inputs
+      const bf16_t* lk = x_new ? a.k_new + (size_t)u * IM_D : a.K + last * IM_D;
+      const bf16_t* lv = x_new ? a.v_new + (size_t)u * IM_D : a.V + last * IM_D;
+      if (x_new) {
+      } else if (a.hs) {   // 16 values per indexer key: lanes kq = 0, 1 carry 8 each
         if (kq < 2) yki0 = *(const uint4*)(a.Kidx + ilast * IM_DI_SHARED + 8 * kq);
       } else {
         yki0 = *(const uint4*)(a.Kidx + ilast * IM_DI + 16 * kq);
         yki1 = *(const uint4*)(a.Kidx + ilast * IM_DI + 16 * kq + 8);
       }
-      yk = *(const uint4*)(a.K + last * IM_D + 32 * wl + 8 * kq);
+      yk = *(const uint4*)(lk + 32 * wl + 8 * kq);
       yq = *(const uint4*)(a.q + ((size_t)b * a.H + h * G + min(l16, G - 1)) * IM_D + 32 * wl + 8 * kq);
-      ykv = *(const uint4*)(((lane & 16) ? a.V : a.K) + last * IM_D + 8 * l16);
-      ypos = a.pos[ilast];
+      ykv = *(const uint4*)(((lane & 16) ? lv : lk) + 8 * l16);
+      ypos = x_new ? a.pos_new[b] : a.pos[ilast];
     }
     // keep every load above this line, in this order: loads return in order, so each phase below
     // waits only for what it uses while the rest is still streaming in
@@ -1791,4 +1829,26 @@ template <int G, int CHW>
 __global__ __launch_bounds__(DEC_TT) void k_dec_tail_head(const DecArgs a) {
   __shared__ __attribute__((aligned(16))) DecTailHeadSmem<CHW> sm;
   dec_tail_head<G, CHW>(a, blockIdx.x / G, blockIdx.x % G, sm);
+}
+
+// The attend-only split kernel with the prep roles in the same launch (they do not feed it: the
+// split workgroups take the new token's rows from the inputs): role blocks first, then the
+// (unit, split) workgroups.  Two launches per layer-step instead of three.
+template <int G>
+__global__ __launch_bounds__(DEC_MT / 2, G <= 4 ? 4 : 2) void k_att_merged(const DecArgs a, const int n_roles) {
+  __shared__ __attribute__((aligned(16))) union SM { DecSplitSmem sm; DecPrepSmem ps; __device__ SM() {} } s;
+  const int U = a.B * a.H_kv;
+  if ((int)blockIdx.x >= n_roles) {
+    const int blk = blockIdx.x - n_roles;
+    dec_split<G, false, true>(a, blk % U, blk / U, s.sm, nullptr, nullptr);
+    return;
+  }
+  const int r = blockIdx.x;
+  if (r < U) {
+    if (a.hs) hs_prep_unit(a, r); else dec_prep_unit(a, r, s.ps);
+  } else if (r < (1 + DEC_MP) * U) {
+    dec_prep_memory(a, (r - U) / DEC_MP, (r - U) % DEC_MP, s.ps);
+  } else {   // head-shared layout: the U_k rows
+    hs_prep_gemv(a, r - (1 + DEC_MP) * U + a.H_idx * IM_DI_SHARED / 2 + (a.H_idx + 1) / 2, s.ps);
+  }
 }

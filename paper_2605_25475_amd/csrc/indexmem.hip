@@ -540,15 +540,21 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
     const int hs_main_blocks = units * (a.S > 0 ? a.S : 1);
     const bool hprof = h->prof_ev && h->prof_n < h->prof_max;
     hipEvent_t hev0 = hprof ? h->prof_ev[2 * h->prof_n] : nullptr, hev1 = hprof ? h->prof_ev[2 * h->prof_n + 1] : nullptr;
-    if (hprof && h->prof_span != IM_PROFILE_MAIN) (void)hipEventRecord(hev0, s);
-    k_hs_prep<<<hs_prep_blocks, 256, 0, s>>>(a);
-    if (!no_score) k_hs_score<<<c.batch * HS_NSC, HS_ST, 0, s>>>(a);
-    if (hprof && h->prof_span == IM_PROFILE_MAIN) (void)hipEventRecord(hev0, s);
-    if (hprof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(hev1, s);
+    // an attend-only or follower step has nothing between its projections and its attention: the prep
+    // roles ride in the attention launch (two launches in all)
+    const bool merged = no_score;
+    if (hprof && (merged || h->prof_span != IM_PROFILE_MAIN)) (void)hipEventRecord(hev0, s);
+    if (!merged) {
+      k_hs_prep<<<hs_prep_blocks, 256, 0, s>>>(a);
+      k_hs_score<<<c.batch * HS_NSC, HS_ST, 0, s>>>(a);
+      if (hprof && h->prof_span == IM_PROFILE_MAIN) (void)hipEventRecord(hev0, s);
+      if (hprof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(hev1, s);
+    }
 #define IM_HS_CASE(g)                                                                  \
   case g:                                                                              \
-    k_att_main<g><<<hs_main_blocks, DEC_MT / 2, 0, s>>>(a);                            \
-    if (hprof && h->prof_span != IM_PROFILE_PREP) (void)hipEventRecord(hev1, s);       \
+    if (merged) k_att_merged<g><<<hs_prep_blocks + hs_main_blocks, DEC_MT / 2, 0, s>>>(a, hs_prep_blocks); \
+    else k_att_main<g><<<hs_main_blocks, DEC_MT / 2, 0, s>>>(a);                       \
+    if (hprof && (merged || h->prof_span != IM_PROFILE_PREP)) (void)hipEventRecord(hev1, s); \
     if (a.S <= 8) k_dec_tail_head<g, 8><<<units * g, DEC_TT, 0, s>>>(a);               \
     else if (a.S <= 16) k_dec_tail_head<g, 16><<<units * g, DEC_TT, 0, s>>>(a);        \
     else if (a.S <= 32) k_dec_tail_head<g, 32><<<units * g, DEC_TT, 0, s>>>(a);        \
@@ -569,15 +575,21 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   const int main_blocks = units * (a.S > 0 ? a.S : 1);
   const bool prof = h->prof_ev && h->prof_n < h->prof_max;
   hipEvent_t ev0 = prof ? h->prof_ev[2 * h->prof_n] : nullptr, ev1 = prof ? h->prof_ev[2 * h->prof_n + 1] : nullptr;
-  if (prof && h->prof_span != IM_PROFILE_MAIN) (void)hipEventRecord(ev0, s);
-  k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);
-  if (prof && h->prof_span == IM_PROFILE_MAIN) (void)hipEventRecord(ev0, s);
-  if (prof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(ev1, s);
+  // a pure attend-only step has nothing between its prep roles and its attention: they share a launch
+  // (a follower step keeps three: its last-slot record needs the new token's indexer key)
+  const bool merged = no_score && !ext_evict;
+  if (prof && (merged || h->prof_span != IM_PROFILE_MAIN)) (void)hipEventRecord(ev0, s);
+  if (!merged) {
+    k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);
+    if (prof && h->prof_span == IM_PROFILE_MAIN) (void)hipEventRecord(ev0, s);
+    if (prof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(ev1, s);
+  }
 #define IM_DEC_CASE(g)                                              \
   case g:                                                           \
-    if (no_score) k_att_main<g><<<main_blocks, DEC_MT / 2, 0, s>>>(a); \
+    if (merged) k_att_merged<g><<<prep_blocks + main_blocks, DEC_MT / 2, 0, s>>>(a, prep_blocks); \
+    else if (no_score) k_att_main<g><<<main_blocks, DEC_MT / 2, 0, s>>>(a); \
     else k_dec_main<g><<<main_blocks, DEC_MT, 0, s>>>(a, a.qy, a.alpha); \
-    if (prof && h->prof_span != IM_PROFILE_PREP) (void)hipEventRecord(ev1, s); \
+    if (prof && (merged || h->prof_span != IM_PROFILE_PREP)) (void)hipEventRecord(ev1, s); \
     launch_tail<g>(a, units, s);                                    \
     break;
   switch (G) {
