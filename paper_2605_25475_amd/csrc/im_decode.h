@@ -88,6 +88,8 @@ struct DecArgs {
   int hs, H_set, di;
   int attend;         // head-shared layout, attend-only step: no query-side projections, no decision; the
                       // new token's indexer key is stored by the tail
+  int kidx_in_cache;  // per-unit layout, merged follower launch: the last-slot record holds no indexer key
+                      // (the new token's is made in the same launch), so the tail moves it from the cache
   const int32_t* hs_named;   // head-shared layout, optional [B]: with attend = 1, the slot each sequence
                              // evicts is given by the caller (-1 or >= len: none)
   float rms_eps, mem_eps, scale, lambda, eta;
@@ -1318,6 +1320,8 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   // the last live slot's rows (they move into the hole): K, V and indexer-key rows are adjacent in the record
   uint4 mv = make_uint4(0, 0, 0, 0);
   if (tid < 40) mv = *(const uint4*)(lsrec + DEC_CAND_K + 4 * tid);
+  if (a.kidx_in_cache && tid >= 32 && tid < 40 && n > 0)
+    mv = *(const uint4*)(a.Kidx + ((size_t)u * a.C + (n - 1)) * IM_DI + (tid - 32) * 8);
   const int mvpos = (int)lsrec[12];
   // ---------------- merge, second pass: add back the candidates that stay ----------------
 #pragma unroll
@@ -1685,6 +1689,8 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   }
   uint4 mv = make_uint4(0, 0, 0, 0);           // the last live slot's rows (they move into the hole)
   if (tid < 40) mv = *(const uint4*)(lsrec + DEC_CAND_K + 4 * tid);
+  if (a.kidx_in_cache && tid >= 32 && tid < 40 && n > 0)
+    mv = *(const uint4*)(a.Kidx + ((size_t)u * a.C + (n - 1)) * IM_DI + (tid - 32) * 8);
   const int mvpos = (int)lsrec[12];
   {   // merge, second pass: add back the candidates that stay
     float cl[PER], cv[PER];

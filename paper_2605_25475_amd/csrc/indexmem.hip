@@ -575,9 +575,11 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   const int main_blocks = units * (a.S > 0 ? a.S : 1);
   const bool prof = h->prof_ev && h->prof_n < h->prof_max;
   hipEvent_t ev0 = prof ? h->prof_ev[2 * h->prof_n] : nullptr, ev1 = prof ? h->prof_ev[2 * h->prof_n + 1] : nullptr;
-  // a pure attend-only step has nothing between its prep roles and its attention: they share a launch
-  // (a follower step keeps three: its last-slot record needs the new token's indexer key)
-  const bool merged = no_score && !ext_evict;
+  // a step that scores nothing has nothing between its prep roles and its attention: they share a
+  // launch (a follower's tail then takes the moved entry's indexer key from the cache, where the
+  // launch's unit block has put the new token's, instead of from the last-slot record)
+  const bool merged = no_score;
+  a.kidx_in_cache = (merged && ext_evict) ? 1 : 0;
   if (prof && (merged || h->prof_span != IM_PROFILE_MAIN)) (void)hipEventRecord(ev0, s);
   if (!merged) {
     k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);

@@ -92,6 +92,22 @@ def test_index_reuse_across_layers(name, kw):
         _, _, evict, _, _ = lead.event_fused(t, w.budget, f"leader decode@{t}")
         foll.follow_step(t, lead, evict, f"follower decode@{t}")
     assert im.im_query_status(lead.handle) == 0 and im.im_query_status(foll.handle) == 0
+    # a follower never reads its indexer keys, but the keys of the tokens it appended while decoding
+    # must still be those tokens' keys wherever the hole filling has moved them
+    from helpers import f64, oracle_params
+    from workloads import layer_params
+    p = oracle_params(layer_params(w, 1))
+    st = foll.gpu.st
+    pos = st.pos.cpu().numpy(); lens = st.len.cpu().numpy()
+    seen = 0
+    for b in range(w.batch):
+        for h in range(w.n_kv_heads):
+            n = int(lens[b, h])
+            new = np.nonzero(pos[b, h, :n] >= w.context)[0]
+            want = O.key_feature(f64(st.K[b, h, :n])[new], p.Uk, p.norm_k_w, float(np.float32(1e-6)))
+            assert np.array_equal(f64(st.Kidx[b, h, :n])[new], want), f"follower unit ({b},{h}): moved indexer keys"
+            seen += len(new)
+    assert seen > 0
 
 
 @pytest.mark.parametrize("name,kw", [
@@ -110,6 +126,21 @@ def test_index_reuse_across_layers_head_shared_layout(name, kw):
         _, _, evict, _, _ = lead.event_fused(t, w.budget, f"leader decode@{t}")
         foll.follow_step(t, lead, evict, f"follower decode@{t}")
     assert im.im_query_status(lead.handle) == 0 and im.im_query_status(foll.handle) == 0
+    # a follower never reads its indexer keys, but the keys of the tokens it appended while decoding
+    # must still be those tokens' keys wherever the hole filling has moved them
+    from helpers import f64, oracle_params
+    from workloads import layer_params
+    p = oracle_params(layer_params(w, 1))
+    st = foll.gpu.st
+    pos = st.pos.cpu().numpy(); lens = st.len.cpu().numpy()
+    seen = 0
+    for b in range(w.batch):
+        n = int(lens[b])
+        new = np.nonzero(pos[b, :n] >= w.context)[0]
+        want = O.key_feature(f64(foll.X[b])[pos[b, :n][new]], p.Uk, p.norm_k_w, float(np.float32(1e-6)))
+        assert np.array_equal(f64(st.Kidx[b, :n])[new], want), f"follower sequence {b}: moved indexer keys"
+        seen += len(new)
+    assert seen > 0
 
 
 def test_fused_decode_ties_evict_newest_then_largest_slot():
