@@ -314,6 +314,8 @@ def test_head_shared_layout(name, kw):
     ("cfg1", dict(n_q_heads=64, context=500, budget=140, decode_steps=3)),   # 16 indexer heads, 8 per group
     ("cfg1", dict(n_q_heads=8, n_kv_heads=1, context=500, budget=140, decode_steps=3)),   # a single KV head
     ("cfg1", dict(batch=11, context=260, budget=4, decode_steps=3)),         # budget = the sinks alone
+    ("cfg1", dict(batch=2, n_kv_heads=16, context=400, budget=150, decode_steps=3)),   # 16 KV heads: two rounds of row sums
+    ("cfg1", dict(batch=64, n_kv_heads=2, n_q_heads=8, context=150, budget=40, decode_steps=2)),   # the largest batch
 ])
 def test_head_shared_layout_fused_decode(name, kw):
     w = WORKLOADS[name].shared(n_layers=1, **kw)
