@@ -410,3 +410,48 @@ def test_fused_decode_from_an_empty_cache(shared):
     for t in range(w.decode_steps):
         ls.event_fused(t, w.budget, f"fused decode@{t}")
     assert im.im_query_status(ls.handle) == 0
+
+
+def _random_shapes(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        n_kv = int(rng.choice([1, 2, 4, 8]))
+        g = int(rng.choice([1, 2, 3, 4, 5, 7, 8]))
+        n_q = n_kv * g
+        if n_q % 4 or n_q // 4 > 16:        # H_index = H / 4 must be an integer in 1..16
+            continue
+        context = int(rng.integers(5, 700))
+        budget = int(rng.integers(4, max(6, context)))
+        n_recent = int(rng.choice([0, 0, 3]))
+        if budget < 4 + n_recent:
+            budget = 4 + n_recent
+        out.append(dict(batch=int(rng.integers(1, 6)), n_kv_heads=n_kv, n_q_heads=n_q, context=context,
+                        budget=budget, decode_steps=int(rng.integers(2, 6)), n_recent=n_recent))
+    return out
+
+
+@pytest.mark.parametrize("kw", _random_shapes(20260525, 14), ids=lambda kw: "-".join(str(v) for v in kw.values()))
+@pytest.mark.parametrize("shared", [False, True])
+def test_seeded_random_shapes_fused_decode(kw, shared):
+    # shapes drawn from a fixed seed: head counts, ragged contexts and budgets, recent windows
+    w = WORKLOADS["cfg1"].scaled(n_layers=1, **kw)
+    if shared:
+        LockStepShared(w.shared(), capacity=max(w.capacity, w.budget + 2)).run_schedule(fused_decode=True)
+    else:
+        LockStep(w, capacity=max(w.capacity, w.budget + 2)).run_schedule(fused_decode=True)
+
+
+@pytest.mark.parametrize("kw", _random_shapes(7, 9), ids=lambda kw: "-".join(str(v) for v in kw.values()))
+@pytest.mark.parametrize("shared", [False, True])
+def test_seeded_random_shapes_periodic_schedule(kw, shared):
+    # the two-launch attend-only step and the compression event on the same kind of shapes
+    tau = 3 + kw["decode_steps"] * 7
+    w = WORKLOADS["cfg1"].scaled(n_layers=1, **{**kw, "decode_steps": 2 * tau})
+    if w.context == 0 or w.budget < 4 + w.n_recent:
+        pytest.skip("degenerate draw")
+    cap = max(w.context, w.budget + tau)
+    if shared:
+        LockStepShared(w.shared(), capacity=cap).run_window_schedule(tau, 2)
+    else:
+        LockStep(w, capacity=cap, max_queries=max(w.context, tau)).run_window_schedule(tau, 2)
