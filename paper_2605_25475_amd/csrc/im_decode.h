@@ -97,19 +97,15 @@ struct DecArgs {
 
 #define HS_NSC 8   // scoring workgroups per sequence in the head-shared layout
 
-// The entry a sequence evicts in the head-shared layout: the last-ranked one over its scoring
-// workgroups' results (on a full tie the largest slot: chunks ascend), if the sequence is above its
-// budget with its n live entries; else -1.
-__device__ __forceinline__ int hs_pick(const DecArgs& a, const int b, const int n) {
-  const uint4* p = a.hs_part + (size_t)b * HS_NSC;
+// The entry a sequence would evict in the head-shared layout: the last-ranked one over the results of
+// its HS_NSC scoring workgroups (on a full tie the largest slot: chunks ascend); -1 if there is none.
+__device__ __forceinline__ int hs_pick(const uint4 (&pk)[HS_NSC]) {
   uint32_t bh = 0xffffffffu, bl = 0xffffffffu;
   int at = -1;
 #pragma unroll
-  for (int c = 0; c < HS_NSC; ++c) {
-    const uint4 v = p[c];
-    if ((int)v.z >= 0 && (v.x < bh || (v.x == bh && v.y <= bl))) { bh = v.x; bl = v.y; at = (int)v.z; }
-  }
-  return (n > a.budget) ? at : -1;
+  for (int c = 0; c < HS_NSC; ++c)
+    if ((int)pk[c].z >= 0 && (pk[c].x < bh || (pk[c].x == bh && pk[c].y <= bl))) { bh = pk[c].x; bl = pk[c].y; at = (int)pk[c].z; }
+  return at;
 }
 
 __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
@@ -445,7 +441,7 @@ __global__ __launch_bounds__(256) void k_hs_prep(const DecArgs a) {
 // of the step's query features and the head gates (every workgroup, for itself), the new token's
 // indexer key (stored by c = 0), the scores of the chunk's keys, and the chunk's entry ranked last by
 // (score, then position, then slot) with sinks and the recent window forced to the top.  The
-// consumers (attention and tail kernels) take the last-ranked of the HS_NSC results: hs_pick.
+// attention kernel takes the last-ranked of the HS_NSC results (hs_pick) and hands it to the tail.
 // Optionally writes the scores to a.scores [B][C].
 #define HS_ST 512
 __global__ __launch_bounds__(HS_ST) void k_hs_score(const DecArgs a) {
@@ -864,14 +860,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     if (!SCORE && tid < 4) {
       // the named entry is this split's candidate if it lies here (wave tid's 32 keys)
       int ev = ev_in;
-      if (a.hs) {   // as hs_pick; the sequence's decision is handed to the tail per unit
-        uint32_t bh = 0xffffffffu, bl = 0xffffffffu;
-        int at = -1;
-        if (!a.attend) {
-#pragma unroll
-          for (int c = 0; c < HS_NSC; ++c)
-            if ((int)pk[c].z >= 0 && (pk[c].x < bh || (pk[c].x == bh && pk[c].y <= bl))) { bh = pk[c].x; bl = pk[c].y; at = (int)pk[c].z; }
-        }
+      if (a.hs) {   // the sequence's decision is found here and handed to the tail per unit
+        const int at = a.attend ? -1 : hs_pick(pk);
         ev = a.hs_named ? ev_in : (n > a.budget) ? at : -1;
         if (s == 0 && tid == 0) a.hs_evict[u] = ev;
       }
