@@ -63,6 +63,13 @@ def test_parameter_counts():
                              mem_dim=128, n_layers=32)
     assert idx == 19_922_944 and round(idx / 1e6, 2) == golden["indexer_millions"]
     assert mem == 524_288 and round(mem / 1e6, 2) == golden["memory_millions"]
+    # the head-shared layout's weights at configuration 3's shape are exactly these modules: the
+    # generated tensors add up to the printed counts
+    w = WORKLOADS["cfg3"].shared()
+    p = layer_params(w, 0)
+    per_layer_idx = p["Uq"].numel() + p["Uk"].numel() + p["G"].numel()
+    assert per_layer_idx * w.n_layers == idx and p["Wtheta"].numel() * w.n_layers == mem
+    assert tuple(p["Uk"].shape) == (16, 4096) and tuple(p["Uq"].shape) == (8 * 16, 4096)
 
 
 # ----------------------------------------------------------------------------- a1 indexer
