@@ -1831,7 +1831,7 @@ __global__ __launch_bounds__(DEC_TT) void k_dec_tail_head(const DecArgs a) {
 // split workgroups take the new token's rows from the inputs): role blocks first, then the
 // (unit, split) workgroups.  Two launches per layer-step instead of three.
 template <int G>
-__global__ __launch_bounds__(DEC_MT / 2, G <= 4 ? 4 : 2) void k_att_merged(const DecArgs a, const int n_roles) {
+__global__ __launch_bounds__(DEC_MT / 2, G <= 4 ? 3 : 2) void k_att_merged(const DecArgs a, const int n_roles) {
   __shared__ __attribute__((aligned(16))) union SM { DecSplitSmem sm; DecPrepSmem ps; __device__ SM() {} } s;
   const int U = a.B * a.H_kv;
   if ((int)blockIdx.x >= n_roles) {
