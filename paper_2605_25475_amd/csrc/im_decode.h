@@ -108,6 +108,13 @@ __device__ __forceinline__ int hs_pick(const uint4 (&pk)[HS_NSC]) {
   return at;
 }
 
+// a 16-byte load with the streaming hint: data that is read once per step
+typedef unsigned int dec_u4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const dec_u4 v = __builtin_nontemporal_load((const dec_u4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
   f[0] = bf_lo(u.x); f[1] = bf_hi(u.x); f[2] = bf_lo(u.y); f[3] = bf_hi(u.y);
   f[4] = bf_lo(u.z); f[5] = bf_hi(u.z); f[6] = bf_lo(u.w); f[7] = bf_hi(u.w);
@@ -671,7 +678,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       const int kr = min(16 * (2 * wl + tt) + l16, nk - 1);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
-        kif[tt][i] = *(const uint4*)(a.Kidx + (base + kr) * IM_DI + 16 * kq + 8 * i);
+        kif[tt][i] = load_stream16(a.Kidx + (base + kr) * IM_DI + 16 * kq + 8 * i);
     }
     const int kk = 32 * wl + (lane & 31);       // the key this lane ranks (both half-waves hold it)
     mypos = a.pos[base + min(kk, nk - 1)];
@@ -813,7 +820,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       const int kr = min(16 * (2 * wl + tt) + l16, nk - 1);
       const bf16_t* krow = (MERGED && k0 + kr == n_old) ? a.k_new + (size_t)u * IM_D : a.K + (base + kr) * IM_D;
 #pragma unroll
-      for (int c = 0; c < 4; ++c) kf[tt][c] = *(const uint4*)(krow + 32 * c + 8 * kq);
+      for (int c = 0; c < 4; ++c) kf[tt][c] = load_stream16(krow + 32 * c + 8 * kq);
     }
     {
       const int jq = min(l16, G - 1);   // lanes past the group read its last head; masked below
@@ -829,7 +836,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       for (int i = 0; i < 4; ++i) {
         const int vr = min(16 * (2 * wl + tt) + 4 * i + kq, nk - 1);
         const bf16_t* vrow = (MERGED && k0 + vr == n_old) ? a.v_new + (size_t)u * IM_D : a.V + (base + vr) * IM_D;
-        vf[tt][i] = *(const uint4*)(vrow + 8 * l16);
+        vf[tt][i] = load_stream16(vrow + 8 * l16);
       }
     }
     // without scoring waves, split 0's attention waves look after the one key beyond the splits
