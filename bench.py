@@ -89,7 +89,8 @@ class Job:
         self.handle = im.Handle(cfg, device)
         self.layers, self.dec, self.qwin, self.tau, self.share, self.xdec, self.xwin = [], [], [], tau, share, [], []
         L = w.context
-        assert n_steps <= w.decode_steps, "the workload defines fewer decode steps"
+        # (the configuration's own number of decode steps is a parity-test size; the benchmark draws as
+        # many tokens from the same seeded streams as it is asked to time)
         for li in range(w.n_layers):
             p = layer_params(w, li, device)
             params = im.Params(p["Uq"], p["G"], p["Uk"], p["Wtheta"], p["wg"], p["cg"],
@@ -291,6 +292,8 @@ def main() -> None:
             sys.exit(f"bench.py: with --path periodic, --steps and --warmup must be multiples of --tau ({tau})")
         assert w.budget + tau <= w.capacity
     n_total = a.warmup + (1 if tau else 2) * a.steps
+    if a.steps < 1 or a.warmup < 0 or n_total > 8192:
+        sys.exit("bench.py: --steps must be >= 1, --warmup >= 0, and warmup + 2 x steps at most 8192")
     t_setup = time.perf_counter()
     job = Job(w, n_total, log=log, tau=tau, share=a.share if a.path == "shared" else 1)
     torch.cuda.synchronize()
