@@ -208,6 +208,22 @@ struct DecPrepSmem {
   int mp[4];
 };
 
+// Workgroups go to the 8 XCDs round-robin by their index.  Everything a unit owns (its memory state,
+// readout terms, split records, appended rows) is touched by several launches per step; with the
+// unit's workgroups of every launch on XCD u % 8 those lines are found in that XCD's L2.  For a block
+// range that starts at a multiple of 8 and holds `per` workgroups for each of U units (U a multiple of
+// 8), index r maps to unit (r % 8) + 8 ((r / 8) / per) and item (r / 8) % per; else plain division.
+__device__ __forceinline__ void xcd_unit_map(const int r, const int per, const int U, int& u, int& item) {
+  if (U % 8 == 0) {
+    const int x = r & 7, k = r >> 3;
+    u = x + 8 * (k / per);
+    item = k % per;
+  } else {
+    u = r / per;
+    item = r % per;
+  }
+}
+
 __device__ __forceinline__ void dec_prep_memory(const DecArgs& a, const int u, const int mp, DecPrepSmem& ps) {
   float (*s_phq)[32] = ps.phq;
   float (*s_red)[DEC_GMAX][IM_D] = ps.red;
@@ -377,7 +393,9 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
     return;
   }
   if (blk >= nU + nG + U) {
-    dec_prep_memory(a, (blk - nU - nG - U) / DEC_MP, (blk - nU - nG - U) % DEC_MP, ps);
+    int mu, mp;
+    xcd_unit_map(blk - nU - nG - U, DEC_MP, U, mu, mp);   // (these blocks start at grid index U: a multiple of 8 with U)
+    dec_prep_memory(a, mu, mp, ps);
     return;
   }
   dec_prep_unit(a, blk - nU - nG, ps);
@@ -437,7 +455,9 @@ __global__ __launch_bounds__(256) void k_hs_prep(const DecArgs a) {
   if (blk < U) {
     hs_prep_unit(a, blk);
   } else if (blk < (1 + DEC_MP) * U) {
-    dec_prep_memory(a, (blk - U) / DEC_MP, (blk - U) % DEC_MP, ps);
+    int mu, mp;
+    xcd_unit_map(blk - U, DEC_MP, U, mu, mp);
+    dec_prep_memory(a, mu, mp, ps);
   } else {   // an attend-only step has the U_k blocks alone
     const int nUG = a.H_idx * IM_DI_SHARED / 2 + (a.H_idx + 1) / 2;
     hs_prep_gemv(a, blk - (1 + DEC_MP) * U + (a.attend ? nUG : 0), ps);
@@ -1831,7 +1851,9 @@ __global__ __launch_bounds__(DEC_TT) void k_dec_tail(const DecArgs a) {
 template <int G, int CHW>
 __global__ __launch_bounds__(DEC_TT) void k_dec_tail_head(const DecArgs a) {
   __shared__ __attribute__((aligned(16))) DecTailHeadSmem<CHW> sm;
-  dec_tail_head<G, CHW>(a, blockIdx.x / G, blockIdx.x % G, sm);
+  int u, j;   // the unit's tail on the XCD whose L2 has just seen its records (xcd_unit_map)
+  xcd_unit_map(blockIdx.x, G, a.B * a.H_kv, u, j);
+  dec_tail_head<G, CHW>(a, u, j, sm);
 }
 
 // The attend-only split kernel with the prep roles in the same launch (they do not feed it: the
@@ -1850,7 +1872,9 @@ __global__ __launch_bounds__(DEC_MT / 2, G <= 4 ? 3 : 2) void k_att_merged(const
   if (r < U) {
     if (a.hs) hs_prep_unit(a, r); else dec_prep_unit(a, r, s.ps);
   } else if (r < (1 + DEC_MP) * U) {
-    dec_prep_memory(a, (r - U) / DEC_MP, (r - U) % DEC_MP, s.ps);
+    int mu, mp;
+    xcd_unit_map(r - U, DEC_MP, U, mu, mp);
+    dec_prep_memory(a, mu, mp, s.ps);
   } else {   // head-shared layout: the U_k rows
     hs_prep_gemv(a, r - (1 + DEC_MP) * U + a.H_idx * IM_DI_SHARED / 2 + (a.H_idx + 1) / 2, s.ps);
   }
