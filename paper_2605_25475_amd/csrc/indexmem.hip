@@ -126,9 +126,8 @@ int n_sets(const im_config& c) { return c.batch * c.n_kv_heads / heads_per_set(c
 // splits (more splits than the largest variant are merged in several rounds)
 template <int G>
 void launch_tail(const DecArgs& a, int units, hipStream_t s) {
-  // one workgroup per (unit, head) when those fill at most half the CUs (measured: at 256 such
-  // workgroups the per-unit form is faster again) and one staging round holds the splits
-  if (units * G <= 128 && a.S <= 64) {
+  // one workgroup per (unit, head) when those fit the chip once and one staging round holds the splits
+  if (units * G <= 256 && a.S <= 64) {
     if (a.S <= 8) k_dec_tail_head<G, 8><<<units * G, DEC_TT, 0, s>>>(a);
     else if (a.S <= 16) k_dec_tail_head<G, 16><<<units * G, DEC_TT, 0, s>>>(a);
     else if (a.S <= 32) k_dec_tail_head<G, 32><<<units * G, DEC_TT, 0, s>>>(a);
