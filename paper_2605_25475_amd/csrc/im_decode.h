@@ -1499,9 +1499,9 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
 // --------------------------------------------------------------------------------------------
 // k_dec_tail_head: the tail with one workgroup per (unit, query head), for launches whose units x
 // heads fit the chip once (at most one such workgroup per CU).  Every workgroup ranks the
-// candidates and forms phi_e for itself; it merges only its head's partials, 8 threads per output,
-// and the workgroup of head 0 also updates the memory state, fills the hole and publishes the
-// length.  CHW (a multiple of 8, at most 64) must hold every split of the launch.
+// candidates and forms phi_e for itself; it merges only its head's partials, 8 threads per output;
+// the unit's workgroups share the rows of the memory update, and that of head 0 also fills the hole
+// and publishes the length.  CHW (a multiple of 8, at most 64) must hold every split of the launch.
 // --------------------------------------------------------------------------------------------
 template <int CHW>
 struct DecTailHeadSmem {
@@ -1527,11 +1527,12 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   const float* pbase = a.part + (size_t)u * a.S_alloc * G * DEC_REC;
   const int su = u / a.H_set;                // the set that owns the lengths, indexer keys and the memory
   const bool lead = u % a.H_set == 0;        // ... and the unit that updates them
-  const int d4 = tid & 31, rg = tid >> 5;    // head 0's workgroup: patch of M, rows 4 rg .. + 3, columns 4 d4 .. + 3
+  const int d4 = tid & 31, rg = tid >> 5;    // this thread's part of M: row group rg, columns 4 d4 .. 4 d4 + 3
   float* Mu = a.M + (size_t)su * IM_DM * IM_D;
   const int wc = tid & 127, hh = tid >> 7;   // W_theta row wc, dims 16 hh .. 16 hh + 15
   const int cs0 = min(CH, a.S);
   const int LS = min(a.S, CH);               // index (and staged slot) of the last-slot record
+  DEC_STAMP(8);
   {
     // one batch: every load of the regions is in flight before the first LDS store
     constexpr int NBP = (CH * (DEC_REC / 2) + DEC_TT - 1) / DEC_TT;
@@ -1583,9 +1584,15 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     else if (tid < 64 * (1 + DEC_MP)) ((float2*)&sm.rpart[0][0])[tid - 64] = rq;
     else if (tid <= 64 * (1 + DEC_MP) + DEC_MP) sm.sc[t3] = rs;
   }
-  float4 Mr[4] = {};
+  // The rank-one update of M is shared by the G head workgroups of the unit that owns the memory (rows
+  // MROWS j .. MROWS j + MROWS - 1 each) when G divides 128; else head 0 takes all rows.
+  constexpr int MROWS = (IM_DM % G == 0) ? IM_DM / G : IM_DM;
+  constexpr int MPT = (MROWS + 31) / 32;          // rows per thread (thread = (row group tid >> 5, 4 columns tid & 31))
+  const bool m_mine = lead && ((IM_DM % G == 0) || j == 0);
+  const int m_row0 = (IM_DM % G == 0) ? MROWS * j : 0;
+  float4 Mr[MPT] = {};
   float b_old = 0.f;
-  const bool writer = j == 0 && lead;   // uniform per workgroup: it updates the memory state
+  const bool writer = j == 0 && lead;   // uniform per workgroup: it updates b, fills the hole, publishes the length
   // attend-only / follower step of the head-shared layout: nothing scored the new token, so its
   // indexer key Norm(U_k x) is made here (one 16-lane row of the writer workgroup) and stored at the
   // end, where the token's final slot is known
@@ -1599,14 +1606,16 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     const double wk = a.nkw ? (double)bf2f(a.nkw[dd]) : 1.0;
     new_key = d2bf_rne(v / rr * wk);
   }
-  if (writer) {
+  if (m_mine) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);
-    b_old = a.bvec[(size_t)su * IM_DM + wc];
+    for (int i = 0; i < MPT; ++i)
+      if (rg + 32 * i < MROWS) Mr[i] = *(const float4*)(Mu + (m_row0 + rg + 32 * i) * IM_D + 4 * d4);
   }
+  if (writer) b_old = a.bvec[(size_t)su * IM_DM + wc];
   const uint4 Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
   const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
   __syncthreads();
+  DEC_STAMP(9);
   const int n = (int)sm.cst[0][3];
   const int n_act = min((n + DEC_KEYS - 1) / DEC_KEYS, a.S);
   const bool has_x = n > a.S * DEC_KEYS;      // one key beyond the splits: described by the last-slot record
@@ -1679,6 +1688,7 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     }
   }
   __syncthreads();
+  DEC_STAMP(10);
   const int e_split = sm.e_split, e_slot = sm.e_slot;
   const uint32_t* er = (e_split == x_split) ? lsrec : (const uint32_t*)&sm.cst[max(e_split, 0)][0];
   float ve_d = 0.f;
@@ -1744,6 +1754,7 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   }
   sm.mrg[0][part][d] = rm; sm.mrg[1][part][d] = rl; sm.mrg[2][part][d] = ro;
   __syncthreads();
+  DEC_STAMP(11);
   if (w == 15) {   // phi_q . phi_e and the readout's denominator
     float dn = 0.f, dt = 0.f;
 #pragma unroll
@@ -1758,12 +1769,12 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
       dn = fmaf(a.lambda, dn, a.eta * sq);
     }
     if (lane == 0) { sm.den = dn + a.mem_eps; sm.dot = dt; }
-  } else if (writer && w >= 6 && w < 8 && e_slot >= 0) {   // b <- lambda b + eta phi_e^2 (wc = tid - 384 here)
+  } else if (m_mine && w >= 6 && w < 8 && e_slot >= 0) {   // phi_e; b <- lambda b + eta phi_e^2 (wc = tid - 384 here)
     float pe = 0.f;
 #pragma unroll
     for (int k = 0; k < 8; ++k) pe += sm.phe2[k][wc];
     sm.phe[wc] = pe;
-    a.bvec[(size_t)su * IM_DM + wc] = fmaf(a.lambda, b_old, a.eta * pe * pe);
+    if (writer) a.bvec[(size_t)su * IM_DM + wc] = fmaf(a.lambda, b_old, a.eta * pe * pe);
   }
   float o_attn = 0.f;
   if (tid < IM_D) {   // fold the 8 thread groups of output d
@@ -1790,18 +1801,22 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     a.out[oi] = f2bf_rne(o_attn + res);
     if (a.readout) a.readout[oi] = res;
   }
-  if (j != 0) return;
-  if (e_slot >= 0 && writer) {
-    // M <- lambda M + eta phi_e v_e^T for this thread's 4 x 4 patch
+  DEC_STAMP(12);
+  if (e_slot >= 0 && m_mine) {
+    // M <- lambda M + eta phi_e v_e^T for this thread's rows, 4 columns each
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float f = a.eta * sm.phe[rg * 4 + i];
-      float4 m = Mr[i];
-      m.x = fmaf(a.lambda, m.x, f * ve4.x); m.y = fmaf(a.lambda, m.y, f * ve4.y);
-      m.z = fmaf(a.lambda, m.z, f * ve4.z); m.w = fmaf(a.lambda, m.w, f * ve4.w);
-      *(float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4) = m;
+    for (int i = 0; i < MPT; ++i) {
+      const int row = m_row0 + rg + 32 * i;
+      if (rg + 32 * i < MROWS) {
+        const float f = a.eta * sm.phe[row];
+        float4 m = Mr[i];
+        m.x = fmaf(a.lambda, m.x, f * ve4.x); m.y = fmaf(a.lambda, m.y, f * ve4.y);
+        m.z = fmaf(a.lambda, m.z, f * ve4.z); m.w = fmaf(a.lambda, m.w, f * ve4.w);
+        *(float4*)(Mu + row * IM_D + 4 * d4) = m;
+      }
     }
   }
+  if (j != 0) return;
   // fill the hole with the last entry, publish the new length
   const int n_keep = (e_slot >= 0) ? n - 1 : n;
   if (e_slot >= 0 && e_slot < n_keep) {
@@ -1821,6 +1836,7 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     a.nproj[su] = n_keep;
     if (a.evicted) a.evicted[su] = e_slot;
   }
+  DEC_STAMP(13);
 }
 
 // grid: units * S blocks; consecutive blocks take different units, the short last splits come last
