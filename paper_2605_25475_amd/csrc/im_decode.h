@@ -44,7 +44,11 @@
 extern "C" __device__ unsigned long long im_trace_buf[2048 * 16];
 __device__ unsigned long long im_trace_buf[2048 * 16];
 #define DEC_STAMP_AT(slot, thread) do { if (threadIdx.x == (thread) && blockIdx.x < 2048) im_trace_buf[blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
+extern "C" __device__ unsigned long long im_trace_prep[2048 * 2];
+__device__ unsigned long long im_trace_prep[2048 * 2];
+#define PREP_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x < 2048) im_trace_prep[blockIdx.x * 2 + (slot)] = wall_clock64(); } while (0)
 #else
+#define PREP_STAMP(slot) do { } while (0)
 #define DEC_STAMP_AT(slot, thread) do { } while (0)
 #endif
 #define DEC_STAMP(slot) DEC_STAMP_AT(slot, 0)
@@ -365,6 +369,7 @@ __device__ __forceinline__ void dec_prep_unit(const DecArgs& a, const int u, Dec
 
 __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   __shared__ DecPrepSmem ps;
+  PREP_STAMP(0);
   double (*part)[16] = ps.part;
   double* rows = ps.rows;
   const int tid = threadIdx.x;
@@ -380,6 +385,7 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
     else dec_gemv2<8>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
     // raw projections; the consumer applies the QK-Norm (it needs a whole head, this block has 2 rows)
     for (int i = tid; i < a.B * 2; i += 256) a.qy[(size_t)(i >> 1) * Nq + n0 + (i & 1)] = rows[i];
+    PREP_STAMP(1);
     return;
   }
   if (blk < nU + nG) {
@@ -390,15 +396,18 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
       const int r = n0 + (i & 1);
       if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = rows[i];   // raw G x; scaled by the consumer
     }
+    PREP_STAMP(1);
     return;
   }
   if (blk >= nU + nG + U) {
     int mu, mp;
     xcd_unit_map(blk - nU - nG - U, DEC_MP, U, mu, mp);   // (these blocks start at grid index U: a multiple of 8 with U)
     dec_prep_memory(a, mu, mp, ps);
+    PREP_STAMP(1);
     return;
   }
   dec_prep_unit(a, blk - nU - nG, ps);
+  PREP_STAMP(1);
 }
 
 // --------------------------------------------------------------------------------------------

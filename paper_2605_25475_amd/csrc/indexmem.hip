@@ -655,6 +655,9 @@ int32_t im_decode_step_shared_hidden(im_handle* h, const im_params* p, const im_
 }  // extern "C"
 
 #ifdef IM_DEC_TRACE
+extern "C" int im_trace_read_prep(unsigned long long* host) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(im_trace_prep), 2048 * 2 * sizeof(unsigned long long));
+}
 extern "C" int im_trace_read(unsigned long long* host) {
   return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(im_trace_buf), 2048 * 16 * sizeof(unsigned long long));
 }
