@@ -624,7 +624,8 @@ struct DecSplitSmem {
 template <int G, bool SCORE, bool MERGED = false>
 __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const int s, DecSplitSmem& sm,
                                           const double* __restrict__ qy, const double* __restrict__ alpha) {
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // a scalar, so that branches on the wave's role are uniform
   const int wl = w & 3;                 // wave within its role
   const bool scoring = SCORE && w >= 4; // wave-uniform role
   const int b = u / a.H_kv, h = u % a.H_kv;
@@ -1154,7 +1155,8 @@ template <int G, int CHW>
 __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailSmem<G, CHW>& sm) {
   constexpr int CH = DecTailSmem<G, CHW>::CH;
   constexpr int NS = DecTailSmem<G, CHW>::NS;
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // a scalar, so that branches on the wave's role are uniform
   const int b = u / a.H_kv, h = u % a.H_kv;
   DEC_STAMP(8);
   const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
@@ -1530,7 +1532,8 @@ struct DecTailHeadSmem {
 template <int G, int CHW>
 __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, const int j, DecTailHeadSmem<CHW>& sm) {
   constexpr int CH = CHW, PER = CH / 8;
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // a scalar, so that branches on the wave's role are uniform
   const int b = u / a.H_kv, h = u % a.H_kv;
   const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
   const float* pbase = a.part + (size_t)u * a.S_alloc * G * DEC_REC;
