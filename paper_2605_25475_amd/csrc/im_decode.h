@@ -125,8 +125,9 @@ __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
 }
 
 // --------------------------------------------------------------------------------------------
-// k_dec_prep.  Block roles, in the order of `blk` below.  Blocks [0, nU): two rows of U_q each, all batch rows (raw projections, fp64).
-// Blocks [nU, nU + nG): two rows of G.
+// k_dec_prep.  Block roles, in the order of `blk` below.  Blocks [0, nU): two rows of U_q each against PR
+// batch rows (raw projections, fp64; a larger batch takes more blocks per row pair, not more rounds per block).
+// Blocks [nU, nU + nG): two rows of G, likewise.
 // Blocks after: one per unit, append + indexer key of the new token; then DEC_MP more per unit, the
 // eviction-independent terms of the memory readout.
 // --------------------------------------------------------------------------------------------
@@ -134,10 +135,12 @@ __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
 // accumulation).  Each round issues the loads of two 2048-wide slabs before any arithmetic.
 template <int MB>
 __device__ __forceinline__ void dec_gemv2(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Bm, int n0,
-                                          int N, int M, int Kd, double (*part)[16], double* out_rows) {
+                                          int N, int M, int Kd, double (*part)[16], double* out_rows,
+                                          int m_first = 0, int m_end = 1 << 30) {
   const int tid = threadIdx.x;
   const int r1 = (n0 + 1 < N) ? n0 + 1 : n0;   // an absent second row repeats the first (result unused)
-  for (int mb = 0; mb < M; mb += MB) {
+  m_end = min(m_end, M);                       // batch rows [m_first, m_end) only
+  for (int mb = m_first; mb < m_end; mb += MB) {
     double acc[MB][2];
 #pragma unroll
     for (int i = 0; i < MB; ++i) acc[i][0] = acc[i][1] = 0.0;
@@ -153,6 +156,16 @@ __device__ __forceinline__ void dec_gemv2(const bf16_t* __restrict__ A, const bf
           const int m = (mb + i < M) ? mb + i : M - 1;
           au[it][i] = *(const uint4*)(A + (size_t)m * Kd + k);
         }
+      }
+      // MB = 4: every load above is issued before the arithmetic starts.  The empty statement needs a word of
+      // each, and nothing is scheduled across the barrier; else the second slab's loads sink into its branch
+      // below and their latency is paid a second time.  (With 8 batch rows the registers this takes would
+      // halve the number of resident workgroups.)
+      if constexpr (MB == 4) {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" : "+v"(bu[0][0].x), "+v"(bu[0][1].x), "+v"(bu[1][0].x), "+v"(bu[1][1].x),
+                          "+v"(au[0][0].x), "+v"(au[0][1].x), "+v"(au[0][2].x), "+v"(au[0][3].x),
+                          "+v"(au[1][0].x), "+v"(au[1][1].x), "+v"(au[1][2].x), "+v"(au[1][3].x));
       }
 #pragma unroll
       for (int it = 0; it < 2; ++it) {
@@ -185,7 +198,7 @@ __device__ __forceinline__ void dec_gemv2(const bf16_t* __restrict__ A, const bf
       for (int i = 0; i < MB; ++i) { part[tid >> 6][2 * i] = acc[i][0]; part[tid >> 6][2 * i + 1] = acc[i][1]; }
     }
     __syncthreads();
-    if (tid < 2 * MB && mb + (tid >> 1) < M)
+    if (tid < 2 * MB && mb + (tid >> 1) < m_end)
       out_rows[(mb + (tid >> 1)) * 2 + (tid & 1)] = part[0][tid] + part[1][tid] + part[2][tid] + part[3][tid];
   }
   __syncthreads();
@@ -305,15 +318,18 @@ __device__ __forceinline__ void dec_prep_unit(const DecArgs& a, const int u, Dec
   const int b = u / a.H_kv;
   const int n_old = a.len[u];
   // loads that do not depend on the length go out together with it
-  uint4 ukr[4], newrow = make_uint4(0, 0, 0, 0);
+  uint4 ukr[4], newrow;
   {
     const uint4* ur = (const uint4*)(a.Uk + (tid >> 2) * IM_D + (tid & 3) * 32);
 #pragma unroll
     for (int i = 0; i < 4; ++i) ukr[i] = ur[i];
-    if (tid < 16) newrow = *(const uint4*)(a.k_new + (size_t)u * IM_D + tid * 8);
-    else if (tid < 32) newrow = *(const uint4*)(a.v_new + (size_t)u * IM_D + (tid - 16) * 8);
+    // (no branch around this load: a value defined in one arm of a branch is waited for at the arm's end;
+    // threads past 31 repeat thread 31's piece)
+    const int t = min(tid, 31);
+    newrow = *(const uint4*)(((t < 16) ? a.k_new : a.v_new) + (size_t)u * IM_D + (t & 15) * 8);
   }
   const int newpos = a.pos_new[b];
+  asm volatile("" : "+v"(ukr[0].x), "+v"(ukr[1].x), "+v"(ukr[2].x), "+v"(ukr[3].x), "+v"(newrow.x));
   if (a.n_recent > 0) {  // newest position of the unit (new token included) for the recent window
     int m = INT_MIN;
     const int nn = min(n_old, a.max_live);
@@ -367,6 +383,7 @@ __device__ __forceinline__ void dec_prep_unit(const DecArgs& a, const int u, Dec
   }
 }
 
+template <int PR>   // batch rows per projection block: 4 or 8
 __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   __shared__ DecPrepSmem ps;
   PREP_STAMP(0);
@@ -374,25 +391,27 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   double* rows = ps.rows;
   const int tid = threadIdx.x;
   const int Nq = a.H_idx * IM_DI;
-  const int nU = Nq / 2, nG = (a.H_idx + 1) / 2;
+  // a projection block takes two weight rows and PR batch rows (one round of loads): nB blocks per row pair
+  const int nB = (a.B + PR - 1) / PR;
+  const int nU = Nq / 2 * nB, nG = (a.H_idx + 1) / 2 * nB;
   const int U = a.B * a.H_kv;
   // the per-unit blocks (longer chains of short phases) are dispatched first
   const int blk = ((int)blockIdx.x >= (1 + DEC_MP) * U) ? (int)blockIdx.x - (1 + DEC_MP) * U
                                                         : nU + nG + (int)blockIdx.x;
   if (blk < nU) {
-    const int n0 = blk * 2;
-    if (a.B <= 4) dec_gemv2<4>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
-    else dec_gemv2<8>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows);
+    const int rp = (nB == 1) ? blk : blk / nB;   // (no division on the common path)
+    const int n0 = rp * 2, m0 = (blk - rp * nB) * PR, m1 = min(m0 + PR, a.B);
+    dec_gemv2<PR>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows, m0, m1);
     // raw projections; the consumer applies the QK-Norm (it needs a whole head, this block has 2 rows)
-    for (int i = tid; i < a.B * 2; i += 256) a.qy[(size_t)(i >> 1) * Nq + n0 + (i & 1)] = rows[i];
+    for (int i = 2 * m0 + tid; i < 2 * m1; i += 256) a.qy[(size_t)(i >> 1) * Nq + n0 + (i & 1)] = rows[i];
     PREP_STAMP(1);
     return;
   }
   if (blk < nU + nG) {
-    const int n0 = (blk - nU) * 2;
-    if (a.B <= 4) dec_gemv2<4>(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
-    else dec_gemv2<8>(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows);
-    for (int i = tid; i < a.B * 2; i += 256) {
+    const int rp = (nB == 1) ? blk - nU : (blk - nU) / nB;
+    const int n0 = rp * 2, m0 = (blk - nU - rp * nB) * PR, m1 = min(m0 + PR, a.B);
+    dec_gemv2<PR>(a.xg, a.Gw, n0, a.H_idx, a.B, a.gate_in, part, rows, m0, m1);
+    for (int i = 2 * m0 + tid; i < 2 * m1; i += 256) {
       const int r = n0 + (i & 1);
       if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = rows[i];   // raw G x; scaled by the consumer
     }
@@ -421,9 +440,8 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
 __device__ __forceinline__ void hs_prep_unit(const DecArgs& a, const int u) {
   const int tid = threadIdx.x, b = u / a.H_kv;
   const int n_old = a.len[b];
-  uint4 newrow = make_uint4(0, 0, 0, 0);
-  if (tid < 16) newrow = *(const uint4*)(a.k_new + (size_t)u * IM_D + tid * 8);
-  else if (tid < 32) newrow = *(const uint4*)(a.v_new + (size_t)u * IM_D + (tid - 16) * 8);
+  const int t = min(tid, 31);   // (one load without a branch around it; threads past 31 repeat thread 31's piece)
+  uint4 newrow = *(const uint4*)(((t < 16) ? a.k_new : a.v_new) + (size_t)u * IM_D + (t & 15) * 8);
   const int newpos = a.pos_new[b];
   const bool lead = u % a.H_kv == 0;
   if (n_old + 1 > a.C) {
@@ -1199,7 +1217,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       if (tid + DEC_TT * k < nq2) ((float2*)&sm.phq[0][0])[tid + DEC_TT * k] = rq[k];
   }
   // the memory state and W_theta are used further down (rank-one update, phi_e): their loads go out
-  // behind the staging batch, whose registers are free again
+  // behind the staging batch, whose registers are free again (issued with it, they delay it: measured)
   float4 Mr[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) Mr[i] = *(const float4*)(Mu + (rg * 4 + i) * IM_D + 4 * d4);
@@ -1544,6 +1562,30 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   const int wc = tid & 127, hh = tid >> 7;   // W_theta row wc, dims 16 hh .. 16 hh + 15
   const int cs0 = min(CH, a.S);
   const int LS = min(a.S, CH);               // index (and staged slot) of the last-slot record
+  // The rank-one update of M is shared by the G head workgroups of the unit that owns the memory (rows
+  // MROWS j .. MROWS j + MROWS - 1 each) when G divides 128; else head 0 takes all rows.
+  constexpr int MROWS = (IM_DM % G == 0) ? IM_DM / G : IM_DM;
+  constexpr int MPT = (MROWS + 31) / 32;          // rows per thread (thread = (row group tid >> 5, 4 columns tid & 31))
+  const bool m_mine = lead && ((IM_DM % G == 0) || j == 0);
+  const int m_row0 = (IM_DM % G == 0) ? MROWS * j : 0;
+  float4 Mr[MPT] = {};
+  float b_old = 0.f;
+  const bool writer = j == 0 && lead;   // uniform per workgroup: it updates b, fills the hole, publishes the length
+  uint4 Wr0, Wr1;
+  // the loads of the later phases (this thread's patch of M, b, its piece of W_theta) go out with the
+  // staging batch when that is small, else behind it: next to a long batch they delay the records the
+  // first phases wait for (measured: 8 splits gain 1 %, 16 splits lose 2 %)
+  constexpr bool ML_EARLY = CHW <= 8;
+  auto later_loads = [&]() {
+    if (m_mine) {
+#pragma unroll
+      for (int i = 0; i < MPT; ++i)
+        if (rg + 32 * i < MROWS) Mr[i] = *(const float4*)(Mu + (m_row0 + rg + 32 * i) * IM_D + 4 * d4);
+    }
+    if (writer) b_old = a.bvec[(size_t)su * IM_DM + wc];
+    Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
+    Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
+  };
   DEC_STAMP(8);
   {
     // one batch: every load of the regions is in flight before the first LDS store
@@ -1583,6 +1625,7 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
         hvs += (hh < a.H_set) ? vx : 0.f;
       }
     }
+    if constexpr (ML_EARLY) later_loads();
     __asm__ volatile("" ::: "memory");
     if (a.hs) { sm.hk[tid >> 7][tid & 127] = hks; sm.hv[tid >> 7][tid & 127] = hvs; }
     if (tid < DEC_CAND / 2) ((float2*)&sm.cst[LS][0])[tid] = rl;
@@ -1596,15 +1639,6 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     else if (tid < 64 * (1 + DEC_MP)) ((float2*)&sm.rpart[0][0])[tid - 64] = rq;
     else if (tid <= 64 * (1 + DEC_MP) + DEC_MP) sm.sc[t3] = rs;
   }
-  // The rank-one update of M is shared by the G head workgroups of the unit that owns the memory (rows
-  // MROWS j .. MROWS j + MROWS - 1 each) when G divides 128; else head 0 takes all rows.
-  constexpr int MROWS = (IM_DM % G == 0) ? IM_DM / G : IM_DM;
-  constexpr int MPT = (MROWS + 31) / 32;          // rows per thread (thread = (row group tid >> 5, 4 columns tid & 31))
-  const bool m_mine = lead && ((IM_DM % G == 0) || j == 0);
-  const int m_row0 = (IM_DM % G == 0) ? MROWS * j : 0;
-  float4 Mr[MPT] = {};
-  float b_old = 0.f;
-  const bool writer = j == 0 && lead;   // uniform per workgroup: it updates b, fills the hole, publishes the length
   // attend-only / follower step of the head-shared layout: nothing scored the new token, so its
   // indexer key Norm(U_k x) is made here (one 16-lane row of the writer workgroup) and stored at the
   // end, where the token's final slot is known
@@ -1618,14 +1652,7 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     const double wk = a.nkw ? (double)bf2f(a.nkw[dd]) : 1.0;
     new_key = d2bf_rne(v / rr * wk);
   }
-  if (m_mine) {
-#pragma unroll
-    for (int i = 0; i < MPT; ++i)
-      if (rg + 32 * i < MROWS) Mr[i] = *(const float4*)(Mu + (m_row0 + rg + 32 * i) * IM_D + 4 * d4);
-  }
-  if (writer) b_old = a.bvec[(size_t)su * IM_DM + wc];
-  const uint4 Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
-  const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
+  if constexpr (!ML_EARLY) later_loads();
   __syncthreads();
   DEC_STAMP(9);
   const int n = (int)sm.cst[0][3];

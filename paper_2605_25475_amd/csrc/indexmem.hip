@@ -570,7 +570,11 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   }
   // the per-unit blocks come first in the prep kernel's block order: an attend-only step launches
   // just those (no query-side indexer projections)
-  const int prep_blocks = (no_score ? 0 : c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2) + (1 + DEC_MP) * units;
+  const int row_pairs = c.n_idx_heads * IM_DI / 2 + (c.n_idx_heads + 1) / 2;
+  // projection blocks take 4 batch rows each (a shorter chain per block) while the grid then still is
+  // one generation of workgroups (4 per CU), else 8
+  const int prep_rows = (row_pairs * ((c.batch + 3) / 4) + (1 + DEC_MP) * units <= 4 * 256) ? 4 : 8;
+  const int prep_blocks = (no_score ? 0 : row_pairs * ((c.batch + prep_rows - 1) / prep_rows)) + (1 + DEC_MP) * units;
   const int main_blocks = units * (a.S > 0 ? a.S : 1);
   const bool prof = h->prof_ev && h->prof_n < h->prof_max;
   hipEvent_t ev0 = prof ? h->prof_ev[2 * h->prof_n] : nullptr, ev1 = prof ? h->prof_ev[2 * h->prof_n + 1] : nullptr;
@@ -581,7 +585,8 @@ static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* s
   a.kidx_in_cache = (merged && ext_evict) ? 1 : 0;
   if (prof && (merged || h->prof_span != IM_PROFILE_MAIN)) (void)hipEventRecord(ev0, s);
   if (!merged) {
-    k_dec_prep<<<prep_blocks, 256, 0, s>>>(a);
+    if (prep_rows == 4) k_dec_prep<4><<<prep_blocks, 256, 0, s>>>(a);
+    else k_dec_prep<8><<<prep_blocks, 256, 0, s>>>(a);
     if (prof && h->prof_span == IM_PROFILE_MAIN) (void)hipEventRecord(ev0, s);
     if (prof && h->prof_span == IM_PROFILE_PREP) (void)hipEventRecord(ev1, s);
   }

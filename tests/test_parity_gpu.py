@@ -49,7 +49,9 @@ def test_cfg1_full_trajectory_fused_decode():
     ("cfg1", dict(n_q_heads=64, context=500, budget=140, decode_steps=3)),   # 16 indexer heads, 8 per group
     ("cfg1", dict(n_q_heads=8, context=500, budget=140, decode_steps=3)),    # 2 indexer heads, 1 per group
     ("cfg1", dict(batch=64, n_kv_heads=2, n_q_heads=8, context=150, budget=40, decode_steps=2)),   # the largest batch
-    ("cfg1", dict(batch=11, context=260, budget=4, decode_steps=3)),         # budget = the sinks alone
+    ("cfg1", dict(batch=11, context=260, budget=4, decode_steps=3)),         # budget = the sinks alone; projection blocks of 8 + 3 batch rows
+    ("cfg1", dict(batch=5, context=200, budget=48, decode_steps=2)),         # projection blocks of 4 + 1 batch rows
+    ("cfg1", dict(batch=12, n_kv_heads=2, n_q_heads=8, context=150, budget=40, decode_steps=2)),   # three blocks of 4 batch rows
 ])
 def test_reduced_configurations_fused_decode(name, kw):
     w = WORKLOADS[name].scaled(n_layers=1, **kw)
