@@ -118,6 +118,8 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
   const dec_u4 v = __builtin_nontemporal_load((const dec_u4*)p);
   return make_uint4(v.x, v.y, v.z, v.w);
 }
+// wait until at most 4 of this wave's vector memory loads are outstanding (loads return in order)
+__device__ __forceinline__ void dec_pace4() { asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); }
 
 __device__ __forceinline__ void unpack8(const uint4& u, float* f) {
   f[0] = bf_lo(u.x); f[1] = bf_hi(u.x); f[2] = bf_lo(u.y); f[3] = bf_hi(u.y);
@@ -863,6 +865,10 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     DEC_STAMP_AT(15, 256);
   } else {
     // ================= attention waves: issue the K, Q and V loads =================
+    // Five groups of 4 loads per lane (K tile 0, K tile 1, Q, V tile 0, V tile 1), paced: a group goes out
+    // when all but the last 4 loads before it have arrived, so a lane has at most 8 in flight.  With every
+    // workgroup of the launch resident at once, issuing all 20 at the start oversubscribes the memory queues
+    // (measured at configuration 3: 0.832 ms per step unpaced, 0.821 paced; stricter pacing loses again).
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
       const int kr = min(16 * (2 * wl + tt) + l16, nk - 1);
@@ -870,13 +876,15 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
 #pragma unroll
       for (int c = 0; c < 4; ++c) kf[tt][c] = load_stream16(krow + 32 * c + 8 * kq);
     }
+    dec_pace4();
     {
-      const int jq = min(l16, G - 1);   // lanes past the group read its last head; masked below
+      // lanes past the group read its last head; they are zeroed where the fragments are used (zeroing a
+      // register here would wait for its load, and with it for every load issued before it)
+      const int jq = min(l16, G - 1);
 #pragma unroll
-      for (int c = 0; c < 4; ++c) {
+      for (int c = 0; c < 4; ++c)
         qf[c] = *(const uint4*)(a.q + ((size_t)b * a.H + h * G + jq) * IM_D + 32 * c + 8 * kq);
-        if (l16 >= G) qf[c] = make_uint4(0, 0, 0, 0);
-      }
+      dec_pace4();
     }
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
@@ -886,6 +894,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         const bf16_t* vrow = (MERGED && k0 + vr == n_old) ? a.v_new + (size_t)u * IM_D : a.V + (base + vr) * IM_D;
         vf[tt][i] = load_stream16(vrow + 8 * l16);
       }
+      if (tt == 0) dec_pace4();
     }
     // without scoring waves, split 0's attention waves look after the one key beyond the splits
     // (wave wl: dims 32 wl .. 32 wl + 31 of its logits; wave 0: its rows for the last-slot record)
@@ -957,7 +966,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       v4f acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int c = 0; c < 4; ++c) {
-        const uint4 ka = kf[tt][c], qb = qf[c];
+        const uint4 ka = kf[tt][c], qb = (l16 < G) ? qf[c] : make_uint4(0, 0, 0, 0);
         const v4s a0 = __builtin_bit_cast(v4s, make_uint2(ka.x, ka.y));
         const v4s a1 = __builtin_bit_cast(v4s, make_uint2(ka.z, ka.w));
         const v4s b0 = __builtin_bit_cast(v4s, make_uint2(qb.x, qb.y));
