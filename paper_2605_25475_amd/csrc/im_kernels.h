@@ -575,6 +575,91 @@ __global__ __launch_bounds__(256) void k_score(const bf16_t* __restrict__ Kidx,
   }
 }
 
+// a1 (iii) for a few queries (a decode step: fewer queries than indexer heads; Section 3.1, Eq. (5)).
+// Here the 16 columns of the 16x16x4 product are the indexer HEADS of one query (H_idx <= 16; absent
+// heads carry a zero gate), so one pass over the DI dims gives a tile of 16 keys its similarities to
+// all heads; the gated ReLU terms of a key then sit in the 16 lanes of a row and meet by four
+// rotations.  grid (ceil(max_live / 64), units), 4 waves, one tile of 16 keys per wave.
+template <int DI>
+__global__ __launch_bounds__(256) void k_score_few(const bf16_t* __restrict__ Kidx,
+                                                   const int32_t* __restrict__ pos,
+                                                   const int32_t* __restrict__ len,
+                                                   int32_t* __restrict__ n_projected,
+                                                   const double* __restrict__ qhat,
+                                                   const double* __restrict__ alpha,
+                                                   const int32_t* __restrict__ q_pos, int n_q, int H_kv,
+                                                   int C, int H_idx, int max_live,
+                                                   float* __restrict__ scores) {
+  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int l16 = lane & 15, kq = lane >> 4;
+  const int b = unit / H_kv;
+  const int n = min(len[unit], max_live);
+  if (blockIdx.x == 0 && tid == 0) n_projected[unit] = n;  // the projection kernel ran before
+  const int kbase = blockIdx.x * 64 + 16 * w;
+  if (kbase >= n) return;
+  constexpr int WPL = DI / 8, DPL = DI / 4;
+  // A operand: lane (row l16, kq) holds dims DPL kq .. DPL kq + DPL - 1 of key kbase + l16 (rows past the
+  // end repeat the last live one; their scores are never written)
+  uint32_t ka[WPL];
+  {
+    const size_t row = (size_t)unit * C + min(kbase + l16, n - 1);
+    if constexpr (DI == 64) {
+      const uint4 u0 = *(const uint4*)(Kidx + row * DI + DPL * kq);
+      const uint4 u1 = *(const uint4*)(Kidx + row * DI + DPL * kq + 8);
+      ka[0] = u0.x; ka[1] = u0.y; ka[2] = u0.z; ka[3] = u0.w;
+      ka[4] = u1.x; ka[5] = u1.y; ka[6] = u1.z; ka[7] = u1.w;
+    } else {
+      static_assert(DI == 16, "indexer head dim 64 or 16");
+      const uint2 u0 = *(const uint2*)(Kidx + row * DI + DPL * kq);
+      ka[0] = u0.x; ka[1] = u0.y;
+    }
+  }
+  int posk[4];   // positions of the keys of this lane's result registers (row 4 r + kq)
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int key = kbase + 4 * r + kq;
+    const int p = pos[(size_t)unit * C + min(key, n - 1)];
+    posk[r] = (key < n) ? p : INT_MAX;
+  }
+  const bool hv = l16 < H_idx;
+  const int jh = hv ? l16 : 0;
+  float imp[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+#pragma unroll 1
+  for (int s = 0; s < n_q; ++s) {
+    // B operand: lane (column l16 = head, kq) holds dims DPL kq .. of head l16 of query s
+    double qd[DPL];
+    {
+      const uint4* src = (const uint4*)(qhat + (((size_t)b * n_q + s) * H_idx + jh) * DI + DPL * kq);
+#pragma unroll
+      for (int m = 0; m < DPL / 2; ++m) {
+        const uint4 u = src[m];
+        qd[2 * m] = __longlong_as_double(((long long)u.y << 32) | u.x);
+        qd[2 * m + 1] = __longlong_as_double(((long long)u.w << 32) | u.z);
+      }
+    }
+    const double al_in = alpha[((size_t)b * n_q + s) * H_idx + jh];
+    const int qp = q_pos[(size_t)b * n_q + s];
+    const double al = hv ? al_in : 0.0;   // (an absent head's column repeats head 0 and is gated off)
+    im_v4d z = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int m = 0; m < DPL; ++m) {
+      const uint32_t wd = ka[m >> 1];
+      const float f = (m & 1) ? bf_hi(wd) : bf_lo(wd);
+      z = __builtin_amdgcn_mfma_f64_16x16x4f64((double)f, qd[m], z, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const double sum = row16_sum_d(al * fmax(z[r], 0.0));   // over the heads, in every lane of the row
+      imp[r] = (posk[r] <= qp) ? fmaxf(imp[r], (float)sum) : imp[r];
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int key = kbase + 4 * r + kq;
+    if (l16 == 0 && key < n) scores[(size_t)unit * C + key] = imp[r];
+  }
+}
+
 // scores[unit][key] = max over the query groups' partial maxima.  grid (ceil(max_live/256), units)
 __global__ __launch_bounds__(256) void k_score_max(const float* __restrict__ part, int groups,
                                                    const int32_t* __restrict__ len, int C, int max_live,

@@ -353,6 +353,19 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
   const int rows = M * c.n_idx_heads;
   k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, di, (const bf16_t*)p->norm_q_w, c.rms_eps);
   k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, sqrt((double)(c.n_idx_heads * di)));
+  // fewer queries than indexer heads (a decode step): the heads of a query are the product's columns
+  if (n_q < c.n_idx_heads && c.n_idx_heads <= 16) {
+    const dim3 grid((h->max_live + 63) / 64, units);
+    if (c.head_shared)
+      k_score_few<IM_DI_SHARED><<<grid, 256, 0, s>>>((const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al,
+                                                     q_pos, n_q, c.n_kv_heads / heads_per_set(c), c.capacity,
+                                                     c.n_idx_heads, h->max_live, scores_out);
+    else
+      k_score_few<IM_DI><<<grid, 256, 0, s>>>((const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al,
+                                              q_pos, n_q, c.n_kv_heads / heads_per_set(c), c.capacity,
+                                              c.n_idx_heads, h->max_live, scores_out);
+    return launch_check(h, "im_index_score");
+  }
   // a launch over a short cache has few (256-key tile, unit) workgroups: its queries then go in up
   // to IM_SCORE_GROUPS groups with workgroups of their own (partial maxima in the workspace,
   // folded by k_score_max); a very short one also drops to 16 keys per wave

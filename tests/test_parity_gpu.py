@@ -64,6 +64,8 @@ def test_reduced_configurations_fused_decode(name, kw):
     ("cfg4", dict(batch=2, context=700, budget=130, decode_steps=128), 128, 1),      # the paper's tau
     ("cfg3", dict(batch=1, context=900, budget=300, decode_steps=48), 24, 2),
     ("cfg1", dict(context=500, budget=200, decode_steps=114), 57, 2),    # live bound 257: one key beyond the splits
+    ("cfg1", dict(batch=2, context=300, budget=100, decode_steps=15), 5, 3),    # 5 queries < 8 indexer heads: the few-query scoring kernel
+    ("cfg4", dict(batch=2, context=300, budget=70, decode_steps=12), 6, 2),     # 6 queries < 7 heads
 ])
 @pytest.mark.parametrize("fused", [True, False])
 def test_periodic_compression_schedule(name, kw, tau, n_win, fused):
@@ -328,6 +330,7 @@ def test_head_shared_layout_fused_decode(name, kw):
     ("cfg1", dict(context=600, budget=200, decode_steps=96), 32, 3),
     ("cfg4", dict(batch=2, context=700, budget=130, decode_steps=128), 128, 1),      # the paper's tau
     ("cfg1", dict(batch=2, context=500, budget=200, decode_steps=114), 57, 2),       # live bound 257: one key beyond the splits
+    ("cfg1", dict(batch=2, context=300, budget=100, decode_steps=15), 5, 3),         # 5 queries < 8 indexer heads: the few-query scoring kernel
 ])
 @pytest.mark.parametrize("fused", [True, False])
 def test_head_shared_layout_periodic_schedule(name, kw, tau, n_win, fused):
