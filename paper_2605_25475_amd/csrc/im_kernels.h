@@ -692,6 +692,33 @@ __device__ __forceinline__ unsigned block_excl_scan_1024(bool flag, unsigned* ws
   return off + inwave;
 }
 
+// Of 256 bins, the first one (from bin 255 downwards if DESC, else from bin 0 upwards) at which the running
+// count reaches rem (1 <= rem <= the total): its index, the count before it, and its own count, left in
+// sh[0..2].  A scan by the first 4 waves of the workgroup (a serial walk over the bins by one thread cost
+// ~10 us per radix pass).  All threads of the workgroup call it.
+template <bool DESC>
+__device__ __forceinline__ void select_pick_bin(const unsigned* hist, unsigned rem, unsigned* wtot, unsigned* sh) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int bin = DESC ? 255 - tid : tid;
+  unsigned v = 0, incl = 0;
+  if (tid < 256) {
+    v = hist[bin];
+    incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned t = __shfl_up(incl, o, 64);
+      if (lane >= o) incl += t;
+    }
+    if (lane == 63) wtot[w] = incl;
+  }
+  __syncthreads();
+  if (tid < 256) {
+    for (int i = 0; i < w; ++i) incl += wtot[i];
+    if (incl >= rem && incl - v < rem) { sh[0] = (unsigned)bin; sh[1] = incl - v; sh[2] = v; }
+  }
+  __syncthreads();
+}
+
 // grid (units), 1024 threads
 __global__ __launch_bounds__(1024) void k_select(const float* __restrict__ scores,
                                                  const int32_t* __restrict__ pos,
@@ -702,7 +729,7 @@ __global__ __launch_bounds__(1024) void k_select(const float* __restrict__ score
                                                  int32_t* __restrict__ n_keep,
                                                  int32_t* __restrict__ n_evict) {
   __shared__ unsigned hist[256];
-  __shared__ unsigned sh_prefix, sh_rem, sh_cnt;
+  __shared__ unsigned sh_prefix, sh_rem, sh_cnt, sh_pick[3];
   __shared__ int sh_red[16];
   __shared__ unsigned wsum[16];
   const int unit = blockIdx.x, tid = threadIdx.x;
@@ -748,16 +775,12 @@ __global__ __launch_bounds__(1024) void k_select(const float* __restrict__ score
         if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
       }
       __syncthreads();
+      const unsigned rem = sh_rem;
+      select_pick_bin<true>(hist, rem, wsum, sh_pick);
       if (tid == 0) {
-        unsigned rem = sh_rem, cum = 0;
-        int d = 255;
-        for (; d > 0; --d) {
-          if (cum + hist[d] >= rem) break;
-          cum += hist[d];
-        }
-        sh_prefix = prefix | ((uint32_t)d << shift);
-        sh_rem = rem - cum;
-        sh_cnt = hist[d];
+        sh_prefix = prefix | (sh_pick[0] << shift);
+        sh_rem = rem - sh_pick[1];
+        sh_cnt = sh_pick[2];
       }
       mask |= 255u << shift;
       __syncthreads();
@@ -780,15 +803,11 @@ __global__ __launch_bounds__(1024) void k_select(const float* __restrict__ score
           if ((pk & mask) == prefix) atomicAdd(&hist[(pk >> shift) & 255u], 1u);
         }
         __syncthreads();
+        const unsigned r = sh_rem;
+        select_pick_bin<false>(hist, r, wsum, sh_pick);
         if (tid == 0) {
-          unsigned r = sh_rem, cum = 0;
-          int d = 0;
-          for (; d < 255; ++d) {
-            if (cum + hist[d] >= r) break;
-            cum += hist[d];
-          }
-          sh_prefix = prefix | ((uint32_t)d << shift);
-          sh_rem = r - cum;
+          sh_prefix = prefix | (sh_pick[0] << shift);
+          sh_rem = r - sh_pick[1];
         }
         mask |= 255u << shift;
         __syncthreads();
