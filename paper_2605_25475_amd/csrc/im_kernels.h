@@ -91,6 +91,17 @@ __device__ __forceinline__ double row16_ror_d(double v) {   // value of the lane
   const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), 0x120 + N, 0xF, 0xF, false);
   return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
+template <int N>
+__device__ __forceinline__ float row16_ror_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float row16_sum_f(float v) {
+  v += row16_ror_f<1>(v);
+  v += row16_ror_f<2>(v);
+  v += row16_ror_f<4>(v);
+  v += row16_ror_f<8>(v);
+  return v;
+}
 // sum over the 16 lanes of a row, in every lane (rotations of 1, 2, 4, 8)
 __device__ __forceinline__ double row16_sum_d(double v) {
   v += row16_ror_d<1>(v);
@@ -1175,7 +1186,7 @@ __global__ __launch_bounds__(256) void k_compact(bf16_t* __restrict__ K, bf16_t*
 // ------------------------------------------------------------------------------------------
 // a5: split-K decode attention, then the combine with the gated memory readout
 // ------------------------------------------------------------------------------------------
-#define IM_ATT_CHUNK 256
+#define IM_ATT_CHUNK 128   // keys per workgroup: 32 per wave
 #define IM_ATT_REC (IM_D + 2)  // partial record: running max, denominator, 128 numerators
 
 // grid (chunks, units).  16 lanes share a key row (8 dims each); a wave handles 4 keys at a time.
@@ -1212,47 +1223,47 @@ __global__ __launch_bounds__(256) void k_attn_partial(const bf16_t* __restrict__
   }
   const bf16_t* Kb = K + (size_t)unit * C * IM_D;
   const bf16_t* Vb = V + (size_t)unit * C * IM_D;
-  for (int it = 0; it < 16; ++it) {
-    const int key = k0 + w * 64 + it * 4 + grp;
-    const bool valid = key < n;
-    const int kc = valid ? key : n - 1;
-    const uint4 ku = *(const uint4*)(Kb + (size_t)kc * IM_D + l16 * 8);
-    const uint4 vu = *(const uint4*)(Vb + (size_t)kc * IM_D + l16 * 8);
-    const float kf[8] = {bf_lo(ku.x), bf_hi(ku.x), bf_lo(ku.y), bf_hi(ku.y),
-                         bf_lo(ku.z), bf_hi(ku.z), bf_lo(ku.w), bf_hi(ku.w)};
-    const float vf[8] = {bf_lo(vu.x), bf_hi(vu.x), bf_lo(vu.y), bf_hi(vu.y),
-                         bf_lo(vu.z), bf_hi(vu.z), bf_lo(vu.w), bf_hi(vu.w)};
+  // 4 keys of the 16-lane row per round: their 8 loads go out together, ahead of the arithmetic
+#pragma unroll 1
+  for (int it0 = 0; it0 < IM_ATT_CHUNK / 16; it0 += 4) {
+    uint4 ku[4], vu[4];
 #pragma unroll
-    for (int j = 0; j < G; ++j) {
-      float s = 0.f;
+    for (int i = 0; i < 4; ++i) {
+      const int kc = min(k0 + w * (IM_ATT_CHUNK / 4) + (it0 + i) * 4 + grp, n - 1);
+      ku[i] = *(const uint4*)(Kb + (size_t)kc * IM_D + l16 * 8);
+      vu[i] = *(const uint4*)(Vb + (size_t)kc * IM_D + l16 * 8);
+    }
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s = fmaf(qf[j][e], kf[e], s);
-      s += __shfl_xor(s, 1, 64); s += __shfl_xor(s, 2, 64);
-      s += __shfl_xor(s, 4, 64); s += __shfl_xor(s, 8, 64);
-      if (!valid) s = -INFINITY;
-      const float mn = fmaxf(mx[j], s);
-      const float corr = __expf(mx[j] - mn), p = __expf(s - mn);
-      ls[j] = fmaf(ls[j], corr, p);
+    for (int i = 0; i < 4; ++i) {
+      const bool valid = k0 + w * (IM_ATT_CHUNK / 4) + (it0 + i) * 4 + grp < n;
+      const float kf[8] = {bf_lo(ku[i].x), bf_hi(ku[i].x), bf_lo(ku[i].y), bf_hi(ku[i].y),
+                           bf_lo(ku[i].z), bf_hi(ku[i].z), bf_lo(ku[i].w), bf_hi(ku[i].w)};
+      const float vf[8] = {bf_lo(vu[i].x), bf_hi(vu[i].x), bf_lo(vu[i].y), bf_hi(vu[i].y),
+                           bf_lo(vu[i].z), bf_hi(vu[i].z), bf_lo(vu[i].w), bf_hi(vu[i].w)};
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(acc[j][e], corr, p * vf[e]);
-      mx[j] = mn;
+      for (int j = 0; j < G; ++j) {
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s = fmaf(qf[j][e], kf[e], s);
+        s = row16_sum_f(s);   // (DPP rotations inside the 16-lane row)
+        if (!valid) s = -INFINITY;
+        const float mn = fmaxf(mx[j], s);
+        const float corr = __expf(mx[j] - mn), p = __expf(s - mn);
+        ls[j] = fmaf(ls[j], corr, p);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(acc[j][e], corr, p * vf[e]);
+        mx[j] = mn;
+      }
     }
   }
-  // merge the 4 key streams of the wave
+  // merge the 4 key streams of the wave (the same lane of the four 16-lane rows)
 #pragma unroll
   for (int j = 0; j < G; ++j) {
-    float m = mx[j];
-    m = fmaxf(m, __shfl_xor(m, 16, 64));
-    m = fmaxf(m, __shfl_xor(m, 32, 64));
+    const float m = rows_max_f(mx[j]);
     const float sc = __expf(mx[j] - m);
-    float l = ls[j] * sc;
-    l += __shfl_xor(l, 16, 64); l += __shfl_xor(l, 32, 64);
+    const float l = rows_sum_f(ls[j] * sc);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float a = acc[j][e] * sc;
-      a += __shfl_xor(a, 16, 64); a += __shfl_xor(a, 32, 64);
-      acc[j][e] = a;
-    }
+    for (int e = 0; e < 8; ++e) acc[j][e] = rows_sum_f(acc[j][e] * sc);
     if (grp == 0) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) s_acc[w][j][l16 * 8 + e] = acc[j][e];
@@ -1296,9 +1307,21 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
   const int n = min(len[unit], max_live);
   const int nch = min((n + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK, n_chunks);
   const float* rec = part + (size_t)bh * n_chunks * IM_ATT_REC;
+  // the loads that depend on nothing go out first: q, this thread's row of W_theta, b, w_g
+  const float qd = bf2f(q[(size_t)bh * IM_D + tid]);
+  uint4 wrow[16];
+  {
+    const uint4* wr = (const uint4*)(Wtheta + tid * IM_D);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) wrow[i] = wr[i];
+  }
+  const float bv = bvec[(size_t)unit * IM_DM + tid];
+  const float wgv = bf2f(wg[tid]);
   float m = -1e30f;
+#pragma unroll 4
   for (int c = 0; c < nch; ++c) m = fmaxf(m, rec[(size_t)c * IM_ATT_REC]);
   float o = 0.f, l = 0.f;
+#pragma unroll 4
   for (int c = 0; c < nch; ++c) {
     const float sc = __expf(rec[(size_t)c * IM_ATT_REC] - m);
     o = fmaf(sc, rec[(size_t)c * IM_ATT_REC + 2 + tid], o);
@@ -1306,24 +1329,20 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
   }
   const float o_attn = (nch > 0) ? o / l : 0.f;
   // memory readout
-  const float qd = bf2f(q[(size_t)bh * IM_D + tid]);
   qs[tid] = qd;
   __syncthreads();
   float ph = 0.f;
-  {
-    const uint4* wr = (const uint4*)(Wtheta + tid * IM_D);
-#pragma unroll 4
-    for (int i = 0; i < 16; ++i) {
-      const uint4 u = wr[i];
-      ph = fmaf(bf_lo(u.x), qs[8 * i + 0], ph); ph = fmaf(bf_hi(u.x), qs[8 * i + 1], ph);
-      ph = fmaf(bf_lo(u.y), qs[8 * i + 2], ph); ph = fmaf(bf_hi(u.y), qs[8 * i + 3], ph);
-      ph = fmaf(bf_lo(u.z), qs[8 * i + 4], ph); ph = fmaf(bf_hi(u.z), qs[8 * i + 5], ph);
-      ph = fmaf(bf_lo(u.w), qs[8 * i + 6], ph); ph = fmaf(bf_hi(u.w), qs[8 * i + 7], ph);
-    }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const uint4 u = wrow[i];
+    ph = fmaf(bf_lo(u.x), qs[8 * i + 0], ph); ph = fmaf(bf_hi(u.x), qs[8 * i + 1], ph);
+    ph = fmaf(bf_lo(u.y), qs[8 * i + 2], ph); ph = fmaf(bf_hi(u.y), qs[8 * i + 3], ph);
+    ph = fmaf(bf_lo(u.z), qs[8 * i + 4], ph); ph = fmaf(bf_hi(u.z), qs[8 * i + 5], ph);
+    ph = fmaf(bf_lo(u.w), qs[8 * i + 6], ph); ph = fmaf(bf_hi(u.w), qs[8 * i + 7], ph);
   }
   phi[tid] = ph;
-  float den = wave_sum_f(ph * ph * bvec[(size_t)unit * IM_DM + tid]);
-  float gz = wave_sum_f(bf2f(wg[tid]) * qd);
+  float den = wave_sum_f(ph * ph * bv);
+  float gz = wave_sum_f(wgv * qd);
   if ((tid & 63) == 0) { red[tid >> 6][0] = den; red[tid >> 6][1] = gz; }
   __syncthreads();
   den = red[0][0] + red[1][0] + mem_eps;
@@ -1331,7 +1350,7 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
   const float gate = 1.f / (1.f + __expf(-gz));
   const float* Mu = M + (size_t)unit * IM_DM * IM_D;
   float mr = 0.f;
-#pragma unroll 8
+#pragma unroll 16
   for (int c = 0; c < IM_DM; ++c) mr = fmaf(phi[c], Mu[c * IM_D + tid], mr);
   const float res = gate * (mr / den);
   out[(size_t)bh * IM_D + tid] = f2bf_rne(o_attn + res);
