@@ -869,6 +869,8 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     // when all but the last 4 loads before it have arrived, so a lane has at most 8 in flight.  With every
     // workgroup of the launch resident at once, issuing all 20 at the start oversubscribes the memory queues
     // (measured at configuration 3: 0.832 ms per step unpaced, 0.821 paced; stricter pacing loses again).
+    // Without scoring waves in the workgroup one wait, behind the Q group, does best (the periodic schedule:
+    // 0.699 ms per step unpaced, 0.697 with all three waits, 0.688 with this one).
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
       const int kr = min(16 * (2 * wl + tt) + l16, nk - 1);
@@ -876,7 +878,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
 #pragma unroll
       for (int c = 0; c < 4; ++c) kf[tt][c] = load_stream16(krow + 32 * c + 8 * kq);
     }
-    dec_pace4();
+    if constexpr (SCORE) dec_pace4();
     {
       // lanes past the group read its last head; they are zeroed where the fragments are used (zeroing a
       // register here would wait for its load, and with it for every load issued before it)
@@ -894,7 +896,7 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         const bf16_t* vrow = (MERGED && k0 + vr == n_old) ? a.v_new + (size_t)u * IM_D : a.V + (base + vr) * IM_D;
         vf[tt][i] = load_stream16(vrow + 8 * l16);
       }
-      if (tt == 0) dec_pace4();
+      if (SCORE && tt == 0) dec_pace4();
     }
     // without scoring waves, split 0's attention waves look after the one key beyond the splits
     // (wave wl: dims 32 wl .. 32 wl + 31 of its logits; wave 0: its rows for the last-slot record)
