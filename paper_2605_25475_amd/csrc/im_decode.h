@@ -1900,7 +1900,7 @@ __global__ __launch_bounds__(DEC_MT, 4) void k_dec_main(const DecArgs a, const d
 
 // the attend-only variant: same grid, 4 waves per workgroup
 template <int G>
-__global__ __launch_bounds__(DEC_MT / 2, G <= 4 ? 4 : 2) void k_att_main(const DecArgs a) {
+__global__ __launch_bounds__(DEC_MT / 2, G <= 4 ? 3 : 2) void k_att_main(const DecArgs a) {
   __shared__ __attribute__((aligned(16))) DecSplitSmem sm;
   const int U = a.B * a.H_kv;
   dec_split<G, false>(a, blockIdx.x % U, blockIdx.x / U, sm, nullptr, nullptr);
