@@ -639,7 +639,7 @@ struct DecSplitSmem {
 // last-ranked entry while the K / V rows are still arriving.  The two roles meet at the first
 // workgroup barrier, when the attention waves have issued their loads.
 // SCORE = false is the attend-only step: no scoring waves (the workgroup is the 4 attention waves
-// alone, so twice as many fit on a CU), nothing is left out of the partial.
+// alone, so more of them fit on a CU), nothing is left out of the partial.
 // MERGED: the launch also holds the prep roles, so the new token's rows come from the inputs.
 template <int G, bool SCORE, bool MERGED = false>
 __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const int s, DecSplitSmem& sm,
