@@ -26,6 +26,23 @@ def test_cfg4_shape_full_context_sampled_units():
     ls.run_schedule(fused_decode=True)
 
 
+def test_cfg4_full_batch_sampled_units():
+    # the benchmark's own launch configuration of configuration 4: batch 16 x 4 KV heads (projection blocks
+    # of 8 batch rows, the per-unit tail: 64 units x 7 heads do not fit the chip once)
+    w = WORKLOADS["cfg4"].scaled(n_layers=1, decode_steps=3)
+    ls = LockStep(w, gen_device="cuda", batch_ids=[11], kv_heads=[1, 2])
+    ls.run_schedule(fused_decode=True)
+
+
+def test_cfg3_full_size_periodic_schedule_sampled_units():
+    # the paper's decode schedule at the benchmark's size: 128 attend-only steps (two launches each, 2049 ..
+    # 2176 live entries), then one compression event with the interval's 128 queries
+    w = WORKLOADS["cfg3"].scaled(n_layers=1, decode_steps=128)
+    ls = LockStep(w, gen_device="cuda", batch_ids=[2], kv_heads=[0, 7], capacity=w.context,
+                  max_queries=w.context)
+    ls.run_window_schedule(128, 1, fused=True)
+
+
 def test_cfg2_full_size_sampled_units():
     w = WORKLOADS["cfg2"].scaled(n_layers=1, decode_steps=6)
     ls = LockStep(w, gen_device="cuda", batch_ids=[0, 5], kv_heads=[1, 6])
