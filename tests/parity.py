@@ -180,7 +180,7 @@ class LockStep:
         self.gpu.follow_event(d(k_new), d(v_new), d(pos), d(q_attn), leader.gpu, w.lam, w.eta)
         torch.cuda.synchronize()
         bi = self.batch_ids
-        bi_t = torch.tensor(bi); hs_t = torch.tensor(self.kv_heads)
+        bi_t = torch.tensor(bi, device=k_new.device); hs_t = torch.tensor(self.kv_heads, device=k_new.device)
         sel = lambda x: f64(x.index_select(0, bi_t).index_select(1, hs_t))
         self.ref.append_kv(sel(k_new), sel(v_new), pos.numpy()[bi])
         keep = self._keep_from(evict)
@@ -199,7 +199,7 @@ class LockStep:
         self.gpu.follow_step(d(k_new), d(v_new), d(pos), d(q), leader.gpu.evicted, w.lam, w.eta, debug=True)
         torch.cuda.synchronize()
         bi = self.batch_ids
-        bi_t = torch.tensor(bi); hs_t = torch.tensor(self.kv_heads)
+        bi_t = torch.tensor(bi, device=k_new.device); hs_t = torch.tensor(self.kv_heads, device=k_new.device)
         sel = lambda x: f64(x.index_select(0, bi_t).index_select(1, hs_t))
         self.ref.append_kv(sel(k_new), sel(v_new), pos.numpy()[bi].reshape(-1, 1))
         keep = self._keep_from(evict)

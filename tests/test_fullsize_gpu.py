@@ -5,7 +5,10 @@ units (they are independent) through the same events and every observable of tho
 compared to the usual bars.  Configuration 4's head shape (7 query heads per KV head, 7 indexer
 heads) gets the same treatment at a reduced batch; configuration 2 (batch 8, 4096 -> 1024) and
 configuration 5 (one sequence of 131072 tokens in 32 chunks of 4096, running cache evicted to
-4096 after every chunk) run one layer at their stated sizes."""
+4096 after every chunk) run one layer at their stated sizes; configuration 4 also at its own batch
+of 16.  The other decode paths of the benchmark run at configuration 3's size as well: the periodic
+schedule (128 attend-only steps, then one compression event) and a leader / follower pair of an
+index-sharing group."""
 import pytest
 
 from parity import LockStep, LockStepShared
@@ -41,6 +44,23 @@ def test_cfg3_full_size_periodic_schedule_sampled_units():
     ls = LockStep(w, gen_device="cuda", batch_ids=[2], kv_heads=[0, 7], capacity=w.context,
                   max_queries=w.context)
     ls.run_window_schedule(128, 1, fused=True)
+
+
+def test_cfg3_full_size_index_reuse_sampled_units():
+    # two layers of an index-sharing group at the benchmark's size: layer 1 applies layer 0's lists at the
+    # prefill event and layer 0's evicted slot at every decode step (its two-launch follower step)
+    import paper_2605_25475_amd as im
+    w = WORKLOADS["cfg3"].scaled(n_layers=2, decode_steps=4)
+    kw = dict(gen_device="cuda", batch_ids=[0], kv_heads=[4, 6])
+    lead, foll = LockStep(w, layer=0, **kw), LockStep(w, layer=1, **kw)
+    _, _, evict, _, _ = lead.event(0, w.context, w.budget, "leader prefill")
+    foll.follow_event(0, w.context, lead, evict, "follower prefill")
+    for ls in (lead, foll):
+        im.im_set_max_live(ls.handle, w.budget + 1)
+    for t in range(w.context, w.context + w.decode_steps):
+        _, _, evict, _, _ = lead.event_fused(t, w.budget, f"leader decode@{t}")
+        foll.follow_step(t, lead, evict, f"follower decode@{t}")
+    assert im.im_query_status(lead.handle) == 0 and im.im_query_status(foll.handle) == 0
 
 
 def test_cfg2_full_size_sampled_units():
