@@ -17,8 +17,10 @@ indexer keys are stored in bf16, query features / head gates / scores in fp32, t
 output in bf16, the memory state in fp32 (rounded only when compared).
 
 Every function below is pinned by tests/test_oracle_pins.py against closed forms, invariants,
-brute force and library routines; none is "parity unpinned".  The paper prints no worked
-numeric example, so there are no golden values of the paper's to compare with.
+brute force, scalar loops and library routines (read_gate and fuse on random inputs with gates
+strictly inside (0, 1); a layer that follows a subset of KV heads against the same heads of a
+full layer); none is "parity unpinned".  The paper prints no worked numeric example, so there
+are no golden values of the paper's to compare with.
 """
 from __future__ import annotations
 

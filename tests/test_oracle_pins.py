@@ -308,6 +308,77 @@ def test_empty_memory_reads_zero_and_closed_gate_falls_back_to_attention():
     assert np.all(g1 == 0.5)
 
 
+@pytest.mark.parametrize("cg", [0.0, 1.5, -1.5])
+def test_read_gate_is_the_logistic_of_the_weighted_query(cg):
+    # g(q) in [0, 1] (Section 3.2, "Readout as residual compensation"): sigmoid(w_g . q + c_g), one
+    # value per query head.  Weights large enough that the w_g . q term moves the gate far from 0.5.
+    q = bf(RNG.standard_normal((5, 128)))
+    wg = bf(RNG.standard_normal(128) * 0.15)
+    got = O.read_gate(q, wg, cg)
+    assert got.shape == (5,)
+    for r in range(5):   # scalar loop, term by term
+        z = cg
+        for d in range(128):
+            z += wg[d] * q[r, d]
+        assert abs(got[r] - 1.0 / (1.0 + math.exp(-z))) <= 1e-14
+    want = torch.sigmoid(torch.nn.functional.linear(torch.tensor(q), torch.tensor(wg)[None]) + cg)[:, 0].numpy()
+    assert np.allclose(got, want, rtol=0, atol=1e-14)
+    assert np.ptp(got) > 0.2                       # the heads' gates differ: the query term is at work
+    # reflecting the query reflects the gate around the bias' own value
+    assert np.allclose(got + O.read_gate(-q, wg, -cg), 1.0, atol=1e-14)
+
+
+@pytest.mark.parametrize("gval", [0.25, 1.0])
+def test_fuse_adds_the_gated_readout_once_and_rounds_once(gval):
+    # Eq. latent_residual_fuse: o = o_attn + g(q) m(q), per element; stored in bf16, the residual in fp32
+    o = RNG.standard_normal((3, 128)); m = RNG.standard_normal((3, 128)) * 0.3
+    gate = np.array([gval, gval * 0.5, gval])
+    out, res = O.fuse(o, gate, m)
+    for r in range(3):
+        for d in range(128):
+            exact = o[r, d] + gate[r] * m[r, d]
+            assert out[r, d] == bf(out[r, d])[()]                                 # a bf16 value ...
+            assert abs(out[r, d] - exact) <= 2.0 ** -8 * abs(exact) + 1e-300     # ... half an ulp from the sum at most
+            assert res[r, d] == float(np.float32(gate[r] * m[r, d]))
+    # linear in the gate: twice the gate doubles the residual (a squared gate would quadruple it)
+    _, res2 = O.fuse(o, 2.0 * gate, m)
+    assert np.allclose(res2, 2.0 * res, rtol=1e-6)
+    # the bf16 result is the rounding of the exact sum, not of separately rounded terms
+    want = torch.tensor(o + gate[:, None] * m, dtype=torch.float64).to(torch.float32)
+    exact_in_f32 = want.to(torch.float64).numpy() == (o + gate[:, None] * m)
+    assert np.array_equal(out[exact_in_f32], want.to(torch.bfloat16).to(torch.float64).numpy()[exact_in_f32])
+
+
+def test_layer_on_a_subset_of_kv_heads_reproduces_those_heads_of_the_full_layer():
+    # the full-size GPU tests let the oracle follow a few KV heads (kv_head_ids): local index hi then stands
+    # for global head heads[hi], whose g query heads are heads[hi] g .. heads[hi] g + g - 1
+    w, K, V, Q = _small_layer(context=72, budget=24, steps=3)
+    heads = [2, 5]
+    full = make_oracle_layer(w)
+    sub = make_oracle_layer(w, kv_head_ids=heads)
+    L = w.context
+
+    def both(t0, t1):
+        pos = np.tile(np.arange(t0, t1, dtype=np.int32), (w.batch, 1))
+        q = Q[:, t0:t1]
+        xg = q.reshape(w.batch, t1 - t0, -1)
+        rf = full.step(K[:, :, t0:t1], V[:, :, t0:t1], pos, q, xg, pos, Q[:, t1 - 1], w.budget, w.lam, w.eta)
+        rs = sub.step(K[:, heads, t0:t1], V[:, heads, t0:t1], pos, q, xg, pos, Q[:, t1 - 1], w.budget, w.lam, w.eta)
+        return rf, rs
+
+    for t0, t1 in [(0, L)] + [(t, t + 1) for t in range(L, L + w.decode_steps)]:
+        (sf, kf, ef, of, rf), (ss, ks, es, os_, rs) = both(t0, t1)
+        for hi, h in enumerate(heads):
+            for bi in range(w.batch):
+                assert np.array_equal(sf[bi, h], ss[bi, hi], equal_nan=True)
+                assert np.array_equal(kf[bi][h], ks[bi][hi]) and np.array_equal(ef[bi][h], es[bi][hi])
+                assert np.array_equal(of[bi, h], os_[bi, hi]) and np.array_equal(rf[bi, h], rs[bi, hi])
+                assert np.array_equal(full.M[bi, h], sub.M[bi, hi]) and np.array_equal(full.b[bi, h], sub.b[bi, hi])
+                assert np.array_equal(full.K[bi, h], sub.K[bi, hi]) and np.array_equal(full.pos[bi, h], sub.pos[bi, hi])
+    # the heads' outputs differ from one another, so a mix-up of local and global index would show
+    assert not np.array_equal(of[0, 2], of[0, 0]) and np.max(np.abs(rf[0, 2] - rf[0, 0])) > 0
+
+
 # ----------------------------------------------------------------------------- a5 attention
 @pytest.mark.parametrize("n", [1, 5, 300])
 def test_attend_equals_library_softmax_attention(n):
