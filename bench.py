@@ -282,7 +282,6 @@ def main() -> None:
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     w = WORKLOADS[a.workload]
     if a.head_shared:
-        pass
         w = w.shared()
     log = (lambda s: None) if a.quiet else (lambda s: print("[bench] " + s, file=sys.stderr, flush=True))
     torch.cuda.set_device(0)

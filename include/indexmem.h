@@ -119,8 +119,12 @@ void im_destroy(im_handle* h);
 const char* im_last_error(const im_handle* h);
 
 /* Promise that no unit's `len` exceeds `max_live` until the next call of this function;
- * kernels size their grids by it (default: capacity).  A violated promise sets
- * IM_STATUS_LIVE_EXCEEDED and the entries beyond max_live are ignored. */
+ * kernels size their grids by it (default: capacity).  A unit (set) found longer than that sets
+ * IM_STATUS_LIVE_EXCEEDED; its entries beyond max_live are not looked at (scores are written and
+ * attention runs over the first max_live entries only), and nothing is dropped on that basis:
+ * im_topb_select gives it a keep list of those entries and an empty evict list, im_compact_kv leaves
+ * it as it is, and the fused steps append its new token but evict nothing from it and keep its
+ * true length. */
 int32_t im_set_max_live(im_handle* h, int32_t max_live);
 
 /* Copy the device status word to *status_host (host pointer), clear it, and WAIT for `stream`. */

@@ -30,28 +30,10 @@
 #define DEC_CAND_V 80
 #define DEC_CAND_KI 144
 // header words: 0 rank key (score part), 1 rank key (position part), 2 slot, 3 live entries n of the
-// unit, 4..11 attention logits of the entry, 12 its token position.  Record index S (one past the
+// unit (at most max_live), 4..11 attention logits of the entry, 12 its token position, 13 the unit's
+// true length (above word 3 only if the live-length promise is broken).  Record index S (one past the
 // splits) describes the LAST live slot: the entry that moves into the hole, and, when n = 128 S + 1,
 // the one key no split covers (then it also carries that key's rank key and logits).
-
-#define IM_STATUS_APPEND_OVERFLOW_BIT 1
-#define IM_STATUS_LIVE_EXCEEDED_BIT 2
-#define IM_STATUS_OVER_BUDGET_BIT 8
-
-// Optional phase stamps for kernel tuning (compiled out unless IM_DEC_TRACE is defined):
-// every workgroup writes wall_clock64() (100 MHz) at phase boundaries into a buffer.
-#ifdef IM_DEC_TRACE
-extern "C" __device__ unsigned long long im_trace_buf[2048 * 16];
-__device__ unsigned long long im_trace_buf[2048 * 16];
-#define DEC_STAMP_AT(slot, thread) do { if (threadIdx.x == (thread) && blockIdx.x < 2048) im_trace_buf[blockIdx.x * 16 + (slot)] = wall_clock64(); } while (0)
-extern "C" __device__ unsigned long long im_trace_prep[2048 * 2];
-__device__ unsigned long long im_trace_prep[2048 * 2];
-#define PREP_STAMP(slot) do { if (threadIdx.x == 0 && blockIdx.x < 2048) im_trace_prep[blockIdx.x * 2 + (slot)] = wall_clock64(); } while (0)
-#else
-#define PREP_STAMP(slot) do { } while (0)
-#define DEC_STAMP_AT(slot, thread) do { } while (0)
-#endif
-#define DEC_STAMP(slot) DEC_STAMP_AT(slot, 0)
 
 typedef short v4s __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
@@ -388,7 +370,6 @@ __device__ __forceinline__ void dec_prep_unit(const DecArgs& a, const int u, Dec
 template <int PR>   // batch rows per projection block: 4 or 8
 __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
   __shared__ DecPrepSmem ps;
-  PREP_STAMP(0);
   double (*part)[16] = ps.part;
   double* rows = ps.rows;
   const int tid = threadIdx.x;
@@ -406,7 +387,6 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
     dec_gemv2<PR>(a.q, a.Uq, n0, Nq, a.B, a.H * IM_D, part, rows, m0, m1);
     // raw projections; the consumer applies the QK-Norm (it needs a whole head, this block has 2 rows)
     for (int i = 2 * m0 + tid; i < 2 * m1; i += 256) a.qy[(size_t)(i >> 1) * Nq + n0 + (i & 1)] = rows[i];
-    PREP_STAMP(1);
     return;
   }
   if (blk < nU + nG) {
@@ -417,18 +397,15 @@ __global__ __launch_bounds__(256) void k_dec_prep(const DecArgs a) {
       const int r = n0 + (i & 1);
       if (r < a.H_idx) a.alpha[(size_t)(i >> 1) * a.H_idx + r] = rows[i];   // raw G x; scaled by the consumer
     }
-    PREP_STAMP(1);
     return;
   }
   if (blk >= nU + nG + U) {
     int mu, mp;
     xcd_unit_map(blk - nU - nG - U, DEC_MP, U, mu, mp);   // (these blocks start at grid index U: a multiple of 8 with U)
     dec_prep_memory(a, mu, mp, ps);
-    PREP_STAMP(1);
     return;
   }
   dec_prep_unit(a, blk - nU - nG, ps);
-  PREP_STAMP(1);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -651,13 +628,15 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   const int b = u / a.H_kv, h = u % a.H_kv;
   const int su = u / a.H_set;           // the set that owns the length, positions and indexer keys
   const int n_old = a.len[su];
-  const int n = min(n_old + ((n_old + 1 <= a.C) ? 1 : 0), a.max_live);
+  const int n_true = n_old + ((n_old + 1 <= a.C) ? 1 : 0);
+  const int n = min(n_true, a.max_live);
   const int k0 = s * DEC_KEYS;
   const int nk = max(0, min(DEC_KEYS, n - k0));
   uint32_t* crec = a.cand + ((size_t)u * a.S_alloc + s) * DEC_CAND;
   if (nk <= 0) {
     if (s == 0 && tid == 0) {
       crec[3] = (uint32_t)n;   // an empty unit still tells the tail its length
+      crec[13] = (uint32_t)n_true;
       if (a.hs) a.hs_evict[u] = -1;
     }
     return;
@@ -668,7 +647,6 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
   uint32_t* lrec = a.cand + ((size_t)u * a.S_alloc + a.S) * DEC_CAND;
   const int ll = n - 1 - k0;
   const bool do_x_any = (s == 0) && (n > a.S * DEC_KEYS);   // split 0 also covers the one key beyond the splits
-  DEC_STAMP(0);
   // rows past the end of the split are read from its last row instead (finite values, no branches):
   // their logits are masked and their probabilities are zero further down
   uint4 kif[2][2], kf[2][4], vf[2][4], qf[4];
@@ -750,7 +728,6 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       xpos = a.pos[last];
     }
     __asm__ volatile("" ::: "memory");   // every load above is issued before the arithmetic below
-    DEC_STAMP_AT(14, 256);
     // ---- QK-Norm of the query features (per head over its 64 dims), head gate
     double alj;
     {
@@ -760,16 +737,23 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       ss = rows_sum_d(ss);
       const double rr = sqrt(ss / (double)IM_DI + (double)a.rms_eps);
       const double inv = 1.0 / rr;
+      const double live = hv ? 1.0 : 0.0;
       float wf[16];
       unpack8(nw[0], wf);
       unpack8(nw[1], wf + 8);
 #pragma unroll
       for (int m = 0; m < 16; ++m) {
-        // y / rr: one reciprocal, then a residual correction (the quotient's last-bit rounding
-        // cannot matter after the fp32 rounding below except on a 2^-29 fraction of inputs)
+        // y / rr, correctly rounded, without 16 division sequences per lane: inv is the correctly
+        // rounded reciprocal; the first residual step leaves a quotient within one ulp, and a residual
+        // step on such a quotient yields the correctly rounded one (Markstein's theorem on
+        // FMA-based division).  The step-by-step path and the oracle divide; all three then round the
+        // same fp64 value to fp32.
         double qq = qd[m] * inv;
         qq = fma(fma(-qq, rr, qd[m]), inv, qq);
-        qd[m] = hv ? (double)(float)(qq * (double)wf[m]) : 0.0;
+        qq = fma(fma(-qq, rr, qd[m]), inv, qq);
+        // (lanes past the last indexer head hold head 0's values: finite; zeroed by a product, which the
+        // compiler keeps as one instruction where a select became sixteen branches)
+        qd[m] = (double)(float)(qq * (double)wf[m]) * live;
       }
       alj = hv ? (double)(float)(araw / sqrt((double)(a.H_idx * IM_DI))) : 0.0;
     }
@@ -862,7 +846,6 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       sm.c64[wl] = ((unsigned long long)mh << 32) | ml;
       sm.cslot[wl] = (win >= 0) ? 32 * wl + win : -1;
     }
-    DEC_STAMP_AT(15, 256);
   } else {
     // ================= attention waves: issue the K, Q and V loads =================
     // Five groups of 4 loads per lane (K tile 0, K tile 1, Q, V tile 0, V tile 1), paced: a group goes out
@@ -922,7 +905,6 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     // keep every load above this line, in this order: loads return in order, so each phase below
     // waits only for what it uses while the rest is still streaming in
     __asm__ volatile("" ::: "memory");
-    DEC_STAMP(1);
     if (!SCORE && tid < 4) {
       // the named entry is this split's candidate if it lies here (wave tid's 32 keys)
       int ev = ev_in;
@@ -981,7 +963,6 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     }
   }
   __syncthreads();
-  DEC_STAMP(2);
   // ---- the split's candidate: last-ranked over the 4 scoring waves (upwards with <= keeps the largest slot)
   int cl = -1;  // candidate's key index inside the split
   unsigned long long cbest = ~0ull;
@@ -1042,7 +1023,6 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    DEC_STAMP(4);
     // O[head][d] += P[head][key] V[key][d]; 16 lanes share a key row (8 dims each)
 #pragma unroll
     for (int j = 0; j < G; ++j)
@@ -1071,7 +1051,6 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
     const int j = tid - 256;
     lrec[4 + j] = __float_as_uint((sm.xlp[0][j] + sm.xlp[1][j] + sm.xlp[2][j] + sm.xlp[3][j]) * a.scale);
   }
-  DEC_STAMP(5);
   // the 16 (attention wave, key group) streams meet in LDS, 4 heads at a time; all 8 waves add them up
   float* prec = a.part + ((size_t)u * a.S_alloc + s) * G * DEC_REC;   // dense [split][head][record]
 #pragma unroll
@@ -1108,12 +1087,12 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       }
     }
   }
-  DEC_STAMP(6);
   if (tid == 0) {
     crec[0] = (uint32_t)(cbest >> 32);
     crec[1] = (uint32_t)cbest;
     crec[2] = (uint32_t)(k0 + cl);
     crec[3] = (uint32_t)n;
+    crec[13] = (uint32_t)n_true;
   }
   if (tid < G) crec[4 + tid] = __float_as_uint(cl >= 0 ? sm.clog[tid] : -INFINITY);   // -inf: no candidate
   if (!SCORE && own_last) {
@@ -1132,7 +1111,6 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       }
     }
   }
-  DEC_STAMP(7);
 }
 
 #define DEC_TT 1024   // threads of a tail workgroup: the tail is a chain of short phases, so it is
@@ -1187,7 +1165,6 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // a scalar, so that branches on the wave's role are uniform
   const int b = u / a.H_kv, h = u % a.H_kv;
-  DEC_STAMP(8);
   const uint32_t* cbase = a.cand + (size_t)u * a.S_alloc * DEC_CAND;
   const float* pbase = a.part + (size_t)u * a.S_alloc * G * DEC_REC;
   // ---------------- every load is issued now: no address depends on another load ----------------
@@ -1236,15 +1213,18 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
   const uint4 Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
   const float b_old = a.bvec[(size_t)u * IM_DM + wc];
   __syncthreads();
-  DEC_STAMP(9);
   const int n = (int)sm.cst[0][3];
+  // a unit longer than the caller's promise (flagged by the prep launch) evicts nothing and keeps its
+  // true length: the entries beyond max_live were not looked at
+  const int n_true = (int)sm.cst[0][13];
+  const bool over = n_true > n;
   const int n_act = min((n + DEC_KEYS - 1) / DEC_KEYS, a.S);
   const bool has_x = n > a.S * DEC_KEYS;      // one key beyond the splits: described by the last-slot record
   const int n_last = n - 1;
   const uint32_t* lsrec = (const uint32_t*)&sm.cst[LSI][0];
   const int x_split = has_x ? n_act : -2;   // index the leftover key goes by in the ranking
   const int cn0 = min(CH, n_act);
-  const bool evict = n > a.budget;
+  const bool evict = n > a.budget && !over;
   // ---------------- the evicted entry: ranked last over all splits and the leftover key ----------------
   if (n_act > CH) {   // rare: more splits than one staged round; their rank keys come from global memory
     unsigned long long best = ~0ull;
@@ -1287,7 +1267,7 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
       }
       if (a.ext_evict) {   // the caller names the slot: the record of its split holds its rows
         const int e = a.ext_evict[u];
-        const bool ev = e >= 0 && e < n;
+        const bool ev = e >= 0 && e < n && !over;
         sm.e_split = ev ? e / DEC_KEYS : -1;
         sm.e_slot = ev ? e : -1;
       } else {
@@ -1338,7 +1318,6 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     rm = m;
   }
   __syncthreads();
-  DEC_STAMP(10);
   const int e_split = sm.e_split, e_slot = sm.e_slot;
   // the evicted entry's rows: in the staged record of its split or the last-slot record (LDS), or,
   // with more splits than one staging round holds, in its split's record in global memory
@@ -1460,7 +1439,6 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     if (part == 1 && act) { sm.mrg[0][oidx] = rm; sm.mrg[1][oidx] = rl; sm.mrg[2][oidx] = ro; }
   }
   __syncthreads();
-  DEC_STAMP(11);
   if (w >= 16 - G) {   // one wave per head: phi_q . phi_e and the readout's denominator
     const int jj = 15 - w;
     float dn = 0.f, dt = 0.f;
@@ -1496,7 +1474,6 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     o_attn = (l > 0.f) ? o / l : 0.f;
   }
   __syncthreads();
-  DEC_STAMP(12);
   if (part == 0 && act) {
     // phi_q^T (lambda M + eta phi_e v_e^T) = lambda phi_q^T M + eta (phi_q . phi_e) v_e
     float mr = 0.f;
@@ -1508,7 +1485,6 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     a.out[oi] = f2bf_rne(o_attn + res);
     if (a.readout) a.readout[oi] = res;
   }
-  DEC_STAMP(13);
   if (e_slot >= 0) {
     // M <- lambda M + eta phi_e v_e^T for this thread's 4 x 4 patch
 #pragma unroll
@@ -1530,8 +1506,8 @@ __device__ __forceinline__ void dec_tail(const DecArgs& a, const int u, DecTailS
     else if (tid == 40) a.pos[dst] = mvpos;
   }
   if (tid == 0) {
-    a.len[u] = n_keep;
-    a.nproj[u] = n_keep;
+    a.len[u] = over ? n_true : n_keep;
+    a.nproj[u] = over ? n_true : n_keep;
     if (a.evicted) a.evicted[u] = e_slot;
   }
 }
@@ -1597,7 +1573,6 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     Wr0 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16);
     Wr1 = *(const uint4*)(a.Wt + wc * IM_D + hh * 16 + 8);
   };
-  DEC_STAMP(8);
   {
     // one batch: every load of the regions is in flight before the first LDS store
     constexpr int NBP = (CH * (DEC_REC / 2) + DEC_TT - 1) / DEC_TT;
@@ -1665,8 +1640,9 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   }
   if constexpr (!ML_EARLY) later_loads();
   __syncthreads();
-  DEC_STAMP(9);
   const int n = (int)sm.cst[0][3];
+  const int n_true = (int)sm.cst[0][13];      // above n only if the live-length promise is broken: then
+  const bool over = n_true > n;               // nothing is evicted and the true length stays
   const int n_act = min((n + DEC_KEYS - 1) / DEC_KEYS, a.S);
   const bool has_x = n > a.S * DEC_KEYS;      // one key beyond the splits: described by the last-slot record
   const uint32_t* lsrec = (const uint32_t*)&sm.cst[LS][0];
@@ -1684,7 +1660,7 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     if (lane == 0) {
       if (a.ext_evict) {   // the caller names the slot: the record of its split holds its rows
         const int e = a.ext_evict[u];
-        const bool ev = e >= 0 && e < n;
+        const bool ev = e >= 0 && e < n && !over;
         sm.e_split = ev ? e / DEC_KEYS : -1;
         sm.e_slot = ev ? e : -1;
       } else {
@@ -1694,7 +1670,7 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
           const unsigned long long xc = ((unsigned long long)lsrec[0] << 32) | lsrec[1];
           if (bi < 0 || xc <= bb) { bb = xc; bi = x_split; }
         }
-        const bool ev = n > a.budget && bi >= 0;
+        const bool ev = n > a.budget && bi >= 0 && !over;
         sm.e_split = ev ? bi : -1;
         sm.e_slot = !ev ? -1 : (bi == x_split) ? n - 1 : (int)sm.cst[bi][2];
         if (j == 0 && n > a.budget + 1) atomicOr(a.status, IM_STATUS_OVER_BUDGET_BIT);
@@ -1738,7 +1714,6 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     }
   }
   __syncthreads();
-  DEC_STAMP(10);
   const int e_split = sm.e_split, e_slot = sm.e_slot;
   const uint32_t* er = (e_split == x_split) ? lsrec : (const uint32_t*)&sm.cst[max(e_split, 0)][0];
   float ve_d = 0.f;
@@ -1804,7 +1779,6 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   }
   sm.mrg[0][part][d] = rm; sm.mrg[1][part][d] = rl; sm.mrg[2][part][d] = ro;
   __syncthreads();
-  DEC_STAMP(11);
   if (w == 15) {   // phi_q . phi_e and the readout's denominator
     float dn = 0.f, dt = 0.f;
 #pragma unroll
@@ -1851,7 +1825,6 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
     a.out[oi] = f2bf_rne(o_attn + res);
     if (a.readout) a.readout[oi] = res;
   }
-  DEC_STAMP(12);
   if (e_slot >= 0 && m_mine) {
     // M <- lambda M + eta phi_e v_e^T for this thread's rows, 4 columns each
 #pragma unroll
@@ -1878,15 +1851,14 @@ __device__ __forceinline__ void dec_tail_head(const DecArgs& a, const int u, con
   }
   if (new_fits && tid >= 128 && tid < 128 + IM_DI_SHARED) {
     // the new token sits in the last live slot n - 1, unless that entry has just moved into the hole
-    const int at = (e_slot >= 0 && e_slot < n_keep) ? e_slot : n - 1;
+    const int at = (e_slot >= 0 && e_slot < n_keep) ? e_slot : n_true - 1;
     if (!(e_slot == n - 1)) a.Kidx[((size_t)su * a.C + at) * IM_DI_SHARED + (tid - 128)] = new_key;
   }
   if (tid == 0 && lead) {
-    a.len[su] = n_keep;
-    a.nproj[su] = n_keep;
+    a.len[su] = over ? n_true : n_keep;
+    a.nproj[su] = over ? n_true : n_keep;
     if (a.evicted) a.evicted[su] = e_slot;
   }
-  DEC_STAMP(13);
 }
 
 // grid: units * S blocks; consecutive blocks take different units, the short last splits come last

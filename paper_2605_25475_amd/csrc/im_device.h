@@ -11,6 +11,11 @@ typedef uint16_t bf16_t;
 #define IM_DM 128     // mem_dim
 #define IM_WAVE 64
 
+// bits of the device-side status word (the public header names them without the suffix)
+#define IM_STATUS_APPEND_OVERFLOW_BIT 1
+#define IM_STATUS_LIVE_EXCEEDED_BIT 2
+#define IM_STATUS_OVER_BUDGET_BIT 8
+
 __device__ __forceinline__ float bf2f(bf16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }

@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void k_project_keys(const bf16_t* __restrict__
   const int l16 = lane & 15, kq = lane >> 4;
   int n = len[unit];
   if (n > max_live) {
-    if (tid == 0 && blockIdx.x == 0) atomicOr(status, 2);
+    if (tid == 0 && blockIdx.x == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
     n = max_live;
   }
   const int row0 = n_projected[unit] + blockIdx.x * 64 + 16 * w;
@@ -738,18 +738,25 @@ __global__ __launch_bounds__(1024) void k_select(const float* __restrict__ score
                                                  int32_t* __restrict__ keep_idx,
                                                  int32_t* __restrict__ evict_idx,
                                                  int32_t* __restrict__ n_keep,
-                                                 int32_t* __restrict__ n_evict) {
+                                                 int32_t* __restrict__ n_evict,
+                                                 int32_t* __restrict__ status) {
   __shared__ unsigned hist[256];
   __shared__ unsigned sh_prefix, sh_rem, sh_cnt, sh_pick[3];
   __shared__ int sh_red[16];
   __shared__ unsigned wsum[16];
   const int unit = blockIdx.x, tid = threadIdx.x;
-  const int n = min(len[unit], max_live);
+  const int n_true = len[unit];
+  const int n = min(n_true, max_live);
   const float* sc = scores + (size_t)unit * C;
   const int32_t* ps = pos + (size_t)unit * C;
   int32_t* keep = keep_idx + (size_t)unit * C;
   int32_t* evict = evict_idx + (size_t)unit * C;
-  const int k = min(budget, n);
+  // A unit longer than the caller's promise is flagged and evicts nothing: its lists keep the first
+  // max_live slots, so the memory update skips it, and the compaction (which sees the same length)
+  // leaves it as it is.
+  const bool over = n_true > max_live;
+  if (over && tid == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
+  const int k = over ? n : min(budget, n);
 
   int maxpos = INT_MIN;
   if (n_recent > 0) {
@@ -1156,10 +1163,16 @@ __global__ __launch_bounds__(256) void k_compact(bf16_t* __restrict__ K, bf16_t*
                                                  const int32_t* __restrict__ keep_idx,
                                                  const int32_t* __restrict__ n_keep,
                                                  const int32_t* __restrict__ evict_idx, int C, int H_set,
-                                                 int di) {
+                                                 int di, int max_live, int32_t* __restrict__ status) {
   const int unit = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int set = unit / H_set;
   const bool lead = unit % H_set == 0;
+  // a set longer than the caller's promise is flagged and left as it is (its lists cover only the
+  // first max_live slots: applying them would drop the rest without a trace in the memory)
+  if (len[set] > max_live) {
+    if (lead && blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
+    return;
+  }
   const int nk = n_keep[set];
   const int32_t* keep = keep_idx + (size_t)set * C;
   const int32_t* evict = evict_idx + (size_t)set * C;
@@ -1196,12 +1209,15 @@ __global__ __launch_bounds__(256) void k_attn_partial(const bf16_t* __restrict__
                                                       const int32_t* __restrict__ len,
                                                       const bf16_t* __restrict__ q, int H, int H_kv,
                                                       int H_set, int C, int max_live, float scale,
-                                                      float* __restrict__ part, int n_chunks) {
+                                                      float* __restrict__ part, int n_chunks,
+                                                      int32_t* __restrict__ status) {
   __shared__ float s_ml[4][G][2];
   __shared__ float s_acc[4][G][IM_D];
   const int unit = blockIdx.y, chunk = blockIdx.x;
   const int b = unit / H_kv, h = unit % H_kv;
-  const int n = min(len[unit / H_set], max_live);
+  const int n_true = len[unit / H_set];
+  const int n = min(n_true, max_live);
+  if (n_true > max_live && chunk == 0 && threadIdx.x == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
   const int k0 = chunk * IM_ATT_CHUNK;
   if (k0 >= n) return;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, grp = lane >> 4, l16 = lane & 15;

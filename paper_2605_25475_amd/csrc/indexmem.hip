@@ -408,7 +408,7 @@ int32_t im_topb_select(im_handle* h, const float* scores, const im_state* st, in
   const im_config& c = h->cfg;
   k_select<<<n_sets(c), 1024, 0, s>>>(scores, st->pos, st->len, c.capacity, h->max_live,
                                                   budget, c.n_sink, c.n_recent, keep_idx, evict_idx,
-                                                  n_keep, n_evict);
+                                                  n_keep, n_evict, status_ptr(h));
   return launch_check(h, "im_topb_select");
 }
 
@@ -453,7 +453,7 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
   if (gx > 64) gx = 64;
   k_compact<<<dim3(gx, c.batch * c.n_kv_heads), 256, 0, s>>>(
       (bf16_t*)st->K, (bf16_t*)st->V, (bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, keep_idx,
-      n_keep, evict_idx, c.capacity, heads_per_set(c), c.idx_dim);
+      n_keep, evict_idx, c.capacity, heads_per_set(c), c.idx_dim, h->max_live, status_ptr(h));
   return launch_check(h, "im_compact_kv");
 }
 
@@ -477,7 +477,7 @@ int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_s
                                            (const bf16_t*)q, c.n_q_heads, c.n_kv_heads,         \
                                            heads_per_set(c), c.capacity, h->max_live,           \
                                            c.softmax_scale, part,                               \
-                                           h->attn_chunks);                                     \
+                                           h->attn_chunks, status_ptr(h));                      \
     break;
   switch (G) {
     IM_ATT_CASE(1) IM_ATT_CASE(2) IM_ATT_CASE(3) IM_ATT_CASE(4)
@@ -671,12 +671,3 @@ int32_t im_decode_step_shared_hidden(im_handle* h, const im_params* p, const im_
 }
 
 }  // extern "C"
-
-#ifdef IM_DEC_TRACE
-extern "C" int im_trace_read_prep(unsigned long long* host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(im_trace_prep), 2048 * 2 * sizeof(unsigned long long));
-}
-extern "C" int im_trace_read(unsigned long long* host) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(im_trace_buf), 2048 * 16 * sizeof(unsigned long long));
-}
-#endif

@@ -32,6 +32,7 @@ def oracle_config(w: Workload, capacity=None, batch=None, kv_head_ids=None) -> O
                           kv_head_ids=kv_head_ids)
 
 
-def make_oracle_layer(w: Workload, layer: int = 0, device="cpu", **kw):
+def make_oracle_layer(w: Workload, layer: int = 0, device="cpu", params=None, **kw):
+    """params: the layer's weights as layer_params returns them (default: generated here)."""
     cls = O.OracleLayerShared if w.head_shared else O.OracleLayer
-    return cls(oracle_config(w, **kw), oracle_params(layer_params(w, layer, device)))
+    return cls(oracle_config(w, **kw), oracle_params(layer_params(w, layer, device) if params is None else params))

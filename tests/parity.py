@@ -37,12 +37,17 @@ class LockStep:
     """One layer on the GPU and in the oracle, fed the same events."""
 
     def __init__(self, w: Workload, layer: int = 0, capacity=None, max_queries=None, device="cuda",
-                 gen_device="cpu", kv_heads=None, batch_ids=None, ref_capacity=None):
+                 gen_device="cpu", kv_heads=None, batch_ids=None, ref_capacity=None, params_mod=None,
+                 null_norms=False):
+        """params_mod: a function that edits the generated weights (a dict) before both sides get them;
+        null_norms: the library gets NULL norm-weight pointers (the oracle keeps the ones)."""
         self.w = w
         self.dev = device
         cap = w.capacity if capacity is None else capacity
         self.cap = cap
         p = layer_params(w, layer, gen_device)
+        if params_mod is not None:
+            params_mod(p)
         cfg = im.Config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, capacity=cap,
                         n_idx_heads=w.n_idx_heads, n_sink=w.n_sink, n_recent=w.n_recent,
                         fold_block=w.fold_block,
@@ -50,13 +55,13 @@ class LockStep:
         self.handle = im.Handle(cfg, device)
         pd = {k: (v.to(device) if torch.is_tensor(v) else v) for k, v in p.items()}
         self.params = im.Params(pd["Uq"], pd["G"], pd["Uk"], pd["Wtheta"], pd["wg"], pd["cg"],
-                                pd["norm_q_w"], pd["norm_k_w"])
+                                None if null_norms else pd["norm_q_w"], None if null_norms else pd["norm_k_w"])
         self.gpu = im.Layer(self.handle, self.params, device)
         # the oracle may follow a subset of units (all by default)
         self.batch_ids = list(range(w.batch)) if batch_ids is None else list(batch_ids)
         self.kv_heads = list(range(w.n_kv_heads)) if kv_heads is None else list(kv_heads)
-        self.ref = make_oracle_layer(w, layer, gen_device, capacity=ref_capacity or cap, batch=len(self.batch_ids),
-                                     kv_head_ids=self.kv_heads)
+        self.ref = make_oracle_layer(w, layer, gen_device, params=p, capacity=ref_capacity or cap,
+                                     batch=len(self.batch_ids), kv_head_ids=self.kv_heads)
         self.K, self.V, self.Q = token_stream(w, layer, gen_device)
 
     # -- one event on both sides ---------------------------------------------------------------
@@ -278,11 +283,14 @@ class LockStepShared:
     eviction set and one memory per sequence): events through the step-by-step entry points.  The
     oracle follows a subset of the sequences, with all their KV heads."""
 
-    def __init__(self, w: Workload, layer: int = 0, device="cuda", gen_device="cpu", batch_ids=None, capacity=None):
+    def __init__(self, w: Workload, layer: int = 0, device="cuda", gen_device="cpu", batch_ids=None, capacity=None,
+                 params_mod=None, null_norms=False):
         assert w.head_shared
         self.w, self.dev = w, device
         self.cap = cap = w.capacity if capacity is None else capacity
         p = layer_params(w, layer, gen_device)
+        if params_mod is not None:
+            params_mod(p)
         cfg = im.Config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, capacity=cap,
                         n_idx_heads=w.n_idx_heads, idx_dim=w.idx_dim, n_sink=w.n_sink, n_recent=w.n_recent,
                         fold_block=w.fold_block, head_shared=1,
@@ -290,10 +298,10 @@ class LockStepShared:
         self.handle = im.Handle(cfg, device)
         pd = {k: (v.to(device) if torch.is_tensor(v) else v) for k, v in p.items()}
         self.params = im.Params(pd["Uq"], pd["G"], pd["Uk"], pd["Wtheta"], pd["wg"], pd["cg"],
-                                pd["norm_q_w"], pd["norm_k_w"])
+                                None if null_norms else pd["norm_q_w"], None if null_norms else pd["norm_k_w"])
         self.gpu = im.Layer(self.handle, self.params, device)
         self.batch_ids = list(range(w.batch)) if batch_ids is None else list(batch_ids)
-        self.ref = make_oracle_layer(w, layer, gen_device, batch=len(self.batch_ids), capacity=cap)
+        self.ref = make_oracle_layer(w, layer, gen_device, params=p, batch=len(self.batch_ids), capacity=cap)
         self.K, self.V, self.Q = token_stream(w, layer, gen_device)
         self.X = hidden_stream(w, layer, gen_device)
 
