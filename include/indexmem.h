@@ -116,7 +116,8 @@ size_t im_workspace_bytes(const im_config* cfg);
  * touches no GPU.  The first enqueuing call clears the part of the workspace that needs it. */
 int32_t im_create(const im_config* cfg, void* workspace, size_t workspace_bytes, im_handle** out);
 void im_destroy(im_handle* h);
-const char* im_last_error(const im_handle* h);
+const char* im_last_error(const im_handle* h);   /* h = NULL: the calling thread's last error of a call
+                                                    that takes no handle */
 
 /* Promise that no unit's `len` exceeds `max_live` until the next call of this function;
  * kernels size their grids by it (default: capacity).  A unit (set) found longer than that sets
@@ -209,6 +210,26 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
  * head_shared = 1: every query head of the sequence reads the sequence's one (M, b). */
 int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_state* st,
                                     const void* q, void* out, float* readout_dbg, void* stream);
+
+/* For callers that cannot allocate device memory or bring a workspace (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): im_decode_attn_with_readout without a handle
+ * and without a workspace.  The attention partials go to a buffer of IM_STATIC_SCRATCH_BYTES that is
+ * part of the library's device code (one copy per GPU, held until the process ends); the call
+ * allocates nothing, on the host or on the device, and only enqueues work on `stream`.
+ * cfg (host pointer) is validated on every call; max_live (1..capacity) bounds every unit's length as
+ * im_set_max_live does.  Needs 256 + 520 * batch * n_q_heads * ceil(max_live / 128) bytes of the
+ * buffer: a larger call is rejected with IM_ERR_INVALID_ARG before anything is enqueued
+ * (im_last_error(NULL) gives this thread's text for a call without a handle).
+ * status_dev: optional device word that IM_STATUS_LIVE_EXCEEDED is OR-ed into (NULL: not reported).
+ * Results are those of im_decode_attn_with_readout, bit for bit.
+ * The GPU that owns `stream` must be the current device.  All calls on one GPU share that GPU's
+ * buffer: calls that overlap in time on one GPU (two streams, two threads) race; calls in stream
+ * order on one stream do not.  The first call on a GPU looks the buffer's address up
+ * (hipGetSymbolAddress): make it outside a graph capture. */
+#define IM_STATIC_SCRATCH_BYTES (16u << 20)
+int32_t im_decode_attn_with_readout_static(const im_config* cfg, int32_t max_live, const im_params* p,
+                                           const im_state* st, const void* q, void* out,
+                                           float* readout_dbg, int32_t* status_dev, void* stream);
 
 /* The whole step for ONE new token per sequence, fused into three launches: exactly
  *   im_append_kv(n_new = 1) -> im_index_score(n_q = 1) -> im_topb_select(budget) ->

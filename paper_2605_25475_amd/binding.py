@@ -17,11 +17,12 @@ from . import build as _build
 
 IM_OK, IM_ERR_INVALID_ARG, IM_ERR_UNSUPPORTED, IM_ERR_LAUNCH = 0, -1, -2, -3
 IM_STATUS_APPEND_OVERFLOW, IM_STATUS_LIVE_EXCEEDED, IM_STATUS_OVER_BUDGET = 1, 2, 8
+IM_STATIC_SCRATCH_BYTES = 16 << 20
 
 EXPORTS = [
     "im_workspace_bytes", "im_create", "im_destroy", "im_last_error", "im_set_max_live",
     "im_query_status", "im_append_kv", "im_append_kv_hidden", "im_index_score", "im_topb_select", "im_memory_update",
-    "im_compact_kv", "im_decode_attn_with_readout", "im_decode_step", "im_attend_step", "im_attend_step_hidden", "im_decode_step_shared", "im_decode_step_shared_hidden", "im_profile_start",
+    "im_compact_kv", "im_decode_attn_with_readout", "im_decode_attn_with_readout_static", "im_decode_step", "im_attend_step", "im_attend_step_hidden", "im_decode_step_shared", "im_decode_step_shared_hidden", "im_profile_start",
     "im_profile_stop",
 ]
 
@@ -89,6 +90,9 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     lib.im_compact_kv.argtypes = [vp, C.POINTER(ImState), vp, vp, vp, vp, vp]
     lib.im_decode_attn_with_readout.restype = i32
     lib.im_decode_attn_with_readout.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, vp]
+    lib.im_decode_attn_with_readout_static.restype = i32
+    lib.im_decode_attn_with_readout_static.argtypes = [C.POINTER(ImConfig), i32, C.POINTER(ImParams), C.POINTER(ImState),
+                                                       vp, vp, vp, vp, vp]
     lib.im_decode_step.restype = i32
     lib.im_decode_step.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, vp, vp, vp, i32,
                                    f32, f32, vp, vp, vp, vp, vp]
@@ -264,6 +268,17 @@ def im_compact_kv(h: Handle, st: State, keep_idx, n_keep, evict_idx, n_evict) ->
 def im_decode_attn_with_readout(h: Handle, p: Params, st: State, q, out, readout_dbg=None) -> None:
     h.check(h.lib.im_decode_attn_with_readout(h.h, C.byref(p.c), C.byref(st.c), _ptr(q), _ptr(out),
                                               _ptr(readout_dbg), _stream()))
+
+
+def im_decode_attn_with_readout_static(cfg: Config, max_live: int, p: Params, st: State, q, out,
+                                       readout_dbg=None, status_dev=None) -> None:
+    """The same without a handle or a workspace (the library's built-in scratch buffer)."""
+    lib = load_library()
+    c = cfg.c_struct()
+    rc = lib.im_decode_attn_with_readout_static(C.byref(c), max_live, C.byref(p.c), C.byref(st.c), _ptr(q), _ptr(out),
+                                                _ptr(readout_dbg), _ptr(status_dev), _stream())
+    if rc != IM_OK:
+        raise IndexMemError(rc, lib.im_last_error(None).decode())
 
 
 def im_decode_step(h: Handle, p: Params, st: State, q, x_gate, q_pos, k_new, v_new, pos_new, budget: int,

@@ -10,6 +10,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "im_kernels.h"
 #include "im_decode.h"
 
@@ -29,6 +31,17 @@ struct im_handle {
 };
 
 #define IM_SCORE_GROUPS 8   // query groups of a scoring launch over a short cache
+
+// Scratch of the entry point that allocates nothing (im_decode_attn_with_readout_static): a status
+// word in the first 256 bytes, then the attention partials.  Every GPU the library runs on holds
+// its own copy of this array, at its own address, until the process ends.  In host code the name is
+// only a handle for hipGetSymbolAddress: the per-device address it returns is what kernels, fills and
+// copies are given.
+#define IM_STATIC_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char im_static_scratch[IM_STATIC_SCRATCH_BYTES];
+static void* g_static_ptr[IM_STATIC_MAX_DEVICES];
+static std::mutex g_static_mu;
+static thread_local char g_static_err[256] = "";
 
 namespace {
 
@@ -243,7 +256,7 @@ int32_t im_profile_stop(im_handle* h, float* ms_host, int32_t* n_records, void* 
   return IM_OK;
 }
 
-const char* im_last_error(const im_handle* h) { return h ? h->err : "handle is NULL"; }
+const char* im_last_error(const im_handle* h) { return h ? h->err : g_static_err; }
 
 int32_t im_set_max_live(im_handle* h, int32_t max_live) {
   if (!h) return IM_ERR_INVALID_ARG;
@@ -457,6 +470,34 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
   return launch_check(h, "im_compact_kv");
 }
 
+// the two launches of step a5 over `part` (attention partials, attn_chunks records per query head)
+static int launch_attn(const im_config& c, int max_live, const im_params* p, const im_state* st, const void* q,
+                       void* out, float* readout_dbg, float* part, int attn_chunks, int32_t* status,
+                       hipStream_t s) {
+  const int units = c.batch * c.n_kv_heads, G = c.n_q_heads / c.n_kv_heads;
+  const int H_set = c.head_shared ? c.n_kv_heads : 1;
+  const int chunks = (max_live + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK;
+  dim3 grid(chunks, units);
+#define IM_ATT_CASE(g)                                                                          \
+  case g:                                                                                       \
+    k_attn_partial<g><<<grid, 256, 0, s>>>((const bf16_t*)st->K, (const bf16_t*)st->V, st->len,   \
+                                           (const bf16_t*)q, c.n_q_heads, c.n_kv_heads, H_set,   \
+                                           c.capacity, max_live, c.softmax_scale, part,         \
+                                           attn_chunks, status);                                \
+    break;
+  switch (G) {
+    IM_ATT_CASE(1) IM_ATT_CASE(2) IM_ATT_CASE(3) IM_ATT_CASE(4)
+    IM_ATT_CASE(5) IM_ATT_CASE(6) IM_ATT_CASE(7) IM_ATT_CASE(8)
+    default: return IM_ERR_UNSUPPORTED;
+  }
+#undef IM_ATT_CASE
+  k_attn_combine<<<c.batch * c.n_q_heads, 128, 0, s>>>(
+      part, attn_chunks, st->len, (const bf16_t*)q, (const bf16_t*)p->Wtheta, (const bf16_t*)p->wg,
+      p->cg, st->M, st->b, c.n_q_heads, c.n_kv_heads, H_set, max_live, c.mem_eps, (bf16_t*)out,
+      readout_dbg);
+  return IM_OK;
+}
+
 int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_state* st,
                                     const void* q, void* out, float* readout_dbg, void* stream) {
   if (!h) return IM_ERR_INVALID_ARG;
@@ -466,30 +507,74 @@ int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_s
   hipStream_t s = (hipStream_t)stream;
   int rc = ensure_ws(h, s);
   if (rc) return rc;
-  const im_config& c = h->cfg;
-  const int units = c.batch * c.n_kv_heads, G = c.n_q_heads / c.n_kv_heads;
-  const int chunks = (h->max_live + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK;
-  float* part = (float*)(h->ws + h->off_attn);
-  dim3 grid(chunks, units);
-#define IM_ATT_CASE(g)                                                                          \
-  case g:                                                                                       \
-    k_attn_partial<g><<<grid, 256, 0, s>>>((const bf16_t*)st->K, (const bf16_t*)st->V, st->len,   \
-                                           (const bf16_t*)q, c.n_q_heads, c.n_kv_heads,         \
-                                           heads_per_set(c), c.capacity, h->max_live,           \
-                                           c.softmax_scale, part,                               \
-                                           h->attn_chunks, status_ptr(h));                      \
-    break;
-  switch (G) {
-    IM_ATT_CASE(1) IM_ATT_CASE(2) IM_ATT_CASE(3) IM_ATT_CASE(4)
-    IM_ATT_CASE(5) IM_ATT_CASE(6) IM_ATT_CASE(7) IM_ATT_CASE(8)
-    default: return set_err(h, IM_ERR_UNSUPPORTED, "group size %d", G);
-  }
-#undef IM_ATT_CASE
-  k_attn_combine<<<c.batch * c.n_q_heads, 128, 0, s>>>(
-      part, h->attn_chunks, st->len, (const bf16_t*)q, (const bf16_t*)p->Wtheta, (const bf16_t*)p->wg,
-      p->cg, st->M, st->b, c.n_q_heads, c.n_kv_heads, heads_per_set(c), h->max_live, c.mem_eps, (bf16_t*)out,
-      readout_dbg);
+  rc = launch_attn(h->cfg, h->max_live, p, st, q, out, readout_dbg, (float*)(h->ws + h->off_attn),
+                   h->attn_chunks, status_ptr(h), s);
+  if (rc) return set_err(h, rc, "group size %d", h->cfg.n_q_heads / h->cfg.n_kv_heads);
   return launch_check(h, "im_decode_attn_with_readout");
+}
+
+static int static_err(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_static_err, sizeof(g_static_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+static size_t static_scratch_bytes(const im_config* cfg, int32_t max_live) {
+  int code;
+  if (config_problem(cfg, &code) || max_live < 1 || max_live > cfg->capacity) return 0;
+  const size_t chunks = ((size_t)max_live + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK;
+  return 256 + (size_t)cfg->batch * cfg->n_q_heads * chunks * IM_ATT_REC * sizeof(float);
+}
+
+int32_t im_decode_attn_with_readout_static(const im_config* cfg, int32_t max_live, const im_params* p,
+                                           const im_state* st, const void* q, void* out,
+                                           float* readout_dbg, int32_t* status_dev, void* stream) {
+  // host-only validation first: an invalid call touches no GPU
+  int code;
+  if (const char* why = config_problem(cfg, &code)) return static_err(code, "im_decode_attn_with_readout_static: %s", why);
+  if (!params_ok(p) || !state_ok(st) || !q || !out)
+    return static_err(IM_ERR_INVALID_ARG, "im_decode_attn_with_readout_static: a params / state / q / out pointer is NULL");
+  if (max_live < 1 || max_live > cfg->capacity)
+    return static_err(IM_ERR_INVALID_ARG, "im_decode_attn_with_readout_static: max_live must be in 1..capacity");
+  const size_t need = static_scratch_bytes(cfg, max_live);
+  if (need > (size_t)IM_STATIC_SCRATCH_BYTES)
+    return static_err(IM_ERR_INVALID_ARG,
+                      "im_decode_attn_with_readout_static: batch %d x %d query heads x %d live entries need %zu bytes of "
+                      "scratch, the built-in buffer holds %zu (IM_STATIC_SCRATCH_BYTES); use im_decode_attn_with_readout "
+                      "with a workspace",
+                      cfg->batch, cfg->n_q_heads, max_live, need, (size_t)IM_STATIC_SCRATCH_BYTES);
+  // this device's copy of the scratch array: looked up once per device, with that device current
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess || dev < 0 || dev >= IM_STATIC_MAX_DEVICES)
+    return static_err(IM_ERR_LAUNCH, "im_decode_attn_with_readout_static: hipGetDevice: %s (device %d)",
+                      hipGetErrorString(e), dev);
+  char* scratch = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[dev]) {
+      void* sym = nullptr;
+      e = hipGetSymbolAddress(&sym, HIP_SYMBOL(im_static_scratch));
+      if (e != hipSuccess || !sym)
+        return static_err(IM_ERR_LAUNCH, "im_decode_attn_with_readout_static: hipGetSymbolAddress: %s",
+                          hipGetErrorString(e));
+      g_static_ptr[dev] = sym;
+    }
+    scratch = (char*)g_static_ptr[dev];
+  }
+  hipStream_t s = (hipStream_t)stream;
+  // the buffer keeps the last call's contents.  The partial records need no clearing (every record the
+  // combine reads is written by this call's first launch); the status word does when it is the sink.
+  int32_t* status = status_dev ? status_dev : (int32_t*)scratch;
+  if (!status_dev) k_fill_i32<<<1, 64, 0, s>>>((int32_t*)scratch, 1, 0);
+  const int chunks = (max_live + IM_ATT_CHUNK - 1) / IM_ATT_CHUNK;
+  const int rc = launch_attn(*cfg, max_live, p, st, q, out, readout_dbg, (float*)(scratch + 256), chunks, status, s);
+  if (rc) return static_err(rc, "im_decode_attn_with_readout_static: group size %d", cfg->n_q_heads / cfg->n_kv_heads);
+  e = hipGetLastError();
+  if (e != hipSuccess) return static_err(IM_ERR_LAUNCH, "im_decode_attn_with_readout_static: %s", hipGetErrorString(e));
+  return IM_OK;
 }
 
 static int32_t decode_launch(im_handle* h, const im_params* p, const im_state* st, const void* q,

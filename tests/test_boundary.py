@@ -145,3 +145,25 @@ def test_head_shared_layout_validation(lib):
 def test_binding_fails_loudly_on_invalid_config():
     with pytest.raises(im.IndexMemError):
         im.Handle(good_cfg(head_dim=64), device="cpu")
+
+
+def test_static_entry_point_validates_on_the_host(lib):
+    # im_decode_attn_with_readout_static: invalid arguments and sizes beyond its built-in buffer are
+    # refused before any GPU call, with a text under im_last_error(NULL)
+    cfg = good_cfg().c_struct()
+    p = B.ImParams(1 << 20, 1 << 20, 1 << 20, None, None, 1 << 20, 1 << 20, 0.0)
+    st = B.ImState(*([1 << 20] * 8))
+    f = lib.im_decode_attn_with_readout_static
+    assert f(None, 10, C.byref(p), C.byref(st), 1 << 20, 1 << 20, None, None, None) == im.IM_ERR_INVALID_ARG
+    assert f(C.byref(cfg), 0, C.byref(p), C.byref(st), 1 << 20, 1 << 20, None, None, None) == im.IM_ERR_INVALID_ARG
+    assert f(C.byref(cfg), 513, C.byref(p), C.byref(st), 1 << 20, 1 << 20, None, None, None) == im.IM_ERR_INVALID_ARG
+    assert b"max_live" in lib.im_last_error(None)
+    assert f(C.byref(cfg), 10, C.byref(p), C.byref(st), None, 1 << 20, None, None, None) == im.IM_ERR_INVALID_ARG
+    big = good_cfg(batch=64, n_q_heads=64, n_kv_heads=8, n_idx_heads=16, capacity=16384).c_struct()
+    need = 256 + 520 * 64 * 64 * 128
+    assert need > im.IM_STATIC_SCRATCH_BYTES
+    assert f(C.byref(big), 16384, C.byref(p), C.byref(st), 1 << 20, 1 << 20, None, None, None) == im.IM_ERR_INVALID_ARG
+    msg = lib.im_last_error(None).decode()
+    assert str(need) in msg and "IM_STATIC_SCRATCH_BYTES" in msg
+    bad = good_cfg(head_dim=64).c_struct()
+    assert f(C.byref(bad), 10, C.byref(p), C.byref(st), 1 << 20, 1 << 20, None, None, None) == im.IM_ERR_UNSUPPORTED
