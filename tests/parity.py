@@ -120,6 +120,18 @@ class LockStep:
             self.compare(scores, keep, evict, out, res, tag, fused=True)
         return scores, keep, evict, out, res
 
+    def compare_decision(self, evict, tag):
+        """The cheap part of a fused decode step's comparison, for every step of a long trajectory: the
+        evicted slot and the new length of the sampled units, bit for bit."""
+        evicted = self.gpu.evicted.cpu().numpy(); lens = self.gpu.st.len.cpu().numpy()
+        for ib, b in enumerate(self.batch_ids):
+            for ih, h in enumerate(self.kv_heads):
+                er = evict[ib][ih]
+                assert len(er) <= 1, f"{tag} unit(b={b},h={h})"
+                want = int(er[0]) if len(er) else -1
+                assert evicted[b, h] == want, f"{tag} unit(b={b},h={h}): evicted slot {evicted[b, h]} != {want}"
+                assert lens[b, h] == int(self.ref.len[ib, ih]), f"{tag} unit(b={b},h={h}): length"
+
     def compare(self, scores, keep, evict, out, res, tag, fused=False, lists=True, outputs=True):
         w, g = self.w, self.gpu
         G = w.group
@@ -260,7 +272,9 @@ class LockStep:
             self.window(L + k * tau, tau, w.budget, f"window {k}", fused=fused)
         assert im.im_query_status(self.handle) == 0
 
-    def run_schedule(self, decode_steps=None, fused_decode=False):
+    def run_schedule(self, decode_steps=None, fused_decode=False, full_every=1):
+        """full_every = k > 1 (fused decode only): every observable is compared at every k-th decode step
+        and at the last one; the steps between compare the decision (evicted slot, length) alone."""
         w = self.w
         steps = w.decode_steps if decode_steps is None else decode_steps
         L = w.context
@@ -270,9 +284,12 @@ class LockStep:
             for c0 in range(0, L, w.prefill_chunk):
                 self.event(c0, min(L, c0 + w.prefill_chunk), w.budget, f"chunk@{c0}")
         im.im_set_max_live(self.handle, min(self.cap, w.budget + 1))
-        for t in range(L, L + steps):
+        for i, t in enumerate(range(L, L + steps)):
             if fused_decode:
-                self.event_fused(t, w.budget, f"fused decode@{t}")
+                full = (i + 1) % full_every == 0 or i == steps - 1
+                ref = self.event_fused(t, w.budget, f"fused decode@{t} (step {i + 1} of {steps})", check=full)
+                if not full:
+                    self.compare_decision(ref[2], f"fused decode@{t} (step {i + 1} of {steps})")
             else:
                 self.event(t, t + 1, w.budget, f"decode@{t}")
         assert im.im_query_status(self.handle) == 0
@@ -323,7 +340,7 @@ class LockStepShared:
         self.compare(*ref, tag)
         return ref
 
-    def event_fused(self, t: int, budget: int, tag: str):
+    def event_fused(self, t: int, budget: int, tag: str, check=True):
         """One decode token through im_decode_step (four launches in this layout)."""
         w, dev = self.w, self.dev
         d = lambda x: x.to(dev)
@@ -340,7 +357,8 @@ class LockStepShared:
         xn = sel(x_new)
         ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn, posn, sel(q_new)[:, 0], budget,
                             w.lam, w.eta)
-        self.compare(*ref, tag, fused=True)
+        if check:
+            self.compare(*ref, tag, fused=True)
         return ref
 
     # -- a follower layer of an index-sharing group (Appendix, IndexCache-style reuse) -------------
@@ -374,6 +392,14 @@ class LockStepShared:
                              x_new=d(x_new))
         torch.cuda.synchronize()
         self._follow(k_new, v_new, x_new, pos, q, evict, tag)
+
+    def compare_decision(self, evict, tag):
+        evicted = self.gpu.evicted.cpu().numpy(); lens = self.gpu.st.len.cpu().numpy()
+        for ib, b in enumerate(self.batch_ids):
+            assert len(evict[ib]) <= 1, f"{tag} sequence {b}"
+            want = int(evict[ib][0]) if len(evict[ib]) else -1
+            assert evicted[b] == want, f"{tag} sequence {b}: evicted slot {evicted[b]} != {want}"
+            assert lens[b] == int(self.ref.len[ib]), f"{tag} sequence {b}: length"
 
     def compare(self, scores, keep, evict, out, res, tag, fused=False, lists=True, outputs=True):
         w, g, st = self.w, self.gpu, self.gpu.st
@@ -451,7 +477,7 @@ class LockStepShared:
             self.window(w.context + k * tau, tau, w.budget, f"window {k}", fused=fused)
         assert im.im_query_status(self.handle) == 0
 
-    def run_schedule(self, decode_steps=None, fused_decode=False):
+    def run_schedule(self, decode_steps=None, fused_decode=False, full_every=1):
         w = self.w
         steps = w.decode_steps if decode_steps is None else decode_steps
         L = w.context
@@ -461,9 +487,12 @@ class LockStepShared:
             for c0 in range(0, L, w.prefill_chunk):
                 self.event(c0, min(L, c0 + w.prefill_chunk), w.budget, f"chunk@{c0}")
         im.im_set_max_live(self.handle, min(self.cap, w.budget + 1))
-        for t in range(L, L + steps):
+        for i, t in enumerate(range(L, L + steps)):
             if fused_decode:
-                self.event_fused(t, w.budget, f"fused decode@{t}")
+                full = (i + 1) % full_every == 0 or i == steps - 1
+                ref = self.event_fused(t, w.budget, f"fused decode@{t} (step {i + 1} of {steps})", check=full)
+                if not full:
+                    self.compare_decision(ref[2], f"fused decode@{t} (step {i + 1} of {steps})")
             else:
                 self.event(t, t + 1, w.budget, f"decode@{t}")
         assert im.im_query_status(self.handle) == 0

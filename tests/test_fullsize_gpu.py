@@ -1,14 +1,11 @@
-"""Parity at the benchmark's full size and launch configuration: configuration 3 (batch 4, 8 KV
-heads, a 16384-token prompt evicted to 2048, then decode through im_decode_step with the live
-bound the benchmark sets).  The GPU runs every unit of one layer; the oracle follows a sample of
-units (they are independent) through the same events and every observable of those units is
-compared to the usual bars.  Configuration 4's head shape (7 query heads per KV head, 7 indexer
-heads) gets the same treatment at a reduced batch; configuration 2 (batch 8, 4096 -> 1024) and
-configuration 5 (one sequence of 131072 tokens in 32 chunks of 4096, running cache evicted to
-4096 after every chunk) run one layer at their stated sizes; configuration 4 also at its own batch
-of 16.  The other decode paths of the benchmark run at configuration 3's size as well: the periodic
-schedule (128 attend-only steps, then one compression event) and a leader / follower pair of an
-index-sharing group."""
+"""Parity at the configurations' stated sizes, in the launch configuration the benchmark times.
+The GPU runs every unit of one layer; the oracle follows a sample of units (they are independent)
+through the same events, and every observable of those units is compared to the usual bars.
+Configurations 2-5 run their own trajectories (stated context, budget, batch and all 256 / 512 /
+256 / 1024 decode steps through im_decode_step; configuration 5 after its 31 chunk evictions).  The
+other decode paths of the benchmark run at configuration 3's size as well: the periodic schedule
+(128 attend-only steps, then one compression event), a leader / follower pair of an index-sharing
+group, and the head-shared layout (step by step, and its fused step over 512 decode steps)."""
 import pytest
 
 from parity import LockStep, LockStepShared
@@ -17,24 +14,26 @@ from workloads import WORKLOADS
 pytestmark = pytest.mark.gpu
 
 
-def test_cfg3_full_size_sampled_units():
-    w = WORKLOADS["cfg3"].scaled(n_layers=1, decode_steps=6)
-    ls = LockStep(w, gen_device="cuda", batch_ids=[1, 3], kv_heads=[2, 5])
-    ls.run_schedule(fused_decode=True)
-
-
-def test_cfg4_shape_full_context_sampled_units():
-    w = WORKLOADS["cfg4"].scaled(n_layers=1, batch=4, decode_steps=4)
-    ls = LockStep(w, gen_device="cuda", batch_ids=[2], kv_heads=[0, 3])
-    ls.run_schedule(fused_decode=True)
-
-
-def test_cfg4_full_batch_sampled_units():
-    # the benchmark's own launch configuration of configuration 4: batch 16 x 4 KV heads (projection blocks
-    # of 8 batch rows, the per-unit tail: 64 units x 7 heads do not fit the chip once)
-    w = WORKLOADS["cfg4"].scaled(n_layers=1, decode_steps=3)
-    ls = LockStep(w, gen_device="cuda", batch_ids=[11], kv_heads=[1, 2])
-    ls.run_schedule(fused_decode=True)
+# The configurations' own trajectories: the stated context, budget, batch AND number of decode steps,
+# every step through im_decode_step in the launch configuration the benchmark times.  The oracle
+# follows the sampled units in lock step; the decision (evicted slot, length) is compared at every
+# step, every observable (fp32 scores, rows, positions, M, b, output, readout) at every 32nd step and
+# at the last one.  Same bars as everywhere else.
+@pytest.mark.parametrize("name,layer,kw,units", [
+    ("cfg2", 0, dict(decode_steps=256), dict(batch_ids=[0, 5], kv_heads=[1, 6])),
+    ("cfg3", 0, dict(decode_steps=512), dict(batch_ids=[1, 3], kv_heads=[2, 5])),
+    # configuration 4's launch configuration: batch 16 x 4 KV heads (projection blocks of 8 batch rows, the
+    # per-unit tail: 64 units x 7 heads do not fit the chip once)
+    ("cfg4", 0, dict(decode_steps=256), dict(batch_ids=[11], kv_heads=[1, 2])),
+    # ... and its head shape at a reduced batch (the per-(unit, head) tail), on a layer other than the first
+    ("cfg4", 5, dict(decode_steps=256, batch=4), dict(batch_ids=[2], kv_heads=[0, 3])),
+    # 31 chunk evictions of 4096 out of 8192 live entries, then decode at 4097 live entries
+    ("cfg5", 0, dict(decode_steps=1024), dict(kv_heads=[3])),
+], ids=["cfg2-256-steps", "cfg3-512-steps", "cfg4-256-steps", "cfg4-batch4-layer5-256-steps", "cfg5-1024-steps"])
+def test_full_size_trajectory_sampled_units(name, layer, kw, units):
+    w = WORKLOADS[name].scaled(n_layers=layer + 1, **kw)
+    ls = LockStep(w, layer=layer, gen_device="cuda", **units)
+    ls.run_schedule(fused_decode=True, full_every=32)
 
 
 def test_cfg3_full_size_periodic_schedule_sampled_units():
@@ -63,19 +62,6 @@ def test_cfg3_full_size_index_reuse_sampled_units():
     assert im.im_query_status(lead.handle) == 0 and im.im_query_status(foll.handle) == 0
 
 
-def test_cfg2_full_size_sampled_units():
-    w = WORKLOADS["cfg2"].scaled(n_layers=1, decode_steps=6)
-    ls = LockStep(w, gen_device="cuda", batch_ids=[0, 5], kv_heads=[1, 6])
-    ls.run_schedule(fused_decode=True)
-
-
-def test_cfg5_full_size_chunked_prefill_sampled_unit():
-    # 31 chunk evictions of 4096 out of 8192 live entries, then decode at 4097 live entries
-    w = WORKLOADS["cfg5"].scaled(n_layers=1, decode_steps=4)
-    ls = LockStep(w, gen_device="cuda", kv_heads=[3])
-    ls.run_schedule(fused_decode=True)
-
-
 def test_cfg3_head_shared_full_size_sampled_sequence():
     # configuration 3's cache shape in the head-shared layout: one 16384-query scoring pass over 16384
     # keys of 16 dims per sequence, one eviction set per sequence, rows of 8 KV heads summed into one memory
@@ -84,5 +70,6 @@ def test_cfg3_head_shared_full_size_sampled_sequence():
 
 
 def test_cfg3_head_shared_full_size_fused_decode():
-    w = WORKLOADS["cfg3"].shared(n_layers=1, decode_steps=5)
-    LockStepShared(w, gen_device="cuda", batch_ids=[1]).run_schedule(fused_decode=True)
+    # configuration 3's own 512 decode steps through the four-launch step of this layout
+    w = WORKLOADS["cfg3"].shared(n_layers=1, decode_steps=512)
+    LockStepShared(w, gen_device="cuda", batch_ids=[1]).run_schedule(fused_decode=True, full_every=32)
