@@ -293,6 +293,13 @@ int32_t im_decode_step_shared_hidden(im_handle* h, const im_params* p, const im_
                                      const int32_t* pos_new, const int32_t* evict_slot, float lambda,
                                      float eta, void* out, float* readout_dbg, void* stream);
 
+/* Measurement only (not part of the method): one launch that reads `bytes` (a multiple of 16) from
+ * src (device, 16-byte aligned) with 16-byte streaming loads on all CUs and writes nothing, unless the
+ * XOR of all words read equals `never`, in which case that word goes to sink[0] (device; pass a value
+ * the data cannot produce).  The benchmark times it at the decode step's bytes per launch, as the
+ * plain-read ceiling printed beside the step's own rate. */
+int32_t im_stream_read(const void* src, size_t bytes, uint32_t never, void* sink, void* stream);
+
 /* Kernel timing for benchmarks (not part of the method).  After im_profile_start, every
  * im_decode_step on this handle brackets part of its launch sequence (prep kernel, main kernel,
  * tail kernel) with a pair of HIP events on the launch stream, for at most max_records calls:

@@ -22,7 +22,7 @@ IM_STATIC_SCRATCH_BYTES = 16 << 20
 EXPORTS = [
     "im_workspace_bytes", "im_create", "im_destroy", "im_last_error", "im_set_max_live",
     "im_query_status", "im_append_kv", "im_append_kv_hidden", "im_index_score", "im_topb_select", "im_memory_update",
-    "im_compact_kv", "im_decode_attn_with_readout", "im_decode_attn_with_readout_static", "im_decode_step", "im_attend_step", "im_attend_step_hidden", "im_decode_step_shared", "im_decode_step_shared_hidden", "im_profile_start",
+    "im_compact_kv", "im_decode_attn_with_readout", "im_decode_attn_with_readout_static", "im_decode_step", "im_attend_step", "im_attend_step_hidden", "im_decode_step_shared", "im_decode_step_shared_hidden", "im_stream_read", "im_profile_start",
     "im_profile_stop",
 ]
 
@@ -106,6 +106,8 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     lib.im_decode_step_shared_hidden.restype = i32
     lib.im_decode_step_shared_hidden.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, vp, vp, vp,
                                                  f32, f32, vp, vp, vp]
+    lib.im_stream_read.restype = i32
+    lib.im_stream_read.argtypes = [vp, C.c_size_t, C.c_uint32, vp, vp]
     lib.im_profile_start.restype = i32
     lib.im_profile_start.argtypes = [vp, i32, i32]
     lib.im_profile_stop.restype = i32
@@ -311,6 +313,14 @@ def im_decode_step_shared_hidden(h: Handle, p: Params, st: State, q, x_new, k_ne
     h.check(h.lib.im_decode_step_shared_hidden(h.h, C.byref(p.c), C.byref(st.c), _ptr(q), _ptr(x_new), _ptr(k_new),
                                                _ptr(v_new), _ptr(pos_new), _ptr(evict_slot), lam, eta, _ptr(out),
                                                _ptr(readout_dbg), _stream()))
+
+
+def im_stream_read(src: torch.Tensor, nbytes: int, never: int, sink: torch.Tensor) -> None:
+    """One plain streaming read of the first nbytes of src (measurement only; see indexmem.h)."""
+    lib = load_library()
+    rc = lib.im_stream_read(_ptr(src), nbytes, never, _ptr(sink), _stream())
+    if rc != IM_OK:
+        raise IndexMemError(rc, lib.im_last_error(None).decode())
 
 
 IM_PROFILE_MAIN, IM_PROFILE_PREP, IM_PROFILE_PREP_AND_MAIN = 0, 1, 2

@@ -12,6 +12,32 @@ __global__ void k_fill_i32(int32_t* p, int n, int32_t v) {
 }
 
 // ------------------------------------------------------------------------------------------
+// measurement only: a plain streaming read of `n16` 16-byte pieces (the ceiling the decode step's
+// stream kernel is compared with).  Every thread keeps 8 loads with the streaming hint in flight and
+// folds what arrives into one word; the word is stored only if it equals `never` (the benchmark
+// passes a value the data cannot produce), so the loads stay and nothing is written.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_stream_read(const uint4* __restrict__ src, size_t n16,
+                                                     uint32_t never, uint32_t* __restrict__ sink) {
+  typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+  const size_t stride = (size_t)gridDim.x * 256;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  uint32_t acc = 0;
+  for (; i + 7 * stride < n16; i += 8 * stride) {
+    u4 v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = __builtin_nontemporal_load((const u4*)src + i + k * stride);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
+  }
+  for (; i < n16; i += stride) {
+    const u4 v = __builtin_nontemporal_load((const u4*)src + i);
+    acc ^= v.x ^ v.y ^ v.z ^ v.w;
+  }
+  if (acc == never) sink[0] = acc;
+}
+
+// ------------------------------------------------------------------------------------------
 // helper: append rows
 // ------------------------------------------------------------------------------------------
 // A "set" is what shares one slot order: lengths, positions, indexer keys, lists and the memory

@@ -57,6 +57,15 @@ int set_err(im_handle* h, int code, const char* fmt, ...) {
   return code;
 }
 
+// the calling thread's error text of a call that takes no handle (im_last_error(NULL))
+int static_err(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_static_err, sizeof(g_static_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
 const char* config_problem(const im_config* c, int* code) {
   *code = IM_ERR_INVALID_ARG;
   if (!c) return "config is NULL";
@@ -238,6 +247,16 @@ int32_t im_profile_start(im_handle* h, int32_t max_records, int32_t span) {
   }
   h->prof_n = 0;
   h->prof_span = span;
+  return IM_OK;
+}
+
+int32_t im_stream_read(const void* src, size_t bytes, uint32_t never, void* sink, void* stream) {
+  if (!src || !sink || bytes < 16 || bytes % 16 != 0 || ((uintptr_t)src & 15) != 0)
+    return static_err(IM_ERR_INVALID_ARG, "im_stream_read: src / sink is NULL, or bytes / src is not a multiple of 16");
+  // 8 workgroups of 4 waves per CU: 2048 workgroups, each thread 8 x 16 bytes per round
+  k_stream_read<<<2048, 256, 0, (hipStream_t)stream>>>((const uint4*)src, bytes / 16, never, (uint32_t*)sink);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return static_err(IM_ERR_LAUNCH, "im_stream_read: %s", hipGetErrorString(e));
   return IM_OK;
 }
 
@@ -511,14 +530,6 @@ int32_t im_decode_attn_with_readout(im_handle* h, const im_params* p, const im_s
                    h->attn_chunks, status_ptr(h), s);
   if (rc) return set_err(h, rc, "group size %d", h->cfg.n_q_heads / h->cfg.n_kv_heads);
   return launch_check(h, "im_decode_attn_with_readout");
-}
-
-static int static_err(int code, const char* fmt, ...) {
-  va_list ap;
-  va_start(ap, fmt);
-  vsnprintf(g_static_err, sizeof(g_static_err), fmt, ap);
-  va_end(ap);
-  return code;
 }
 
 static size_t static_scratch_bytes(const im_config* cfg, int32_t max_live) {
