@@ -200,6 +200,18 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
                       const int32_t* n_keep, const int32_t* evict_idx, const int32_t* n_evict,
                       void* stream);
 
+/* Step a4 out of place, for evicting a prompt BEFORE it is cached (Section 3.1, "pre-eviction ... caches
+ * only the selected KV states"): the kept entries of `src` (a state of this handle's capacity, e.g. one
+ * that has adopted the prompt's K / V buffers through im_append_kv with no rows, after im_index_score,
+ * im_topb_select and im_memory_update) are written to `dst`, a state of the same shape but with
+ * dst_capacity slots per unit, in the very slots im_compact_kv would leave them in: rows of K, V, Kidx
+ * and pos of slots [0, n_keep); M and b are copied; dst's len = n_projected = n_keep.  src is only
+ * read; the two states must not share buffers.  A unit whose n_keep exceeds dst_capacity is left out
+ * and sets IM_STATUS_APPEND_OVERFLOW.  Lists as im_topb_select wrote them for src. */
+int32_t im_gather_kept(im_handle* h, const im_state* src, const im_state* dst, int32_t dst_capacity,
+                       const int32_t* keep_idx, const int32_t* n_keep, const int32_t* evict_idx,
+                       const int32_t* n_evict, void* stream);
+
 /* Step a5, decode attention over the retained entries plus the gated memory readout
  * (Section 2.1 "KV Caching"; Eqs. latent_readout, latent_residual_fuse): for query head j of
  * KV head h = j / (H / H_kv),

@@ -22,7 +22,7 @@ IM_STATIC_SCRATCH_BYTES = 16 << 20
 EXPORTS = [
     "im_workspace_bytes", "im_create", "im_destroy", "im_last_error", "im_set_max_live",
     "im_query_status", "im_append_kv", "im_append_kv_hidden", "im_index_score", "im_topb_select", "im_memory_update",
-    "im_compact_kv", "im_decode_attn_with_readout", "im_decode_attn_with_readout_static", "im_decode_step", "im_attend_step", "im_attend_step_hidden", "im_decode_step_shared", "im_decode_step_shared_hidden", "im_stream_read", "im_profile_start",
+    "im_compact_kv", "im_gather_kept", "im_decode_attn_with_readout", "im_decode_attn_with_readout_static", "im_decode_step", "im_attend_step", "im_attend_step_hidden", "im_decode_step_shared", "im_decode_step_shared_hidden", "im_stream_read", "im_profile_start",
     "im_profile_stop",
 ]
 
@@ -88,6 +88,8 @@ def load_library(build_if_missing: bool = True) -> C.CDLL:
     lib.im_memory_update.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, f32, f32, vp]
     lib.im_compact_kv.restype = i32
     lib.im_compact_kv.argtypes = [vp, C.POINTER(ImState), vp, vp, vp, vp, vp]
+    lib.im_gather_kept.restype = i32
+    lib.im_gather_kept.argtypes = [vp, C.POINTER(ImState), C.POINTER(ImState), i32, vp, vp, vp, vp, vp]
     lib.im_decode_attn_with_readout.restype = i32
     lib.im_decode_attn_with_readout.argtypes = [vp, C.POINTER(ImParams), C.POINTER(ImState), vp, vp, vp, vp]
     lib.im_decode_attn_with_readout_static.restype = i32
@@ -265,6 +267,11 @@ def im_memory_update(h: Handle, p: Params, st: State, evict_idx, n_evict, lam: f
 def im_compact_kv(h: Handle, st: State, keep_idx, n_keep, evict_idx, n_evict) -> None:
     h.check(h.lib.im_compact_kv(h.h, C.byref(st.c), _ptr(keep_idx), _ptr(n_keep), _ptr(evict_idx),
                                 _ptr(n_evict), _stream()))
+
+
+def im_gather_kept(h: Handle, src: State, dst: State, dst_capacity: int, keep_idx, n_keep, evict_idx, n_evict) -> None:
+    h.check(h.lib.im_gather_kept(h.h, C.byref(src.c), C.byref(dst.c), dst_capacity, _ptr(keep_idx), _ptr(n_keep),
+                                 _ptr(evict_idx), _ptr(n_evict), _stream()))
 
 
 def im_decode_attn_with_readout(h: Handle, p: Params, st: State, q, out, readout_dbg=None) -> None:

@@ -1222,6 +1222,64 @@ __global__ __launch_bounds__(256) void k_compact(bf16_t* __restrict__ K, bf16_t*
   if (lead && blockIdx.x == 0 && threadIdx.x == 0) { len[set] = nk; n_projected[set] = nk; }
 }
 
+// The same Gather out of place: the kept entries of a source state go to the slots the in-place
+// hole filling would leave them in, but of a destination state with its own capacity Cd (kept entry j of
+// the ascending keep list: slot keep[j] if that is below n_keep, else the (j - p)-th evicted slot, p =
+// number of kept slots below n_keep); the memory state is copied along; the destination's lengths are
+// set.  The source is only read.  grid (gx, units), one wave per entry.
+__global__ __launch_bounds__(256) void k_gather_kept(const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+                                                     const bf16_t* __restrict__ Kidx,
+                                                     const int32_t* __restrict__ pos,
+                                                     const int32_t* __restrict__ len,
+                                                     const float* __restrict__ M, const float* __restrict__ bvec,
+                                                     bf16_t* __restrict__ Kd, bf16_t* __restrict__ Vd,
+                                                     bf16_t* __restrict__ Kidxd, int32_t* __restrict__ posd,
+                                                     int32_t* __restrict__ lend, int32_t* __restrict__ nprojd,
+                                                     float* __restrict__ Md, float* __restrict__ bd,
+                                                     const int32_t* __restrict__ keep_idx,
+                                                     const int32_t* __restrict__ n_keep,
+                                                     const int32_t* __restrict__ evict_idx, int C, int Cd,
+                                                     int H_set, int di, int max_live,
+                                                     int32_t* __restrict__ status) {
+  const int unit = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int set = unit / H_set;
+  const bool lead = unit % H_set == 0;
+  const int nk = n_keep[set];
+  // a set longer than the caller's promise has lists that cover only its first max_live slots, and a
+  // kept set that does not fit the destination cannot be gathered: flagged, destination untouched
+  if (len[set] > max_live || nk > Cd) {
+    if (lead && blockIdx.x == 0 && threadIdx.x == 0)
+      atomicOr(status, len[set] > max_live ? IM_STATUS_LIVE_EXCEEDED_BIT : IM_STATUS_APPEND_OVERFLOW_BIT);
+    return;
+  }
+  const int32_t* keep = keep_idx + (size_t)set * C;
+  const int32_t* evict = evict_idx + (size_t)set * C;
+  int lo = 0, hi = nk;   // p = number of kept slots below nk (keep is ascending)
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    if (keep[mid] < nk) lo = mid + 1; else hi = mid;
+  }
+  const int p = lo;
+  for (int j = blockIdx.x * 4 + w; j < nk; j += gridDim.x * 4) {
+    const int ss = keep[j], ds = (j < p) ? ss : evict[j - p];
+    const size_t src = (size_t)unit * C + ss, dst = (size_t)unit * Cd + ds;
+    const size_t isrc = (size_t)set * C + ss, idst = (size_t)set * Cd + ds;
+    if (lane < 16) *(uint4*)(Kd + dst * IM_D + lane * 8) = *(const uint4*)(K + src * IM_D + lane * 8);
+    else if (lane < 32) *(uint4*)(Vd + dst * IM_D + (lane - 16) * 8) = *(const uint4*)(V + src * IM_D + (lane - 16) * 8);
+    else if (lane < 32 + di / 8) {
+      if (lead) *(uint4*)(Kidxd + idst * di + (lane - 32) * 8) = *(const uint4*)(Kidx + isrc * di + (lane - 32) * 8);
+    } else if (lane == 40 && lead) posd[idst] = pos[isrc];
+  }
+  if (lead) {
+    const float* Ms = M + (size_t)set * IM_DM * IM_D;
+    float* Mo = Md + (size_t)set * IM_DM * IM_D;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < IM_DM * IM_D / 4; i += gridDim.x * 256)
+      ((float4*)Mo)[i] = ((const float4*)Ms)[i];
+    if (blockIdx.x == 0 && threadIdx.x < IM_DM) bd[(size_t)set * IM_DM + threadIdx.x] = bvec[(size_t)set * IM_DM + threadIdx.x];
+    if (blockIdx.x == 0 && threadIdx.x == 0) { lend[set] = nk; nprojd[set] = nk; }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // a5: split-K decode attention, then the combine with the gated memory readout
 // ------------------------------------------------------------------------------------------

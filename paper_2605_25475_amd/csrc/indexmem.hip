@@ -489,6 +489,29 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
   return launch_check(h, "im_compact_kv");
 }
 
+int32_t im_gather_kept(im_handle* h, const im_state* src, const im_state* dst, int32_t dst_capacity,
+                       const int32_t* keep_idx, const int32_t* n_keep, const int32_t* evict_idx,
+                       const int32_t* n_evict, void* stream) {
+  if (!h) return IM_ERR_INVALID_ARG;
+  IM_REQUIRE(state_ok(src) && state_ok(dst), "a state has a NULL pointer");
+  IM_REQUIRE(keep_idx && n_keep && evict_idx && n_evict, "a list pointer is NULL");
+  IM_REQUIRE(dst_capacity >= 1, "dst_capacity must be >= 1");
+  IM_REQUIRE(src->K != dst->K && src->V != dst->V && src->Kidx != dst->Kidx && src->pos != dst->pos &&
+                 src->M != dst->M && src->b != dst->b,
+             "source and destination must be different buffers (im_compact_kv works in place)");
+  hipStream_t s = (hipStream_t)stream;
+  int rc = ensure_ws(h, s);
+  if (rc) return rc;
+  const im_config& c = h->cfg;
+  int gx = (h->max_live + 3) / 4;
+  if (gx > 64) gx = 64;
+  k_gather_kept<<<dim3(gx, c.batch * c.n_kv_heads), 256, 0, s>>>(
+      (const bf16_t*)src->K, (const bf16_t*)src->V, (const bf16_t*)src->Kidx, src->pos, src->len, src->M, src->b,
+      (bf16_t*)dst->K, (bf16_t*)dst->V, (bf16_t*)dst->Kidx, dst->pos, dst->len, dst->n_projected, dst->M, dst->b,
+      keep_idx, n_keep, evict_idx, c.capacity, dst_capacity, heads_per_set(c), c.idx_dim, h->max_live, status_ptr(h));
+  return launch_check(h, "im_gather_kept");
+}
+
 // the two launches of step a5 over `part` (attention partials, attn_chunks records per query head)
 static int launch_attn(const im_config& c, int max_live, const im_params* p, const im_state* st, const void* q,
                        void* out, float* readout_dbg, float* part, int attn_chunks, int32_t* status,

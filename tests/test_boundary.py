@@ -99,6 +99,11 @@ def test_calls_validate_before_enqueuing(lib):
     assert lib.im_memory_update(h, C.byref(pr), C.byref(st), X, X, 0.9, 0.0, None) == E
     assert lib.im_memory_update(h, C.byref(pr), C.byref(st), None, X, 0.9, 0.5, None) == E
     assert lib.im_compact_kv(h, C.byref(st), X, None, X, X, None) == E
+    st2 = B.ImState(*([X + 4096] * 8))
+    assert lib.im_gather_kept(h, C.byref(st), C.byref(st), 64, X, X, X, X, None) == E      # in place: im_compact_kv's job
+    assert lib.im_gather_kept(h, C.byref(st), C.byref(st2), 0, X, X, X, X, None) == E
+    assert lib.im_gather_kept(h, C.byref(st), C.byref(st_bad), 64, X, X, X, X, None) == E
+    assert lib.im_gather_kept(h, C.byref(st), C.byref(st2), 64, X, None, X, X, None) == E
     assert lib.im_decode_attn_with_readout(h, C.byref(pr), C.byref(st), None, X, None, None) == E
     assert lib.im_decode_attn_with_readout(h, C.byref(pr), C.byref(st_bad), X, X, None, None) == E
     assert lib.im_decode_step(h, C.byref(pr), C.byref(st), X, X, X, X, X, X, 3, 0.9, 0.5, X, None, None, None, None) == E

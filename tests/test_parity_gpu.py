@@ -359,8 +359,9 @@ def test_head_shared_layout_rejects_what_is_not_built_for_it():
 def test_pre_eviction_prompt_buffers_in_place_then_a_budget_sized_cache():
     # Section 3.1 ("pre-eviction": cache only the selected KV).  The prompt's K / V sit in buffers of
     # their own, as a model's projections leave them; a state of capacity L adopts them in place
-    # (im_append_kv with no rows), the step runs on it, and only the kept slots are copied to the
-    # cache that decoding uses, which holds budget + 2 entries.  The oracle takes the ordinary path.
+    # (im_append_kv with no rows), the step runs on it, and only the kept entries are written
+    # (im_gather_kept) to the cache that decoding uses, which holds budget + 2 entries.  The oracle
+    # takes the ordinary path.  A destination too small for the kept set is refused and flagged.
     w = WORKLOADS["cfg3"].scaled(n_layers=1, batch=2, context=1500, budget=333, decode_steps=4)
     L = w.context
     ls = LockStep(w, capacity=w.budget + 2, ref_capacity=L, max_queries=L)
@@ -372,18 +373,19 @@ def test_pre_eviction_prompt_buffers_in_place_then_a_budget_sized_cache():
     pos = torch.arange(L, dtype=torch.int32).repeat(w.batch, 1).contiguous()
     q = d(ls.Q[:, :L].contiguous())
     im.im_append_kv(big_h, big.st, None, None, d(pos))
-    big.compress(q, q.view(w.batch, L, -1), d(pos), w.budget, w.lam, w.eta)
+    # score -> select -> memory update on the adopted buffers, then ONE launch that writes the kept entries
+    # (and the memory state) straight into the budget-sized cache; the prompt's buffers are only read
+    im.im_index_score(big_h, ls.params, big.st, q, q.view(w.batch, L, -1), d(pos), big.scores)
+    im.im_topb_select(big_h, big.scores, big.st, w.budget, big.keep_idx, big.evict_idx, big.n_keep, big.n_evict)
+    im.im_memory_update(big_h, ls.params, big.st, big.evict_idx, big.n_evict, w.lam, w.eta)
+    snap = {k: getattr(big.st, k).clone() for k in ("K", "V", "pos", "len")}
+    small = ls.gpu.st
+    im.im_gather_kept(big_h, big.st, small, w.budget + 2, big.keep_idx, big.n_keep, big.evict_idx, big.n_evict)
     torch.cuda.synchronize()
     assert im.im_query_status(big_h) == 0
     n = w.budget
-    assert (big.st.len == n).all()
-    small = ls.gpu.st
-    for name in ("K", "V", "Kidx", "pos"):
-        getattr(small, name)[:, :, :n] = getattr(big.st, name)[:, :, :n]
-    for name in ("len", "n_projected", "M", "b"):
-        getattr(small, name).copy_(getattr(big.st, name))
-    for name in ("scores", "keep_idx", "evict_idx"):
-        getattr(ls.gpu, name)[:, :, :w.budget + 2] = getattr(big, name)[:, :, :w.budget + 2]
+    assert (big.st.len == L).all() and all(torch.equal(getattr(big.st, k), v) for k, v in snap.items())
+    assert (small.len == n).all() and (small.n_projected == n).all()
     # the oracle's ordinary prefill event; everything the cache holds must match it
     f = lambda t: t.to(torch.float64).numpy()
     qn = f(ls.Q[:, :L])
@@ -397,10 +399,20 @@ def test_pre_eviction_prompt_buffers_in_place_then_a_budget_sized_cache():
             assert np.array_equal(big.keep_idx[b, h, :n].cpu().numpy(), keep[b][h])
             assert np.array_equal(big.evict_idx[b, h, :L - n].cpu().numpy(), evict[b][h])
     ls.compare(None, None, None, None, None, "adopted cache", lists=False, outputs=False)
+    for b in range(w.batch):   # the indexer keys travelled along (compare() skips them without lists)
+        for h in range(w.n_kv_heads):
+            assert np.array_equal(f(small.Kidx[b, h, :n].cpu()), ls.ref.Kidx[b, h, :n])
     im.im_set_max_live(ls.handle, w.budget + 1)
     for t in range(L, L + w.decode_steps):
         ls.event_fused(t, w.budget, f"fused decode@{t}")
     assert im.im_query_status(ls.handle) == 0
+    # a destination with fewer slots than the kept set: nothing is written, the status word says so
+    tiny = im.State(im.Config(batch=w.batch, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, capacity=w.budget - 1,
+                              n_idx_heads=w.n_idx_heads))
+    im.im_gather_kept(big_h, big.st, tiny, w.budget - 1, big.keep_idx, big.n_keep, big.evict_idx, big.n_evict)
+    torch.cuda.synchronize()
+    assert im.im_query_status(big_h) == im.IM_STATUS_APPEND_OVERFLOW
+    assert not tiny.K.any() and not tiny.len.any() and not tiny.M.any()
 
 
 @pytest.mark.parametrize("shared", [False, True])
