@@ -66,6 +66,8 @@ def test_reduced_configurations_fused_decode(name, kw):
     ("cfg1", dict(context=500, budget=200, decode_steps=114), 57, 2),    # live bound 257: one key beyond the splits
     ("cfg1", dict(batch=2, context=300, budget=100, decode_steps=15), 5, 3),    # 5 queries < 8 indexer heads: the few-query scoring kernel
     ("cfg4", dict(batch=2, context=300, budget=70, decode_steps=12), 6, 2),     # 6 queries < 7 heads
+    ("cfg1", dict(batch=2, context=300, budget=100, decode_steps=22), 11, 2),   # 8 heads <= 11 queries < 16: one ragged query block of the many-query kernel
+    ("cfg1", dict(batch=1, context=260, budget=90, decode_steps=16), 8, 2),     # exactly as many queries as indexer heads
 ])
 @pytest.mark.parametrize("fused", [True, False])
 def test_periodic_compression_schedule(name, kw, tau, n_win, fused):
