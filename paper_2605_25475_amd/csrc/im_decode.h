@@ -170,16 +170,15 @@ __device__ __forceinline__ void dec_gemv2(const bf16_t* __restrict__ A, const bf
         }
       }
     }
-    // wave sums on the DPP path, then the 4 waves meet in LDS
-#pragma unroll
-    for (int i = 0; i < MB; ++i) {
-      acc[i][0] = wave_sum_d(acc[i][0]);
-      acc[i][1] = wave_sum_d(acc[i][1]);
-    }
+    // the 2 MB wave sums as one butterfly (value 2 i + r = batch row i, weight row r), then the 4 waves
+    // meet in LDS: lane 15 of row rho of register i holds value 4 i + 2 (rho & 1) + (rho >> 1)
+    double ws[MB / 2];
+    wave_sums_butterfly_d<2 * MB>(&acc[0][0], ws);
     __syncthreads();
-    if ((tid & 63) == 0) {
+    if ((tid & 15) == 15) {
+      const int rho = (tid >> 4) & 3;
 #pragma unroll
-      for (int i = 0; i < MB; ++i) { part[tid >> 6][2 * i] = acc[i][0]; part[tid >> 6][2 * i + 1] = acc[i][1]; }
+      for (int i = 0; i < MB / 2; ++i) part[tid >> 6][4 * i + 2 * (rho & 1) + (rho >> 1)] = ws[i];
     }
     __syncthreads();
     if (tid < 2 * MB && mb + (tid >> 1) < m_end)

@@ -146,6 +146,38 @@ __device__ __forceinline__ double rows_sum_d(double v) {
   return __longlong_as_double((long long)(((unsigned long long)rh[0] << 32) | rl[0])) +
          __longlong_as_double((long long)(((unsigned long long)rh[1] << 32) | rl[1]));
 }
+// Wave sums of NV (8 or 16) doubles at once, as a butterfly: a swap of 32-lane halves folds two values
+// into one register (value 2 i in the lower half, value 2 i + 1 in the upper), a swap of 16-lane rows
+// folds two of those (one value per row), and only the last step, the sum over the 16 lanes of a row,
+// is done per register: 42 instructions for 8 values where 8 separate wave sums take 160.
+// On return lane 15 of row rho (lane 16 rho + 15) of s[i] holds the wave's sum of value
+// 4 i + 2 (rho & 1) + (rho >> 1).
+template <int NV>
+__device__ __forceinline__ void wave_sums_butterfly_d(const double* v, double* s) {
+  typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+  auto lo = [](double x) { return (unsigned int)(unsigned long long)__double_as_longlong(x); };
+  auto hi = [](double x) { return (unsigned int)((unsigned long long)__double_as_longlong(x) >> 32); };
+  auto mk = [](unsigned int l, unsigned int h) { return __longlong_as_double((long long)(((unsigned long long)h << 32) | l)); };
+  double r[NV / 2];
+#pragma unroll
+  for (int i = 0; i < NV / 2; ++i) {
+    const u2 pl = __builtin_amdgcn_permlane32_swap(lo(v[2 * i]), lo(v[2 * i + 1]), false, false);
+    const u2 ph = __builtin_amdgcn_permlane32_swap(hi(v[2 * i]), hi(v[2 * i + 1]), false, false);
+    r[i] = mk(pl[0], ph[0]) + mk(pl[1], ph[1]);
+  }
+#pragma unroll
+  for (int i = 0; i < NV / 4; ++i) {
+    const u2 pl = __builtin_amdgcn_permlane16_swap(lo(r[2 * i]), lo(r[2 * i + 1]), false, false);
+    const u2 ph = __builtin_amdgcn_permlane16_swap(hi(r[2 * i]), hi(r[2 * i + 1]), false, false);
+    double t = mk(pl[0], ph[0]) + mk(pl[1], ph[1]);
+    t += dpp_zero_d<0x111, 0xF>(t);   // row_shr 1, 2, 4, 8: lane 15 of each row ends with the row's sum
+    t += dpp_zero_d<0x112, 0xF>(t);
+    t += dpp_zero_d<0x114, 0xF>(t);
+    t += dpp_zero_d<0x118, 0xF>(t);
+    s[i] = t;
+  }
+}
+
 // v + (the same lane of the other 32-lane half), in every lane
 __device__ __forceinline__ float halves_sum_f(float v) {
   typedef unsigned int u2 __attribute__((ext_vector_type(2)));
