@@ -376,13 +376,12 @@ __global__ __launch_bounds__(256) void k_gemm_nt_mfma_k4(const bf16_t* __restric
 }
 
 // Few rows (decode): every workgroup owns 2 rows of B and streams them once for all M rows of A.
-// grid (ceil(N/2)); Kd % 8 == 0.
-__global__ __launch_bounds__(256) void k_gemv_nt_f64(const bf16_t* __restrict__ A,
-                                                     const bf16_t* __restrict__ B,
-                                                     double* __restrict__ Cm, int M, int N, int Kd) {
-  __shared__ double red[4][16];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int n0 = blockIdx.x * 2;
+// Kd % 8 == 0.  Rows n0, n0 + 1 of B against all M rows of A (8 at a time), fp64 accumulation; the 16
+// wave sums of a round as one butterfly of half and row swaps.
+__device__ __forceinline__ void gemv_nt_rows(const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                             double* __restrict__ Cm, int M, int N, int Kd, int n0,
+                                             double (*red)[16]) {
+  const int tid = threadIdx.x, w = tid >> 6;
   for (int mb = 0; mb < M; mb += 8) {
     double acc[8][2];
 #pragma unroll
@@ -410,15 +409,15 @@ __global__ __launch_bounds__(256) void k_gemv_nt_f64(const bf16_t* __restrict__ 
         }
       }
     }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      acc[i][0] = wave_sum_d(acc[i][0]);
-      acc[i][1] = wave_sum_d(acc[i][1]);
-    }
+    // value 2 i + r (row mb + i of A, row n0 + r of B): lane 15 of row rho of register j holds the
+    // wave's sum of value 4 j + 2 (rho & 1) + (rho >> 1)
+    double ws[4];
+    wave_sums_butterfly_d<16>(&acc[0][0], ws);
     __syncthreads();
-    if (lane == 0) {
+    if ((tid & 15) == 15) {
+      const int rho = (tid >> 4) & 3;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) { red[w][2 * i] = acc[i][0]; red[w][2 * i + 1] = acc[i][1]; }
+      for (int j = 0; j < 4; ++j) red[w][4 * j + 2 * (rho & 1) + (rho >> 1)] = ws[j];
     }
     __syncthreads();
     if (tid < 16) {
@@ -427,6 +426,26 @@ __global__ __launch_bounds__(256) void k_gemv_nt_f64(const bf16_t* __restrict__ 
         Cm[(size_t)(mb + i) * N + n0 + r] = red[0][tid] + red[1][tid] + red[2][tid] + red[3][tid];
     }
   }
+}
+
+// grid (ceil(N/2))
+__global__ __launch_bounds__(256) void k_gemv_nt_f64(const bf16_t* __restrict__ A,
+                                                     const bf16_t* __restrict__ B,
+                                                     double* __restrict__ Cm, int M, int N, int Kd) {
+  __shared__ double red[4][16];
+  gemv_nt_rows(A, B, Cm, M, N, Kd, blockIdx.x * 2, red);
+}
+
+// Two such products in one launch (the query projection and the head gate of a decode-size scoring call):
+// grid (ceil(N1/2) + ceil(N2/2))
+__global__ __launch_bounds__(256) void k_gemv2_nt_f64(const bf16_t* __restrict__ A1, const bf16_t* __restrict__ B1,
+                                                      double* __restrict__ C1, int N1, int K1,
+                                                      const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2,
+                                                      double* __restrict__ C2, int N2, int K2, int M) {
+  __shared__ double red[4][16];
+  const int nb1 = (N1 + 1) / 2;
+  if ((int)blockIdx.x < nb1) gemv_nt_rows(A1, B1, C1, M, N1, K1, blockIdx.x * 2, red);
+  else gemv_nt_rows(A2, B2, C2, M, N2, K2, ((int)blockIdx.x - nb1) * 2, red);
 }
 
 // RMSNorm of every indexer query head in place: y[m][j][0..di-1] -> fp32-rounded q, kept as fp64.
@@ -447,6 +466,26 @@ __global__ __launch_bounds__(256) void k_qnorm(double* __restrict__ y, int rows,
 __global__ void k_alpha_scale(double* __restrict__ a, int n, double denom) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) a[i] = (double)(float)(a[i] / denom);
+}
+
+// Both of the above in one launch (few rows: a decode-size scoring call).  grid (ceil(rows/4) + ceil(n/256))
+__global__ __launch_bounds__(256) void k_qnorm_alpha(double* __restrict__ y, int rows, int di,
+                                                     const bf16_t* __restrict__ norm_w, float rms_eps,
+                                                     double* __restrict__ a, int n, double denom) {
+  const int nbq = (rows + 3) / 4;
+  if ((int)blockIdx.x >= nbq) {
+    const int i = ((int)blockIdx.x - nbq) * 256 + threadIdx.x;
+    if (i < n) a[i] = (double)(float)(a[i] / denom);
+    return;
+  }
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= rows) return;
+  const bool on = lane < di;
+  const double v = on ? y[(size_t)row * di + lane] : 0.0;
+  const double ss = wave_sum_d(v * v);
+  const double rr = sqrt(ss / (double)di + (double)rms_eps);
+  const double w = (norm_w && on) ? (double)bf2f(norm_w[lane]) : 1.0;
+  if (on) y[(size_t)row * di + lane] = (double)(float)(v / rr * w);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -801,6 +840,34 @@ __global__ __launch_bounds__(1024) void k_select(const float* __restrict__ score
     return forced ? IM_KEY_PINF : score_key(sc[i]);
   };
 
+  if (k == n - 1 && n >= 2) {
+    // One entry leaves (a decode step): it is the one ranked last: smallest score key, then largest
+    // position, then largest slot.  One reduction instead of the radix passes; the lists follow from it.
+    unsigned long long best = ~0ull;   // (key << 32) | ~position key: its minimum is the last-ranked (score, position)
+    int bslot = -1;
+    for (int i = tid; i < n; i += 1024) {
+      const unsigned long long c = ((unsigned long long)key_of(i) << 32) | (uint32_t)(~((uint32_t)ps[i] ^ 0x80000000u));
+      if (c <= best) { best = c; bslot = i; }   // ascending slots: <= keeps the largest
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const unsigned long long ob = __shfl_xor(best, o, 64);
+      const int os = __shfl_xor(bslot, o, 64);
+      if (os >= 0 && (bslot < 0 || ob < best || (ob == best && os > bslot))) { best = ob; bslot = os; }
+    }
+    __shared__ unsigned long long sh_b[16];
+    if ((tid & 63) == 0) { sh_b[tid >> 6] = best; sh_red[tid >> 6] = bslot; }
+    __syncthreads();
+    for (int i = 0; i < 16; ++i) {
+      const unsigned long long ob = sh_b[i];
+      const int os = sh_red[i];
+      if (os >= 0 && (bslot < 0 || ob < best || (ob == best && os > bslot))) { best = ob; bslot = os; }
+    }
+    const int e = bslot;
+    for (int i = tid; i < n - 1; i += 1024) keep[i] = (i < e) ? i : i + 1;
+    if (tid == 0) { evict[0] = e; n_keep[unit] = n - 1; n_evict[unit] = 1; }
+    return;
+  }
   // mode: 0 = keep all, 1 = keep none, 2 = threshold
   uint32_t T = 0, P = 0xffffffffu;
   unsigned rem2 = 0;
@@ -906,6 +973,8 @@ __global__ __launch_bounds__(1024) void k_select(const float* __restrict__ score
 // then the decayed update (deterministic: splits are added in order).
 // ------------------------------------------------------------------------------------------
 #define IM_MEM_TOK 32  // evicted rows per MFMA tile (a sub-tile of the fold block)
+#define IM_MEM_FEW 4   // up to this many evicted rows (a decode step evicts one) k_mem_finalize does the whole
+                       // update in fp32 FMAs by itself and the partial kernels return at once
 
 typedef short im_v4s __attribute__((ext_vector_type(4)));
 typedef float im_v16f __attribute__((ext_vector_type(16)));
@@ -932,7 +1001,7 @@ __global__ __launch_bounds__(256) void k_mem_partial(const bf16_t* __restrict__ 
   __shared__ __attribute__((aligned(16))) bf16_t Vs[IM_MEM_TOK][IM_D + 8];     // V rows of the tile
   const int unit = blockIdx.y, split = blockIdx.x, tid = threadIdx.x;
   const int ne = n_evict[unit];
-  if (ne <= 0) return;
+  if (ne <= IM_MEM_FEW) return;
   const int bps = im_mem_blocks_per_split(ne, fold_block, n_split);
   const int i0 = split * bps * fold_block;
   const int i1 = min(ne, i0 + bps * fold_block);
@@ -1063,7 +1132,7 @@ __global__ __launch_bounds__(256) void k_mem_partial_sets(const bf16_t* __restri
   __shared__ __attribute__((aligned(16))) bf16_t Vs[IM_MEM_TOK][IM_D + 8];
   const int set = blockIdx.y, split = blockIdx.x, tid = threadIdx.x;
   const int ne = n_evict[set];
-  if (ne <= 0) return;
+  if (ne <= IM_MEM_FEW) return;
   const int bps = im_mem_blocks_per_split(ne, fold_block, n_split);
   const int i0 = split * bps * fold_block;
   const int i1 = min(ne, i0 + bps * fold_block);
@@ -1157,14 +1226,76 @@ __global__ __launch_bounds__(256) void k_mem_partial_sets(const bf16_t* __restri
   }
 }
 
-// grid (ceil((DM*D + DM)/256), units)
+// grid (ceil((DM*D + DM)/256), sets): a workgroup owns two rows of M, the last one owns b.
+// With at most IM_MEM_FEW evicted rows there are no partials: the workgroup sums the rows over the set's
+// heads (fp32), takes Phi = W k for its own rows of W and applies the update itself.
 __global__ __launch_bounds__(256) void k_mem_finalize(float* __restrict__ M, float* __restrict__ bvec,
                                                       const int32_t* __restrict__ n_evict,
                                                       const float* __restrict__ part, int fold_block,
-                                                      int n_split, float lambda, float eta) {
+                                                      int n_split, float lambda, float eta,
+                                                      const bf16_t* __restrict__ K, const bf16_t* __restrict__ V,
+                                                      const int32_t* __restrict__ evict_idx,
+                                                      const bf16_t* __restrict__ Wtheta, int C, int H_set) {
   const int unit = blockIdx.y;
   const int ne = n_evict[unit];
   if (ne <= 0) return;
+  if (ne <= IM_MEM_FEW) {
+    __shared__ float ks[IM_MEM_FEW][IM_D], vs[IM_MEM_FEW][IM_D], red[IM_MEM_FEW][4];
+    const int tid = threadIdx.x, w = tid >> 6;
+    const bool bblock = blockIdx.x == IM_DM * IM_D / 256;   // the workgroup of the 128 entries of b
+    for (int idx = tid; idx < ne * IM_D; idx += 256) {
+      const int i = idx >> 7, d = idx & 127;
+      const int slot = evict_idx[(size_t)unit * C + i];
+      float kk = 0.f, vv = 0.f;
+      for (int hh = 0; hh < H_set; ++hh) {
+        const size_t row = ((size_t)(unit * H_set + hh) * C + slot) * IM_D + d;
+        kk += bf2f(K[row]);
+        if (!bblock) vv += bf2f(V[row]);
+      }
+      ks[i][d] = kk;
+      vs[i][d] = vv;
+    }
+    __syncthreads();
+    if (bblock) {
+      if (tid < IM_DM) {
+        const uint4* wp = (const uint4*)(Wtheta + tid * IM_D);
+        float ph[IM_MEM_FEW];
+#pragma unroll
+        for (int i = 0; i < IM_MEM_FEW; ++i) ph[i] = 0.f;
+#pragma unroll 4
+        for (int g = 0; g < 16; ++g) {
+          const uint4 u = wp[g];
+          const float wr[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
+                               bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
+#pragma unroll
+          for (int i = 0; i < IM_MEM_FEW; ++i)
+            if (i < ne) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) ph[i] = fmaf(wr[e], ks[i][8 * g + e], ph[i]);
+            }
+        }
+        float s = 0.f;
+#pragma unroll
+        for (int i = 0; i < IM_MEM_FEW; ++i)
+          if (i < ne) s = fmaf(ph[i], ph[i], s);
+        float* dst = bvec + (size_t)unit * IM_DM + tid;
+        *dst = fmaf(lambda, *dst, eta * s);
+      }
+      return;
+    }
+    const int c = blockIdx.x * 2 + (tid >> 7), d = tid & 127;
+    const float wv = bf2f(Wtheta[c * IM_D + d]);
+    for (int i = 0; i < ne; ++i) {
+      const float t = wave_sum_f(wv * ks[i][d]);
+      if ((tid & 63) == 0) red[i][w] = t;
+    }
+    __syncthreads();
+    float s = 0.f;
+    for (int i = 0; i < ne; ++i) s = fmaf(red[i][w & 2] + red[i][(w & 2) + 1], vs[i][d], s);
+    float* dst = M + (size_t)unit * IM_DM * IM_D + c * IM_D + d;
+    *dst = fmaf(lambda, *dst, eta * s);
+    return;
+  }
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= IM_DM * IM_D + IM_DM) return;
   const int bps = im_mem_blocks_per_split(ne, fold_block, n_split);
@@ -1188,7 +1319,8 @@ __global__ __launch_bounds__(256) void k_compact(bf16_t* __restrict__ K, bf16_t*
                                                  int32_t* __restrict__ n_projected,
                                                  const int32_t* __restrict__ keep_idx,
                                                  const int32_t* __restrict__ n_keep,
-                                                 const int32_t* __restrict__ evict_idx, int C, int H_set,
+                                                 const int32_t* __restrict__ evict_idx,
+                                                 const int32_t* __restrict__ n_evict, int C, int H_set,
                                                  int di, int max_live, int32_t* __restrict__ status) {
   const int unit = blockIdx.y, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int set = unit / H_set;
@@ -1199,16 +1331,28 @@ __global__ __launch_bounds__(256) void k_compact(bf16_t* __restrict__ K, bf16_t*
     if (lead && blockIdx.x == 0 && threadIdx.x == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
     return;
   }
-  const int nk = n_keep[set];
+  const int nk = n_keep[set], ne = n_evict[set];
   const int32_t* keep = keep_idx + (size_t)set * C;
   const int32_t* evict = evict_idx + (size_t)set * C;
-  // p = number of kept slots below nk (keep is ascending)
-  int lo = 0, hi = nk;
-  while (lo < hi) {
-    const int mid = (lo + hi) >> 1;
-    if (keep[mid] < nk) lo = mid + 1; else hi = mid;
+  // p = number of kept slots below nk = nk - number of evicted slots below nk (both lists ascend, and
+  // together they hold every live slot once): found in the shorter list, one probe for a single eviction
+  int p;
+  if (ne < nk) {
+    int lo = 0, hi = ne;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (evict[mid] < nk) lo = mid + 1; else hi = mid;
+    }
+    p = nk - lo;
+  } else {
+    int lo = 0, hi = nk;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (keep[mid] < nk) lo = mid + 1; else hi = mid;
+    }
+    p = lo;
   }
-  const int p = lo, n_moves = nk - p;
+  const int n_moves = nk - p;
   for (int j = blockIdx.x * 4 + w; j < n_moves; j += gridDim.x * 4) {
     const int ss = keep[p + j], ds = evict[j];
     const size_t src = (size_t)unit * C + ss, dst = (size_t)unit * C + ds;
@@ -1323,36 +1467,54 @@ __global__ __launch_bounds__(256) void k_attn_partial(const bf16_t* __restrict__
   }
   const bf16_t* Kb = K + (size_t)unit * C * IM_D;
   const bf16_t* Vb = V + (size_t)unit * C * IM_D;
-  // 4 keys of the 16-lane row per round: their 8 loads go out together, ahead of the arithmetic
-#pragma unroll 1
-  for (int it0 = 0; it0 < IM_ATT_CHUNK / 16; it0 += 4) {
-    uint4 ku[4], vu[4];
+  // the 8 keys of this 16-lane row: all 16 loads go out before any arithmetic (one memory round trip);
+  // then two rounds of 4 keys, each with one rescaling of the running sums
+  uint4 ku[8], vu[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int kc = min(k0 + w * (IM_ATT_CHUNK / 4) + i * 4 + grp, n - 1);
+    ku[i] = *(const uint4*)(Kb + (size_t)kc * IM_D + l16 * 8);
+    vu[i] = *(const uint4*)(Vb + (size_t)kc * IM_D + l16 * 8);
+  }
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    float sv[4][G];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int kc = min(k0 + w * (IM_ATT_CHUNK / 4) + (it0 + i) * 4 + grp, n - 1);
-      ku[i] = *(const uint4*)(Kb + (size_t)kc * IM_D + l16 * 8);
-      vu[i] = *(const uint4*)(Vb + (size_t)kc * IM_D + l16 * 8);
+      const uint4 u = ku[4 * r + i];
+      const bool valid = k0 + w * (IM_ATT_CHUNK / 4) + (4 * r + i) * 4 + grp < n;
+      const float kf[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
+                           bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
+#pragma unroll
+      for (int j = 0; j < G; ++j) {
+        float t = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) t = fmaf(qf[j][e], kf[e], t);
+        t = row16_sum_f(t);   // (DPP rotations inside the 16-lane row)
+        sv[i][j] = valid ? t : -INFINITY;
+      }
+    }
+    float corr[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+      const float mn = fmaxf(fmaxf(mx[j], fmaxf(sv[0][j], sv[1][j])), fmaxf(sv[2][j], sv[3][j]));
+      corr[j] = __expf(mx[j] - mn);
+      mx[j] = mn;
+      ls[j] *= corr[j];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[j][e] *= corr[j];
     }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const bool valid = k0 + w * (IM_ATT_CHUNK / 4) + (it0 + i) * 4 + grp < n;
-      const float kf[8] = {bf_lo(ku[i].x), bf_hi(ku[i].x), bf_lo(ku[i].y), bf_hi(ku[i].y),
-                           bf_lo(ku[i].z), bf_hi(ku[i].z), bf_lo(ku[i].w), bf_hi(ku[i].w)};
-      const float vf[8] = {bf_lo(vu[i].x), bf_hi(vu[i].x), bf_lo(vu[i].y), bf_hi(vu[i].y),
-                           bf_lo(vu[i].z), bf_hi(vu[i].z), bf_lo(vu[i].w), bf_hi(vu[i].w)};
+      const uint4 u = vu[4 * r + i];
+      const float vf[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
+                           bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
 #pragma unroll
       for (int j = 0; j < G; ++j) {
-        float s = 0.f;
+        const float p = __expf(sv[i][j] - mx[j]);
+        ls[j] += p;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) s = fmaf(qf[j][e], kf[e], s);
-        s = row16_sum_f(s);   // (DPP rotations inside the 16-lane row)
-        if (!valid) s = -INFINITY;
-        const float mn = fmaxf(mx[j], s);
-        const float corr = __expf(mx[j] - mn), p = __expf(s - mn);
-        ls[j] = fmaf(ls[j], corr, p);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(acc[j][e], corr, p * vf[e]);
-        mx[j] = mn;
+        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, vf[e], acc[j][e]);
       }
     }
   }

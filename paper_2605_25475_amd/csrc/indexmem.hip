@@ -374,17 +374,21 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
         (const bf16_t*)p->norm_k_w, c.capacity, h->max_live, c.rms_eps, status_ptr(h));
 
   const int M = c.batch * n_q, Nq = c.n_idx_heads * di, Kq = c.n_q_heads * IM_D;
+  const int rows = M * c.n_idx_heads;
   if (M <= 32) {
-    k_gemv_nt_f64<<<(Nq + 1) / 2, 256, 0, s>>>((const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, M, Nq, Kq);
-    k_gemv_nt_f64<<<(c.n_idx_heads + 1) / 2, 256, 0, s>>>((const bf16_t*)x_gate, (const bf16_t*)p->G, al,
-                                                         M, c.n_idx_heads, c.gate_in_dim);
+    // a decode-size call: both products in one launch, then the QK-Norm and the gate scaling in one
+    k_gemv2_nt_f64<<<(Nq + 1) / 2 + (c.n_idx_heads + 1) / 2, 256, 0, s>>>(
+        (const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, Nq, Kq, (const bf16_t*)x_gate, (const bf16_t*)p->G, al,
+        c.n_idx_heads, c.gate_in_dim, M);
+    k_qnorm_alpha<<<(rows + 3) / 4 + (rows + 255) / 256, 256, 0, s>>>(qy, rows, di, (const bf16_t*)p->norm_q_w,
+                                                                     c.rms_eps, al, rows,
+                                                                     sqrt((double)(c.n_idx_heads * di)));
   } else {
     gemm_nt(s, (const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, M, Nq, Kq);
     gemm_nt(s, (const bf16_t*)x_gate, (const bf16_t*)p->G, al, M, c.n_idx_heads, c.gate_in_dim);
+    k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, di, (const bf16_t*)p->norm_q_w, c.rms_eps);
+    k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, sqrt((double)(c.n_idx_heads * di)));
   }
-  const int rows = M * c.n_idx_heads;
-  k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, di, (const bf16_t*)p->norm_q_w, c.rms_eps);
-  k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, sqrt((double)(c.n_idx_heads * di)));
   // fewer queries than indexer heads (a decode step): the heads of a query are the product's columns
   if (n_q < c.n_idx_heads && c.n_idx_heads <= 16) {
     const dim3 grid((h->max_live + 63) / 64, units);
@@ -468,7 +472,8 @@ int32_t im_memory_update(im_handle* h, const im_params* p, const im_state* st,
         (const bf16_t*)st->K, (const bf16_t*)st->V, evict_idx, n_evict, (const bf16_t*)p->Wtheta,
         c.capacity, c.fold_block, h->mem_split, part);
   k_mem_finalize<<<dim3((IM_DM * IM_D + IM_DM + 255) / 256, units), 256, 0, s>>>(
-      st->M, st->b, n_evict, part, c.fold_block, h->mem_split, lambda, eta);
+      st->M, st->b, n_evict, part, c.fold_block, h->mem_split, lambda, eta, (const bf16_t*)st->K,
+      (const bf16_t*)st->V, evict_idx, (const bf16_t*)p->Wtheta, c.capacity, heads_per_set(c));
   return launch_check(h, "im_memory_update");
 }
 
@@ -485,7 +490,7 @@ int32_t im_compact_kv(im_handle* h, const im_state* st, const int32_t* keep_idx,
   if (gx > 64) gx = 64;
   k_compact<<<dim3(gx, c.batch * c.n_kv_heads), 256, 0, s>>>(
       (bf16_t*)st->K, (bf16_t*)st->V, (bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, keep_idx,
-      n_keep, evict_idx, c.capacity, heads_per_set(c), c.idx_dim, h->max_live, status_ptr(h));
+      n_keep, evict_idx, n_evict, c.capacity, heads_per_set(c), c.idx_dim, h->max_live, status_ptr(h));
   return launch_check(h, "im_compact_kv");
 }
 
