@@ -94,12 +94,6 @@ __device__ __forceinline__ int hs_pick(const uint4 (&pk)[HS_NSC]) {
   return at;
 }
 
-// a 16-byte load with the streaming hint: data that is read once per step
-typedef unsigned int dec_u4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ uint4 load_stream16(const void* p) {
-  const dec_u4 v = __builtin_nontemporal_load((const dec_u4*)p);
-  return make_uint4(v.x, v.y, v.z, v.w);
-}
 // wait until at most 4 of this wave's vector memory loads are outstanding (loads return in order)
 __device__ __forceinline__ void dec_pace4() { asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); }
 

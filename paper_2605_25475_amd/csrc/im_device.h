@@ -184,3 +184,10 @@ __device__ __forceinline__ float halves_sum_f(float v) {
   const u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+
+// a 16-byte load with the streaming hint: data that is read once per step
+typedef unsigned int dec_u4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  const dec_u4 v = __builtin_nontemporal_load((const dec_u4*)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}

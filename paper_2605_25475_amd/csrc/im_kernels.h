@@ -153,7 +153,54 @@ __global__ __launch_bounds__(256) void k_project_keys(const bf16_t* __restrict__
     if (tid == 0 && blockIdx.x == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
     n = max_live;
   }
-  const int row0 = n_projected[unit] + blockIdx.x * 64 + 16 * w;
+  const int np = n_projected[unit];
+  if (n - np <= 4) {
+    // A few new rows (a decode step appends one): the unit's first workgroup projects them with plain
+    // fp64 FMAs: 4 lanes per output column, 32 dims each.  (Products of bf16 values summed in fp64 are
+    // exact at these sizes, so the order of the sum is immaterial and the rows equal the matrix-core ones.)
+    if (blockIdx.x != 0 || n <= np) return;
+    __shared__ double ys[4][IM_DI];
+    const int nr = n - np, c = tid >> 2, q4 = tid & 3;
+    uint4 ub[4], ka[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ub[i] = *(const uint4*)(Uk + c * IM_D + 32 * q4 + 8 * i);
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        ka[r][i] = *(const uint4*)(K + ((size_t)unit * C + np + min(r, nr - 1)) * IM_D + 32 * q4 + 8 * i);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint4 u = ub[i];
+      const float fb[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
+                           bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const uint4 v = ka[r][i];
+        const float fa[8] = {bf_lo(v.x), bf_hi(v.x), bf_lo(v.y), bf_hi(v.y),
+                             bf_lo(v.z), bf_hi(v.z), bf_lo(v.w), bf_hi(v.w)};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[r] = fma((double)fa[e], (double)fb[e], acc[r]);
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      acc[r] += __shfl_xor(acc[r], 1, 64);
+      acc[r] += __shfl_xor(acc[r], 2, 64);
+      if (q4 == 0) ys[r][c] = acc[r];
+    }
+    __syncthreads();
+    if (w < nr) {   // wave w: row w, lane = column
+      const double y = ys[w][lane];
+      const double ss = wave_sum_d(y * y);
+      const double rr = sqrt(ss / (double)IM_DI + (double)rms_eps);
+      const double wn1 = norm_w ? (double)bf2f(norm_w[lane]) : 1.0;
+      Kidx[((size_t)unit * C + np + w) * IM_DI + lane] = d2bf_rne(y / rr * wn1);
+    }
+    return;
+  }
+  const int row0 = np + blockIdx.x * 64 + 16 * w;
   if (row0 >= n) return;                       // wave-uniform; no workgroup barrier below
   const int rows = min(16, n - row0);
   const size_t krow = ((size_t)unit * C + row0 + min(l16, rows - 1)) * IM_D;   // rows past the end repeat the last
@@ -1120,7 +1167,7 @@ __global__ __launch_bounds__(256) void k_mem_partial(const bf16_t* __restrict__ 
 // are summed across heads per token): Phi^T = sum_h W K_h and M += sum_h Phi V_h by linearity, so
 // the sums over heads are taken inside the two products' accumulators and no summed row is ever
 // rounded.  K, V are per unit (set * H_set + head); lists, counts and the partials per set.
-// grid (n_split, sets), 4 waves; no prefetch: this runs once per eviction event of a prompt.
+// grid (n_split, sets), 4 waves.
 __global__ __launch_bounds__(256) void k_mem_partial_sets(const bf16_t* __restrict__ K,
                                                           const bf16_t* __restrict__ V,
                                                           const int32_t* __restrict__ evict_idx,
@@ -1152,20 +1199,40 @@ __global__ __launch_bounds__(256) void k_mem_partial_sets(const bf16_t* __restri
   for (int r = 0; r < 16; ++r) bsum[r] = 0.f;
   const int32_t* ev = evict_idx + (size_t)set * C;
   const int vr0 = tid >> 4, vc16 = tid & 15;
+  // Software pipeline over (tile, head): while one head's rows are in the matrix cores the next head's
+  // rows are in flight (K rows during the first product, V rows during the second; the last V phase of a
+  // tile fetches the first K rows of the next tile), and a tile's list entries are read one tile ahead.
+  // Entries past the end of the split repeat its last one; their rows are zeroed after the load.
+  auto list_at = [&](int t) { return ev[min(t, i1 - 1)]; };
+  auto load_k = [&](int hh, int slot, im_v4s* dst) {
+    const bf16_t* kr = K + ((size_t)(set * H_set + hh) * C + slot) * IM_D + 4 * kh;
+#pragma unroll
+    for (int ks = 0; ks < 16; ++ks) dst[ks] = *(const im_v4s*)(kr + 8 * ks);
+  };
+  int ek = list_at(i0 + l32), ev0 = list_at(i0 + vr0), ev1 = list_at(i0 + vr0 + 16);
+  im_v4s kb_n[16];
+  load_k(0, ek, kb_n);
 #pragma unroll 1
   for (int t0 = i0; t0 < i1; t0 += IM_MEM_TOK) {
-    const int ek = ev[min(t0 + l32, i1 - 1)];
-    const int ev0 = ev[min(t0 + vr0, i1 - 1)], ev1 = ev[min(t0 + vr0 + 16, i1 - 1)];
+    const int ek_n = list_at(t0 + IM_MEM_TOK + l32);
+    const int ev0_n = list_at(t0 + IM_MEM_TOK + vr0), ev1_n = list_at(t0 + IM_MEM_TOK + vr0 + 16);
     const bool k_on = t0 + l32 < i1, v0_on = t0 + vr0 < i1, v1_on = t0 + vr0 + 16 < i1;
     im_v16f ph;
 #pragma unroll
     for (int r = 0; r < 16; ++r) ph[r] = 0.f;
+    uint4 vv0_n = make_uint4(0, 0, 0, 0), vv1_n = vv0_n;
 #pragma unroll 1
     for (int hh = 0; hh < H_set; ++hh) {
-      const bf16_t* kr = K + ((size_t)(set * H_set + hh) * C + ek) * IM_D + 4 * kh;
       im_v4s kb[16];
 #pragma unroll
-      for (int ks = 0; ks < 16; ++ks) kb[ks] = k_on ? *(const im_v4s*)(kr + 8 * ks) : im_v4s{0, 0, 0, 0};
+      for (int ks = 0; ks < 16; ++ks) kb[ks] = k_on ? kb_n[ks] : im_v4s{0, 0, 0, 0};
+      if (hh + 1 < H_set) {
+        load_k(hh + 1, ek, kb_n);
+      } else {   // the first head's V rows of this tile
+        const size_t ub = (size_t)(set * H_set) * C;
+        vv0_n = *(const uint4*)(V + (ub + ev0) * IM_D + vc16 * 8);
+        vv1_n = *(const uint4*)(V + (ub + ev1) * IM_D + vc16 * 8);
+      }
 #pragma unroll
       for (int ks = 0; ks < 16; ++ks) ph = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(wa[ks], kb[ks], ph, 0, 0, 0);
     }
@@ -1189,9 +1256,15 @@ __global__ __launch_bounds__(256) void k_mem_partial_sets(const bf16_t* __restri
       }
 #pragma unroll 1
     for (int hh = 0; hh < H_set; ++hh) {
-      const size_t ub = (size_t)(set * H_set + hh) * C;
-      const uint4 vv0 = v0_on ? *(const uint4*)(V + (ub + ev0) * IM_D + vc16 * 8) : make_uint4(0, 0, 0, 0);
-      const uint4 vv1 = v1_on ? *(const uint4*)(V + (ub + ev1) * IM_D + vc16 * 8) : make_uint4(0, 0, 0, 0);
+      const uint4 vv0 = v0_on ? vv0_n : make_uint4(0, 0, 0, 0);
+      const uint4 vv1 = v1_on ? vv1_n : make_uint4(0, 0, 0, 0);
+      if (hh + 1 < H_set) {
+        const size_t ub = (size_t)(set * H_set + hh + 1) * C;
+        vv0_n = *(const uint4*)(V + (ub + ev0) * IM_D + vc16 * 8);
+        vv1_n = *(const uint4*)(V + (ub + ev1) * IM_D + vc16 * 8);
+      } else {   // the first head's K rows of the next tile (of the last entry again, unused, after the last tile)
+        load_k(0, ek_n, kb_n);
+      }
       __syncthreads();   // the previous head's reads of Vs are done
       *(uint4*)&Vs[vr0][vc16 * 8] = vv0;
       *(uint4*)&Vs[vr0 + 16][vc16 * 8] = vv1;
@@ -1207,6 +1280,7 @@ __global__ __launch_bounds__(256) void k_mem_partial_sets(const bf16_t* __restri
           macc[db] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(al[kt], vb, macc[db], 0, 0, 0);
         }
     }
+    ek = ek_n; ev0 = ev0_n; ev1 = ev1_n;
   }
   float* out = part + ((size_t)set * n_split + split) * (IM_DM * IM_D + IM_DM);
 #pragma unroll
@@ -1243,6 +1317,13 @@ __global__ __launch_bounds__(256) void k_mem_finalize(float* __restrict__ M, flo
     __shared__ float ks[IM_MEM_FEW][IM_D], vs[IM_MEM_FEW][IM_D], red[IM_MEM_FEW][4];
     const int tid = threadIdx.x, w = tid >> 6;
     const bool bblock = blockIdx.x == IM_DM * IM_D / 256;   // the workgroup of the 128 entries of b
+    // this thread's weight and old entry of M depend on nothing: their loads go out with the list's
+    float wv = 0.f, mold = 0.f;
+    float* mdst = M + (size_t)unit * IM_DM * IM_D + (blockIdx.x * 2 + (tid >> 7)) * IM_D + (tid & 127);
+    if (!bblock) {
+      wv = bf2f(Wtheta[(blockIdx.x * 2 + (tid >> 7)) * IM_D + (tid & 127)]);
+      mold = *mdst;
+    }
     for (int idx = tid; idx < ne * IM_D; idx += 256) {
       const int i = idx >> 7, d = idx & 127;
       const int slot = evict_idx[(size_t)unit * C + i];
@@ -1283,8 +1364,7 @@ __global__ __launch_bounds__(256) void k_mem_finalize(float* __restrict__ M, flo
       }
       return;
     }
-    const int c = blockIdx.x * 2 + (tid >> 7), d = tid & 127;
-    const float wv = bf2f(Wtheta[c * IM_D + d]);
+    const int d = tid & 127;
     for (int i = 0; i < ne; ++i) {
       const float t = wave_sum_f(wv * ks[i][d]);
       if ((tid & 63) == 0) red[i][w] = t;
@@ -1292,8 +1372,7 @@ __global__ __launch_bounds__(256) void k_mem_finalize(float* __restrict__ M, flo
     __syncthreads();
     float s = 0.f;
     for (int i = 0; i < ne; ++i) s = fmaf(red[i][w & 2] + red[i][(w & 2) + 1], vs[i][d], s);
-    float* dst = M + (size_t)unit * IM_DM * IM_D + c * IM_D + d;
-    *dst = fmaf(lambda, *dst, eta * s);
+    *mdst = fmaf(lambda, mold, eta * s);
     return;
   }
   const int e = blockIdx.x * 256 + threadIdx.x;
@@ -1429,8 +1508,18 @@ __global__ __launch_bounds__(256) void k_gather_kept(const bf16_t* __restrict__ 
 // ------------------------------------------------------------------------------------------
 #define IM_ATT_CHUNK 128   // keys per workgroup: 32 per wave
 #define IM_ATT_REC (IM_D + 2)  // partial record: running max, denominator, 128 numerators
+#define IM_COMB_LDS 512        // chunks whose maxima and denominators the combine stages in LDS
 
-// grid (chunks, units).  16 lanes share a key row (8 dims each); a wave handles 4 keys at a time.
+// grid (chunks, units), 4 waves; wave w owns keys 32 w .. 32 w + 31 of the chunk as 2 tiles of 16.
+// Logits on the bf16 matrix cores: S[key][head] = K_tile Q^T, 16x16x16, fp32 accumulation (operand lane
+// (l16, kq): row l16, k = 4 kq .. 4 kq + 3 of a 16-wide step; a 32-dim chunk c of the rows gives two steps,
+// lane (l16, kq) holding dims 32 c + 8 kq .. + 7 of row l16; result register r of the lane is key 4 kq + r,
+// head l16).  Softmax statistics per wave (relative to the maximum of the wave's own 32 keys), the
+// probabilities through LDS, P V with 16 lanes sharing a V row (8 dims each); the 4 waves' partials are
+// rescaled to the chunk's maximum at the end.
+typedef short im_att_v4s __attribute__((ext_vector_type(4)));
+typedef float im_att_v4f __attribute__((ext_vector_type(4)));
+
 template <int G>
 __global__ __launch_bounds__(256) void k_attn_partial(const bf16_t* __restrict__ K,
                                                       const bf16_t* __restrict__ V,
@@ -1441,6 +1530,7 @@ __global__ __launch_bounds__(256) void k_attn_partial(const bf16_t* __restrict__
                                                       int32_t* __restrict__ status) {
   __shared__ float s_ml[4][G][2];
   __shared__ float s_acc[4][G][IM_D];
+  __shared__ float pl[IM_ATT_CHUNK][8];   // probabilities [key][head]
   const int unit = blockIdx.y, chunk = blockIdx.x;
   const int b = unit / H_kv, h = unit % H_kv;
   const int n_true = len[unit / H_set];
@@ -1448,88 +1538,96 @@ __global__ __launch_bounds__(256) void k_attn_partial(const bf16_t* __restrict__
   if (n_true > max_live && chunk == 0 && threadIdx.x == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
   const int k0 = chunk * IM_ATT_CHUNK;
   if (k0 >= n) return;
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, grp = lane >> 4, l16 = lane & 15;
-  float qf[G][8];
+  const int nk = min(IM_ATT_CHUNK, n - k0);
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, kq = lane >> 4, l16 = lane & 15;
+  const bf16_t* Kb = K + ((size_t)unit * C + k0) * IM_D;
+  const bf16_t* Vb = V + ((size_t)unit * C + k0) * IM_D;
+  // every load first (rows past the end of the chunk repeat its last row: finite values, masked below)
+  uint4 kf[2][4], qf[4], vf[2][4];
 #pragma unroll
-  for (int j = 0; j < G; ++j) {
-    const uint4 u = *(const uint4*)(q + ((size_t)b * H + h * G + j) * IM_D + l16 * 8);
-    qf[j][0] = bf_lo(u.x) * scale; qf[j][1] = bf_hi(u.x) * scale;
-    qf[j][2] = bf_lo(u.y) * scale; qf[j][3] = bf_hi(u.y) * scale;
-    qf[j][4] = bf_lo(u.z) * scale; qf[j][5] = bf_hi(u.z) * scale;
-    qf[j][6] = bf_lo(u.w) * scale; qf[j][7] = bf_hi(u.w) * scale;
+  for (int tt = 0; tt < 2; ++tt) {
+    const int kr = min(16 * (2 * w + tt) + l16, nk - 1);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) kf[tt][c] = load_stream16(Kb + (size_t)kr * IM_D + 32 * c + 8 * kq);
   }
-  float mx[G], ls[G], acc[G][8];
+  {
+    const int jq = min(l16, G - 1);   // lanes past the group read its last head; zeroed where used
 #pragma unroll
-  for (int j = 0; j < G; ++j) {
-    mx[j] = -1e30f; ls[j] = 0.f;
+    for (int c = 0; c < 4; ++c) qf[c] = *(const uint4*)(q + ((size_t)b * H + h * G + jq) * IM_D + 32 * c + 8 * kq);
+  }
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int vr = min(16 * (2 * w + tt) + 4 * i + kq, nk - 1);
+      vf[tt][i] = load_stream16(Vb + (size_t)vr * IM_D + 8 * l16);
+    }
+  __asm__ volatile("" ::: "memory");   // keep the loads above the arithmetic, in this order
+  float sreg[2][4];
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt) {
+    im_att_v4f acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint4 ka = kf[tt][c], qb = (l16 < G) ? qf[c] : make_uint4(0, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(im_att_v4s, make_uint2(ka.x, ka.y)),
+                                                      __builtin_bit_cast(im_att_v4s, make_uint2(qb.x, qb.y)), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(im_att_v4s, make_uint2(ka.z, ka.w)),
+                                                      __builtin_bit_cast(im_att_v4s, make_uint2(qb.z, qb.w)), acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)   // this lane: head l16, key 16 (2 w + tt) + 4 kq + r
+      sreg[tt][r] = (16 * (2 * w + tt) + 4 * kq + r < nk) ? acc[r] * scale : -INFINITY;
+  }
+  float lmax = fmaxf(fmaxf(fmaxf(sreg[0][0], sreg[0][1]), fmaxf(sreg[0][2], sreg[0][3])),
+                     fmaxf(fmaxf(sreg[1][0], sreg[1][1]), fmaxf(sreg[1][2], sreg[1][3])));
+  lmax = rows_max_f(lmax);   // over the wave's 32 keys, per head (lane column)
+  const float mw = (lmax == -INFINITY) ? -1e30f : lmax;
+  float lsum = 0.f;
+#pragma unroll
+  for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float p = (sreg[tt][r] == -INFINITY) ? 0.f : __expf(sreg[tt][r] - mw);
+      lsum += p;
+      if (l16 < 8) pl[16 * (2 * w + tt) + 4 * kq + r][l16] = p;
+    }
+  lsum = rows_sum_f(lsum);
+  if (kq == 0 && l16 < G) { s_ml[w][l16][0] = mw; s_ml[w][l16][1] = lsum; }
+  // the probabilities just written are this wave's own keys: read back without a workgroup barrier
+  // (LDS operations of one wave complete in order)
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  float acc[G][8];
+#pragma unroll
+  for (int j = 0; j < G; ++j)
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[j][e] = 0.f;
-  }
-  const bf16_t* Kb = K + (size_t)unit * C * IM_D;
-  const bf16_t* Vb = V + (size_t)unit * C * IM_D;
-  // the 8 keys of this 16-lane row: all 16 loads go out before any arithmetic (one memory round trip);
-  // then two rounds of 4 keys, each with one rescaling of the running sums
-  uint4 ku[8], vu[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int kc = min(k0 + w * (IM_ATT_CHUNK / 4) + i * 4 + grp, n - 1);
-    ku[i] = *(const uint4*)(Kb + (size_t)kc * IM_D + l16 * 8);
-    vu[i] = *(const uint4*)(Vb + (size_t)kc * IM_D + l16 * 8);
-  }
-#pragma unroll
-  for (int r = 0; r < 2; ++r) {
-    float sv[4][G];
+  for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint4 u = ku[4 * r + i];
-      const bool valid = k0 + w * (IM_ATT_CHUNK / 4) + (4 * r + i) * 4 + grp < n;
-      const float kf[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
-                           bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
+      const int kl = 16 * (2 * w + tt) + 4 * i + kq;
+      float pv[8];
+      *(float4*)&pv[0] = *(const float4*)&pl[kl][0];
+      if (G > 4) *(float4*)&pv[4] = *(const float4*)&pl[kl][4];
+      const uint4 u = vf[tt][i];
+      const float v[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
+                          bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
 #pragma unroll
-      for (int j = 0; j < G; ++j) {
-        float t = 0.f;
+      for (int j = 0; j < G; ++j)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) t = fmaf(qf[j][e], kf[e], t);
-        t = row16_sum_f(t);   // (DPP rotations inside the 16-lane row)
-        sv[i][j] = valid ? t : -INFINITY;
-      }
+        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(pv[j], v[e], acc[j][e]);
     }
-    float corr[G];
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-      const float mn = fmaxf(fmaxf(mx[j], fmaxf(sv[0][j], sv[1][j])), fmaxf(sv[2][j], sv[3][j]));
-      corr[j] = __expf(mx[j] - mn);
-      mx[j] = mn;
-      ls[j] *= corr[j];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[j][e] *= corr[j];
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint4 u = vu[4 * r + i];
-      const float vf[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
-                           bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
-#pragma unroll
-      for (int j = 0; j < G; ++j) {
-        const float p = __expf(sv[i][j] - mx[j]);
-        ls[j] += p;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p, vf[e], acc[j][e]);
-      }
-    }
-  }
-  // merge the 4 key streams of the wave (the same lane of the four 16-lane rows)
+  // the wave's 4 key streams (the same lane of the four 16-lane rows) share the wave's maximum: plain sums
 #pragma unroll
   for (int j = 0; j < G; ++j) {
-    const float m = rows_max_f(mx[j]);
-    const float sc = __expf(mx[j] - m);
-    const float l = rows_sum_f(ls[j] * sc);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[j][e] = rows_sum_f(acc[j][e] * sc);
-    if (grp == 0) {
+    for (int e = 0; e < 8; ++e) acc[j][e] = rows_sum_f(acc[j][e]);
+    if (kq == 0) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) s_acc[w][j][l16 * 8 + e] = acc[j][e];
-      if (l16 == 0) { s_ml[w][j][0] = m; s_ml[w][j][1] = l; }
     }
   }
   __syncthreads();
@@ -1579,15 +1677,35 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
   }
   const float bv = bvec[(size_t)unit * IM_DM + tid];
   const float wgv = bf2f(wg[tid]);
-  float m = -1e30f;
+  float m = -1e30f, o = 0.f, l = 0.f;
+  if (nch <= IM_COMB_LDS) {
+    // thread c brings in chunk c's maximum and denominator (one round trip for all of them), the scale
+    // factors are made once, and the numerators follow with 8 loads in flight; same sums in the same order
+    // as the plain loops below
+    __shared__ float cm[IM_COMB_LDS], cl[IM_COMB_LDS];
+    for (int c = tid; c < nch; c += 128) {
+      cm[c] = rec[(size_t)c * IM_ATT_REC];
+      cl[c] = rec[(size_t)c * IM_ATT_REC + 1];
+    }
+    __syncthreads();
+    for (int c = 0; c < nch; ++c) m = fmaxf(m, cm[c]);
+    __syncthreads();
+    for (int c = tid; c < nch; c += 128) cm[c] = __expf(cm[c] - m);
+    __syncthreads();
+#pragma unroll 8
+    for (int c = 0; c < nch; ++c) {
+      o = fmaf(cm[c], rec[(size_t)c * IM_ATT_REC + 2 + tid], o);
+      l = fmaf(cm[c], cl[c], l);
+    }
+  } else {
 #pragma unroll 4
-  for (int c = 0; c < nch; ++c) m = fmaxf(m, rec[(size_t)c * IM_ATT_REC]);
-  float o = 0.f, l = 0.f;
+    for (int c = 0; c < nch; ++c) m = fmaxf(m, rec[(size_t)c * IM_ATT_REC]);
 #pragma unroll 4
-  for (int c = 0; c < nch; ++c) {
-    const float sc = __expf(rec[(size_t)c * IM_ATT_REC] - m);
-    o = fmaf(sc, rec[(size_t)c * IM_ATT_REC + 2 + tid], o);
-    l = fmaf(sc, rec[(size_t)c * IM_ATT_REC + 1], l);
+    for (int c = 0; c < nch; ++c) {
+      const float sc = __expf(rec[(size_t)c * IM_ATT_REC] - m);
+      o = fmaf(sc, rec[(size_t)c * IM_ATT_REC + 2 + tid], o);
+      l = fmaf(sc, rec[(size_t)c * IM_ATT_REC + 1], l);
+    }
   }
   const float o_attn = (nch > 0) ? o / l : 0.f;
   // memory readout

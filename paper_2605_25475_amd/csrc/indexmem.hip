@@ -463,16 +463,19 @@ int32_t im_memory_update(im_handle* h, const im_params* p, const im_state* st,
   const im_config& c = h->cfg;
   const int units = n_sets(c);
   float* part = (float*)(h->ws + h->off_mem);
+  // (the partials' buffer holds mem_split records per (batch element, KV head): a set of H_kv heads has
+  // one memory, so its rows can go to H_kv times as many splits; with only `batch` sets the launch needs them)
+  const int n_split = c.head_shared ? h->mem_split * c.n_kv_heads : h->mem_split;
   if (c.head_shared)
-    k_mem_partial_sets<<<dim3(h->mem_split, units), 256, 0, s>>>(
+    k_mem_partial_sets<<<dim3(n_split, units), 256, 0, s>>>(
         (const bf16_t*)st->K, (const bf16_t*)st->V, evict_idx, n_evict, (const bf16_t*)p->Wtheta,
-        c.capacity, c.n_kv_heads, c.fold_block, h->mem_split, part);
+        c.capacity, c.n_kv_heads, c.fold_block, n_split, part);
   else
-    k_mem_partial<<<dim3(h->mem_split, units), 256, 0, s>>>(
+    k_mem_partial<<<dim3(n_split, units), 256, 0, s>>>(
         (const bf16_t*)st->K, (const bf16_t*)st->V, evict_idx, n_evict, (const bf16_t*)p->Wtheta,
-        c.capacity, c.fold_block, h->mem_split, part);
+        c.capacity, c.fold_block, n_split, part);
   k_mem_finalize<<<dim3((IM_DM * IM_D + IM_DM + 255) / 256, units), 256, 0, s>>>(
-      st->M, st->b, n_evict, part, c.fold_block, h->mem_split, lambda, eta, (const bf16_t*)st->K,
+      st->M, st->b, n_evict, part, c.fold_block, n_split, lambda, eta, (const bf16_t*)st->K,
       (const bf16_t*)st->V, evict_idx, (const bf16_t*)p->Wtheta, c.capacity, heads_per_set(c));
   return launch_check(h, "im_memory_update");
 }
