@@ -236,13 +236,24 @@ __device__ __forceinline__ void dec_prep_memory(const DecArgs& a, const int u, c
   const float bc = a.bvec[(size_t)(u / a.H_set) * IM_DM + 32 * mp + (lane & 31)];
   const float g0 = bf2f(a.wg[lane]), g1 = bf2f(a.wg[lane + 64]);
   const bf16_t* qb = a.q + ((size_t)b * a.H + h * G) * IM_D;
+  // (the query rows too: inside the loop over the heads each pair of loads would be a round trip of its
+  // own; heads past the group repeat its last row and are not used)
+  uint4 qr[DEC_GMAX][2];
+#pragma unroll
+  for (int j = 0; j < DEC_GMAX; ++j) {
+    const bf16_t* qj = qb + min(j, G - 1) * IM_D + 16 * pt;
+    qr[j][0] = *(const uint4*)qj;
+    qr[j][1] = *(const uint4*)(qj + 8);
+  }
   float wv[16];
   unpack8(Wr0, wv);
   unpack8(Wr1, wv + 8);
-  for (int j = 0; j < G; ++j) {
+#pragma unroll
+  for (int j = 0; j < DEC_GMAX; ++j) {
+    if (j >= G) break;
     float qv[16];
-    unpack8(*(const uint4*)(qb + j * IM_D + 16 * pt), qv);
-    unpack8(*(const uint4*)(qb + j * IM_D + 16 * pt + 8), qv + 8);
+    unpack8(qr[j][0], qv);
+    unpack8(qr[j][1], qv + 8);
     float pq = 0.f;
 #pragma unroll
     for (int e = 0; e < 16; ++e) pq = fmaf(wv[e], qv[e], pq);
