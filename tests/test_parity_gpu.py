@@ -214,6 +214,29 @@ def test_select_ties_infinities_and_degenerate_sizes():
     pos_dup = (pos // 7).astype(np.int32)
     _select_case(cases["quantised"], pos_dup, 500, lens=lens)
     _select_case(cases["all_equal"], pos_dup, 77, lens=lens)
+    # exactly one entry leaves (units of 3000, 1025 and 5 entries): the slot index decides among equal
+    # (score, position) pairs there too
+    for budget in (2999, 1024, 4):
+        _select_case(cases["quantised"], pos_dup, budget, lens=lens)
+        _select_case(cases["all_equal"], pos_dup, budget, lens=lens)
+        _select_case(cases["infs"], pos_dup, budget, n_sink=0, n_recent=2, lens=lens)
+
+
+@pytest.mark.parametrize("shared", [False, True], ids=["per-unit", "head-shared"])
+def test_events_of_one_to_six_new_tokens(shared):
+    # events that append m tokens and evict m entries, m = 1 .. 6: the sizes around which the kernels of the
+    # step-by-step calls change paths (up to 4 new rows are projected, and up to 4 evicted rows folded into
+    # the memory, without the matrix-core tiles; a single eviction is selected by one reduction; the
+    # compaction probes the shorter of its two lists)
+    kw = dict(context=300, budget=140, decode_steps=32, batch=2, n_layers=1)
+    w = WORKLOADS["cfg1"].shared(**kw) if shared else WORKLOADS["cfg1"].scaled(**kw)
+    ls = (LockStepShared if shared else LockStep)(w, capacity=w.context + 32)
+    ls.event(0, w.context, w.budget, "prefill")
+    t = w.context
+    for m in (1, 2, 3, 4, 5, 6, 4, 1):
+        ls.event(t, t + m, w.budget, f"event of {m} tokens at {t}")
+        t += m
+    assert im.im_query_status(ls.handle) == 0
 
 
 def test_empty_and_single_entry_units_through_the_whole_step():
