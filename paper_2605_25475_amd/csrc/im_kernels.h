@@ -117,17 +117,6 @@ __device__ __forceinline__ double row16_ror_d(double v) {   // value of the lane
   const int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), 0x120 + N, 0xF, 0xF, false);
   return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
 }
-template <int N>
-__device__ __forceinline__ float row16_ror_f(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x120 + N, 0xF, 0xF, false));
-}
-__device__ __forceinline__ float row16_sum_f(float v) {
-  v += row16_ror_f<1>(v);
-  v += row16_ror_f<2>(v);
-  v += row16_ror_f<4>(v);
-  v += row16_ror_f<8>(v);
-  return v;
-}
 // sum over the 16 lanes of a row, in every lane (rotations of 1, 2, 4, 8)
 __device__ __forceinline__ double row16_sum_d(double v) {
   v += row16_ror_d<1>(v);
