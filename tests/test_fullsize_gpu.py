@@ -5,7 +5,8 @@ Configurations 2-5 run their own trajectories (stated context, budget, batch and
 256 / 1024 decode steps through im_decode_step; configuration 5 after its 31 chunk evictions).  The
 other decode paths of the benchmark run at configuration 3's size as well: the periodic schedule
 (128 attend-only steps, then one compression event), a leader / follower pair of an index-sharing
-group, and the head-shared layout (step by step, and its fused step over 512 decode steps)."""
+group, the six separate calls at decode size, and the head-shared layout (step by step, and its fused
+step over 512 decode steps)."""
 import pytest
 
 from parity import LockStep, LockStepShared
@@ -34,6 +35,19 @@ def test_full_size_trajectory_sampled_units(name, layer, kw, units):
     w = WORKLOADS[name].scaled(n_layers=layer + 1, **kw)
     ls = LockStep(w, layer=layer, gen_device="cuda", **units)
     ls.run_schedule(fused_decode=True, full_every=32)
+
+
+@pytest.mark.parametrize("name,units", [
+    ("cfg3", dict(batch_ids=[0, 2], kv_heads=[3, 6])),
+    ("cfg4", dict(batch_ids=[7], kv_heads=[0, 3])),
+], ids=["cfg3", "cfg4"])
+def test_full_size_step_by_step_decode_sampled_units(name, units):
+    # the six separate calls at the benchmark's sizes (bench.py --path steps): after the prompt's event, 8
+    # decode steps of one new token and one eviction each, through the decode-size paths of the generic
+    # kernels (single-eviction selection, few-row projection and memory update, matrix-core attention
+    # partials with 4 and 7 query heads per KV head)
+    w = WORKLOADS[name].scaled(n_layers=1, decode_steps=8)
+    LockStep(w, gen_device="cuda", **units).run_schedule()
 
 
 def test_cfg3_full_size_periodic_schedule_sampled_units():
