@@ -19,7 +19,8 @@ output in bf16, the memory state in fp32 (rounded only when compared).
 Every function below is pinned by tests/test_oracle_pins.py against closed forms, invariants,
 brute force, scalar loops and library routines (read_gate and fuse on random inputs with gates
 strictly inside (0, 1); a layer that follows a subset of KV heads against the same heads of a
-full layer); none is "parity unpinned".  The paper prints no worked numeric example, so there
+full layer; a batch of sequences with different positions against layers of one sequence each);
+none is "parity unpinned".  The paper prints no worked numeric example, so there
 are no golden values of the paper's to compare with.
 """
 from __future__ import annotations

@@ -611,3 +611,50 @@ def test_shared_scores_against_explicit_loops():
                 a += al * max(0.0, float(qj @ kt))
             best = max(best, a)
         assert abs(float(O.round_f32(best)) - scores[0, t]) <= 1e-12 * max(1.0, abs(best))
+
+
+@pytest.mark.parametrize("shared", [False, True], ids=["per-unit", "head-shared"])
+def test_sequences_of_a_batch_are_independent_and_keep_their_own_positions(shared):
+    # Batch elements share nothing but the weights: a layer of 3 sequences whose token positions differ
+    # (offsets 0, 7 and 900: only the first sequence holds sink positions, and the causal mask and the
+    # position tie-break see different numbers in each) must give, for every sequence, exactly what a
+    # layer of that one sequence gives.  Pins every per-sequence index of the layer classes (positions,
+    # query positions, gate inputs, hidden states, queries).
+    kw = dict(batch=3, context=40, budget=16, decode_steps=3, n_recent=2)
+    w = WORKLOADS["cfg1"].shared(**kw) if shared else WORKLOADS["cfg1"].scaled(**kw)
+    K, V, Q = (f64(t) for t in token_stream(w, 0))
+    X = f64(hidden_stream(w, 0)) if shared else None
+    offs = np.array([0, 7, 900], np.int32)
+
+    def run(layer, rows):
+        outs = []
+        for t0, t1 in [(0, w.context)] + [(t, t + 1) for t in range(w.context, w.n_tokens)]:
+            pos = (np.arange(t0, t1, dtype=np.int32)[None] + offs[rows, None]).astype(np.int32)
+            k, v, q = K[rows][:, :, t0:t1], V[rows][:, :, t0:t1], Q[rows][:, t0:t1]
+            if shared:
+                x = X[rows][:, t0:t1]
+                outs.append(layer.step(k, v, x, pos, q, x, pos, Q[rows][:, t1 - 1], w.budget, w.lam, w.eta))
+            else:
+                xg = q.reshape(len(rows), t1 - t0, -1)
+                outs.append(layer.step(k, v, pos, q, xg, pos, Q[rows][:, t1 - 1], w.budget, w.lam, w.eta))
+        return outs
+
+    full = make_oracle_layer(w)
+    got = run(full, [0, 1, 2])
+    decisions = []
+    for bi in range(3):
+        one = make_oracle_layer(w, batch=1)
+        want = run(one, [bi])
+        for g, r in zip(got, want):
+            assert np.array_equal(g[0][bi], r[0][0], equal_nan=True)                 # scores
+            flat = (lambda x: [x]) if shared else (lambda x: x)
+            for a, b in zip(flat(g[1][bi]), flat(r[1][0])):
+                assert np.array_equal(a, b)                                          # keep lists
+            for a, b in zip(flat(g[2][bi]), flat(r[2][0])):
+                assert np.array_equal(a, b)                                          # evict lists
+            assert np.array_equal(g[3][bi], r[3][0]) and np.array_equal(g[4][bi], r[4][0])
+        assert np.array_equal(full.M[bi], one.M[0]) and np.array_equal(full.b[bi], one.b[0])
+        assert np.array_equal(full.pos[bi], one.pos[0]) and np.array_equal(full.K[bi], one.K[0])
+        decisions.append(got[0][2][bi] if shared else got[0][2][bi][0])
+    # the offsets matter: the sequence that holds the sink positions evicts a different set
+    assert not np.array_equal(decisions[0], decisions[2])
