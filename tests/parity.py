@@ -65,6 +65,13 @@ class LockStep:
         self.K, self.V, self.Q = token_stream(w, layer, gen_device)
 
     # -- one event on both sides ---------------------------------------------------------------
+    def pos_offsets(self):
+        """Per-sequence offsets added to every token position ([batch, 1] int32; zeros unless a test sets
+        `self.pos_off`): sequences then differ in what the causal mask, the sinks and the position
+        tie-break see."""
+        off = getattr(self, "pos_off", None)
+        return torch.zeros((self.w.batch, 1), dtype=torch.int32) if off is None else off
+
     def event(self, t0: int, t1: int, budget: int, tag: str, check=True):
         """Tokens [t0, t1) enter; their queries score the cache; evict to `budget`; attend with
         the last token's query."""
@@ -73,7 +80,7 @@ class LockStep:
         k_new = self.K[:, :, t0:t1].contiguous()
         v_new = self.V[:, :, t0:t1].contiguous()
         q_new = self.Q[:, t0:t1].contiguous()
-        pos = torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+        pos = (torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1) + self.pos_offsets()).contiguous()
         q_attn = self.Q[:, t1 - 1].contiguous()
         d = lambda t: t.to(dev)
         bi_t = torch.tensor(self.batch_ids, device=k_new.device)
@@ -100,7 +107,7 @@ class LockStep:
         k_new = self.K[:, :, t:t + 1].contiguous()
         v_new = self.V[:, :, t:t + 1].contiguous()
         q_new = self.Q[:, t:t + 1].contiguous()
-        pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+        pos = torch.full((w.batch, 1), t, dtype=torch.int32) + self.pos_offsets()
         d = lambda x: x.to(dev)
         bi_t = torch.tensor(self.batch_ids, device=k_new.device)
         hs_t = torch.tensor(self.kv_heads, device=k_new.device)
@@ -192,7 +199,7 @@ class LockStep:
         w, dev = self.w, self.dev
         d = lambda x: x.to(dev)
         k_new = self.K[:, :, t0:t1].contiguous(); v_new = self.V[:, :, t0:t1].contiguous()
-        pos = torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+        pos = (torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1) + self.pos_offsets()).contiguous()
         q_attn = self.Q[:, t1 - 1].contiguous()
         self.gpu.follow_event(d(k_new), d(v_new), d(pos), d(q_attn), leader.gpu, w.lam, w.eta)
         torch.cuda.synchronize()
@@ -237,7 +244,7 @@ class LockStep:
         for t in range(t0, t0 + tau):
             k_new = self.K[:, :, t:t + 1].contiguous(); v_new = self.V[:, :, t:t + 1].contiguous()
             q_attn = self.Q[:, t].contiguous()
-            pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+            pos = torch.full((w.batch, 1), t, dtype=torch.int32) + self.pos_offsets()
             self.gpu.attend_step(d(k_new), d(v_new), d(pos), d(q_attn), fused=fused)
             torch.cuda.synchronize()
             self.ref.append_kv(sel(k_new), sel(v_new), pos.numpy()[bi])
@@ -322,12 +329,19 @@ class LockStepShared:
         self.K, self.V, self.Q = token_stream(w, layer, gen_device)
         self.X = hidden_stream(w, layer, gen_device)
 
+    def pos_offsets(self):
+        """Per-sequence offsets added to every token position ([batch, 1] int32; zeros unless a test sets
+        `self.pos_off`): sequences then differ in what the causal mask, the sinks and the position
+        tie-break see."""
+        off = getattr(self, "pos_off", None)
+        return torch.zeros((self.w.batch, 1), dtype=torch.int32) if off is None else off
+
     def event(self, t0: int, t1: int, budget: int, tag: str):
         w, dev = self.w, self.dev
         d = lambda t: t.to(dev)
         k_new = self.K[:, :, t0:t1].contiguous(); v_new = self.V[:, :, t0:t1].contiguous()
         q_new = self.Q[:, t0:t1].contiguous(); x_new = self.X[:, t0:t1].contiguous()
-        pos = torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+        pos = (torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1) + self.pos_offsets()).contiguous()
         q_attn = self.Q[:, t1 - 1].contiguous()
         xd = d(x_new)
         self.gpu.step(d(k_new), d(v_new), d(pos), d(q_new), xd, d(pos), d(q_attn), budget, w.lam, w.eta, x_new=xd)
@@ -346,7 +360,7 @@ class LockStepShared:
         d = lambda x: x.to(dev)
         k_new = self.K[:, :, t:t + 1].contiguous(); v_new = self.V[:, :, t:t + 1].contiguous()
         q_new = self.Q[:, t:t + 1].contiguous(); x_new = self.X[:, t:t + 1].contiguous()
-        pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+        pos = torch.full((w.batch, 1), t, dtype=torch.int32) + self.pos_offsets()
         posd = d(pos).view(w.batch)
         self.gpu.decode_step(d(k_new), d(v_new), posd, d(q_new).view(w.batch, w.n_q_heads, w.head_dim),
                              d(x_new).view(w.batch, -1), posd, budget, w.lam, w.eta, debug=True)
@@ -377,7 +391,7 @@ class LockStepShared:
         w, d = self.w, (lambda x: x.to(self.dev))
         k_new = self.K[:, :, t0:t1].contiguous(); v_new = self.V[:, :, t0:t1].contiguous()
         x_new = self.X[:, t0:t1].contiguous()
-        pos = torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+        pos = (torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1) + self.pos_offsets()).contiguous()
         q_attn = self.Q[:, t1 - 1].contiguous()
         self.gpu.follow_event(d(k_new), d(v_new), d(pos), d(q_attn), leader.gpu, w.lam, w.eta, x_new=d(x_new))
         torch.cuda.synchronize()
@@ -387,7 +401,7 @@ class LockStepShared:
         w, d = self.w, (lambda x: x.to(self.dev))
         k_new = self.K[:, :, t:t + 1].contiguous(); v_new = self.V[:, :, t:t + 1].contiguous()
         x_new = self.X[:, t:t + 1].contiguous(); q = self.Q[:, t].contiguous()
-        pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+        pos = torch.full((w.batch, 1), t, dtype=torch.int32) + self.pos_offsets()
         self.gpu.follow_step(d(k_new), d(v_new), d(pos).view(-1), d(q), leader.gpu.evicted, w.lam, w.eta, debug=True,
                              x_new=d(x_new))
         torch.cuda.synchronize()
@@ -453,7 +467,7 @@ class LockStepShared:
         for t in range(t0, t0 + tau):
             k_new = self.K[:, :, t:t + 1].contiguous(); v_new = self.V[:, :, t:t + 1].contiguous()
             x_new = self.X[:, t:t + 1].contiguous(); q_attn = self.Q[:, t].contiguous()
-            pos = torch.full((w.batch, 1), t, dtype=torch.int32)
+            pos = torch.full((w.batch, 1), t, dtype=torch.int32) + self.pos_offsets()
             self.gpu.attend_step(d(k_new), d(v_new), d(pos), d(q_attn), fused=fused, x_new=d(x_new))
             torch.cuda.synchronize()
             self.ref.append_kv_hidden(sel(k_new), sel(v_new), sel(x_new), pos.numpy()[bi])

@@ -143,3 +143,19 @@ def test_unit_above_the_budget_loses_one_entry_and_sets_the_status_bit(shared):
                           w.lam, w.eta)
     ls.compare(*ref, "over budget", fused=True)
     assert (g.st.len == 103).all()
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["steps", "fused"])
+@pytest.mark.parametrize("shared", [False, True], ids=["per-unit", "head-shared"])
+def test_sequences_with_different_token_positions(fused, shared):
+    # the benchmark's sequences all count their tokens from 0; here the three sequences of a batch start at
+    # 0, 7 and 900, so only the first holds sink positions and every per-sequence position (the new
+    # token's, the query's, the recent window's newest) is a different number in each
+    kw = dict(context=330, budget=90, decode_steps=4, batch=3, n_layers=1, n_recent=3)
+    w = WORKLOADS["cfg1"].shared(**kw) if shared else WORKLOADS["cfg1"].scaled(**kw)
+    ls = (LockStepShared if shared else LockStep)(w, capacity=max(w.capacity, w.budget + 2))
+    ls.pos_off = torch.tensor([[0], [7], [900]], dtype=torch.int32)
+    ls.run_schedule(fused_decode=fused)
+    pos = ls.gpu.st.pos.cpu()
+    n = int(ls.gpu.st.len.flatten()[0])
+    assert int(pos[0].flatten()[:4].max()) <= 3 and int(pos[2].min()) >= 900 and n == w.budget
