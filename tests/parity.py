@@ -86,7 +86,8 @@ class LockStep:
         bi_t = torch.tensor(self.batch_ids, device=k_new.device)
         hs_t = torch.tensor(self.kv_heads, device=k_new.device)
         qd = d(q_new)
-        self.gpu.step(d(k_new), d(v_new), d(pos), qd, qd.view(w.batch, n_new, -1), d(pos), d(q_attn),
+        qpos = pos - getattr(self, "qpos_shift", 0)   # (a test may let the queries lag behind their tokens)
+        self.gpu.step(d(k_new), d(v_new), d(pos), qd, qd.view(w.batch, n_new, -1), d(qpos), d(q_attn),
                       budget, w.lam, w.eta)
         torch.cuda.synchronize()
         bi = self.batch_ids
@@ -95,7 +96,7 @@ class LockStep:
         qn = f64(q_new.index_select(0, bi_t))
         posn = pos.numpy()[bi]
         scores, keep, evict, out, res = self.ref.step(
-            sel(k_new), sel(v_new), posn, qn, qn.reshape(len(bi), n_new, -1), posn,
+            sel(k_new), sel(v_new), posn, qn, qn.reshape(len(bi), n_new, -1), qpos.numpy()[bi],
             f64(q_attn.index_select(0, bi_t)), budget, w.lam, w.eta)
         if check:
             self.compare(scores, keep, evict, out, res, tag)
@@ -113,15 +114,16 @@ class LockStep:
         hs_t = torch.tensor(self.kv_heads, device=k_new.device)
         qd = d(q_new).view(w.batch, w.n_q_heads, w.head_dim)
         posd = d(pos).view(w.batch)
-        self.gpu.decode_step(d(k_new), d(v_new), posd, qd, qd.view(w.batch, -1), posd, budget, w.lam, w.eta,
-                             debug=True)
+        qpos = pos - getattr(self, "qpos_shift", 0)
+        self.gpu.decode_step(d(k_new), d(v_new), posd, qd, qd.view(w.batch, -1), d(qpos).view(w.batch), budget,
+                             w.lam, w.eta, debug=True)
         torch.cuda.synchronize()
         bi = self.batch_ids
         sel = lambda x: f64(x.index_select(0, bi_t).index_select(1, hs_t))
         qn = f64(q_new.index_select(0, bi_t))
         posn = pos.numpy()[bi]
         scores, keep, evict, out, res = self.ref.step(
-            sel(k_new), sel(v_new), posn, qn, qn.reshape(len(bi), 1, -1), posn, qn[:, 0],
+            sel(k_new), sel(v_new), posn, qn, qn.reshape(len(bi), 1, -1), qpos.numpy()[bi], qn[:, 0],
             budget, w.lam, w.eta)
         if check:
             self.compare(scores, keep, evict, out, res, tag, fused=True)
@@ -344,13 +346,15 @@ class LockStepShared:
         pos = (torch.arange(t0, t1, dtype=torch.int32).repeat(w.batch, 1) + self.pos_offsets()).contiguous()
         q_attn = self.Q[:, t1 - 1].contiguous()
         xd = d(x_new)
-        self.gpu.step(d(k_new), d(v_new), d(pos), d(q_new), xd, d(pos), d(q_attn), budget, w.lam, w.eta, x_new=xd)
+        qpos = pos - getattr(self, "qpos_shift", 0)
+        self.gpu.step(d(k_new), d(v_new), d(pos), d(q_new), xd, d(qpos), d(q_attn), budget, w.lam, w.eta, x_new=xd)
         torch.cuda.synchronize()
         bi_t = torch.tensor(self.batch_ids, device=k_new.device)
         sel = lambda x: f64(x.index_select(0, bi_t))
         posn = pos.numpy()[self.batch_ids]
         xn = sel(x_new)
-        ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn, posn, sel(q_attn), budget, w.lam, w.eta)
+        ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn, qpos.numpy()[self.batch_ids],
+                            sel(q_attn), budget, w.lam, w.eta)
         self.compare(*ref, tag)
         return ref
 
@@ -363,13 +367,15 @@ class LockStepShared:
         pos = torch.full((w.batch, 1), t, dtype=torch.int32) + self.pos_offsets()
         posd = d(pos).view(w.batch)
         self.gpu.decode_step(d(k_new), d(v_new), posd, d(q_new).view(w.batch, w.n_q_heads, w.head_dim),
-                             d(x_new).view(w.batch, -1), posd, budget, w.lam, w.eta, debug=True)
+                             d(x_new).view(w.batch, -1), d(pos - getattr(self, "qpos_shift", 0)).view(w.batch),
+                             budget, w.lam, w.eta, debug=True)
         torch.cuda.synchronize()
         bi_t = torch.tensor(self.batch_ids, device=k_new.device)
         sel = lambda x: f64(x.index_select(0, bi_t))
         posn = pos.numpy()[self.batch_ids]
         xn = sel(x_new)
-        ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn, posn, sel(q_new)[:, 0], budget,
+        ref = self.ref.step(sel(k_new), sel(v_new), xn, posn, sel(q_new), xn,
+                            (pos - getattr(self, "qpos_shift", 0)).numpy()[self.batch_ids], sel(q_new)[:, 0], budget,
                             w.lam, w.eta)
         if check:
             self.compare(*ref, tag, fused=True)

@@ -159,3 +159,19 @@ def test_sequences_with_different_token_positions(fused, shared):
     pos = ls.gpu.st.pos.cpu()
     n = int(ls.gpu.st.len.flatten()[0])
     assert int(pos[0].flatten()[:4].max()) <= 3 and int(pos[2].min()) >= 900 and n == w.budget
+
+
+@pytest.mark.parametrize("fused", [False, True], ids=["steps", "fused"])
+@pytest.mark.parametrize("shared", [False, True], ids=["per-unit", "head-shared"])
+def test_queries_that_do_not_see_the_newest_tokens(fused, shared):
+    # query positions 6 behind their tokens' (Algorithm 1's causal mask is by position, not by slot): the
+    # newest cached tokens are invisible to every query that scores them, their importance is -inf and,
+    # not being forced, they are the first to leave: among equal -inf scores the older position stays
+    kw = dict(context=330, budget=90, decode_steps=4, batch=2, n_layers=1)
+    w = WORKLOADS["cfg1"].shared(**kw) if shared else WORKLOADS["cfg1"].scaled(**kw)
+    ls = (LockStepShared if shared else LockStep)(w, capacity=max(w.capacity, w.budget + 2))
+    ls.qpos_shift = 6
+    ls.run_schedule(fused_decode=fused)
+    # each decode step's new token was invisible to its own query, so it is the one that left again
+    assert (ls.gpu.st.len == w.budget).all()
+    assert int(ls.gpu.st.pos[..., :w.budget].max()) < w.context
