@@ -1,5 +1,6 @@
 """GPU parity on parameter values the benchmark's recipe never takes (norm weights other than one,
-NULL norm pointers, a gate bias, lambda = 1, eta other than 0.5), and the device-side status bits
+NULL norm pointers, a gate bias, lambda = 1, eta other than 0.5, other sink and recent-window sizes,
+per-sequence position offsets, queries behind their tokens), and the device-side status bits
 of a broken live-length promise and of a unit above the budget.  Every case runs through the
 step-by-step calls AND the fused step, in both state layouts."""
 import numpy as np
@@ -33,6 +34,8 @@ VARIANTS = {
     "gate-bias-minus": dict(params_mod=_cg(-1.5)),
     "lambda-one": dict(scale=dict(lam=1.0)),
     "eta-two": dict(scale=dict(eta=2.0)),
+    "no-sinks": dict(scale=dict(n_sink=0)),
+    "nine-sinks-five-recent": dict(scale=dict(n_sink=9, n_recent=5)),
 }
 
 
