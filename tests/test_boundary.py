@@ -172,3 +172,24 @@ def test_static_entry_point_validates_on_the_host(lib):
     assert str(need) in msg and "IM_STATIC_SCRATCH_BYTES" in msg
     bad = good_cfg(head_dim=64).c_struct()
     assert f(C.byref(bad), 10, C.byref(p), C.byref(st), 1 << 20, 1 << 20, None, None, None) == im.IM_ERR_UNSUPPORTED
+
+
+def test_a_plain_c_program_compiles_against_the_header_links_and_runs(tmp_path):
+    # the boundary is a C ABI: tests/c_abi/host_calls.c is C99 (-pedantic), includes the header, links the
+    # library and drives its host-only calls
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    from paper_2605_25475_amd import build as _build
+    im.load_library()   # (builds the library if it is absent)
+    libdir = os.path.dirname(_build.LIB_PATH)
+    exe = str(tmp_path / "host_calls")
+    cmd = [gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+           os.path.join(ROOT, "tests", "c_abi", "host_calls.c"), "-L", libdir, "-lindexmem",
+           "-Wl,-rpath," + libdir, "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and r.stdout.startswith("ok "), r.stdout + r.stderr
