@@ -741,7 +741,6 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
       ss = rows_sum_d(ss);
       const double rr = sqrt(ss / (double)IM_DI + (double)a.rms_eps);
       const double inv = 1.0 / rr;
-      const double live = hv ? 1.0 : 0.0;
       float wf[16];
       unpack8(nw[0], wf);
       unpack8(nw[1], wf + 8);
@@ -755,9 +754,9 @@ __device__ __forceinline__ void dec_split(const DecArgs& a, const int u, const i
         double qq = qd[m] * inv;
         qq = fma(fma(-qq, rr, qd[m]), inv, qq);
         qq = fma(fma(-qq, rr, qd[m]), inv, qq);
-        // (lanes past the last indexer head hold head 0's values: finite; zeroed by a product, which the
-        // compiler keeps as one instruction where a select became sixteen branches)
-        qd[m] = (double)(float)(qq * (double)wf[m]) * live;
+        // (lanes past the last indexer head hold head 0's values: finite, and never used: their columns of
+        // the similarity product are not stored and their gate is zero)
+        qd[m] = (double)(float)(qq * (double)wf[m]);
       }
       alj = hv ? (double)(float)(araw / sqrt((double)(a.H_idx * IM_DI))) : 0.0;
     }
