@@ -126,71 +126,19 @@ __device__ __forceinline__ double row16_sum_d(double v) {
   return v;
 }
 
-__global__ __launch_bounds__(256) void k_project_keys(const bf16_t* __restrict__ K,
-                                                      bf16_t* __restrict__ Kidx,
-                                                      const int32_t* __restrict__ len,
-                                                      const int32_t* __restrict__ n_projected,
-                                                      const bf16_t* __restrict__ Uk,
-                                                      const bf16_t* __restrict__ norm_w, int C,
-                                                      int max_live, float rms_eps,
-                                                      int32_t* __restrict__ status) {
-  __shared__ __attribute__((aligned(16))) bf16_t outs[4][16][IM_DI + 8];
-  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+// LDS of the key projection: a 16 x 64 output tile per wave, and the few-row path's raw outputs
+struct ProjectSmem {
+  __attribute__((aligned(16))) bf16_t outs[4][16][IM_DI + 8];
+  double ys[4][IM_DI];
+};
+
+// One wave: rows row0 .. row0 + 15 of the unit (those below n) on the fp64 matrix cores.
+__device__ __forceinline__ void project_keys_tile(const bf16_t* __restrict__ K, bf16_t* __restrict__ Kidx,
+                                                  const bf16_t* __restrict__ Uk,
+                                                  const bf16_t* __restrict__ norm_w, int C, float rms_eps,
+                                                  int unit, int row0, int n, ProjectSmem& sm) {
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int l16 = lane & 15, kq = lane >> 4;
-  int n = len[unit];
-  if (n > max_live) {
-    if (tid == 0 && blockIdx.x == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
-    n = max_live;
-  }
-  const int np = n_projected[unit];
-  if (n - np <= 4) {
-    // A few new rows (a decode step appends one): the unit's first workgroup projects them with plain
-    // fp64 FMAs: 4 lanes per output column, 32 dims each.  (Products of bf16 values summed in fp64 are
-    // exact at these sizes, so the order of the sum is immaterial and the rows equal the matrix-core ones.)
-    if (blockIdx.x != 0 || n <= np) return;
-    __shared__ double ys[4][IM_DI];
-    const int nr = n - np, c = tid >> 2, q4 = tid & 3;
-    uint4 ub[4], ka[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) ub[i] = *(const uint4*)(Uk + c * IM_D + 32 * q4 + 8 * i);
-#pragma unroll
-    for (int r = 0; r < 4; ++r)
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        ka[r][i] = *(const uint4*)(K + ((size_t)unit * C + np + min(r, nr - 1)) * IM_D + 32 * q4 + 8 * i);
-    double acc[4] = {0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const uint4 u = ub[i];
-      const float fb[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
-                           bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const uint4 v = ka[r][i];
-        const float fa[8] = {bf_lo(v.x), bf_hi(v.x), bf_lo(v.y), bf_hi(v.y),
-                             bf_lo(v.z), bf_hi(v.z), bf_lo(v.w), bf_hi(v.w)};
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[r] = fma((double)fa[e], (double)fb[e], acc[r]);
-      }
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      acc[r] += __shfl_xor(acc[r], 1, 64);
-      acc[r] += __shfl_xor(acc[r], 2, 64);
-      if (q4 == 0) ys[r][c] = acc[r];
-    }
-    __syncthreads();
-    if (w < nr) {   // wave w: row w, lane = column
-      const double y = ys[w][lane];
-      const double ss = wave_sum_d(y * y);
-      const double rr = sqrt(ss / (double)IM_DI + (double)rms_eps);
-      const double wn1 = norm_w ? (double)bf2f(norm_w[lane]) : 1.0;
-      Kidx[((size_t)unit * C + np + w) * IM_DI + lane] = d2bf_rne(y / rr * wn1);
-    }
-    return;
-  }
-  const int row0 = np + blockIdx.x * 64 + 16 * w;
-  if (row0 >= n) return;                       // wave-uniform; no workgroup barrier below
   const int rows = min(16, n - row0);
   const size_t krow = ((size_t)unit * C + row0 + min(l16, rows - 1)) * IM_D;   // rows past the end repeat the last
   uint4 ka[4], ub[4][4];
@@ -229,7 +177,7 @@ __global__ __launch_bounds__(256) void k_project_keys(const bf16_t* __restrict__
     ss = row16_sum_d(ss);
     const double rr = sqrt(ss / (double)IM_DI + (double)rms_eps);
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) outs[w][4 * r + kq][16 * cb + l16] = d2bf_rne(acc[cb][r] / rr * wn[cb]);
+    for (int cb = 0; cb < 4; ++cb) sm.outs[w][4 * r + kq][16 * cb + l16] = d2bf_rne(acc[cb][r] / rr * wn[cb]);
   }
   // the wave's own 16 x 64 tile goes out in 16-byte pieces (LDS operations of one wave complete in order)
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -239,8 +187,85 @@ __global__ __launch_bounds__(256) void k_project_keys(const bf16_t* __restrict__
   for (int k = 0; k < 2; ++k) {
     const int idx = lane + 64 * k, r = idx >> 3, ch = idx & 7;
     if (r < rows)
-      *(uint4*)(Kidx + ((size_t)unit * C + row0 + r) * IM_DI + 8 * ch) = *(const uint4*)&outs[w][r][8 * ch];
+      *(uint4*)(Kidx + ((size_t)unit * C + row0 + r) * IM_DI + 8 * ch) = *(const uint4*)&sm.outs[w][r][8 * ch];
   }
+  // (the next tile of this wave may overwrite the staging rows only after these reads)
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// One workgroup: rows np .. n - 1 of the unit, at most 4 of them (a decode step appends one), with plain
+// fp64 FMAs: 4 lanes per output column, 32 dims each.  (Products of bf16 values summed in fp64 are exact
+// at these sizes, so the order of the sum is immaterial and the rows equal the matrix-core ones.)
+__device__ __forceinline__ void project_keys_few(const bf16_t* __restrict__ K, bf16_t* __restrict__ Kidx,
+                                                 const bf16_t* __restrict__ Uk,
+                                                 const bf16_t* __restrict__ norm_w, int C, float rms_eps,
+                                                 int unit, int np, int n, ProjectSmem& sm) {
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int nr = n - np, c = tid >> 2, q4 = tid & 3;
+  uint4 ub[4], ka[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) ub[i] = *(const uint4*)(Uk + c * IM_D + 32 * q4 + 8 * i);
+#pragma unroll
+  for (int r = 0; r < 4; ++r)
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      ka[r][i] = *(const uint4*)(K + ((size_t)unit * C + np + min(r, nr - 1)) * IM_D + 32 * q4 + 8 * i);
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint4 u = ub[i];
+    const float fb[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
+                         bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint4 v = ka[r][i];
+      const float fa[8] = {bf_lo(v.x), bf_hi(v.x), bf_lo(v.y), bf_hi(v.y),
+                           bf_lo(v.z), bf_hi(v.z), bf_lo(v.w), bf_hi(v.w)};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[r] = fma((double)fa[e], (double)fb[e], acc[r]);
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    acc[r] += __shfl_xor(acc[r], 1, 64);
+    acc[r] += __shfl_xor(acc[r], 2, 64);
+    if (q4 == 0) sm.ys[r][c] = acc[r];
+  }
+  __syncthreads();
+  if (w < nr) {   // wave w: row w, lane = column
+    const double y = sm.ys[w][lane];
+    const double ss = wave_sum_d(y * y);
+    const double rr = sqrt(ss / (double)IM_DI + (double)rms_eps);
+    const double wn1 = norm_w ? (double)bf2f(norm_w[lane]) : 1.0;
+    Kidx[((size_t)unit * C + np + w) * IM_DI + lane] = d2bf_rne(y / rr * wn1);
+  }
+}
+
+// grid (tiles of 64 rows, units), 4 waves; wave w projects rows 16 w .. 16 w + 15 of the tile
+__global__ __launch_bounds__(256) void k_project_keys(const bf16_t* __restrict__ K,
+                                                      bf16_t* __restrict__ Kidx,
+                                                      const int32_t* __restrict__ len,
+                                                      const int32_t* __restrict__ n_projected,
+                                                      const bf16_t* __restrict__ Uk,
+                                                      const bf16_t* __restrict__ norm_w, int C,
+                                                      int max_live, float rms_eps,
+                                                      int32_t* __restrict__ status) {
+  __shared__ ProjectSmem sm;
+  const int unit = blockIdx.y, tid = threadIdx.x, w = tid >> 6;
+  int n = len[unit];
+  if (n > max_live) {
+    if (tid == 0 && blockIdx.x == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
+    n = max_live;
+  }
+  const int np = n_projected[unit];
+  if (n - np <= 4) {   // (uniform per workgroup)
+    if (blockIdx.x == 0 && n > np) project_keys_few(K, Kidx, Uk, norm_w, C, rms_eps, unit, np, n, sm);
+    return;
+  }
+  const int row0 = np + blockIdx.x * 64 + 16 * w;
+  if (row0 >= n) return;                       // wave-uniform; no workgroup barrier below
+  project_keys_tile(K, Kidx, Uk, norm_w, C, rms_eps, unit, row0, n, sm);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -418,29 +443,43 @@ __device__ __forceinline__ void gemv_nt_rows(const bf16_t* __restrict__ A, const
                                              double* __restrict__ Cm, int M, int N, int Kd, int n0,
                                              double (*red)[16]) {
   const int tid = threadIdx.x, w = tid >> 6;
+  const int r1 = (n0 + 1 < N) ? n0 + 1 : n0;   // an absent second row repeats the first (result unused)
   for (int mb = 0; mb < M; mb += 8) {
     double acc[8][2];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i][0] = acc[i][1] = 0.0;
-    for (int k = tid * 8; k < Kd; k += 256 * 8) {
-      float bv[2][8];
+    // a round covers two 2048-wide chunks of the contraction; the loads of both go out before the arithmetic
+    // (an absent second chunk repeats the first, unused; rows past M repeat the last row, unused)
+    for (int k0 = tid * 8; k0 < Kd; k0 += 2 * 2048) {
+      uint4 bu[2][2], au[2][8];
 #pragma unroll
-      for (int r = 0; r < 2; ++r) {
-        uint4 u = make_uint4(0, 0, 0, 0);
-        if (n0 + r < N) u = *(const uint4*)(B + (size_t)(n0 + r) * Kd + k);
-        bv[r][0] = bf_lo(u.x); bv[r][1] = bf_hi(u.x); bv[r][2] = bf_lo(u.y); bv[r][3] = bf_hi(u.y);
-        bv[r][4] = bf_lo(u.z); bv[r][5] = bf_hi(u.z); bv[r][6] = bf_lo(u.w); bv[r][7] = bf_hi(u.w);
+      for (int it = 0; it < 2; ++it) {
+        const int k = (k0 + it * 2048 < Kd) ? k0 + it * 2048 : k0;
+        bu[it][0] = *(const uint4*)(B + (size_t)n0 * Kd + k);
+        bu[it][1] = *(const uint4*)(B + (size_t)r1 * Kd + k);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) au[it][i] = *(const uint4*)(A + (size_t)min(mb + i, M - 1) * Kd + k);
       }
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (mb + i < M) {
-          uint4 u = *(const uint4*)(A + (size_t)(mb + i) * Kd + k);
-          float av[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
-                         bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
+      for (int it = 0; it < 2; ++it) {
+        if (k0 + it * 2048 < Kd) {
+          const uint4 u0 = bu[it][0], u1 = bu[it][1];
+          const float b0[8] = {bf_lo(u0.x), bf_hi(u0.x), bf_lo(u0.y), bf_hi(u0.y),
+                               bf_lo(u0.z), bf_hi(u0.z), bf_lo(u0.w), bf_hi(u0.w)};
+          const float b1[8] = {bf_lo(u1.x), bf_hi(u1.x), bf_lo(u1.y), bf_hi(u1.y),
+                               bf_lo(u1.z), bf_hi(u1.z), bf_lo(u1.w), bf_hi(u1.w)};
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            acc[i][0] = fma((double)av[e], (double)bv[0][e], acc[i][0]);
-            acc[i][1] = fma((double)av[e], (double)bv[1][e], acc[i][1]);
+          for (int i = 0; i < 8; ++i) {
+            if (mb + i < M) {
+              const uint4 u = au[it][i];
+              const float av[8] = {bf_lo(u.x), bf_hi(u.x), bf_lo(u.y), bf_hi(u.y),
+                                   bf_lo(u.z), bf_hi(u.z), bf_lo(u.w), bf_hi(u.w)};
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                acc[i][0] = fma((double)av[e], (double)b0[e], acc[i][0]);
+                acc[i][1] = fma((double)av[e], (double)b1[e], acc[i][1]);
+              }
+            }
           }
         }
       }
@@ -472,16 +511,38 @@ __global__ __launch_bounds__(256) void k_gemv_nt_f64(const bf16_t* __restrict__ 
   gemv_nt_rows(A, B, Cm, M, N, Kd, blockIdx.x * 2, red);
 }
 
-// Two such products in one launch (the query projection and the head gate of a decode-size scoring call):
-// grid (ceil(N1/2) + ceil(N2/2))
-__global__ __launch_bounds__(256) void k_gemv2_nt_f64(const bf16_t* __restrict__ A1, const bf16_t* __restrict__ B1,
-                                                      double* __restrict__ C1, int N1, int K1,
-                                                      const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2,
-                                                      double* __restrict__ C2, int N2, int K2, int M) {
-  __shared__ double red[4][16];
-  const int nb1 = (N1 + 1) / 2;
-  if ((int)blockIdx.x < nb1) gemv_nt_rows(A1, B1, C1, M, N1, K1, blockIdx.x * 2, red);
-  else gemv_nt_rows(A2, B2, C2, M, N2, K2, ((int)blockIdx.x - nb1) * 2, red);
+// The query side of a decode-size scoring call in one launch: the two products (query projection, head
+// gate) and, in the per-unit layout, the indexer keys of the rows not yet projected (IM_PROJ_WGS workgroups
+// per unit walk over the unit's tiles of 64 rows; a few rows go through the plain-FMA path).
+// grid (n_proj_units * IM_PROJ_WGS + ceil(N1/2) + ceil(N2/2))
+#define IM_PROJ_WGS 4
+__global__ __launch_bounds__(256) void k_query_side_few(
+    const bf16_t* __restrict__ A1, const bf16_t* __restrict__ B1, double* __restrict__ C1, int N1, int K1,
+    const bf16_t* __restrict__ A2, const bf16_t* __restrict__ B2, double* __restrict__ C2, int N2, int K2, int M,
+    int n_proj_units, const bf16_t* __restrict__ K, bf16_t* __restrict__ Kidx, const int32_t* __restrict__ len,
+    const int32_t* __restrict__ n_projected, const bf16_t* __restrict__ Uk, const bf16_t* __restrict__ norm_k_w,
+    int C, int max_live, float rms_eps, int32_t* __restrict__ status) {
+  __shared__ union { ProjectSmem proj; double red[4][16]; } sm;
+  const int np_blocks = n_proj_units * IM_PROJ_WGS;
+  if ((int)blockIdx.x < np_blocks) {
+    const int unit = blockIdx.x / IM_PROJ_WGS, pb = blockIdx.x % IM_PROJ_WGS, tid = threadIdx.x, w = tid >> 6;
+    int n = len[unit];
+    if (n > max_live) {
+      if (tid == 0 && pb == 0) atomicOr(status, IM_STATUS_LIVE_EXCEEDED_BIT);
+      n = max_live;
+    }
+    const int np = n_projected[unit];
+    if (n - np <= 4) {   // (uniform per workgroup)
+      if (pb == 0 && n > np) project_keys_few(K, Kidx, Uk, norm_k_w, C, rms_eps, unit, np, n, sm.proj);
+      return;
+    }
+    for (int row0 = np + pb * 64 + 16 * w; row0 < n; row0 += IM_PROJ_WGS * 64)   // wave-uniform; no workgroup barrier
+      project_keys_tile(K, Kidx, Uk, norm_k_w, C, rms_eps, unit, row0, n, sm.proj);
+    return;
+  }
+  const int g = (int)blockIdx.x - np_blocks, nb1 = (N1 + 1) / 2;
+  if (g < nb1) gemv_nt_rows(A1, B1, C1, M, N1, K1, g * 2, sm.red);
+  else gemv_nt_rows(A2, B2, C2, M, N2, K2, (g - nb1) * 2, sm.red);
 }
 
 // RMSNorm of every indexer query head in place: y[m][j][0..di-1] -> fp32-rounded q, kept as fp64.

@@ -368,29 +368,32 @@ int32_t im_index_score(im_handle* h, const im_params* p, const im_state* st, con
   double* qy = (double*)(h->ws + h->off_qy);
   double* al = (double*)(h->ws + h->off_alpha);
 
-  if (!c.head_shared)
-    k_project_keys<<<dim3((h->max_live + 63) / 64, units), 256, 0, s>>>(
-        (const bf16_t*)st->K, (bf16_t*)st->Kidx, st->len, st->n_projected, (const bf16_t*)p->Uk,
-        (const bf16_t*)p->norm_k_w, c.capacity, h->max_live, c.rms_eps, status_ptr(h));
-
   const int M = c.batch * n_q, Nq = c.n_idx_heads * di, Kq = c.n_q_heads * IM_D;
   const int rows = M * c.n_idx_heads;
+  const double alpha_denom = sqrt((double)(c.n_idx_heads * di));
+  // fewer queries than indexer heads (a decode step): the heads of a query are the scoring product's columns
+  const bool few = n_q < c.n_idx_heads && c.n_idx_heads <= 16;
   if (M <= 32) {
-    // a decode-size call: both products in one launch, then the QK-Norm and the gate scaling in one
-    k_gemv2_nt_f64<<<(Nq + 1) / 2 + (c.n_idx_heads + 1) / 2, 256, 0, s>>>(
+    // a decode-size call: the key projection of the new rows and both query-side products in one launch,
+    // the QK-Norm and the gate scaling in another
+    const int n_proj = c.head_shared ? 0 : units;
+    k_query_side_few<<<n_proj * IM_PROJ_WGS + (Nq + 1) / 2 + (c.n_idx_heads + 1) / 2, 256, 0, s>>>(
         (const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, Nq, Kq, (const bf16_t*)x_gate, (const bf16_t*)p->G, al,
-        c.n_idx_heads, c.gate_in_dim, M);
+        c.n_idx_heads, c.gate_in_dim, M, n_proj, (const bf16_t*)st->K, (bf16_t*)st->Kidx, st->len, st->n_projected,
+        (const bf16_t*)p->Uk, (const bf16_t*)p->norm_k_w, c.capacity, h->max_live, c.rms_eps, status_ptr(h));
     k_qnorm_alpha<<<(rows + 3) / 4 + (rows + 255) / 256, 256, 0, s>>>(qy, rows, di, (const bf16_t*)p->norm_q_w,
-                                                                     c.rms_eps, al, rows,
-                                                                     sqrt((double)(c.n_idx_heads * di)));
+                                                                     c.rms_eps, al, rows, alpha_denom);
   } else {
+    if (!c.head_shared)
+      k_project_keys<<<dim3((h->max_live + 63) / 64, units), 256, 0, s>>>(
+          (const bf16_t*)st->K, (bf16_t*)st->Kidx, st->len, st->n_projected, (const bf16_t*)p->Uk,
+          (const bf16_t*)p->norm_k_w, c.capacity, h->max_live, c.rms_eps, status_ptr(h));
     gemm_nt(s, (const bf16_t*)q_new, (const bf16_t*)p->Uq, qy, M, Nq, Kq);
     gemm_nt(s, (const bf16_t*)x_gate, (const bf16_t*)p->G, al, M, c.n_idx_heads, c.gate_in_dim);
     k_qnorm<<<(rows + 3) / 4, 256, 0, s>>>(qy, rows, di, (const bf16_t*)p->norm_q_w, c.rms_eps);
-    k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, sqrt((double)(c.n_idx_heads * di)));
+    k_alpha_scale<<<(rows + 255) / 256, 256, 0, s>>>(al, rows, alpha_denom);
   }
-  // fewer queries than indexer heads (a decode step): the heads of a query are the product's columns
-  if (n_q < c.n_idx_heads && c.n_idx_heads <= 16) {
+  if (few) {
     const dim3 grid((h->max_live + 63) / 64, units);
     if (c.head_shared)
       k_score_few<IM_DI_SHARED><<<grid, 256, 0, s>>>((const bf16_t*)st->Kidx, st->pos, st->len, st->n_projected, qy, al,
