@@ -1727,6 +1727,14 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
   }
   const float bv = bvec[(size_t)unit * IM_DM + tid];
   const float wgv = bf2f(wg[tid]);
+  // ... and this thread's column of the memory (row c of M is 512 contiguous bytes across the threads): 128
+  // independent loads here instead of 8 dependent batches of 16 at the end
+  float mcol[IM_DM];
+  {
+    const float* Mu = M + (size_t)unit * IM_DM * IM_D + tid;
+#pragma unroll
+    for (int c = 0; c < IM_DM; ++c) mcol[c] = Mu[c * IM_D];
+  }
   float m = -1e30f, o = 0.f, l = 0.f;
   if (nch <= IM_COMB_LDS) {
     // thread c brings in chunk c's maximum and denominator (one round trip for all of them), the scale
@@ -1778,10 +1786,9 @@ __global__ __launch_bounds__(128) void k_attn_combine(const float* __restrict__ 
   den = red[0][0] + red[1][0] + mem_eps;
   gz = red[0][1] + red[1][1] + cg;
   const float gate = 1.f / (1.f + __expf(-gz));
-  const float* Mu = M + (size_t)unit * IM_DM * IM_D;
   float mr = 0.f;
-#pragma unroll 16
-  for (int c = 0; c < IM_DM; ++c) mr = fmaf(phi[c], Mu[c * IM_D + tid], mr);
+#pragma unroll
+  for (int c = 0; c < IM_DM; ++c) mr = fmaf(phi[c], mcol[c], mr);
   const float res = gate * (mr / den);
   out[(size_t)bh * IM_D + tid] = f2bf_rne(o_attn + res);
   if (readout_dbg) readout_dbg[(size_t)bh * IM_D + tid] = res;
