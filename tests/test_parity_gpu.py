@@ -6,6 +6,7 @@ import torch
 
 import paper_2605_25475_amd as im
 from oracle import indexmem_oracle as O
+from helpers import f64
 from parity import LockStep, LockStepShared
 from workloads import WORKLOADS
 
@@ -497,3 +498,29 @@ def test_seeded_random_shapes_periodic_schedule(kw, shared):
         LockStepShared(w.shared(), capacity=cap).run_window_schedule(tau, 2)
     else:
         LockStep(w, capacity=cap, max_queries=max(w.context, tau)).run_window_schedule(tau, 2)
+
+
+def test_few_queries_score_a_cache_with_many_rows_not_yet_projected():
+    # 300 rows are appended without a scoring call in between, then ONE query scores the cache: the
+    # decode-size scoring call has to project all of them (its projection workgroups walk over the unit's
+    # tiles), bit for bit as the prefill-size call would, and the scores follow the oracle's
+    w = WORKLOADS["cfg1"].scaled(batch=2, context=371, budget=400, decode_steps=1, n_layers=1)
+    ls = LockStep(w, capacity=400)
+    g, ref, dev = ls.gpu, ls.ref, "cuda"
+    n0 = 70
+    ls.event(0, n0, w.budget, "first rows")                       # 70 rows, projected by a 70-query call
+    t1 = w.context
+    k = ls.K[:, :, n0:t1].contiguous(); v = ls.V[:, :, n0:t1].contiguous()
+    pos = torch.arange(n0, t1, dtype=torch.int32).repeat(w.batch, 1).contiguous()
+    im.im_append_kv(ls.handle, g.st, k.to(dev), v.to(dev), pos.to(dev))
+    ref.append_kv(f64(k), f64(v), pos.numpy())
+    q = ls.Q[:, t1 - 1:t1].contiguous()
+    qpos = torch.full((w.batch, 1), t1 - 1, dtype=torch.int32)
+    qd = q.to(dev)
+    im.im_index_score(ls.handle, ls.params, g.st, qd, qd.view(w.batch, 1, -1), qpos.to(dev), g.scores)
+    torch.cuda.synchronize()
+    want = ref.index_score(f64(q), f64(q).reshape(w.batch, 1, -1), qpos.numpy())
+    assert (g.st.n_projected == t1).all()
+    assert np.array_equal(f64(g.st.Kidx[:, :, :t1]), ref.Kidx[:, :, :t1])
+    assert np.array_equal(g.scores[:, :, :t1].cpu().numpy().astype(np.float64), want[:, :, :t1])
+    assert im.im_query_status(ls.handle) == 0
